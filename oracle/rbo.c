@@ -1,0 +1,273 @@
+/*
+ * CPU oracle of the per-process rehearsal buffer (TEST INFRASTRUCTURE ONLY).
+ *
+ * A plain, sequential, single-threaded C implementation of what one process
+ * of the paper does each training iteration with its local buffer B_n:
+ *
+ *   - the buffer is one sub-buffer R^i_n per class i, each of the same
+ *     capacity (Sec. IV-A);
+ *   - update_buffer(m) (Algorithm 1): pick c random candidates of the
+ *     mini-batch m, then for every candidate append it to the sub-buffer of
+ *     its class while that sub-buffer has room, otherwise overwrite a random
+ *     representative of that class;
+ *   - mini-batch augmentation (Sec. IV-C): draw r representatives uniformly,
+ *     without replacement, from everything stored, and hand them out so the
+ *     caller can concatenate them to the mini-batch (Listing 1).
+ *
+ * The paper names no random generator, no subset-sampling algorithm and no
+ * insertion order; the readings taken here (Philox4x32-10 counter-based
+ * draws, multiply-high range reduction, Floyd's subset sampling, insertion in
+ * ascending mini-batch position) are chosen so that every random choice is a
+ * pure function of (seed, step, purpose, index) and a parallel implementation
+ * can reproduce the sequential result bit for bit.
+ *
+ * Nothing here is shared with the GPU library: no header, no table, no
+ * helper.  Only tests, the smoke check and the bench's cpu_baseline leg may
+ * use this file.  Parity status: every function below is pinned by the CPU
+ * test-suite (known-answer vectors for Philox, closed forms / library
+ * routines for the policy, chi-square tests for the distributions); the exact
+ * seeded result at the five workload shapes is fixed by no printed example in
+ * the paper (its two-iteration figures carry no numbers) -- "parity unpinned
+ * by the paper" for those, pinned only through the properties above.
+ */
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+#define RBO_SELECT 1u   /* purpose tag of the draws that choose candidates       */
+#define RBO_EVICT  2u   /* purpose tag of the draws that choose a slot to replace */
+#define RBO_SAMPLE 3u   /* purpose tag of the draws that choose representatives   */
+
+/* ------------------------------------------------------------------------ */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as  */
+/* easy as 1, 2, 3", SC'11, Sec. 3.3 and Table 2 for the constants).        */
+/* ------------------------------------------------------------------------ */
+void rbo_philox4x32_10(const uint32_t ctr_in[4], const uint32_t key_in[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr_in[0], c1 = ctr_in[1], c2 = ctr_in[2], c3 = ctr_in[3];
+    uint32_t k0 = key_in[0], k1 = key_in[1];
+    for (int round = 0; round < 10; ++round) {
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;   /* multiplier of word 0 */
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;   /* multiplier of word 2 */
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+        k0 += 0x9E3779B9u;                          /* Weyl key schedule    */
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/* One 64-bit uniform draw per (seed, step, purpose, index). */
+uint64_t rbo_draw64(uint64_t seed, uint64_t step, uint32_t purpose, uint32_t index)
+{
+    uint32_t ctr[4] = { index, purpose, (uint32_t)step, (uint32_t)(step >> 32) };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t w[4];
+    rbo_philox4x32_10(ctr, key, w);
+    return (uint64_t)w[0] | ((uint64_t)w[1] << 32);
+}
+
+/* Uniform integer in [0, n): floor(u * n / 2^64) of the 64-bit draw u. */
+uint64_t rbo_bounded(uint64_t seed, uint64_t step, uint32_t purpose, uint32_t index, uint64_t n)
+{
+    unsigned __int128 prod = (unsigned __int128)rbo_draw64(seed, step, purpose, index) * n;
+    return (uint64_t)(prod >> 64);
+}
+
+/*
+ * Floyd's algorithm for a uniformly distributed m-subset of {0..n-1}
+ * (Bentley & Floyd, "Programming pearls: a sample of brilliance", CACM 1987).
+ * out[i] is the element added in iteration i.  Membership is tested by a
+ * plain linear search over what was emitted so far.
+ */
+void rbo_floyd(uint64_t seed, uint64_t step, uint32_t purpose, int64_t n, int64_t m, int64_t *out)
+{
+    for (int64_t i = 0; i < m; ++i) {
+        int64_t j = n - m + i;
+        int64_t t = (int64_t)rbo_bounded(seed, step, purpose, (uint32_t)i, (uint64_t)j + 1);
+        int seen = 0;
+        for (int64_t q = 0; q < i; ++q)
+            if (out[q] == t) { seen = 1; break; }
+        out[i] = seen ? j : t;
+    }
+}
+
+/* ------------------------------------------------------------------------ */
+/* The buffer                                                                */
+/* ------------------------------------------------------------------------ */
+typedef struct rbo_buffer {
+    int64_t K;            /* number of classes                                   */
+    int64_t S;            /* capacity of every per-class sub-buffer, in samples  */
+    int64_t row_bytes;    /* bytes of one stored sample                          */
+    int32_t *fill;        /* [K]   samples currently held per class              */
+    int64_t *buf_y;       /* [K*S] label of each slot, -1 while never written    */
+    unsigned char **rows; /* [K*S] sample bytes of each slot, NULL until written */
+    uint32_t flags;       /* bit 0: a candidate carried a label outside [0,K)    */
+    int64_t last_n;       /* representatives handed out by the last sampling     */
+    /* record of the last calls, for tests that inspect the decisions */
+    int64_t n_ins;        /* insertions performed by the last update             */
+    int64_t *ins_pos;     /* [c] mini-batch position of each insertion           */
+    int64_t *ins_class;   /* [c] its class                                       */
+    int64_t *ins_slot;    /* [c] the slot it went to                             */
+    int64_t *smp_g;       /* [last_n] index, among the filled slots in class-major order, of each representative */
+    int64_t cap_ins, cap_smp;
+} rbo_buffer;
+
+rbo_buffer *rbo_create(int64_t classes, int64_t slots_per_class, int64_t row_bytes)
+{
+    if (classes < 1 || slots_per_class < 1 || row_bytes < 1) return NULL;
+    rbo_buffer *rb = (rbo_buffer *)calloc(1, sizeof *rb);
+    if (!rb) return NULL;
+    rb->K = classes; rb->S = slots_per_class; rb->row_bytes = row_bytes;
+    size_t slots = (size_t)classes * (size_t)slots_per_class;
+    rb->fill = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
+    rb->buf_y = (int64_t *)malloc(slots * sizeof(int64_t));
+    rb->rows = (unsigned char **)calloc(slots, sizeof(unsigned char *));
+    if (!rb->fill || !rb->buf_y || !rb->rows) { free(rb->fill); free(rb->buf_y); free(rb->rows); free(rb); return NULL; }
+    for (size_t i = 0; i < slots; ++i) rb->buf_y[i] = -1;
+    return rb;
+}
+
+void rbo_destroy(rbo_buffer *rb)
+{
+    if (!rb) return;
+    size_t slots = (size_t)rb->K * (size_t)rb->S;
+    for (size_t i = 0; i < slots; ++i) free(rb->rows[i]);
+    free(rb->rows); free(rb->buf_y); free(rb->fill);
+    free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot); free(rb->smp_g);
+    free(rb);
+}
+
+static int cmp_i64(const void *a, const void *b)
+{
+    int64_t x = *(const int64_t *)a, y = *(const int64_t *)b;
+    return (x > y) - (x < y);
+}
+
+/*
+ * Algorithm 1, update_buffer(m).  batch_x: b rows of row_bytes; batch_y: b
+ * labels.  Returns 0, or -1 on invalid arguments / out of memory.
+ */
+int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
+               int64_t b, int64_t c, uint64_t seed, uint64_t step)
+{
+    if (!rb || !batch_x || !batch_y || b < 1 || c < 0 || c > b) return -1;
+    if (c > rb->cap_ins) {
+        free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot);
+        rb->ins_pos = (int64_t *)malloc((size_t)c * sizeof(int64_t));
+        rb->ins_class = (int64_t *)malloc((size_t)c * sizeof(int64_t));
+        rb->ins_slot = (int64_t *)malloc((size_t)c * sizeof(int64_t));
+        rb->cap_ins = c;
+        if (!rb->ins_pos || !rb->ins_class || !rb->ins_slot) return -1;
+    }
+    rb->n_ins = 0;
+    if (c == 0) return 0;
+
+    /* "C <- select c random candidates from mini-batch m": a uniform c-subset
+     * of the b positions. */
+    int64_t *cand = (int64_t *)malloc((size_t)c * sizeof(int64_t));
+    if (!cand) return -1;
+    rbo_floyd(seed, step, RBO_SELECT, b, c, cand);
+
+    /* "for c in C": visited in ascending mini-batch position. */
+    qsort(cand, (size_t)c, sizeof(int64_t), cmp_i64);
+
+    const unsigned char *src = (const unsigned char *)batch_x;
+    for (int64_t q = 0; q < c; ++q) {
+        int64_t pos = cand[q];
+        int64_t k = batch_y[pos];
+        if (k < 0 || k >= rb->K) { rb->flags |= 1u; continue; }
+        int64_t s;
+        if (rb->fill[k] >= rb->S) {
+            /* "replace a random representative from R^i_n": every slot of the
+             * class equally likely, whatever its age. */
+            s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)rb->S);
+        } else {
+            /* "append c to R^i_n" */
+            s = rb->fill[k];
+            rb->fill[k] += 1;
+        }
+        size_t slot = (size_t)k * (size_t)rb->S + (size_t)s;
+        if (!rb->rows[slot]) {
+            rb->rows[slot] = (unsigned char *)malloc((size_t)rb->row_bytes);
+            if (!rb->rows[slot]) { free(cand); return -1; }
+        }
+        memcpy(rb->rows[slot], src + (size_t)pos * (size_t)rb->row_bytes, (size_t)rb->row_bytes);
+        rb->buf_y[slot] = k;
+        rb->ins_pos[rb->n_ins] = pos; rb->ins_class[rb->n_ins] = k; rb->ins_slot[rb->n_ins] = s;
+        rb->n_ins += 1;
+    }
+    free(cand);
+    return 0;
+}
+
+/*
+ * Mini-batch augmentation: draw n = min(r, F) representatives uniformly and
+ * without replacement from the F stored samples and copy them (and their
+ * labels) to out_x / out_y; out_y[j] = -1 for n <= j < r, the matching out_x
+ * rows are left alone.  Returns n, or -1 on invalid arguments.
+ */
+int64_t rbo_sample_augment(rbo_buffer *rb, int64_t r, uint64_t seed, uint64_t step,
+                           void *out_x, int64_t *out_y)
+{
+    if (!rb || r < 0 || (r > 0 && (!out_x || !out_y))) return -1;
+    int64_t F = 0;
+    for (int64_t k = 0; k < rb->K; ++k) F += rb->fill[k];
+    int64_t n = r < F ? r : F;
+    if (n > rb->cap_smp) {
+        free(rb->smp_g);
+        rb->smp_g = (int64_t *)malloc((size_t)n * sizeof(int64_t));
+        rb->cap_smp = n;
+        if (!rb->smp_g) return -1;
+    }
+    rb->last_n = n;
+    if (n > 0) rbo_floyd(seed, step, RBO_SAMPLE, F, n, rb->smp_g);
+
+    unsigned char *dst = (unsigned char *)out_x;
+    for (int64_t j = 0; j < n; ++j) {
+        /* the g-th stored sample, counting class 0's slots first, then class
+         * 1's, ... (a fuller class is therefore drawn more often). */
+        int64_t g = rb->smp_g[j], k = 0;
+        while (g >= rb->fill[k]) { g -= rb->fill[k]; ++k; }
+        size_t slot = (size_t)k * (size_t)rb->S + (size_t)g;
+        memcpy(dst + (size_t)j * (size_t)rb->row_bytes, rb->rows[slot], (size_t)rb->row_bytes);
+        out_y[j] = k;
+    }
+    for (int64_t j = n; j < r; ++j) out_y[j] = -1;
+    return n;
+}
+
+/* ------------------------------------------------------------------------ */
+/* Read-only access for the tests                                            */
+/* ------------------------------------------------------------------------ */
+const int32_t *rbo_fill(const rbo_buffer *rb) { return rb->fill; }
+const int64_t *rbo_buf_y(const rbo_buffer *rb) { return rb->buf_y; }
+uint32_t rbo_flags(const rbo_buffer *rb) { return rb->flags; }
+int64_t rbo_last_n(const rbo_buffer *rb) { return rb->last_n; }
+int64_t rbo_n_inserted(const rbo_buffer *rb) { return rb->n_ins; }
+const int64_t *rbo_ins_pos(const rbo_buffer *rb) { return rb->ins_pos; }
+const int64_t *rbo_ins_class(const rbo_buffer *rb) { return rb->ins_class; }
+const int64_t *rbo_ins_slot(const rbo_buffer *rb) { return rb->ins_slot; }
+const int64_t *rbo_sampled_g(const rbo_buffer *rb) { return rb->smp_g; }
+
+/* Sample bytes of slot s of class k, or NULL while that slot was never written. */
+const void *rbo_row(const rbo_buffer *rb, int64_t k, int64_t s)
+{
+    if (k < 0 || k >= rb->K || s < 0 || s >= rb->S) return NULL;
+    return rb->rows[(size_t)k * (size_t)rb->S + (size_t)s];
+}
+
+/* Copy slots [first, first+count) (flat index k*S+s) into dst, row after row;
+ * never-written slots are filled with zero bytes. */
+void rbo_export_rows(const rbo_buffer *rb, int64_t first, int64_t count, void *dst)
+{
+    unsigned char *d = (unsigned char *)dst;
+    for (int64_t i = 0; i < count; ++i) {
+        const unsigned char *src = rb->rows[(size_t)(first + i)];
+        if (src) memcpy(d + (size_t)i * (size_t)rb->row_bytes, src, (size_t)rb->row_bytes);
+        else memset(d + (size_t)i * (size_t)rb->row_bytes, 0, (size_t)rb->row_bytes);
+    }
+}
