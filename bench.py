@@ -1,0 +1,333 @@
+#!/usr/bin/env python3
+"""Benchmark of the rehearsal-buffer hot path on one MI355X.
+
+A step is one rb_update + one rb_sample_augment on one mini-batch of synthetic
+input that is already resident in HBM.  Prints ONE JSON line: augmented
+samples/s of the whole job, the HBM roofline of the dominant kernel, and the
+CPU oracle timed on the host beside it.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--prefill]
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this much memory (>> 256 MB of last-level cache)
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+class Rig:
+    """Device-side state of one workload: the buffer, a side stream and a rotating pool of augmented batches."""
+
+    def __init__(self, w, torch, rb, wl, pool_slots=None):
+        self.w, self.torch, self.rb = w, torch, rb
+        self.dev = torch.device("cuda:0")
+        self.stream = torch.cuda.Stream(self.dev)
+        self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream)
+        aug_bytes = (w.b + w.r) * w.row_bytes
+        self.P = pool_slots or max(8, -(-POOL_BYTES // aug_bytes))
+        self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
+        self.aug_y = torch.empty((self.P, w.b + w.r), dtype=torch.int64, device=self.dev)
+        # distinct sample bytes for a few slots, replicated over the pool (generation is not what is measured);
+        # labels are generated for every slot, they drive the plan.
+        distinct = min(self.P, 4)
+        for i in range(distinct):
+            self.aug_x[i, :w.b].copy_(wl.make_samples(w, i, self.dev))
+        for i in range(distinct, self.P):
+            self.aug_x[i, :w.b].copy_(self.aug_x[i % distinct, :w.b])
+        for i in range(self.P):
+            self.aug_y[i, :w.b].copy_(wl.make_labels(w, i, self.dev))
+        self.aug_x[:, w.b:].zero_()
+        self.aug_y[:, w.b:].fill_(-1)
+        torch.cuda.synchronize()
+        rs = w.row_bytes
+        self.args = []
+        for i in range(self.P):
+            bx, by = self.aug_x[i].data_ptr(), self.aug_y[i].data_ptr()
+            self.args.append((bx, by, bx + w.b * rs, by + w.b * 8))
+        self.step = 0
+
+    def prefill(self):
+        """Fill every slot: updates with c = b and round-robin labels until F = K*S."""
+        w, torch = self.w, self.torch
+        h = self.buf.handle
+        y = torch.empty(w.b, dtype=torch.int64, device=self.dev)
+        total = w.K * w.S
+        done = 0
+        with torch.cuda.stream(self.stream):
+            while done < total + w.b:
+                y.copy_((torch.arange(w.b, device=self.dev) + done) % w.K)
+                rc = self.rb.rb_update(h, self.args[0][0], y, w.b, w.b, 12345, 1 << 40 | done)
+                assert rc == 0, rc
+                done += w.b
+        self.stream.synchronize()
+        fill, _, _ = self.buf.read_state()
+        assert int(fill.sum()) == total, (int(fill.sum()), total)
+
+    def enqueue(self, n, do_update=True, do_sample=True):
+        """Enqueue n consecutive steps on the side stream (no synchronisation)."""
+        w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
+        upd, smp = rb.rb_update, rb.rb_sample_augment
+        b, c, r, seed = w.b, w.c, w.r, w.lib_seed
+        t = self.step
+        for _ in range(n):
+            bx, by, ox, oy = args[t % P]
+            if do_update:
+                rc = upd(h, bx, by, b, c, seed, t)
+                if rc:
+                    raise RuntimeError(f"rb_update -> {rc}")
+            if do_sample:
+                rc = smp(h, r, seed, t, ox, oy)
+                if rc:
+                    raise RuntimeError(f"rb_sample_augment -> {rc}")
+            t += 1
+        self.step = t
+
+    def timed(self, n, **kw):
+        """ms per step over n steps enqueued back to back, HIP events on the side stream."""
+        torch = self.torch
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(self.stream)
+        self.enqueue(n, **kw)
+        e1.record(self.stream)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    def kernel_ms(self, n, which):
+        """Average duration of one kernel: an event pair around each of n launches, inside a normal step sequence."""
+        torch = self.torch
+        w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
+        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
+        torch.cuda.synchronize()
+        t = self.step
+        for i in range(n):
+            bx, by, ox, oy = args[t % P]
+            if which == "update":
+                ev[i][0].record(self.stream)
+            rc = rb.rb_update(h, bx, by, w.b, w.c, w.lib_seed, t)
+            assert rc == 0
+            if which == "update":
+                ev[i][1].record(self.stream)
+            else:
+                ev[i][0].record(self.stream)
+            rc = rb.rb_sample_augment(h, w.r, w.lib_seed, t, ox, oy)
+            assert rc == 0
+            if which == "sample":
+                ev[i][1].record(self.stream)
+            t += 1
+        self.step = t
+        torch.cuda.synchronize()
+        times = sorted(a.elapsed_time(b) for a, b in ev)
+        return sum(times) / n, times[n // 2]
+
+    def close(self):
+        self.buf.close()
+        del self.aug_x, self.aug_y, self.buf
+        self.torch.cuda.empty_cache()
+
+
+def copy_ceiling(torch, rb, nbytes=1 << 30, reps=20):
+    """GB/s (read + write) of a plain large device copy with the mover's inner loop."""
+    src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
+    src.fill_(1)
+    best = 0.0
+    for unroll in (2, 4, 8):
+        for nt in (0, 1):
+            for _ in range(3):
+                rb.rb_copy_bytes(None, dst, src, nbytes, unroll, nt)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            torch.cuda.synchronize()
+            e0.record()
+            for _ in range(reps):
+                rb.rb_copy_bytes(None, dst, src, nbytes, unroll, nt)
+            e1.record()
+            torch.cuda.synchronize()
+            gbs = 2 * nbytes * reps / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            best = max(best, gbs)
+    del src, dst
+    torch.cuda.empty_cache()
+    return best
+
+
+def overlap_leg(rig, steps, target_ms):
+    """Steps of the asynchronous pipeline of Sec. IV-D: buffer work on the side stream under a stand-in
+    compute kernel on the main stream.  Returns ms per iteration: compute alone, buffer alone, both."""
+    torch, rb, w = rig.torch, rig.rb, rig.w
+    main = torch.cuda.current_stream(rig.dev)
+    blocks = 256 * 8
+    sink = torch.empty(blocks * 256, dtype=torch.float32, device=rig.dev)
+
+    def compute_ms(iters, n=5):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record(main)
+        for _ in range(n):
+            rb.rb_standin_compute(None, sink, blocks, iters)
+        e1.record(main)
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    compute_ms(1000)
+    iters = max(1, int(20000 * target_ms / compute_ms(20000)))
+    t_compute = compute_ms(iters, steps)
+    t_rb = rig.timed(steps)
+    done = [torch.cuda.Event() for _ in range(4)]
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record(main)
+    for t in range(steps):
+        if t > 0:
+            main.wait_event(done[(t - 1) % 4])        # (1) representatives sampled during the previous iteration
+        rig.enqueue(1)                                 # (2) update with this mini-batch, then sample the next representatives
+        done[t % 4].record(rig.stream)
+        rb.rb_standin_compute(None, sink, blocks, iters)   # (3), (4) forward and backward pass stand-in
+    main.wait_event(done[(steps - 1) % 4])
+    e1.record(main)
+    torch.cuda.synchronize()
+    t_both = e0.elapsed_time(e1) / steps
+    return {"compute_ms": round(t_compute, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
+            "overhead_frac": round((t_both - t_compute) / t_compute, 4)}
+
+
+def cpu_baseline(w, wl, budget_s=12.0, max_steps=4000):
+    """The CPU oracle on the same workload from an empty buffer, host batches cycled from a small pool."""
+    from oracle import rbo
+    import numpy as np
+    pool = []
+    for i in range(3):
+        x, y = wl.make_batch(w, i)
+        pool.append((wl.as_row_bytes(x), y.numpy()))
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    out = np.zeros((w.r, w.row_bytes), dtype=np.uint8)
+    t0 = time.perf_counter()
+    steps = 0
+    while steps < max_steps:
+        x, y = pool[steps % len(pool)]
+        orc.update(x, y, w.c, w.lib_seed, steps)
+        orc.sample_augment(w.r, w.lib_seed, steps, out_x=out)
+        steps += 1
+        if steps % 10 == 0 and time.perf_counter() - t0 > budget_s:
+            break
+    dt = time.perf_counter() - t0
+    orc.close()
+    return {"value": round((w.b + w.r) * steps / dt, 1), "unit": "augmented samples/s", "cores": 1, "kind": "oracle",
+            "sample": f"first {steps} steps of {w.name} from an empty buffer, {dt:.1f} s, host batches cycled from a pool of {len(pool)}",
+            "ms_per_step": round(dt / steps * 1e3, 4),
+            "gb_per_s": round(w.bytes_per_step() * steps / dt / 1e9, 3)}
+
+
+def measure(w, torch, rb, wl, steps, warmup, prefill, kernel_launches=200):
+    rig = Rig(w, torch, rb, wl)
+    if prefill:
+        rig.prefill()
+    rig.enqueue(warmup)
+    torch.cuda.synchronize()
+    ms = rig.timed(steps)
+    ms_update = rig.timed(min(steps, 500), do_sample=False)
+    # the sample-only loop re-reads the same buffer state; rows come from the whole buffer
+    ms_sample = rig.timed(min(steps, 500), do_update=False)
+    k_sample_avg, k_sample_med = rig.kernel_ms(kernel_launches, "sample")
+    k_update_avg, k_update_med = rig.kernel_ms(kernel_launches, "update")
+    fill, last_n, flags = rig.buf.read_state()
+    res = {
+        "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
+        "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
+        "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "update_only_ms": ms_update, "sample_only_ms": ms_sample,
+        "sample_kernel_ms_event_avg": k_sample_avg, "sample_kernel_ms_event_med": k_sample_med,
+        "update_kernel_ms_event_avg": k_update_avg, "update_kernel_ms_event_med": k_update_med,
+        "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
+    }
+    return rig, res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=100)
+    ap.add_argument("--workload", default="C4")
+    ap.add_argument("--prefill", action="store_true", help="fill every slot before timing (all inserts replace)")
+    ap.add_argument("--others", default="C3,C5", help="comma list of further workloads reported inside the line ('' = none)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-overlap", action="store_true")
+    ap.add_argument("--unroll", type=int, default=0)
+    ap.add_argument("--nontemporal", type=int, default=1)
+    a = ap.parse_args()
+    if a.gpus != 1:
+        sys.exit("bench.py: this build covers one GPU's local buffer only (no collectives); run with --gpus 1")
+
+    import torch
+    import rb_workloads as wl
+    import paper_2406_03285_amd as rb
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; there is no CPU path")
+
+    def tune(rig):
+        rig.buf.set_option(rb.RB_OPT_UNROLL, a.unroll)
+        rig.buf.set_option(rb.RB_OPT_NONTEMPORAL, a.nontemporal)
+
+    w = wl.by_name(a.workload)
+    log(f"[bench] {w.name}: buffer {w.buffer_bytes / 1e9:.1f} GB, {w.bytes_per_step() / 1e6:.2f} MB/step")
+    ceiling = copy_ceiling(torch, rb)
+    log(f"[bench] plain copy ceiling {ceiling:.0f} GB/s")
+    rig, res = measure(w, torch, rb, wl, a.steps, a.warmup, a.prefill)
+    log(f"[bench] {json.dumps(res)}")
+    pre = None
+    if not a.prefill:
+        rig.close()
+        rig, pre = measure(w, torch, rb, wl, min(a.steps, 500), a.warmup, True)
+        log(f"[bench] prefilled {json.dumps(pre)}")
+    rig.close()
+
+    others = {}
+    for name in [s for s in a.others.split(",") if s]:
+        ow = wl.by_name(name)
+        orig, ores = measure(ow, torch, rb, wl, min(a.steps, ow.steps), a.warmup, False)
+        if ow.name.startswith("C3") and not a.no_overlap:
+            ores["overlap"] = {f"{d}ms": overlap_leg(orig, 200, d) for d in (0.5, 2.0, 10.0)}
+        orig.close()
+        others[ow.name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in ores.items()}
+        log(f"[bench] {json.dumps(others[ow.name])}")
+
+    # roofline of the dominant kernel: the gather of rb_sample_augment moves r rows, read once and written once
+    k_ms = res["sample_kernel_ms_event_avg"]
+    n_rows = min(w.r, res["last_n"])
+    achieved = 2 * n_rows * w.row_bytes / (k_ms * 1e-3) / 1e9
+    line = {
+        "metric": "augmented samples/sec and achieved HBM GB/s (% of peak) per update+sample step",
+        "value": round(res["aug_samples_per_s"], 1), "unit": "augmented samples/s",
+        "n_gpus": 1, "steps": a.steps, "warmup": a.warmup, "ms_per_step": round(res["ms_per_step"], 5),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
+        "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
+                   "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
+                   "stream": "side stream, inputs resident in HBM, pool rotation"},
+        "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
+        "reps_per_s": round(res["reps_per_s"], 1),
+        "roofline": {"bound": "hbm", "kernel": "rb_sample_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "bytes_per_launch": 2 * n_rows * w.row_bytes, "kernel_ms": round(k_ms, 5),
+                     "copy_ceiling_gbs": round(ceiling, 1)},
+        "detail": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()},
+        "prefilled": None if pre is None else {k: (round(v, 5) if isinstance(v, float) else v) for k, v in pre.items()},
+        "others": others,
+    }
+    if not a.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(w, wl)
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,165 @@
+/*
+ * rb.h -- C ABI of the per-GPU rehearsal buffer (gfx950 / MI355X).
+ *
+ * One process's local rehearsal buffer B_n of the paper "Efficient
+ * Data-Parallel Continual Learning with Asynchronous Distributed Rehearsal
+ * Buffers": one sub-buffer R^i_n per class, all of equal capacity (Sec. IV-A),
+ * populated by Algorithm 1 (Sec. IV-B) and read by uniform sampling without
+ * replacement to augment the next mini-batch (Sec. IV-C, Listing 1).  The
+ * paper keeps the buffer in pinned host memory and hides its management on
+ * background threads (Sec. IV-D, Sec. V); here the buffer lives in HBM and the
+ * two hot calls only enqueue kernels on a caller-supplied HIP stream.
+ *
+ * Conventions
+ *   - "device" pointers are HIP device memory of the current device, "host"
+ *     pointers ordinary host memory.  The library never allocates or frees
+ *     device memory: buffer storage, workspace, mini-batches and outputs are
+ *     all owned by the caller and only borrowed for the duration stated.
+ *   - Samples are opaque rows of row_bytes = prod(sample_shape) * sizeof(dtype)
+ *     bytes; row_bytes must be a multiple of 16 and every sample pointer
+ *     16-byte aligned.  Slot s of class k is row k*slots_per_class + s of
+ *     buf_x / element k*slots_per_class + s of buf_y.
+ *   - Labels are int64.  A never-written slot has buf_y = -1 and unspecified
+ *     sample bytes.
+ *   - Every random choice is a pure function of (seed, step, purpose, index)
+ *     through Philox4x32-10, so a (seed, step) pair always reproduces the same
+ *     decisions; the caller advances step once per training iteration.
+ *   - rb_update and rb_sample_augment validate what the host can see, enqueue
+ *     on the bound stream and return without synchronising.  Work is ordered
+ *     by that stream: update(t), sample(t), update(t+1), ...  Calls on one
+ *     handle must not be issued from two host threads at once.
+ *   - All functions return RB_OK (0) or a negative rb_status; nothing aborts
+ *     or throws.  On an error no kernel was enqueued by that call.
+ */
+#ifndef RB_H
+#define RB_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rb_buffer rb_buffer;   /* opaque host-side handle */
+
+enum rb_dtype { RB_F32 = 0, RB_BF16 = 1 };   /* only fixes the element size: 4 or 2 bytes */
+
+enum rb_status {
+    RB_OK = 0,
+    RB_EINVAL = -1,   /* an argument is out of range, null or misaligned          */
+    RB_ENOMEM = -2,   /* host allocation of the handle failed                     */
+    RB_ESTATE = -3,   /* hot call before rb_bind                                  */
+    RB_EHIP = -4      /* a HIP call (launch, copy, synchronise) reported an error */
+};
+
+#define RB_MAX_BATCH 4096          /* largest b, c and r accepted                          */
+#define RB_MAX_CLASSES (1 << 20)   /* largest number of classes                            */
+#define RB_MAX_SLOTS 2147483647LL  /* classes * slots_per_class must not exceed this       */
+#define RB_FLAG_BAD_LABEL 1u       /* state flag: a candidate's label was outside [0, K)   */
+
+/*
+ * Describe a buffer of `classes` sub-buffers of `slots_per_class` samples each
+ * (Sec. IV-A: the per-process space is divided evenly between the classes; the
+ * capacity |R^i_n|max is given directly, in samples).  sample_shape: host
+ * array of ndim >= 1 positive extents.  Host-only: touches no device.
+ * RB_EINVAL: null out/shape, classes < 1 or > RB_MAX_CLASSES, slots < 1,
+ * classes*slots > RB_MAX_SLOTS, ndim < 1, non-positive extent, unknown dtype,
+ * row_bytes not a multiple of 16.
+ */
+int rb_create(rb_buffer **out, int64_t classes, int64_t slots_per_class,
+              const int64_t *sample_shape, int32_t ndim, int32_t dtype);
+
+/* Bytes the caller must provide to rb_bind: sample storage, label storage,
+ * workspace (per-class fill counts and their partial sums, state words).  Any
+ * of the three out pointers may be null. */
+int rb_query_sizes(const rb_buffer *rb, size_t *x_bytes, size_t *y_bytes, size_t *workspace_bytes);
+
+/*
+ * Attach device storage and a stream (hipStream_t, null = the default stream)
+ * and enqueue the reset of the buffer to "empty": fill counts 0, buf_y = -1;
+ * buf_x is not touched.  buf_x (16-byte aligned), buf_y and workspace (256-byte
+ * aligned) are device pointers of at least the rb_query_sizes sizes and stay
+ * borrowed until rb_destroy or the next rb_bind.  Binding again resets again.
+ */
+int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *hip_stream);
+
+/* Replace the stream later calls enqueue on.  The caller orders the old and
+ * the new stream itself (events) if work is still pending on the old one. */
+int rb_set_stream(rb_buffer *rb, void *hip_stream);
+
+/*
+ * Algorithm 1, update_buffer(m), for the mini-batch m = (batch_x, batch_y) of
+ * b samples (device pointers; batch_x 16-byte aligned, b rows of row_bytes):
+ *   1. C <- a uniformly random subset of exactly c of the b positions;
+ *   2. for every candidate of C in ascending mini-batch position, with class
+ *      k = batch_y[pos]: if R^k_n holds fewer than slots_per_class samples,
+ *      append; otherwise overwrite a slot of R^k_n drawn uniformly from all
+ *      its slots.  If several candidates of one step end on the same slot, the
+ *      one latest in the mini-batch is what the slot holds afterwards.
+ * A candidate whose label is outside [0, classes) is dropped and sets
+ * RB_FLAG_BAD_LABEL.  c = 0 is a no-op.  batch_x / batch_y must stay valid and
+ * unchanged until the enqueued work has run.
+ * RB_EINVAL: null pointers, b < 1, b > RB_MAX_BATCH, c < 0, c > b,
+ * misaligned batch_x / batch_y.  RB_ESTATE: not bound.
+ */
+int rb_update(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
+              int64_t b, int64_t c, uint64_t seed, uint64_t step);
+
+/*
+ * Mini-batch augmentation (Sec. IV-C; the `r = update(m); concat(m, r)` of
+ * Listing 1): draw n = min(r, F) representatives uniformly without
+ * replacement from the F samples currently stored (every stored sample equally
+ * likely, whatever its class) and copy sample j to row j of out_x and its
+ * label to out_y[j]; out_y[j] = -1 for n <= j < r and those out_x rows are not
+ * written.  out_x (16-byte aligned, r rows) and out_y (r labels) are device
+ * pointers; pointing out_x at row b of a (b+r)-row tensor whose first b rows
+ * hold the mini-batch yields the augmented mini-batch without another copy.
+ * r = 0 is a no-op.  RB_EINVAL: r < 0, r > RB_MAX_BATCH, null or misaligned
+ * outputs with r > 0.  RB_ESTATE: not bound.
+ */
+int rb_sample_augment(rb_buffer *rb, int64_t r, uint64_t seed, uint64_t step,
+                      void *out_x, int64_t *out_y);
+
+/*
+ * Synchronise the bound stream and copy state to the host: fill_host[classes]
+ * (samples held per class), *last_n_host (n of the latest rb_sample_augment),
+ * *flags_host (RB_FLAG_*).  Any pointer may be null.  Not for the hot path.
+ */
+int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint32_t *flags_host);
+
+/* Launch-shape knobs for measurement sweeps.  RB_OPT_UNROLL: 16-byte vectors a
+ * thread keeps in flight while moving a row (0 = automatic, else 1, 2, 4 or 8).
+ * RB_OPT_NONTEMPORAL: 1 (default) moves rows with streaming loads/stores, 0
+ * with plain ones.  RB_OPT_ROWS_PER_BLOCK: rows one workgroup moves one after
+ * the other when a row fits a single tile (0 = automatic, else 1..16). */
+enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2 };
+int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
+
+/* Free the host handle.  Device memory stays the caller's. */
+int rb_destroy(rb_buffer *rb);
+
+/* Static description of an rb_status. */
+const char *rb_strerror(int status);
+
+/* ---- measurement helpers (not part of the method) ----------------------- */
+
+/*
+ * Stand-in for the training computation that buffer management overlaps with
+ * (Sec. IV-D): a register-only multiply-add loop of `iters` iterations on
+ * `blocks` workgroups of 256 threads; every thread writes one float to
+ * sink[blocks*256] (device) so the loop is not optimised away.
+ */
+int rb_standin_compute(void *hip_stream, float *sink, int64_t blocks, int64_t iters);
+
+/*
+ * Plain contiguous device-to-device copy of `bytes` (multiple of 16, both
+ * pointers 16-byte aligned) with the same per-thread inner loop the row mover
+ * uses: the practical ceiling of that loop, and an HBM-bound stand-in load.
+ */
+int rb_copy_bytes(void *hip_stream, void *dst, const void *src, size_t bytes, int32_t unroll, int32_t nontemporal);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RB_H */

@@ -1,0 +1,201 @@
+"""Thin ctypes binding of the C ABI in include/rb.h (argument marshalling only).
+
+Every function has the name and argument order of its C counterpart; tensors
+are passed as device pointers.  PyTorch is used for device memory and streams
+only.  There is no fallback: if librb.so is missing the import fails.
+"""
+import ctypes as C
+import os
+
+import torch  # first: the library must bind to the HIP runtime PyTorch has loaded
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "librb.so")
+
+RB_F32, RB_BF16 = 0, 1
+RB_OK, RB_EINVAL, RB_ENOMEM, RB_ESTATE, RB_EHIP = 0, -1, -2, -3, -4
+RB_MAX_BATCH = 4096
+RB_MAX_CLASSES = 1 << 20
+RB_FLAG_BAD_LABEL = 1
+RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK = 0, 1, 2
+
+EXPORTS = (
+    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_stream", "rb_update", "rb_sample_augment",
+    "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
+)
+
+
+class RbError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        super().__init__(f"{where}: {rb_strerror(status)} ({status})")
+
+
+def _load():
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(
+            f"{LIB_PATH} is missing: build it with `python -m paper_2406_03285_amd.build` "
+            "(there is no fallback path)")
+    L = C.CDLL(LIB_PATH)
+    vp, i64, u64, i32, sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_int32, C.c_size_t
+    L.rb_create.argtypes = [C.POINTER(vp), i64, i64, C.POINTER(i64), i32, i32]
+    L.rb_query_sizes.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
+    L.rb_bind.argtypes = [vp, vp, vp, vp, vp]
+    L.rb_set_stream.argtypes = [vp, vp]
+    L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
+    L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
+    L.rb_read_state.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(C.c_uint32)]
+    L.rb_set_option.argtypes = [vp, i32, i64]
+    L.rb_destroy.argtypes = [vp]
+    L.rb_strerror.argtypes = [C.c_int]
+    L.rb_strerror.restype = C.c_char_p
+    L.rb_standin_compute.argtypes = [vp, vp, i64, i64]
+    L.rb_copy_bytes.argtypes = [vp, vp, vp, sz, i32, i32]
+    for name in EXPORTS:
+        if name != "rb_strerror":
+            getattr(L, name).restype = C.c_int
+    return L
+
+
+_L = _load()
+
+
+def _ptr(t):
+    """Device (or null) pointer of a tensor / int / None."""
+    if t is None:
+        return None
+    if isinstance(t, int):
+        return t
+    return t.data_ptr()
+
+
+def _stream(s):
+    if s is None:
+        return None
+    if isinstance(s, int):
+        return s or None
+    return s.cuda_stream or None
+
+
+def rb_strerror(status):
+    return _L.rb_strerror(int(status)).decode()
+
+
+def rb_create(classes, slots_per_class, sample_shape, dtype):
+    h = C.c_void_p()
+    shape = (C.c_int64 * len(sample_shape))(*[int(v) for v in sample_shape])
+    rc = _L.rb_create(C.byref(h), int(classes), int(slots_per_class), shape, len(sample_shape), int(dtype))
+    return rc, h.value
+
+
+def rb_query_sizes(rb):
+    x, y, w = C.c_size_t(), C.c_size_t(), C.c_size_t()
+    rc = _L.rb_query_sizes(rb, C.byref(x), C.byref(y), C.byref(w))
+    return rc, x.value, y.value, w.value
+
+
+def rb_bind(rb, buf_x, buf_y, workspace, hip_stream=None):
+    return _L.rb_bind(rb, _ptr(buf_x), _ptr(buf_y), _ptr(workspace), _stream(hip_stream))
+
+
+def rb_set_stream(rb, hip_stream):
+    return _L.rb_set_stream(rb, _stream(hip_stream))
+
+
+def rb_update(rb, batch_x, batch_y, b, c, seed, step):
+    return _L.rb_update(rb, _ptr(batch_x), _ptr(batch_y), int(b), int(c), int(seed), int(step))
+
+
+def rb_sample_augment(rb, r, seed, step, out_x, out_y):
+    return _L.rb_sample_augment(rb, int(r), int(seed), int(step), _ptr(out_x), _ptr(out_y))
+
+
+def rb_read_state(rb, classes):
+    """Returns (status, fill [classes] int32 numpy array, last_n, flags)."""
+    import numpy as np
+    fill = np.zeros(int(classes), dtype=np.int32)
+    n, fl = C.c_int64(), C.c_uint32()
+    rc = _L.rb_read_state(rb, fill.ctypes.data, C.byref(n), C.byref(fl))
+    return rc, fill, n.value, fl.value
+
+
+def rb_set_option(rb, option, value):
+    return _L.rb_set_option(rb, int(option), int(value))
+
+
+def rb_destroy(rb):
+    return _L.rb_destroy(rb)
+
+
+def rb_standin_compute(hip_stream, sink, blocks, iters):
+    return _L.rb_standin_compute(_stream(hip_stream), _ptr(sink), int(blocks), int(iters))
+
+
+def rb_copy_bytes(hip_stream, dst, src, nbytes, unroll=4, nontemporal=1):
+    return _L.rb_copy_bytes(_stream(hip_stream), _ptr(dst), _ptr(src), int(nbytes), int(unroll), int(nontemporal))
+
+
+def _check(rc, where):
+    if rc != RB_OK:
+        raise RbError(rc, where)
+
+
+class RehearsalBuffer:
+    """Owns the device tensors of one buffer and forwards to the C ABI.
+
+    Convenience only: allocates buf_x / buf_y / workspace with PyTorch, keeps the
+    handle, raises RbError on a non-zero status.  All work is done by the library.
+    """
+
+    def __init__(self, classes, slots_per_class, sample_shape, dtype=torch.float32, device="cuda:0", stream=None):
+        code = {torch.float32: RB_F32, torch.bfloat16: RB_BF16}[dtype]
+        rc, self.handle = rb_create(classes, slots_per_class, tuple(sample_shape), code)
+        _check(rc, "rb_create")
+        self.K, self.S, self.sample_shape, self.dtype = int(classes), int(slots_per_class), tuple(sample_shape), dtype
+        rc, xb, yb, wb = rb_query_sizes(self.handle)
+        _check(rc, "rb_query_sizes")
+        self.row_bytes = xb // (self.K * self.S)
+        self.device = torch.device(device)
+        self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, device=self.device)
+        self.buf_y = torch.empty((self.K, self.S), dtype=torch.int64, device=self.device)
+        self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
+        assert self.buf_x.numel() * self.buf_x.element_size() == xb and self.buf_y.numel() * 8 == yb
+        self.stream = stream
+        _check(rb_bind(self.handle, self.buf_x, self.buf_y, self.workspace, stream), "rb_bind")
+
+    def set_stream(self, stream):
+        self.stream = stream
+        _check(rb_set_stream(self.handle, stream), "rb_set_stream")
+
+    def update(self, batch_x, batch_y, c, seed, step):
+        assert batch_x.is_contiguous() and batch_y.is_contiguous() and batch_y.dtype == torch.int64
+        assert batch_x.dtype == self.dtype and tuple(batch_x.shape[1:]) == self.sample_shape
+        assert batch_x.device == self.device and batch_y.device == self.device
+        b = batch_y.shape[0]
+        assert batch_x.shape[0] == b
+        _check(rb_update(self.handle, batch_x, batch_y, b, c, seed, step), "rb_update")
+
+    def sample_augment(self, r, seed, step, out_x, out_y):
+        """out_x: [>= r, *sample_shape] contiguous, out_y: [>= r] int64; typically the tail of a (b+r)-row batch."""
+        if r > 0:
+            assert out_x.is_contiguous() and out_y.is_contiguous() and out_y.dtype == torch.int64
+            assert out_x.dtype == self.dtype and tuple(out_x.shape[1:]) == self.sample_shape
+            assert out_x.shape[0] >= r and out_y.shape[0] >= r
+            assert out_x.device == self.device and out_y.device == self.device
+        _check(rb_sample_augment(self.handle, r, seed, step, out_x, out_y), "rb_sample_augment")
+
+    def read_state(self):
+        rc, fill, last_n, flags = rb_read_state(self.handle, self.K)
+        _check(rc, "rb_read_state")
+        return fill, last_n, flags
+
+    def set_option(self, option, value):
+        _check(rb_set_option(self.handle, option, value), "rb_set_option")
+
+    def close(self):
+        if getattr(self, "handle", None):
+            rb_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()

@@ -1,0 +1,783 @@
+// Rehearsal-buffer hot path for gfx950 (MI355X): kernels and the C ABI of include/rb.h.
+//
+// One kernel launch per hot call.  Every workgroup first re-derives, in LDS,
+// the few integers of the step's plan it needs (which mini-batch positions are
+// candidates, which slot a candidate goes to, which stored sample a
+// representative is) and then moves its share of one sample row with 16-byte
+// vector loads and stores.  The plan is O(b + K) integers while a row is
+// hundreds of kilobytes, so recomputing it per workgroup is cheaper than a
+// second, dependent launch.  Nothing is staged through LDS: a row is read once
+// and written once, so the data path is global -> registers -> global.
+//
+// Per-class fill counts are kept twice (ping-pong): an update reads the "old"
+// copy everywhere and a few bookkeeping workgroups write the "new" one, so no
+// workgroup can observe a count another workgroup of the same launch changed.
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+#include <cstdlib>
+#include <new>
+
+#include "rb.h"
+
+namespace {
+
+constexpr int TPB = 256;               // threads per workgroup: four 64-wide wavefronts
+constexpr int WAVE = 64;
+constexpr int NWAVE = TPB / WAVE;
+constexpr int CH = 256;                // classes per chunk of the two-level fill index
+constexpr uint32_t PURPOSE_SELECT = 1; // counter word that separates the three kinds of draws
+constexpr uint32_t PURPOSE_EVICT = 2;
+constexpr uint32_t PURPOSE_SAMPLE = 3;
+constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a candidate
+constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
+
+typedef uint32_t vec16 __attribute__((ext_vector_type(4)));   // one 16-byte transfer
+
+// Device-resident state words at the start of the workspace.
+struct DevState {
+    uint32_t flags;
+    uint32_t pad;
+    int64_t last_n;
+};
+constexpr size_t STATE_BYTES = 256;
+
+struct Seed {
+    uint32_t seed_lo, seed_hi, step_lo, step_hi;
+};
+
+// ---------------------------------------------------------------------------
+// Counter-based random draws: Philox4x32-10 (Salmon et al., SC'11).  Counter =
+// (index, purpose, step), key = seed; the low two output words form one 64-bit
+// draw.  An integer in [0, n) is the high half of draw * n.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t draw64(const Seed& sd, uint32_t purpose, uint32_t index)
+{
+    uint32_t x0 = index, x1 = purpose, x2 = sd.step_lo, x3 = sd.step_hi;
+    uint32_t ka = sd.seed_lo, kb = sd.seed_hi;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        const uint32_t ma = 0xD2511F53u, mb = 0xCD9E8D57u;
+        uint32_t a_hi = __umulhi(ma, x0), a_lo = ma * x0;
+        uint32_t b_hi = __umulhi(mb, x2), b_lo = mb * x2;
+        x0 = b_hi ^ x1 ^ ka;
+        x2 = a_hi ^ x3 ^ kb;
+        x1 = b_lo;
+        x3 = a_lo;
+        ka += 0x9E3779B9u;
+        kb += 0xBB67AE85u;
+    }
+    return (uint64_t)x0 | ((uint64_t)x1 << 32);
+}
+
+__device__ __forceinline__ uint64_t below(const Seed& sd, uint32_t purpose, uint32_t index, uint64_t n)
+{
+    return __umul64hi(draw64(sd, purpose, index), n);
+}
+
+// ---------------------------------------------------------------------------
+// Workgroup-wide exclusive prefix sum of one int per thread.  s_wave: NWAVE
+// ints of LDS.  Must be called by all threads of the workgroup.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
+{
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        int up = __shfl_up(inc, d, WAVE);
+        if (lane >= d) inc += up;
+    }
+    if (lane == WAVE - 1) s_wave[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < NWAVE; ++i) {
+        int x = s_wave[i];
+        all += x;
+        if (i < w) before += x;
+    }
+    __syncthreads();
+    total = all;
+    return before + inc - v;
+}
+
+// ---------------------------------------------------------------------------
+// Row mover: the workgroup's tile of one row, U vectors per thread in flight.
+// ---------------------------------------------------------------------------
+template <int U, bool NT>
+struct Tile {
+    vec16 v[U];
+
+    __device__ __forceinline__ void load(const vec16* __restrict__ src, int64_t lo, int64_t hi)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
+            if (i < hi) v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+        }
+    }
+    __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
+            if (i < hi) {
+                if (NT) __builtin_nontemporal_store(v[u], dst + i);
+                else dst[i] = v[u];
+            }
+        }
+    }
+};
+
+// ---------------------------------------------------------------------------
+// Reset: fill counts, partial sums and state words to zero, labels to -1.
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) rb_reset_kernel(uint32_t* __restrict__ ws, int64_t ws_words,
+                                                        int64_t* __restrict__ buf_y, int64_t slots)
+{
+    const int64_t stride = (int64_t)gridDim.x * TPB;
+    const int64_t first = (int64_t)blockIdx.x * TPB + threadIdx.x;
+    for (int64_t i = first; i < ws_words; i += stride) ws[i] = 0u;
+    for (int64_t i = first; i < slots; i += stride) buf_y[i] = -1;
+}
+
+// ---------------------------------------------------------------------------
+// rb_update: Algorithm 1.
+//
+// LDS (dynamic): s_a[b] u32 (first index per drawn value, later: slot per
+// position), s_lab[b] i32 (label per candidate position), s_t[c] u16 (Floyd
+// draws), s_x[c] u16 (candidate positions in Floyd emission order).
+//
+// Grid: `nchunks` bookkeeping workgroups (new fill counts and chunk sums for CH
+// classes each), then ceil(c / rpb) * tpr mover workgroups; a mover owns tile
+// `tile` of the rows of candidates [group*rpb, group*rpb + rpb).
+// ---------------------------------------------------------------------------
+struct UpdateArgs {
+    const vec16* batch_x;
+    const int64_t* batch_y;
+    vec16* buf_x;
+    int64_t* buf_y;
+    const int32_t* fill_old;
+    int32_t* fill_new;
+    int32_t* chunk_new;
+    DevState* state;
+    Seed sd;
+    int32_t b, c;
+    int32_t K, nchunks;
+    int64_t S;
+    int64_t row_vec;      // 16-byte vectors per row
+    int32_t tpr;          // tiles per row
+    int32_t tile_vec;     // vectors per tile (multiple of TPB, at most TPB * U)
+    int32_t rpb;          // rows per mover workgroup (1 unless tpr == 1)
+};
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t* s_a = lds;                                       // [b]
+    int32_t* s_lab = reinterpret_cast<int32_t*>(lds + a.b);    // [b]
+    uint16_t* s_t = reinterpret_cast<uint16_t*>(lds + 2 * a.b); // [c]
+    uint16_t* s_x = s_t + a.c;                                 // [c]
+    __shared__ int s_wave[NWAVE];
+    __shared__ int s_hist[CH];
+
+    const int tid = threadIdx.x;
+    const int b = a.b, c = a.c;
+
+    // ---- candidate selection: Floyd's c-subset of [0, b), all draws at once --
+    // Draw i is t_i in [0, b-c+i]; it is "taken" iff an earlier draw had the same
+    // value, or it equals b-c+q for an earlier q whose own draw was taken; a
+    // taken draw is replaced by b-c+i.
+    for (int q = tid; q < b; q += TPB) {
+        s_a[q] = 0xFFFFFFFFu;
+        s_lab[q] = LAB_UNSELECTED;
+    }
+    __syncthreads();
+    const int base = b - c;
+    for (int i = tid; i < c; i += TPB) {
+        uint32_t t = (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)i, (uint64_t)(base + i + 1));
+        s_t[i] = (uint16_t)t;
+        atomicMin(&s_a[t], (uint32_t)i);
+    }
+    __syncthreads();
+    for (int i = tid; i < c; i += TPB) {
+        int cur = i;
+        bool taken = false;
+        for (;;) {
+            int t = s_t[cur];
+            if (s_a[t] != (uint32_t)cur) { taken = true; break; }   // an earlier draw had this value
+            int q = t - base;                                       // the step whose fallback value is t
+            if (q < 0 || q >= cur) break;
+            cur = q;                                                // taken iff that step fell back
+        }
+        int x = taken ? base + i : (int)s_t[i];
+        s_x[i] = (uint16_t)x;
+        int64_t y = a.batch_y[x];
+        s_lab[x] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+    }
+    __syncthreads();
+
+    const int per = (b + TPB - 1) / TPB;       // mini-batch positions owned by one thread
+    const int q_lo = tid * per;
+
+    if ((int)blockIdx.x < a.nchunks) {
+        // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
+        const int k_lo = blockIdx.x * CH;
+        s_hist[tid] = 0;
+        __syncthreads();
+        bool bad = false;
+        for (int u = 0; u < per; ++u) {
+            int q = q_lo + u;
+            if (q < b) {
+                int32_t k = s_lab[q];
+                if (k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
+                bad |= (k == LAB_INVALID);
+            }
+        }
+        __syncthreads();
+        const int k = k_lo + tid;
+        int32_t nf = 0;
+        if (k < a.K) {
+            int64_t v = (int64_t)a.fill_old[k] + s_hist[tid];
+            nf = (int32_t)(v < a.S ? v : a.S);
+            a.fill_new[k] = nf;
+        }
+        int total;
+        block_scan_excl(nf, total, s_wave);
+        if (tid == 0) a.chunk_new[blockIdx.x] = total;
+        if (blockIdx.x == 0 && bad) atomicOr(&a.state->flags, RB_FLAG_BAD_LABEL);
+        return;
+    }
+
+    // ---- movers ---------------------------------------------------------------
+    const int mover = blockIdx.x - a.nchunks;
+    const int group = mover / a.tpr, tile = mover % a.tpr;
+    const int64_t v_lo = (int64_t)tile * a.tile_vec;
+    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+
+    for (int rr = 0; rr < a.rpb; ++rr) {
+        const int i = group * a.rpb + rr;      // candidate, in Floyd emission order
+        if (i >= c) break;
+        const int p = s_x[i];                  // its mini-batch position
+        const int32_t k = s_lab[p];
+        if (k < 0) continue;                   // label outside [0, K): dropped (flagged by bookkeeping)
+
+        // Start reading the row now; where it goes is worked out while it is in flight.
+        Tile<U, NT> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+
+        const int64_t fill0 = a.fill_old[k];
+        // Candidates of class k, in mini-batch order: the one at position q with
+        // `rank` class-mates before it is insertion number fill0 + rank of the class.
+        int mine = 0;
+        for (int u = 0; u < per; ++u) {
+            int q = q_lo + u;
+            mine += (q < b && s_lab[q] == k);
+        }
+        int total;
+        int rank = block_scan_excl(mine, total, s_wave);
+        int64_t slot;
+        bool dropped = false;
+        if (fill0 + total <= a.S) {
+            // all of them append: distinct slots, nothing to resolve
+            if (p >= q_lo && p < q_lo + per) {
+                for (int q = q_lo; q < p; ++q) rank += (s_lab[q] == k);
+                s_hist[0] = rank;
+            }
+            __syncthreads();
+            slot = fill0 + s_hist[0];
+            __syncthreads();
+        } else {
+            // some overwrite a uniformly drawn slot; if a later candidate of the
+            // class ends on this candidate's slot, this one is not stored.
+            for (int u = 0; u < per; ++u) {
+                int q = q_lo + u;
+                if (q < b && s_lab[q] == k) {
+                    int64_t at = fill0 + rank++;
+                    s_a[q] = (uint32_t)(at < a.S ? at : (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)q, (uint64_t)a.S));
+                }
+            }
+            __syncthreads();
+            const uint32_t own = s_a[p];
+            int later = 0;
+            for (int u = 0; u < per; ++u) {
+                int q = q_lo + u;
+                later |= (q < b && q > p && s_lab[q] == k && s_a[q] == own);
+            }
+            dropped = __syncthreads_or(later) != 0;
+            slot = own;
+        }
+        if (dropped) continue;
+        const int64_t dst_row = (int64_t)k * a.S + slot;
+        t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+        if (tile == 0 && tid == 0) a.buf_y[dst_row] = k;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// rb_sample_augment: n = min(r, F) distinct stored samples, uniformly.
+//
+// LDS (dynamic): s_cpre[nchunks] i32 (stored samples before each chunk of CH
+// classes), s_t[r] u32 (Floyd draws).
+// Grid: ceil(r / rpb) * tpr workgroups, row/tile mapping as in rb_update.
+// ---------------------------------------------------------------------------
+struct SampleArgs {
+    const vec16* buf_x;
+    vec16* out_x;
+    int64_t* out_y;
+    const int32_t* fill;
+    const int32_t* chunk;
+    DevState* state;
+    Seed sd;
+    int32_t r;
+    int32_t K, nchunks;
+    int64_t S;
+    int64_t row_vec;
+    int32_t tpr;
+    int32_t tile_vec;
+    int32_t rpb;
+};
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    int32_t* s_cpre = reinterpret_cast<int32_t*>(lds);    // [nchunks]
+    uint32_t* s_t = lds + a.nchunks;                      // [r]
+    __shared__ int s_wave[NWAVE];
+    __shared__ int s_pick[2];
+
+    const int tid = threadIdx.x;
+
+    // ---- F and the number of stored samples before every chunk -----------------
+    const int cper = (a.nchunks + TPB - 1) / TPB;
+    int csum = 0;
+    for (int u = 0; u < cper; ++u) {
+        int ch = tid * cper + u;
+        if (ch < a.nchunks) csum += a.chunk[ch];
+    }
+    int F;
+    int cbefore = block_scan_excl(csum, F, s_wave);
+    for (int u = 0; u < cper; ++u) {
+        int ch = tid * cper + u;
+        if (ch < a.nchunks) {
+            s_cpre[ch] = cbefore;
+            cbefore += a.chunk[ch];
+        }
+    }
+    const int n = a.r < F ? a.r : F;
+    if (blockIdx.x == 0 && tid == 0) a.state->last_n = n;
+
+    // ---- Floyd's n-subset of [0, F): all draws ----------------------------------
+    const int base = F - n;
+    for (int i = tid; i < n; i += TPB)
+        s_t[i] = (uint32_t)below(a.sd, PURPOSE_SAMPLE, (uint32_t)i, (uint64_t)base + i + 1);
+    __syncthreads();
+
+    const int group = blockIdx.x / a.tpr, tile = blockIdx.x % a.tpr;
+    const int64_t v_lo = (int64_t)tile * a.tile_vec;
+    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+
+    for (int rr = 0; rr < a.rpb; ++rr) {
+        const int j = group * a.rpb + rr;      // output row
+        if (j >= a.r) break;
+        if (j >= n) {                          // fewer stored samples than asked for
+            if (tile == 0 && tid == 0) a.out_y[j] = -1;
+            continue;
+        }
+        // Is draw j taken?  (same rule as in rb_update; the earlier-draw test is a
+        // workgroup-wide search because the value range is too large for a table)
+        int cur = j;
+        bool taken = false;
+        for (;;) {
+            const uint32_t t = s_t[cur];
+            int same = 0;
+            for (int q = tid; q < cur; q += TPB) same |= (s_t[q] == t);
+            if (__syncthreads_or(same)) { taken = true; break; }
+            const int64_t q = (int64_t)t - base;
+            if (q < 0 || q >= cur) break;
+            cur = (int)q;
+        }
+        const int g = taken ? base + j : (int)s_t[j];   // g-th stored sample, class-major
+
+        // chunk holding g: the last one with s_cpre <= g
+        int lo = 0, hi = a.nchunks - 1;
+        while (lo < hi) {
+            int mid = (lo + hi + 1) >> 1;
+            if (s_cpre[mid] <= g) lo = mid; else hi = mid - 1;
+        }
+        const int gl = g - s_cpre[lo];
+        if (tid == 0) { s_pick[0] = 0; s_pick[1] = 0; }   // never left undefined
+        const int k = lo * CH + tid;
+        const int f = k < a.K ? a.fill[k] : 0;
+        int unused;
+        const int before = block_scan_excl(f, unused, s_wave);
+        if (gl >= before && gl < before + f) {
+            s_pick[0] = k;
+            s_pick[1] = gl - before;
+        }
+        __syncthreads();
+        const int pk = s_pick[0], ps = s_pick[1];
+        __syncthreads();
+
+        Tile<U, NT> t;
+        t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
+        t.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
+        if (tile == 0 && tid == 0) a.out_y[j] = pk;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Measurement helpers
+// ---------------------------------------------------------------------------
+__global__ void __launch_bounds__(TPB) rb_standin_kernel(float* __restrict__ sink, int64_t iters)
+{
+    float x0 = threadIdx.x * 1e-3f, x1 = x0 + 1.f, x2 = x0 + 2.f, x3 = x0 + 3.f;
+    const float m = 0.999f, d = 1e-3f;
+    for (int64_t i = 0; i < iters; ++i) {
+        x0 = fmaf(x0, m, d); x1 = fmaf(x1, m, d); x2 = fmaf(x2, m, d); x3 = fmaf(x3, m, d);
+        x0 = fmaf(x0, m, d); x1 = fmaf(x1, m, d); x2 = fmaf(x2, m, d); x3 = fmaf(x3, m, d);
+    }
+    sink[(int64_t)blockIdx.x * TPB + threadIdx.x] = x0 + x1 + x2 + x3;
+}
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_copy_kernel(vec16* __restrict__ dst, const vec16* __restrict__ src, int64_t nvec)
+{
+    const int64_t lo = (int64_t)blockIdx.x * (TPB * U);
+    const int64_t hi = lo + TPB * U < nvec ? lo + TPB * U : nvec;
+    Tile<U, NT> t;
+    t.load(src, lo, hi);
+    t.store(dst, lo, hi);
+}
+
+inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
+inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+}  // namespace
+
+// ===========================================================================
+// Host side: the C ABI
+// ===========================================================================
+struct rb_buffer {
+    int64_t K, S, row_bytes, row_vec;
+    int32_t dtype;
+    int32_t nchunks;
+    // device storage (borrowed)
+    void* buf_x;
+    int64_t* buf_y;
+    char* ws;
+    hipStream_t stream;
+    bool bound;
+    int cur;                 // which of the two fill-count copies is current
+    // workspace layout (byte offsets)
+    size_t off_fill[2], off_chunk[2], ws_bytes;
+    // launch-shape knobs
+    int opt_unroll, opt_nt, opt_rpb;
+};
+
+namespace {
+
+struct Shape {
+    int unroll, tpr, tile_vec, rpb;
+    int64_t groups;
+};
+
+// Split `rows` rows of `row_vec` vectors into workgroup tiles.
+Shape plan_shape(const rb_buffer* rb, int64_t rows)
+{
+    Shape s;
+    const int64_t row_vec = rb->row_vec;
+    int u = rb->opt_unroll;
+    if (u == 0) {
+        // largest unroll that still leaves about four workgroups per compute unit
+        u = 8;
+        while (u > 1 && rows * ((row_vec + (int64_t)TPB * u - 1) / ((int64_t)TPB * u)) < 1024) u >>= 1;
+    }
+    s.unroll = u;
+    const int64_t cap = (int64_t)TPB * u;
+    s.tpr = (int)((row_vec + cap - 1) / cap);
+    // even tiles, rounded up to whole workgroup widths
+    int64_t per_tile = (row_vec + s.tpr - 1) / s.tpr;
+    s.tile_vec = (int)round_up((size_t)per_tile, TPB);
+    s.rpb = 1;
+    if (s.tpr == 1) {
+        int r = rb->opt_rpb;
+        if (r == 0) {
+            r = 1;
+            while (r < 16 && (rows + r - 1) / r > 1024) r <<= 1;
+        }
+        s.rpb = r;
+    }
+    s.groups = (rows + s.rpb - 1) / s.rpb;
+    return s;
+}
+
+template <bool NT>
+hipError_t launch_update(const UpdateArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: rb_update_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_update_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_update_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_update_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <bool NT>
+hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: rb_sample_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_sample_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_sample_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_sample_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <bool NT>
+hipError_t launch_copy(vec16* dst, const vec16* src, int64_t nvec, int unroll, hipStream_t st)
+{
+    const int64_t cap = (int64_t)TPB * unroll;
+    dim3 grid((unsigned)((nvec + cap - 1) / cap));
+    switch (unroll) {
+    case 1: rb_copy_kernel<1, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    case 2: rb_copy_kernel<2, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    case 4: rb_copy_kernel<4, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    default: rb_copy_kernel<8, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    }
+    return hipGetLastError();
+}
+
+Seed make_seed(uint64_t seed, uint64_t step)
+{
+    Seed s;
+    s.seed_lo = (uint32_t)seed;
+    s.seed_hi = (uint32_t)(seed >> 32);
+    s.step_lo = (uint32_t)step;
+    s.step_hi = (uint32_t)(step >> 32);
+    return s;
+}
+
+}  // namespace
+
+extern "C" {
+
+int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
+              const int64_t* sample_shape, int32_t ndim, int32_t dtype)
+{
+    if (!out) return RB_EINVAL;
+    *out = nullptr;
+    if (!sample_shape || ndim < 1 || ndim > 16) return RB_EINVAL;
+    if (classes < 1 || classes > RB_MAX_CLASSES || slots_per_class < 1) return RB_EINVAL;
+    if (slots_per_class > RB_MAX_SLOTS / classes) return RB_EINVAL;
+    if (dtype != RB_F32 && dtype != RB_BF16) return RB_EINVAL;
+    int64_t elems = 1;
+    for (int i = 0; i < ndim; ++i) {
+        if (sample_shape[i] < 1) return RB_EINVAL;
+        if (elems > (INT64_C(1) << 40) / sample_shape[i]) return RB_EINVAL;   // a row of more than 2^40 elements
+        elems *= sample_shape[i];
+    }
+    const int64_t row_bytes = elems * (dtype == RB_F32 ? 4 : 2);
+    if (row_bytes % 16 != 0) return RB_EINVAL;
+    rb_buffer* rb = new (std::nothrow) rb_buffer();
+    if (!rb) return RB_ENOMEM;
+    rb->K = classes;
+    rb->S = slots_per_class;
+    rb->row_bytes = row_bytes;
+    rb->row_vec = row_bytes / 16;
+    rb->dtype = dtype;
+    rb->nchunks = (int32_t)((classes + CH - 1) / CH);
+    rb->buf_x = nullptr; rb->buf_y = nullptr; rb->ws = nullptr; rb->stream = nullptr;
+    rb->bound = false;
+    rb->cur = 0;
+    size_t off = STATE_BYTES;
+    const size_t fill_bytes = round_up((size_t)rb->nchunks * CH * sizeof(int32_t), 256);
+    const size_t chunk_bytes = round_up((size_t)rb->nchunks * sizeof(int32_t), 256);
+    rb->off_fill[0] = off; off += fill_bytes;
+    rb->off_fill[1] = off; off += fill_bytes;
+    rb->off_chunk[0] = off; off += chunk_bytes;
+    rb->off_chunk[1] = off; off += chunk_bytes;
+    rb->ws_bytes = off;
+    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0;
+    *out = rb;
+    return RB_OK;
+}
+
+int rb_query_sizes(const rb_buffer* rb, size_t* x_bytes, size_t* y_bytes, size_t* workspace_bytes)
+{
+    if (!rb) return RB_EINVAL;
+    if (x_bytes) *x_bytes = (size_t)rb->K * (size_t)rb->S * (size_t)rb->row_bytes;
+    if (y_bytes) *y_bytes = (size_t)rb->K * (size_t)rb->S * sizeof(int64_t);
+    if (workspace_bytes) *workspace_bytes = rb->ws_bytes;
+    return RB_OK;
+}
+
+int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* hip_stream)
+{
+    if (!rb || !buf_x || !buf_y || !workspace) return RB_EINVAL;
+    if (!aligned(buf_x, 16) || !aligned(buf_y, 8) || !aligned(workspace, 256)) return RB_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    const int64_t slots = rb->K * rb->S;
+    int64_t blocks = (slots + TPB - 1) / TPB;
+    if (blocks > 4096) blocks = 4096;
+    if (blocks < 1) blocks = 1;
+    rb_reset_kernel<<<dim3((unsigned)blocks), TPB, 0, st>>>(static_cast<uint32_t*>(workspace),
+                                                           (int64_t)(rb->ws_bytes / 4), buf_y, slots);
+    if (hipGetLastError() != hipSuccess) return RB_EHIP;
+    rb->buf_x = buf_x;
+    rb->buf_y = buf_y;
+    rb->ws = static_cast<char*>(workspace);
+    rb->stream = st;
+    rb->cur = 0;
+    rb->bound = true;
+    return RB_OK;
+}
+
+int rb_set_stream(rb_buffer* rb, void* hip_stream)
+{
+    if (!rb) return RB_EINVAL;
+    rb->stream = static_cast<hipStream_t>(hip_stream);
+    return RB_OK;
+}
+
+int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
+              int64_t b, int64_t c, uint64_t seed, uint64_t step)
+{
+    if (!rb || !batch_x || !batch_y) return RB_EINVAL;
+    if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b) return RB_EINVAL;
+    if (!aligned(batch_x, 16) || !aligned(batch_y, 8)) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+    if (c == 0) return RB_OK;
+
+    const Shape sh = plan_shape(rb, c);
+    UpdateArgs a;
+    a.batch_x = static_cast<const vec16*>(batch_x);
+    a.batch_y = batch_y;
+    a.buf_x = static_cast<vec16*>(rb->buf_x);
+    a.buf_y = rb->buf_y;
+    a.fill_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    a.fill_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_fill[rb->cur ^ 1]);
+    a.chunk_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_chunk[rb->cur ^ 1]);
+    a.state = reinterpret_cast<DevState*>(rb->ws);
+    a.sd = make_seed(seed, step);
+    a.b = (int32_t)b; a.c = (int32_t)c;
+    a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
+    a.S = rb->S;
+    a.row_vec = rb->row_vec;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = sh.rpb;
+    const dim3 grid((unsigned)(rb->nchunks + sh.groups * sh.tpr));
+    const size_t lds = (size_t)b * 8 + (size_t)c * 4;
+    hipError_t e = rb->opt_nt ? launch_update<true>(a, sh.unroll, grid, lds, rb->stream)
+                              : launch_update<false>(a, sh.unroll, grid, lds, rb->stream);
+    if (e != hipSuccess) return RB_EHIP;
+    rb->cur ^= 1;
+    return RB_OK;
+}
+
+int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, void* out_x, int64_t* out_y)
+{
+    if (!rb || r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
+    if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+    if (r == 0) return RB_OK;
+
+    const Shape sh = plan_shape(rb, r);
+    SampleArgs a;
+    a.buf_x = static_cast<const vec16*>(rb->buf_x);
+    a.out_x = static_cast<vec16*>(out_x);
+    a.out_y = out_y;
+    a.fill = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    a.chunk = reinterpret_cast<const int32_t*>(rb->ws + rb->off_chunk[rb->cur]);
+    a.state = reinterpret_cast<DevState*>(rb->ws);
+    a.sd = make_seed(seed, step);
+    a.r = (int32_t)r;
+    a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
+    a.S = rb->S;
+    a.row_vec = rb->row_vec;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = sh.rpb;
+    const dim3 grid((unsigned)(sh.groups * sh.tpr));
+    const size_t lds = ((size_t)rb->nchunks + (size_t)r) * 4;
+    hipError_t e = rb->opt_nt ? launch_sample<true>(a, sh.unroll, grid, lds, rb->stream)
+                              : launch_sample<false>(a, sh.unroll, grid, lds, rb->stream);
+    return e == hipSuccess ? RB_OK : RB_EHIP;
+}
+
+int rb_read_state(rb_buffer* rb, int32_t* fill_host, int64_t* last_n_host, uint32_t* flags_host)
+{
+    if (!rb) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+    if (hipStreamSynchronize(rb->stream) != hipSuccess) return RB_EHIP;
+    DevState st;
+    if (hipMemcpy(&st, rb->ws, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) return RB_EHIP;
+    if (fill_host &&
+        hipMemcpy(fill_host, rb->ws + rb->off_fill[rb->cur], (size_t)rb->K * sizeof(int32_t), hipMemcpyDeviceToHost) != hipSuccess)
+        return RB_EHIP;
+    if (last_n_host) *last_n_host = st.last_n;
+    if (flags_host) *flags_host = st.flags;
+    return RB_OK;
+}
+
+int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
+{
+    if (!rb) return RB_EINVAL;
+    switch (option) {
+    case RB_OPT_UNROLL:
+        if (value != 0 && value != 1 && value != 2 && value != 4 && value != 8) return RB_EINVAL;
+        rb->opt_unroll = (int)value;
+        return RB_OK;
+    case RB_OPT_NONTEMPORAL:
+        if (value != 0 && value != 1) return RB_EINVAL;
+        rb->opt_nt = (int)value;
+        return RB_OK;
+    case RB_OPT_ROWS_PER_BLOCK:
+        if (value < 0 || value > 16) return RB_EINVAL;
+        rb->opt_rpb = (int)value;
+        return RB_OK;
+    default:
+        return RB_EINVAL;
+    }
+}
+
+int rb_destroy(rb_buffer* rb)
+{
+    delete rb;
+    return RB_OK;
+}
+
+const char* rb_strerror(int status)
+{
+    switch (status) {
+    case RB_OK: return "ok";
+    case RB_EINVAL: return "invalid argument";
+    case RB_ENOMEM: return "out of host memory";
+    case RB_ESTATE: return "buffer is not bound to device storage";
+    case RB_EHIP: return "a HIP call failed";
+    default: return "unknown status";
+    }
+}
+
+int rb_standin_compute(void* hip_stream, float* sink, int64_t blocks, int64_t iters)
+{
+    if (!sink || blocks < 1 || blocks > (1 << 20) || iters < 0) return RB_EINVAL;
+    rb_standin_kernel<<<dim3((unsigned)blocks), TPB, 0, static_cast<hipStream_t>(hip_stream)>>>(sink, iters);
+    return hipGetLastError() == hipSuccess ? RB_OK : RB_EHIP;
+}
+
+int rb_copy_bytes(void* hip_stream, void* dst, const void* src, size_t bytes, int32_t unroll, int32_t nontemporal)
+{
+    if (!dst || !src || bytes == 0 || bytes % 16 != 0 || !aligned(dst, 16) || !aligned(src, 16)) return RB_EINVAL;
+    if (unroll != 1 && unroll != 2 && unroll != 4 && unroll != 8) return RB_EINVAL;
+    const int64_t nvec = (int64_t)(bytes / 16);
+    if ((nvec + (int64_t)TPB * unroll - 1) / ((int64_t)TPB * unroll) > 0x7FFFFFFF) return RB_EINVAL;
+    hipStream_t st = static_cast<hipStream_t>(hip_stream);
+    hipError_t e = nontemporal ? launch_copy<true>(static_cast<vec16*>(dst), static_cast<const vec16*>(src), nvec, unroll, st)
+                               : launch_copy<false>(static_cast<vec16*>(dst), static_cast<const vec16*>(src), nvec, unroll, st);
+    return e == hipSuccess ? RB_OK : RB_EHIP;
+}
+
+}  // extern "C"

@@ -1,0 +1,112 @@
+"""Drive the HIP library and the CPU oracle side by side on the same seeded inputs
+and compare everything observable, byte for byte."""
+import numpy as np
+import torch
+
+import rb_workloads as wl
+from oracle import rbo
+
+SENTINEL = 0x5A
+
+
+def _bytes(t):
+    """uint8 view [rows, row_bytes] of a contiguous sample tensor (stays on its device)."""
+    return t.view(torch.uint8).reshape(t.shape[0], -1)
+
+
+def compare_state(buf, orc, tag):
+    fill, last_n, flags = buf.read_state()
+    assert np.array_equal(fill, orc.fill), f"{tag}: per-class fill differs"
+    assert flags == orc.flags, f"{tag}: flags {flags} != {orc.flags}"
+    return fill
+
+
+def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
+    """Labels of all slots, and sample bytes of every filled slot."""
+    fill = compare_state(buf, orc, tag)
+    gy = buf.buf_y.cpu().numpy()
+    assert np.array_equal(gy, orc.buf_y), f"{tag}: buf_y differs"
+    rows_per_chunk = max(1, chunk_bytes // buf.row_bytes)
+    bx = buf.buf_x.view(buf.K * buf.S, -1).view(torch.uint8)      # [K*S, row_bytes] on the device
+    pending, count = [], 0
+
+    def flush():
+        nonlocal pending, count
+        if not pending:
+            return
+        host = np.concatenate([orc.export_rows(first, n) for first, n in pending])
+        idx = torch.cat([torch.arange(first, first + n) for first, n in pending]).to(bx.device)
+        want = torch.from_numpy(host).to(bx.device)
+        got = bx.index_select(0, idx)
+        if not torch.equal(got, want):
+            bad = (got != want).any(dim=1).nonzero().flatten()[:5].tolist()
+            raise AssertionError(f"{tag}: stored rows differ at slots {[int(idx[i]) for i in bad]}")
+        pending, count = [], 0
+
+    for k in range(buf.K):
+        f = int(fill[k])
+        at = 0
+        while at < f:
+            n = min(f - at, rows_per_chunk - count)
+            pending.append((k * buf.S + at, n))
+            count += n
+            at += n
+            if count >= rows_per_chunk:
+                flush()
+    flush()
+
+
+def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
+               first_step=0, progress=None, buf=None, orc=None, final_check=True):
+    """Runs `steps` update+sample steps of workload `w` on both sides.
+
+    Every step: out_y equal, the n sampled rows byte-equal, rows >= n untouched.
+    At the end (and every `check_state_every` steps): fill, flags, buf_y and all
+    filled buf_x rows.  Returns (buf, orc) for further checks.
+    """
+    import paper_2406_03285_amd as rb
+
+    steps = w.steps if steps is None else steps
+    dev = torch.device(device)
+    own = buf is None
+    if own:
+        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream)
+        orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+        for opt, val in options:
+            buf.set_option(opt, val)
+    aug_x = torch.empty((w.b + w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    aug_y = torch.empty(w.b + w.r, dtype=torch.int64, device=dev)
+    for step in range(first_step, first_step + steps):
+        x, y = wl.make_batch(w, step, dev)
+        aug_x[:w.b].copy_(x)
+        aug_y[:w.b].copy_(y)
+        _bytes(aug_x[w.b:]).fill_(SENTINEL)
+        aug_y[w.b:].fill_(-7)
+        if stream is not None:
+            stream.wait_stream(torch.cuda.current_stream(dev))
+        buf.update(aug_x[:w.b], aug_y[:w.b], w.c, w.lib_seed, step)
+        buf.sample_augment(w.r, w.lib_seed, step, aug_x[w.b:], aug_y[w.b:])
+        if stream is not None:
+            torch.cuda.current_stream(dev).wait_stream(stream)
+        # oracle on the host copies of the very same bytes
+        hx = _bytes(aug_x[:w.b]).cpu().numpy()
+        hy = aug_y[:w.b].cpu().numpy()
+        orc.update(hx, hy, w.c, w.lib_seed, step)
+        ref_x = np.full((w.r, w.row_bytes), SENTINEL, dtype=np.uint8)
+        n, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, step, out_x=ref_x)
+        got_y = aug_y[w.b:].cpu().numpy()
+        tag = f"{w.name} step {step}"
+        assert np.array_equal(got_y, ref_y), f"{tag}: out_y differs\n gpu {got_y[:16]}\n ref {ref_y[:16]}"
+        got_x = _bytes(aug_x[w.b:]).cpu().numpy()
+        if not np.array_equal(got_x, ref_x):
+            bad = np.nonzero((got_x != ref_x).any(axis=1))[0]
+            raise AssertionError(f"{tag}: out_x rows {bad[:8].tolist()} differ (n={n})")
+        if check_state_every and (step + 1) % check_state_every == 0:
+            compare_buffers(buf, orc, tag)
+            _, last_n, _ = buf.read_state()
+            assert last_n == n
+        if progress and (step + 1) % progress == 0:
+            print(f"  {tag} ok", flush=True)
+    if final_check:
+        compare_buffers(buf, orc, f"{w.name} final")
+    return buf, orc

@@ -1,0 +1,74 @@
+"""CPU-side checks of the C-ABI library: it loads, exports every function the
+header declares, and rejects bad arguments on the host before any device work."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _declared():
+    text = open(os.path.join(ROOT, "include", "rb.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rb_[a-z_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_function():
+    import paper_2406_03285_amd as rb
+    names = _declared()
+    assert len(names) >= 10 and set(names) == set(rb.EXPORTS)
+    lib = C.CDLL(rb.LIB_PATH)
+    for name in names:
+        assert getattr(lib, name) is not None
+
+
+def test_binding_has_the_same_names():
+    import paper_2406_03285_amd as rb
+    for name in _declared():
+        assert callable(getattr(rb, name))
+
+
+def test_create_validation_and_sizes():
+    import paper_2406_03285_amd as rb
+    rc, h = rb.rb_create(1000, 130, (3, 224, 224), rb.RB_F32)
+    assert rc == rb.RB_OK and h
+    rc, xb, yb, wb = rb.rb_query_sizes(h)
+    assert rc == rb.RB_OK and xb == 1000 * 130 * 602112 and yb == 1000 * 130 * 8 and wb % 256 == 0 and wb < (1 << 20)
+    # hot calls before rb_bind
+    assert rb.rb_update(h, 256, 256, 4, 2, 0, 0) == rb.RB_ESTATE
+    assert rb.rb_sample_augment(h, 2, 0, 0, 256, 256) == rb.RB_ESTATE
+    # argument errors are reported before the state error
+    assert rb.rb_update(h, None, 256, 4, 2, 0, 0) == rb.RB_EINVAL
+    assert rb.rb_update(h, 256, 256, 0, 0, 0, 0) == rb.RB_EINVAL            # b < 1
+    assert rb.rb_update(h, 256, 256, 4, 5, 0, 0) == rb.RB_EINVAL            # c > b
+    assert rb.rb_update(h, 256, 256, 4, -1, 0, 0) == rb.RB_EINVAL
+    assert rb.rb_update(h, 256, 256, rb.RB_MAX_BATCH + 1, 1, 0, 0) == rb.RB_EINVAL
+    assert rb.rb_update(h, 264, 256, 4, 2, 0, 0) == rb.RB_EINVAL            # batch_x not 16-byte aligned
+    assert rb.rb_sample_augment(h, -1, 0, 0, 256, 256) == rb.RB_EINVAL
+    assert rb.rb_sample_augment(h, rb.RB_MAX_BATCH + 1, 0, 0, 256, 256) == rb.RB_EINVAL
+    assert rb.rb_sample_augment(h, 2, 0, 0, None, 256) == rb.RB_EINVAL
+    assert rb.rb_bind(h, None, 256, 256) == rb.RB_EINVAL
+    assert rb.rb_bind(h, 256, 256, 128) == rb.RB_EINVAL                     # workspace not 256-byte aligned
+    assert rb.rb_set_option(h, rb.RB_OPT_UNROLL, 3) == rb.RB_EINVAL
+    assert rb.rb_set_option(h, rb.RB_OPT_UNROLL, 4) == rb.RB_OK
+    assert rb.rb_set_option(h, 99, 0) == rb.RB_EINVAL
+    assert rb.rb_destroy(h) == rb.RB_OK
+
+
+@pytest.mark.parametrize("args", [
+    (0, 10, (4,), 0), (10, 0, (4,), 0), (10, 10, (), 0), (10, 10, (3,), 0),      # 12-byte row
+    (10, 10, (4,), 7), (10, 10, (4, 0), 0), ((1 << 20) + 1, 1, (4,), 0), (1 << 20, 1 << 12, (4,), 0),
+    (10, 10, (4,), 1),                                                            # bf16: 8-byte row
+])
+def test_create_rejects(args):
+    import paper_2406_03285_amd as rb
+    rc, h = rb.rb_create(*args)
+    assert rc == rb.RB_EINVAL and not h
+
+
+def test_strerror():
+    import paper_2406_03285_amd as rb
+    assert rb.rb_strerror(0) == "ok"
+    assert len({rb.rb_strerror(s) for s in (0, -1, -2, -3, -4, -99)}) == 6

@@ -1,0 +1,186 @@
+"""GPU parity: the HIP library against the CPU oracle, byte for byte, through the C ABI.
+
+Integer / byte work only, so the bar is bit-exact: per-class fill, flags, every
+slot label, every stored row, every augmented row and label, on every step.
+"""
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import rb_workloads as wl
+from oracle import rbo
+from parity_util import SENTINEL, compare_buffers, run_parity
+
+pytestmark = pytest.mark.gpu
+
+FULL = os.environ.get("RB_FULL", "0") == "1"      # run the large workloads for all their steps
+
+
+@pytest.fixture(autouse=True)
+def _free_device_memory():
+    yield
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+
+
+def _rb():
+    import paper_2406_03285_amd as rb
+    return rb
+
+
+# ------------------------------------------------------ the five workloads ---
+
+def test_c1_tiny_all_steps():
+    run_parity(wl.C1, check_state_every=10)
+
+
+def test_c2_all_steps():
+    run_parity(wl.C2, check_state_every=250, progress=250)
+
+
+@pytest.mark.parametrize("w,steps", [(wl.C3, 120), (wl.C4, 50), (wl.C5, 40)], ids=["C3", "C4", "C5"])
+def test_full_size_workloads(w, steps):
+    """Real shapes (78-90 GB buffers) in the launch configuration the bench times."""
+    print(f"\n{w.name}: buffer {w.buffer_bytes / 1e9:.1f} GB", flush=True)
+    run_parity(w, steps=w.steps if FULL else steps, progress=10 if not FULL else 100)
+
+
+def test_c3_on_a_side_stream():
+    s = torch.cuda.Stream()
+    run_parity(wl.variant(wl.C3, name="C3-side-stream", S=8), steps=30, stream=s)
+
+
+# ------------------------------------------- stress variants (replace path) ---
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C3, name="C3-S4", S=4), 150),                               # 16 per class > 4 slots: heavy replacement
+    (wl.variant(wl.C4, name="C4-S8", S=8, shape=(3, 32, 32)), 100),            # Zipf head: many same-class evictions per step
+    (wl.variant(wl.C5, name="C5-S16-K200", K=200, S=16, shape=(64,)), 40),     # 1024 candidates into 50 classes x 16 slots
+    (wl.variant(wl.C2, name="C2-S3", S=3), 200),
+    (wl.variant(wl.C5, name="C5-small-rows", S=40, shape=(256,)), 30),         # K = 10000: two-level fill index, append chains
+])
+def test_stress_variants(w, steps):
+    run_parity(w, steps=steps, check_state_every=max(1, steps // 3))
+
+
+# -------------------------------------------------- launch-shape invariance ---
+
+@pytest.mark.parametrize("unroll", [1, 2, 4, 8])
+@pytest.mark.parametrize("nt", [0, 1])
+def test_launch_shape_does_not_change_results(unroll, nt):
+    rb = _rb()
+    w = wl.variant(wl.C1, name=f"C1-u{unroll}-nt{nt}", shape=(777, 4), S=6, steps=40)   # 777 vectors per row: ragged tiles
+    run_parity(w, options=((rb.RB_OPT_UNROLL, unroll), (rb.RB_OPT_NONTEMPORAL, nt)))
+
+
+@pytest.mark.parametrize("rpb", [1, 2, 3, 16])
+def test_rows_per_block(rpb):
+    rb = _rb()
+    w = wl.variant(wl.C2, name=f"C2-rpb{rpb}", shape=(64,), S=5, b=200, c=77, r=61, steps=30)
+    run_parity(w, options=((rb.RB_OPT_ROWS_PER_BLOCK, rpb),))
+
+
+# ------------------------------------------------------------- edge cases ---
+
+@pytest.mark.parametrize("K,S,shape,dtype,b,c,r", [
+    (1, 1, (4,), "f32", 1, 1, 1),                    # smallest everything: 16-byte rows
+    (1, 5000, (8,), "bf16", 4096, 4096, 4096),       # maximum b = c = r, one class, append then replace
+    (3, 2, (8,), "f32", 4096, 4096, 4096),           # maximum sizes into 6 slots: collisions everywhere; r >> F
+    (257, 3, (12,), "f32", 64, 64, 100),             # two chunks of classes, ragged second chunk
+    (70000, 2, (4,), "f32", 4096, 2048, 512),        # 274 chunks: several chunk sums per thread
+    (5, 4, (3, 5, 8), "bf16", 33, 7, 9),
+    (10, 20, (3, 32, 32), "f32", 16, 16, 300),       # c = b; r above capacity (200)
+])
+def test_edge_shapes(K, S, shape, dtype, b, c, r):
+    w = wl.Workload(f"edge-{K}x{S}-{b}-{c}-{r}", 9, K, S, shape, dtype, b, c, r, 12, "normal", "uniform")
+    run_parity(w, check_state_every=4)
+
+
+def test_noop_calls_and_empty_buffer():
+    rb = _rb()
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    x, y = wl.make_batch(w, 0, "cuda:0")
+    out_x = torch.zeros((w.r, *w.shape), device="cuda:0")
+    out_y = torch.full((w.r,), 5, dtype=torch.int64, device="cuda:0")
+    # sampling from an empty buffer: n = 0, labels -1, rows untouched
+    buf.sample_augment(w.r, 0, 0, out_x, out_y)
+    fill, last_n, flags = buf.read_state()
+    assert last_n == 0 and fill.sum() == 0 and flags == 0
+    assert out_y.tolist() == [-1] * w.r and not out_x.any()
+    # c = 0 and r = 0 are no-ops
+    buf.update(x, y, 0, 0, 0)
+    buf.sample_augment(0, 0, 0, None, None)
+    assert buf.read_state()[0].sum() == 0
+    assert torch.all(buf.buf_y == -1)
+    # several updates without sampling, then several samplings without update
+    for step in range(5):
+        x, y = wl.make_batch(w, step, "cuda:0")
+        buf.update(x, y, w.c, 3, step)
+        orc.update(wl.as_row_bytes(x), y.cpu().numpy(), w.c, 3, step)
+    compare_buffers(buf, orc, "updates only")
+    for step in range(5):
+        buf.sample_augment(w.r, 3, 100 + step, out_x, out_y)
+        n, rx, ry = orc.sample_augment(w.r, 3, 100 + step)
+        assert out_y.cpu().numpy().tolist() == ry.tolist()
+        assert np.array_equal(wl.as_row_bytes(out_x), rx)
+        assert buf.read_state()[1] == n == w.r
+
+
+def test_bad_labels_are_dropped_and_flagged():
+    rb = _rb()
+    K, S, b = 4, 8, 8
+    buf = rb.RehearsalBuffer(K, S, (4,), torch.float32)
+    orc = rbo.Buffer(K, S, 16)
+    x = torch.randn(b, 4, device="cuda:0")
+    y = torch.tensor([0, -1, 1, K, 2, 10**12, 3, -7], dtype=torch.int64, device="cuda:0")
+    assert buf.read_state()[2] == 0
+    buf.update(x, y, b, 0, 0)
+    orc.update(wl.as_row_bytes(x), y.cpu().numpy(), b, 0, 0)
+    fill, _, flags = buf.read_state()
+    assert flags & rb.RB_FLAG_BAD_LABEL and fill.tolist() == [1, 1, 1, 1]
+    compare_buffers(buf, orc, "bad labels")
+
+
+def test_bind_again_resets():
+    rb = _rb()
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype)
+    x, y = wl.make_batch(w, 0, "cuda:0")
+    buf.update(x, y, w.c, 0, 0)
+    assert buf.read_state()[0].sum() == w.c
+    assert rb.rb_bind(buf.handle, buf.buf_x, buf.buf_y, buf.workspace, None) == rb.RB_OK
+    assert buf.read_state()[0].sum() == 0 and torch.all(buf.buf_y == -1)
+    run_parity(w, steps=20, buf=buf, orc=rbo.Buffer(w.K, w.S, w.row_bytes))
+
+
+def test_device_pointer_validation_on_gpu():
+    rb = _rb()
+    buf = rb.RehearsalBuffer(4, 4, (8,), torch.float32)
+    x = torch.zeros(9, 8, device="cuda:0")
+    y = torch.zeros(9, dtype=torch.int64, device="cuda:0")
+    assert rb.rb_update(buf.handle, x.data_ptr() + 4, y, 8, 2, 0, 0) == rb.RB_EINVAL
+    assert rb.rb_sample_augment(buf.handle, 2, 0, 0, x.data_ptr() + 8, y) == rb.RB_EINVAL
+    assert rb.rb_update(buf.handle, x, y, 8, 2, 0, 0) == rb.RB_OK
+
+
+def test_copy_helper_moves_bytes():
+    rb = _rb()
+    src = torch.randint(0, 255, (3_000_016,), dtype=torch.uint8, device="cuda:0")
+    for unroll in (1, 2, 4, 8):
+        for nt in (0, 1):
+            dst = torch.zeros_like(src)
+            assert rb.rb_copy_bytes(None, dst, src, src.numel(), unroll, nt) == rb.RB_OK
+            assert torch.equal(dst, src)
+    assert rb.rb_copy_bytes(None, dst, src, 24, 4, 1) == rb.RB_EINVAL
+
+
+def test_standin_compute_runs():
+    rb = _rb()
+    sink = torch.zeros(8 * 256, device="cuda:0")
+    assert rb.rb_standin_compute(None, sink, 8, 1000) == rb.RB_OK
+    torch.cuda.synchronize()
+    assert torch.isfinite(sink).all() and sink.abs().sum() > 0
