@@ -31,6 +31,7 @@ constexpr uint32_t PURPOSE_EVICT = 2;
 constexpr uint32_t PURPOSE_SAMPLE = 3;
 constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a candidate
 constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
+constexpr int MAXPER = RB_MAX_BATCH / TPB;   // most mini-batch positions (or classes, direct mode) one thread owns
 
 typedef uint32_t vec16 __attribute__((ext_vector_type(4)));   // one 16-byte transfer
 
@@ -100,6 +101,21 @@ __device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
     __syncthreads();
     total = all;
     return before + inc - v;
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront-level pieces of the small-count kernels (at most WAVE candidates or
+// representatives: one lane per item, all 64 lanes of the wavefront active).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int wave_scan_incl(int v)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+#pragma unroll
+    for (int d = 1; d < WAVE; d <<= 1) {
+        int up = __shfl_up(v, d, WAVE);
+        if (lane >= d) v += up;
+    }
+    return v;
 }
 
 // ---------------------------------------------------------------------------
@@ -265,10 +281,10 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         if (k < 0) continue;                   // label outside [0, K): dropped (flagged by bookkeeping)
 
         // Start reading the row now; where it goes is worked out while it is in flight.
+        const int64_t fill0 = a.fill_old[k];
         Tile<U, NT> t;
         t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
 
-        const int64_t fill0 = a.fill_old[k];
         // Candidates of class k, in mini-batch order: the one at position q with
         // `rank` class-mates before it is insertion number fill0 + rank of the class.
         int mine = 0;
@@ -317,10 +333,176 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// rb_update for c <= WAVE candidates: the plan is computed by the first
+// wavefront of each workgroup alone, one lane per candidate, with ballots and
+// lane reads instead of workgroup scans; the other three wavefronts only move
+// data.  Same grid and arguments as rb_update_kernel.
+//
+// LDS (dynamic): s_first[b] u32 (lowest lane that drew a value), s_y[b] i32
+// (label of every mini-batch position, LAB_INVALID when outside [0, K)).
+// ---------------------------------------------------------------------------
+constexpr int YPRE = 4;    // label loads per thread issued before anything else (covers b <= 1024)
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    uint32_t* s_first = lds;                                   // [b]
+    int32_t* s_y = reinterpret_cast<int32_t*>(lds + a.b);      // [b]
+    __shared__ int s_wave[NWAVE];
+    __shared__ int s_hist[CH];
+    __shared__ int s_p[2];          // mini-batch position of the current candidate (double-buffered over rows)
+    __shared__ int64_t s_dst[2];    // slot row it is stored to, -1: not stored
+
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const bool w0 = tid < WAVE;
+    const int b = a.b, c = a.c, base = b - c;
+
+    // all labels of the mini-batch: requested now, parked in LDS once the selection is done
+    int64_t yv[YPRE];
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        yv[u] = q < b ? a.batch_y[q] : -1;
+    }
+
+    // wavefront 0: lane i computes candidate i of Floyd's emission order
+    bool active = false;
+    int x = 0;                       // its mini-batch position
+    if (w0) {
+        active = lane < c;
+        const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)lane, (uint64_t)(base + lane + 1)) : 0u;
+        // draw i is replaced by base + i iff an earlier lane drew the same value, or it
+        // equals base + q for an earlier q whose own draw was replaced
+        if (active) s_first[t] = 0xFFFFFFFFu;
+        if (active) atomicMin(&s_first[t], (uint32_t)lane);
+        const bool dup = active && s_first[t] != (uint32_t)lane;
+        int cur = lane;
+        bool taken = false, done = !active;
+        while (__ballot(!done) != 0) {
+            const int tc = __shfl((int)t, cur, WAVE);
+            const int dc = __shfl((int)dup, cur, WAVE);
+            if (!done) {
+                if (dc) {
+                    taken = true;
+                    done = true;
+                } else {
+                    const int q = tc - base;
+                    if (q < 0 || q >= cur) done = true;
+                    else cur = q;
+                }
+            }
+        }
+        x = active ? (taken ? base + lane : (int)t) : 0;
+    }
+
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        if (q < b) s_y[q] = (yv[u] >= 0 && yv[u] < a.K) ? (int32_t)yv[u] : LAB_INVALID;
+    }
+    for (int q = tid + YPRE * TPB; q < b; q += TPB) {
+        const int64_t y = a.batch_y[q];
+        s_y[q] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+    }
+
+    if ((int)blockIdx.x < a.nchunks) {
+        // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
+        const int k_lo = blockIdx.x * CH;
+        s_hist[tid] = 0;
+        __syncthreads();
+        if (w0) {
+            const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
+            if (active && k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
+            if (blockIdx.x == 0 && __ballot(active && k == LAB_INVALID) != 0 && lane == 0)
+                atomicOr(&a.state->flags, RB_FLAG_BAD_LABEL);
+        }
+        __syncthreads();
+        const int kk = k_lo + tid;
+        int32_t nf = 0;
+        if (kk < a.K) {
+            int64_t v = (int64_t)a.fill_old[kk] + s_hist[tid];
+            nf = (int32_t)(v < a.S ? v : a.S);
+            a.fill_new[kk] = nf;
+        }
+        int total;
+        block_scan_excl(nf, total, s_wave);
+        if (tid == 0) a.chunk_new[blockIdx.x] = total;
+        return;
+    }
+
+    // ---- movers ---------------------------------------------------------------
+    const int mover = blockIdx.x - a.nchunks;
+    const int group = mover / a.tpr, tile = mover % a.tpr;
+    const int64_t v_lo = (int64_t)tile * a.tile_vec;
+    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+
+    int32_t k = LAB_UNSELECTED;      // wavefront 0: class of the lane's candidate
+    for (int rr = 0; rr < a.rpb; ++rr) {
+        const int i = group * a.rpb + rr;      // candidate, in Floyd emission order
+        if (i >= c) break;
+        const int par = rr & 1;
+        if (w0) {
+            const int pi = __shfl(x, i, WAVE);
+            if (lane == 0) s_p[par] = pi;
+        }
+        __syncthreads();
+        const int p = s_p[par];
+        // the row is read while wavefront 0 works out where it goes
+        Tile<U, NT> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+
+        if (w0) {
+            if (rr == 0) k = active ? s_y[x] : LAB_UNSELECTED;
+            const int32_t ki = __shfl(k, i, WAVE);
+            int64_t dst = -1;
+            if (ki >= 0) {
+                // candidates of class ki; in mini-batch order the one with `rank`
+                // class-mates before it is insertion number fill0 + rank of the class
+                const bool same = active && k == ki;
+                const int total = __popcll(__ballot(same));
+                const int rank = __popcll(__ballot(same && x < p));
+                const int64_t fill0 = a.fill_old[ki];
+                if (fill0 + total <= a.S) {
+                    dst = (int64_t)ki * a.S + fill0 + rank;        // all append: distinct slots
+                } else {
+                    // Insertions beyond the capacity overwrite a uniformly drawn slot.  This
+                    // candidate is not stored if a later class-mate overwrites its slot.
+                    const int draw = same ? (int)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S) : -1;
+                    const int own = fill0 + rank < a.S ? (int)(fill0 + rank) : __shfl(draw, i, WAVE);
+                    uint64_t rivals = __ballot(same && x > p && draw == own);
+                    bool beaten = false;
+                    while (rivals != 0) {
+                        const int m = __builtin_ctzll(rivals);
+                        rivals &= rivals - 1;
+                        const int xm = __builtin_amdgcn_readlane(x, m);
+                        const int rank_m = __popcll(__ballot(same && x < xm));
+                        beaten |= (fill0 + rank_m >= a.S);         // m does overwrite
+                    }
+                    if (!beaten) dst = (int64_t)ki * a.S + own;
+                }
+            }
+            if (lane == 0) s_dst[par] = dst;
+        }
+        __syncthreads();
+        const int64_t dst_row = s_dst[par];
+        if (dst_row >= 0) {
+            t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // rb_sample_augment: n = min(r, F) distinct stored samples, uniformly.
 //
+// The g-th stored sample (class-major order) is located through the per-class
+// fill counts.  Up to MAXPER * TPB classes every workgroup reads all counts in
+// one round of loads ("direct"); above that it reads the per-chunk sums first
+// and then the CH counts of the one chunk that holds g.
+//
 // LDS (dynamic): s_cpre[nchunks] i32 (stored samples before each chunk of CH
-// classes), s_t[r] u32 (Floyd draws).
+// classes; unused in direct mode), s_t[r] u32 (Floyd draws).
 // Grid: ceil(r / rpb) * tpr workgroups, row/tile mapping as in rb_update.
 // ---------------------------------------------------------------------------
 struct SampleArgs {
@@ -338,6 +520,7 @@ struct SampleArgs {
     int32_t tpr;
     int32_t tile_vec;
     int32_t rpb;
+    int32_t direct;       // 1: K <= MAXPER * TPB, all fill counts are read at once
 };
 
 template <int U, bool NT>
@@ -351,20 +534,34 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
 
     const int tid = threadIdx.x;
 
-    // ---- F and the number of stored samples before every chunk -----------------
-    const int cper = (a.nchunks + TPB - 1) / TPB;
-    int csum = 0;
-    for (int u = 0; u < cper; ++u) {
-        int ch = tid * cper + u;
-        if (ch < a.nchunks) csum += a.chunk[ch];
-    }
+    // ---- F, and where every class (direct) or chunk of classes starts ----------
     int F;
-    int cbefore = block_scan_excl(csum, F, s_wave);
-    for (int u = 0; u < cper; ++u) {
-        int ch = tid * cper + u;
-        if (ch < a.nchunks) {
-            s_cpre[ch] = cbefore;
-            cbefore += a.chunk[ch];
+    int32_t freg[MAXPER];          // direct mode: fill counts of classes [tid*kper, tid*kper + kper)
+    int before = 0;                // direct mode: stored samples in classes below tid*kper
+    const int kper = (a.K + TPB - 1) / TPB;
+    if (a.direct) {
+        int local = 0;
+#pragma unroll
+        for (int u = 0; u < MAXPER; ++u) {
+            const int k = tid * kper + u;
+            freg[u] = (u < kper && k < a.K) ? a.fill[k] : 0;
+            local += freg[u];
+        }
+        before = block_scan_excl(local, F, s_wave);
+    } else {
+        const int cper = (a.nchunks + TPB - 1) / TPB;
+        int csum = 0;
+        for (int u = 0; u < cper; ++u) {
+            int ch = tid * cper + u;
+            if (ch < a.nchunks) csum += a.chunk[ch];
+        }
+        int cbefore = block_scan_excl(csum, F, s_wave);
+        for (int u = 0; u < cper; ++u) {
+            int ch = tid * cper + u;
+            if (ch < a.nchunks) {
+                s_cpre[ch] = cbefore;
+                cbefore += a.chunk[ch];
+            }
         }
     }
     const int n = a.r < F ? a.r : F;
@@ -402,21 +599,34 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
         }
         const int g = taken ? base + j : (int)s_t[j];   // g-th stored sample, class-major
 
-        // chunk holding g: the last one with s_cpre <= g
-        int lo = 0, hi = a.nchunks - 1;
-        while (lo < hi) {
-            int mid = (lo + hi + 1) >> 1;
-            if (s_cpre[mid] <= g) lo = mid; else hi = mid - 1;
-        }
-        const int gl = g - s_cpre[lo];
         if (tid == 0) { s_pick[0] = 0; s_pick[1] = 0; }   // never left undefined
-        const int k = lo * CH + tid;
-        const int f = k < a.K ? a.fill[k] : 0;
-        int unused;
-        const int before = block_scan_excl(f, unused, s_wave);
-        if (gl >= before && gl < before + f) {
-            s_pick[0] = k;
-            s_pick[1] = gl - before;
+        if (a.direct) {
+            __syncthreads();
+            int acc = before;
+#pragma unroll
+            for (int u = 0; u < MAXPER; ++u) {
+                if (g >= acc && g < acc + freg[u]) {
+                    s_pick[0] = tid * kper + u;
+                    s_pick[1] = g - acc;
+                }
+                acc += freg[u];
+            }
+        } else {
+            // chunk holding g: the last one with s_cpre <= g
+            int lo = 0, hi = a.nchunks - 1;
+            while (lo < hi) {
+                int mid = (lo + hi + 1) >> 1;
+                if (s_cpre[mid] <= g) lo = mid; else hi = mid - 1;
+            }
+            const int gl = g - s_cpre[lo];
+            const int k = lo * CH + tid;
+            const int f = k < a.K ? a.fill[k] : 0;
+            int unused;
+            const int kbefore = block_scan_excl(f, unused, s_wave);
+            if (gl >= kbefore && gl < kbefore + f) {
+                s_pick[0] = k;
+                s_pick[1] = gl - kbefore;
+            }
         }
         __syncthreads();
         const int pk = s_pick[0], ps = s_pick[1];
@@ -425,6 +635,119 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
         Tile<U, NT> t;
         t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
         t.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
+        if (tile == 0 && tid == 0) a.out_y[j] = pk;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// rb_sample_augment for r <= WAVE representatives and at most WAVE chunks of
+// classes: the first wavefront of each workgroup computes the plan, the others
+// only move data.  Up to DIRECT_CHUNKS chunks the wavefront reads every fill
+// count at once (16 consecutive classes per lane); above, lane ch reads the sum
+// of chunk ch and the CH counts of the one chunk that holds the wanted sample
+// are read afterwards (4 consecutive classes per lane).
+// ---------------------------------------------------------------------------
+constexpr int DIRECT_CHUNKS = 4;
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a)
+{
+    __shared__ int s_pick[2][2];    // (class, slot) of the current row, double-buffered over rows
+    __shared__ int s_n;
+
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const bool w0 = tid < WAVE;
+    const bool direct = a.nchunks <= DIRECT_CHUNKS;
+
+    int n = 0, base = 0;
+    uint32_t t = 0xFFFFFFFFu;       // wavefront 0, lane i < n: Floyd draw i
+    int fv[16];                     // direct: fill counts of classes [16*lane, 16*lane + 16)
+    int cs = 0, incl = 0;           // direct: samples in / up to the lane's 16 classes; else: in / up to chunk `lane`
+    if (w0) {
+        if (direct) {
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const int first = 16 * lane + 4 * m;
+                int4 f = make_int4(0, 0, 0, 0);
+                if (first < a.nchunks * CH) f = *reinterpret_cast<const int4*>(a.fill + first);
+                fv[4 * m] = f.x; fv[4 * m + 1] = f.y; fv[4 * m + 2] = f.z; fv[4 * m + 3] = f.w;
+            }
+#pragma unroll
+            for (int m = 0; m < 16; ++m) cs += fv[m];
+        } else {
+            cs = lane < a.nchunks ? a.chunk[lane] : 0;
+        }
+        incl = wave_scan_incl(cs);
+        const int F = __shfl(incl, WAVE - 1, WAVE);
+        n = a.r < F ? a.r : F;
+        base = F - n;
+        if (lane < n) t = (uint32_t)below(a.sd, PURPOSE_SAMPLE, (uint32_t)lane, (uint64_t)base + lane + 1);
+        if (lane == 0) {
+            s_n = n;
+            if (blockIdx.x == 0) a.state->last_n = n;
+        }
+    }
+
+    const int group = blockIdx.x / a.tpr, tile = blockIdx.x % a.tpr;
+    const int64_t v_lo = (int64_t)tile * a.tile_vec;
+    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+
+    for (int rr = 0; rr < a.rpb; ++rr) {
+        const int j = group * a.rpb + rr;      // output row
+        if (j >= a.r) break;
+        const int par = rr & 1;
+        if (w0 && j < n) {
+            if (lane == 0) { s_pick[par][0] = 0; s_pick[par][1] = 0; }   // never left undefined
+            // Floyd: draw j is replaced by base + j iff an earlier draw had the same value, or
+            // it equals base + q for an earlier q whose own draw was replaced.
+            int cur = j;
+            bool taken = false;
+            for (;;) {
+                const uint32_t tc = (uint32_t)__shfl((int)t, cur, WAVE);
+                if (__ballot(lane < cur && t == tc) != 0) { taken = true; break; }
+                const int64_t q = (int64_t)tc - base;
+                if (q < 0 || q >= cur) break;
+                cur = (int)q;
+            }
+            const int gj = taken ? base + j : __shfl((int)t, j, WAVE);   // class-major index of the sample
+            if (direct) {
+                int acc = incl - cs;
+                if (gj >= acc && gj < incl) {
+                    int u = 0;
+#pragma unroll
+                    for (int m = 0; m < 15; ++m) {
+                        if (u == m && gj >= acc + fv[m]) { acc += fv[m]; u = m + 1; }
+                    }
+                    s_pick[par][0] = 16 * lane + u;
+                    s_pick[par][1] = gj - acc;
+                }
+            } else {
+                // chunk holding gj: the number of chunks that end at or before it
+                const int ch = __popcll(__ballot(lane < a.nchunks && incl <= gj));
+                const int gl = gj - (__shfl(incl, ch, WAVE) - __shfl(cs, ch, WAVE));
+                const int4 f = *reinterpret_cast<const int4*>(a.fill + (int64_t)ch * CH + 4 * lane);
+                const int local = f.x + f.y + f.z + f.w;
+                const int lincl = wave_scan_incl(local);
+                int acc = lincl - local;
+                if (gl >= acc && gl < lincl) {
+                    int u = 0;
+                    if (gl >= acc + f.x) { acc += f.x; u = 1;
+                        if (gl >= acc + f.y) { acc += f.y; u = 2;
+                            if (gl >= acc + f.z) { acc += f.z; u = 3; } } }
+                    s_pick[par][0] = ch * CH + 4 * lane + u;
+                    s_pick[par][1] = gl - acc;
+                }
+            }
+        }
+        __syncthreads();
+        if (j >= s_n) {                        // fewer stored samples than asked for
+            if (tile == 0 && tid == 0) a.out_y[j] = -1;
+            continue;
+        }
+        const int pk = s_pick[par][0], ps = s_pick[par][1];
+        Tile<U, NT> t2;
+        t2.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
+        t2.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
         if (tile == 0 && tid == 0) a.out_y[j] = pk;
     }
 }
@@ -518,6 +841,15 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows)
 template <bool NT>
 hipError_t launch_update(const UpdateArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
+    if (a.c <= WAVE) {
+        switch (unroll) {
+        case 1: rb_update_small_kernel<1, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
+        case 2: rb_update_small_kernel<2, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
+        case 4: rb_update_small_kernel<4, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
+        default: rb_update_small_kernel<8, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
+        }
+        return hipGetLastError();
+    }
     switch (unroll) {
     case 1: rb_update_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
     case 2: rb_update_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
@@ -530,6 +862,15 @@ hipError_t launch_update(const UpdateArgs& a, int unroll, dim3 grid, size_t lds,
 template <bool NT>
 hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
+    if (a.r <= WAVE && a.nchunks <= WAVE) {
+        switch (unroll) {
+        case 1: rb_sample_small_kernel<1, NT><<<grid, TPB, 0, st>>>(a); break;
+        case 2: rb_sample_small_kernel<2, NT><<<grid, TPB, 0, st>>>(a); break;
+        case 4: rb_sample_small_kernel<4, NT><<<grid, TPB, 0, st>>>(a); break;
+        default: rb_sample_small_kernel<8, NT><<<grid, TPB, 0, st>>>(a); break;
+        }
+        return hipGetLastError();
+    }
     switch (unroll) {
     case 1: rb_sample_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
     case 2: rb_sample_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
@@ -700,6 +1041,7 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     a.S = rb->S;
     a.row_vec = rb->row_vec;
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = sh.rpb;
+    a.direct = rb->K <= (int64_t)MAXPER * TPB ? 1 : 0;
     const dim3 grid((unsigned)(sh.groups * sh.tpr));
     const size_t lds = ((size_t)rb->nchunks + (size_t)r) * 4;
     hipError_t e = rb->opt_nt ? launch_sample<true>(a, sh.unroll, grid, lds, rb->stream)
