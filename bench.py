@@ -20,6 +20,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this much memory (>> 256 MB of last-level cache)
+# HBM bytes per launch of the dominant kernel (the gather of rb_sample_augment) as counted by two
+# `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
+# known size; the text summaries with the exact commands are kept under profiles/.
+MEASURED_TRAFFIC = {"C4-1000x300-bf16-3x224x224-zipf": 38637524}
 
 
 def log(*a):
@@ -104,33 +108,6 @@ class Rig:
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    def kernel_ms(self, n, which):
-        """Average duration of one kernel: an event pair around each of n launches, inside a normal step sequence."""
-        torch = self.torch
-        w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
-        ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n)]
-        torch.cuda.synchronize()
-        t = self.step
-        for i in range(n):
-            bx, by, ox, oy = args[t % P]
-            if which == "update":
-                ev[i][0].record(self.stream)
-            rc = rb.rb_update(h, bx, by, w.b, w.c, w.lib_seed, t)
-            assert rc == 0
-            if which == "update":
-                ev[i][1].record(self.stream)
-            else:
-                ev[i][0].record(self.stream)
-            rc = rb.rb_sample_augment(h, w.r, w.lib_seed, t, ox, oy)
-            assert rc == 0
-            if which == "sample":
-                ev[i][1].record(self.stream)
-            t += 1
-        self.step = t
-        torch.cuda.synchronize()
-        times = sorted(a.elapsed_time(b) for a, b in ev)
-        return sum(times) / n, times[n // 2]
-
     def close(self):
         self.buf.close()
         del self.aug_x, self.aug_y, self.buf
@@ -161,27 +138,42 @@ def copy_ceiling(torch, rb, nbytes=1 << 30, reps=20):
     return best
 
 
-def overlap_leg(rig, steps, target_ms):
+def overlap_leg(rig, steps, target_ms, kind="fma"):
     """Steps of the asynchronous pipeline of Sec. IV-D: buffer work on the side stream under a stand-in
-    compute kernel on the main stream.  Returns ms per iteration: compute alone, buffer alone, both."""
+    for the training computation on the main stream (kind "fma": register-only multiply-add loop on all
+    compute units; kind "hbm": a large streaming copy, the worst case for a bandwidth-bound path).
+    Returns ms per iteration: stand-in alone, buffer alone, both overlapped."""
     torch, rb, w = rig.torch, rig.rb, rig.w
     main = torch.cuda.current_stream(rig.dev)
     blocks = 256 * 8
     sink = torch.empty(blocks * 256, dtype=torch.float32, device=rig.dev)
+    big = None
+    if kind == "hbm":
+        big = torch.empty((2, 1 << 30), dtype=torch.uint8, device=rig.dev)
+        big.fill_(3)
 
-    def compute_ms(iters, n=5):
+    def standin(amount):
+        if kind == "fma":
+            rb.rb_standin_compute(None, sink, blocks, amount)
+        else:
+            rb.rb_copy_bytes(None, big[1], big[0], amount, 2, 1)
+
+    def standin_ms(amount, n=5):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         torch.cuda.synchronize()
         e0.record(main)
         for _ in range(n):
-            rb.rb_standin_compute(None, sink, blocks, iters)
+            standin(amount)
         e1.record(main)
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / n
 
-    compute_ms(1000)
-    iters = max(1, int(20000 * target_ms / compute_ms(20000)))
-    t_compute = compute_ms(iters, steps)
+    probe = 20000 if kind == "fma" else (256 << 20)
+    standin_ms(probe)
+    amount = max(1, int(probe * target_ms / standin_ms(probe)))
+    if kind == "hbm":
+        amount = min(1 << 30, max(1 << 20, amount // 4096 * 4096))
+    t_alone = standin_ms(amount, steps)
     t_rb = rig.timed(steps)
     done = [torch.cuda.Event() for _ in range(4)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
@@ -192,13 +184,14 @@ def overlap_leg(rig, steps, target_ms):
             main.wait_event(done[(t - 1) % 4])        # (1) representatives sampled during the previous iteration
         rig.enqueue(1)                                 # (2) update with this mini-batch, then sample the next representatives
         done[t % 4].record(rig.stream)
-        rb.rb_standin_compute(None, sink, blocks, iters)   # (3), (4) forward and backward pass stand-in
+        standin(amount)                                # (3), (4) forward and backward pass stand-in
     main.wait_event(done[(steps - 1) % 4])
     e1.record(main)
     torch.cuda.synchronize()
     t_both = e0.elapsed_time(e1) / steps
-    return {"compute_ms": round(t_compute, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
-            "overhead_frac": round((t_both - t_compute) / t_compute, 4)}
+    del big
+    return {"standin": kind, "standin_ms": round(t_alone, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
+            "overhead_frac": round((t_both - t_alone) / t_alone, 4)}
 
 
 def cpu_baseline(w, wl, budget_s=12.0, max_steps=4000):
@@ -228,26 +221,24 @@ def cpu_baseline(w, wl, budget_s=12.0, max_steps=4000):
             "gb_per_s": round(w.bytes_per_step() * steps / dt / 1e9, 3)}
 
 
-def measure(w, torch, rb, wl, steps, warmup, prefill, kernel_launches=200):
+def measure(w, torch, rb, wl, steps, warmup, prefill):
     rig = Rig(w, torch, rb, wl)
     if prefill:
         rig.prefill()
     rig.enqueue(warmup)
     torch.cuda.synchronize()
     ms = rig.timed(steps)
-    ms_update = rig.timed(min(steps, 500), do_sample=False)
-    # the sample-only loop re-reads the same buffer state; rows come from the whole buffer
-    ms_sample = rig.timed(min(steps, 500), do_update=False)
-    k_sample_avg, k_sample_med = rig.kernel_ms(kernel_launches, "sample")
-    k_update_avg, k_update_med = rig.kernel_ms(kernel_launches, "update")
+    # One kernel alone, launched back to back on the same stream with HIP events around the whole
+    # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
+    # gap (an event pair around every single launch would add several microseconds to each).
+    ms_update = rig.timed(min(steps, 1000), do_sample=False)
+    ms_sample = rig.timed(min(steps, 1000), do_update=False)
     fill, last_n, flags = rig.buf.read_state()
     res = {
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "update_only_ms": ms_update, "sample_only_ms": ms_sample,
-        "sample_kernel_ms_event_avg": k_sample_avg, "sample_kernel_ms_event_med": k_sample_med,
-        "update_kernel_ms_event_avg": k_update_avg, "update_kernel_ms_event_med": k_update_med,
+        "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }
     return rig, res
@@ -263,6 +254,9 @@ def main():
     ap.add_argument("--others", default="C3,C5", help="comma list of further workloads reported inside the line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
+    ap.add_argument("--pmc-run", action="store_true",
+                    help="short fixed sequence for `rocprofv3 --pmc`: 100 warm-up steps, 20 steps, then 3 plain copies "
+                         "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
     ap.add_argument("--unroll", type=int, default=0)
     ap.add_argument("--nontemporal", type=int, default=1)
     a = ap.parse_args()
@@ -280,6 +274,20 @@ def main():
         rig.buf.set_option(rb.RB_OPT_NONTEMPORAL, a.nontemporal)
 
     w = wl.by_name(a.workload)
+    if a.pmc_run:
+        rig = Rig(w, torch, rb, wl)
+        if a.prefill:
+            rig.prefill()
+        rig.enqueue(120)
+        torch.cuda.synchronize()
+        nbytes = 256 << 20
+        src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            rb.rb_copy_bytes(None, dst, src, nbytes, 4, 1)
+        torch.cuda.synchronize()
+        log(f"[bench] pmc run done: {w.name}, 120 steps, 3 copies of {nbytes} bytes")
+        return
     log(f"[bench] {w.name}: buffer {w.buffer_bytes / 1e9:.1f} GB, {w.bytes_per_step() / 1e6:.2f} MB/step")
     ceiling = copy_ceiling(torch, rb)
     log(f"[bench] plain copy ceiling {ceiling:.0f} GB/s")
@@ -297,13 +305,14 @@ def main():
         ow = wl.by_name(name)
         orig, ores = measure(ow, torch, rb, wl, min(a.steps, ow.steps), a.warmup, False)
         if ow.name.startswith("C3") and not a.no_overlap:
-            ores["overlap"] = {f"{d}ms": overlap_leg(orig, 200, d) for d in (0.5, 2.0, 10.0)}
+            ores["overlap"] = {f"fma_{d}ms": overlap_leg(orig, 200, d) for d in (0.5, 2.0, 10.0)}
+            ores["overlap"]["hbm_copy_0.3ms"] = overlap_leg(orig, 200, 0.3, kind="hbm")
         orig.close()
         others[ow.name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in ores.items()}
         log(f"[bench] {json.dumps(others[ow.name])}")
 
     # roofline of the dominant kernel: the gather of rb_sample_augment moves r rows, read once and written once
-    k_ms = res["sample_kernel_ms_event_avg"]
+    k_ms = res["sample_kernel_ms"]
     n_rows = min(w.r, res["last_n"])
     achieved = 2 * n_rows * w.row_bytes / (k_ms * 1e-3) / 1e9
     line = {
@@ -317,7 +326,8 @@ def main():
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
         "reps_per_s": round(res["reps_per_s"], 1),
         "roofline": {"bound": "hbm", "kernel": "rb_sample_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": None,
+                     "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
+                     "traffic": MEASURED_TRAFFIC.get(w.name) if not a.prefill else None,
                      "bytes_per_launch": 2 * n_rows * w.row_bytes, "kernel_ms": round(k_ms, 5),
                      "copy_ceiling_gbs": round(ceiling, 1)},
         "detail": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()},
