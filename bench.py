@@ -78,14 +78,20 @@ class Rig:
         fill, _, _ = self.buf.read_state()
         assert int(fill.sum()) == total, (int(fill.sum()), total)
 
-    def enqueue(self, n, do_update=True, do_sample=True):
+    def enqueue(self, n, do_update=True, do_sample=True, single_call=False):
         """Enqueue n consecutive steps on the side stream (no synchronisation)."""
         w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
-        upd, smp = rb.rb_update, rb.rb_sample_augment
+        upd, smp, both = rb.rb_update, rb.rb_sample_augment, rb.rb_update_sample
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
         t = self.step
         for _ in range(n):
             bx, by, ox, oy = args[t % P]
+            if single_call:
+                rc = both(h, bx, by, b, c, r, seed, t, ox, oy)
+                if rc:
+                    raise RuntimeError(f"rb_update_sample -> {rc}")
+                t += 1
+                continue
             if do_update:
                 rc = upd(h, bx, by, b, c, seed, t)
                 if rc:

@@ -122,6 +122,20 @@ int rb_sample_augment(rb_buffer *rb, int64_t r, uint64_t seed, uint64_t step,
                       void *out_x, int64_t *out_y);
 
 /*
+ * The paper's single primitive (Listing 1, `r = RehearsalBuffer.update(m)`;
+ * Sec. IV-D step 2: update the buffer with the mini-batch, then sample the next
+ * representatives): rb_update(rb, batch_x, batch_y, b, c, seed, step) followed
+ * by rb_sample_augment(rb, r, seed, step, out_x, out_y), as one call with the
+ * same arguments, meaning, errors and, bit for bit, the same results.  When
+ * 1 <= c <= 64, 1 <= r <= 64 and classes <= 1024 both halves run as ONE kernel
+ * launch (a representative whose slot is being written in this very step is
+ * copied from the mini-batch row stored there); otherwise the two kernels are
+ * enqueued one after the other.  out_x must not overlap batch_x.
+ */
+int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y, int64_t b, int64_t c,
+                     int64_t r, uint64_t seed, uint64_t step, void *out_x, int64_t *out_y);
+
+/*
  * Synchronise the bound stream and copy state to the host: fill_host[classes]
  * (samples held per class), *last_n_host (n of the latest rb_sample_augment),
  * *flags_host (RB_FLAG_*).  Any pointer may be null.  Not for the hot path.
@@ -132,8 +146,10 @@ int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint3
  * thread keeps in flight while moving a row (0 = automatic, else 1, 2, 4 or 8).
  * RB_OPT_NONTEMPORAL: 1 (default) moves rows with streaming loads/stores, 0
  * with plain ones.  RB_OPT_ROWS_PER_BLOCK: rows one workgroup moves one after
- * the other when a row fits a single tile (0 = automatic, else 1..16). */
-enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2 };
+ * the other when a row fits a single tile (0 = automatic, else 1..16).
+ * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
+ * 0 makes it always enqueue the two kernels. */
+enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
 
 /* Free the host handle.  Device memory stays the caller's. */

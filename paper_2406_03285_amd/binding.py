@@ -17,10 +17,10 @@ RB_OK, RB_EINVAL, RB_ENOMEM, RB_ESTATE, RB_EHIP = 0, -1, -2, -3, -4
 RB_MAX_BATCH = 4096
 RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
-RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK = 0, 1, 2
+RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE = 0, 1, 2, 3
 
 EXPORTS = (
-    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_stream", "rb_update", "rb_sample_augment",
+    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -44,6 +44,7 @@ def _load():
     L.rb_set_stream.argtypes = [vp, vp]
     L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
+    L.rb_update_sample.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp]
     L.rb_read_state.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(C.c_uint32)]
     L.rb_set_option.argtypes = [vp, i32, i64]
     L.rb_destroy.argtypes = [vp]
@@ -108,6 +109,11 @@ def rb_update(rb, batch_x, batch_y, b, c, seed, step):
 
 def rb_sample_augment(rb, r, seed, step, out_x, out_y):
     return _L.rb_sample_augment(rb, int(r), int(seed), int(step), _ptr(out_x), _ptr(out_y))
+
+
+def rb_update_sample(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y):
+    return _L.rb_update_sample(rb, _ptr(batch_x), _ptr(batch_y), int(b), int(c), int(r), int(seed), int(step),
+                               _ptr(out_x), _ptr(out_y))
 
 
 def rb_read_state(rb, classes):
@@ -183,6 +189,17 @@ class RehearsalBuffer:
             assert out_x.shape[0] >= r and out_y.shape[0] >= r
             assert out_x.device == self.device and out_y.device == self.device
         _check(rb_sample_augment(self.handle, r, seed, step, out_x, out_y), "rb_sample_augment")
+
+    def update_sample(self, batch_x, batch_y, c, r, seed, step, out_x, out_y):
+        assert batch_x.is_contiguous() and batch_y.is_contiguous() and batch_y.dtype == torch.int64
+        assert batch_x.dtype == self.dtype and tuple(batch_x.shape[1:]) == self.sample_shape
+        b = batch_y.shape[0]
+        assert batch_x.shape[0] == b
+        if r > 0:
+            assert out_x.is_contiguous() and out_y.is_contiguous() and out_y.dtype == torch.int64
+            assert out_x.dtype == self.dtype and tuple(out_x.shape[1:]) == self.sample_shape
+            assert out_x.shape[0] >= r and out_y.shape[0] >= r
+        _check(rb_update_sample(self.handle, batch_x, batch_y, b, c, r, seed, step, out_x, out_y), "rb_update_sample")
 
     def read_state(self):
         rc, fill, last_n, flags = rb_read_state(self.handle, self.K)

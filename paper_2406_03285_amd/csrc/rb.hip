@@ -333,6 +333,74 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 }
 
 // ---------------------------------------------------------------------------
+// Pieces of the plan shared by the small-count kernels.  Called by wavefront 0
+// only, with all of its 64 lanes active.
+// ---------------------------------------------------------------------------
+
+// Floyd's c-subset of the b mini-batch positions, all draws at once: lane i < c
+// draws t_i uniform in [0, b-c+i]; the sequential algorithm replaces t_i by
+// b-c+i when t_i was chosen before, which is the case iff an earlier lane drew
+// the same value, or t_i = b-c+q for an earlier q whose own draw was replaced.
+// Returns the lane's candidate position (0 for lanes >= c); s_first: b words of LDS.
+__device__ __forceinline__ int wave_select(const Seed& sd, int b, int c, uint32_t* s_first, bool& active)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const int base = b - c;
+    active = lane < c;
+    const uint32_t t = active ? (uint32_t)below(sd, PURPOSE_SELECT, (uint32_t)lane, (uint64_t)(base + lane + 1)) : 0u;
+    if (active) s_first[t] = 0xFFFFFFFFu;
+    if (active) atomicMin(&s_first[t], (uint32_t)lane);
+    const bool dup = active && s_first[t] != (uint32_t)lane;
+    int cur = lane;
+    bool taken = false, done = !active;
+    while (__ballot(!done) != 0) {
+        const int tc = __shfl((int)t, cur, WAVE);
+        const int dc = __shfl((int)dup, cur, WAVE);
+        if (!done) {
+            if (dc) {
+                taken = true;
+                done = true;
+            } else {
+                const int q = tc - base;
+                if (q < 0 || q >= cur) done = true;
+                else cur = q;
+            }
+        }
+    }
+    return active ? (taken ? base + lane : (int)t) : 0;
+}
+
+// Where candidate i (mini-batch position p) is stored: row index k*S + slot, or
+// -1 if it is not stored (label outside [0, K), or a later class-mate overwrites
+// its slot).  Lane l holds candidate l: position x, class k.
+__device__ __forceinline__ int64_t wave_place(const Seed& sd, bool active, int x, int32_t k, int i, int p,
+                                              const int32_t* __restrict__ fill_old, int64_t S)
+{
+    const int32_t ki = __shfl(k, i, WAVE);
+    if (ki < 0) return -1;
+    // candidates of class ki; in mini-batch order the one with `rank` class-mates
+    // before it is insertion number fill0 + rank of the class
+    const bool same = active && k == ki;
+    const int total = __popcll(__ballot(same));
+    const int rank = __popcll(__ballot(same && x < p));
+    const int64_t fill0 = fill_old[ki];
+    if (fill0 + total <= S) return (int64_t)ki * S + fill0 + rank;     // all append: distinct slots
+    // Insertions beyond the capacity overwrite a uniformly drawn slot.  This
+    // candidate is not stored if a later class-mate overwrites its slot.
+    const int draw = same ? (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S) : -1;
+    const int own = fill0 + rank < S ? (int)(fill0 + rank) : __shfl(draw, i, WAVE);
+    uint64_t rivals = __ballot(same && x > p && draw == own);
+    while (rivals != 0) {
+        const int m = __builtin_ctzll(rivals);
+        rivals &= rivals - 1;
+        const int xm = __builtin_amdgcn_readlane(x, m);
+        const int rank_m = __popcll(__ballot(same && x < xm));
+        if (fill0 + rank_m >= S) return -1;                            // m does overwrite
+    }
+    return (int64_t)ki * S + own;
+}
+
+// ---------------------------------------------------------------------------
 // rb_update for c <= WAVE candidates: the plan is computed by the first
 // wavefront of each workgroup alone, one lane per candidate, with ballots and
 // lane reads instead of workgroup scans; the other three wavefronts only move
@@ -356,7 +424,7 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const bool w0 = tid < WAVE;
-    const int b = a.b, c = a.c, base = b - c;
+    const int b = a.b, c = a.c;
 
     // all labels of the mini-batch: requested now, parked in LDS once the selection is done
     int64_t yv[YPRE];
@@ -369,32 +437,7 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
     // wavefront 0: lane i computes candidate i of Floyd's emission order
     bool active = false;
     int x = 0;                       // its mini-batch position
-    if (w0) {
-        active = lane < c;
-        const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)lane, (uint64_t)(base + lane + 1)) : 0u;
-        // draw i is replaced by base + i iff an earlier lane drew the same value, or it
-        // equals base + q for an earlier q whose own draw was replaced
-        if (active) s_first[t] = 0xFFFFFFFFu;
-        if (active) atomicMin(&s_first[t], (uint32_t)lane);
-        const bool dup = active && s_first[t] != (uint32_t)lane;
-        int cur = lane;
-        bool taken = false, done = !active;
-        while (__ballot(!done) != 0) {
-            const int tc = __shfl((int)t, cur, WAVE);
-            const int dc = __shfl((int)dup, cur, WAVE);
-            if (!done) {
-                if (dc) {
-                    taken = true;
-                    done = true;
-                } else {
-                    const int q = tc - base;
-                    if (q < 0 || q >= cur) done = true;
-                    else cur = q;
-                }
-            }
-        }
-        x = active ? (taken ? base + lane : (int)t) : 0;
-    }
+    if (w0) x = wave_select(a.sd, b, c, s_first, active);
 
 #pragma unroll
     for (int u = 0; u < YPRE; ++u) {
@@ -454,34 +497,7 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
 
         if (w0) {
             if (rr == 0) k = active ? s_y[x] : LAB_UNSELECTED;
-            const int32_t ki = __shfl(k, i, WAVE);
-            int64_t dst = -1;
-            if (ki >= 0) {
-                // candidates of class ki; in mini-batch order the one with `rank`
-                // class-mates before it is insertion number fill0 + rank of the class
-                const bool same = active && k == ki;
-                const int total = __popcll(__ballot(same));
-                const int rank = __popcll(__ballot(same && x < p));
-                const int64_t fill0 = a.fill_old[ki];
-                if (fill0 + total <= a.S) {
-                    dst = (int64_t)ki * a.S + fill0 + rank;        // all append: distinct slots
-                } else {
-                    // Insertions beyond the capacity overwrite a uniformly drawn slot.  This
-                    // candidate is not stored if a later class-mate overwrites its slot.
-                    const int draw = same ? (int)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S) : -1;
-                    const int own = fill0 + rank < a.S ? (int)(fill0 + rank) : __shfl(draw, i, WAVE);
-                    uint64_t rivals = __ballot(same && x > p && draw == own);
-                    bool beaten = false;
-                    while (rivals != 0) {
-                        const int m = __builtin_ctzll(rivals);
-                        rivals &= rivals - 1;
-                        const int xm = __builtin_amdgcn_readlane(x, m);
-                        const int rank_m = __popcll(__ballot(same && x < xm));
-                        beaten |= (fill0 + rank_m >= a.S);         // m does overwrite
-                    }
-                    if (!beaten) dst = (int64_t)ki * a.S + own;
-                }
-            }
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
             if (lane == 0) s_dst[par] = dst;
         }
         __syncthreads();
@@ -664,6 +680,8 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
     int fv[16];                     // direct: fill counts of classes [16*lane, 16*lane + 16)
     int cs = 0, incl = 0;           // direct: samples in / up to the lane's 16 classes; else: in / up to chunk `lane`
     if (w0) {
+        // the fill counts are requested first; the random bits do not depend on them
+        // (only their reduction to [0, F-n+i] does) and are computed while the loads fly
         if (direct) {
 #pragma unroll
             for (int m = 0; m < 4; ++m) {
@@ -672,16 +690,19 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
                 if (first < a.nchunks * CH) f = *reinterpret_cast<const int4*>(a.fill + first);
                 fv[4 * m] = f.x; fv[4 * m + 1] = f.y; fv[4 * m + 2] = f.z; fv[4 * m + 3] = f.w;
             }
-#pragma unroll
-            for (int m = 0; m < 16; ++m) cs += fv[m];
         } else {
             cs = lane < a.nchunks ? a.chunk[lane] : 0;
+        }
+        const uint64_t bits = lane < a.r ? draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)lane) : 0;
+        if (direct) {
+#pragma unroll
+            for (int m = 0; m < 16; ++m) cs += fv[m];
         }
         incl = wave_scan_incl(cs);
         const int F = __shfl(incl, WAVE - 1, WAVE);
         n = a.r < F ? a.r : F;
         base = F - n;
-        if (lane < n) t = (uint32_t)below(a.sd, PURPOSE_SAMPLE, (uint32_t)lane, (uint64_t)base + lane + 1);
+        if (lane < n) t = (uint32_t)__umul64hi(bits, (uint64_t)base + lane + 1);
         if (lane == 0) {
             s_n = n;
             if (blockIdx.x == 0) a.state->last_n = n;
@@ -753,6 +774,236 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
 }
 
 // ---------------------------------------------------------------------------
+// rb_update_sample, c <= WAVE, r <= WAVE, at most DIRECT_CHUNKS chunks of
+// classes: update and sampling of one step in ONE launch.
+//
+// Grid: bookkeeping workgroups, then the movers of the c candidate rows
+// (exactly as in rb_update_small_kernel), then the movers of the r
+// representative rows.  A representative mover cannot read the fill counts
+// the bookkeeping workgroups of the same launch are writing, so it derives
+// them itself: old counts + a histogram of this step's candidates.  A
+// representative whose slot is written in this very step is copied from the
+// mini-batch row that is being stored there ("forwarding"), never from the
+// slot, so no workgroup reads a row another one is writing.
+//
+// LDS (dynamic): s_first[b], s_y[b] as in rb_update_small_kernel, then
+// s_old[DIRECT_CHUNKS*CH] (fill counts before the step) and
+// s_cnt[DIRECT_CHUNKS*CH] (candidates of each class in this step).
+// ---------------------------------------------------------------------------
+struct StepArgs {
+    UpdateArgs u;
+    vec16* out_x;
+    int64_t* out_y;
+    int32_t r;
+    int32_t first_gather;    // index of the first representative mover
+};
+
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
+{
+    const UpdateArgs& a = sa.u;
+    constexpr int NCLS = DIRECT_CHUNKS * CH;
+    extern __shared__ uint32_t lds[];
+    uint32_t* s_first = lds;                                       // [b]
+    int32_t* s_y = reinterpret_cast<int32_t*>(lds + a.b);          // [b]
+    int32_t* s_old = reinterpret_cast<int32_t*>(lds + ((2 * a.b + 3) & ~3));   // [NCLS], 16-byte aligned
+    int32_t* s_cnt = s_old + NCLS;                                 // [NCLS]
+    __shared__ int s_wave[NWAVE];
+    __shared__ int s_hist[CH];
+    __shared__ int s_p;             // candidate mover: mini-batch position of the row
+    __shared__ int64_t s_dst;       // candidate mover: slot row it is stored to, -1: not stored
+    __shared__ int s_n;             // representative mover: n = min(r, F)
+    __shared__ int s_pick[3];       // representative mover: class, slot, forwarding position (-1: read the slot)
+
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1);
+    const bool w0 = tid < WAVE;
+    const int b = a.b, c = a.c;
+    const bool gather = (int)blockIdx.x >= sa.first_gather;
+
+    // labels of the mini-batch (and, for representative movers, the fill counts): requested now
+    int64_t yv[YPRE];
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        yv[u] = q < b ? a.batch_y[q] : -1;
+    }
+    int4 fo = make_int4(0, 0, 0, 0);
+    if (gather && 4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+
+    bool active = false;
+    int x = 0;
+    uint64_t bits = 0;       // representative movers: random bits of the lane's sampling draw
+    if (w0) {
+        x = wave_select(a.sd, b, c, s_first, active);
+        if (gather && lane < sa.r) bits = draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)lane);
+    }
+
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        if (q < b) s_y[q] = (yv[u] >= 0 && yv[u] < a.K) ? (int32_t)yv[u] : LAB_INVALID;
+    }
+    for (int q = tid + YPRE * TPB; q < b; q += TPB) {
+        const int64_t y = a.batch_y[q];
+        s_y[q] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+    }
+
+    if ((int)blockIdx.x < a.nchunks) {
+        // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
+        const int k_lo = blockIdx.x * CH;
+        s_hist[tid] = 0;
+        __syncthreads();
+        if (w0) {
+            const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
+            if (active && k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
+            if (blockIdx.x == 0 && __ballot(active && k == LAB_INVALID) != 0 && lane == 0)
+                atomicOr(&a.state->flags, RB_FLAG_BAD_LABEL);
+        }
+        __syncthreads();
+        const int kk = k_lo + tid;
+        int32_t nf = 0;
+        if (kk < a.K) {
+            int64_t v = (int64_t)a.fill_old[kk] + s_hist[tid];
+            nf = (int32_t)(v < a.S ? v : a.S);
+            a.fill_new[kk] = nf;
+        }
+        int total;
+        block_scan_excl(nf, total, s_wave);
+        if (tid == 0) a.chunk_new[blockIdx.x] = total;
+        return;
+    }
+
+    if (!gather) {
+        // ---- candidate movers (rows of the mini-batch into their slots) ----------
+        const int mover = blockIdx.x - a.nchunks;
+        const int i = mover / a.tpr, tile = mover % a.tpr;     // candidate in Floyd emission order, tile of its row
+        const int64_t v_lo = (int64_t)tile * a.tile_vec;
+        const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+        if (w0) {
+            const int pi = __shfl(x, i, WAVE);
+            if (lane == 0) s_p = pi;
+        }
+        __syncthreads();
+        const int p = s_p;
+        Tile<U, NT> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+        if (w0) {
+            const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
+            if (lane == 0) s_dst = dst;
+        }
+        __syncthreads();
+        const int64_t dst_row = s_dst;
+        if (dst_row >= 0) {
+            t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+        }
+        return;
+    }
+
+    // ---- representative movers (stored samples into the augmented mini-batch) ---
+    const int mover = blockIdx.x - sa.first_gather;
+    const int j = mover / a.tpr, tile = mover % a.tpr;         // output row, tile of it
+    const int64_t v_lo = (int64_t)tile * a.tile_vec;
+    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+
+    *reinterpret_cast<int4*>(s_old + 4 * tid) = fo;
+    *reinterpret_cast<int4*>(s_cnt + 4 * tid) = make_int4(0, 0, 0, 0);
+    __syncthreads();
+    if (w0) {
+        const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
+        if (active && k >= 0) atomicAdd(&s_cnt[k], 1);
+        // fill counts after this step's update, 16 consecutive classes per lane
+        int fv[16];
+        int cs = 0;
+#pragma unroll
+        for (int m = 0; m < 16; ++m) {
+            const int64_t v = (int64_t)s_old[16 * lane + m] + s_cnt[16 * lane + m];
+            fv[m] = (int)(v < a.S ? v : a.S);
+            cs += fv[m];
+        }
+        const int incl = wave_scan_incl(cs);
+        const int F = __shfl(incl, WAVE - 1, WAVE);
+        const int n = sa.r < F ? sa.r : F;
+        const int base = F - n;
+        uint32_t t = 0xFFFFFFFFu;
+        if (lane < n) t = (uint32_t)__umul64hi(bits, (uint64_t)base + lane + 1);
+        if (lane == 0) {
+            s_n = n;
+            s_pick[0] = 0; s_pick[1] = 0; s_pick[2] = -1;
+            if (mover == 0) a.state->last_n = n;
+        }
+        if (j < n) {
+            // Floyd: draw j is replaced by base + j iff an earlier draw had the same value, or
+            // it equals base + q for an earlier q whose own draw was replaced.
+            int cur = j;
+            bool taken = false;
+            for (;;) {
+                const uint32_t tc = (uint32_t)__shfl((int)t, cur, WAVE);
+                if (__ballot(lane < cur && t == tc) != 0) { taken = true; break; }
+                const int64_t q = (int64_t)tc - base;
+                if (q < 0 || q >= cur) break;
+                cur = (int)q;
+            }
+            const int gj = taken ? base + j : __shfl((int)t, j, WAVE);   // class-major index of the sample
+            // locate it: the lane whose 16 classes hold it walks them
+            int acc = incl - cs;
+            const bool mine = gj >= acc && gj < incl;
+            int u = 0;
+            if (mine) {
+#pragma unroll
+                for (int m = 0; m < 15; ++m) {
+                    if (u == m && gj >= acc + fv[m]) { acc += fv[m]; u = m + 1; }
+                }
+            }
+            const int owner = __builtin_ctzll(__ballot(mine) | (1ull << 63));
+            const int pk = __shfl(16 * lane + u, owner, WAVE);
+            const int ps = __shfl(gj - acc, owner, WAVE);
+
+            // Is slot ps of class pk written in this step, and by which candidate?
+            const bool same = active && k == pk;
+            const uint64_t same_mask = __ballot(same);
+            const int64_t fill0 = s_old[pk];
+            int fwd = -1;
+            if (same_mask != 0 && (ps >= fill0 || fill0 + __popcll(same_mask) > a.S)) {
+                int my_rank = 0;                       // class-mates earlier in the mini-batch
+                uint64_t sm = same_mask;
+                while (sm != 0) {
+                    const int m = __builtin_ctzll(sm);
+                    sm &= sm - 1;
+                    my_rank += (int)(__builtin_amdgcn_readlane(x, m) < x);
+                }
+                int slot = -1;
+                if (same) {
+                    const int64_t at = fill0 + my_rank;
+                    slot = (int)(at < a.S ? at : (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S));
+                }
+                uint64_t writers = __ballot(same && slot == ps);
+                while (writers != 0) {                 // the one latest in the mini-batch is what the slot holds
+                    const int m = __builtin_ctzll(writers);
+                    writers &= writers - 1;
+                    const int xm = __builtin_amdgcn_readlane(x, m);
+                    fwd = xm > fwd ? xm : fwd;
+                }
+            }
+            if (lane == 0) { s_pick[0] = pk; s_pick[1] = ps; s_pick[2] = fwd; }
+        }
+    }
+    __syncthreads();
+    if (j >= s_n) {                            // fewer stored samples than asked for
+        if (tile == 0 && tid == 0) sa.out_y[j] = -1;
+        return;
+    }
+    const int pk = s_pick[0], ps = s_pick[1], fwd = s_pick[2];
+    const vec16* src = fwd >= 0 ? a.batch_x + (int64_t)fwd * a.row_vec
+                                : a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec;
+    Tile<U, NT> t;
+    t.load(src, v_lo, v_hi);
+    t.store(sa.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
+    if (tile == 0 && tid == 0) sa.out_y[j] = pk;
+}
+
+// ---------------------------------------------------------------------------
 // Measurement helpers
 // ---------------------------------------------------------------------------
 __global__ void __launch_bounds__(TPB) rb_standin_kernel(float* __restrict__ sink, int64_t iters)
@@ -798,7 +1049,7 @@ struct rb_buffer {
     // workspace layout (byte offsets)
     size_t off_fill[2], off_chunk[2], ws_bytes;
     // launch-shape knobs
-    int opt_unroll, opt_nt, opt_rpb;
+    int opt_unroll, opt_nt, opt_rpb, opt_fuse;
 };
 
 namespace {
@@ -881,6 +1132,18 @@ hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds,
 }
 
 template <bool NT>
+hipError_t launch_step(const StepArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: rb_step_small_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_step_small_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_step_small_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_step_small_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
+    }
+    return hipGetLastError();
+}
+
+template <bool NT>
 hipError_t launch_copy(vec16* dst, const vec16* src, int64_t nvec, int unroll, hipStream_t st)
 {
     const int64_t cap = (int64_t)TPB * unroll;
@@ -944,7 +1207,7 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_chunk[0] = off; off += chunk_bytes;
     rb->off_chunk[1] = off; off += chunk_bytes;
     rb->ws_bytes = off;
-    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0;
+    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1;
     *out = rb;
     return RB_OK;
 }
@@ -1049,6 +1312,52 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     return e == hipSuccess ? RB_OK : RB_EHIP;
 }
 
+int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c,
+                     int64_t r, uint64_t seed, uint64_t step, void* out_x, int64_t* out_y)
+{
+    if (!rb || !batch_x || !batch_y) return RB_EINVAL;
+    if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b) return RB_EINVAL;
+    if (!aligned(batch_x, 16) || !aligned(batch_y, 8)) return RB_EINVAL;
+    if (r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
+    if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+
+    const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse;
+    if (!fused) {
+        const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);
+        if (rc != RB_OK) return rc;
+        return rb_sample_augment(rb, r, seed, step, out_x, out_y);
+    }
+    const Shape sh = plan_shape(rb, c + r);
+    StepArgs sa;
+    UpdateArgs& a = sa.u;
+    a.batch_x = static_cast<const vec16*>(batch_x);
+    a.batch_y = batch_y;
+    a.buf_x = static_cast<vec16*>(rb->buf_x);
+    a.buf_y = rb->buf_y;
+    a.fill_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    a.fill_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_fill[rb->cur ^ 1]);
+    a.chunk_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_chunk[rb->cur ^ 1]);
+    a.state = reinterpret_cast<DevState*>(rb->ws);
+    a.sd = make_seed(seed, step);
+    a.b = (int32_t)b; a.c = (int32_t)c;
+    a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
+    a.S = rb->S;
+    a.row_vec = rb->row_vec;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = 1;
+    sa.out_x = static_cast<vec16*>(out_x);
+    sa.out_y = out_y;
+    sa.r = (int32_t)r;
+    sa.first_gather = (int32_t)(rb->nchunks + c * sh.tpr);
+    const dim3 grid((unsigned)(rb->nchunks + (c + r) * sh.tpr));
+    const size_t lds = (((size_t)b * 2 + 3) & ~(size_t)3) * 4 + (size_t)DIRECT_CHUNKS * CH * 8;
+    hipError_t e = rb->opt_nt ? launch_step<true>(sa, sh.unroll, grid, lds, rb->stream)
+                              : launch_step<false>(sa, sh.unroll, grid, lds, rb->stream);
+    if (e != hipSuccess) return RB_EHIP;
+    rb->cur ^= 1;
+    return RB_OK;
+}
+
 int rb_read_state(rb_buffer* rb, int32_t* fill_host, int64_t* last_n_host, uint32_t* flags_host)
 {
     if (!rb) return RB_EINVAL;
@@ -1079,6 +1388,10 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
     case RB_OPT_ROWS_PER_BLOCK:
         if (value < 0 || value > 16) return RB_EINVAL;
         rb->opt_rpb = (int)value;
+        return RB_OK;
+    case RB_OPT_FUSE:
+        if (value != 0 && value != 1) return RB_EINVAL;
+        rb->opt_fuse = (int)value;
         return RB_OK;
     default:
         return RB_EINVAL;

@@ -57,9 +57,10 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
 
 
 def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
-               first_step=0, progress=None, buf=None, orc=None, final_check=True):
+               first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False):
     """Runs `steps` update+sample steps of workload `w` on both sides.
 
+    single_call: drive the HIP side through rb_update_sample instead of the two calls.
     Every step: out_y equal, the n sampled rows byte-equal, rows >= n untouched.
     At the end (and every `check_state_every` steps): fill, flags, buf_y and all
     filled buf_x rows.  Returns (buf, orc) for further checks.
@@ -84,8 +85,11 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
         aug_y[w.b:].fill_(-7)
         if stream is not None:
             stream.wait_stream(torch.cuda.current_stream(dev))
-        buf.update(aug_x[:w.b], aug_y[:w.b], w.c, w.lib_seed, step)
-        buf.sample_augment(w.r, w.lib_seed, step, aug_x[w.b:], aug_y[w.b:])
+        if single_call:
+            buf.update_sample(aug_x[:w.b], aug_y[:w.b], w.c, w.r, w.lib_seed, step, aug_x[w.b:], aug_y[w.b:])
+        else:
+            buf.update(aug_x[:w.b], aug_y[:w.b], w.c, w.lib_seed, step)
+            buf.sample_augment(w.r, w.lib_seed, step, aug_x[w.b:], aug_y[w.b:])
         if stream is not None:
             torch.cuda.current_stream(dev).wait_stream(stream)
         # oracle on the host copies of the very same bytes

@@ -52,6 +52,33 @@ def test_c3_on_a_side_stream():
     run_parity(wl.variant(wl.C3, name="C3-side-stream", S=8), steps=30, stream=s)
 
 
+# ------------------------------ the single-call primitive (one fused launch) ---
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.C1, 100),                                                              # fills up: forwarding of appended and overwritten slots
+    (wl.C2, 300),
+    (wl.variant(wl.C3, name="C3-S4-single", S=4), 120),
+    (wl.variant(wl.C4, name="C4-S8-single", S=8, shape=(3, 32, 32)), 100),     # Zipf head: several overwrites of one class per step
+    (wl.variant(wl.C1, name="C1-one-class", K=1, S=7, c=16, r=16), 40),        # every representative competes with this step's writes
+    (wl.variant(wl.C1, name="C1-r-large", S=3, c=16, r=64, b=64), 40),         # r above what is stored for a while, then r = F
+    (wl.variant(wl.C2, name="C2-odd-b", b=77, c=33, r=21, S=2), 60),           # odd b: LDS table alignment
+    (wl.variant(wl.C5, name="C5-fallback", K=2000, S=4, shape=(64,), b=256, c=100, r=30), 20),   # not eligible: two launches
+])
+def test_single_call_primitive(w, steps):
+    run_parity(w, steps=steps, check_state_every=max(1, steps // 4), single_call=True)
+
+
+@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40)], ids=["C3", "C4"])
+def test_single_call_full_size(w, steps):
+    run_parity(w, steps=w.steps if FULL else steps, progress=10 if not FULL else 100, single_call=True)
+
+
+def test_single_call_equals_two_calls_without_fusion():
+    rb = _rb()
+    w = wl.variant(wl.C1, name="C1-nofuse", S=5)
+    run_parity(w, steps=40, options=((rb.RB_OPT_FUSE, 0),), single_call=True)
+
+
 # ------------------------------------------- stress variants (replace path) ---
 
 @pytest.mark.parametrize("w,steps", [
