@@ -10,7 +10,7 @@ import os
 import torch  # first: the library must bind to the HIP runtime PyTorch has loaded
 
 HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(HERE, "librb.so")
+LIB_PATH = os.environ.get("RB_LIBRARY") or os.path.join(HERE, "librb.so")   # RB_LIBRARY: another build of the same library
 
 RB_F32, RB_BF16 = 0, 1
 RB_OK, RB_EINVAL, RB_ENOMEM, RB_ESTATE, RB_EHIP = 0, -1, -2, -3, -4

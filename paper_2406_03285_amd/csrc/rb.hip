@@ -26,6 +26,7 @@ constexpr int TPB = 256;               // threads per workgroup: four 64-wide wa
 constexpr int WAVE = 64;
 constexpr int NWAVE = TPB / WAVE;
 constexpr int CH = 256;                // classes per chunk of the two-level fill index
+constexpr int TILE_UNIT = 64;          // granularity, in 16-byte vectors, at which a row is cut into tiles
 constexpr uint32_t PURPOSE_SELECT = 1; // counter word that separates the three kinds of draws
 constexpr uint32_t PURPOSE_EVICT = 2;
 constexpr uint32_t PURPOSE_SAMPLE = 3;
@@ -58,13 +59,13 @@ __device__ __forceinline__ uint64_t draw64(const Seed& sd, uint32_t purpose, uin
     uint32_t ka = sd.seed_lo, kb = sd.seed_hi;
 #pragma unroll
     for (int i = 0; i < 10; ++i) {
-        const uint32_t ma = 0xD2511F53u, mb = 0xCD9E8D57u;
-        uint32_t a_hi = __umulhi(ma, x0), a_lo = ma * x0;
-        uint32_t b_hi = __umulhi(mb, x2), b_lo = mb * x2;
-        x0 = b_hi ^ x1 ^ ka;
-        x2 = a_hi ^ x3 ^ kb;
-        x1 = b_lo;
-        x3 = a_lo;
+        // one 32x32->64 multiply per word pair (v_mad_u64_u32) instead of separate high and low halves
+        const uint64_t pa = (uint64_t)0xD2511F53u * x0;
+        const uint64_t pb = (uint64_t)0xCD9E8D57u * x2;
+        x0 = (uint32_t)(pb >> 32) ^ x1 ^ ka;
+        x2 = (uint32_t)(pa >> 32) ^ x3 ^ kb;
+        x1 = (uint32_t)pb;
+        x3 = (uint32_t)pa;
         ka += 0x9E3779B9u;
         kb += 0xBB67AE85u;
     }
@@ -77,18 +78,37 @@ __device__ __forceinline__ uint64_t below(const Seed& sd, uint32_t purpose, uint
 }
 
 // ---------------------------------------------------------------------------
+// Wavefront-level pieces of the small-count kernels (at most WAVE candidates or
+// representatives: one lane per item, all 64 lanes of the wavefront active).
+// ---------------------------------------------------------------------------
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (no LDS round
+// trips): Hillis-Steele steps of 1, 2, 4, 8 lanes inside each row of 16 lanes, then the last
+// lane of row 0 / row 2 is added to row 1 / row 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_scan_incl(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// Value of `v` in lane `src`, the same lane for the whole wavefront.
+__device__ __forceinline__ int lane_read(int v, int src)
+{
+    return __builtin_amdgcn_readlane(v, src);
+}
+
+// ---------------------------------------------------------------------------
 // Workgroup-wide exclusive prefix sum of one int per thread.  s_wave: NWAVE
 // ints of LDS.  Must be called by all threads of the workgroup.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
 {
     const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
-    int inc = v;
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        int up = __shfl_up(inc, d, WAVE);
-        if (lane >= d) inc += up;
-    }
+    const int inc = wave_scan_incl(v);
     if (lane == WAVE - 1) s_wave[w] = inc;
     __syncthreads();
     int before = 0, all = 0;
@@ -104,47 +124,56 @@ __device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
 }
 
 // ---------------------------------------------------------------------------
-// Wavefront-level pieces of the small-count kernels (at most WAVE candidates or
-// representatives: one lane per item, all 64 lanes of the wavefront active).
-// ---------------------------------------------------------------------------
-__device__ __forceinline__ int wave_scan_incl(int v)
-{
-    const int lane = threadIdx.x & (WAVE - 1);
-#pragma unroll
-    for (int d = 1; d < WAVE; d <<= 1) {
-        int up = __shfl_up(v, d, WAVE);
-        if (lane >= d) v += up;
-    }
-    return v;
-}
-
-// ---------------------------------------------------------------------------
 // Row mover: the workgroup's tile of one row, U vectors per thread in flight.
 // ---------------------------------------------------------------------------
 template <int U, bool NT>
 struct Tile {
     vec16 v[U];
 
+    // Requires lo < hi.  No lane is ever masked off: a lane whose index falls past the end of
+    // the tile moves the tile's last vector again (same source, same destination, same bytes as
+    // the lane that owns it), so the copy stays correct and branch-free.  That keeps the number
+    // of loads in flight known at compile time - a wait for an earlier load then does not have
+    // to drain these - and keeps the compiler from moving loads down into a guarded store.
     __device__ __forceinline__ void load(const vec16* __restrict__ src, int64_t lo, int64_t hi)
     {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
-            if (i < hi) v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+            i = i < hi ? i : hi - 1;
+            v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
         }
     }
+    // All loads are waited for first and every store is waited for before the next one is
+    // issued.  Measured on MI355X with a bare mover of the same shape (64 rows of 301 056 bytes,
+    // U = 4): 7.6 us against 8.6 us when each store is issued as soon as its load has arrived
+    // and 8.9 us with the guarded form; the memory system does better with few writes in flight.
     __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
     {
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
-            if (i < hi) {
-                if (NT) __builtin_nontemporal_store(v[u], dst + i);
-                else dst[i] = v[u];
-            }
+            i = i < hi ? i : hi - 1;
+            if (NT) __builtin_nontemporal_store(v[u], dst + i);
+            else dst[i] = v[u];
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 };
+
+// Vector range [lo, hi) of tile `tile` of a row of row_vec vectors.  The row is cut into units of
+// TILE_UNIT vectors (1 KiB: what one wavefront moves per instruction, so that a wavefront's access
+// does not straddle two such blocks of a 1 KiB-aligned row) and the units are dealt evenly: the
+// first `rem` tiles get `units + 1`, the others `units` (>= 1).  Tiles are never empty and never
+// longer than TPB * U vectors.
+__device__ __forceinline__ void tile_bounds(int tile, int units, int rem, int64_t row_vec, int64_t& lo, int64_t& hi)
+{
+    const int64_t ulo = (int64_t)tile * units + (tile < rem ? tile : rem);
+    const int64_t uhi = ulo + units + (tile < rem ? 1 : 0);
+    lo = ulo * TILE_UNIT;
+    hi = uhi * TILE_UNIT < row_vec ? uhi * TILE_UNIT : row_vec;
+}
 
 // ---------------------------------------------------------------------------
 // Reset: fill counts, partial sums and state words to zero, labels to -1.
@@ -184,7 +213,8 @@ struct UpdateArgs {
     int64_t S;
     int64_t row_vec;      // 16-byte vectors per row
     int32_t tpr;          // tiles per row
-    int32_t tile_vec;     // vectors per tile (multiple of TPB, at most TPB * U)
+    int32_t tile_vec;     // a row is split evenly into tpr tiles in units of TILE_UNIT vectors: the first
+    int32_t tile_rem;     // tile_rem tiles hold tile_vec + 1 units, the others tile_vec; see tile_bounds
     int32_t rpb;          // rows per mover workgroup (1 unless tpr == 1)
 };
 
@@ -270,8 +300,8 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
     // ---- movers ---------------------------------------------------------------
     const int mover = blockIdx.x - a.nchunks;
     const int group = mover / a.tpr, tile = mover % a.tpr;
-    const int64_t v_lo = (int64_t)tile * a.tile_vec;
-    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
     for (int rr = 0; rr < a.rpb; ++rr) {
         const int i = group * a.rpb + rr;      // candidate, in Floyd emission order
@@ -332,6 +362,29 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
     }
 }
 
+constexpr int YPRE = 4;    // label loads per thread issued before anything else (covers b <= 1024)
+
+// Labels of the whole mini-batch into LDS (LAB_INVALID when outside [0, K)).  The
+// first YPRE per thread were requested earlier into yv[]; called by all threads.
+__device__ __forceinline__ void park_labels(const int64_t (&yv)[YPRE], const int64_t* __restrict__ batch_y,
+                                            int b, int K, int32_t* s_y)
+{
+    const int tid = threadIdx.x;
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        int64_t y = yv[u];
+        // keeps the compiler from evaluating the range test (and so waiting for the load) any
+        // earlier than here; the loads are meant to stay in flight across the code before
+        asm volatile("" : "+v"(y));
+        if (q < b) s_y[q] = (y >= 0 && y < K) ? (int32_t)y : LAB_INVALID;
+    }
+    for (int q = tid + YPRE * TPB; q < b; q += TPB) {
+        const int64_t y = batch_y[q];
+        s_y[q] = (y >= 0 && y < K) ? (int32_t)y : LAB_INVALID;
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Pieces of the plan shared by the small-count kernels.  Called by wavefront 0
 // only, with all of its 64 lanes active.
@@ -351,17 +404,17 @@ __device__ __forceinline__ int wave_select(const Seed& sd, int b, int c, uint32_
     if (active) s_first[t] = 0xFFFFFFFFu;
     if (active) atomicMin(&s_first[t], (uint32_t)lane);
     const bool dup = active && s_first[t] != (uint32_t)lane;
+    const int packed = (int)(t | (dup ? 0x80000000u : 0u));      // t < 4096: bit 31 is free for the flag
     int cur = lane;
     bool taken = false, done = !active;
     while (__ballot(!done) != 0) {
-        const int tc = __shfl((int)t, cur, WAVE);
-        const int dc = __shfl((int)dup, cur, WAVE);
+        const int pc = __shfl(packed, cur, WAVE);
         if (!done) {
-            if (dc) {
+            if (pc < 0) {
                 taken = true;
                 done = true;
             } else {
-                const int q = tc - base;
+                const int q = pc - base;
                 if (q < 0 || q >= cur) done = true;
                 else cur = q;
             }
@@ -376,7 +429,7 @@ __device__ __forceinline__ int wave_select(const Seed& sd, int b, int c, uint32_
 __device__ __forceinline__ int64_t wave_place(const Seed& sd, bool active, int x, int32_t k, int i, int p,
                                               const int32_t* __restrict__ fill_old, int64_t S)
 {
-    const int32_t ki = __shfl(k, i, WAVE);
+    const int32_t ki = lane_read(k, i);
     if (ki < 0) return -1;
     // candidates of class ki; in mini-batch order the one with `rank` class-mates
     // before it is insertion number fill0 + rank of the class
@@ -388,7 +441,7 @@ __device__ __forceinline__ int64_t wave_place(const Seed& sd, bool active, int x
     // Insertions beyond the capacity overwrite a uniformly drawn slot.  This
     // candidate is not stored if a later class-mate overwrites its slot.
     const int draw = same ? (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S) : -1;
-    const int own = fill0 + rank < S ? (int)(fill0 + rank) : __shfl(draw, i, WAVE);
+    const int own = fill0 + rank < S ? (int)(fill0 + rank) : lane_read(draw, i);
     uint64_t rivals = __ballot(same && x > p && draw == own);
     while (rivals != 0) {
         const int m = __builtin_ctzll(rivals);
@@ -409,8 +462,6 @@ __device__ __forceinline__ int64_t wave_place(const Seed& sd, bool active, int x
 // LDS (dynamic): s_first[b] u32 (lowest lane that drew a value), s_y[b] i32
 // (label of every mini-batch position, LAB_INVALID when outside [0, K)).
 // ---------------------------------------------------------------------------
-constexpr int YPRE = 4;    // label loads per thread issued before anything else (covers b <= 1024)
-
 template <int U, bool NT>
 __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a)
 {
@@ -439,18 +490,9 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
     int x = 0;                       // its mini-batch position
     if (w0) x = wave_select(a.sd, b, c, s_first, active);
 
-#pragma unroll
-    for (int u = 0; u < YPRE; ++u) {
-        const int q = tid + u * TPB;
-        if (q < b) s_y[q] = (yv[u] >= 0 && yv[u] < a.K) ? (int32_t)yv[u] : LAB_INVALID;
-    }
-    for (int q = tid + YPRE * TPB; q < b; q += TPB) {
-        const int64_t y = a.batch_y[q];
-        s_y[q] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
-    }
-
     if ((int)blockIdx.x < a.nchunks) {
         // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
+        park_labels(yv, a.batch_y, b, a.K, s_y);
         const int k_lo = blockIdx.x * CH;
         s_hist[tid] = 0;
         __syncthreads();
@@ -477,26 +519,52 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
     // ---- movers ---------------------------------------------------------------
     const int mover = blockIdx.x - a.nchunks;
     const int group = mover / a.tpr, tile = mover % a.tpr;
-    const int64_t v_lo = (int64_t)tile * a.tile_vec;
-    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
+    // The first row is handled outside the loop over further rows: the label loads are still in
+    // flight here and a loop header would make the compiler wait for them before the barrier.
     int32_t k = LAB_UNSELECTED;      // wavefront 0: class of the lane's candidate
-    for (int rr = 0; rr < a.rpb; ++rr) {
-        const int i = group * a.rpb + rr;      // candidate, in Floyd emission order
+    {
+        const int i = group * a.rpb;           // candidate, in Floyd emission order
+        if (i >= c) return;
+        if (w0) {
+            const int pi = lane_read(x, i);
+            if (lane == 0) s_p[0] = pi;
+        }
+        __syncthreads();
+        const int p = s_p[0];
+        // The row is requested as soon as its position is known: before the labels have
+        // arrived, and long before wavefront 0 has worked out where it goes.
+        Tile<U, NT> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+        park_labels(yv, a.batch_y, b, a.K, s_y);
+        __syncthreads();
+        if (w0) {
+            k = active ? s_y[x] : LAB_UNSELECTED;
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
+            if (lane == 0) s_dst[0] = dst;
+        }
+        __syncthreads();
+        const int64_t dst_row = s_dst[0];
+        if (dst_row >= 0) {
+            t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+        }
+    }
+    for (int rr = 1; rr < a.rpb; ++rr) {
+        const int i = group * a.rpb + rr;
         if (i >= c) break;
         const int par = rr & 1;
         if (w0) {
-            const int pi = __shfl(x, i, WAVE);
+            const int pi = lane_read(x, i);
             if (lane == 0) s_p[par] = pi;
         }
         __syncthreads();
         const int p = s_p[par];
-        // the row is read while wavefront 0 works out where it goes
         Tile<U, NT> t;
         t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
-
         if (w0) {
-            if (rr == 0) k = active ? s_y[x] : LAB_UNSELECTED;
             const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
             if (lane == 0) s_dst[par] = dst;
         }
@@ -535,6 +603,7 @@ struct SampleArgs {
     int64_t row_vec;
     int32_t tpr;
     int32_t tile_vec;
+    int32_t tile_rem;
     int32_t rpb;
     int32_t direct;       // 1: K <= MAXPER * TPB, all fill counts are read at once
 };
@@ -590,8 +659,8 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
     __syncthreads();
 
     const int group = blockIdx.x / a.tpr, tile = blockIdx.x % a.tpr;
-    const int64_t v_lo = (int64_t)tile * a.tile_vec;
-    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
     for (int rr = 0; rr < a.rpb; ++rr) {
         const int j = group * a.rpb + rr;      // output row
@@ -699,7 +768,7 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
             for (int m = 0; m < 16; ++m) cs += fv[m];
         }
         incl = wave_scan_incl(cs);
-        const int F = __shfl(incl, WAVE - 1, WAVE);
+        const int F = lane_read(incl, WAVE - 1);
         n = a.r < F ? a.r : F;
         base = F - n;
         if (lane < n) t = (uint32_t)__umul64hi(bits, (uint64_t)base + lane + 1);
@@ -710,8 +779,8 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
     }
 
     const int group = blockIdx.x / a.tpr, tile = blockIdx.x % a.tpr;
-    const int64_t v_lo = (int64_t)tile * a.tile_vec;
-    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
     for (int rr = 0; rr < a.rpb; ++rr) {
         const int j = group * a.rpb + rr;      // output row
@@ -724,13 +793,13 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
             int cur = j;
             bool taken = false;
             for (;;) {
-                const uint32_t tc = (uint32_t)__shfl((int)t, cur, WAVE);
+                const uint32_t tc = (uint32_t)lane_read((int)t, cur);
                 if (__ballot(lane < cur && t == tc) != 0) { taken = true; break; }
                 const int64_t q = (int64_t)tc - base;
                 if (q < 0 || q >= cur) break;
                 cur = (int)q;
             }
-            const int gj = taken ? base + j : __shfl((int)t, j, WAVE);   // class-major index of the sample
+            const int gj = taken ? base + j : lane_read((int)t, j);   // class-major index of the sample
             if (direct) {
                 int acc = incl - cs;
                 if (gj >= acc && gj < incl) {
@@ -745,7 +814,7 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
             } else {
                 // chunk holding gj: the number of chunks that end at or before it
                 const int ch = __popcll(__ballot(lane < a.nchunks && incl <= gj));
-                const int gl = gj - (__shfl(incl, ch, WAVE) - __shfl(cs, ch, WAVE));
+                const int gl = gj - (lane_read(incl, ch) - lane_read(cs, ch));
                 const int4 f = *reinterpret_cast<const int4*>(a.fill + (int64_t)ch * CH + 4 * lane);
                 const int local = f.x + f.y + f.z + f.w;
                 const int lincl = wave_scan_incl(local);
@@ -838,18 +907,9 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
         if (gather && lane < sa.r) bits = draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)lane);
     }
 
-#pragma unroll
-    for (int u = 0; u < YPRE; ++u) {
-        const int q = tid + u * TPB;
-        if (q < b) s_y[q] = (yv[u] >= 0 && yv[u] < a.K) ? (int32_t)yv[u] : LAB_INVALID;
-    }
-    for (int q = tid + YPRE * TPB; q < b; q += TPB) {
-        const int64_t y = a.batch_y[q];
-        s_y[q] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
-    }
-
     if ((int)blockIdx.x < a.nchunks) {
         // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
+        park_labels(yv, a.batch_y, b, a.K, s_y);
         const int k_lo = blockIdx.x * CH;
         s_hist[tid] = 0;
         __syncthreads();
@@ -877,16 +937,19 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
         // ---- candidate movers (rows of the mini-batch into their slots) ----------
         const int mover = blockIdx.x - a.nchunks;
         const int i = mover / a.tpr, tile = mover % a.tpr;     // candidate in Floyd emission order, tile of its row
-        const int64_t v_lo = (int64_t)tile * a.tile_vec;
-        const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+        int64_t v_lo, v_hi;
+        tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
         if (w0) {
-            const int pi = __shfl(x, i, WAVE);
+            const int pi = lane_read(x, i);
             if (lane == 0) s_p = pi;
         }
         __syncthreads();
         const int p = s_p;
+        // requested as soon as the position is known, before the labels have arrived
         Tile<U, NT> t;
         t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+        park_labels(yv, a.batch_y, b, a.K, s_y);
+        __syncthreads();
         if (w0) {
             const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
             const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
@@ -904,9 +967,10 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
     // ---- representative movers (stored samples into the augmented mini-batch) ---
     const int mover = blockIdx.x - sa.first_gather;
     const int j = mover / a.tpr, tile = mover % a.tpr;         // output row, tile of it
-    const int64_t v_lo = (int64_t)tile * a.tile_vec;
-    const int64_t v_hi = (v_lo + a.tile_vec < a.row_vec) ? v_lo + a.tile_vec : a.row_vec;
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
+    park_labels(yv, a.batch_y, b, a.K, s_y);
     *reinterpret_cast<int4*>(s_old + 4 * tid) = fo;
     *reinterpret_cast<int4*>(s_cnt + 4 * tid) = make_int4(0, 0, 0, 0);
     __syncthreads();
@@ -923,7 +987,7 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
             cs += fv[m];
         }
         const int incl = wave_scan_incl(cs);
-        const int F = __shfl(incl, WAVE - 1, WAVE);
+        const int F = lane_read(incl, WAVE - 1);
         const int n = sa.r < F ? sa.r : F;
         const int base = F - n;
         uint32_t t = 0xFFFFFFFFu;
@@ -939,13 +1003,13 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
             int cur = j;
             bool taken = false;
             for (;;) {
-                const uint32_t tc = (uint32_t)__shfl((int)t, cur, WAVE);
+                const uint32_t tc = (uint32_t)lane_read((int)t, cur);
                 if (__ballot(lane < cur && t == tc) != 0) { taken = true; break; }
                 const int64_t q = (int64_t)tc - base;
                 if (q < 0 || q >= cur) break;
                 cur = (int)q;
             }
-            const int gj = taken ? base + j : __shfl((int)t, j, WAVE);   // class-major index of the sample
+            const int gj = taken ? base + j : lane_read((int)t, j);   // class-major index of the sample
             // locate it: the lane whose 16 classes hold it walks them
             int acc = incl - cs;
             const bool mine = gj >= acc && gj < incl;
@@ -957,8 +1021,8 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
                 }
             }
             const int owner = __builtin_ctzll(__ballot(mine) | (1ull << 63));
-            const int pk = __shfl(16 * lane + u, owner, WAVE);
-            const int ps = __shfl(gj - acc, owner, WAVE);
+            const int pk = lane_read(16 * lane + u, owner);
+            const int ps = lane_read(gj - acc, owner);
 
             // Is slot ps of class pk written in this step, and by which candidate?
             const bool same = active && k == pk;
@@ -1055,7 +1119,7 @@ struct rb_buffer {
 namespace {
 
 struct Shape {
-    int unroll, tpr, tile_vec, rpb;
+    int unroll, tpr, tile_vec, tile_rem, rpb;
     int64_t groups;
 };
 
@@ -1066,16 +1130,18 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows)
     const int64_t row_vec = rb->row_vec;
     int u = rb->opt_unroll;
     if (u == 0) {
-        // largest unroll that still leaves about four workgroups per compute unit
+        // largest unroll that still leaves about four workgroups per compute unit; never
+        // below two vectors in flight per thread (one was slower at every size measured)
         u = 8;
-        while (u > 1 && rows * ((row_vec + (int64_t)TPB * u - 1) / ((int64_t)TPB * u)) < 1024) u >>= 1;
+        while (u > 2 && rows * ((row_vec + (int64_t)TPB * u - 1) / ((int64_t)TPB * u)) < 1024) u >>= 1;
     }
     s.unroll = u;
     const int64_t cap = (int64_t)TPB * u;
     s.tpr = (int)((row_vec + cap - 1) / cap);
-    // even tiles, rounded up to whole workgroup widths
-    int64_t per_tile = (row_vec + s.tpr - 1) / s.tpr;
-    s.tile_vec = (int)round_up((size_t)per_tile, TPB);
+    // even split in units of TILE_UNIT vectors: every tile holds nunits / tpr units, the first nunits % tpr one more
+    const int64_t nunits = (row_vec + TILE_UNIT - 1) / TILE_UNIT;
+    s.tile_vec = (int)(nunits / s.tpr);
+    s.tile_rem = (int)(nunits % s.tpr);
     s.rpb = 1;
     if (s.tpr == 1) {
         int r = rb->opt_rpb;
@@ -1273,7 +1339,7 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
     a.S = rb->S;
     a.row_vec = rb->row_vec;
-    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = sh.rpb;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
     const dim3 grid((unsigned)(rb->nchunks + sh.groups * sh.tpr));
     const size_t lds = (size_t)b * 8 + (size_t)c * 4;
     hipError_t e = rb->opt_nt ? launch_update<true>(a, sh.unroll, grid, lds, rb->stream)
@@ -1303,7 +1369,7 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
     a.S = rb->S;
     a.row_vec = rb->row_vec;
-    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = sh.rpb;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
     a.direct = rb->K <= (int64_t)MAXPER * TPB ? 1 : 0;
     const dim3 grid((unsigned)(sh.groups * sh.tpr));
     const size_t lds = ((size_t)rb->nchunks + (size_t)r) * 4;
@@ -1344,7 +1410,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.K = (int32_t)rb->K; a.nchunks = rb->nchunks;
     a.S = rb->S;
     a.row_vec = rb->row_vec;
-    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.rpb = 1;
+    a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = 1;
     sa.out_x = static_cast<vec16*>(out_x);
     sa.out_y = out_y;
     sa.r = (int32_t)r;
