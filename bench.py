@@ -1,10 +1,13 @@
 #!/usr/bin/env python3
 """Benchmark of the rehearsal-buffer hot path on one MI355X.
 
-A step is one rb_update + one rb_sample_augment on one mini-batch of synthetic
-input that is already resident in HBM.  Prints ONE JSON line: augmented
-samples/s of the whole job, the HBM roofline of the dominant kernel, and the
-CPU oracle timed on the host beside it.
+A step is one update of the buffer with a mini-batch plus one sampling of r
+representatives into the augmented mini-batch, on synthetic input that is
+already resident in HBM.  The headline drives it through the single-call
+primitive rb_update_sample (one kernel launch per step where eligible); the
+same step issued as rb_update + rb_sample_augment (two launches) is reported
+beside it.  Prints ONE JSON line: augmented samples/s of the whole job, the HBM
+roofline of the dominant kernel, and the CPU oracle timed on the host.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--prefill]
 """
@@ -20,10 +23,10 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this much memory (>> 256 MB of last-level cache)
-# HBM bytes per launch of the dominant kernel (the gather of rb_sample_augment) as counted by two
+# HBM bytes per launch of the dominant kernel as counted by two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
 # known size; the text summaries with the exact commands are kept under profiles/.
-MEASURED_TRAFFIC = {"C4-1000x300-bf16-3x224x224-zipf": 38637524}
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77297509}
 
 
 def log(*a):
@@ -180,7 +183,7 @@ def overlap_leg(rig, steps, target_ms, kind="fma"):
     if kind == "hbm":
         amount = min(1 << 30, max(1 << 20, amount // 4096 * 4096))
     t_alone = standin_ms(amount, steps)
-    t_rb = rig.timed(steps)
+    t_rb = rig.timed(steps, single_call=True)
     done = [torch.cuda.Event() for _ in range(4)]
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
@@ -188,7 +191,7 @@ def overlap_leg(rig, steps, target_ms, kind="fma"):
     for t in range(steps):
         if t > 0:
             main.wait_event(done[(t - 1) % 4])        # (1) representatives sampled during the previous iteration
-        rig.enqueue(1)                                 # (2) update with this mini-batch, then sample the next representatives
+        rig.enqueue(1, single_call=True)               # (2) update with this mini-batch, then sample the next representatives
         done[t % 4].record(rig.stream)
         standin(amount)                                # (3), (4) forward and backward pass stand-in
     main.wait_event(done[(steps - 1) % 4])
@@ -231,19 +234,25 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     rig = Rig(w, torch, rb, wl)
     if prefill:
         rig.prefill()
-    rig.enqueue(warmup)
+    rig.enqueue(warmup, single_call=True)
     torch.cuda.synchronize()
-    ms = rig.timed(steps)
+    # headline: the single-call primitive, K steps enqueued back to back on the side stream
+    ms = rig.timed(steps, single_call=True)
+    n_side = min(steps, 1000)
+    ms_two = rig.timed(n_side)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).
-    ms_update = rig.timed(min(steps, 1000), do_sample=False)
-    ms_sample = rig.timed(min(steps, 1000), do_update=False)
+    ms_update = rig.timed(n_side, do_sample=False)
+    ms_sample = rig.timed(n_side, do_update=False)
     fill, last_n, flags = rig.buf.read_state()
+    fused = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
     res = {
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "launches_per_step": 1 if fused else 2,
+        "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }
@@ -261,10 +270,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
-                    help="short fixed sequence for `rocprofv3 --pmc`: 100 warm-up steps, 20 steps, then 3 plain copies "
+                    help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
-    ap.add_argument("--unroll", type=int, default=0)
-    ap.add_argument("--nontemporal", type=int, default=1)
     a = ap.parse_args()
     if a.gpus != 1:
         sys.exit("bench.py: this build covers one GPU's local buffer only (no collectives); run with --gpus 1")
@@ -275,16 +282,13 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU path")
 
-    def tune(rig):
-        rig.buf.set_option(rb.RB_OPT_UNROLL, a.unroll)
-        rig.buf.set_option(rb.RB_OPT_NONTEMPORAL, a.nontemporal)
-
     w = wl.by_name(a.workload)
     if a.pmc_run:
         rig = Rig(w, torch, rb, wl)
         if a.prefill:
             rig.prefill()
         rig.enqueue(120)
+        rig.enqueue(120, single_call=True)
         torch.cuda.synchronize()
         nbytes = 256 << 20
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
@@ -317,10 +321,15 @@ def main():
         others[ow.name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in ores.items()}
         log(f"[bench] {json.dumps(others[ow.name])}")
 
-    # roofline of the dominant kernel: the gather of rb_sample_augment moves r rows, read once and written once
-    k_ms = res["sample_kernel_ms"]
+    # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
+    # (rb_step_small_kernel: every inserted row and every representative row read once and written
+    # once) and its duration is ms_per_step; otherwise it is the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
-    achieved = 2 * n_rows * w.row_bytes / (k_ms * 1e-3) / 1e9
+    if res["launches_per_step"] == 1:
+        kernel, k_ms, k_bytes = "rb_step_small_kernel", res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
+    else:
+        kernel, k_ms, k_bytes = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes
+    achieved = k_bytes / (k_ms * 1e-3) / 1e9
     line = {
         "metric": "augmented samples/sec and achieved HBM GB/s (% of peak) per update+sample step",
         "value": round(res["aug_samples_per_s"], 1), "unit": "augmented samples/s",
@@ -328,13 +337,14 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
+                   "api": "rb_update_sample (single call per step)",
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
         "reps_per_s": round(res["reps_per_s"], 1),
-        "roofline": {"bound": "hbm", "kernel": "rb_sample_kernel", "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
+        "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get(w.name) if not a.prefill else None,
-                     "bytes_per_launch": 2 * n_rows * w.row_bytes, "kernel_ms": round(k_ms, 5),
+                     "traffic": MEASURED_TRAFFIC.get((w.name, kernel)) if not a.prefill else None,
+                     "bytes_per_launch": k_bytes, "kernel_ms": round(k_ms, 5),
                      "copy_ceiling_gbs": round(ceiling, 1)},
         "detail": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()},
         "prefilled": None if pre is None else {k: (round(v, 5) if isinstance(v, float) else v) for k, v in pre.items()},

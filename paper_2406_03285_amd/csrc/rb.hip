@@ -423,20 +423,18 @@ __device__ __forceinline__ int wave_select(const Seed& sd, int b, int c, uint32_
     return active ? (taken ? base + lane : (int)t) : 0;
 }
 
-// Where candidate i (mini-batch position p) is stored: row index k*S + slot, or
-// -1 if it is not stored (label outside [0, K), or a later class-mate overwrites
-// its slot).  Lane l holds candidate l: position x, class k.
+// Where candidate i (mini-batch position p, class ki, fill0 samples of that class stored before
+// the step) is stored: row index ki*S + slot, or -1 if it is not stored (label outside [0, K),
+// or a later class-mate overwrites its slot).  Lane l holds candidate l: position x, class k.
 __device__ __forceinline__ int64_t wave_place(const Seed& sd, bool active, int x, int32_t k, int i, int p,
-                                              const int32_t* __restrict__ fill_old, int64_t S)
+                                              int32_t ki, int64_t fill0, int64_t S)
 {
-    const int32_t ki = lane_read(k, i);
     if (ki < 0) return -1;
     // candidates of class ki; in mini-batch order the one with `rank` class-mates
     // before it is insertion number fill0 + rank of the class
     const bool same = active && k == ki;
     const int total = __popcll(__ballot(same));
     const int rank = __popcll(__ballot(same && x < p));
-    const int64_t fill0 = fill_old[ki];
     if (fill0 + total <= S) return (int64_t)ki * S + fill0 + rank;     // all append: distinct slots
     // Insertions beyond the capacity overwrite a uniformly drawn slot.  This
     // candidate is not stored if a later class-mate overwrites its slot.
@@ -542,7 +540,8 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
         __syncthreads();
         if (w0) {
             k = active ? s_y[x] : LAB_UNSELECTED;
-            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
+            const int32_t ki = lane_read(k, i);
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, ki, ki >= 0 ? a.fill_old[ki] : 0, a.S);
             if (lane == 0) s_dst[0] = dst;
         }
         __syncthreads();
@@ -565,7 +564,8 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
         Tile<U, NT> t;
         t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
         if (w0) {
-            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
+            const int32_t ki = lane_read(k, i);
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, ki, ki >= 0 ? a.fill_old[ki] : 0, a.S);
             if (lane == 0) s_dst[par] = dst;
         }
         __syncthreads();
@@ -864,7 +864,7 @@ struct StepArgs {
     vec16* out_x;
     int64_t* out_y;
     int32_t r;
-    int32_t first_gather;    // index of the first representative mover
+    int32_t first_gather;   // index of the first representative mover (the candidate movers come before)
 };
 
 template <int U, bool NT>
@@ -883,6 +883,7 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
     __shared__ int64_t s_dst;       // candidate mover: slot row it is stored to, -1: not stored
     __shared__ int s_n;             // representative mover: n = min(r, F)
     __shared__ int s_pick[3];       // representative mover: class, slot, forwarding position (-1: read the slot)
+    __shared__ uint64_t s_bits[WAVE];   // representative mover: random bits of sampling draw i, made by wavefront 1
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1);
     const bool w0 = tid < WAVE;
@@ -899,12 +900,13 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
     int4 fo = make_int4(0, 0, 0, 0);
     if (gather && 4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
 
+    // wavefront 0 selects the candidates while wavefront 1 makes the random bits of the sampling draws
     bool active = false;
     int x = 0;
-    uint64_t bits = 0;       // representative movers: random bits of the lane's sampling draw
     if (w0) {
         x = wave_select(a.sd, b, c, s_first, active);
-        if (gather && lane < sa.r) bits = draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)lane);
+    } else if (gather && tid < 2 * WAVE) {
+        if (lane < sa.r) s_bits[lane] = draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)lane);
     }
 
     if ((int)blockIdx.x < a.nchunks) {
@@ -952,7 +954,8 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
         __syncthreads();
         if (w0) {
             const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
-            const int64_t dst = wave_place(a.sd, active, x, k, i, p, a.fill_old, a.S);
+            const int32_t ki = lane_read(k, i);
+            const int64_t dst = wave_place(a.sd, active, x, k, i, p, ki, ki >= 0 ? a.fill_old[ki] : 0, a.S);
             if (lane == 0) s_dst = dst;
         }
         __syncthreads();
@@ -991,7 +994,7 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
         const int n = sa.r < F ? sa.r : F;
         const int base = F - n;
         uint32_t t = 0xFFFFFFFFu;
-        if (lane < n) t = (uint32_t)__umul64hi(bits, (uint64_t)base + lane + 1);
+        if (lane < n) t = (uint32_t)__umul64hi(s_bits[lane], (uint64_t)base + lane + 1);
         if (lane == 0) {
             s_n = n;
             s_pick[0] = 0; s_pick[1] = 0; s_pick[2] = -1;
