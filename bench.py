@@ -42,7 +42,7 @@ class Rig:
         self.stream = torch.cuda.Stream(self.dev)
         self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream)
         aug_bytes = (w.b + w.r) * w.row_bytes
-        self.P = pool_slots or max(8, -(-POOL_BYTES // aug_bytes))
+        self.P = pool_slots or min(1024, max(8, -(-POOL_BYTES // aug_bytes)))
         self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
         self.aug_y = torch.empty((self.P, w.b + w.r), dtype=torch.int64, device=self.dev)
         # distinct sample bytes for a few slots, replicated over the pool (generation is not what is measured);
@@ -266,7 +266,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--prefill", action="store_true", help="fill every slot before timing (all inserts replace)")
-    ap.add_argument("--others", default="C3,C5", help="comma list of further workloads reported inside the line ('' = none)")
+    ap.add_argument("--others", default="C3,C5,C2,C1", help="comma list of further workloads reported inside the line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",

@@ -32,7 +32,6 @@ constexpr uint32_t PURPOSE_EVICT = 2;
 constexpr uint32_t PURPOSE_SAMPLE = 3;
 constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a candidate
 constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
-constexpr int MAXPER = RB_MAX_BATCH / TPB;   // most mini-batch positions (or classes, direct mode) one thread owns
 
 typedef uint32_t vec16 __attribute__((ext_vector_type(4)));   // one 16-byte transfer
 
@@ -124,9 +123,9 @@ __device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
 }
 
 // ---------------------------------------------------------------------------
-// Row mover: the workgroup's tile of one row, U vectors per thread in flight.
+// Row mover: one tile of one row, U vectors per thread in flight.
 // ---------------------------------------------------------------------------
-template <int U, bool NT>
+template <int U, bool NT, int W = TPB, bool PACED = true>   // W: threads that share the tile (a workgroup or one wavefront)
 struct Tile {
     vec16 v[U];
 
@@ -139,7 +138,7 @@ struct Tile {
     {
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
+            int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
             v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
         }
@@ -150,14 +149,14 @@ struct Tile {
     // and 8.9 us with the guarded form; the memory system does better with few writes in flight.
     __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
     {
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
 #pragma unroll
         for (int u = 0; u < U; ++u) {
-            int64_t i = lo + (int64_t)u * TPB + threadIdx.x;
+            int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
             if (NT) __builtin_nontemporal_store(v[u], dst + i);
             else dst[i] = v[u];
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 };
@@ -166,7 +165,7 @@ struct Tile {
 // TILE_UNIT vectors (1 KiB: what one wavefront moves per instruction, so that a wavefront's access
 // does not straddle two such blocks of a 1 KiB-aligned row) and the units are dealt evenly: the
 // first `rem` tiles get `units + 1`, the others `units` (>= 1).  Tiles are never empty and never
-// longer than TPB * U vectors.
+// longer than W * U vectors for the tile width W the host planned for.
 __device__ __forceinline__ void tile_bounds(int tile, int units, int rem, int64_t row_vec, int64_t& lo, int64_t& hi)
 {
     const int64_t ulo = (int64_t)tile * units + (tile < rem ? tile : rem);
@@ -188,15 +187,19 @@ __global__ void __launch_bounds__(TPB) rb_reset_kernel(uint32_t* __restrict__ ws
 }
 
 // ---------------------------------------------------------------------------
-// rb_update: Algorithm 1.
+// rb_update: Algorithm 1, any c (used for c > WAVE).
 //
-// LDS (dynamic): s_a[b] u32 (first index per drawn value, later: slot per
-// position), s_lab[b] i32 (label per candidate position), s_t[c] u16 (Floyd
-// draws), s_x[c] u16 (candidate positions in Floyd emission order).
+// The whole workgroup first computes, once, what every candidate is (its
+// mini-batch position and class) into LDS; then each of its four wavefronts
+// takes one work item (candidate row, tile of WAVE * U vectors) and works out
+// alone, with ballots over the candidate list, where that candidate goes.
+//
+// LDS (dynamic): s_first[b] u32 (lowest candidate index that drew a value),
+// s_k[c] i32 (class per candidate, LAB_INVALID outside [0, K)), s_t[c] u16
+// (Floyd draws), s_x[c] u16 (candidate positions in Floyd emission order).
 //
 // Grid: `nchunks` bookkeeping workgroups (new fill counts and chunk sums for CH
-// classes each), then ceil(c / rpb) * tpr mover workgroups; a mover owns tile
-// `tile` of the rows of candidates [group*rpb, group*rpb + rpb).
+// classes each), then ceil(c * tpr / NWAVE) mover workgroups.
 // ---------------------------------------------------------------------------
 struct UpdateArgs {
     const vec16* batch_x;
@@ -215,37 +218,35 @@ struct UpdateArgs {
     int32_t tpr;          // tiles per row
     int32_t tile_vec;     // a row is split evenly into tpr tiles in units of TILE_UNIT vectors: the first
     int32_t tile_rem;     // tile_rem tiles hold tile_vec + 1 units, the others tile_vec; see tile_bounds
-    int32_t rpb;          // rows per mover workgroup (1 unless tpr == 1)
+    int32_t rpb;          // small kernels: rows per mover workgroup (1 unless tpr == 1)
 };
 
 template <int U, bool NT>
 __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 {
     extern __shared__ uint32_t lds[];
-    uint32_t* s_a = lds;                                       // [b]
-    int32_t* s_lab = reinterpret_cast<int32_t*>(lds + a.b);    // [b]
-    uint16_t* s_t = reinterpret_cast<uint16_t*>(lds + 2 * a.b); // [c]
-    uint16_t* s_x = s_t + a.c;                                 // [c]
+    uint32_t* s_first = lds;                                        // [b]
+    int32_t* s_k = reinterpret_cast<int32_t*>(lds + a.b);           // [c]
+    uint16_t* s_t = reinterpret_cast<uint16_t*>(lds + a.b + a.c);   // [c]
+    uint16_t* s_x = s_t + a.c;                                      // [c]
     __shared__ int s_wave[NWAVE];
     __shared__ int s_hist[CH];
+    __shared__ uint16_t s_pend[NWAVE][2 * WAVE];    // per wavefront: later class-mates waiting for their evict draw
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int b = a.b, c = a.c;
 
     // ---- candidate selection: Floyd's c-subset of [0, b), all draws at once --
     // Draw i is t_i in [0, b-c+i]; it is "taken" iff an earlier draw had the same
     // value, or it equals b-c+q for an earlier q whose own draw was taken; a
     // taken draw is replaced by b-c+i.
-    for (int q = tid; q < b; q += TPB) {
-        s_a[q] = 0xFFFFFFFFu;
-        s_lab[q] = LAB_UNSELECTED;
-    }
+    for (int q = tid; q < b; q += TPB) s_first[q] = 0xFFFFFFFFu;
     __syncthreads();
     const int base = b - c;
     for (int i = tid; i < c; i += TPB) {
         uint32_t t = (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)i, (uint64_t)(base + i + 1));
         s_t[i] = (uint16_t)t;
-        atomicMin(&s_a[t], (uint32_t)i);
+        atomicMin(&s_first[t], (uint32_t)i);
     }
     __syncthreads();
     for (int i = tid; i < c; i += TPB) {
@@ -253,20 +254,17 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         bool taken = false;
         for (;;) {
             int t = s_t[cur];
-            if (s_a[t] != (uint32_t)cur) { taken = true; break; }   // an earlier draw had this value
-            int q = t - base;                                       // the step whose fallback value is t
+            if (s_first[t] != (uint32_t)cur) { taken = true; break; }   // an earlier draw had this value
+            int q = t - base;                                           // the step whose fallback value is t
             if (q < 0 || q >= cur) break;
-            cur = q;                                                // taken iff that step fell back
+            cur = q;                                                    // taken iff that step fell back
         }
         int x = taken ? base + i : (int)s_t[i];
         s_x[i] = (uint16_t)x;
         int64_t y = a.batch_y[x];
-        s_lab[x] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+        s_k[i] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
     }
     __syncthreads();
-
-    const int per = (b + TPB - 1) / TPB;       // mini-batch positions owned by one thread
-    const int q_lo = tid * per;
 
     if ((int)blockIdx.x < a.nchunks) {
         // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
@@ -274,13 +272,10 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         s_hist[tid] = 0;
         __syncthreads();
         bool bad = false;
-        for (int u = 0; u < per; ++u) {
-            int q = q_lo + u;
-            if (q < b) {
-                int32_t k = s_lab[q];
-                if (k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
-                bad |= (k == LAB_INVALID);
-            }
+        for (int i = tid; i < c; i += TPB) {
+            const int32_t k = s_k[i];
+            if (k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
+            bad |= (k == LAB_INVALID);
         }
         __syncthreads();
         const int k = k_lo + tid;
@@ -297,69 +292,78 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         return;
     }
 
-    // ---- movers ---------------------------------------------------------------
-    const int mover = blockIdx.x - a.nchunks;
-    const int group = mover / a.tpr, tile = mover % a.tpr;
+    // ---- movers: one work item per wavefront, no workgroup barrier from here on ----
+    const int64_t item = (int64_t)(blockIdx.x - a.nchunks) * NWAVE + wave;
+    if (item >= (int64_t)c * a.tpr) return;
+    const int i = (int)(item / a.tpr), tile = (int)(item % a.tpr);   // candidate in Floyd emission order, tile of its row
+    const int p = s_x[i];                                             // its mini-batch position
+    const int32_t ki = s_k[i];
+    if (ki < 0) return;                    // label outside [0, K): dropped (flagged by bookkeeping)
     int64_t v_lo, v_hi;
     tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
-    for (int rr = 0; rr < a.rpb; ++rr) {
-        const int i = group * a.rpb + rr;      // candidate, in Floyd emission order
-        if (i >= c) break;
-        const int p = s_x[i];                  // its mini-batch position
-        const int32_t k = s_lab[p];
-        if (k < 0) continue;                   // label outside [0, K): dropped (flagged by bookkeeping)
+    const int64_t fill0 = a.fill_old[ki];
+    // the row is read while the wavefront works out where it goes
+    Tile<U, NT, WAVE, false> t;
+    t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
 
-        // Start reading the row now; where it goes is worked out while it is in flight.
-        const int64_t fill0 = a.fill_old[k];
-        Tile<U, NT> t;
-        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
-
-        // Candidates of class k, in mini-batch order: the one at position q with
-        // `rank` class-mates before it is insertion number fill0 + rank of the class.
-        int mine = 0;
-        for (int u = 0; u < per; ++u) {
-            int q = q_lo + u;
-            mine += (q < b && s_lab[q] == k);
-        }
-        int total;
-        int rank = block_scan_excl(mine, total, s_wave);
-        int64_t slot;
-        bool dropped = false;
-        if (fill0 + total <= a.S) {
-            // all of them append: distinct slots, nothing to resolve
-            if (p >= q_lo && p < q_lo + per) {
-                for (int q = q_lo; q < p; ++q) rank += (s_lab[q] == k);
-                s_hist[0] = rank;
-            }
-            __syncthreads();
-            slot = fill0 + s_hist[0];
-            __syncthreads();
-        } else {
-            // some overwrite a uniformly drawn slot; if a later candidate of the
-            // class ends on this candidate's slot, this one is not stored.
-            for (int u = 0; u < per; ++u) {
-                int q = q_lo + u;
-                if (q < b && s_lab[q] == k) {
-                    int64_t at = fill0 + rank++;
-                    s_a[q] = (uint32_t)(at < a.S ? at : (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)q, (uint64_t)a.S));
-                }
-            }
-            __syncthreads();
-            const uint32_t own = s_a[p];
-            int later = 0;
-            for (int u = 0; u < per; ++u) {
-                int q = q_lo + u;
-                later |= (q < b && q > p && s_lab[q] == k && s_a[q] == own);
-            }
-            dropped = __syncthreads_or(later) != 0;
-            slot = own;
-        }
-        if (dropped) continue;
-        const int64_t dst_row = (int64_t)k * a.S + slot;
-        t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-        if (tile == 0 && tid == 0) a.buf_y[dst_row] = k;
+    // Candidates of class ki, in mini-batch order: the one with `rank` class-mates before it is
+    // insertion number fill0 + rank of the class.
+    int total = 0, rank = 0;
+    for (int m0 = 0; m0 < c; m0 += WAVE) {
+        const int m = m0 + lane;
+        const bool same = m < c && s_k[m] == ki;
+        const int xm = m < c ? s_x[m] : 0;
+        total += __popcll(__ballot(same));
+        rank += __popcll(__ballot(same && xm < p));
     }
+    int64_t slot;
+    if (fill0 + total <= a.S) {
+        slot = fill0 + rank;               // all of them append: distinct slots
+    } else {
+        // Insertions beyond the capacity overwrite a uniformly drawn slot.  This candidate is not
+        // stored if a later class-mate overwrites its slot.
+        const int64_t own = fill0 + rank < a.S ? fill0 + rank : (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)p, (uint64_t)a.S);
+        // later class-mates are gathered WAVE at a time so that their draws are made with full wavefronts
+        uint16_t* pend = s_pend[wave];
+        int npend = 0;
+        bool beaten = false;
+        for (int m0 = 0; m0 < c + WAVE; m0 += WAVE) {
+            if (m0 < c) {
+                const int m = m0 + lane;
+                const int xm = m < c ? s_x[m] : 0;
+                const bool later = m < c && s_k[m] == ki && xm > p;
+                const uint64_t mask = __ballot(later);
+                if (later) pend[npend + __popcll(mask & ((1ull << lane) - 1))] = (uint16_t)xm;
+                npend += __popcll(mask);
+            }
+            if (npend >= WAVE || (m0 >= c && npend > 0)) {
+                const int take = npend < WAVE ? npend : WAVE;
+                const int xr = lane < take ? pend[lane] : 0;
+                const bool hit = lane < take && (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)xr, (uint64_t)a.S) == own;
+                uint64_t rivals = __ballot(hit);
+                while (rivals != 0) {              // rare: does that rival overwrite (is it beyond the capacity)?
+                    const int l = __builtin_ctzll(rivals);
+                    rivals &= rivals - 1;
+                    const int xl = lane_read(xr, l);
+                    int rank_l = 0;
+                    for (int q0 = 0; q0 < c; q0 += WAVE) {
+                        const int q = q0 + lane;
+                        rank_l += __popcll(__ballot(q < c && s_k[q] == ki && s_x[q] < xl));
+                    }
+                    beaten |= (fill0 + rank_l >= a.S);
+                }
+                const int rest = lane + take < npend ? pend[lane + take] : 0;    // at most WAVE - 1 left over
+                if (lane + take < npend) pend[lane] = (uint16_t)rest;
+                npend -= take;
+            }
+        }
+        if (beaten) return;
+        slot = own;
+    }
+    const int64_t dst_row = (int64_t)ki * a.S + slot;
+    t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+    if (tile == 0 && lane == 0) a.buf_y[dst_row] = ki;
 }
 
 constexpr int YPRE = 4;    // label loads per thread issued before anything else (covers b <= 1024)
@@ -578,16 +582,18 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
 }
 
 // ---------------------------------------------------------------------------
-// rb_sample_augment: n = min(r, F) distinct stored samples, uniformly.
+// rb_sample_augment: n = min(r, F) distinct stored samples, uniformly; any r
+// and any number of classes (used when r > WAVE or there are more than WAVE
+// chunks of classes).
 //
-// The g-th stored sample (class-major order) is located through the per-class
-// fill counts.  Up to MAXPER * TPB classes every workgroup reads all counts in
-// one round of loads ("direct"); above that it reads the per-chunk sums first
-// and then the CH counts of the one chunk that holds g.
+// The workgroup computes F, the number of stored samples before every chunk of
+// CH classes, and all n Floyd draws into LDS once; then each wavefront takes
+// one work item (output row, tile of WAVE * U vectors): it decides whether its
+// draw is taken, finds the chunk that holds the wanted sample, reads that
+// chunk's CH fill counts (four consecutive classes per lane) and moves its tile.
 //
-// LDS (dynamic): s_cpre[nchunks] i32 (stored samples before each chunk of CH
-// classes; unused in direct mode), s_t[r] u32 (Floyd draws).
-// Grid: ceil(r / rpb) * tpr workgroups, row/tile mapping as in rb_update.
+// LDS (dynamic): s_cpre[nchunks] i32, s_t[r] u32.
+// Grid: ceil(r * tpr / NWAVE) workgroups.
 // ---------------------------------------------------------------------------
 struct SampleArgs {
     const vec16* buf_x;
@@ -604,8 +610,7 @@ struct SampleArgs {
     int32_t tpr;
     int32_t tile_vec;
     int32_t tile_rem;
-    int32_t rpb;
-    int32_t direct;       // 1: K <= MAXPER * TPB, all fill counts are read at once
+    int32_t rpb;          // small kernel: rows per workgroup (1 unless tpr == 1)
 };
 
 template <int U, bool NT>
@@ -615,38 +620,23 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
     int32_t* s_cpre = reinterpret_cast<int32_t*>(lds);    // [nchunks]
     uint32_t* s_t = lds + a.nchunks;                      // [r]
     __shared__ int s_wave[NWAVE];
-    __shared__ int s_pick[2];
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
 
-    // ---- F, and where every class (direct) or chunk of classes starts ----------
+    // ---- F and the number of stored samples before every chunk -----------------
+    const int cper = (a.nchunks + TPB - 1) / TPB;
+    int csum = 0;
+    for (int u = 0; u < cper; ++u) {
+        int ch = tid * cper + u;
+        if (ch < a.nchunks) csum += a.chunk[ch];
+    }
     int F;
-    int32_t freg[MAXPER];          // direct mode: fill counts of classes [tid*kper, tid*kper + kper)
-    int before = 0;                // direct mode: stored samples in classes below tid*kper
-    const int kper = (a.K + TPB - 1) / TPB;
-    if (a.direct) {
-        int local = 0;
-#pragma unroll
-        for (int u = 0; u < MAXPER; ++u) {
-            const int k = tid * kper + u;
-            freg[u] = (u < kper && k < a.K) ? a.fill[k] : 0;
-            local += freg[u];
-        }
-        before = block_scan_excl(local, F, s_wave);
-    } else {
-        const int cper = (a.nchunks + TPB - 1) / TPB;
-        int csum = 0;
-        for (int u = 0; u < cper; ++u) {
-            int ch = tid * cper + u;
-            if (ch < a.nchunks) csum += a.chunk[ch];
-        }
-        int cbefore = block_scan_excl(csum, F, s_wave);
-        for (int u = 0; u < cper; ++u) {
-            int ch = tid * cper + u;
-            if (ch < a.nchunks) {
-                s_cpre[ch] = cbefore;
-                cbefore += a.chunk[ch];
-            }
+    int cbefore = block_scan_excl(csum, F, s_wave);
+    for (int u = 0; u < cper; ++u) {
+        int ch = tid * cper + u;
+        if (ch < a.nchunks) {
+            s_cpre[ch] = cbefore;
+            cbefore += a.chunk[ch];
         }
     }
     const int n = a.r < F ? a.r : F;
@@ -658,70 +648,58 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
         s_t[i] = (uint32_t)below(a.sd, PURPOSE_SAMPLE, (uint32_t)i, (uint64_t)base + i + 1);
     __syncthreads();
 
-    const int group = blockIdx.x / a.tpr, tile = blockIdx.x % a.tpr;
+    // ---- one work item per wavefront, no workgroup barrier from here on ---------
+    const int64_t item = (int64_t)blockIdx.x * NWAVE + wave;
+    if (item >= (int64_t)a.r * a.tpr) return;
+    const int j = (int)(item / a.tpr), tile = (int)(item % a.tpr);    // output row, tile of it
+    if (j >= n) {                              // fewer stored samples than asked for
+        if (tile == 0 && lane == 0) a.out_y[j] = -1;
+        return;
+    }
     int64_t v_lo, v_hi;
     tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
-    for (int rr = 0; rr < a.rpb; ++rr) {
-        const int j = group * a.rpb + rr;      // output row
-        if (j >= a.r) break;
-        if (j >= n) {                          // fewer stored samples than asked for
-            if (tile == 0 && tid == 0) a.out_y[j] = -1;
-            continue;
-        }
-        // Is draw j taken?  (same rule as in rb_update; the earlier-draw test is a
-        // workgroup-wide search because the value range is too large for a table)
-        int cur = j;
-        bool taken = false;
-        for (;;) {
-            const uint32_t t = s_t[cur];
-            int same = 0;
-            for (int q = tid; q < cur; q += TPB) same |= (s_t[q] == t);
-            if (__syncthreads_or(same)) { taken = true; break; }
-            const int64_t q = (int64_t)t - base;
-            if (q < 0 || q >= cur) break;
-            cur = (int)q;
-        }
-        const int g = taken ? base + j : (int)s_t[j];   // g-th stored sample, class-major
-
-        if (tid == 0) { s_pick[0] = 0; s_pick[1] = 0; }   // never left undefined
-        if (a.direct) {
-            __syncthreads();
-            int acc = before;
-#pragma unroll
-            for (int u = 0; u < MAXPER; ++u) {
-                if (g >= acc && g < acc + freg[u]) {
-                    s_pick[0] = tid * kper + u;
-                    s_pick[1] = g - acc;
-                }
-                acc += freg[u];
-            }
-        } else {
-            // chunk holding g: the last one with s_cpre <= g
-            int lo = 0, hi = a.nchunks - 1;
-            while (lo < hi) {
-                int mid = (lo + hi + 1) >> 1;
-                if (s_cpre[mid] <= g) lo = mid; else hi = mid - 1;
-            }
-            const int gl = g - s_cpre[lo];
-            const int k = lo * CH + tid;
-            const int f = k < a.K ? a.fill[k] : 0;
-            int unused;
-            const int kbefore = block_scan_excl(f, unused, s_wave);
-            if (gl >= kbefore && gl < kbefore + f) {
-                s_pick[0] = k;
-                s_pick[1] = gl - kbefore;
-            }
-        }
-        __syncthreads();
-        const int pk = s_pick[0], ps = s_pick[1];
-        __syncthreads();
-
-        Tile<U, NT> t;
-        t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
-        t.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
-        if (tile == 0 && tid == 0) a.out_y[j] = pk;
+    // Draw j is replaced by base + j iff an earlier draw had the same value, or it equals
+    // base + q for an earlier q whose own draw was replaced.
+    int cur = j;
+    bool taken = false;
+    for (;;) {
+        const uint32_t t = s_t[cur];
+        bool same = false;
+        for (int q = lane; q < cur; q += WAVE) same |= (s_t[q] == t);
+        if (__ballot(same) != 0) { taken = true; break; }
+        const int64_t q = (int64_t)t - base;
+        if (q < 0 || q >= cur) break;
+        cur = (int)q;
     }
+    const int g = taken ? base + j : (int)s_t[j];      // g-th stored sample, class-major
+
+    // chunk holding g: the last one with s_cpre <= g
+    int lo = 0, hi = a.nchunks - 1;
+    while (lo < hi) {
+        int mid = (lo + hi + 1) >> 1;
+        if (s_cpre[mid] <= g) lo = mid; else hi = mid - 1;
+    }
+    const int gl = g - s_cpre[lo];
+    const int4 f = *reinterpret_cast<const int4*>(a.fill + (int64_t)lo * CH + 4 * lane);
+    const int local = f.x + f.y + f.z + f.w;
+    const int lincl = wave_scan_incl(local);
+    int acc = lincl - local;
+    const bool mine = gl >= acc && gl < lincl;
+    int u = 0;
+    if (mine) {
+        if (gl >= acc + f.x) { acc += f.x; u = 1;
+            if (gl >= acc + f.y) { acc += f.y; u = 2;
+                if (gl >= acc + f.z) { acc += f.z; u = 3; } } }
+    }
+    const int owner = __builtin_ctzll(__ballot(mine) | (1ull << 63));
+    const int pk = lane_read(lo * CH + 4 * lane + u, owner);
+    const int ps = lane_read(gl - acc, owner);
+
+    Tile<U, NT, WAVE, false> t;
+    t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
+    t.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
+    if (tile == 0 && lane == 0) a.out_y[j] = pk;
 }
 
 // ---------------------------------------------------------------------------
@@ -1126,27 +1104,31 @@ struct Shape {
     int64_t groups;
 };
 
-// Split `rows` rows of `row_vec` vectors into workgroup tiles.
-Shape plan_shape(const rb_buffer* rb, int64_t rows)
+// Split `rows` rows of `row_vec` vectors into tiles of at most width * unroll vectors, where `width`
+// is the number of threads that share a tile: TPB in the small-count kernels (a workgroup per tile),
+// WAVE in the general ones (a wavefront per tile).
+Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
 {
     Shape s;
     const int64_t row_vec = rb->row_vec;
     int u = rb->opt_unroll;
     if (u == 0) {
-        // largest unroll that still leaves about four workgroups per compute unit; never
-        // below two vectors in flight per thread (one was slower at every size measured)
+        // Largest unroll that still leaves at least 1024 tiles (four workgroups per compute unit in
+        // the small-count kernels, four wavefronts in the general ones); never below two vectors in
+        // flight per thread (one was slower at every size measured) unless the row is shorter.
         u = 8;
-        while (u > 2 && rows * ((row_vec + (int64_t)TPB * u - 1) / ((int64_t)TPB * u)) < 1024) u >>= 1;
+        while (u > 2 && rows * ((row_vec + (int64_t)width * u - 1) / ((int64_t)width * u)) < 1024) u >>= 1;
+        while (u > 1 && (int64_t)width * (u / 2) >= row_vec) u >>= 1;
     }
     s.unroll = u;
-    const int64_t cap = (int64_t)TPB * u;
+    const int64_t cap = (int64_t)width * u;
     s.tpr = (int)((row_vec + cap - 1) / cap);
     // even split in units of TILE_UNIT vectors: every tile holds nunits / tpr units, the first nunits % tpr one more
     const int64_t nunits = (row_vec + TILE_UNIT - 1) / TILE_UNIT;
     s.tile_vec = (int)(nunits / s.tpr);
     s.tile_rem = (int)(nunits % s.tpr);
     s.rpb = 1;
-    if (s.tpr == 1) {
+    if (width == TPB && s.tpr == 1) {
         int r = rb->opt_rpb;
         if (r == 0) {
             r = 1;
@@ -1163,10 +1145,10 @@ hipError_t launch_update(const UpdateArgs& a, int unroll, dim3 grid, size_t lds,
 {
     if (a.c <= WAVE) {
         switch (unroll) {
-        case 1: rb_update_small_kernel<1, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
-        case 2: rb_update_small_kernel<2, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
-        case 4: rb_update_small_kernel<4, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
-        default: rb_update_small_kernel<8, NT><<<grid, TPB, (size_t)a.b * 8, st>>>(a); break;
+        case 1: rb_update_small_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_update_small_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_update_small_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_update_small_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
         }
         return hipGetLastError();
     }
@@ -1184,10 +1166,10 @@ hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds,
 {
     if (a.r <= WAVE && a.nchunks <= WAVE) {
         switch (unroll) {
-        case 1: rb_sample_small_kernel<1, NT><<<grid, TPB, 0, st>>>(a); break;
-        case 2: rb_sample_small_kernel<2, NT><<<grid, TPB, 0, st>>>(a); break;
-        case 4: rb_sample_small_kernel<4, NT><<<grid, TPB, 0, st>>>(a); break;
-        default: rb_sample_small_kernel<8, NT><<<grid, TPB, 0, st>>>(a); break;
+        case 1: rb_sample_small_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_sample_small_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_sample_small_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_sample_small_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
         }
         return hipGetLastError();
     }
@@ -1327,7 +1309,8 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (!rb->bound) return RB_ESTATE;
     if (c == 0) return RB_OK;
 
-    const Shape sh = plan_shape(rb, c);
+    const bool small = c <= WAVE;
+    const Shape sh = plan_shape(rb, c, small ? TPB : WAVE);
     UpdateArgs a;
     a.batch_x = static_cast<const vec16*>(batch_x);
     a.batch_y = batch_y;
@@ -1343,8 +1326,8 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.S = rb->S;
     a.row_vec = rb->row_vec;
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
-    const dim3 grid((unsigned)(rb->nchunks + sh.groups * sh.tpr));
-    const size_t lds = (size_t)b * 8 + (size_t)c * 4;
+    const dim3 grid((unsigned)(rb->nchunks + (small ? sh.groups * sh.tpr : (c * sh.tpr + NWAVE - 1) / NWAVE)));
+    const size_t lds = small ? (size_t)b * 8 : (size_t)b * 4 + (size_t)c * 8;
     hipError_t e = rb->opt_nt ? launch_update<true>(a, sh.unroll, grid, lds, rb->stream)
                               : launch_update<false>(a, sh.unroll, grid, lds, rb->stream);
     if (e != hipSuccess) return RB_EHIP;
@@ -1359,7 +1342,8 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     if (!rb->bound) return RB_ESTATE;
     if (r == 0) return RB_OK;
 
-    const Shape sh = plan_shape(rb, r);
+    const bool small = r <= WAVE && rb->nchunks <= WAVE;
+    const Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
     SampleArgs a;
     a.buf_x = static_cast<const vec16*>(rb->buf_x);
     a.out_x = static_cast<vec16*>(out_x);
@@ -1373,9 +1357,8 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     a.S = rb->S;
     a.row_vec = rb->row_vec;
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
-    a.direct = rb->K <= (int64_t)MAXPER * TPB ? 1 : 0;
-    const dim3 grid((unsigned)(sh.groups * sh.tpr));
-    const size_t lds = ((size_t)rb->nchunks + (size_t)r) * 4;
+    const dim3 grid((unsigned)(small ? sh.groups * sh.tpr : (r * sh.tpr + NWAVE - 1) / NWAVE));
+    const size_t lds = small ? 0 : ((size_t)rb->nchunks + (size_t)r) * 4;
     hipError_t e = rb->opt_nt ? launch_sample<true>(a, sh.unroll, grid, lds, rb->stream)
                               : launch_sample<false>(a, sh.unroll, grid, lds, rb->stream);
     return e == hipSuccess ? RB_OK : RB_EHIP;
@@ -1397,7 +1380,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
         if (rc != RB_OK) return rc;
         return rb_sample_augment(rb, r, seed, step, out_x, out_y);
     }
-    const Shape sh = plan_shape(rb, c + r);
+    const Shape sh = plan_shape(rb, c + r, TPB);
     StepArgs sa;
     UpdateArgs& a = sa.u;
     a.batch_x = static_cast<const vec16*>(batch_x);
