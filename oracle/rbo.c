@@ -30,6 +30,7 @@
  * the paper (its two-iteration figures carry no numbers) -- "parity unpinned
  * by the paper" for those, pinned only through the properties above.
  */
+#include <limits.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -37,6 +38,21 @@
 #define RBO_SELECT 1u   /* purpose tag of the draws that choose candidates       */
 #define RBO_EVICT  2u   /* purpose tag of the draws that choose a slot to replace */
 #define RBO_SAMPLE 3u   /* purpose tag of the draws that choose representatives   */
+#define RBO_COIN   4u   /* purpose tag of the per-sample coin of the Bernoulli selection */
+
+/* Policy variants (the default pair is what Algorithm 1 prints).
+ * Selection: EXACT  - "select c random candidates": a uniform subset of exactly c positions;
+ *            BERNOULLI - the text's "every sample of m_n has a c/b probability to be pushed":
+ *                        an independent coin of probability c/b per sample.
+ * Eviction ("replace old representatives ... at random or using a different strategy", Sec. IV-A):
+ *            UNIFORM   - overwrite a uniformly drawn slot of the class;
+ *            FIFO      - overwrite the oldest representative of the class;
+ *            RESERVOIR - reservoir sampling per class (Vitter's Algorithm R): the n-th sample ever
+ *                        offered to a full class replaces a uniformly drawn slot with probability
+ *                        S/n and is discarded otherwise, so that the class holds a uniform sample
+ *                        of everything it was offered. */
+enum { RBO_SELECT_EXACT = 0, RBO_SELECT_BERNOULLI = 1 };
+enum { RBO_EVICT_UNIFORM = 0, RBO_EVICT_FIFO = 1, RBO_EVICT_RESERVOIR = 2 };
 
 /* ------------------------------------------------------------------------ */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as  */
@@ -114,6 +130,9 @@ typedef struct rbo_buffer {
     int64_t *ins_slot;    /* [c] the slot it went to                             */
     int64_t *smp_g;       /* [last_n] index, among the filled slots in class-major order, of each representative */
     int64_t cap_ins, cap_smp;
+    int selection, eviction;   /* policy variant, see the enums above */
+    int32_t *head;        /* [K] FIFO: slot of the oldest representative of a full class       */
+    int32_t *seen;        /* [K] RESERVOIR: samples offered to the class so far (saturating)   */
 } rbo_buffer;
 
 rbo_buffer *rbo_create(int64_t classes, int64_t slots_per_class, int64_t row_bytes)
@@ -124,9 +143,13 @@ rbo_buffer *rbo_create(int64_t classes, int64_t slots_per_class, int64_t row_byt
     rb->K = classes; rb->S = slots_per_class; rb->row_bytes = row_bytes;
     size_t slots = (size_t)classes * (size_t)slots_per_class;
     rb->fill = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
+    rb->head = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
+    rb->seen = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
     rb->buf_y = (int64_t *)malloc(slots * sizeof(int64_t));
     rb->rows = (unsigned char **)calloc(slots, sizeof(unsigned char *));
-    if (!rb->fill || !rb->buf_y || !rb->rows) { free(rb->fill); free(rb->buf_y); free(rb->rows); free(rb); return NULL; }
+    if (!rb->fill || !rb->head || !rb->seen || !rb->buf_y || !rb->rows) {
+        free(rb->fill); free(rb->head); free(rb->seen); free(rb->buf_y); free(rb->rows); free(rb); return NULL;
+    }
     for (size_t i = 0; i < slots; ++i) rb->buf_y[i] = -1;
     return rb;
 }
@@ -136,9 +159,20 @@ void rbo_destroy(rbo_buffer *rb)
     if (!rb) return;
     size_t slots = (size_t)rb->K * (size_t)rb->S;
     for (size_t i = 0; i < slots; ++i) free(rb->rows[i]);
-    free(rb->rows); free(rb->buf_y); free(rb->fill);
+    free(rb->rows); free(rb->buf_y); free(rb->fill); free(rb->head); free(rb->seen);
     free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot); free(rb->smp_g);
     free(rb);
+}
+
+/* Choose the policy variant; only while the buffer is still empty.  Returns 0, or -1. */
+int rbo_set_policy(rbo_buffer *rb, int selection, int eviction)
+{
+    if (!rb || selection < 0 || selection > 1 || eviction < 0 || eviction > 2) return -1;
+    for (int64_t k = 0; k < rb->K; ++k)
+        if (rb->fill[k] != 0 || rb->seen[k] != 0) return -1;
+    rb->selection = selection;
+    rb->eviction = eviction;
+    return 0;
 }
 
 static int cmp_i64(const void *a, const void *b)
@@ -155,40 +189,61 @@ int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
                int64_t b, int64_t c, uint64_t seed, uint64_t step)
 {
     if (!rb || !batch_x || !batch_y || b < 1 || c < 0 || c > b) return -1;
-    if (c > rb->cap_ins) {
+    /* at most c candidates with the exact selection, at most b with the Bernoulli one */
+    int64_t cap = rb->selection == RBO_SELECT_BERNOULLI ? b : c;
+    if (cap > rb->cap_ins) {
         free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot);
-        rb->ins_pos = (int64_t *)malloc((size_t)c * sizeof(int64_t));
-        rb->ins_class = (int64_t *)malloc((size_t)c * sizeof(int64_t));
-        rb->ins_slot = (int64_t *)malloc((size_t)c * sizeof(int64_t));
-        rb->cap_ins = c;
+        rb->ins_pos = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
+        rb->ins_class = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
+        rb->ins_slot = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
+        rb->cap_ins = cap;
         if (!rb->ins_pos || !rb->ins_class || !rb->ins_slot) return -1;
     }
     rb->n_ins = 0;
     if (c == 0) return 0;
 
-    /* "C <- select c random candidates from mini-batch m": a uniform c-subset
-     * of the b positions. */
-    int64_t *cand = (int64_t *)malloc((size_t)c * sizeof(int64_t));
+    int64_t *cand = (int64_t *)malloc((size_t)cap * sizeof(int64_t));
     if (!cand) return -1;
-    rbo_floyd(seed, step, RBO_SELECT, b, c, cand);
-
-    /* "for c in C": visited in ascending mini-batch position. */
-    qsort(cand, (size_t)c, sizeof(int64_t), cmp_i64);
+    int64_t ncand;
+    if (rb->selection == RBO_SELECT_BERNOULLI) {
+        /* "Every sample of m_n has a c/b probability to be pushed": one coin per position,
+         * heads iff a uniform integer below b is below c. */
+        ncand = 0;
+        for (int64_t pos = 0; pos < b; ++pos)
+            if ((int64_t)rbo_bounded(seed, step, RBO_COIN, (uint32_t)pos, (uint64_t)b) < c) cand[ncand++] = pos;
+    } else {
+        /* "C <- select c random candidates from mini-batch m": a uniform c-subset
+         * of the b positions. */
+        rbo_floyd(seed, step, RBO_SELECT, b, c, cand);
+        ncand = c;
+        /* "for c in C": visited in ascending mini-batch position. */
+        qsort(cand, (size_t)c, sizeof(int64_t), cmp_i64);
+    }
 
     const unsigned char *src = (const unsigned char *)batch_x;
-    for (int64_t q = 0; q < c; ++q) {
+    for (int64_t q = 0; q < ncand; ++q) {
         int64_t pos = cand[q];
         int64_t k = batch_y[pos];
         if (k < 0 || k >= rb->K) { rb->flags |= 1u; continue; }
         int64_t s;
-        if (rb->fill[k] >= rb->S) {
-            /* "replace a random representative from R^i_n": every slot of the
-             * class equally likely, whatever its age. */
-            s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)rb->S);
-        } else {
+        int64_t offered = rb->seen[k];          /* samples offered to class k before this one */
+        if (rb->seen[k] < INT32_MAX) rb->seen[k] += 1;
+        if (rb->fill[k] < rb->S) {
             /* "append c to R^i_n" */
             s = rb->fill[k];
             rb->fill[k] += 1;
+        } else if (rb->eviction == RBO_EVICT_FIFO) {
+            /* replace the oldest representative */
+            s = rb->head[k];
+            rb->head[k] = (int32_t)((rb->head[k] + 1) % rb->S);
+        } else if (rb->eviction == RBO_EVICT_RESERVOIR) {
+            /* Algorithm R: sample number `offered` (0-based) stays with probability S/(offered+1) */
+            s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)offered + 1);
+            if (s >= rb->S) continue;
+        } else {
+            /* "replace a random representative from R^i_n": every slot of the
+             * class equally likely, whatever its age. */
+            s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)rb->S);
         }
         size_t slot = (size_t)k * (size_t)rb->S + (size_t)s;
         if (!rb->rows[slot]) {

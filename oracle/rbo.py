@@ -11,7 +11,9 @@ import numpy as np
 
 from . import build as _build
 
-SELECT, EVICT, SAMPLE = 1, 2, 3
+SELECT, EVICT, SAMPLE, COIN = 1, 2, 3, 4
+SELECT_EXACT, SELECT_BERNOULLI = 0, 1
+EVICT_UNIFORM, EVICT_FIFO, EVICT_RESERVOIR = 0, 1, 2
 
 _lib = None
 
@@ -36,6 +38,8 @@ def lib():
         L.rbo_create.restype = vp
         L.rbo_destroy.argtypes = [vp]
         L.rbo_destroy.restype = None
+        L.rbo_set_policy.argtypes = [vp, C.c_int, C.c_int]
+        L.rbo_set_policy.restype = C.c_int
         L.rbo_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
         L.rbo_update.restype = C.c_int
         L.rbo_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
@@ -95,6 +99,10 @@ class Buffer:
         self._h = lib().rbo_create(self.K, self.S, self.row_bytes)
         if not self._h:
             raise ValueError("rbo_create rejected the arguments")
+
+    def set_policy(self, selection, eviction):
+        if lib().rbo_set_policy(self._h, int(selection), int(eviction)) != 0:
+            raise ValueError("rbo_set_policy rejected the arguments (unknown variant, or the buffer is not empty)")
 
     def close(self):
         if self._h:

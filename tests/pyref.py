@@ -9,7 +9,7 @@ samples).
 """
 
 MASK32 = 0xFFFFFFFF
-SELECT, EVICT, SAMPLE = 1, 2, 3
+SELECT, EVICT, SAMPLE, COIN = 1, 2, 3, 4
 
 
 def philox4x32_10(ctr, key):
@@ -44,23 +44,41 @@ def floyd(seed, step, purpose, n, m):
 
 
 class PyBuffer:
-    def __init__(self, K, S):
+    def __init__(self, K, S, selection="exact", eviction="uniform"):
         self.K, self.S = K, S
         self.R = {k: [] for k in range(K)}     # class -> list of stored rows (bytes objects), index = slot
         self.bad_label = False
+        self.selection, self.eviction = selection, eviction
+        self.age = {k: [] for k in range(K)}   # fifo: arrival number of what each slot holds
+        self.offered = {k: 0 for k in range(K)}
 
     def update(self, rows, labels, c, seed, step):
         b = len(labels)
-        for pos in sorted(floyd(seed, step, SELECT, b, c)):
+        if self.selection == "bernoulli":
+            chosen = [pos for pos in range(b) if bounded(seed, step, COIN, pos, b) < c]
+        else:
+            chosen = sorted(floyd(seed, step, SELECT, b, c))
+        for pos in chosen:
             k = labels[pos]
             if not (0 <= k < self.K):
                 self.bad_label = True
                 continue
             sub = self.R[k]
-            if len(sub) >= self.S:
-                sub[bounded(seed, step, EVICT, pos, self.S)] = rows[pos]
-            else:
+            n = self.offered[k]
+            self.offered[k] += 1
+            if len(sub) < self.S:
                 sub.append(rows[pos])
+                self.age[k].append(n)
+            elif self.eviction == "fifo":
+                oldest = min(range(self.S), key=lambda s: self.age[k][s])
+                sub[oldest] = rows[pos]
+                self.age[k][oldest] = n
+            elif self.eviction == "reservoir":
+                j = bounded(seed, step, EVICT, pos, n + 1)
+                if j < self.S:
+                    sub[j] = rows[pos]
+            else:
+                sub[bounded(seed, step, EVICT, pos, self.S)] = rows[pos]
 
     def stored(self):
         """Every stored sample as (class, slot, row), class after class."""
