@@ -84,6 +84,27 @@ int rb_query_sizes(const rb_buffer *rb, size_t *x_bytes, size_t *y_bytes, size_t
  */
 int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *hip_stream);
 
+/*
+ * Policy variants of Algorithm 1.  The defaults are what Algorithm 1 prints.
+ * Selection: RB_SELECT_EXACT - "select c random candidates": a uniform subset
+ * of exactly c positions; RB_SELECT_BERNOULLI - the text of Sec. IV-B, "every
+ * sample of m_n has a c/b probability to be pushed": an independent coin of
+ * probability c/b per sample (any number of candidates from 0 to b).
+ * Eviction (Sec. IV-A: "at random or using a different strategy"):
+ * RB_EVICT_UNIFORM - overwrite a uniformly drawn slot of the class;
+ * RB_EVICT_FIFO - overwrite the oldest sample of the class;
+ * RB_EVICT_RESERVOIR - reservoir sampling per class: the n-th sample ever
+ * offered to a full class replaces a uniformly drawn slot with probability
+ * slots_per_class / n and is dropped otherwise (exact while a class has been
+ * offered fewer than 2^31 - 1 samples).
+ * With a variant selected the general kernels are used and rb_update_sample
+ * enqueues two launches.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update
+ * was already enqueued since the last rb_bind.
+ */
+enum rb_selection { RB_SELECT_EXACT = 0, RB_SELECT_BERNOULLI = 1 };
+enum rb_eviction { RB_EVICT_UNIFORM = 0, RB_EVICT_FIFO = 1, RB_EVICT_RESERVOIR = 2 };
+int rb_set_policy(rb_buffer *rb, int32_t selection, int32_t eviction);
+
 /* Replace the stream later calls enqueue on.  The caller orders the old and
  * the new stream itself (events) if work is still pending on the old one. */
 int rb_set_stream(rb_buffer *rb, void *hip_stream);

@@ -18,9 +18,11 @@ RB_MAX_BATCH = 4096
 RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
 RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE = 0, 1, 2, 3
+RB_SELECT_EXACT, RB_SELECT_BERNOULLI = 0, 1
+RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
-    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
+    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -41,6 +43,7 @@ def _load():
     L.rb_create.argtypes = [C.POINTER(vp), i64, i64, C.POINTER(i64), i32, i32]
     L.rb_query_sizes.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     L.rb_bind.argtypes = [vp, vp, vp, vp, vp]
+    L.rb_set_policy.argtypes = [vp, i32, i32]
     L.rb_set_stream.argtypes = [vp, vp]
     L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
@@ -97,6 +100,10 @@ def rb_query_sizes(rb):
 
 def rb_bind(rb, buf_x, buf_y, workspace, hip_stream=None):
     return _L.rb_bind(rb, _ptr(buf_x), _ptr(buf_y), _ptr(workspace), _stream(hip_stream))
+
+
+def rb_set_policy(rb, selection, eviction):
+    return _L.rb_set_policy(rb, int(selection), int(eviction))
 
 
 def rb_set_stream(rb, hip_stream):
@@ -168,6 +175,9 @@ class RehearsalBuffer:
         assert self.buf_x.numel() * self.buf_x.element_size() == xb and self.buf_y.numel() * 8 == yb
         self.stream = stream
         _check(rb_bind(self.handle, self.buf_x, self.buf_y, self.workspace, stream), "rb_bind")
+
+    def set_policy(self, selection, eviction):
+        _check(rb_set_policy(self.handle, selection, eviction), "rb_set_policy")
 
     def set_stream(self, stream):
         self.stream = stream

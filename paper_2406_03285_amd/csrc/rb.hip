@@ -30,6 +30,7 @@ constexpr int TILE_UNIT = 64;          // granularity, in 16-byte vectors, at wh
 constexpr uint32_t PURPOSE_SELECT = 1; // counter word that separates the three kinds of draws
 constexpr uint32_t PURPOSE_EVICT = 2;
 constexpr uint32_t PURPOSE_SAMPLE = 3;
+constexpr uint32_t PURPOSE_COIN = 4;   // per-sample coin of the Bernoulli selection
 constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a candidate
 constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
 
@@ -219,52 +220,89 @@ struct UpdateArgs {
     int32_t tile_vec;     // a row is split evenly into tpr tiles in units of TILE_UNIT vectors: the first
     int32_t tile_rem;     // tile_rem tiles hold tile_vec + 1 units, the others tile_vec; see tile_bounds
     int32_t rpb;          // small kernels: rows per mover workgroup (1 unless tpr == 1)
+    // policy variants (general kernel only)
+    int32_t selection;    // RB_SELECT_*
+    int32_t eviction;     // RB_EVICT_*
+    int32_t cap;          // most candidates a step can have: c (exact selection) or b (Bernoulli)
+    const int32_t* aux_old;   // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
+    int32_t* aux_new;
 };
 
 template <int U, bool NT>
 __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 {
     extern __shared__ uint32_t lds[];
-    uint32_t* s_first = lds;                                        // [b]
-    int32_t* s_k = reinterpret_cast<int32_t*>(lds + a.b);           // [c]
-    uint16_t* s_t = reinterpret_cast<uint16_t*>(lds + a.b + a.c);   // [c]
-    uint16_t* s_x = s_t + a.c;                                      // [c]
+    uint32_t* s_first = lds;                                          // [b]
+    int32_t* s_k = reinterpret_cast<int32_t*>(lds + a.b);             // [cap]
+    uint16_t* s_t = reinterpret_cast<uint16_t*>(lds + a.b + a.cap);   // [cap]
+    uint16_t* s_x = s_t + a.cap;                                      // [cap]
     __shared__ int s_wave[NWAVE];
     __shared__ int s_hist[CH];
     __shared__ uint16_t s_pend[NWAVE][2 * WAVE];    // per wavefront: later class-mates waiting for their evict draw
+    __shared__ uint32_t s_cm[NWAVE][RB_MAX_BATCH / 32];     // per wavefront: bitmap of the class-mates' positions
+    __shared__ uint16_t s_cmpre[NWAVE][RB_MAX_BATCH / 32];  // class-mates before each bitmap word
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int b = a.b, c = a.c;
+    int m;      // number of candidates of this step (the same in every workgroup)
 
-    // ---- candidate selection: Floyd's c-subset of [0, b), all draws at once --
-    // Draw i is t_i in [0, b-c+i]; it is "taken" iff an earlier draw had the same
-    // value, or it equals b-c+q for an earlier q whose own draw was taken; a
-    // taken draw is replaced by b-c+i.
-    for (int q = tid; q < b; q += TPB) s_first[q] = 0xFFFFFFFFu;
-    __syncthreads();
-    const int base = b - c;
-    for (int i = tid; i < c; i += TPB) {
-        uint32_t t = (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)i, (uint64_t)(base + i + 1));
-        s_t[i] = (uint16_t)t;
-        atomicMin(&s_first[t], (uint32_t)i);
-    }
-    __syncthreads();
-    for (int i = tid; i < c; i += TPB) {
-        int cur = i;
-        bool taken = false;
-        for (;;) {
-            int t = s_t[cur];
-            if (s_first[t] != (uint32_t)cur) { taken = true; break; }   // an earlier draw had this value
-            int q = t - base;                                           // the step whose fallback value is t
-            if (q < 0 || q >= cur) break;
-            cur = q;                                                    // taken iff that step fell back
+    if (a.selection == RB_SELECT_BERNOULLI) {
+        // ---- one coin per sample, heads with probability c/b; candidates in mini-batch order ----
+        const int per = (b + TPB - 1) / TPB;
+        const int q_lo = tid * per;
+        int mine = 0;
+        for (int u = 0; u < per; ++u) {
+            const int q = q_lo + u;
+            if (q < b && (int64_t)below(a.sd, PURPOSE_COIN, (uint32_t)q, (uint64_t)b) < c) {
+                s_first[q] = 1u;
+                ++mine;
+            } else if (q < b) {
+                s_first[q] = 0u;
+            }
         }
-        int x = taken ? base + i : (int)s_t[i];
-        s_x[i] = (uint16_t)x;
-        int64_t y = a.batch_y[x];
-        s_k[i] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+        int at = block_scan_excl(mine, m, s_wave);
+        for (int u = 0; u < per; ++u) {
+            const int q = q_lo + u;
+            if (q < b && s_first[q] != 0u) {
+                s_x[at] = (uint16_t)q;
+                const int64_t y = a.batch_y[q];
+                s_k[at] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+                ++at;
+            }
+        }
+        __syncthreads();
+    } else {
+        // ---- candidate selection: Floyd's c-subset of [0, b), all draws at once --
+        // Draw i is t_i in [0, b-c+i]; it is "taken" iff an earlier draw had the same
+        // value, or it equals b-c+q for an earlier q whose own draw was taken; a
+        // taken draw is replaced by b-c+i.
+        m = c;
+        for (int q = tid; q < b; q += TPB) s_first[q] = 0xFFFFFFFFu;
+        __syncthreads();
+        const int base = b - c;
+        for (int i = tid; i < c; i += TPB) {
+            uint32_t t = (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)i, (uint64_t)(base + i + 1));
+            s_t[i] = (uint16_t)t;
+            atomicMin(&s_first[t], (uint32_t)i);
+        }
+        __syncthreads();
+        for (int i = tid; i < c; i += TPB) {
+            int cur = i;
+            bool taken = false;
+            for (;;) {
+                int t = s_t[cur];
+                if (s_first[t] != (uint32_t)cur) { taken = true; break; }   // an earlier draw had this value
+                int q = t - base;                                           // the step whose fallback value is t
+                if (q < 0 || q >= cur) break;
+                cur = q;                                                    // taken iff that step fell back
+            }
+            int x = taken ? base + i : (int)s_t[i];
+            s_x[i] = (uint16_t)x;
+            int64_t y = a.batch_y[x];
+            s_k[i] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+        }
+        __syncthreads();
     }
-    __syncthreads();
 
     if ((int)blockIdx.x < a.nchunks) {
         // ---- bookkeeping: fill_new = min(fill_old + candidates of the class, S) ----
@@ -272,7 +310,7 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         s_hist[tid] = 0;
         __syncthreads();
         bool bad = false;
-        for (int i = tid; i < c; i += TPB) {
+        for (int i = tid; i < m; i += TPB) {
             const int32_t k = s_k[i];
             if (k >= k_lo && k < k_lo + CH) atomicAdd(&s_hist[k - k_lo], 1);
             bad |= (k == LAB_INVALID);
@@ -281,9 +319,18 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         const int k = k_lo + tid;
         int32_t nf = 0;
         if (k < a.K) {
-            int64_t v = (int64_t)a.fill_old[k] + s_hist[tid];
+            const int64_t old = a.fill_old[k];
+            const int64_t v = old + s_hist[tid];
             nf = (int32_t)(v < a.S ? v : a.S);
             a.fill_new[k] = nf;
+            if (a.eviction == RB_EVICT_FIFO) {
+                // the oldest sample moves on by the number of overwrites
+                const int64_t over = v > a.S ? v - a.S : 0;
+                a.aux_new[k] = (int32_t)(((int64_t)a.aux_old[k] + over) % a.S);
+            } else if (a.eviction == RB_EVICT_RESERVOIR) {
+                const int64_t seen = (int64_t)a.aux_old[k] + s_hist[tid];
+                a.aux_new[k] = (int32_t)(seen < INT32_MAX ? seen : INT32_MAX);
+            }
         }
         int total;
         block_scan_excl(nf, total, s_wave);
@@ -292,78 +339,103 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         return;
     }
 
-    // ---- movers: one work item per wavefront, no workgroup barrier from here on ----
-    const int64_t item = (int64_t)(blockIdx.x - a.nchunks) * NWAVE + wave;
-    if (item >= (int64_t)c * a.tpr) return;
-    const int i = (int)(item / a.tpr), tile = (int)(item % a.tpr);   // candidate in Floyd emission order, tile of its row
-    const int p = s_x[i];                                             // its mini-batch position
-    const int32_t ki = s_k[i];
-    if (ki < 0) return;                    // label outside [0, K): dropped (flagged by bookkeeping)
-    int64_t v_lo, v_hi;
-    tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
+    // ---- movers: one work item per wavefront and round, no workgroup barrier from here on ----
+    const int64_t stride = (int64_t)(gridDim.x - a.nchunks) * NWAVE;
+    for (int64_t item = (int64_t)(blockIdx.x - a.nchunks) * NWAVE + wave; item < (int64_t)m * a.tpr; item += stride) {
+        const int i = (int)(item / a.tpr), tile = (int)(item % a.tpr);   // candidate, tile of its row
+        const int p = s_x[i];                                             // its mini-batch position
+        const int32_t ki = s_k[i];
+        if (ki < 0) continue;                  // label outside [0, K): dropped (flagged by bookkeeping)
+        int64_t v_lo, v_hi;
+        tile_bounds(tile, a.tile_vec, a.tile_rem, a.row_vec, v_lo, v_hi);
 
-    const int64_t fill0 = a.fill_old[ki];
-    // the row is read while the wavefront works out where it goes
-    Tile<U, NT, WAVE, false> t;
-    t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
+        const int64_t fill0 = a.fill_old[ki];
+        const int64_t aux0 = a.eviction != RB_EVICT_UNIFORM ? a.aux_old[ki] : 0;
+        // the row is read while the wavefront works out where it goes
+        Tile<U, NT, WAVE, false> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
 
-    // Candidates of class ki, in mini-batch order: the one with `rank` class-mates before it is
-    // insertion number fill0 + rank of the class.
-    int total = 0, rank = 0;
-    for (int m0 = 0; m0 < c; m0 += WAVE) {
-        const int m = m0 + lane;
-        const bool same = m < c && s_k[m] == ki;
-        const int xm = m < c ? s_x[m] : 0;
-        total += __popcll(__ballot(same));
-        rank += __popcll(__ballot(same && xm < p));
-    }
-    int64_t slot;
-    if (fill0 + total <= a.S) {
-        slot = fill0 + rank;               // all of them append: distinct slots
-    } else {
-        // Insertions beyond the capacity overwrite a uniformly drawn slot.  This candidate is not
-        // stored if a later class-mate overwrites its slot.
-        const int64_t own = fill0 + rank < a.S ? fill0 + rank : (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)p, (uint64_t)a.S);
-        // later class-mates are gathered WAVE at a time so that their draws are made with full wavefronts
-        uint16_t* pend = s_pend[wave];
-        int npend = 0;
-        bool beaten = false;
-        for (int m0 = 0; m0 < c + WAVE; m0 += WAVE) {
-            if (m0 < c) {
-                const int m = m0 + lane;
-                const int xm = m < c ? s_x[m] : 0;
-                const bool later = m < c && s_k[m] == ki && xm > p;
-                const uint64_t mask = __ballot(later);
-                if (later) pend[npend + __popcll(mask & ((1ull << lane) - 1))] = (uint16_t)xm;
-                npend += __popcll(mask);
-            }
-            if (npend >= WAVE || (m0 >= c && npend > 0)) {
-                const int take = npend < WAVE ? npend : WAVE;
-                const int xr = lane < take ? pend[lane] : 0;
-                const bool hit = lane < take && (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)xr, (uint64_t)a.S) == own;
-                uint64_t rivals = __ballot(hit);
-                while (rivals != 0) {              // rare: does that rival overwrite (is it beyond the capacity)?
-                    const int l = __builtin_ctzll(rivals);
-                    rivals &= rivals - 1;
-                    const int xl = lane_read(xr, l);
-                    int rank_l = 0;
-                    for (int q0 = 0; q0 < c; q0 += WAVE) {
-                        const int q = q0 + lane;
-                        rank_l += __popcll(__ballot(q < c && s_k[q] == ki && s_x[q] < xl));
-                    }
-                    beaten |= (fill0 + rank_l >= a.S);
-                }
-                const int rest = lane + take < npend ? pend[lane + take] : 0;    // at most WAVE - 1 left over
-                if (lane + take < npend) pend[lane] = (uint16_t)rest;
-                npend -= take;
-            }
+        // Candidates of class ki, in mini-batch order: the one with `rank` class-mates before it is
+        // insertion number fill0 + rank of the class.
+        int total = 0, rank = 0;
+        for (int m0 = 0; m0 < m; m0 += WAVE) {
+            const int q = m0 + lane;
+            const bool same = q < m && s_k[q] == ki;
+            const int xq = q < m ? s_x[q] : 0;
+            total += __popcll(__ballot(same));
+            rank += __popcll(__ballot(same && xq < p));
         }
-        if (beaten) return;
-        slot = own;
+        int64_t slot;
+        if (fill0 + total <= a.S) {
+            slot = fill0 + rank;               // all of them append: distinct slots
+        } else if (a.eviction == RB_EVICT_FIFO) {
+            // insertion number fill0 + rank overwrites the oldest sample once the class is full; it is
+            // itself overwritten in this step if a class-mate comes a whole round of S later
+            const int64_t at = fill0 + rank;
+            if (at + a.S < fill0 + total) continue;
+            slot = at < a.S ? at : (aux0 + at - a.S) % a.S;
+        } else {
+            const bool reservoir = a.eviction == RB_EVICT_RESERVOIR;
+            // Insertions beyond the capacity overwrite a uniformly drawn slot (or, with reservoir
+            // sampling, are kept with probability S / offers).  This candidate is not stored if a
+            // later class-mate overwrites its slot.
+            int64_t own = fill0 + rank;
+            if (own >= a.S) {
+                const int64_t offers = aux0 + rank < INT32_MAX ? aux0 + rank : INT32_MAX;   // to the class, before this one
+                own = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)p, reservoir ? (uint64_t)offers + 1 : (uint64_t)a.S);
+                if (own >= a.S) continue;      // reservoir: not kept
+            }
+            // bitmap of the class-mates' positions: rank of a position = class-mates below it
+            uint32_t* cm = s_cm[wave];
+            uint16_t* cmpre = s_cmpre[wave];
+            cm[2 * lane] = 0u;
+            cm[2 * lane + 1] = 0u;
+            for (int m0 = 0; m0 < m; m0 += WAVE) {
+                const int q = m0 + lane;
+                if (q < m && s_k[q] == ki) atomicOr(&cm[s_x[q] >> 5], 1u << (s_x[q] & 31));
+            }
+            {
+                const int p0 = __popc(cm[2 * lane]), p1 = __popc(cm[2 * lane + 1]);
+                const int before = wave_scan_incl(p0 + p1) - (p0 + p1);
+                cmpre[2 * lane] = (uint16_t)before;
+                cmpre[2 * lane + 1] = (uint16_t)(before + p0);
+            }
+            // later class-mates are gathered WAVE at a time so that their draws are made with full wavefronts
+            uint16_t* pend = s_pend[wave];
+            int npend = 0;
+            bool beaten = false;
+            for (int m0 = 0; m0 < m + WAVE; m0 += WAVE) {
+                if (m0 < m) {
+                    const int q = m0 + lane;
+                    const int xq = q < m ? s_x[q] : 0;
+                    const bool later = q < m && s_k[q] == ki && xq > p;
+                    const uint64_t mask = __ballot(later);
+                    if (later) pend[npend + __popcll(mask & ((1ull << lane) - 1))] = (uint16_t)xq;
+                    npend += __popcll(mask);
+                }
+                if (npend >= WAVE || (m0 >= m && npend > 0)) {
+                    const int take = npend < WAVE ? npend : WAVE;
+                    const int xr = lane < take ? pend[lane] : 0;
+                    // the rival's insertion number decides whether it overwrites at all, and (reservoir) its odds
+                    const int rank_r = cmpre[xr >> 5] + __popc(cm[xr >> 5] & ((1u << (xr & 31)) - 1u));
+                    bool hit = false;
+                    if (lane < take && fill0 + rank_r >= a.S) {
+                        const int64_t offers = aux0 + rank_r < INT32_MAX ? aux0 + rank_r : INT32_MAX;
+                        hit = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)xr, reservoir ? (uint64_t)offers + 1 : (uint64_t)a.S) == own;
+                    }
+                    beaten |= __ballot(hit) != 0;
+                    const int rest = lane + take < npend ? pend[lane + take] : 0;    // at most WAVE - 1 left over
+                    if (lane + take < npend) pend[lane] = (uint16_t)rest;
+                    npend -= take;
+                }
+            }
+            if (beaten) continue;
+            slot = own;
+        }
+        const int64_t dst_row = (int64_t)ki * a.S + slot;
+        t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
+        if (tile == 0 && lane == 0) a.buf_y[dst_row] = ki;
     }
-    const int64_t dst_row = (int64_t)ki * a.S + slot;
-    t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-    if (tile == 0 && lane == 0) a.buf_y[dst_row] = ki;
 }
 
 constexpr int YPRE = 4;    // label loads per thread issued before anything else (covers b <= 1024)
@@ -1095,6 +1167,10 @@ struct rb_buffer {
     size_t off_fill[2], off_chunk[2], ws_bytes;
     // launch-shape knobs
     int opt_unroll, opt_nt, opt_rpb, opt_fuse;
+    // policy variant and its per-class state (two copies, like the fill counts)
+    int selection, eviction;
+    size_t off_aux[2];
+    int64_t updates;         // rb_update calls since the last rb_bind
 };
 
 namespace {
@@ -1141,9 +1217,9 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
 }
 
 template <bool NT>
-hipError_t launch_update(const UpdateArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
+hipError_t launch_update(const UpdateArgs& a, bool small, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (a.c <= WAVE) {
+    if (small) {
         switch (unroll) {
         case 1: rb_update_small_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
         case 2: rb_update_small_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
@@ -1257,7 +1333,10 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_fill[1] = off; off += fill_bytes;
     rb->off_chunk[0] = off; off += chunk_bytes;
     rb->off_chunk[1] = off; off += chunk_bytes;
+    rb->off_aux[0] = off; off += fill_bytes;
+    rb->off_aux[1] = off; off += fill_bytes;
     rb->ws_bytes = off;
+    rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
     rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1;
     *out = rb;
     return RB_OK;
@@ -1289,6 +1368,7 @@ int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* h
     rb->ws = static_cast<char*>(workspace);
     rb->stream = st;
     rb->cur = 0;
+    rb->updates = 0;
     rb->bound = true;
     return RB_OK;
 }
@@ -1297,6 +1377,17 @@ int rb_set_stream(rb_buffer* rb, void* hip_stream)
 {
     if (!rb) return RB_EINVAL;
     rb->stream = static_cast<hipStream_t>(hip_stream);
+    return RB_OK;
+}
+
+int rb_set_policy(rb_buffer* rb, int32_t selection, int32_t eviction)
+{
+    if (!rb) return RB_EINVAL;
+    if (selection != RB_SELECT_EXACT && selection != RB_SELECT_BERNOULLI) return RB_EINVAL;
+    if (eviction != RB_EVICT_UNIFORM && eviction != RB_EVICT_FIFO && eviction != RB_EVICT_RESERVOIR) return RB_EINVAL;
+    if (rb->updates != 0) return RB_ESTATE;      // the per-class state of one strategy means nothing to another
+    rb->selection = selection;
+    rb->eviction = eviction;
     return RB_OK;
 }
 
@@ -1309,8 +1400,18 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (!rb->bound) return RB_ESTATE;
     if (c == 0) return RB_OK;
 
-    const bool small = c <= WAVE;
-    const Shape sh = plan_shape(rb, c, small ? TPB : WAVE);
+    const bool variant = rb->selection != RB_SELECT_EXACT || rb->eviction != RB_EVICT_UNIFORM;
+    const bool small = c <= WAVE && !variant;
+    // Rows the grid is sized for.  The Bernoulli selection yields a random number of candidates
+    // (mean c, at most b); the movers loop over the work items, so any number is handled, and
+    // the grid only has to be large enough for the usual case.
+    int64_t rows = c;
+    if (rb->selection == RB_SELECT_BERNOULLI) {
+        int64_t slack = 16;
+        while (slack * slack < 36 * c) ++slack;          // about six standard deviations
+        rows = c + slack < b ? c + slack : b;
+    }
+    const Shape sh = plan_shape(rb, rows, small ? TPB : WAVE);
     UpdateArgs a;
     a.batch_x = static_cast<const vec16*>(batch_x);
     a.batch_y = batch_y;
@@ -1326,12 +1427,17 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.S = rb->S;
     a.row_vec = rb->row_vec;
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
-    const dim3 grid((unsigned)(rb->nchunks + (small ? sh.groups * sh.tpr : (c * sh.tpr + NWAVE - 1) / NWAVE)));
-    const size_t lds = small ? (size_t)b * 8 : (size_t)b * 4 + (size_t)c * 8;
-    hipError_t e = rb->opt_nt ? launch_update<true>(a, sh.unroll, grid, lds, rb->stream)
-                              : launch_update<false>(a, sh.unroll, grid, lds, rb->stream);
+    a.selection = rb->selection; a.eviction = rb->eviction;
+    a.cap = (int32_t)(rb->selection == RB_SELECT_BERNOULLI ? b : c);
+    a.aux_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_aux[rb->cur]);
+    a.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
+    const dim3 grid((unsigned)(rb->nchunks + (small ? sh.groups * sh.tpr : (rows * sh.tpr + NWAVE - 1) / NWAVE)));
+    const size_t lds = small ? (size_t)b * 8 : (size_t)b * 4 + (size_t)a.cap * 8;
+    hipError_t e = rb->opt_nt ? launch_update<true>(a, small, sh.unroll, grid, lds, rb->stream)
+                              : launch_update<false>(a, small, sh.unroll, grid, lds, rb->stream);
     if (e != hipSuccess) return RB_EHIP;
     rb->cur ^= 1;
+    rb->updates += 1;
     return RB_OK;
 }
 
@@ -1374,7 +1480,8 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
     if (!rb->bound) return RB_ESTATE;
 
-    const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse;
+    const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
+                       rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
     if (!fused) {
         const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);
         if (rc != RB_OK) return rc;
@@ -1397,6 +1504,8 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.S = rb->S;
     a.row_vec = rb->row_vec;
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = 1;
+    a.selection = RB_SELECT_EXACT; a.eviction = RB_EVICT_UNIFORM; a.cap = (int32_t)c;
+    a.aux_old = nullptr; a.aux_new = nullptr;
     sa.out_x = static_cast<vec16*>(out_x);
     sa.out_y = out_y;
     sa.r = (int32_t)r;
@@ -1407,6 +1516,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
                               : launch_step<false>(sa, sh.unroll, grid, lds, rb->stream);
     if (e != hipSuccess) return RB_EHIP;
     rb->cur ^= 1;
+    rb->updates += 1;
     return RB_OK;
 }
 

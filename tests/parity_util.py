@@ -57,10 +57,12 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
 
 
 def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
-               first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False):
+               first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False,
+               policy=None):
     """Runs `steps` update+sample steps of workload `w` on both sides.
 
     single_call: drive the HIP side through rb_update_sample instead of the two calls.
+    policy: (selection, eviction) variant codes, set on both sides (the codes are the same numbers).
     Every step: out_y equal, the n sampled rows byte-equal, rows >= n untouched.
     At the end (and every `check_state_every` steps): fill, flags, buf_y and all
     filled buf_x rows.  Returns (buf, orc) for further checks.
@@ -75,6 +77,9 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
         orc = rbo.Buffer(w.K, w.S, w.row_bytes)
         for opt, val in options:
             buf.set_option(opt, val)
+        if policy is not None:
+            buf.set_policy(*policy)
+            orc.set_policy(*policy)
     aug_x = torch.empty((w.b + w.r, *w.shape), dtype=w.torch_dtype, device=dev)
     aug_y = torch.empty(w.b + w.r, dtype=torch.int64, device=dev)
     for step in range(first_step, first_step + steps):

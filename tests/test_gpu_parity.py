@@ -79,6 +79,43 @@ def test_single_call_equals_two_calls_without_fusion():
     run_parity(w, steps=40, options=((rb.RB_OPT_FUSE, 0),), single_call=True)
 
 
+# ------------------------------------- policy variants of Algorithm 1 (NEXT-1) ---
+
+POLICIES = {"bernoulli-uniform": (1, 0), "exact-fifo": (0, 1), "exact-reservoir": (0, 2), "bernoulli-fifo": (1, 1),
+            "bernoulli-reservoir": (1, 2)}
+
+
+@pytest.mark.parametrize("policy", sorted(POLICIES))
+@pytest.mark.parametrize("w,steps", [
+    (wl.C1, 100),                                                                  # fills up: every strategy replaces
+    (wl.variant(wl.C2, name="C2-S3-policy", S=3), 120),
+    (wl.variant(wl.C4, name="C4-S8-policy", S=8, shape=(3, 32, 32)), 60),          # Zipf head: many class-mates per step
+    (wl.variant(wl.C5, name="C5-S16-K200-policy", K=200, S=16, shape=(64,)), 25),  # ~20 candidates per class and step into 16 slots
+    (wl.Workload("laps", 9, 3, 2, (8,), "f32", 4096, 4096, 64, 6, "normal", "uniform"), 6),   # ~1365 candidates per class into 2 slots
+    (wl.Workload("one-class", 9, 1, 5000, (8,), "bf16", 4096, 2000, 4096, 8, "normal", "uniform"), 8),
+], ids=["C1", "C2-S3", "C4-S8", "C5-S16", "laps", "one-class"])
+def test_policy_variants(policy, w, steps):
+    run_parity(w, steps=steps, check_state_every=max(1, steps // 3), policy=POLICIES[policy])
+
+
+def test_policy_variant_through_the_single_call_and_at_full_size():
+    run_parity(wl.C4, steps=30, policy=POLICIES["bernoulli-fifo"], single_call=True, progress=10)
+
+
+def test_policy_cannot_change_after_an_update():
+    rb = _rb()
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype)
+    assert rb.rb_set_policy(buf.handle, 2, 0) == rb.RB_EINVAL
+    assert rb.rb_set_policy(buf.handle, 0, 3) == rb.RB_EINVAL
+    assert rb.rb_set_policy(buf.handle, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_FIFO) == rb.RB_OK
+    x, y = wl.make_batch(w, 0, "cuda:0")
+    buf.update(x, y, w.c, 0, 0)
+    assert rb.rb_set_policy(buf.handle, 0, 0) == rb.RB_ESTATE
+    assert rb.rb_bind(buf.handle, buf.buf_x, buf.buf_y, buf.workspace, None) == rb.RB_OK
+    assert rb.rb_set_policy(buf.handle, 0, 0) == rb.RB_OK
+
+
 # ------------------------------------------- stress variants (replace path) ---
 
 @pytest.mark.parametrize("w,steps", [
