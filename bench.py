@@ -259,6 +259,23 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     return rig, res
 
 
+def variants_leg(w, torch, rb, wl, steps):
+    """The policy variants of Algorithm 1 on the same workload (general kernels, two launches per step)."""
+    out = {}
+    names = {(1, 0): "bernoulli+uniform", (0, 1): "exact+fifo", (0, 2): "exact+reservoir", (1, 1): "bernoulli+fifo"}
+    for (sel, ev), name in names.items():
+        rig = Rig(w, torch, rb, wl)
+        rig.buf.set_policy(sel, ev)
+        rig.prefill()                       # every slot filled, so that every insertion exercises the eviction strategy
+        rig.enqueue(100, single_call=True)
+        torch.cuda.synchronize()
+        ms = rig.timed(steps, single_call=True)
+        out[name] = {"ms_per_step": round(ms, 5), "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1),
+                     "gb_per_s_nominal": round(w.bytes_per_step() / (ms * 1e-3) / 1e9, 1), "prefilled": True}
+        rig.close()
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -269,6 +286,7 @@ def main():
     ap.add_argument("--others", default="C3,C5,C2,C1", help="comma list of further workloads reported inside the line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
+    ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
@@ -321,6 +339,10 @@ def main():
         others[ow.name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in ores.items()}
         log(f"[bench] {json.dumps(others[ow.name])}")
 
+    variants = None if a.no_variants else variants_leg(w, torch, rb, wl, min(a.steps, 500))
+    if variants:
+        log(f"[bench] variants {json.dumps(variants)}")
+
     # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
     # (rb_step_small_kernel: every inserted row and every representative row read once and written
     # once) and its duration is ms_per_step; otherwise it is the gather of rb_sample_augment.
@@ -349,6 +371,7 @@ def main():
         "detail": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()},
         "prefilled": None if pre is None else {k: (round(v, 5) if isinstance(v, float) else v) for k, v in pre.items()},
         "others": others,
+        "policy_variants": variants,
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, wl)
