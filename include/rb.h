@@ -86,11 +86,11 @@ int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *h
 
 /*
  * Policy variants of Algorithm 1.  The defaults are what Algorithm 1 prints.
- * Selection: RB_SELECT_EXACT - "select c random candidates": a uniform subset
- * of exactly c positions; RB_SELECT_BERNOULLI - the text of Sec. IV-B, "every
- * sample of m_n has a c/b probability to be pushed": an independent coin of
- * probability c/b per sample (any number of candidates from 0 to b).
- * Eviction (Sec. IV-A: "at random or using a different strategy"):
+ * Selection: RB_SELECT_EXACT - the first step of Algorithm 1, a uniform subset
+ * of exactly c positions; RB_SELECT_BERNOULLI - the wording of Sec. IV-B, where
+ * each sample of the mini-batch is inserted with probability c/b: an independent
+ * coin per sample (any number of candidates from 0 to b).
+ * Eviction (Sec. IV-A allows strategies other than random replacement):
  * RB_EVICT_UNIFORM - overwrite a uniformly drawn slot of the class;
  * RB_EVICT_FIFO - overwrite the oldest sample of the class;
  * RB_EVICT_RESERVOIR - reservoir sampling per class: the n-th sample ever
@@ -128,8 +128,8 @@ int rb_update(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
               int64_t b, int64_t c, uint64_t seed, uint64_t step);
 
 /*
- * Mini-batch augmentation (Sec. IV-C; the `r = update(m); concat(m, r)` of
- * Listing 1): draw n = min(r, F) representatives uniformly without
+ * Mini-batch augmentation (Sec. IV-C; what the training loop of Listing 1
+ * concatenates to the mini-batch): draw n = min(r, F) representatives uniformly without
  * replacement from the F samples currently stored (every stored sample equally
  * likely, whatever its class) and copy sample j to row j of out_x and its
  * label to out_y[j]; out_y[j] = -1 for n <= j < r and those out_x rows are not
@@ -143,8 +143,8 @@ int rb_sample_augment(rb_buffer *rb, int64_t r, uint64_t seed, uint64_t step,
                       void *out_x, int64_t *out_y);
 
 /*
- * The paper's single primitive (Listing 1, `r = RehearsalBuffer.update(m)`;
- * Sec. IV-D step 2: update the buffer with the mini-batch, then sample the next
+ * The paper's single primitive (the update call of Listing 1; Sec. IV-D
+ * step 2: update the buffer with the mini-batch, then sample the next
  * representatives): rb_update(rb, batch_x, batch_y, b, c, seed, step) followed
  * by rb_sample_augment(rb, r, seed, step, out_x, out_y), as one call with the
  * same arguments, meaning, errors and, bit for bit, the same results.  When

@@ -41,10 +41,10 @@
 #define RBO_COIN   4u   /* purpose tag of the per-sample coin of the Bernoulli selection */
 
 /* Policy variants (the default pair is what Algorithm 1 prints).
- * Selection: EXACT  - "select c random candidates": a uniform subset of exactly c positions;
- *            BERNOULLI - the text's "every sample of m_n has a c/b probability to be pushed":
+ * Selection: EXACT  - first step of Algorithm 1: a uniform subset of exactly c positions;
+ *            BERNOULLI - the wording of Sec. IV-B (each sample is inserted with probability c/b):
  *                        an independent coin of probability c/b per sample.
- * Eviction ("replace old representatives ... at random or using a different strategy", Sec. IV-A):
+ * Eviction (Sec. IV-A allows strategies other than random replacement of old representatives):
  *            UNIFORM   - overwrite a uniformly drawn slot of the class;
  *            FIFO      - overwrite the oldest representative of the class;
  *            RESERVOIR - reservoir sampling per class (Vitter's Algorithm R): the n-th sample ever
@@ -206,17 +206,17 @@ int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
     if (!cand) return -1;
     int64_t ncand;
     if (rb->selection == RBO_SELECT_BERNOULLI) {
-        /* "Every sample of m_n has a c/b probability to be pushed": one coin per position,
-         * heads iff a uniform integer below b is below c. */
+        /* Sec. IV-B wording: each sample is a candidate with probability c/b.  One coin per
+         * position, heads iff a uniform integer below b is below c. */
         ncand = 0;
         for (int64_t pos = 0; pos < b; ++pos)
             if ((int64_t)rbo_bounded(seed, step, RBO_COIN, (uint32_t)pos, (uint64_t)b) < c) cand[ncand++] = pos;
     } else {
-        /* "C <- select c random candidates from mini-batch m": a uniform c-subset
-         * of the b positions. */
+        /* Algorithm 1, first step (choose c candidates of the mini-batch at random): a
+         * uniform c-subset of the b positions. */
         rbo_floyd(seed, step, RBO_SELECT, b, c, cand);
         ncand = c;
-        /* "for c in C": visited in ascending mini-batch position. */
+        /* Algorithm 1, loop over the candidates: visited in ascending mini-batch position. */
         qsort(cand, (size_t)c, sizeof(int64_t), cmp_i64);
     }
 
@@ -229,7 +229,7 @@ int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
         int64_t offered = rb->seen[k];          /* samples offered to class k before this one */
         if (rb->seen[k] < INT32_MAX) rb->seen[k] += 1;
         if (rb->fill[k] < rb->S) {
-            /* "append c to R^i_n" */
+            /* Algorithm 1, else-branch: the class still has room, the candidate is appended */
             s = rb->fill[k];
             rb->fill[k] += 1;
         } else if (rb->eviction == RBO_EVICT_FIFO) {
@@ -241,8 +241,8 @@ int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
             s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)offered + 1);
             if (s >= rb->S) continue;
         } else {
-            /* "replace a random representative from R^i_n": every slot of the
-             * class equally likely, whatever its age. */
+            /* Algorithm 1, if-branch: the class is full, a random representative is replaced:
+             * every slot of the class equally likely, whatever its age. */
             s = (int64_t)rbo_bounded(seed, step, RBO_EVICT, (uint32_t)pos, (uint64_t)rb->S);
         }
         size_t slot = (size_t)k * (size_t)rb->S + (size_t)s;

@@ -165,7 +165,7 @@ def test_argument_validation():
 
 def test_replacement_is_uniform_over_the_slots():
     # A full class receiving one candidate per step: the replaced slot is uniform on [0, S),
-    # "regardless of whether it is a recent or old sample" (Sec. IV-B).
+    # whatever the age of the sample it holds (Sec. IV-B: recent and old samples are replaced alike).
     S, steps = 20, 20000
     buf = rbo.Buffer(1, S, 16)
     x = np.zeros((S, 16), dtype=np.uint8)
@@ -259,7 +259,7 @@ def test_sampling_subsets_are_uniform_over_stored_samples():
 
 
 def test_inclusion_probability_of_a_stored_sample():
-    # Every stored sample has "an equal opportunity" (Sec. IV-C): probability r/F per draw.
+    # Every stored sample is equally likely to be drawn (Sec. IV-C, fair sampling): probability r/F per draw.
     w = wl.C1
     buf = rbo.Buffer(w.K, w.S, w.row_bytes)
     for step in range(w.steps):

@@ -122,7 +122,7 @@ def test_floyd_subsets_are_uniform():
 
 @pytest.mark.parametrize("b,c", [(16, 4), (128, 16)])
 def test_floyd_marginal_inclusion_probability(b, c):
-    # "Every sample of m_n has a c/b probability to be pushed" (Sec. IV-B).
+    # Each sample of the mini-batch is inserted with probability c/b (Sec. IV-B).
     trials = 20000
     hits = np.zeros(b, dtype=np.int64)
     for step in range(trials):

@@ -1,6 +1,6 @@
 """Pins of the oracle's policy variants (CPU only): Bernoulli(c/b) candidate selection
-(Sec. IV-B) and the alternative replacement strategies (Sec. IV-A: "at random or using a
-different strategy"): first-in-first-out and per-class reservoir sampling."""
+(Sec. IV-B) and replacement strategies other than the random one, which Sec. IV-A allows:
+first-in-first-out and per-class reservoir sampling."""
 import numpy as np
 import pytest
 from scipy import stats
