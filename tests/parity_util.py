@@ -11,7 +11,10 @@ SENTINEL = 0x5A
 
 def _bytes(t):
     """uint8 view [rows, row_bytes] of a contiguous sample tensor (stays on its device)."""
-    return t.view(torch.uint8).reshape(t.shape[0], -1)
+    row_bytes = t.element_size()
+    for d in t.shape[1:]:
+        row_bytes *= d
+    return t.view(torch.uint8).reshape(t.shape[0], row_bytes)
 
 
 def compare_state(buf, orc, tag):

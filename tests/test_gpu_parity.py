@@ -146,6 +146,37 @@ def test_rows_per_block(rpb):
     run_parity(w, options=((rb.RB_OPT_ROWS_PER_BLOCK, rpb),))
 
 
+# ------------------------------------------------------ random configurations ---
+
+def _random_workload(rng, i):
+    big = rng.random() < 0.3                                  # sometimes large counts (general kernels)
+    b = int(rng.integers(1, 4097 if big else 200))
+    c = int(rng.integers(0, b + 1)) if rng.random() < 0.7 else int(min(b, rng.integers(0, 65)))
+    r = int(rng.integers(0, 4097 if big else 130))
+    K = int(rng.choice([1, 2, 7, 100, 1000, 1024, 1025, 3000, 20000]))
+    S = int(rng.choice([1, 2, 3, 10, 60]))
+    vecs = int(rng.choice([1, 2, 63, 64, 65, 255, 256, 257, 1000, 2049]))   # 16-byte vectors per row
+    dtype = "f32" if rng.random() < 0.5 else "bf16"
+    shape = (vecs * (4 if dtype == "f32" else 8),)
+    labels = str(rng.choice(["uniform", "zipf", "active50"]))
+    return wl.Workload(f"rand{i}-K{K}-S{S}-b{b}-c{c}-r{r}-v{vecs}", 9, K, S, shape, dtype, b, c, r, 6, "normal", labels)
+
+
+@pytest.mark.parametrize("chunk", range(6))
+def test_random_configurations(chunk):
+    """Seeded random shapes, counts, policies, launch options and call styles, a few steps each."""
+    rb = _rb()
+    rng = np.random.default_rng(1000 + chunk)
+    for i in range(12):
+        w = _random_workload(rng, chunk * 100 + i)
+        policy = (int(rng.integers(0, 2)), int(rng.integers(0, 3))) if rng.random() < 0.5 else None
+        options = ((rb.RB_OPT_UNROLL, int(rng.choice([0, 1, 2, 4, 8]))), (rb.RB_OPT_NONTEMPORAL, int(rng.integers(0, 2))),
+                   (rb.RB_OPT_ROWS_PER_BLOCK, int(rng.choice([0, 1, 3, 16]))), (rb.RB_OPT_FUSE, int(rng.integers(0, 2))))
+        single = bool(rng.integers(0, 2))
+        print(f"  {w.name} policy={policy} options={[v for _, v in options]} single_call={single}", flush=True)
+        run_parity(w, steps=6, check_state_every=3, policy=policy, options=options, single_call=single)
+
+
 # ------------------------------------------------------------- edge cases ---
 
 @pytest.mark.parametrize("K,S,shape,dtype,b,c,r", [
