@@ -36,11 +36,12 @@ def log(*a):
 class Rig:
     """Device-side state of one workload: the buffer, a side stream and a rotating pool of augmented batches."""
 
-    def __init__(self, w, torch, rb, wl, pool_slots=None):
+    def __init__(self, w, torch, rb, wl, pool_slots=None, storage="hbm"):
         self.w, self.torch, self.rb = w, torch, rb
         self.dev = torch.device("cuda:0")
         self.stream = torch.cuda.Stream(self.dev)
-        self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream)
+        self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream,
+                                      storage=storage)
         aug_bytes = (w.b + w.r) * w.row_bytes
         self.P = pool_slots or min(1024, max(8, -(-POOL_BYTES // aug_bytes)))
         self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
@@ -259,6 +260,19 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     return rig, res
 
 
+def host_pinned_leg(torch, rb, wl, steps=200):
+    """Where the paper keeps its buffers (Sec. IV-C): sample rows in pinned host memory, moved by the same
+    kernels over the host link.  Workload C3 with 4 slots per class (2.4 GB of pinned rows)."""
+    w = wl.variant(wl.C3, name="C3-rows-in-pinned-host-memory-S4", S=4)
+    rig = Rig(w, torch, rb, wl, storage="host_pinned")
+    rig.enqueue(50, single_call=True)
+    torch.cuda.synchronize()
+    ms = rig.timed(steps, single_call=True)
+    rig.close()
+    return {"workload": w.name, "ms_per_step": round(ms, 5), "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1),
+            "host_link_gb_per_s": round((w.c + w.r) * w.row_bytes / (ms * 1e-3) / 1e9, 2)}
+
+
 def variants_leg(w, torch, rb, wl, steps):
     """The policy variants of Algorithm 1 on the same workload (general kernels, two launches per step)."""
     out = {}
@@ -342,6 +356,9 @@ def main():
     variants = None if a.no_variants else variants_leg(w, torch, rb, wl, min(a.steps, 500))
     if variants:
         log(f"[bench] variants {json.dumps(variants)}")
+    pinned = None if a.no_variants else host_pinned_leg(torch, rb, wl)
+    if pinned:
+        log(f"[bench] host-pinned {json.dumps(pinned)}")
 
     # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
     # (rb_step_small_kernel: every inserted row and every representative row read once and written
@@ -372,6 +389,7 @@ def main():
         "prefilled": None if pre is None else {k: (round(v, 5) if isinstance(v, float) else v) for k, v in pre.items()},
         "others": others,
         "policy_variants": variants,
+        "host_pinned_rows": pinned,
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, wl)

@@ -160,7 +160,11 @@ class RehearsalBuffer:
     handle, raises RbError on a non-zero status.  All work is done by the library.
     """
 
-    def __init__(self, classes, slots_per_class, sample_shape, dtype=torch.float32, device="cuda:0", stream=None):
+    def __init__(self, classes, slots_per_class, sample_shape, dtype=torch.float32, device="cuda:0", stream=None,
+                 storage="hbm"):
+        """storage: "hbm" keeps the sample rows in device memory; "host_pinned" keeps them in pinned host
+        memory that the kernels read and write directly over the host link (where the paper keeps its
+        buffers, Sec. IV-C); labels and workspace stay on the device either way."""
         code = {torch.float32: RB_F32, torch.bfloat16: RB_BF16}[dtype]
         rc, self.handle = rb_create(classes, slots_per_class, tuple(sample_shape), code)
         _check(rc, "rb_create")
@@ -169,7 +173,13 @@ class RehearsalBuffer:
         _check(rc, "rb_query_sizes")
         self.row_bytes = xb // (self.K * self.S)
         self.device = torch.device(device)
-        self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, device=self.device)
+        if storage == "hbm":
+            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, device=self.device)
+        elif storage == "host_pinned":
+            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, pin_memory=True)
+        else:
+            raise ValueError(storage)
+        self.storage = storage
         self.buf_y = torch.empty((self.K, self.S), dtype=torch.int64, device=self.device)
         self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
         assert self.buf_x.numel() * self.buf_x.element_size() == xb and self.buf_y.numel() * 8 == yb

@@ -39,7 +39,7 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
             return
         host = np.concatenate([orc.export_rows(first, n) for first, n in pending])
         idx = torch.cat([torch.arange(first, first + n) for first, n in pending]).to(bx.device)
-        want = torch.from_numpy(host).to(bx.device)
+        want = torch.from_numpy(host).to(bx.device)   # bx is on the device, or in pinned host memory
         got = bx.index_select(0, idx)
         if not torch.equal(got, want):
             bad = (got != want).any(dim=1).nonzero().flatten()[:5].tolist()
@@ -61,7 +61,7 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
 
 def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
                first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False,
-               policy=None):
+               policy=None, storage="hbm"):
     """Runs `steps` update+sample steps of workload `w` on both sides.
 
     single_call: drive the HIP side through rb_update_sample instead of the two calls.
@@ -76,7 +76,7 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     dev = torch.device(device)
     own = buf is None
     if own:
-        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream)
+        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream, storage=storage)
         orc = rbo.Buffer(w.K, w.S, w.row_bytes)
         for opt, val in options:
             buf.set_option(opt, val)

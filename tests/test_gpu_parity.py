@@ -146,6 +146,17 @@ def test_rows_per_block(rpb):
     run_parity(w, options=((rb.RB_OPT_ROWS_PER_BLOCK, rpb),))
 
 
+# ------------------------------------------ buffer rows in pinned host memory ---
+
+@pytest.mark.parametrize("single", [False, True])
+def test_rows_in_pinned_host_memory(single):
+    """The paper keeps the buffers in pinned host memory; the same kernels run on such storage."""
+    w = wl.variant(wl.C3, name="C3-host-pinned", K=40, S=5, shape=(3, 64, 64))        # 9.8 MB of pinned rows
+    run_parity(w, steps=40, storage="host_pinned", single_call=single, check_state_every=10)
+    w = wl.variant(wl.C5, name="C5-host-pinned", K=300, S=8, shape=(256,), b=512, c=200, r=150)
+    run_parity(w, steps=10, storage="host_pinned", single_call=single)
+
+
 # ------------------------------------------------------ random configurations ---
 
 def _random_workload(rng, i):
