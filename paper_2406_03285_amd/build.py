@@ -1,4 +1,4 @@
-"""Compile the HIP library (csrc/rb.hip -> librb.so, gfx950 only) in-tree with hipcc."""
+"""Compile the HIP library (csrc/rb.hip and the headers it includes -> librb.so, gfx950 only) in-tree with hipcc."""
 import os
 import subprocess
 

@@ -1,0 +1,222 @@
+// Device-side building blocks of the rehearsal-buffer kernels (gfx950): constants, counter-based
+// random draws, wavefront and workgroup primitives, the row mover and the launch-argument structs.
+// Included by rb.hip only.
+#pragma once
+
+#include <hip/hip_runtime.h>
+
+#include <cstdint>
+
+#include "rb.h"
+
+namespace {
+
+constexpr int TPB = 256;               // threads per workgroup: four 64-wide wavefronts
+constexpr int WAVE = 64;
+constexpr int NWAVE = TPB / WAVE;
+constexpr int CH = 256;                // classes per chunk of the two-level fill index
+constexpr int TILE_UNIT = 64;          // granularity, in 16-byte vectors, at which a row is cut into tiles
+constexpr uint32_t PURPOSE_SELECT = 1; // counter word that separates the three kinds of draws
+constexpr uint32_t PURPOSE_EVICT = 2;
+constexpr uint32_t PURPOSE_SAMPLE = 3;
+constexpr uint32_t PURPOSE_COIN = 4;   // per-sample coin of the Bernoulli selection
+constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a candidate
+constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
+
+typedef uint32_t vec16 __attribute__((ext_vector_type(4)));   // one 16-byte transfer
+
+// Device-resident state words at the start of the workspace.
+struct DevState {
+    uint32_t flags;
+    uint32_t pad;
+    int64_t last_n;
+};
+constexpr size_t STATE_BYTES = 256;
+
+struct Seed {
+    uint32_t seed_lo, seed_hi, step_lo, step_hi;
+};
+
+// ---------------------------------------------------------------------------
+// Counter-based random draws: Philox4x32-10 (Salmon et al., SC'11).  Counter =
+// (index, purpose, step), key = seed; the low two output words form one 64-bit
+// draw.  An integer in [0, n) is the high half of draw * n.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint64_t draw64(const Seed& sd, uint32_t purpose, uint32_t index)
+{
+    uint32_t x0 = index, x1 = purpose, x2 = sd.step_lo, x3 = sd.step_hi;
+    uint32_t ka = sd.seed_lo, kb = sd.seed_hi;
+#pragma unroll
+    for (int i = 0; i < 10; ++i) {
+        // one 32x32->64 multiply per word pair (v_mad_u64_u32) instead of separate high and low halves
+        const uint64_t pa = (uint64_t)0xD2511F53u * x0;
+        const uint64_t pb = (uint64_t)0xCD9E8D57u * x2;
+        x0 = (uint32_t)(pb >> 32) ^ x1 ^ ka;
+        x2 = (uint32_t)(pa >> 32) ^ x3 ^ kb;
+        x1 = (uint32_t)pb;
+        x3 = (uint32_t)pa;
+        ka += 0x9E3779B9u;
+        kb += 0xBB67AE85u;
+    }
+    return (uint64_t)x0 | ((uint64_t)x1 << 32);
+}
+
+__device__ __forceinline__ uint64_t below(const Seed& sd, uint32_t purpose, uint32_t index, uint64_t n)
+{
+    return __umul64hi(draw64(sd, purpose, index), n);
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront-level pieces of the small-count kernels (at most WAVE candidates or
+// representatives: one lane per item, all 64 lanes of the wavefront active).
+// ---------------------------------------------------------------------------
+// Inclusive prefix sum over the 64 lanes with data-parallel-primitive moves (no LDS round
+// trips): Hillis-Steele steps of 1, 2, 4, 8 lanes inside each row of 16 lanes, then the last
+// lane of row 0 / row 2 is added to row 1 / row 3, then lane 31 to rows 2 and 3.
+__device__ __forceinline__ int wave_scan_incl(int v)
+{
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xf, 0xf, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xf, 0xf, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xf, 0xf, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xf, 0xf, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xa, 0xf, false);   // row_bcast:15 into rows 1 and 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xc, 0xf, false);   // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// Value of `v` in lane `src`, the same lane for the whole wavefront.
+__device__ __forceinline__ int lane_read(int v, int src)
+{
+    return __builtin_amdgcn_readlane(v, src);
+}
+
+// ---------------------------------------------------------------------------
+// Workgroup-wide exclusive prefix sum of one int per thread.  s_wave: NWAVE
+// ints of LDS.  Must be called by all threads of the workgroup.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
+{
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    const int inc = wave_scan_incl(v);
+    if (lane == WAVE - 1) s_wave[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < NWAVE; ++i) {
+        int x = s_wave[i];
+        all += x;
+        if (i < w) before += x;
+    }
+    __syncthreads();
+    total = all;
+    return before + inc - v;
+}
+
+// ---------------------------------------------------------------------------
+// Row mover: one tile of one row, U vectors per thread in flight.
+// ---------------------------------------------------------------------------
+template <int U, bool NT, int W = TPB, bool PACED = true>   // W: threads that share the tile (a workgroup or one wavefront)
+struct Tile {
+    vec16 v[U];
+
+    // Requires lo < hi.  No lane is ever masked off: a lane whose index falls past the end of
+    // the tile moves the tile's last vector again (same source, same destination, same bytes as
+    // the lane that owns it), so the copy stays correct and branch-free.  That keeps the number
+    // of loads in flight known at compile time - a wait for an earlier load then does not have
+    // to drain these - and keeps the compiler from moving loads down into a guarded store.
+    __device__ __forceinline__ void load(const vec16* __restrict__ src, int64_t lo, int64_t hi)
+    {
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+            i = i < hi ? i : hi - 1;
+            v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+        }
+    }
+    // All loads are waited for first and every store is waited for before the next one is
+    // issued.  Measured on MI355X with a bare mover of the same shape (64 rows of 301 056 bytes,
+    // U = 4): 7.6 us against 8.6 us when each store is issued as soon as its load has arrived
+    // and 8.9 us with the guarded form; the memory system does better with few writes in flight.
+    __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
+    {
+        if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+#pragma unroll
+        for (int u = 0; u < U; ++u) {
+            int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+            i = i < hi ? i : hi - 1;
+            if (NT) __builtin_nontemporal_store(v[u], dst + i);
+            else dst[i] = v[u];
+            if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        }
+    }
+};
+
+// Vector range [lo, hi) of tile `tile` of a row of row_vec vectors.  The row is cut into units of
+// TILE_UNIT vectors (1 KiB: what one wavefront moves per instruction, so that a wavefront's access
+// does not straddle two such blocks of a 1 KiB-aligned row) and the units are dealt evenly: the
+// first `rem` tiles get `units + 1`, the others `units` (>= 1).  Tiles are never empty and never
+// longer than W * U vectors for the tile width W the host planned for.
+__device__ __forceinline__ void tile_bounds(int tile, int units, int rem, int64_t row_vec, int64_t& lo, int64_t& hi)
+{
+    const int64_t ulo = (int64_t)tile * units + (tile < rem ? tile : rem);
+    const int64_t uhi = ulo + units + (tile < rem ? 1 : 0);
+    lo = ulo * TILE_UNIT;
+    hi = uhi * TILE_UNIT < row_vec ? uhi * TILE_UNIT : row_vec;
+}
+
+// ---------------------------------------------------------------------------
+// Launch arguments
+// ---------------------------------------------------------------------------
+struct UpdateArgs {
+    const vec16* batch_x;
+    const int64_t* batch_y;
+    vec16* buf_x;
+    int64_t* buf_y;
+    const int32_t* fill_old;
+    int32_t* fill_new;
+    int32_t* chunk_new;
+    DevState* state;
+    Seed sd;
+    int32_t b, c;
+    int32_t K, nchunks;
+    int64_t S;
+    int64_t row_vec;      // 16-byte vectors per row
+    int32_t tpr;          // tiles per row
+    int32_t tile_vec;     // a row is split evenly into tpr tiles in units of TILE_UNIT vectors: the first
+    int32_t tile_rem;     // tile_rem tiles hold tile_vec + 1 units, the others tile_vec; see tile_bounds
+    int32_t rpb;          // small kernels: rows per mover workgroup (1 unless tpr == 1)
+    // policy variants (general kernel only)
+    int32_t selection;    // RB_SELECT_*
+    int32_t eviction;     // RB_EVICT_*
+    int32_t cap;          // most candidates a step can have: c (exact selection) or b (Bernoulli)
+    const int32_t* aux_old;   // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
+    int32_t* aux_new;
+};
+
+struct SampleArgs {
+    const vec16* buf_x;
+    vec16* out_x;
+    int64_t* out_y;
+    const int32_t* fill;
+    const int32_t* chunk;
+    DevState* state;
+    Seed sd;
+    int32_t r;
+    int32_t K, nchunks;
+    int64_t S;
+    int64_t row_vec;
+    int32_t tpr;
+    int32_t tile_vec;
+    int32_t tile_rem;
+    int32_t rpb;          // small kernel: rows per workgroup (1 unless tpr == 1)
+};
+
+struct StepArgs {
+    UpdateArgs u;
+    vec16* out_x;
+    int64_t* out_y;
+    int32_t r;
+    int32_t first_gather;   // index of the first representative mover (the candidate movers come before)
+};
+
+}  // namespace
