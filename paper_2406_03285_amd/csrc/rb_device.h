@@ -164,6 +164,22 @@ __device__ __forceinline__ void tile_bounds(int tile, int units, int rem, int64_
     hi = uhi * TILE_UNIT < row_vec ? uhi * TILE_UNIT : row_vec;
 }
 
+// Work item -> (row, tile of the row), tpr tiles per row.  The common cases avoid the 64-bit division.
+__device__ __forceinline__ void split_item(int64_t item, int tpr, int& row, int& tile)
+{
+    if (tpr == 1) {
+        row = (int)item;
+        tile = 0;
+    } else if (item <= 0x7FFFFFFF) {
+        const uint32_t it = (uint32_t)item;
+        row = (int)(it / (uint32_t)tpr);
+        tile = (int)(it - (uint32_t)row * (uint32_t)tpr);
+    } else {
+        row = (int)(item / tpr);
+        tile = (int)(item % tpr);
+    }
+}
+
 // ---------------------------------------------------------------------------
 // Launch arguments
 // ---------------------------------------------------------------------------

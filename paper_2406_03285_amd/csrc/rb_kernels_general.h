@@ -26,9 +26,11 @@ __global__ void __launch_bounds__(TPB) rb_reset_kernel(uint32_t* __restrict__ ws
 // takes one work item (candidate row, tile of WAVE * U vectors) and works out
 // alone, with ballots over the candidate list, where that candidate goes.
 //
-// LDS (dynamic): s_first[b] u32 (lowest candidate index that drew a value),
-// s_k[c] i32 (class per candidate, LAB_INVALID outside [0, K)), s_t[c] u16
-// (Floyd draws), s_x[c] u16 (candidate positions in Floyd emission order).
+// LDS (dynamic): s_first[b] u32 (lowest candidate index that drew a value;
+// with the Bernoulli selection: the class of every position whose coin came up heads),
+// s_k[cap] i32 (class per candidate, LAB_INVALID outside [0, K)), s_t[cap] u16
+// (Floyd draws), s_x[cap] u16 (candidate positions, Floyd emission order or,
+// with the Bernoulli selection, mini-batch order); cap = c, or b for Bernoulli.
 //
 // Grid: `nchunks` bookkeeping workgroups (new fill counts and chunk sums for CH
 // classes each), then ceil(c * tpr / NWAVE) mover workgroups.
@@ -54,25 +56,36 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 
     if (a.selection == RB_SELECT_BERNOULLI) {
         // ---- one coin per sample, heads with probability c/b; candidates in mini-batch order ----
-        const int per = (b + TPB - 1) / TPB;
-        const int q_lo = tid * per;
-        int mine = 0;
-        for (int u = 0; u < per; ++u) {
-            const int q = q_lo + u;
-            if (q < b && (int64_t)below(a.sd, PURPOSE_COIN, (uint32_t)q, (uint64_t)b) < c) {
-                s_first[q] = 1u;
-                ++mine;
-            } else if (q < b) {
-                s_first[q] = 0u;
-            }
+        // s_lab[q] = class of sample q if its coin came up heads, LAB_UNSELECTED otherwise.  All labels
+        // are requested first (coalesced, MAX_PER = RB_MAX_BATCH / TPB per thread) so that their memory
+        // round trip overlaps the coin draws.
+        int32_t* s_lab = reinterpret_cast<int32_t*>(s_first);
+        constexpr int MAX_PER = RB_MAX_BATCH / TPB;
+        int64_t yl[MAX_PER];
+#pragma unroll
+        for (int u = 0; u < MAX_PER; ++u) {
+            const int q = tid + u * TPB;
+            yl[u] = q < b ? a.batch_y[q] : -1;
         }
+        uint32_t heads = 0;                    // bit u: the coin of sample tid + u * TPB
+        for (int q = tid, u = 0; q < b; q += TPB, ++u)
+            heads |= (uint32_t)((int64_t)below(a.sd, PURPOSE_COIN, (uint32_t)q, (uint64_t)b) < c) << u;
+#pragma unroll
+        for (int u = 0; u < MAX_PER; ++u) {
+            const int q = tid + u * TPB;
+            if (q < b) s_lab[q] = !((heads >> u) & 1u) ? LAB_UNSELECTED : (yl[u] >= 0 && yl[u] < a.K) ? (int32_t)yl[u] : LAB_INVALID;
+        }
+        __syncthreads();
+        const int per = (b + TPB - 1) / TPB;
+        const int q_lo = tid * per, q_hi = q_lo + per < b ? q_lo + per : b;
+        int mine = 0;
+        for (int q = q_lo; q < q_hi; ++q) mine += s_lab[q] != LAB_UNSELECTED;
         int at = block_scan_excl(mine, m, s_wave);
-        for (int u = 0; u < per; ++u) {
-            const int q = q_lo + u;
-            if (q < b && s_first[q] != 0u) {
+        for (int q = q_lo; q < q_hi; ++q) {
+            const int32_t k = s_lab[q];
+            if (k != LAB_UNSELECTED) {
                 s_x[at] = (uint16_t)q;
-                const int64_t y = a.batch_y[q];
-                s_k[at] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+                s_k[at] = k;
                 ++at;
             }
         }
@@ -83,14 +96,16 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         // value, or it equals b-c+q for an earlier q whose own draw was taken; a
         // taken draw is replaced by b-c+i.
         m = c;
-        for (int q = tid; q < b; q += TPB) s_first[q] = 0xFFFFFFFFu;
-        __syncthreads();
         const int base = b - c;
+        // s_first[v] = lowest candidate index that drew v: only the entries that are drawn at all
+        // are initialised (by every thread that drew them), then minimised
         for (int i = tid; i < c; i += TPB) {
             uint32_t t = (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)i, (uint64_t)(base + i + 1));
             s_t[i] = (uint16_t)t;
-            atomicMin(&s_first[t], (uint32_t)i);
+            s_first[t] = 0xFFFFFFFFu;
         }
+        __syncthreads();
+        for (int i = tid; i < c; i += TPB) atomicMin(&s_first[s_t[i]], (uint32_t)i);
         __syncthreads();
         for (int i = tid; i < c; i += TPB) {
             int cur = i;
@@ -102,10 +117,21 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
                 if (q < 0 || q >= cur) break;
                 cur = q;                                                    // taken iff that step fell back
             }
-            int x = taken ? base + i : (int)s_t[i];
-            s_x[i] = (uint16_t)x;
-            int64_t y = a.batch_y[x];
-            s_k[i] = (y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID;
+            s_x[i] = (uint16_t)(taken ? base + i : (int)s_t[i]);
+        }
+        // the candidates' labels, four loads in flight per thread
+        for (int i0 = tid; i0 < c; i0 += 4 * TPB) {
+            int64_t y[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * TPB;
+                y[u] = i < c ? a.batch_y[s_x[i]] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * TPB;
+                if (i < c) s_k[i] = (y[u] >= 0 && y[u] < a.K) ? (int32_t)y[u] : LAB_INVALID;
+            }
         }
         __syncthreads();
     }
@@ -148,7 +174,8 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
     // ---- movers: one work item per wavefront and round, no workgroup barrier from here on ----
     const int64_t stride = (int64_t)(gridDim.x - a.nchunks) * NWAVE;
     for (int64_t item = (int64_t)(blockIdx.x - a.nchunks) * NWAVE + wave; item < (int64_t)m * a.tpr; item += stride) {
-        const int i = (int)(item / a.tpr), tile = (int)(item % a.tpr);   // candidate, tile of its row
+        int i, tile;                           // candidate, tile of its row
+        split_item(item, a.tpr, i, tile);
         const int p = s_x[i];                                             // its mini-batch position
         const int32_t ki = s_k[i];
         if (ki < 0) continue;                  // label outside [0, K): dropped (flagged by bookkeeping)
@@ -162,15 +189,21 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         t.load(a.batch_x + (int64_t)p * a.row_vec, v_lo, v_hi);
 
         // Candidates of class ki, in mini-batch order: the one with `rank` class-mates before it is
-        // insertion number fill0 + rank of the class.
-        int total = 0, rank = 0;
-        for (int m0 = 0; m0 < m; m0 += WAVE) {
+        // insertion number fill0 + rank of the class.  Each lane looks at every WAVE-th candidate,
+        // remembers in a bit mask which of them are class-mates, and the counts are summed over the
+        // wavefront once at the end (no ballot, hence no scalar dependency, per round).
+        uint64_t hit = 0;                      // bit `round`: candidate round * WAVE + lane is a class-mate (m <= 64 * WAVE)
+        int my_rank = 0;
+        for (int m0 = 0, round = 0; m0 < m; m0 += WAVE, ++round) {
             const int q = m0 + lane;
             const bool same = q < m && s_k[q] == ki;
             const int xq = q < m ? s_x[q] : 0;
-            total += __popcll(__ballot(same));
-            rank += __popcll(__ballot(same && xq < p));
+            hit |= (uint64_t)same << round;
+            my_rank += same && xq < p;
         }
+        const int mine = __popcll(hit);
+        const int incl = wave_scan_incl(mine | (my_rank << 16));      // both sums are <= 4096
+        const int total = lane_read(incl, WAVE - 1) & 0xFFFF, rank = lane_read(incl, WAVE - 1) >> 16;
         int64_t slot;
         if (fill0 + total <= a.S) {
             slot = fill0 + rank;               // all of them append: distinct slots
@@ -180,11 +213,37 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
             const int64_t at = fill0 + rank;
             if (at + a.S < fill0 + total) continue;
             slot = at < a.S ? at : (aux0 + at - a.S) % a.S;
-        } else {
-            const bool reservoir = a.eviction == RB_EVICT_RESERVOIR;
+        } else if (total <= WAVE) {
             // Insertions beyond the capacity overwrite a uniformly drawn slot (or, with reservoir
             // sampling, are kept with probability S / offers).  This candidate is not stored if a
-            // later class-mate overwrites its slot.
+            // later class-mate overwrites its slot.  The usual case: every class-mate gets a lane
+            // (in no particular order), which works out its insertion number (class-mates before it)
+            // and, if it overwrites, the slot it draws.
+            const bool reservoir = a.eviction == RB_EVICT_RESERVOIR;
+            uint16_t* pend = s_pend[wave];
+            int at = (incl & 0xFFFF) - mine;
+            for (uint64_t h = hit; h != 0; h &= h - 1) pend[at++] = s_x[__builtin_ctzll(h) * WAVE + lane];
+            const bool has = lane < total;
+            const int xl = has ? pend[lane] : 0;
+            int rl = 0;
+            for (int j = 0; j < total; ++j) rl += lane_read(xl, j) < xl;
+            const bool draws = has && xl >= p && fill0 + rl >= a.S;     // this candidate and the later ones
+            int dr = -1;
+            if (draws) {
+                const int64_t offers = aux0 + rl < INT32_MAX ? aux0 + rl : INT32_MAX;   // to the class, before this one
+                dr = (int)below(a.sd, PURPOSE_EVICT, (uint32_t)xl, reservoir ? (uint64_t)offers + 1 : (uint64_t)a.S);
+            }
+            int64_t own = fill0 + rank;
+            if (own >= a.S) {
+                const int me = __builtin_ctzll(__ballot(has && xl == p) | (1ull << 63));
+                own = lane_read(dr, me);
+                if (own >= a.S) continue;      // reservoir: not kept
+            }
+            if (__ballot(draws && xl > p && dr == (int)own) != 0) continue;
+            slot = own;
+        } else {
+            // the same for a class with more than WAVE candidates in this step
+            const bool reservoir = a.eviction == RB_EVICT_RESERVOIR;
             int64_t own = fill0 + rank;
             if (own >= a.S) {
                 const int64_t offers = aux0 + rank < INT32_MAX ? aux0 + rank : INT32_MAX;   // to the class, before this one
@@ -297,7 +356,8 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
     // ---- one work item per wavefront, no workgroup barrier from here on ---------
     const int64_t item = (int64_t)blockIdx.x * NWAVE + wave;
     if (item >= (int64_t)a.r * a.tpr) return;
-    const int j = (int)(item / a.tpr), tile = (int)(item % a.tpr);    // output row, tile of it
+    int j, tile;                               // output row, tile of it
+    split_item(item, a.tpr, j, tile);
     if (j >= n) {                              // fewer stored samples than asked for
         if (tile == 0 && lane == 0) a.out_y[j] = -1;
         return;

@@ -91,9 +91,10 @@ POLICIES = {"bernoulli-uniform": (1, 0), "exact-fifo": (0, 1), "exact-reservoir"
     (wl.variant(wl.C2, name="C2-S3-policy", S=3), 120),
     (wl.variant(wl.C4, name="C4-S8-policy", S=8, shape=(3, 32, 32)), 60),          # Zipf head: many class-mates per step
     (wl.variant(wl.C5, name="C5-S16-K200-policy", K=200, S=16, shape=(64,)), 25),  # ~20 candidates per class and step into 16 slots
+    (wl.variant(wl.C5, name="C5-S50-K5-policy", K=5, S=50, shape=(64,)), 12),      # ~200 candidates per class: more than one wavefront of class-mates
     (wl.Workload("laps", 9, 3, 2, (8,), "f32", 4096, 4096, 64, 6, "normal", "uniform"), 6),   # ~1365 candidates per class into 2 slots
     (wl.Workload("one-class", 9, 1, 5000, (8,), "bf16", 4096, 2000, 4096, 8, "normal", "uniform"), 8),
-], ids=["C1", "C2-S3", "C4-S8", "C5-S16", "laps", "one-class"])
+], ids=["C1", "C2-S3", "C4-S8", "C5-S16", "C5-K5", "laps", "one-class"])
 def test_policy_variants(policy, w, steps):
     run_parity(w, steps=steps, check_state_every=max(1, steps // 3), policy=POLICIES[policy])
 
@@ -122,6 +123,7 @@ def test_policy_cannot_change_after_an_update():
     (wl.variant(wl.C3, name="C3-S4", S=4), 150),                               # 16 per class > 4 slots: heavy replacement
     (wl.variant(wl.C4, name="C4-S8", S=8, shape=(3, 32, 32)), 100),            # Zipf head: many same-class evictions per step
     (wl.variant(wl.C5, name="C5-S16-K200", K=200, S=16, shape=(64,)), 40),     # 1024 candidates into 50 classes x 16 slots
+    (wl.variant(wl.C5, name="C5-S50-K5", K=5, S=50, shape=(64,)), 20),         # ~200 candidates per class: more than one wavefront of class-mates
     (wl.variant(wl.C2, name="C2-S3", S=3), 200),
     (wl.variant(wl.C5, name="C5-small-rows", S=40, shape=(256,)), 30),         # K = 10000: two-level fill index, append chains
 ])
