@@ -63,6 +63,9 @@ class Rig:
         for i in range(self.P):
             bx, by = self.aug_x[i].data_ptr(), self.aug_y[i].data_ptr()
             self.args.append((bx, by, bx + w.b * rs, by + w.b * 8))
+        # host arrays of the same pointers for rb_update_sample_many: the pool twice over, so that any run of
+        # up to P consecutive slots is contiguous
+        self.ptrs = [rb.pointer_array([a[i] for a in self.args] * 2) for i in range(4)]
         self.step = 0
 
     def prefill(self):
@@ -82,12 +85,26 @@ class Rig:
         fill, _, _ = self.buf.read_state()
         assert int(fill.sum()) == total, (int(fill.sum()), total)
 
-    def enqueue(self, n, do_update=True, do_sample=True, single_call=False):
-        """Enqueue n consecutive steps on the side stream (no synchronisation)."""
+    def enqueue(self, n, do_update=True, do_sample=True, single_call=False, many=0):
+        """Enqueue n consecutive steps on the side stream (no synchronisation).
+        many: hand the steps to rb_update_sample_many, `many` of them per call (n a multiple of the pool size)."""
         w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
         upd, smp, both = rb.rb_update, rb.rb_sample_augment, rb.rb_update_sample
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
         t = self.step
+        if many:
+            assert many <= P
+            import ctypes as C
+            for at in range(0, n, many):
+                k = min(many, n - at)
+                o = (t % P) * C.sizeof(C.c_void_p)
+                px, py, ox, oy = (C.cast(C.byref(a, o), C.POINTER(C.c_void_p)) for a in self.ptrs)
+                rc = rb.rb_update_sample_many(h, k, px, py, b, c, r, seed, t, ox, oy)
+                if rc:
+                    raise RuntimeError(f"rb_update_sample_many -> {rc}")
+                t += k
+            self.step = t
+            return
         for _ in range(n):
             bx, by, ox, oy = args[t % P]
             if single_call:
@@ -185,20 +202,27 @@ def overlap_leg(rig, steps, target_ms, kind="fma"):
         amount = min(1 << 30, max(1 << 20, amount // 4096 * 4096))
     t_alone = standin_ms(amount, steps)
     t_rb = rig.timed(steps, single_call=True)
-    done = [torch.cuda.Event() for _ in range(4)]
+    pipe = rb.Pipeline(rig.buf)
+    h, P, args = pipe.handle, rig.P, rig.args
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record(main)
-    for t in range(steps):
-        if t > 0:
-            main.wait_event(done[(t - 1) % 4])        # (1) representatives sampled during the previous iteration
-        rig.enqueue(1, single_call=True)               # (2) update with this mini-batch, then sample the next representatives
-        done[t % 4].record(rig.stream)
+    for _ in range(steps):
+        t = rig.step
+        bx, by = args[t % P][:2]
+        nx, ny = args[(t + 1) % P][2:]                 # tail of the next augmented mini-batch
+        # (1) wait for the representatives sampled during the previous iteration; (2) update with this
+        # mini-batch, then sample the next representatives, on the buffer's stream
+        rc, _ = rb.rb_pipeline_step(h, bx, by, w.b, w.c, w.r, w.lib_seed, t, nx, ny, main)
+        if rc:
+            raise RuntimeError(f"rb_pipeline_step -> {rc}")
+        rig.step = t + 1
         standin(amount)                                # (3), (4) forward and backward pass stand-in
-    main.wait_event(done[(steps - 1) % 4])
+    pipe.drain(main)
     e1.record(main)
     torch.cuda.synchronize()
     t_both = e0.elapsed_time(e1) / steps
+    pipe.close()
     del big
     return {"standin": kind, "standin_ms": round(t_alone, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
             "overhead_frac": round((t_both - t_alone) / t_alone, 4)}
@@ -241,6 +265,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     ms = rig.timed(steps, single_call=True)
     n_side = min(steps, 1000)
     ms_two = rig.timed(n_side)
+    ms_many = rig.timed(n_side, many=min(rig.P, 64))      # 64 steps per host call
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).
@@ -254,6 +279,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "launches_per_step": 1 if fused else 2,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
+        "many_call_ms_per_step": ms_many,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }

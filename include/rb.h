@@ -157,6 +157,58 @@ int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
                      int64_t r, uint64_t seed, uint64_t step, void *out_x, int64_t *out_y);
 
 /*
+ * n consecutive rb_update_sample steps from one call, for callers that have
+ * several mini-batches ready (e.g. a prefetching data pipeline) and want to
+ * pay the host side of the call once: step i uses batch_x[i], batch_y[i],
+ * step number first_step + i and writes to out_x[i], out_y[i]; b, c, r and
+ * seed are common.  The four pointer arrays are HOST arrays of n device
+ * pointers, read before the call returns.  All n steps are validated first;
+ * on an error nothing was enqueued.  Results are those of n separate calls.
+ */
+int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
+                          int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
+                          void *const *out_x, int64_t *const *out_y);
+
+/*
+ * The asynchronous form of that primitive (Sec. IV-D, Fig. 4, Listing 1): the
+ * training loop calls it once per iteration with the iteration's mini-batch;
+ * the call (1) makes `train_stream` wait until the representatives that the
+ * PREVIOUS call started to collect are complete, and reports in *ready_rows
+ * how many rows that call asked for (0 on the first call: the buffer was
+ * empty, so the first iteration trains on the plain mini-batch); (2) enqueues,
+ * on the buffer's bound stream, rb_update_sample with this mini-batch, whose
+ * representatives go to next_x / next_y: the place where the caller wants the
+ * NEXT iteration's representatives, usually the tail rows of the next
+ * augmented mini-batch (or one of two alternating buffers).  Work the caller
+ * then enqueues on train_stream (forward and backward pass on the augmented
+ * mini-batch) runs concurrently with (2).
+ *
+ * Ordering set up by the call, with events and no host synchronisation: the
+ * bound stream waits for everything enqueued on train_stream so far (the
+ * mini-batch has been produced, and whatever read the memory behind next_x /
+ * next_y in earlier iterations is done); train_stream waits for the previous
+ * call's work as said in (1).  The mini-batch must stay unchanged until that
+ * work is complete, i.e. until train_stream has passed the wait of the next
+ * rb_pipeline_step or rb_pipeline_drain.  If train_stream is the bound stream
+ * itself the call degenerates to rb_update_sample.
+ *
+ * rb_pipeline_create makes the two events (no device memory); the pipeline
+ * borrows `rb`, which must outlive it.  rb_pipeline_drain only does (1): it
+ * makes train_stream wait for the last step's representatives (end of
+ * training, or before the caller touches the buffer's state).  Arguments,
+ * limits and errors of rb_pipeline_step are those of rb_update_sample;
+ * ready_rows may be null.  On an error nothing was enqueued and the pipeline
+ * is unchanged.
+ */
+typedef struct rb_pipeline rb_pipeline;
+int rb_pipeline_create(rb_pipeline **out, rb_buffer *rb);
+int rb_pipeline_step(rb_pipeline *p, const void *batch_x, const int64_t *batch_y, int64_t b, int64_t c,
+                     int64_t r, uint64_t seed, uint64_t step, void *next_x, int64_t *next_y,
+                     void *train_stream, int64_t *ready_rows);
+int rb_pipeline_drain(rb_pipeline *p, void *train_stream, int64_t *ready_rows);
+int rb_pipeline_destroy(rb_pipeline *p);
+
+/*
  * Synchronise the bound stream and copy state to the host: fill_host[classes]
  * (samples held per class), *last_n_host (n of the latest rb_sample_augment),
  * *flags_host (RB_FLAG_*).  Any pointer may be null.  Not for the hot path.

@@ -4,4 +4,4 @@ Importing this package loads paper_2406_03285_amd/librb.so and fails if it has
 not been built (`python -m paper_2406_03285_amd.build`); there is no CPU path.
 """
 from .binding import *  # noqa: F401,F403
-from .binding import RehearsalBuffer, RbError, EXPORTS, LIB_PATH  # noqa: F401
+from .binding import RehearsalBuffer, Pipeline, RbError, EXPORTS, LIB_PATH  # noqa: F401

@@ -23,6 +23,7 @@ RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
     "rb_create", "rb_query_sizes", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
+    "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -48,6 +49,11 @@ def _load():
     L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
     L.rb_update_sample.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp]
+    L.rb_update_sample_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp)]
+    L.rb_pipeline_create.argtypes = [C.POINTER(vp), vp]
+    L.rb_pipeline_step.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp, vp, C.POINTER(i64)]
+    L.rb_pipeline_drain.argtypes = [vp, vp, C.POINTER(i64)]
+    L.rb_pipeline_destroy.argtypes = [vp]
     L.rb_read_state.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(C.c_uint32)]
     L.rb_set_option.argtypes = [vp, i32, i64]
     L.rb_destroy.argtypes = [vp]
@@ -121,6 +127,43 @@ def rb_sample_augment(rb, r, seed, step, out_x, out_y):
 def rb_update_sample(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y):
     return _L.rb_update_sample(rb, _ptr(batch_x), _ptr(batch_y), int(b), int(c), int(r), int(seed), int(step),
                                _ptr(out_x), _ptr(out_y))
+
+
+def pointer_array(items):
+    """Host array of device pointers (tensors or ints), reusable across rb_update_sample_many calls."""
+    return (C.c_void_p * len(items))(*[_ptr(t) for t in items])
+
+
+def rb_update_sample_many(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y):
+    """batch_x, batch_y, out_x, out_y: sequences of n tensors / addresses, or arrays made by pointer_array."""
+    arrs = [a if a is None or isinstance(a, (C.Array, C._Pointer)) else pointer_array(a) for a in (batch_x, batch_y, out_x, out_y)]
+    return _L.rb_update_sample_many(rb, int(n), arrs[0], arrs[1], int(b), int(c), int(r), int(seed), int(first_step),
+                                    arrs[2], arrs[3])
+
+
+def rb_pipeline_create(rb):
+    h = C.c_void_p()
+    rc = _L.rb_pipeline_create(C.byref(h), rb)
+    return rc, h.value
+
+
+def rb_pipeline_step(p, batch_x, batch_y, b, c, r, seed, step, next_x, next_y, train_stream=None):
+    """Returns (status, ready_rows)."""
+    n = C.c_int64()
+    rc = _L.rb_pipeline_step(p, _ptr(batch_x), _ptr(batch_y), int(b), int(c), int(r), int(seed), int(step),
+                             _ptr(next_x), _ptr(next_y), _stream(train_stream), C.byref(n))
+    return rc, n.value
+
+
+def rb_pipeline_drain(p, train_stream=None):
+    """Returns (status, ready_rows)."""
+    n = C.c_int64()
+    rc = _L.rb_pipeline_drain(p, _stream(train_stream), C.byref(n))
+    return rc, n.value
+
+
+def rb_pipeline_destroy(p):
+    return _L.rb_pipeline_destroy(p)
 
 
 def rb_read_state(rb, classes):
@@ -232,6 +275,46 @@ class RehearsalBuffer:
     def close(self):
         if getattr(self, "handle", None):
             rb_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        self.close()
+
+
+class Pipeline:
+    """The asynchronous `update` primitive on top of a RehearsalBuffer (argument marshalling only).
+
+    step(batch_x, batch_y, c, r, seed, t, next_x, next_y, train_stream) returns the number of rows that the
+    previous call's representatives hold (0 on the first call) once `train_stream` has been told to wait for them.
+    """
+
+    def __init__(self, buf):
+        self.buf = buf
+        rc, self.handle = rb_pipeline_create(buf.handle)
+        _check(rc, "rb_pipeline_create")
+
+    def step(self, batch_x, batch_y, c, r, seed, step, next_x, next_y, train_stream=None):
+        buf = self.buf
+        assert batch_x.is_contiguous() and batch_y.is_contiguous() and batch_y.dtype == torch.int64
+        assert batch_x.dtype == buf.dtype and tuple(batch_x.shape[1:]) == buf.sample_shape
+        b = batch_y.shape[0]
+        assert batch_x.shape[0] == b
+        if r > 0:
+            assert next_x.is_contiguous() and next_y.is_contiguous() and next_y.dtype == torch.int64
+            assert next_x.dtype == buf.dtype and tuple(next_x.shape[1:]) == buf.sample_shape
+            assert next_x.shape[0] >= r and next_y.shape[0] >= r
+        rc, rows = rb_pipeline_step(self.handle, batch_x, batch_y, b, c, r, seed, step, next_x, next_y, train_stream)
+        _check(rc, "rb_pipeline_step")
+        return rows
+
+    def drain(self, train_stream=None):
+        rc, rows = rb_pipeline_drain(self.handle, train_stream)
+        _check(rc, "rb_pipeline_drain")
+        return rows
+
+    def close(self):
+        if getattr(self, "handle", None):
+            rb_pipeline_destroy(self.handle)
             self.handle = None
 
     def __del__(self):

@@ -175,7 +175,30 @@ Seed make_seed(uint64_t seed, uint64_t step)
     return s;
 }
 
+// What the host can check of the arguments of one update + sample step.
+int check_step(const rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
+               const void* out_x, const int64_t* out_y)
+{
+    if (!rb || !batch_x || !batch_y) return RB_EINVAL;
+    if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b) return RB_EINVAL;
+    if (!aligned(batch_x, 16) || !aligned(batch_y, 8)) return RB_EINVAL;
+    if (r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
+    if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+    return RB_OK;
+}
+
 }  // namespace
+
+// The asynchronous form of the single primitive: two events order the training stream and the
+// buffer's stream against each other.
+struct rb_pipeline {
+    rb_buffer* rb;
+    hipEvent_t ready;     // on the training stream: mini-batch produced, earlier representatives consumed
+    hipEvent_t done;      // on the buffer's stream: the latest step's update and sampling are complete
+    int64_t prev_r;       // rows the latest step asked for
+    bool started;         // at least one step has been enqueued
+};
 
 extern "C" {
 
@@ -354,12 +377,8 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
 int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c,
                      int64_t r, uint64_t seed, uint64_t step, void* out_x, int64_t* out_y)
 {
-    if (!rb || !batch_x || !batch_y) return RB_EINVAL;
-    if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b) return RB_EINVAL;
-    if (!aligned(batch_x, 16) || !aligned(batch_y, 8)) return RB_EINVAL;
-    if (r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
-    if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
-    if (!rb->bound) return RB_ESTATE;
+    const int bad = check_step(rb, batch_x, batch_y, b, c, r, out_x, out_y);
+    if (bad != RB_OK) return bad;
 
     const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
                        rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
@@ -399,6 +418,92 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     rb->cur ^= 1;
     rb->updates += 1;
     return RB_OK;
+}
+
+int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y,
+                          int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
+                          void* const* out_x, int64_t* const* out_y)
+{
+    if (!rb || n < 0 || !batch_x || !batch_y) return RB_EINVAL;
+    if (r > 0 && (!out_x || !out_y)) return RB_EINVAL;
+    for (int64_t i = 0; i < n; ++i) {
+        const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
+        if (bad != RB_OK) return bad;
+    }
+    for (int64_t i = 0; i < n; ++i) {
+        const int rc = rb_update_sample(rb, batch_x[i], batch_y[i], b, c, r, seed, first_step + (uint64_t)i,
+                                        r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
+        if (rc != RB_OK) return rc;      // only a failed launch can get here
+    }
+    return RB_OK;
+}
+
+int rb_pipeline_create(rb_pipeline** out, rb_buffer* rb)
+{
+    if (!out) return RB_EINVAL;
+    *out = nullptr;
+    if (!rb) return RB_EINVAL;
+    rb_pipeline* p = new (std::nothrow) rb_pipeline();
+    if (!p) return RB_ENOMEM;
+    p->rb = rb;
+    p->prev_r = 0;
+    p->started = false;
+    if (hipEventCreateWithFlags(&p->ready, hipEventDisableTiming) != hipSuccess) {
+        delete p;
+        return RB_EHIP;
+    }
+    if (hipEventCreateWithFlags(&p->done, hipEventDisableTiming) != hipSuccess) {
+        (void)hipEventDestroy(p->ready);
+        delete p;
+        return RB_EHIP;
+    }
+    *out = p;
+    return RB_OK;
+}
+
+int rb_pipeline_step(rb_pipeline* p, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c,
+                     int64_t r, uint64_t seed, uint64_t step, void* next_x, int64_t* next_y,
+                     void* train_stream, int64_t* ready_rows)
+{
+    if (!p) return RB_EINVAL;
+    rb_buffer* rb = p->rb;
+    const int bad = check_step(rb, batch_x, batch_y, b, c, r, next_x, next_y);
+    if (bad != RB_OK) return bad;
+    hipStream_t train = static_cast<hipStream_t>(train_stream);
+    const bool two_streams = train != rb->stream;
+    if (two_streams) {
+        // (1) the training stream may go on once the previous step's representatives are complete
+        if (p->started && hipStreamWaitEvent(train, p->done, 0) != hipSuccess) return RB_EHIP;
+        // the buffer's stream starts this step once the training stream has got this far
+        if (hipEventRecord(p->ready, train) != hipSuccess) return RB_EHIP;
+        if (hipStreamWaitEvent(rb->stream, p->ready, 0) != hipSuccess) return RB_EHIP;
+    }
+    // (2) update with this mini-batch, then collect the next representatives
+    const int rc = rb_update_sample(rb, batch_x, batch_y, b, c, r, seed, step, next_x, next_y);
+    if (rc != RB_OK) return rc;
+    if (two_streams && hipEventRecord(p->done, rb->stream) != hipSuccess) return RB_EHIP;
+    if (ready_rows) *ready_rows = p->started ? p->prev_r : 0;
+    p->prev_r = r;
+    p->started = true;
+    return RB_OK;
+}
+
+int rb_pipeline_drain(rb_pipeline* p, void* train_stream, int64_t* ready_rows)
+{
+    if (!p) return RB_EINVAL;
+    hipStream_t train = static_cast<hipStream_t>(train_stream);
+    if (p->started && train != p->rb->stream && hipStreamWaitEvent(train, p->done, 0) != hipSuccess) return RB_EHIP;
+    if (ready_rows) *ready_rows = p->started ? p->prev_r : 0;
+    return RB_OK;
+}
+
+int rb_pipeline_destroy(rb_pipeline* p)
+{
+    if (!p) return RB_EINVAL;
+    const bool ok = hipEventDestroy(p->ready) == hipSuccess;
+    const bool ok2 = hipEventDestroy(p->done) == hipSuccess;
+    delete p;
+    return ok && ok2 ? RB_OK : RB_EHIP;
 }
 
 int rb_read_state(rb_buffer* rb, int32_t* fill_host, int64_t* last_n_host, uint32_t* flags_host)

@@ -11,6 +11,7 @@ import torch
 
 import rb_workloads as wl
 from oracle import rbo
+import parity_util
 from parity_util import SENTINEL, compare_buffers, run_parity
 
 pytestmark = pytest.mark.gpu
@@ -115,6 +116,122 @@ def test_policy_cannot_change_after_an_update():
     assert rb.rb_set_policy(buf.handle, 0, 0) == rb.RB_ESTATE
     assert rb.rb_bind(buf.handle, buf.buf_x, buf.buf_y, buf.workspace, None) == rb.RB_OK
     assert rb.rb_set_policy(buf.handle, 0, 0) == rb.RB_OK
+
+
+# ------------------------------------------------ several steps from one call ---
+
+@pytest.mark.parametrize("w", [
+    wl.variant(wl.C2, name="C2-many", S=4),
+    wl.variant(wl.C5, name="C5-many", K=300, S=12, shape=(256,), b=512, c=200, r=150),
+], ids=["small", "general"])
+def test_many_steps_from_one_call(w):
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    n = 14
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    xs, ys, oxs, oys = [], [], [], []
+    for t in range(2 * n):
+        x, y = wl.make_batch(w, t, dev)
+        xs.append(x.contiguous())
+        ys.append(y)
+        oxs.append(torch.full((w.r, *w.shape), 3, dtype=w.torch_dtype, device=dev))
+        oys.append(torch.full((w.r,), -7, dtype=torch.int64, device=dev))
+    # a bad argument anywhere: nothing is enqueued
+    broken = list(oxs[:n])
+    broken[n - 1] = oxs[n - 1].data_ptr() + 4
+    assert rb.rb_update_sample_many(buf.handle, n, xs[:n], ys[:n], w.b, w.c, w.r, w.lib_seed, 0, broken, oys[:n]) == rb.RB_EINVAL
+    assert int(buf.read_state()[0].sum()) == 0
+    assert rb.rb_update_sample_many(buf.handle, 0, xs[:0], ys[:0], w.b, w.c, w.r, w.lib_seed, 0, oxs[:0], oys[:0]) == rb.RB_OK
+    for first in (0, n):
+        sl = slice(first, first + n)
+        assert rb.rb_update_sample_many(buf.handle, n, xs[sl], ys[sl], w.b, w.c, w.r, w.lib_seed, first, oxs[sl], oys[sl]) == rb.RB_OK
+    torch.cuda.synchronize()
+    untouched = parity_util._bytes(torch.full((w.r, *w.shape), 3, dtype=w.torch_dtype)).numpy()
+    for t in range(2 * n):
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), w.c, w.lib_seed, t)
+        nn, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t)
+        got_y = oys[t].cpu().numpy()
+        assert np.array_equal(got_y, ref_y), f"{w.name} step {t}: labels differ"
+        got_x = parity_util._bytes(oxs[t]).cpu().numpy()
+        assert np.array_equal(got_x[:nn], ref_x[:nn]), f"{w.name} step {t}: rows differ"
+        assert np.array_equal(got_x[nn:], untouched[nn:]), f"{w.name} step {t}: rows beyond n were written"
+    compare_buffers(buf, orc, f"{w.name} final")
+
+
+# ----------------------------------------- the asynchronous primitive (Sec. IV-D) ---
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C2, name="C2-pipeline", S=6), 60),                                      # fused single launch
+    (wl.variant(wl.C5, name="C5-pipeline", K=300, S=12, shape=(256,), b=512, c=200, r=150), 25),   # two general kernels
+], ids=["small", "general"])
+def test_pipelined_primitive_returns_the_previous_iterations_representatives(w, steps):
+    """Iteration t trains on the representatives that iteration t-1 started to collect, while the
+    update with mini-batch t and the next sampling run on the buffer's stream under a stand-in
+    for the training computation."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    side = torch.cuda.Stream(dev)
+    train = torch.cuda.current_stream(dev)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=side)
+    pipe = rb.Pipeline(buf)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    aug_x = torch.empty((2, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=dev)    # two augmented mini-batches in turn
+    aug_y = torch.empty((2, w.b + w.r), dtype=torch.int64, device=dev)
+    sink = torch.empty(64 * 256, dtype=torch.float32, device=dev)
+    want = None                                     # what the oracle sampled in the previous iteration
+    for t in range(steps + 1):
+        cur, nxt = t % 2, (t + 1) % 2
+        if t < steps:
+            x, y = wl.make_batch(w, t, dev)             # produced on the training stream
+            aug_x[cur, :w.b].copy_(x)
+            aug_y[cur, :w.b].copy_(y)
+            # the tail of the NEXT augmented mini-batch receives this iteration's sampling
+            parity_util._bytes(aug_x[nxt, w.b:]).fill_(parity_util.SENTINEL)
+            aug_y[nxt, w.b:].fill_(-7)
+            rows = pipe.step(aug_x[cur, :w.b], aug_y[cur, :w.b], w.c, w.r, w.lib_seed, t,
+                             aug_x[nxt, w.b:], aug_y[nxt, w.b:], train_stream=train)
+            assert rb.rb_standin_compute(train, sink, 64, 2000) == rb.RB_OK     # "forward and backward pass"
+        else:
+            rows = pipe.drain(train)
+        assert rows == (0 if t == 0 else w.r)
+        if t > 0:
+            # ordered on the training stream after the wait that the call enqueued
+            got_y = aug_y[cur, w.b:].cpu().numpy()
+            got_x = parity_util._bytes(aug_x[cur, w.b:]).cpu().numpy()
+            n, ref_x, ref_y = want
+            assert np.array_equal(got_y, ref_y), f"{w.name} iteration {t}: labels of the representatives differ"
+            assert np.array_equal(got_x, ref_x), f"{w.name} iteration {t}: representatives differ (n={n})"
+        if t < steps:
+            hx = parity_util._bytes(aug_x[cur, :w.b]).cpu().numpy()
+            hy = aug_y[cur, :w.b].cpu().numpy()
+            orc.update(hx, hy, w.c, w.lib_seed, t)
+            ref = np.full((w.r, w.row_bytes), parity_util.SENTINEL, dtype=np.uint8)
+            want = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
+    compare_buffers(buf, orc, f"{w.name} final")
+    pipe.close()
+
+
+def test_pipeline_argument_checks_leave_it_unchanged():
+    rb = _rb()
+    w = wl.C1
+    dev = torch.device("cuda:0")
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=torch.cuda.Stream(dev))
+    rc, p = rb.rb_pipeline_create(buf.handle)
+    assert rc == rb.RB_OK
+    assert rb.rb_pipeline_create(None)[0] == rb.RB_EINVAL
+    x, y = wl.make_batch(w, 0, dev)
+    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
+    assert rb.rb_pipeline_step(p, x, y, w.b, w.b + 1, w.r, 0, 0, out_x, out_y)[0] == rb.RB_EINVAL
+    assert rb.rb_pipeline_step(p, x, y, w.b, w.c, w.r, 0, 0, None, out_y)[0] == rb.RB_EINVAL
+    assert rb.rb_pipeline_drain(p) == (rb.RB_OK, 0)                      # nothing was started
+    assert rb.rb_pipeline_step(p, x, y, w.b, w.c, w.r, 0, 0, out_x, out_y) == (rb.RB_OK, 0)
+    assert rb.rb_pipeline_step(p, x, y, w.b, w.c, 3, 0, 1, out_x, out_y) == (rb.RB_OK, w.r)
+    assert rb.rb_pipeline_drain(p) == (rb.RB_OK, 3)
+    torch.cuda.synchronize()
+    assert rb.rb_pipeline_destroy(p) == rb.RB_OK
+    assert rb.rb_pipeline_destroy(None) == rb.RB_EINVAL
 
 
 # ------------------------------------------- stress variants (replace path) ---
