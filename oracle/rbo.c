@@ -54,6 +54,14 @@
 enum { RBO_SELECT_EXACT = 0, RBO_SELECT_BERNOULLI = 1 };
 enum { RBO_EVICT_UNIFORM = 0, RBO_EVICT_FIFO = 1, RBO_EVICT_RESERVOIR = 2 };
 
+/* Storage variants.  The discussion section (Sec. VII) notes that data reduction can be applied to the
+ * stored representatives and names no technique; the one built here is the plainest for floating-point
+ * samples: keep every IEEE binary32 element as a bfloat16.
+ *   SAME - a stored row is the sample's bytes;
+ *   BF16 - the sample is an array of binary32 values; each is stored as the bfloat16 nearest to it (ties
+ *          to the one whose last bit is 0), and handed out widened back to binary32, which is exact. */
+enum { RBO_STORE_SAME = 0, RBO_STORE_BF16 = 1 };
+
 /* ------------------------------------------------------------------------ */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as  */
 /* easy as 1, 2, 3", SC'11, Sec. 3.3 and Table 2 for the constants).        */
@@ -112,12 +120,36 @@ void rbo_floyd(uint64_t seed, uint64_t step, uint32_t purpose, int64_t n, int64_
 }
 
 /* ------------------------------------------------------------------------ */
+/* binary32 -> bfloat16, round to nearest, ties to even, written out from   */
+/* the definition.  A bfloat16 is the upper 16 bits of a binary32, so the   */
+/* two neighbours of a value are its bit pattern with the lower half        */
+/* cleared (towards zero) and that plus one unit in bit 16 (away from zero; */
+/* from the largest finite bfloat16 this is infinity, as rounding demands). */
+/* NaN stays NaN: sign and upper payload bits kept, quiet bit set.          */
+/* ------------------------------------------------------------------------ */
+uint16_t rbo_f32_to_bf16(uint32_t bits)
+{
+    uint32_t magnitude = bits & 0x7FFFFFFFu;
+    if (magnitude > 0x7F800000u) return (uint16_t)((bits >> 16) | 0x0040u);
+    uint32_t down = bits >> 16;             /* neighbour towards zero  */
+    uint32_t up = down + 1u;                /* neighbour away from zero */
+    uint32_t rest = bits & 0xFFFFu;         /* distance from `down`, in units of 2^-16 of the gap */
+    if (rest < 0x8000u) return (uint16_t)down;
+    if (rest > 0x8000u) return (uint16_t)up;
+    return (uint16_t)((down & 1u) ? up : down);
+}
+
+uint32_t rbo_bf16_to_f32(uint16_t h) { return (uint32_t)h << 16; }
+
+/* ------------------------------------------------------------------------ */
 /* The buffer                                                                */
 /* ------------------------------------------------------------------------ */
 typedef struct rbo_buffer {
     int64_t K;            /* number of classes                                   */
     int64_t S;            /* capacity of every per-class sub-buffer, in samples  */
-    int64_t row_bytes;    /* bytes of one stored sample                          */
+    int64_t row_bytes;    /* bytes of one sample as the caller hands it in and gets it back */
+    int64_t stored_bytes; /* bytes of one stored sample (row_bytes, or half of it) */
+    int storage;          /* RBO_STORE_*                                          */
     int32_t *fill;        /* [K]   samples currently held per class              */
     int64_t *buf_y;       /* [K*S] label of each slot, -1 while never written    */
     unsigned char **rows; /* [K*S] sample bytes of each slot, NULL until written */
@@ -141,6 +173,7 @@ rbo_buffer *rbo_create(int64_t classes, int64_t slots_per_class, int64_t row_byt
     rbo_buffer *rb = (rbo_buffer *)calloc(1, sizeof *rb);
     if (!rb) return NULL;
     rb->K = classes; rb->S = slots_per_class; rb->row_bytes = row_bytes;
+    rb->stored_bytes = row_bytes; rb->storage = RBO_STORE_SAME;
     size_t slots = (size_t)classes * (size_t)slots_per_class;
     rb->fill = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
     rb->head = (int32_t *)calloc((size_t)classes, sizeof(int32_t));
@@ -173,6 +206,43 @@ int rbo_set_policy(rbo_buffer *rb, int selection, int eviction)
     rb->selection = selection;
     rb->eviction = eviction;
     return 0;
+}
+
+/* Choose the storage variant; only while the buffer is still empty.  BF16 needs rows made of
+ * binary32 elements.  Returns 0, or -1. */
+int rbo_set_storage(rbo_buffer *rb, int storage)
+{
+    if (!rb || (storage != RBO_STORE_SAME && storage != RBO_STORE_BF16)) return -1;
+    if (storage == RBO_STORE_BF16 && rb->row_bytes % 4 != 0) return -1;
+    for (int64_t k = 0; k < rb->K; ++k)
+        if (rb->fill[k] != 0 || rb->seen[k] != 0) return -1;
+    rb->storage = storage;
+    rb->stored_bytes = storage == RBO_STORE_BF16 ? rb->row_bytes / 2 : rb->row_bytes;
+    return 0;
+}
+
+/* One sample into its stored form / back (both rows may be unaligned: bytes are assembled by hand,
+ * little-endian like the machines this runs on). */
+static void store_row(const rbo_buffer *rb, unsigned char *stored, const unsigned char *sample)
+{
+    if (rb->storage == RBO_STORE_SAME) { memcpy(stored, sample, (size_t)rb->row_bytes); return; }
+    for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
+        uint32_t bits;
+        memcpy(&bits, sample + 4 * e, 4);
+        uint16_t h = rbo_f32_to_bf16(bits);
+        memcpy(stored + 2 * e, &h, 2);
+    }
+}
+
+static void load_row(const rbo_buffer *rb, unsigned char *sample, const unsigned char *stored)
+{
+    if (rb->storage == RBO_STORE_SAME) { memcpy(sample, stored, (size_t)rb->row_bytes); return; }
+    for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
+        uint16_t h;
+        memcpy(&h, stored + 2 * e, 2);
+        uint32_t bits = rbo_bf16_to_f32(h);
+        memcpy(sample + 4 * e, &bits, 4);
+    }
 }
 
 static int cmp_i64(const void *a, const void *b)
@@ -247,10 +317,10 @@ int rbo_update(rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
         }
         size_t slot = (size_t)k * (size_t)rb->S + (size_t)s;
         if (!rb->rows[slot]) {
-            rb->rows[slot] = (unsigned char *)malloc((size_t)rb->row_bytes);
+            rb->rows[slot] = (unsigned char *)malloc((size_t)rb->stored_bytes);
             if (!rb->rows[slot]) { free(cand); return -1; }
         }
-        memcpy(rb->rows[slot], src + (size_t)pos * (size_t)rb->row_bytes, (size_t)rb->row_bytes);
+        store_row(rb, rb->rows[slot], src + (size_t)pos * (size_t)rb->row_bytes);
         rb->buf_y[slot] = k;
         rb->ins_pos[rb->n_ins] = pos; rb->ins_class[rb->n_ins] = k; rb->ins_slot[rb->n_ins] = s;
         rb->n_ins += 1;
@@ -288,7 +358,7 @@ int64_t rbo_sample_augment(rbo_buffer *rb, int64_t r, uint64_t seed, uint64_t st
         int64_t g = rb->smp_g[j], k = 0;
         while (g >= rb->fill[k]) { g -= rb->fill[k]; ++k; }
         size_t slot = (size_t)k * (size_t)rb->S + (size_t)g;
-        memcpy(dst + (size_t)j * (size_t)rb->row_bytes, rb->rows[slot], (size_t)rb->row_bytes);
+        load_row(rb, dst + (size_t)j * (size_t)rb->row_bytes, rb->rows[slot]);
         out_y[j] = k;
     }
     for (int64_t j = n; j < r; ++j) out_y[j] = -1;
@@ -307,22 +377,23 @@ const int64_t *rbo_ins_pos(const rbo_buffer *rb) { return rb->ins_pos; }
 const int64_t *rbo_ins_class(const rbo_buffer *rb) { return rb->ins_class; }
 const int64_t *rbo_ins_slot(const rbo_buffer *rb) { return rb->ins_slot; }
 const int64_t *rbo_sampled_g(const rbo_buffer *rb) { return rb->smp_g; }
+int64_t rbo_stored_row_bytes(const rbo_buffer *rb) { return rb->stored_bytes; }
 
-/* Sample bytes of slot s of class k, or NULL while that slot was never written. */
+/* Stored bytes (rbo_stored_row_bytes of them) of slot s of class k, or NULL while that slot was never written. */
 const void *rbo_row(const rbo_buffer *rb, int64_t k, int64_t s)
 {
     if (k < 0 || k >= rb->K || s < 0 || s >= rb->S) return NULL;
     return rb->rows[(size_t)k * (size_t)rb->S + (size_t)s];
 }
 
-/* Copy slots [first, first+count) (flat index k*S+s) into dst, row after row;
+/* Copy slots [first, first+count) (flat index k*S+s), as stored, into dst, row after row;
  * never-written slots are filled with zero bytes. */
 void rbo_export_rows(const rbo_buffer *rb, int64_t first, int64_t count, void *dst)
 {
     unsigned char *d = (unsigned char *)dst;
     for (int64_t i = 0; i < count; ++i) {
         const unsigned char *src = rb->rows[(size_t)(first + i)];
-        if (src) memcpy(d + (size_t)i * (size_t)rb->row_bytes, src, (size_t)rb->row_bytes);
-        else memset(d + (size_t)i * (size_t)rb->row_bytes, 0, (size_t)rb->row_bytes);
+        if (src) memcpy(d + (size_t)i * (size_t)rb->stored_bytes, src, (size_t)rb->stored_bytes);
+        else memset(d + (size_t)i * (size_t)rb->stored_bytes, 0, (size_t)rb->stored_bytes);
     }
 }

@@ -14,6 +14,7 @@ from . import build as _build
 SELECT, EVICT, SAMPLE, COIN = 1, 2, 3, 4
 SELECT_EXACT, SELECT_BERNOULLI = 0, 1
 EVICT_UNIFORM, EVICT_FIFO, EVICT_RESERVOIR = 0, 1, 2
+STORE_SAME, STORE_BF16 = 0, 1
 
 _lib = None
 
@@ -40,6 +41,14 @@ def lib():
         L.rbo_destroy.restype = None
         L.rbo_set_policy.argtypes = [vp, C.c_int, C.c_int]
         L.rbo_set_policy.restype = C.c_int
+        L.rbo_set_storage.argtypes = [vp, C.c_int]
+        L.rbo_set_storage.restype = C.c_int
+        L.rbo_stored_row_bytes.argtypes = [vp]
+        L.rbo_stored_row_bytes.restype = i64
+        L.rbo_f32_to_bf16.argtypes = [u32]
+        L.rbo_f32_to_bf16.restype = C.c_uint16
+        L.rbo_bf16_to_f32.argtypes = [C.c_uint16]
+        L.rbo_bf16_to_f32.restype = u32
         L.rbo_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
         L.rbo_update.restype = C.c_int
         L.rbo_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
@@ -84,6 +93,15 @@ def floyd(seed, step, purpose, n, m):
     return out
 
 
+def f32_to_bf16(bits):
+    """bfloat16 bit pattern of the binary32 with bit pattern `bits`."""
+    return int(lib().rbo_f32_to_bf16(int(bits)))
+
+
+def bf16_to_f32(h):
+    return int(lib().rbo_bf16_to_f32(int(h)))
+
+
 def _view(ptr, n, dtype):
     if n == 0 or not ptr:
         return np.empty(0, dtype=dtype)
@@ -99,6 +117,15 @@ class Buffer:
         self._h = lib().rbo_create(self.K, self.S, self.row_bytes)
         if not self._h:
             raise ValueError("rbo_create rejected the arguments")
+
+    def set_storage(self, storage):
+        if lib().rbo_set_storage(self._h, int(storage)) != 0:
+            raise ValueError("rbo_set_storage rejected the arguments (unknown variant, rows not made of 4-byte elements, "
+                             "or the buffer is not empty)")
+
+    @property
+    def stored_row_bytes(self):
+        return int(lib().rbo_stored_row_bytes(self._h))
 
     def set_policy(self, selection, eviction):
         if lib().rbo_set_policy(self._h, int(selection), int(eviction)) != 0:
@@ -168,9 +195,10 @@ class Buffer:
         p = lib().rbo_row(self._h, int(k), int(s))
         if not p:
             return None
-        return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint8)), shape=(self.row_bytes,)).copy()
+        return np.ctypeslib.as_array(C.cast(p, C.POINTER(C.c_uint8)), shape=(self.stored_row_bytes,)).copy()
 
     def export_rows(self, first, count):
-        out = np.empty((int(count), self.row_bytes), dtype=np.uint8)
+        """Rows as stored (stored_row_bytes each)."""
+        out = np.empty((int(count), self.stored_row_bytes), dtype=np.uint8)
         lib().rbo_export_rows(self._h, int(first), int(count), out.ctypes.data)
         return out
