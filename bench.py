@@ -36,12 +36,12 @@ def log(*a):
 class Rig:
     """Device-side state of one workload: the buffer, a side stream and a rotating pool of augmented batches."""
 
-    def __init__(self, w, torch, rb, wl, pool_slots=None, storage="hbm"):
+    def __init__(self, w, torch, rb, wl, pool_slots=None, storage="hbm", store_dtype=None):
         self.w, self.torch, self.rb = w, torch, rb
         self.dev = torch.device("cuda:0")
         self.stream = torch.cuda.Stream(self.dev)
         self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream,
-                                      storage=storage)
+                                      storage=storage, store_dtype=store_dtype)
         aug_bytes = (w.b + w.r) * w.row_bytes
         self.P = pool_slots or min(1024, max(8, -(-POOL_BYTES // aug_bytes)))
         self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
@@ -299,6 +299,23 @@ def host_pinned_leg(torch, rb, wl, steps=200):
             "host_link_gb_per_s": round((w.c + w.r) * w.row_bytes / (ms * 1e-3) / 1e9, 2)}
 
 
+def reduced_precision_leg(torch, rb, wl, steps=1000):
+    """Data reduction of the stored samples (Sec. VII): workload C3 (float32 samples) with rows stored as
+    bfloat16.  A candidate is read at 4 bytes and written at 2 bytes per element, a representative the other
+    way round: 3/4 of the bytes of the plain workload, and half the buffer."""
+    w = wl.C3
+    rig = Rig(w, torch, rb, wl, store_dtype=torch.bfloat16)
+    rig.enqueue(100, single_call=True)
+    torch.cuda.synchronize()
+    ms = rig.timed(steps, single_call=True)
+    moved = (w.c + w.r) * (w.row_bytes + w.row_bytes // 2)
+    rig.close()
+    return {"workload": w.name + " stored as bf16", "ms_per_step": round(ms, 5),
+            "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1), "bytes_per_step": moved,
+            "gb_per_s": round(moved / (ms * 1e-3) / 1e9, 1), "buffer_gb": round(w.buffer_bytes / 2 / 1e9, 1),
+            "launches_per_step": 2}
+
+
 def variants_leg(w, torch, rb, wl, steps):
     """The policy variants of Algorithm 1 on the same workload (general kernels, two launches per step)."""
     out = {}
@@ -385,6 +402,9 @@ def main():
     pinned = None if a.no_variants else host_pinned_leg(torch, rb, wl)
     if pinned:
         log(f"[bench] host-pinned {json.dumps(pinned)}")
+    reduced = None if a.no_variants else reduced_precision_leg(torch, rb, wl)
+    if reduced:
+        log(f"[bench] reduced-precision {json.dumps(reduced)}")
 
     # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
     # (rb_step_small_kernel: every inserted row and every representative row read once and written
@@ -416,6 +436,7 @@ def main():
         "others": others,
         "policy_variants": variants,
         "host_pinned_rows": pinned,
+        "bf16_stored_rows": reduced,
     }
     if not a.no_cpu_baseline:
         line["cpu_baseline"] = cpu_baseline(w, wl)

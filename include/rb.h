@@ -85,6 +85,22 @@ int rb_query_sizes(const rb_buffer *rb, size_t *x_bytes, size_t *y_bytes, size_t
 int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *hip_stream);
 
 /*
+ * Reduced-precision storage (Sec. VII notes that data reduction can be applied
+ * to the stored representatives; this is the plainest form for floating-point
+ * samples).  RB_STORE_SAME (default): a stored row is the sample's bytes.
+ * RB_STORE_BF16: samples are binary32 (dtype RB_F32); every element is stored
+ * as the bfloat16 nearest to it (ties to even; NaN keeps its sign and upper
+ * payload bits and is made quiet) by rb_update, and handed out widened back to
+ * binary32, which is exact, by rb_sample_augment.  Mini-batches and outputs
+ * keep the full row size; buf_x rows shrink to half: call this BEFORE
+ * rb_query_sizes / rb_bind (RB_ESTATE once bound).  The sample's byte size
+ * must be a multiple of 32.  The general kernels (two launches per step) serve
+ * this variant.
+ */
+enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1 };
+int rb_set_storage(rb_buffer *rb, int32_t storage);
+
+/*
  * Policy variants of Algorithm 1.  The defaults are what Algorithm 1 prints.
  * Selection: RB_SELECT_EXACT - the first step of Algorithm 1, a uniform subset
  * of exactly c positions; RB_SELECT_BERNOULLI - the wording of Sec. IV-B, where

@@ -19,10 +19,11 @@ RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
 RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE = 0, 1, 2, 3
 RB_SELECT_EXACT, RB_SELECT_BERNOULLI = 0, 1
+RB_STORE_SAME, RB_STORE_BF16 = 0, 1
 RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
-    "rb_create", "rb_query_sizes", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
+    "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
     "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
@@ -45,6 +46,7 @@ def _load():
     L.rb_query_sizes.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     L.rb_bind.argtypes = [vp, vp, vp, vp, vp]
     L.rb_set_policy.argtypes = [vp, i32, i32]
+    L.rb_set_storage.argtypes = [vp, i32]
     L.rb_set_stream.argtypes = [vp, vp]
     L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
@@ -106,6 +108,10 @@ def rb_query_sizes(rb):
 
 def rb_bind(rb, buf_x, buf_y, workspace, hip_stream=None):
     return _L.rb_bind(rb, _ptr(buf_x), _ptr(buf_y), _ptr(workspace), _stream(hip_stream))
+
+
+def rb_set_storage(rb, storage):
+    return _L.rb_set_storage(rb, int(storage))
 
 
 def rb_set_policy(rb, selection, eviction):
@@ -204,22 +210,28 @@ class RehearsalBuffer:
     """
 
     def __init__(self, classes, slots_per_class, sample_shape, dtype=torch.float32, device="cuda:0", stream=None,
-                 storage="hbm"):
+                 storage="hbm", store_dtype=None):
         """storage: "hbm" keeps the sample rows in device memory; "host_pinned" keeps them in pinned host
         memory that the kernels read and write directly over the host link (where the paper keeps its
-        buffers, Sec. IV-C); labels and workspace stay on the device either way."""
+        buffers, Sec. IV-C); labels and workspace stay on the device either way.
+        store_dtype: None keeps rows as they come; torch.bfloat16 with dtype float32 stores them at half size."""
         code = {torch.float32: RB_F32, torch.bfloat16: RB_BF16}[dtype]
         rc, self.handle = rb_create(classes, slots_per_class, tuple(sample_shape), code)
         _check(rc, "rb_create")
         self.K, self.S, self.sample_shape, self.dtype = int(classes), int(slots_per_class), tuple(sample_shape), dtype
+        self.store_dtype = dtype if store_dtype is None else store_dtype
+        if self.store_dtype != dtype:
+            if (dtype, self.store_dtype) != (torch.float32, torch.bfloat16):
+                raise ValueError("only float32 samples stored as bfloat16")
+            _check(rb_set_storage(self.handle, RB_STORE_BF16), "rb_set_storage")
         rc, xb, yb, wb = rb_query_sizes(self.handle)
         _check(rc, "rb_query_sizes")
-        self.row_bytes = xb // (self.K * self.S)
+        self.row_bytes = xb // (self.K * self.S)          # of a stored row
         self.device = torch.device(device)
         if storage == "hbm":
-            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, device=self.device)
+            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=self.store_dtype, device=self.device)
         elif storage == "host_pinned":
-            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=dtype, pin_memory=True)
+            self.buf_x = torch.empty((self.K, self.S, *self.sample_shape), dtype=self.store_dtype, pin_memory=True)
         else:
             raise ValueError(storage)
         self.storage = storage

@@ -31,8 +31,12 @@
 // Host side: the C ABI
 // ===========================================================================
 struct rb_buffer {
-    int64_t K, S, row_bytes, row_vec;
+    int64_t K, S;
+    int64_t row_bytes;       // bytes of one stored row
+    int64_t row_vec;         // 16-byte vectors of one stored row
+    int64_t sample_bytes;    // bytes of one sample as the caller hands it in and gets it back
     int32_t dtype;
+    int32_t storage;         // RB_STORE_*
     int32_t nchunks;
     // device storage (borrowed)
     void* buf_x;
@@ -98,7 +102,7 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
 }
 
 template <bool NT>
-hipError_t launch_update(const UpdateArgs& a, bool small, int unroll, dim3 grid, size_t lds, hipStream_t st)
+hipError_t launch_update(const UpdateArgs& a, bool small, bool narrow, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     if (small) {
         switch (unroll) {
@@ -109,19 +113,28 @@ hipError_t launch_update(const UpdateArgs& a, bool small, int unroll, dim3 grid,
         }
         return hipGetLastError();
     }
+    if (narrow) {
+        switch (unroll) {
+        case 1: rb_update_kernel<1, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_update_kernel<2, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_update_kernel<4, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_update_kernel<8, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        }
+        return hipGetLastError();
+    }
     switch (unroll) {
-    case 1: rb_update_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
-    case 2: rb_update_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
-    case 4: rb_update_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
-    default: rb_update_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 1: rb_update_kernel<1, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_update_kernel<2, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_update_kernel<4, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_update_kernel<8, NT, false><<<grid, TPB, lds, st>>>(a); break;
     }
     return hipGetLastError();
 }
 
 template <bool NT>
-hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds, hipStream_t st)
+hipError_t launch_sample(const SampleArgs& a, bool small, bool widen, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
-    if (a.r <= WAVE && a.nchunks <= WAVE) {
+    if (small) {
         switch (unroll) {
         case 1: rb_sample_small_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
         case 2: rb_sample_small_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
@@ -130,11 +143,20 @@ hipError_t launch_sample(const SampleArgs& a, int unroll, dim3 grid, size_t lds,
         }
         return hipGetLastError();
     }
+    if (widen) {
+        switch (unroll) {
+        case 1: rb_sample_kernel<1, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_sample_kernel<2, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_sample_kernel<4, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_sample_kernel<8, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        }
+        return hipGetLastError();
+    }
     switch (unroll) {
-    case 1: rb_sample_kernel<1, NT><<<grid, TPB, lds, st>>>(a); break;
-    case 2: rb_sample_kernel<2, NT><<<grid, TPB, lds, st>>>(a); break;
-    case 4: rb_sample_kernel<4, NT><<<grid, TPB, lds, st>>>(a); break;
-    default: rb_sample_kernel<8, NT><<<grid, TPB, lds, st>>>(a); break;
+    case 1: rb_sample_kernel<1, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_sample_kernel<2, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_sample_kernel<4, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_sample_kernel<8, NT, false><<<grid, TPB, lds, st>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -225,7 +247,9 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->S = slots_per_class;
     rb->row_bytes = row_bytes;
     rb->row_vec = row_bytes / 16;
+    rb->sample_bytes = row_bytes;
     rb->dtype = dtype;
+    rb->storage = RB_STORE_SAME;
     rb->nchunks = (int32_t)((classes + CH - 1) / CH);
     rb->buf_x = nullptr; rb->buf_y = nullptr; rb->ws = nullptr; rb->stream = nullptr;
     rb->bound = false;
@@ -252,6 +276,18 @@ int rb_query_sizes(const rb_buffer* rb, size_t* x_bytes, size_t* y_bytes, size_t
     if (x_bytes) *x_bytes = (size_t)rb->K * (size_t)rb->S * (size_t)rb->row_bytes;
     if (y_bytes) *y_bytes = (size_t)rb->K * (size_t)rb->S * sizeof(int64_t);
     if (workspace_bytes) *workspace_bytes = rb->ws_bytes;
+    return RB_OK;
+}
+
+int rb_set_storage(rb_buffer* rb, int32_t storage)
+{
+    if (!rb) return RB_EINVAL;
+    if (storage != RB_STORE_SAME && storage != RB_STORE_BF16) return RB_EINVAL;
+    if (rb->bound) return RB_ESTATE;                 // the storage the caller bound was sized for the other form
+    if (storage == RB_STORE_BF16 && (rb->dtype != RB_F32 || rb->sample_bytes % 32 != 0)) return RB_EINVAL;
+    rb->storage = storage;
+    rb->row_bytes = storage == RB_STORE_BF16 ? rb->sample_bytes / 2 : rb->sample_bytes;
+    rb->row_vec = rb->row_bytes / 16;
     return RB_OK;
 }
 
@@ -305,7 +341,8 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (c == 0) return RB_OK;
 
     const bool variant = rb->selection != RB_SELECT_EXACT || rb->eviction != RB_EVICT_UNIFORM;
-    const bool small = c <= WAVE && !variant;
+    const bool narrow = rb->storage == RB_STORE_BF16;
+    const bool small = c <= WAVE && !variant && !narrow;
     // Rows the grid is sized for.  The Bernoulli selection yields a random number of candidates
     // (mean c, at most b); the movers loop over the work items, so any number is handled, and
     // the grid only has to be large enough for the usual case.
@@ -337,8 +374,8 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     a.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
     const dim3 grid((unsigned)(rb->nchunks + (small ? sh.groups * sh.tpr : (rows * sh.tpr + NWAVE - 1) / NWAVE)));
     const size_t lds = small ? (size_t)b * 8 : (size_t)b * 4 + (size_t)a.cap * 8;
-    hipError_t e = rb->opt_nt ? launch_update<true>(a, small, sh.unroll, grid, lds, rb->stream)
-                              : launch_update<false>(a, small, sh.unroll, grid, lds, rb->stream);
+    hipError_t e = rb->opt_nt ? launch_update<true>(a, small, narrow, sh.unroll, grid, lds, rb->stream)
+                              : launch_update<false>(a, small, narrow, sh.unroll, grid, lds, rb->stream);
     if (e != hipSuccess) return RB_EHIP;
     rb->cur ^= 1;
     rb->updates += 1;
@@ -352,7 +389,8 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     if (!rb->bound) return RB_ESTATE;
     if (r == 0) return RB_OK;
 
-    const bool small = r <= WAVE && rb->nchunks <= WAVE;
+    const bool widen = rb->storage == RB_STORE_BF16;
+    const bool small = r <= WAVE && rb->nchunks <= WAVE && !widen;
     const Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
     SampleArgs a;
     a.buf_x = static_cast<const vec16*>(rb->buf_x);
@@ -369,8 +407,8 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     a.tpr = sh.tpr; a.tile_vec = sh.tile_vec; a.tile_rem = sh.tile_rem; a.rpb = sh.rpb;
     const dim3 grid((unsigned)(small ? sh.groups * sh.tpr : (r * sh.tpr + NWAVE - 1) / NWAVE));
     const size_t lds = small ? 0 : ((size_t)rb->nchunks + (size_t)r) * 4;
-    hipError_t e = rb->opt_nt ? launch_sample<true>(a, sh.unroll, grid, lds, rb->stream)
-                              : launch_sample<false>(a, sh.unroll, grid, lds, rb->stream);
+    hipError_t e = rb->opt_nt ? launch_sample<true>(a, small, widen, sh.unroll, grid, lds, rb->stream)
+                              : launch_sample<false>(a, small, widen, sh.unroll, grid, lds, rb->stream);
     return e == hipSuccess ? RB_OK : RB_EHIP;
 }
 
@@ -381,7 +419,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (bad != RB_OK) return bad;
 
     const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
-                       rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
+                       rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
     if (!fused) {
         const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);
         if (rc != RB_OK) return rc;

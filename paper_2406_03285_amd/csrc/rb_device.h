@@ -113,9 +113,43 @@ __device__ __forceinline__ int block_scan_excl(int v, int& total, int* s_wave)
 }
 
 // ---------------------------------------------------------------------------
+// Reduced-precision storage: binary32 elements kept as bfloat16 (the upper half of the binary32,
+// rounded to nearest, ties to even; NaN keeps its sign and upper payload bits and is made quiet).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t bf16_of(uint32_t u)
+{
+    const uint32_t rounded = (u + 0x7FFFu + ((u >> 16) & 1u)) >> 16;    // carries into the exponent where rounding demands it
+    return (u & 0x7FFFFFFFu) > 0x7F800000u ? ((u >> 16) | 0x0040u) : rounded;
+}
+
+// Eight consecutive binary32 elements (two vectors) -> eight bfloat16 (one vector), element order kept.
+__device__ __forceinline__ vec16 narrow8(const vec16 a, const vec16 b)
+{
+    vec16 o;
+    o.x = bf16_of(a.x) | (bf16_of(a.y) << 16);
+    o.y = bf16_of(a.z) | (bf16_of(a.w) << 16);
+    o.z = bf16_of(b.x) | (bf16_of(b.y) << 16);
+    o.w = bf16_of(b.z) | (bf16_of(b.w) << 16);
+    return o;
+}
+
+// and back: exact
+__device__ __forceinline__ void widen8(const vec16 s, vec16& a, vec16& b)
+{
+    a.x = s.x << 16; a.y = s.x & 0xFFFF0000u; a.z = s.y << 16; a.w = s.y & 0xFFFF0000u;
+    b.x = s.z << 16; b.y = s.z & 0xFFFF0000u; b.z = s.w << 16; b.w = s.w & 0xFFFF0000u;
+}
+
+enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2 };
+
+// ---------------------------------------------------------------------------
 // Row mover: one tile of one row, U vectors per thread in flight.
 // ---------------------------------------------------------------------------
-template <int U, bool NT, int W = TPB, bool PACED = true>   // W: threads that share the tile (a workgroup or one wavefront)
+// W: threads that share the tile (a workgroup or one wavefront).  CV: CV_NARROW - the source row is
+// binary32 (two vectors per vector of the tile), converted to bfloat16 while it is loaded; CV_WIDEN -
+// the destination row is binary32, converted from the tile's bfloat16 while it is stored.  Tile
+// indices always count vectors of the narrow (stored) row.
+template <int U, bool NT, int W = TPB, bool PACED = true, int CV = CV_NONE>
 struct Tile {
     vec16 v[U];
 
@@ -130,7 +164,13 @@ struct Tile {
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+            if (CV == CV_NARROW) {
+                const vec16 a = NT ? __builtin_nontemporal_load(src + 2 * i) : src[2 * i];
+                const vec16 b = NT ? __builtin_nontemporal_load(src + 2 * i + 1) : src[2 * i + 1];
+                v[u] = narrow8(a, b);
+            } else {
+                v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
+            }
         }
     }
     // All loads are waited for first and every store is waited for before the next one is
@@ -144,8 +184,21 @@ struct Tile {
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            if (NT) __builtin_nontemporal_store(v[u], dst + i);
-            else dst[i] = v[u];
+            if (CV == CV_WIDEN) {
+                vec16 a, b;
+                widen8(v[u], a, b);
+                if (NT) {
+                    __builtin_nontemporal_store(a, dst + 2 * i);
+                    __builtin_nontemporal_store(b, dst + 2 * i + 1);
+                } else {
+                    dst[2 * i] = a;
+                    dst[2 * i + 1] = b;
+                }
+            } else if (NT) {
+                __builtin_nontemporal_store(v[u], dst + i);
+            } else {
+                dst[i] = v[u];
+            }
             if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
@@ -196,7 +249,7 @@ struct UpdateArgs {
     int32_t b, c;
     int32_t K, nchunks;
     int64_t S;
-    int64_t row_vec;      // 16-byte vectors per row
+    int64_t row_vec;      // 16-byte vectors per stored row (a mini-batch row has twice as many with bfloat16 storage)
     int32_t tpr;          // tiles per row
     int32_t tile_vec;     // a row is split evenly into tpr tiles in units of TILE_UNIT vectors: the first
     int32_t tile_rem;     // tile_rem tiles hold tile_vec + 1 units, the others tile_vec; see tile_bounds

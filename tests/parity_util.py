@@ -61,11 +61,12 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
 
 def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
                first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False,
-               policy=None, storage="hbm"):
+               policy=None, storage="hbm", store_bf16=False):
     """Runs `steps` update+sample steps of workload `w` on both sides.
 
     single_call: drive the HIP side through rb_update_sample instead of the two calls.
     policy: (selection, eviction) variant codes, set on both sides (the codes are the same numbers).
+    store_bf16: float32 samples stored as bfloat16 on both sides.
     Every step: out_y equal, the n sampled rows byte-equal, rows >= n untouched.
     At the end (and every `check_state_every` steps): fill, flags, buf_y and all
     filled buf_x rows.  Returns (buf, orc) for further checks.
@@ -76,8 +77,11 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     dev = torch.device(device)
     own = buf is None
     if own:
-        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream, storage=storage)
+        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream, storage=storage,
+                                 store_dtype=torch.bfloat16 if store_bf16 else None)
         orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+        if store_bf16:
+            orc.set_storage(rbo.STORE_BF16)
         for opt, val in options:
             buf.set_option(opt, val)
         if policy is not None:

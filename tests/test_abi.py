@@ -72,3 +72,31 @@ def test_strerror():
     import paper_2406_03285_amd as rb
     assert rb.rb_strerror(0) == "ok"
     assert len({rb.rb_strerror(s) for s in (0, -1, -2, -3, -4, -99)}) == 6
+
+
+def test_variant_setters_validate_on_the_host():
+    import paper_2406_03285_amd as rb
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_F32)
+    assert rc == rb.RB_OK
+    assert rb.rb_set_policy(h, 2, 0) == rb.RB_EINVAL and rb.rb_set_policy(h, 0, 3) == rb.RB_EINVAL
+    assert rb.rb_set_policy(h, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_RESERVOIR) == rb.RB_OK
+    assert rb.rb_set_policy(None, 0, 0) == rb.RB_EINVAL
+    assert rb.rb_set_storage(h, 2) == rb.RB_EINVAL and rb.rb_set_storage(None, 0) == rb.RB_EINVAL
+    assert rb.rb_query_sizes(h)[1] == 4 * 2 * 32
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_OK
+    assert rb.rb_query_sizes(h)[1] == 4 * 2 * 16                     # stored rows are half the sample
+    assert rb.rb_set_storage(h, rb.RB_STORE_SAME) == rb.RB_OK
+    assert rb.rb_query_sizes(h)[1] == 4 * 2 * 32
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_BF16)
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_EINVAL    # only binary32 samples can be narrowed
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (4,), rb.RB_F32)
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_EINVAL    # a stored row would be 8 bytes
+    rb.rb_destroy(h)
+    # the pipeline and the multi-step call reject what the host can see
+    assert rb.rb_pipeline_create(None)[0] == rb.RB_EINVAL
+    assert rb.rb_pipeline_step(None, 256, 256, 4, 2, 2, 0, 0, 256, 256)[0] == rb.RB_EINVAL
+    assert rb.rb_pipeline_drain(None)[0] == rb.RB_EINVAL
+    assert rb.rb_pipeline_destroy(None) == rb.RB_EINVAL
+    assert rb.rb_update_sample_many(None, 1, [256], [256], 4, 2, 2, 0, 0, [256], [256]) == rb.RB_EINVAL

@@ -118,6 +118,69 @@ def test_policy_cannot_change_after_an_update():
     assert rb.rb_set_policy(buf.handle, 0, 0) == rb.RB_OK
 
 
+# ---------------------------------------------- reduced-precision storage ---
+
+_plain_make_batch = wl.make_batch
+
+
+def _special_values_batch(w, step, dev):
+    """A mini-batch whose float32 elements include every kind of rounding case: ties, values next to
+    ties, subnormals, the largest finite values, infinities and NaNs of both signs."""
+    x, y = _plain_make_batch(w, step, dev)
+    bits = x.view(torch.int32).reshape(-1)
+    special = torch.tensor([0x3F808000, 0x3F818000, 0x3F808001, 0x3F807FFF, 0x7F7FFFFF, 0x7F7F7FFF, 0x7F7F8000,
+                            0x00000001, 0x00008000, 0x00008001, 0x00018000, 0x7F800000, 0x7FC00000, 0x7F800001,
+                            0x00000000], dtype=torch.int64)
+    special = torch.cat([special, special | 0x80000000])
+    special = torch.where(special >= 2**31, special - 2**32, special).to(torch.int32).to(dev)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(step)
+    where = torch.randint(0, bits.numel(), (special.numel() * 40,), generator=g).to(dev)
+    bits[where] = special.repeat(40)
+    return x, y
+
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C2, name="C2-bf16-store", S=4), 60),
+    (wl.variant(wl.C5, name="C5-bf16-store", K=300, S=12, shape=(264,), b=512, c=200, r=150), 25),   # 33 stored vectors per row: ragged tiles
+    (wl.variant(wl.C3, name="C3-bf16-store", K=50, S=6), 20),                                       # 301 056-byte stored rows
+], ids=["C2", "C5", "C3"])
+def test_float32_samples_stored_as_bfloat16(w, steps):
+    buf, orc = run_parity(w, steps=steps, check_state_every=max(1, steps // 2), store_bf16=True)
+    assert buf.buf_x.dtype == torch.bfloat16 and buf.row_bytes == w.row_bytes // 2
+
+
+def test_bfloat16_storage_rounds_every_special_value_like_the_oracle(monkeypatch):
+    w = wl.variant(wl.C2, name="C2-bf16-special", S=3, c=64, r=64)
+    monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _special_values_batch(ww, step, dev))
+    run_parity(w, steps=12, check_state_every=4, store_bf16=True)
+
+
+def test_bfloat16_storage_with_a_policy_variant_and_the_single_call():
+    w = wl.variant(wl.C5, name="C5-bf16-fifo", K=40, S=16, shape=(64,), b=512, c=200, r=150)
+    run_parity(w, steps=15, store_bf16=True, policy=POLICIES["bernoulli-fifo"], single_call=True)
+
+
+def test_storage_variant_argument_checks():
+    rb = _rb()
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_BF16)
+    assert rc == rb.RB_OK
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_EINVAL      # samples are not binary32
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (4,), rb.RB_F32)
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_EINVAL      # 16-byte samples: a stored row would be 8 bytes
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_F32)
+    assert rb.rb_set_storage(h, 2) == rb.RB_EINVAL
+    assert rb.rb_query_sizes(h)[1] == 4 * 2 * 32
+    assert rb.rb_set_storage(h, rb.RB_STORE_BF16) == rb.RB_OK
+    assert rb.rb_query_sizes(h)[1] == 4 * 2 * 16
+    assert rb.rb_set_storage(h, rb.RB_STORE_SAME) == rb.RB_OK
+    rb.rb_destroy(h)
+    buf = rb.RehearsalBuffer(4, 2, (8,), torch.float32)
+    assert rb.rb_set_storage(buf.handle, rb.RB_STORE_BF16) == rb.RB_ESTATE   # already bound
+
+
 # ------------------------------------------------ several steps from one call ---
 
 @pytest.mark.parametrize("w", [
