@@ -26,7 +26,8 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # HBM bytes per launch of the dominant kernel as counted by two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
 # known size; the text summaries with the exact commands are kept under profiles/.
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77297509}
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76928312,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77297208}
 
 
 def log(*a):
@@ -85,9 +86,10 @@ class Rig:
         fill, _, _ = self.buf.read_state()
         assert int(fill.sum()) == total, (int(fill.sum()), total)
 
-    def enqueue(self, n, do_update=True, do_sample=True, single_call=False, many=0):
+    def enqueue(self, n, do_update=True, do_sample=True, single_call=False, many=0, ahead=False):
         """Enqueue n consecutive steps on the side stream (no synchronisation).
-        many: hand the steps to rb_update_sample_many, `many` of them per call (n a multiple of the pool size)."""
+        many: hand the steps to rb_update_sample_many, `many` of them per call.
+        ahead: with single_call, announce the next pool slot's labels before every call (plan-ahead form)."""
         w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
         upd, smp, both = rb.rb_update, rb.rb_sample_augment, rb.rb_update_sample
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
@@ -108,6 +110,8 @@ class Rig:
         for _ in range(n):
             bx, by, ox, oy = args[t % P]
             if single_call:
+                if ahead:
+                    rb.rb_announce_next(h, args[(t + 1) % P][1])
                 rc = both(h, bx, by, b, c, r, seed, t, ox, oy)
                 if rc:
                     raise RuntimeError(f"rb_update_sample -> {rc}")
@@ -259,11 +263,16 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     rig = Rig(w, torch, rb, wl)
     if prefill:
         rig.prefill()
-    rig.enqueue(warmup, single_call=True)
+    # One launch per step is possible for at most 64 candidates and representatives and at most 1024 classes;
+    # the labels of the next mini-batch are then announced before every call (they are resident, like every
+    # input), so that each launch also plans the following step and only moves rows itself.
+    fused = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
+    rig.enqueue(warmup, single_call=True, ahead=fused)
     torch.cuda.synchronize()
     # headline: the single-call primitive, K steps enqueued back to back on the side stream
-    ms = rig.timed(steps, single_call=True)
+    ms = rig.timed(steps, single_call=True, ahead=fused)
     n_side = min(steps, 1000)
+    ms_plain = rig.timed(n_side, single_call=True)        # the same call without the announcement
     ms_two = rig.timed(n_side)
     ms_many = rig.timed(n_side, many=min(rig.P, 64))      # 64 steps per host call
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
@@ -272,12 +281,12 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     ms_update = rig.timed(n_side, do_sample=False)
     ms_sample = rig.timed(n_side, do_update=False)
     fill, last_n, flags = rig.buf.read_state()
-    fused = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
     res = {
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": 1 if fused else 2,
+        "launches_per_step": 1 if fused else 2, "next_labels_announced": fused,
+        "not_announced_ms_per_step": ms_plain, "not_announced_gb_per_s": w.bytes_per_step() / (ms_plain * 1e-3) / 1e9,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
         "many_call_ms_per_step": ms_many,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
@@ -345,7 +354,8 @@ def main():
     ap.add_argument("--no-overlap", action="store_true")
     ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
-                    help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, then 3 plain copies "
+                    help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, 120 single-call steps with "
+                         "the next labels announced, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -364,6 +374,7 @@ def main():
             rig.prefill()
         rig.enqueue(120)
         rig.enqueue(120, single_call=True)
+        rig.enqueue(120, single_call=True, ahead=True)
         torch.cuda.synchronize()
         nbytes = 256 << 20
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
@@ -407,11 +418,12 @@ def main():
         log(f"[bench] reduced-precision {json.dumps(reduced)}")
 
     # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
-    # (rb_step_small_kernel: every inserted row and every representative row read once and written
-    # once) and its duration is ms_per_step; otherwise it is the gather of rb_sample_augment.
+    # (rb_step_planned_kernel: every inserted row and every representative row read once and written
+    # once, plus the one workgroup that plans the next step) and its duration is ms_per_step;
+    # otherwise it is the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
     if res["launches_per_step"] == 1:
-        kernel, k_ms, k_bytes = "rb_step_small_kernel", res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
+        kernel, k_ms, k_bytes = "rb_step_planned_kernel", res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
     else:
         kernel, k_ms, k_bytes = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
@@ -422,7 +434,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
-                   "api": "rb_update_sample (single call per step)",
+                   "api": "rb_announce_next + rb_update_sample (one launch per step; the launch also plans the next step)"
+                          if res["next_labels_announced"] else "rb_update_sample (single call per step)",
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
         "reps_per_s": round(res["reps_per_s"], 1),

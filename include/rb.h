@@ -173,6 +173,27 @@ int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
                      int64_t r, uint64_t seed, uint64_t step, void *out_x, int64_t *out_y);
 
 /*
+ * Plan-ahead form of the single-launch step, for callers that already hold the
+ * NEXT mini-batch's labels (a prefetching data pipeline): announce them, then
+ * call rb_update_sample (or rb_pipeline_step) as usual.  The launch of that
+ * step then also works out, in one extra workgroup and concurrently with the
+ * row movement, the whole plan of the following step (its b, c, r and seed are
+ * taken to be the same, its step number one higher) and leaves it in the
+ * workspace; the following rb_update_sample call, if it comes with exactly
+ * those labels (the same pointer) and arguments, only moves rows by that plan.
+ * Results are bit for bit those of the plain calls.  An announcement serves the
+ * one next rb_update_sample call; if the following call does not match what
+ * was planned, or any other call on the handle comes first, the plan is
+ * dropped and nothing is lost but the time it took.  Used when the step is
+ * eligible for the single launch (see rb_update_sample); ignored otherwise.
+ * next_batch_y: device, b int64 labels that must be in place, as far as the
+ * bound stream is concerned, when the announcing step is enqueued, and stay
+ * unchanged until the step they belong to has run; null withdraws an
+ * announcement.  rb_update_sample_many announces for itself.
+ */
+int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
+
+/*
  * n consecutive rb_update_sample steps from one call, for callers that have
  * several mini-batches ready (e.g. a prefetching data pipeline) and want to
  * pay the host side of the call once: step i uses batch_x[i], batch_y[i],

@@ -24,7 +24,7 @@ RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
     "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
-    "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
+    "rb_announce_next", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -51,6 +51,7 @@ def _load():
     L.rb_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
     L.rb_update_sample.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp]
+    L.rb_announce_next.argtypes = [vp, vp]
     L.rb_update_sample_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp)]
     L.rb_pipeline_create.argtypes = [C.POINTER(vp), vp]
     L.rb_pipeline_step.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp, vp, C.POINTER(i64)]
@@ -133,6 +134,10 @@ def rb_sample_augment(rb, r, seed, step, out_x, out_y):
 def rb_update_sample(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y):
     return _L.rb_update_sample(rb, _ptr(batch_x), _ptr(batch_y), int(b), int(c), int(r), int(seed), int(step),
                                _ptr(out_x), _ptr(out_y))
+
+
+def rb_announce_next(rb, next_batch_y):
+    return _L.rb_announce_next(rb, _ptr(next_batch_y))
 
 
 def pointer_array(items):
@@ -264,6 +269,12 @@ class RehearsalBuffer:
             assert out_x.shape[0] >= r and out_y.shape[0] >= r
             assert out_x.device == self.device and out_y.device == self.device
         _check(rb_sample_augment(self.handle, r, seed, step, out_x, out_y), "rb_sample_augment")
+
+    def announce_next(self, next_batch_y):
+        """Labels of the next mini-batch (or None), so that the next update_sample also plans the step after it."""
+        if next_batch_y is not None:
+            assert next_batch_y.is_contiguous() and next_batch_y.dtype == torch.int64
+        _check(rb_announce_next(self.handle, next_batch_y), "rb_announce_next")
 
     def update_sample(self, batch_x, batch_y, c, r, seed, step, out_x, out_y):
         assert batch_x.is_contiguous() and batch_y.is_contiguous() and batch_y.dtype == torch.int64

@@ -25,6 +25,7 @@
 #include "rb_device.h"
 #include "rb_kernels_general.h"
 #include "rb_kernels_small.h"
+#include "rb_kernels_planned.h"
 #include "rb_kernels_aux.h"
 
 // ===========================================================================
@@ -53,6 +54,15 @@ struct rb_buffer {
     int selection, eviction;
     size_t off_aux[2];
     int64_t updates;         // rb_update calls since the last rb_bind
+    // plan-ahead form of the single-launch step
+    size_t off_tbl[2];       // the two plan tables
+    int tbl_next;            // table the next plan is written to
+    int tbl_planned;         // table that holds the pending plan
+    bool plan_valid;         // a step has been planned (and the fill counts advanced) but not yet executed
+    const int64_t* plan_y;   // ... for these arguments
+    int64_t plan_b, plan_c, plan_r;
+    uint64_t plan_seed, plan_step;
+    const int64_t* next_y;   // announced labels of the next mini-batch, consumed by the next rb_update_sample
 };
 
 namespace {
@@ -197,6 +207,97 @@ Seed make_seed(uint64_t seed, uint64_t step)
     return s;
 }
 
+template <bool NT, bool PLAN_NEXT>
+hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: rb_step_planned_kernel<1, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 2: rb_step_planned_kernel<2, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 4: rb_step_planned_kernel<4, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
+    default: rb_step_planned_kernel<8, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
+    }
+    return hipGetLastError();
+}
+
+// A step that was planned ahead but will not be executed as planned: the fill counts go back to
+// the copy the planner read (it only wrote the other one).
+void discard_plan(rb_buffer* rb)
+{
+    if (rb->plan_valid) {
+        rb->cur ^= 1;
+        rb->plan_valid = false;
+    }
+}
+
+PlanArgs make_plan(const rb_buffer* rb, const int64_t* batch_y, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t step)
+{
+    PlanArgs p;
+    p.batch_y = batch_y;
+    p.fill_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    p.fill_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_fill[rb->cur ^ 1]);
+    p.chunk_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_chunk[rb->cur ^ 1]);
+    p.table = rb->ws + rb->off_tbl[rb->tbl_next];
+    p.sd = make_seed(seed, step);
+    p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
+    p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
+    p.S = rb->S;
+    return p;
+}
+
+// Host bookkeeping after a plan has been enqueued.
+void plan_enqueued(rb_buffer* rb, const int64_t* batch_y, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t step)
+{
+    rb->cur ^= 1;
+    rb->tbl_planned = rb->tbl_next;
+    rb->tbl_next ^= 1;
+    rb->plan_valid = true;
+    rb->plan_y = batch_y; rb->plan_b = b; rb->plan_c = c; rb->plan_r = r; rb->plan_seed = seed; rb->plan_step = step;
+}
+
+// One step of the plan-ahead form: plan it now unless the previous launch already did, move its
+// rows by the table, and let the same launch plan the following step when its labels are known.
+int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
+                 uint64_t seed, uint64_t step, void* out_x, int64_t* out_y, const int64_t* next_y)
+{
+    if (!rb->plan_valid) {
+        const PlanArgs now = make_plan(rb, batch_y, b, c, r, seed, step);
+        rb_plan_kernel<<<dim3(1), TPB, (size_t)b * 8, rb->stream>>>(now);
+        if (hipGetLastError() != hipSuccess) return RB_EHIP;
+        plan_enqueued(rb, batch_y, b, c, r, seed, step);
+    }
+    const Shape sh = plan_shape(rb, c + r, TPB);
+    MoveArgs m;
+    m.batch_x = static_cast<const vec16*>(batch_x);
+    m.buf_x = static_cast<vec16*>(rb->buf_x);
+    m.buf_y = rb->buf_y;
+    m.out_x = static_cast<vec16*>(out_x);
+    m.out_y = out_y;
+    m.table = rb->ws + rb->off_tbl[rb->tbl_planned];
+    m.state = reinterpret_cast<DevState*>(rb->ws);
+    m.c = (int32_t)c; m.r = (int32_t)r;
+    m.S = rb->S;
+    m.row_vec = rb->row_vec;
+    m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
+    const int64_t movers = (c + r) * sh.tpr;
+    rb->plan_valid = false;                     // this step is being executed
+    hipError_t e;
+    if (next_y) {
+        const PlanArgs next = make_plan(rb, next_y, b, c, r, seed, step + 1);
+        const dim3 grid((unsigned)(movers + 1));
+        e = rb->opt_nt ? launch_planned<true, true>(m, next, sh.unroll, grid, (size_t)b * 8, rb->stream)
+                       : launch_planned<false, true>(m, next, sh.unroll, grid, (size_t)b * 8, rb->stream);
+        if (e == hipSuccess) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
+    } else {
+        PlanArgs none = {};
+        const dim3 grid((unsigned)movers);
+        e = rb->opt_nt ? launch_planned<true, false>(m, none, sh.unroll, grid, 0, rb->stream)
+                       : launch_planned<false, false>(m, none, sh.unroll, grid, 0, rb->stream);
+    }
+    if (e != hipSuccess) return RB_EHIP;
+    rb->updates += 1;
+    return RB_OK;
+}
+
 // What the host can check of the arguments of one update + sample step.
 int check_step(const rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
                const void* out_x, const int64_t* out_y)
@@ -263,7 +364,10 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_chunk[1] = off; off += chunk_bytes;
     rb->off_aux[0] = off; off += fill_bytes;
     rb->off_aux[1] = off; off += fill_bytes;
+    rb->off_tbl[0] = off; off += PLAN_BYTES;
+    rb->off_tbl[1] = off; off += PLAN_BYTES;
     rb->ws_bytes = off;
+    rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
     rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
     rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1;
     *out = rb;
@@ -309,6 +413,7 @@ int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* h
     rb->stream = st;
     rb->cur = 0;
     rb->updates = 0;
+    rb->plan_valid = false; rb->next_y = nullptr; rb->tbl_next = 0;
     rb->bound = true;
     return RB_OK;
 }
@@ -338,6 +443,7 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b) return RB_EINVAL;
     if (!aligned(batch_x, 16) || !aligned(batch_y, 8)) return RB_EINVAL;
     if (!rb->bound) return RB_ESTATE;
+    discard_plan(rb);
     if (c == 0) return RB_OK;
 
     const bool variant = rb->selection != RB_SELECT_EXACT || rb->eviction != RB_EVICT_UNIFORM;
@@ -387,6 +493,7 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     if (!rb || r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
     if (r > 0 && (!out_x || !out_y || !aligned(out_x, 16) || !aligned(out_y, 8))) return RB_EINVAL;
     if (!rb->bound) return RB_ESTATE;
+    discard_plan(rb);
     if (r == 0) return RB_OK;
 
     const bool widen = rb->storage == RB_STORE_BF16;
@@ -420,6 +527,13 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
 
     const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
                        rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
+    const int64_t* next_y = rb->next_y;
+    rb->next_y = nullptr;                        // an announcement serves one call
+    if (rb->plan_valid && !(fused && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&
+                            rb->plan_seed == seed && rb->plan_step == step))
+        discard_plan(rb);
+    if (fused && (rb->plan_valid || next_y))
+        return step_planned(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y, next_y);
     if (!fused) {
         const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);
         if (rc != RB_OK) return rc;
@@ -458,6 +572,14 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     return RB_OK;
 }
 
+int rb_announce_next(rb_buffer* rb, const int64_t* next_batch_y)
+{
+    if (!rb) return RB_EINVAL;
+    if (next_batch_y && !aligned(next_batch_y, 8)) return RB_EINVAL;
+    rb->next_y = next_batch_y;
+    return RB_OK;
+}
+
 int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y,
                           int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
                           void* const* out_x, int64_t* const* out_y)
@@ -469,6 +591,7 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
         if (bad != RB_OK) return bad;
     }
     for (int64_t i = 0; i < n; ++i) {
+        rb->next_y = i + 1 < n ? batch_y[i + 1] : nullptr;      // the next step's labels are known: plan ahead
         const int rc = rb_update_sample(rb, batch_x[i], batch_y[i], b, c, r, seed, first_step + (uint64_t)i,
                                         r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (rc != RB_OK) return rc;      // only a failed launch can get here
@@ -548,6 +671,7 @@ int rb_read_state(rb_buffer* rb, int32_t* fill_host, int64_t* last_n_host, uint3
 {
     if (!rb) return RB_EINVAL;
     if (!rb->bound) return RB_ESTATE;
+    discard_plan(rb);
     if (hipStreamSynchronize(rb->stream) != hipSuccess) return RB_EHIP;
     DevState st;
     if (hipMemcpy(&st, rb->ws, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) return RB_EHIP;

@@ -181,6 +181,98 @@ def test_storage_variant_argument_checks():
     assert rb.rb_set_storage(buf.handle, rb.RB_STORE_BF16) == rb.RB_ESTATE   # already bound
 
 
+# ------------------------------------------------------- plan-ahead steps ---
+
+def _ahead_run(w, steps, schedule_seed=None):
+    """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
+    broken at random (other labels, other arguments, other calls in between) and the plan must be
+    dropped without a trace."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    batches = [wl.make_batch(w, t, dev) for t in range(steps + 1)]
+    batches = [(x.contiguous(), y.contiguous()) for x, y in batches]
+    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
+    rng = np.random.default_rng(schedule_seed)
+    for t in range(steps):
+        x, y = batches[t]
+        c, r = w.c, w.r
+        parity_util._bytes(out_x).fill_(SENTINEL)
+        out_y.fill_(-7)
+        what = "keep" if schedule_seed is None else rng.choice(["keep", "keep", "keep", "other-labels", "other-c", "two-calls",
+                                                                "read-state", "no-announce"])
+        if what != "no-announce":
+            buf.announce_next(batches[t + 1][1])
+        if what == "other-labels":              # the step that comes is not the one that was announced
+            y = y.clone()
+        if what == "other-c":
+            c = max(1, w.c - 1)
+        if what == "read-state":
+            assert np.array_equal(buf.read_state()[0], orc.fill)
+        if what == "two-calls":
+            buf.update(x, y, c, w.lib_seed, t)
+            buf.sample_augment(r, w.lib_seed, t, out_x, out_y)
+        else:
+            buf.update_sample(x, y, c, r, w.lib_seed, t, out_x, out_y)
+        orc.update(parity_util._bytes(x).cpu().numpy(), y.cpu().numpy(), c, w.lib_seed, t)
+        ref = np.full((r, w.row_bytes), SENTINEL, dtype=np.uint8)
+        n, ref_x, ref_y = orc.sample_augment(r, w.lib_seed, t, out_x=ref)
+        tag = f"{w.name} step {t} ({what})"
+        assert np.array_equal(out_y.cpu().numpy(), ref_y), f"{tag}: out_y differs"
+        assert np.array_equal(parity_util._bytes(out_x).cpu().numpy(), ref_x), f"{tag}: out_x differs (n={n})"
+        if (t + 1) % max(1, steps // 3) == 0:
+            compare_buffers(buf, orc, tag)
+            assert buf.read_state()[1] == n
+    compare_buffers(buf, orc, f"{w.name} final")
+    assert buf.read_state()[2] == orc.flags
+
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.C1, 100),                                                                   # fills up: append, replace, collisions
+    (wl.variant(wl.C4, name="C4-S8-ahead", S=8, shape=(3, 32, 32)), 80),            # Zipf head: several overwrites of one class per step
+    (wl.variant(wl.C1, name="C1-one-class-ahead", K=1, S=7, c=16, r=16), 40),       # every representative competes with this step's writes
+    (wl.variant(wl.C1, name="C1-r-large-ahead", S=3, c=16, r=64, b=64), 40),        # r above what is stored, then r = F
+    (wl.variant(wl.C2, name="C2-odd-b-ahead", b=77, c=33, r=21, S=2), 60),
+    (wl.variant(wl.C3, name="C3-S4-ahead", S=4, K=1000), 40),                       # full-size rows, many tiles
+    (wl.variant(wl.C5, name="C5-fallback-ahead", K=2000, S=4, shape=(64,), b=256, c=100, r=30), 15),   # not eligible: announcement ignored
+], ids=["C1", "C4-S8", "one-class", "r-large", "odd-b", "C3-S4", "not-eligible"])
+def test_plan_ahead_steps(w, steps):
+    _ahead_run(w, steps)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_plan_ahead_survives_broken_promises(seed):
+    _ahead_run(wl.variant(wl.C4, name=f"C4-S8-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=seed)
+    _ahead_run(wl.variant(wl.C1, name=f"C1-promises-{seed}"), 90, schedule_seed=seed + 10)
+
+
+def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    x0, y0 = wl.make_batch(w, 0, dev)
+    x1, y1 = wl.make_batch(w, 1, dev)
+    y1 = torch.full_like(y1, w.K + 5)                  # every candidate of step 1 is out of range
+    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
+    buf.announce_next(y1)
+    buf.update_sample(x0, y0, w.c, w.r, 0, 0, out_x, out_y)      # plans step 1, which has the bad labels
+    assert buf.read_state()[2] == 0                              # ... but step 1 has not run (and its plan is dropped here)
+    buf.announce_next(None)
+    buf.update_sample(x1, y1, w.c, w.r, 0, 1, out_x, out_y)
+    assert buf.read_state()[2] == rb.RB_FLAG_BAD_LABEL
+    # the same through the planned step itself
+    buf2 = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    buf2.announce_next(y1)
+    buf2.update_sample(x0, y0, w.c, w.r, 0, 0, out_x, out_y)
+    buf2.update_sample(x1, y1, w.c, w.r, 0, 1, out_x, out_y)     # moves rows by the plan: none is stored
+    fill, last_n, flags = buf2.read_state()
+    assert flags == rb.RB_FLAG_BAD_LABEL and int(fill.sum()) == w.c and last_n == min(w.r, w.c)
+
+
 # ------------------------------------------------ several steps from one call ---
 
 @pytest.mark.parametrize("w", [
