@@ -15,6 +15,7 @@ constexpr int TPB = 256;               // threads per workgroup: four 64-wide wa
 constexpr int WAVE = 64;
 constexpr int NWAVE = TPB / WAVE;
 constexpr int CH = 256;                // classes per chunk of the two-level fill index
+constexpr int XCDS = 8;               // accelerator dies of the chip; workgroup w of a grid runs on die w % XCDS
 constexpr int TILE_UNIT = 64;          // granularity, in 16-byte vectors, at which a row is cut into tiles
 constexpr uint32_t PURPOSE_SELECT = 1; // counter word that separates the three kinds of draws
 constexpr uint32_t PURPOSE_EVICT = 2;

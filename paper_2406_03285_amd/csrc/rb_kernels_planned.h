@@ -281,7 +281,19 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
         return;
     }
     const int mover = blockIdx.x - (PLAN_NEXT ? 1 : 0);
-    const int e = mover / m.tpr, tile = mover % m.tpr;
+    // Consecutive workgroups go to the eight accelerator dies in turn, and each die translates
+    // addresses for itself: all tiles of a row are given to workgroups of one die (rows are dealt
+    // to the dies in turn), so that a die touches an eighth of the rows' pages instead of all.
+    int e, tile;
+    const int rows = m.c + m.r, dealt = rows / XCDS * XCDS;
+    if (mover < dealt * m.tpr) {
+        const int die = mover % XCDS, i = mover / XCDS;
+        e = i / m.tpr * XCDS + die;
+        tile = i % m.tpr;
+    } else {
+        e = mover / m.tpr;
+        tile = mover % m.tpr;
+    }
     const PlanHeader* head = reinterpret_cast<const PlanHeader*>(m.table);
     const PlanEntry en = reinterpret_cast<const PlanEntry*>(m.table + sizeof(PlanHeader))[e];
     int64_t v_lo, v_hi;
