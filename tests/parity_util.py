@@ -126,3 +126,50 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     if final_check:
         compare_buffers(buf, orc, f"{w.name} final")
     return buf, orc
+
+
+def run_ahead_parity(w, steps, schedule_seed=None):
+    """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
+    broken at random (other labels, other arguments, other calls in between) and the plan must be
+    dropped without a trace."""
+    import paper_2406_03285_amd as rb
+
+    dev = torch.device("cuda:0")
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    batches = [wl.make_batch(w, t, dev) for t in range(steps + 1)]
+    batches = [(x.contiguous(), y.contiguous()) for x, y in batches]
+    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
+    rng = np.random.default_rng(schedule_seed)
+    for t in range(steps):
+        x, y = batches[t]
+        c, r = w.c, w.r
+        _bytes(out_x).fill_(SENTINEL)
+        out_y.fill_(-7)
+        what = "keep" if schedule_seed is None else rng.choice(["keep", "keep", "keep", "other-labels", "other-c", "two-calls",
+                                                                "read-state", "no-announce"])
+        if what != "no-announce":
+            buf.announce_next(batches[t + 1][1])
+        if what == "other-labels":              # the step that comes is not the one that was announced
+            y = y.clone()
+        if what == "other-c":
+            c = max(1, w.c - 1)
+        if what == "read-state":
+            assert np.array_equal(buf.read_state()[0], orc.fill)
+        if what == "two-calls":
+            buf.update(x, y, c, w.lib_seed, t)
+            buf.sample_augment(r, w.lib_seed, t, out_x, out_y)
+        else:
+            buf.update_sample(x, y, c, r, w.lib_seed, t, out_x, out_y)
+        orc.update(_bytes(x).cpu().numpy(), y.cpu().numpy(), c, w.lib_seed, t)
+        ref = np.full((r, w.row_bytes), SENTINEL, dtype=np.uint8)
+        n, ref_x, ref_y = orc.sample_augment(r, w.lib_seed, t, out_x=ref)
+        tag = f"{w.name} step {t} ({what})"
+        assert np.array_equal(out_y.cpu().numpy(), ref_y), f"{tag}: out_y differs"
+        assert np.array_equal(_bytes(out_x).cpu().numpy(), ref_x), f"{tag}: out_x differs (n={n})"
+        if (t + 1) % max(1, steps // 3) == 0:
+            compare_buffers(buf, orc, tag)
+            assert buf.read_state()[1] == n
+    compare_buffers(buf, orc, f"{w.name} final")
+    assert buf.read_state()[2] == orc.flags

@@ -12,7 +12,7 @@ import torch
 import rb_workloads as wl
 from oracle import rbo
 import parity_util
-from parity_util import SENTINEL, compare_buffers, run_parity
+from parity_util import SENTINEL, compare_buffers, run_ahead_parity, run_parity
 
 pytestmark = pytest.mark.gpu
 
@@ -183,52 +183,6 @@ def test_storage_variant_argument_checks():
 
 # ------------------------------------------------------- plan-ahead steps ---
 
-def _ahead_run(w, steps, schedule_seed=None):
-    """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
-    broken at random (other labels, other arguments, other calls in between) and the plan must be
-    dropped without a trace."""
-    rb = _rb()
-    dev = torch.device("cuda:0")
-    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
-    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
-    batches = [wl.make_batch(w, t, dev) for t in range(steps + 1)]
-    batches = [(x.contiguous(), y.contiguous()) for x, y in batches]
-    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
-    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
-    rng = np.random.default_rng(schedule_seed)
-    for t in range(steps):
-        x, y = batches[t]
-        c, r = w.c, w.r
-        parity_util._bytes(out_x).fill_(SENTINEL)
-        out_y.fill_(-7)
-        what = "keep" if schedule_seed is None else rng.choice(["keep", "keep", "keep", "other-labels", "other-c", "two-calls",
-                                                                "read-state", "no-announce"])
-        if what != "no-announce":
-            buf.announce_next(batches[t + 1][1])
-        if what == "other-labels":              # the step that comes is not the one that was announced
-            y = y.clone()
-        if what == "other-c":
-            c = max(1, w.c - 1)
-        if what == "read-state":
-            assert np.array_equal(buf.read_state()[0], orc.fill)
-        if what == "two-calls":
-            buf.update(x, y, c, w.lib_seed, t)
-            buf.sample_augment(r, w.lib_seed, t, out_x, out_y)
-        else:
-            buf.update_sample(x, y, c, r, w.lib_seed, t, out_x, out_y)
-        orc.update(parity_util._bytes(x).cpu().numpy(), y.cpu().numpy(), c, w.lib_seed, t)
-        ref = np.full((r, w.row_bytes), SENTINEL, dtype=np.uint8)
-        n, ref_x, ref_y = orc.sample_augment(r, w.lib_seed, t, out_x=ref)
-        tag = f"{w.name} step {t} ({what})"
-        assert np.array_equal(out_y.cpu().numpy(), ref_y), f"{tag}: out_y differs"
-        assert np.array_equal(parity_util._bytes(out_x).cpu().numpy(), ref_x), f"{tag}: out_x differs (n={n})"
-        if (t + 1) % max(1, steps // 3) == 0:
-            compare_buffers(buf, orc, tag)
-            assert buf.read_state()[1] == n
-    compare_buffers(buf, orc, f"{w.name} final")
-    assert buf.read_state()[2] == orc.flags
-
-
 @pytest.mark.parametrize("w,steps", [
     (wl.C1, 100),                                                                   # fills up: append, replace, collisions
     (wl.variant(wl.C4, name="C4-S8-ahead", S=8, shape=(3, 32, 32)), 80),            # Zipf head: several overwrites of one class per step
@@ -239,13 +193,13 @@ def _ahead_run(w, steps, schedule_seed=None):
     (wl.variant(wl.C5, name="C5-fallback-ahead", K=2000, S=4, shape=(64,), b=256, c=100, r=30), 15),   # not eligible: announcement ignored
 ], ids=["C1", "C4-S8", "one-class", "r-large", "odd-b", "C3-S4", "not-eligible"])
 def test_plan_ahead_steps(w, steps):
-    _ahead_run(w, steps)
+    run_ahead_parity(w, steps)
 
 
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_plan_ahead_survives_broken_promises(seed):
-    _ahead_run(wl.variant(wl.C4, name=f"C4-S8-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=seed)
-    _ahead_run(wl.variant(wl.C1, name=f"C1-promises-{seed}"), 90, schedule_seed=seed + 10)
+    run_ahead_parity(wl.variant(wl.C4, name=f"C4-S8-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=seed)
+    run_ahead_parity(wl.variant(wl.C1, name=f"C1-promises-{seed}"), 90, schedule_seed=seed + 10)
 
 
 def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
