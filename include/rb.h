@@ -182,9 +182,12 @@ int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
  * workspace; the following rb_update_sample call, if it comes with exactly
  * those labels (the same pointer) and arguments, only moves rows by that plan.
  * Results are bit for bit those of the plain calls.  An announcement serves the
- * one next rb_update_sample call; if the following call does not match what
- * was planned, or any other call on the handle comes first, the plan is
- * dropped and nothing is lost but the time it took.  Used when the step is
+ * one next rb_update_sample call and is forgotten if any other call on the
+ * handle (rb_update, rb_sample_augment, rb_read_state, ...) comes first; if
+ * the call after the announcing step does not match what was planned, or any
+ * other call comes first, the plan is dropped and nothing is lost but the time
+ * it took.  The match is by address: memory that held announced labels must
+ * not be given other contents and passed as the next step's labels.  Used when the step is
  * eligible for the single launch (see rb_update_sample); ignored otherwise.
  * next_batch_y: device, b int64 labels that must be in place, as far as the
  * bound stream is concerned, when the announcing step is enqueued, and stay

@@ -219,14 +219,17 @@ hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int unroll, d
     return hipGetLastError();
 }
 
-// A step that was planned ahead but will not be executed as planned: the fill counts go back to
-// the copy the planner read (it only wrote the other one).
+// Called by every entry point other than rb_update_sample.  A step that was planned ahead will not
+// be executed as planned: the fill counts go back to the copy the planner read (it only wrote the
+// other one).  An announcement that has not been used yet is forgotten as well: it was made for the
+// call that should have come next.
 void discard_plan(rb_buffer* rb)
 {
     if (rb->plan_valid) {
         rb->cur ^= 1;
         rb->plan_valid = false;
     }
+    rb->next_y = nullptr;
 }
 
 PlanArgs make_plan(const rb_buffer* rb, const int64_t* batch_y, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t step)

@@ -137,20 +137,23 @@ def run_ahead_parity(w, steps, schedule_seed=None):
     dev = torch.device("cuda:0")
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
-    batches = [wl.make_batch(w, t, dev) for t in range(steps + 1)]
-    batches = [(x.contiguous(), y.contiguous()) for x, y in batches]
+    def batch(t):
+        x, y = wl.make_batch(w, t, dev)
+        return x.contiguous(), y.contiguous()
+
+    nxt = batch(0)
     out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
     out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
     rng = np.random.default_rng(schedule_seed)
     for t in range(steps):
-        x, y = batches[t]
+        (x, y), nxt = nxt, batch(t + 1)         # the next mini-batch is there before this step is enqueued
         c, r = w.c, w.r
         _bytes(out_x).fill_(SENTINEL)
         out_y.fill_(-7)
         what = "keep" if schedule_seed is None else rng.choice(["keep", "keep", "keep", "other-labels", "other-c", "two-calls",
                                                                 "read-state", "no-announce"])
         if what != "no-announce":
-            buf.announce_next(batches[t + 1][1])
+            buf.announce_next(nxt[1])
         if what == "other-labels":              # the step that comes is not the one that was announced
             y = y.clone()
         if what == "other-c":

@@ -196,10 +196,43 @@ def test_plan_ahead_steps(w, steps):
     run_ahead_parity(w, steps)
 
 
+@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40)], ids=["C3", "C4"])
+def test_plan_ahead_at_full_size(w, steps):
+    """The configuration the bench times: real shapes, one launch per step, next labels announced."""
+    run_ahead_parity(w, w.steps if FULL else steps)
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_plan_ahead_survives_broken_promises(seed):
     run_ahead_parity(wl.variant(wl.C4, name=f"C4-S8-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=seed)
     run_ahead_parity(wl.variant(wl.C1, name=f"C1-promises-{seed}"), 90, schedule_seed=seed + 10)
+
+
+def test_an_announcement_that_was_not_used_is_forgotten():
+    """Labels are announced, then other calls come instead of rb_update_sample.  The announcement
+    must not linger and be taken for the labels of a later step that happens to reuse the memory."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    out_x = torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    out_y = torch.empty(w.r, dtype=torch.int64, device=dev)
+    lab = torch.empty(w.b, dtype=torch.int64, device=dev)          # one piece of memory for every step's labels
+    for t in range(12):
+        x, y = wl.make_batch(w, t, dev)
+        lab.copy_(y)
+        if t % 3 == 0:
+            buf.announce_next(lab)                                 # never followed by rb_update_sample
+            buf.update(x, lab, w.c, w.lib_seed, t)
+            buf.sample_augment(w.r, w.lib_seed, t, out_x, out_y)
+        else:
+            buf.update_sample(x, lab, w.c, w.r, w.lib_seed, t, out_x, out_y)
+        orc.update(parity_util._bytes(x).cpu().numpy(), y.cpu().numpy(), w.c, w.lib_seed, t)
+        n, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t)
+        assert np.array_equal(out_y.cpu().numpy(), ref_y), f"step {t}"
+        assert np.array_equal(parity_util._bytes(out_x).cpu().numpy()[:n], ref_x[:n]), f"step {t}"
+    compare_buffers(buf, orc, "final")
 
 
 def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
