@@ -1,7 +1,8 @@
 // Rehearsal-buffer hot path for gfx950 (MI355X): the C ABI of include/rb.h (host side); the
 // kernels are in rb_kernels_small.h (at most 64 candidates / representatives, and the
-// single-launch step), rb_kernels_general.h (any counts, policy variants) and rb_kernels_aux.h,
-// their common device code in rb_device.h.
+// single-launch step), rb_kernels_planned.h (the same step with its plan made during the previous
+// launch), rb_kernels_general.h (any counts, policy variants, reduced-precision storage) and
+// rb_kernels_aux.h, their common device code in rb_device.h.
 //
 // One kernel launch per hot call.  Every workgroup first re-derives, in LDS,
 // the few integers of the step's plan it needs (which mini-batch positions are
@@ -11,10 +12,15 @@
 // hundreds of kilobytes, so recomputing it per workgroup is cheaper than a
 // second, dependent launch.  Nothing is staged through LDS: a row is read once
 // and written once, so the data path is global -> registers -> global.
+// When the labels of the next mini-batch are known in advance (rb_announce_next)
+// the plan is not recomputed per workgroup at all: one workgroup of the previous
+// launch leaves it as a table in the workspace and the step's launch only moves rows.
 //
 // Per-class fill counts are kept twice (ping-pong): an update reads the "old"
 // copy everywhere and a few bookkeeping workgroups write the "new" one, so no
 // workgroup can observe a count another workgroup of the same launch changed.
+// The same two copies let a plan made ahead be dropped: the host just points
+// back at the copy the planner read.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
