@@ -94,8 +94,8 @@ int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *h
  * binary32, which is exact, by rb_sample_augment.  Mini-batches and outputs
  * keep the full row size; buf_x rows shrink to half: call this BEFORE
  * rb_query_sizes / rb_bind (RB_ESTATE once bound).  The sample's byte size
- * must be a multiple of 32.  The general kernels (two launches per step) serve
- * this variant.
+ * must be a multiple of 32.  Served by the general kernels (two launches per
+ * step) and by the plan-ahead form of the single launch (rb_announce_next).
  */
 enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1 };
 int rb_set_storage(rb_buffer *rb, int32_t storage);

@@ -213,14 +213,14 @@ Seed make_seed(uint64_t seed, uint64_t step)
     return s;
 }
 
-template <bool NT, bool PLAN_NEXT>
+template <bool NT, bool BF16>
 hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_step_planned_kernel<1, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
-    case 2: rb_step_planned_kernel<2, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
-    case 4: rb_step_planned_kernel<4, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
-    default: rb_step_planned_kernel<8, NT, PLAN_NEXT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 1: rb_step_planned_kernel<1, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 2: rb_step_planned_kernel<2, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 4: rb_step_planned_kernel<4, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    default: rb_step_planned_kernel<8, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
     }
     return hipGetLastError();
 }
@@ -289,19 +289,18 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
     m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
     const int64_t movers = (c + r) * sh.tpr;
     rb->plan_valid = false;                     // this step is being executed
+    m.plan_next = next_y ? 1 : 0;
+    PlanArgs next = {};
+    if (next_y) next = make_plan(rb, next_y, b, c, r, seed, step + 1);
+    const dim3 grid((unsigned)(movers + m.plan_next));
+    const size_t lds = next_y ? (size_t)b * 8 : 0;
+    const bool bf16 = rb->storage == RB_STORE_BF16;
     hipError_t e;
-    if (next_y) {
-        const PlanArgs next = make_plan(rb, next_y, b, c, r, seed, step + 1);
-        const dim3 grid((unsigned)(movers + 1));
-        e = rb->opt_nt ? launch_planned<true, true>(m, next, sh.unroll, grid, (size_t)b * 8, rb->stream)
-                       : launch_planned<false, true>(m, next, sh.unroll, grid, (size_t)b * 8, rb->stream);
-        if (e == hipSuccess) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
-    } else {
-        PlanArgs none = {};
-        const dim3 grid((unsigned)movers);
-        e = rb->opt_nt ? launch_planned<true, false>(m, none, sh.unroll, grid, 0, rb->stream)
-                       : launch_planned<false, false>(m, none, sh.unroll, grid, 0, rb->stream);
-    }
+    if (rb->opt_nt) e = bf16 ? launch_planned<true, true>(m, next, sh.unroll, grid, lds, rb->stream)
+                             : launch_planned<true, false>(m, next, sh.unroll, grid, lds, rb->stream);
+    else e = bf16 ? launch_planned<false, true>(m, next, sh.unroll, grid, lds, rb->stream)
+                  : launch_planned<false, false>(m, next, sh.unroll, grid, lds, rb->stream);
+    if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
     return RB_OK;
@@ -534,14 +533,16 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     const int bad = check_step(rb, batch_x, batch_y, b, c, r, out_x, out_y);
     if (bad != RB_OK) return bad;
 
-    const bool fused = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
-                       rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
+    // the plan-ahead form covers both storage forms; the kernel that plans and moves in one launch only the plain one
+    const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
+                           rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
+    const bool fused = plannable && rb->storage == RB_STORE_SAME;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call
-    if (rb->plan_valid && !(fused && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&
+    if (rb->plan_valid && !(plannable && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&
                             rb->plan_seed == seed && rb->plan_step == step))
         discard_plan(rb);
-    if (fused && (rb->plan_valid || next_y))
+    if (plannable && (rb->plan_valid || next_y))
         return step_planned(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y, next_y);
     if (!fused) {
         const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);

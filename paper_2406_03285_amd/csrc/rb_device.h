@@ -141,15 +141,16 @@ __device__ __forceinline__ void widen8(const vec16 s, vec16& a, vec16& b)
     b.x = s.z << 16; b.y = s.z & 0xFFFF0000u; b.z = s.w << 16; b.w = s.w & 0xFFFF0000u;
 }
 
-enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2 };
+enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3 };   // bit 0: convert while loading, bit 1: while storing
 
 // ---------------------------------------------------------------------------
 // Row mover: one tile of one row, U vectors per thread in flight.
 // ---------------------------------------------------------------------------
 // W: threads that share the tile (a workgroup or one wavefront).  CV: CV_NARROW - the source row is
 // binary32 (two vectors per vector of the tile), converted to bfloat16 while it is loaded; CV_WIDEN -
-// the destination row is binary32, converted from the tile's bfloat16 while it is stored.  Tile
-// indices always count vectors of the narrow (stored) row.
+// the destination row is binary32, converted from the tile's bfloat16 while it is stored; CV_BOTH -
+// binary32 to binary32 through the bfloat16 a stored copy would hold.  Tile indices always count
+// vectors of the narrow (stored) row.
 template <int U, bool NT, int W = TPB, bool PACED = true, int CV = CV_NONE>
 struct Tile {
     vec16 v[U];
@@ -165,7 +166,7 @@ struct Tile {
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            if (CV == CV_NARROW) {
+            if (CV & CV_NARROW) {
                 const vec16 a = NT ? __builtin_nontemporal_load(src + 2 * i) : src[2 * i];
                 const vec16 b = NT ? __builtin_nontemporal_load(src + 2 * i + 1) : src[2 * i + 1];
                 v[u] = narrow8(a, b);
@@ -185,7 +186,7 @@ struct Tile {
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            if (CV == CV_WIDEN) {
+            if (CV & CV_WIDEN) {
                 vec16 a, b;
                 widen8(v[u], a, b);
                 if (NT) {

@@ -51,6 +51,7 @@ struct MoveArgs {
     int64_t S;
     int64_t row_vec;
     int32_t tpr, tile_vec, tile_rem;
+    int32_t plan_next;        // 1: workgroup 0 plans the next step and the movers start at workgroup 1
 };
 
 // ---------------------------------------------------------------------------
@@ -269,18 +270,19 @@ __global__ void __launch_bounds__(TPB) rb_plan_kernel(const PlanArgs a)
 
 // ---------------------------------------------------------------------------
 // One step by its table: workgroup (e, tile) moves one tile of row e (candidates
-// first, then representatives); with PLAN_NEXT the first workgroup of the grid
+// first, then representatives); with plan_next the first workgroup of the grid
 // plans the next step instead.
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool PLAN_NEXT>
+template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
 __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, const PlanArgs next)
 {
     extern __shared__ uint32_t lds[];
-    if (PLAN_NEXT && blockIdx.x == 0) {        // dispatched first: it has the longest way to go
+    const bool plan_next = m.plan_next != 0;
+    if (plan_next && blockIdx.x == 0) {        // dispatched first: it has the longest way to go
         plan_step(next, lds);
         return;
     }
-    const int mover = blockIdx.x - (PLAN_NEXT ? 1 : 0);
+    const int mover = blockIdx.x - (plan_next ? 1 : 0);
     // Consecutive workgroups go to the eight accelerator dies in turn, and each die translates
     // addresses for itself: all tiles of a row are given to workgroups of one die (rows are dealt
     // to the dies in turn), so that a die touches an eighth of the rows' pages instead of all.
@@ -304,23 +306,30 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
         m.state->last_n = h.n;
         if (h.flags != 0) atomicOr(&m.state->flags, h.flags);
     }
-    const vec16* src;
-    vec16* dst;
+    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.c) {
         if (en.row < 0) return;                 // label outside [0, K), or a later class-mate takes the slot
-        src = m.batch_x + (int64_t)en.pos * m.row_vec;
-        dst = m.buf_x + en.row * m.row_vec;
         if (first) m.buf_y[en.row] = en.label;
-    } else {
-        const int j = e - m.c;
-        if (first) m.out_y[j] = en.label;       // -1 when fewer samples are stored than asked for
-        if (en.label < 0) return;
-        src = en.pos >= 0 ? m.batch_x + (int64_t)en.pos * m.row_vec : m.buf_x + en.row * m.row_vec;
-        dst = m.out_x + (int64_t)j * m.row_vec;
+        Tile<U, NT, TPB, true, BF16 ? CV_NARROW : CV_NONE> t;
+        t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
+        t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
+        return;
     }
-    Tile<U, NT> t;
-    t.load(src, v_lo, v_hi);
-    t.store(dst, v_lo, v_hi);
+    const int j = e - m.c;
+    if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
+    if (en.label < 0) return;
+    vec16* dst = m.out_x + (int64_t)j * m.row_vec * WIDE;
+    if (BF16 && en.pos >= 0) {
+        // forwarded from the mini-batch: what the slot will hold is the row rounded to bfloat16
+        Tile<U, NT, TPB, true, CV_BOTH> t;
+        t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    } else {
+        const vec16* src = en.pos >= 0 ? m.batch_x + (int64_t)en.pos * m.row_vec : m.buf_x + en.row * m.row_vec;
+        Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> t;
+        t.load(src, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    }
 }
 
 }  // namespace

@@ -128,15 +128,21 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     return buf, orc
 
 
-def run_ahead_parity(w, steps, schedule_seed=None):
+def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None):
     """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
     broken at random (other labels, other arguments, other calls in between) and the plan must be
     dropped without a trace."""
     import paper_2406_03285_amd as rb
 
     dev = torch.device("cuda:0")
-    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=torch.bfloat16 if store_bf16 else None)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    if store_bf16:
+        orc.set_storage(rbo.STORE_BF16)
+    if policy is not None:
+        buf.set_policy(*policy)
+        orc.set_policy(*policy)
+
     def batch(t):
         x, y = wl.make_batch(w, t, dev)
         return x.contiguous(), y.contiguous()

@@ -156,6 +156,20 @@ def test_bfloat16_storage_rounds_every_special_value_like_the_oracle(monkeypatch
     run_parity(w, steps=12, check_state_every=4, store_bf16=True)
 
 
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C2, name="C2-bf16-ahead", S=4), 60),                             # replaces from step ~25 on; forwarding through the rounding
+    (wl.variant(wl.C1, name="C1-bf16-one-class-ahead", K=1, S=7, c=16, r=16), 40),  # every representative competes with this step's writes
+    (wl.variant(wl.C3, name="C3-bf16-ahead", K=50, S=6), 25),                       # 301 056-byte stored rows, many tiles
+], ids=["C2", "one-class", "C3"])
+def test_bfloat16_storage_with_plan_ahead_steps(w, steps):
+    run_ahead_parity(w, steps, store_bf16=True)
+
+
+def test_bfloat16_storage_plan_ahead_special_values_and_broken_promises(monkeypatch):
+    monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _special_values_batch(ww, step, dev))
+    run_ahead_parity(wl.variant(wl.C1, name="C1-bf16-special-ahead", K=2, S=5, c=12, r=12), 40, schedule_seed=5, store_bf16=True)
+
+
 def test_bfloat16_storage_with_a_policy_variant_and_the_single_call():
     w = wl.variant(wl.C5, name="C5-bf16-fifo", K=40, S=16, shape=(64,), b=512, c=200, r=150)
     run_parity(w, steps=15, store_bf16=True, policy=POLICIES["bernoulli-fifo"], single_call=True)
