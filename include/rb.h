@@ -114,7 +114,8 @@ int rb_set_storage(rb_buffer *rb, int32_t storage);
  * slots_per_class / n and is dropped otherwise (exact while a class has been
  * offered fewer than 2^31 - 1 samples).
  * With a variant selected the general kernels are used and rb_update_sample
- * enqueues two launches.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update
+ * enqueues two launches; the plan-ahead form of the single launch
+ * (rb_announce_next) also serves FIFO and reservoir with the exact selection.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update
  * was already enqueued since the last rb_bind.
  */
 enum rb_selection { RB_SELECT_EXACT = 0, RB_SELECT_BERNOULLI = 1 };

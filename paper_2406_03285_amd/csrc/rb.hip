@@ -250,6 +250,9 @@ PlanArgs make_plan(const rb_buffer* rb, const int64_t* batch_y, int64_t b, int64
     p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
     p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
     p.S = rb->S;
+    p.eviction = rb->eviction;
+    p.aux_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_aux[rb->cur]);
+    p.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
     return p;
 }
 
@@ -535,8 +538,8 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
 
     // the plan-ahead form covers both storage forms; the kernel that plans and moves in one launch only the plain one
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
-                           rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
-    const bool fused = plannable && rb->storage == RB_STORE_SAME;
+                           rb->selection == RB_SELECT_EXACT;
+    const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call
     if (rb->plan_valid && !(plannable && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&

@@ -37,6 +37,9 @@ struct PlanArgs {
     int32_t b, c, r;
     int32_t K, nchunks;
     int64_t S;
+    int32_t eviction;         // RB_EVICT_*
+    const int32_t* aux_old;   // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
+    int32_t* aux_new;
 };
 
 struct MoveArgs {
@@ -73,6 +76,7 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
     __shared__ int32_t s_old[NCLS];     // fill counts before the step
     __shared__ int32_t s_cnt[NCLS];     // candidates of each class in this step
     __shared__ int32_t s_pre[NCLS];     // stored samples in the classes before each class, after the update
+    __shared__ int32_t s_aux[NCLS];     // per-class state of the FIFO / reservoir strategies before the step
     __shared__ int s_wave[NWAVE];
     __shared__ uint64_t s_bits[WAVE];   // random bits of sampling draw i
     __shared__ __align__(16) int32_t s_ck[WAVE], s_cslot[WAVE], s_cx[WAVE];   // per candidate: class (-1: none), slot, position
@@ -91,8 +95,11 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
         const int q = tid + u * TPB;
         yv[u] = q < b ? a.batch_y[q] : -1;
     }
-    int4 fo = make_int4(0, 0, 0, 0);
-    if (4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+    int4 fo = make_int4(0, 0, 0, 0), ao = make_int4(0, 0, 0, 0);
+    if (4 * tid < a.nchunks * CH) {
+        fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+        if (a.eviction != RB_EVICT_UNIFORM) ao = *reinterpret_cast<const int4*>(a.aux_old + 4 * tid);
+    }
 
     bool active = false;
     int x = 0;
@@ -103,6 +110,7 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
     }
     park_labels(yv, a.batch_y, b, a.K, s_y);
     *reinterpret_cast<int4*>(s_old + 4 * tid) = fo;
+    *reinterpret_cast<int4*>(s_aux + 4 * tid) = ao;
     *reinterpret_cast<int4*>(s_cnt + 4 * tid) = make_int4(0, 0, 0, 0);
     __syncthreads();
 
@@ -132,7 +140,24 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
         nf[u] = (int)(v < a.S ? v : a.S);
         local += nf[u];
     }
-    if (4 * tid < a.nchunks * CH) *reinterpret_cast<int4*>(a.fill_new + 4 * tid) = make_int4(nf[0], nf[1], nf[2], nf[3]);
+    if (4 * tid < a.nchunks * CH) {
+        *reinterpret_cast<int4*>(a.fill_new + 4 * tid) = make_int4(nf[0], nf[1], nf[2], nf[3]);
+        if (a.eviction != RB_EVICT_UNIFORM) {
+            int na[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t before_k = s_aux[4 * tid + u], v = (int64_t)s_old[4 * tid + u] + s_cnt[4 * tid + u];
+                if (a.eviction == RB_EVICT_FIFO) {
+                    // the oldest sample moves on by the number of overwrites
+                    na[u] = (int)((before_k + (v > a.S ? v - a.S : 0)) % a.S);
+                } else {
+                    const int64_t seen = before_k + s_cnt[4 * tid + u];
+                    na[u] = (int)(seen < INT32_MAX ? seen : INT32_MAX);
+                }
+            }
+            *reinterpret_cast<int4*>(a.aux_new + 4 * tid) = make_int4(na[0], na[1], na[2], na[3]);
+        }
+    }
     {
         // a wavefront covers exactly one chunk of CH classes
         const int wsum = lane_read(wave_scan_incl(local), WAVE - 1);
@@ -153,29 +178,44 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
     if (wave == 0) {
         // insertion number within the class: fill0 + class-mates earlier in the mini-batch
         const int64_t fill0 = valid ? s_old[k] : 0;
-        int rank = 0;
+        const int64_t aux0 = valid ? s_aux[k] : 0;
+        int rank = 0, total = 0;
 #pragma unroll 4
         for (int m = 0; m < c; m += 4) {
             const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
             const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
             rank += (int)(km.x == k && xm.x < x) + (int)(km.y == k && xm.y < x) + (int)(km.z == k && xm.z < x) +
                     (int)(km.w == k && xm.w < x);
+            total += (int)(km.x == k) + (int)(km.y == k) + (int)(km.z == k) + (int)(km.w == k);
         }
         const int64_t at = fill0 + rank;
-        const bool over = valid && at >= a.S;          // beyond the capacity: overwrites a drawn slot
         int slot = valid ? (int)at : -1;
         bool beaten = false;
-        if (__ballot(over) != 0) {
-            if (over) slot = (int)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);
-            s_cw[lane] = over ? slot : -2;             // slot an overwriting candidate drew
-            // not stored if a later class-mate overwrites the same slot
+        if (a.eviction == RB_EVICT_FIFO) {
+            // beyond the capacity the oldest sample is overwritten; a candidate is itself overwritten in this
+            // step if a class-mate comes a whole round of S later (the same slot: the later one is what it holds)
+            if (valid && at >= a.S) slot = (int)((aux0 + at - a.S) % a.S);
+            beaten = valid && at + a.S < fill0 + total;
+        } else {
+            const bool reservoir = a.eviction == RB_EVICT_RESERVOIR;
+            bool over = valid && at >= a.S;            // beyond the capacity: overwrites a drawn slot, if it is kept
+            if (__ballot(over) != 0) {
+                if (over) {
+                    const int64_t offers = aux0 + rank < INT32_MAX ? aux0 + rank : INT32_MAX;   // to the class, before this one
+                    const int64_t draw = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, reservoir ? (uint64_t)offers + 1 : (uint64_t)a.S);
+                    over = draw < a.S;                 // reservoir: otherwise the candidate is not kept
+                    slot = over ? (int)draw : -1;
+                }
+                s_cw[lane] = over ? slot : -2;         // slot an overwriting candidate drew
+                // not stored if a later class-mate overwrites the same slot
 #pragma unroll 4
-            for (int m = 0; m < c; m += 4) {
-                const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
-                const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
-                const int4 wm = *reinterpret_cast<const int4*>(s_cw + m);
-                beaten |= (km.x == k && xm.x > x && wm.x == slot) | (km.y == k && xm.y > x && wm.y == slot) |
-                          (km.z == k && xm.z > x && wm.z == slot) | (km.w == k && xm.w > x && wm.w == slot);
+                for (int m = 0; m < c; m += 4) {
+                    const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
+                    const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
+                    const int4 wm = *reinterpret_cast<const int4*>(s_cw + m);
+                    beaten |= (km.x == k && xm.x > x && wm.x == slot) | (km.y == k && xm.y > x && wm.y == slot) |
+                              (km.z == k && xm.z > x && wm.z == slot) | (km.w == k && xm.w > x && wm.w == slot);
+                }
             }
         }
         s_cslot[lane] = slot;                          // -1 without a candidate
@@ -183,7 +223,7 @@ __device__ __forceinline__ void plan_step(const PlanArgs& a, uint32_t* lds)
             PlanEntry e;
             e.pos = x;
             e.label = valid ? k : -1;
-            e.row = (valid && !beaten) ? (int64_t)k * a.S + slot : -1;
+            e.row = (valid && slot >= 0 && !beaten) ? (int64_t)k * a.S + slot : -1;
             entry[lane] = e;
         }
     } else if (wave == 1) {

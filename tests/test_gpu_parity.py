@@ -222,6 +222,25 @@ def test_plan_ahead_survives_broken_promises(seed):
     run_ahead_parity(wl.variant(wl.C1, name=f"C1-promises-{seed}"), 90, schedule_seed=seed + 10)
 
 
+@pytest.mark.parametrize("policy", ["exact-fifo", "exact-reservoir"])
+@pytest.mark.parametrize("w,steps", [
+    (wl.C1, 100),                                                                           # fills up: every strategy replaces
+    (wl.variant(wl.C4, name="C4-S8-ahead-policy", S=8, shape=(3, 32, 32)), 60),             # Zipf head: many class-mates per step
+    (wl.Workload("laps-ahead", 9, 3, 2, (8,), "f32", 64, 64, 64, 30, "normal", "uniform"), 30),   # ~21 candidates per class into 2 slots
+    (wl.variant(wl.C2, name="C2-S3-ahead-policy", S=3), 80),
+], ids=["C1", "C4-S8", "laps", "C2-S3"])
+def test_plan_ahead_with_other_replacement_strategies(policy, w, steps):
+    run_ahead_parity(w, steps, policy=POLICIES[policy])
+
+
+def test_plan_ahead_policy_bf16_and_broken_promises_together():
+    w = wl.variant(wl.C1, name="C1-fifo-bf16-promises", K=4, S=5, c=12, r=12)
+    run_ahead_parity(w, 60, schedule_seed=7, store_bf16=True, policy=POLICIES["exact-fifo"])
+    run_ahead_parity(w, 60, schedule_seed=8, store_bf16=True, policy=POLICIES["exact-reservoir"])
+    # the Bernoulli selection has no bound of 64 on its candidates: announcements are ignored, results unchanged
+    run_ahead_parity(w, 30, policy=POLICIES["bernoulli-fifo"])
+
+
 def test_an_announcement_that_was_not_used_is_forgotten():
     """Labels are announced, then other calls come instead of rb_update_sample.  The announcement
     must not linger and be taken for the labels of a later step that happens to reuse the memory."""
