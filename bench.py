@@ -30,6 +30,9 @@ MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"
                     ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77297208}
 
 
+MANY = 64           # steps handed to one rb_update_sample_many call
+
+
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
@@ -64,9 +67,10 @@ class Rig:
         for i in range(self.P):
             bx, by = self.aug_x[i].data_ptr(), self.aug_y[i].data_ptr()
             self.args.append((bx, by, bx + w.b * rs, by + w.b * 8))
-        # host arrays of the same pointers for rb_update_sample_many: the pool twice over, so that any run of
-        # up to P consecutive slots is contiguous
-        self.ptrs = [rb.pointer_array([a[i] for a in self.args] * 2) for i in range(4)]
+        # host arrays of the same pointers for rb_update_sample_many: the pool several times over, so that any run
+        # of up to MANY consecutive steps is contiguous (the pool has at least 8 slots: the steps that share a
+        # launch never share a slot)
+        self.ptrs = [rb.pointer_array([a[i] for a in self.args] * (2 + MANY // self.P)) for i in range(4)]
         self.step = 0
 
     def prefill(self):
@@ -95,7 +99,7 @@ class Rig:
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
         t = self.step
         if many:
-            assert many <= P
+            assert many <= MANY
             import ctypes as C
             for at in range(0, n, many):
                 k = min(many, n - at)
@@ -274,7 +278,13 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     n_side = min(steps, 1000)
     ms_plain = rig.timed(n_side, single_call=True)        # the same call without the announcement
     ms_two = rig.timed(n_side)
-    ms_many = rig.timed(n_side, many=min(rig.P, 64))      # 64 steps per host call
+    ms_many = rig.timed(n_side, many=MANY)                # 64 steps per host call
+    ms_win = None
+    if fused and w.b <= 2048:
+        rig.buf.set_option(rb.RB_OPT_WINDOW, 8)           # ... with up to eight steps per launch
+        rig.enqueue(MANY, many=MANY)
+        ms_win = rig.timed(n_side, many=MANY)
+        rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).
@@ -288,7 +298,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "launches_per_step": 1 if fused else 2, "next_labels_announced": fused,
         "not_announced_ms_per_step": ms_plain, "not_announced_gb_per_s": w.bytes_per_step() / (ms_plain * 1e-3) / 1e9,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
-        "many_call_ms_per_step": ms_many,
+        "many_call_ms_per_step": ms_many, "many_call_8_steps_per_launch_ms_per_step": ms_win,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }

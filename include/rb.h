@@ -205,6 +205,7 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * seed are common.  The four pointer arrays are HOST arrays of n device
  * pointers, read before the call returns.  All n steps are validated first;
  * on an error nothing was enqueued.  Results are those of n separate calls.
+ * The outputs and mini-batches of any 8 consecutive steps must not overlap.
  */
 int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
                           int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
@@ -262,8 +263,12 @@ int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint3
  * with plain ones.  RB_OPT_ROWS_PER_BLOCK: rows one workgroup moves one after
  * the other when a row fits a single tile (0 = automatic, else 1..16).
  * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
- * 0 makes it always enqueue the two kernels. */
-enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3 };
+ * 0 makes it always enqueue the two kernels.  RB_OPT_WINDOW: most steps that
+ * rb_update_sample_many puts into one launch (1..8; default 1 = one launch
+ * per step, which measured fastest; with 2 or more the steps of a launch are
+ * planned by a launch of their own on a second stream that the library
+ * creates on first use). */
+enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
 
 /* Free the host handle.  Device memory stays the caller's. */

@@ -23,6 +23,7 @@
 // back at the copy the planner read.
 #include <hip/hip_runtime.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstdlib>
 #include <new>
@@ -32,6 +33,7 @@
 #include "rb_kernels_general.h"
 #include "rb_kernels_small.h"
 #include "rb_kernels_planned.h"
+#include "rb_kernels_window.h"
 #include "rb_kernels_aux.h"
 
 // ===========================================================================
@@ -55,13 +57,16 @@ struct rb_buffer {
     // workspace layout (byte offsets)
     size_t off_fill[2], off_chunk[2], ws_bytes;
     // launch-shape knobs
-    int opt_unroll, opt_nt, opt_rpb, opt_fuse;
+    int opt_unroll, opt_nt, opt_rpb, opt_fuse, opt_window;
     // policy variant and its per-class state (two copies, like the fill counts)
     int selection, eviction;
     size_t off_aux[2];
     int64_t updates;         // rb_update calls since the last rb_bind
     // plan-ahead form of the single-launch step
     size_t off_tbl[2];       // the two plan tables
+    size_t off_wtbl[2];      // the two plan tables of the several-steps-per-launch form
+    hipStream_t plan_stream; // ... its planners' stream and the events between that and the bound stream (made on first use)
+    hipEvent_t ev_start, ev_plan[2], ev_move[2];
     int tbl_next;            // table the next plan is written to
     int tbl_planned;         // table that holds the pending plan
     bool plan_valid;         // a step has been planned (and the fill counts advanced) but not yet executed
@@ -309,6 +314,120 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
     return RB_OK;
 }
 
+template <bool NT>
+hipError_t launch_window(const WinMoveArgs& m, int unroll, dim3 grid, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: rb_window_kernel<1, NT><<<grid, TPB, 0, st>>>(m); break;
+    case 2: rb_window_kernel<2, NT><<<grid, TPB, 0, st>>>(m); break;
+    case 4: rb_window_kernel<4, NT><<<grid, TPB, 0, st>>>(m); break;
+    default: rb_window_kernel<8, NT><<<grid, TPB, 0, st>>>(m); break;
+    }
+    return hipGetLastError();
+}
+
+// The second stream (planners) and the events that order it against the bound stream; made on
+// first use, kept until rb_destroy.
+bool ensure_plan_stream(rb_buffer* rb)
+{
+    if (rb->plan_stream) return true;
+    hipStream_t st = nullptr;
+    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return false;
+    hipEvent_t ev[5] = {};
+    for (int i = 0; i < 5; ++i) {
+        if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) {
+            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
+            (void)hipStreamDestroy(st);
+            return false;
+        }
+    }
+    rb->plan_stream = st;
+    rb->ev_start = ev[0];
+    rb->ev_plan[0] = ev[1]; rb->ev_plan[1] = ev[2];
+    rb->ev_move[0] = ev[3]; rb->ev_move[1] = ev[4];
+    return true;
+}
+
+// Enqueue the plan of steps [at, at + w) on the planners' stream, into table `table`.
+int enqueue_window_plan(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
+                        uint64_t seed, uint64_t first_step, int table)
+{
+    WinPlanArgs p = {};
+    for (int64_t i = 0; i < w; ++i) p.batch_y[i] = batch_y[at + i];
+    p.fill_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    p.fill_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_fill[rb->cur ^ 1]);
+    p.chunk_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_chunk[rb->cur ^ 1]);
+    p.table = rb->ws + rb->off_wtbl[table];
+    p.seed_lo = (uint32_t)seed; p.seed_hi = (uint32_t)(seed >> 32);
+    p.first_step = first_step + (uint64_t)at;
+    p.w = (int32_t)w;
+    p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
+    p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
+    p.S = rb->S;
+    rb_window_plan_kernel<<<dim3(1), TPB, (size_t)b * 8, rb->plan_stream>>>(p);
+    if (hipGetLastError() != hipSuccess) return RB_EHIP;
+    if (hipEventRecord(rb->ev_plan[table], rb->plan_stream) != hipSuccess) return RB_EHIP;
+    rb->cur ^= 1;
+    return RB_OK;
+}
+
+// n steps as launches of up to WIN_MAX steps each.  Window i is planned on the planners' stream
+// while window i - 1 is being moved on the bound stream; the first window is a single step so that
+// the movers get going early.
+int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
+                   int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y)
+{
+    if (!ensure_plan_stream(rb)) return RB_EHIP;
+    const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(WIN_MAX, rb->opt_window));
+    // With thousands of workgroups per launch the smallest tiles measured best (one vector per thread
+    // in flight, many workgroups per compute unit), unlike the one-step launches.
+    const int unroll_option = rb->opt_unroll;
+    if (unroll_option == 0) rb->opt_unroll = 1;
+    const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
+    rb->opt_unroll = unroll_option;
+    // the planners come after everything enqueued on the bound stream so far
+    if (hipEventRecord(rb->ev_start, rb->stream) != hipSuccess) return RB_EHIP;
+    if (hipStreamWaitEvent(rb->plan_stream, rb->ev_start, 0) != hipSuccess) return RB_EHIP;
+    int64_t at = 0, w = 1;
+    int i = 0;                                   // window number; its table is i & 1
+    int rc = enqueue_window_plan(rb, batch_y, at, w, b, c, r, seed, first_step, 0);
+    if (rc != RB_OK) return rc;
+    while (at < n) {
+        const int64_t next_at = at + w, next_w = std::min(wmax, n - next_at);
+        if (next_w > 0) {
+            // its table was last read by the movers of window i - 1
+            if (i >= 1 && hipStreamWaitEvent(rb->plan_stream, rb->ev_move[(i - 1) & 1], 0) != hipSuccess) return RB_EHIP;
+            rc = enqueue_window_plan(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
+            if (rc != RB_OK) return rc;
+        }
+        WinMoveArgs m = {};
+        for (int64_t k = 0; k < w; ++k) {
+            m.batch_x[k] = static_cast<const vec16*>(batch_x[at + k]);
+            m.out_x[k] = static_cast<vec16*>(out_x[at + k]);
+            m.out_y[k] = out_y[at + k];
+        }
+        m.buf_x = static_cast<vec16*>(rb->buf_x);
+        m.buf_y = rb->buf_y;
+        m.table = rb->ws + rb->off_wtbl[i & 1];
+        m.state = reinterpret_cast<DevState*>(rb->ws);
+        m.w = (int32_t)w; m.c = (int32_t)c; m.r = (int32_t)r;
+        m.S = rb->S;
+        m.row_vec = rb->row_vec;
+        m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
+        if (hipStreamWaitEvent(rb->stream, rb->ev_plan[i & 1], 0) != hipSuccess) return RB_EHIP;
+        const dim3 grid((unsigned)(w * (c + r) * sh.tpr));
+        const hipError_t e = rb->opt_nt ? launch_window<true>(m, sh.unroll, grid, rb->stream)
+                                        : launch_window<false>(m, sh.unroll, grid, rb->stream);
+        if (e != hipSuccess) return RB_EHIP;
+        if (hipEventRecord(rb->ev_move[i & 1], rb->stream) != hipSuccess) return RB_EHIP;
+        at = next_at;
+        w = next_w;
+        ++i;
+    }
+    rb->updates += n;
+    return RB_OK;
+}
+
 // What the host can check of the arguments of one update + sample step.
 int check_step(const rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
                const void* out_x, const int64_t* out_y)
@@ -377,10 +496,13 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_aux[1] = off; off += fill_bytes;
     rb->off_tbl[0] = off; off += PLAN_BYTES;
     rb->off_tbl[1] = off; off += PLAN_BYTES;
+    rb->off_wtbl[0] = off; off += WIN_TABLE_BYTES;
+    rb->off_wtbl[1] = off; off += WIN_TABLE_BYTES;
     rb->ws_bytes = off;
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
+    rb->plan_stream = nullptr;
     rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
-    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1;
+    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = 1;
     *out = rb;
     return RB_OK;
 }
@@ -603,6 +725,13 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
         const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (bad != RB_OK) return bad;
     }
+    const bool windowed = n >= 2 && c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 &&
+                          rb->opt_fuse && rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT &&
+                          rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
+    if (windowed) {
+        discard_plan(rb);
+        return steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y);
+    }
     for (int64_t i = 0; i < n; ++i) {
         rb->next_y = i + 1 < n ? batch_y[i + 1] : nullptr;      // the next step's labels are known: plan ahead
         const int rc = rb_update_sample(rb, batch_x[i], batch_y[i], b, c, r, seed, first_step + (uint64_t)i,
@@ -716,6 +845,10 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
         if (value != 0 && value != 1) return RB_EINVAL;
         rb->opt_fuse = (int)value;
         return RB_OK;
+    case RB_OPT_WINDOW:
+        if (value < 1 || value > WIN_MAX) return RB_EINVAL;
+        rb->opt_window = (int)value;
+        return RB_OK;
     default:
         return RB_EINVAL;
     }
@@ -723,6 +856,15 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
 
 int rb_destroy(rb_buffer* rb)
 {
+    if (rb && rb->plan_stream) {
+        (void)hipStreamSynchronize(rb->plan_stream);
+        (void)hipEventDestroy(rb->ev_start);
+        for (int i = 0; i < 2; ++i) {
+            (void)hipEventDestroy(rb->ev_plan[i]);
+            (void)hipEventDestroy(rb->ev_move[i]);
+        }
+        (void)hipStreamDestroy(rb->plan_stream);
+    }
     delete rb;
     return RB_OK;
 }

@@ -1,0 +1,420 @@
+// Several steps per launch (rb_update_sample_many, at most 64 candidates and representatives, at
+// most 1024 classes, default policy): one workgroup plans a whole window of steps, one after the
+// other, in a launch of its own on a second stream while the previous window's rows are being
+// moved; the window's own launch then moves the rows of all its steps at once by the table the
+// planner left.
+// Included by rb.hip only, after rb_kernels_small.h (whose candidate selection it uses).
+#pragma once
+
+#include "rb_device.h"
+#include "rb_kernels_small.h"
+
+namespace {
+
+constexpr int WIN_MAX = 8;                    // most steps one launch covers
+constexpr int WIN_ROWS = 2 * WAVE;            // table entries per step: candidates first, then representatives
+constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_MAX * WIN_ROWS keys)
+constexpr uint32_t WIN_NONE = 0xFFFFu;        // "no entry" in the 16-bit links below
+constexpr uint32_t WIN_EMPTY = 0xFFFFFFFFu;   // free slot of the row table (no buffer row has this index)
+
+// Steps of one launch share the buffer, so the planner resolves what the stream order resolves
+// between separate launches:
+//   - a representative whose slot is written earlier in the window (or in its own step) is copied
+//     from the mini-batch row that was stored there;
+//   - of several writes to one slot only the last one is carried out;
+//   - a representative that needs what a slot held BEFORE the window, while a later step of the
+//     window overwrites that slot, is served by the workgroups that carry out that write: each of
+//     them first copies its tile of the old content to the representative's row, then overwrites it.
+struct WinHeader {        // one per step
+    int32_t n;            // representatives the step hands out: min(r, F)
+    uint32_t flags;       // RB_FLAG_* raised by the step
+    int32_t pad[2];
+};
+struct WinEntry {         // 32 bytes; entry index = step * WIN_ROWS + (candidate i | c + representative j)
+    int32_t src;          // candidate: its mini-batch position.  representative: -1 = read the slot, else
+                          // (step in the window << 16 | mini-batch position) of the row stored there
+    int32_t label;        // class; representative: -1 = fewer samples stored than asked for
+    int64_t row;          // candidate: slot row it is written to, -1 = not written by this launch.
+                          // representative: slot row it is read from
+    int32_t chain;        // candidate: first representative (entry index) that gets the slot's old content
+                          // from this candidate's workgroups, -1 = none.  representative: the next one of that chain
+    int32_t handled;      // representative: 1 = served by a candidate's workgroups, its own do nothing
+    int32_t pad[2];
+};
+constexpr size_t WIN_TABLE_BYTES = (WIN_MAX * sizeof(WinHeader) + WIN_MAX * WIN_ROWS * sizeof(WinEntry) + 255) / 256 * 256;
+
+struct WinPlanArgs {
+    const int64_t* batch_y[WIN_MAX];   // labels of the steps that are planned
+    const int32_t* fill_old;           // fill counts before the window
+    int32_t* fill_new;                 // ... and after it
+    int32_t* chunk_new;
+    char* table;
+    uint32_t seed_lo, seed_hi;
+    uint64_t first_step;
+    int32_t w;                         // steps in the window
+    int32_t b, c, r;
+    int32_t K, nchunks;
+    int64_t S;
+};
+
+struct WinMoveArgs {
+    const vec16* batch_x[WIN_MAX];
+    vec16* out_x[WIN_MAX];
+    int64_t* out_y[WIN_MAX];
+    vec16* buf_x;
+    int64_t* buf_y;
+    const char* table;
+    DevState* state;
+    int32_t w, c, r;
+    int64_t S;
+    int64_t row_vec;
+    int32_t tpr, tile_vec, tile_rem;
+};
+
+__device__ __forceinline__ uint32_t win_hash(uint32_t row)
+{
+    return (row * 2654435761u) >> 21;          // 11 bits: WIN_HASH slots
+}
+
+// Slot of `row` in the row table, inserting it if it is not there (open addressing; the table
+// never fills: at most half of its slots are ever used).
+__device__ __forceinline__ int win_find_or_insert(uint32_t* s_hkey, uint32_t row)
+{
+    uint32_t h = win_hash(row);
+    for (;;) {
+        const uint32_t prev = atomicCAS(&s_hkey[h], WIN_EMPTY, row);
+        if (prev == WIN_EMPTY || prev == row) return (int)h;
+        h = (h + 1) & (WIN_HASH - 1);
+    }
+}
+
+// ---------------------------------------------------------------------------
+// The plan of a.w consecutive steps by one workgroup (all TPB threads call it).
+// Per step, as in the single-step planner: wavefront 0 = one lane per candidate,
+// all threads = prefix of the fill counts over the classes, wavefront 1 = one
+// lane per representative; the fill counts stay in LDS from step to step.
+//
+// LDS (dynamic): s_first[b] u32, s_y[b] i32.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
+{
+    constexpr int NCLS = DIRECT_CHUNKS * CH;
+    uint32_t* s_first = lds;                                   // [b]
+    int32_t* s_y = reinterpret_cast<int32_t*>(lds + a.b);      // [b]: labels of the current step
+    __shared__ __align__(16) int32_t s_fill[NCLS];    // fill counts, carried from step to step
+    __shared__ __align__(16) int32_t s_pre[NCLS];     // stored samples in the classes before each class, after the step's update
+    __shared__ uint32_t s_hkey[WIN_HASH];             // buffer rows the window touches ...
+    __shared__ uint32_t s_hval[WIN_HASH];             // ... low half: entry of the last candidate written there; high half:
+                                                      //     head of the chain of representatives that read its old content
+    __shared__ uint64_t s_bits[WIN_MAX * WAVE];       // random bits of every step's sampling draws
+    __shared__ uint16_t s_next[WIN_MAX * WAVE];       // per representative (step * WAVE + j): next entry of its chain
+    __shared__ uint16_t s_wpos[WIN_MAX * WAVE];       // per candidate (step * WAVE + i): its mini-batch position
+    __shared__ int s_wave[NWAVE];
+    __shared__ __align__(16) int32_t s_ck[WAVE], s_cx[WAVE], s_cw[WAVE];
+    __shared__ __align__(16) uint32_t s_t[WAVE];
+    __shared__ uint32_t s_flags;
+
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int b = a.b, c = a.c, r = a.r, w = a.w;
+    WinHeader* head = reinterpret_cast<WinHeader*>(a.table);
+    WinEntry* entry = reinterpret_cast<WinEntry*>(a.table + WIN_MAX * sizeof(WinHeader));
+
+    // ---- before the first step: fill counts, empty row table, all sampling bits ----
+    int64_t yv[YPRE];
+#pragma unroll
+    for (int u = 0; u < YPRE; ++u) {
+        const int q = tid + u * TPB;
+        yv[u] = q < b ? a.batch_y[0][q] : -1;
+    }
+    int4 fo = make_int4(0, 0, 0, 0);
+    if (4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+    for (int i = tid; i < WIN_HASH; i += TPB) {
+        s_hkey[i] = WIN_EMPTY;
+        s_hval[i] = 0xFFFFFFFFu;
+    }
+    if (wave != 0) {
+        // wavefronts 1..3 share the steps; wavefront 0 is already selecting the first step's candidates
+        for (int s = wave - 1; s < w; s += NWAVE - 1) {
+            Seed sd;
+            sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
+            sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
+            if (lane < r) s_bits[s * WAVE + lane] = draw64(sd, PURPOSE_SAMPLE, (uint32_t)lane);
+        }
+    }
+    *reinterpret_cast<int4*>(s_fill + 4 * tid) = fo;
+    if (tid == 0) s_flags = 0;
+
+    for (int s = 0; s < w; ++s) {
+        Seed sd;
+        sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
+        sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
+
+        // ---- candidates of step s (wavefront 0); everybody parks the step's labels ----
+        bool active = false;
+        int x = 0;
+        if (wave == 0) x = wave_select(sd, b, c, s_first, active);
+        park_labels(yv, a.batch_y[s], b, a.K, s_y);
+        if (s + 1 < w) {                        // the next step's labels are requested now and parked a step later
+#pragma unroll
+            for (int u = 0; u < YPRE; ++u) {
+                const int q = tid + u * TPB;
+                yv[u] = q < b ? a.batch_y[s + 1][q] : -1;
+            }
+        }
+        __syncthreads();
+
+        if (wave == 0) {
+            const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
+            const bool valid = active && k >= 0;
+            const bool bad = __ballot(active && k == LAB_INVALID) != 0;
+            s_ck[lane] = valid ? k : -1;
+            s_cx[lane] = x;
+            s_wpos[s * WAVE + lane] = (uint16_t)x;
+            const int64_t fill0 = valid ? s_fill[k] : 0;
+            // insertion number within the class: fill0 + class-mates earlier in the mini-batch
+            int rank = 0, total = 0;
+#pragma unroll 4
+            for (int m = 0; m < c; m += 4) {
+                const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
+                const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
+                rank += (int)(km.x == k && xm.x < x) + (int)(km.y == k && xm.y < x) + (int)(km.z == k && xm.z < x) +
+                        (int)(km.w == k && xm.w < x);
+                total += (int)(km.x == k) + (int)(km.y == k) + (int)(km.z == k) + (int)(km.w == k);
+            }
+            const int64_t at = fill0 + rank;
+            const bool over = valid && at >= a.S;      // beyond the capacity: overwrites a drawn slot
+            int slot = valid ? (int)at : -1;
+            bool beaten = false;
+            if (__ballot(over) != 0) {
+                if (over) slot = (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);
+                s_cw[lane] = over ? slot : -2;
+                // not stored if a later class-mate overwrites the same slot
+#pragma unroll 4
+                for (int m = 0; m < c; m += 4) {
+                    const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
+                    const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
+                    const int4 wm = *reinterpret_cast<const int4*>(s_cw + m);
+                    beaten |= (km.x == k && xm.x > x && wm.x == slot) | (km.y == k && xm.y > x && wm.y == slot) |
+                              (km.z == k && xm.z > x && wm.z == slot) | (km.w == k && xm.w > x && wm.w == slot);
+                }
+            }
+            const bool stored = valid && !beaten;
+            const int64_t row = stored ? (int64_t)k * a.S + slot : -1;
+            const int me = s * WIN_ROWS + lane;
+            int chain = -1;
+            if (stored) {
+                // the stored candidates of one step go to different slots, so no two lanes share a table slot here
+                const int h = win_find_or_insert(s_hkey, (uint32_t)row);
+                const uint32_t v = s_hval[h];
+                const uint32_t before = v & 0xFFFFu, readers = v >> 16;
+                if (before != WIN_NONE) {              // an earlier step of the window wrote this slot: that write is dropped
+                    entry[before].row = -1;
+                    entry[before].chain = -1;
+                }
+                if (readers != WIN_NONE) chain = (int)readers;   // they read what the slot held before the window
+                s_hval[h] = (readers << 16) | (uint32_t)me;
+            }
+            if (lane < c) {
+                WinEntry e;
+                e.src = x;
+                e.label = valid ? k : -1;
+                e.row = row;
+                e.chain = chain;
+                e.handled = 0;
+                e.pad[0] = 0; e.pad[1] = 0;
+                entry[me] = e;
+            }
+            // the class's fill count after this step (one lane per class: its first candidate)
+            if (valid && rank == 0) {
+                const int64_t v = fill0 + total;
+                s_fill[k] = (int32_t)(v < a.S ? v : a.S);
+            }
+            if (bad && lane == 0) s_flags |= RB_FLAG_BAD_LABEL;
+        }
+        __syncthreads();
+
+        // ---- prefix of the fill counts over the classes, four consecutive classes per thread ----
+        const int4 f4 = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
+        int F;
+        int before = block_scan_excl(f4.x + f4.y + f4.z + f4.w, F, s_wave);
+        s_pre[4 * tid] = before;
+        s_pre[4 * tid + 1] = before + f4.x;
+        s_pre[4 * tid + 2] = before + f4.x + f4.y;
+        s_pre[4 * tid + 3] = before + f4.x + f4.y + f4.z;
+        __syncthreads();
+
+        if (wave == 1) {
+            // ---- representatives of step s: lane j = draw j of Floyd's n-subset of the F stored samples ----
+            const int n = r < F ? r : F;
+            const int base = F - n;
+            const uint32_t t = lane < n ? (uint32_t)__umul64hi(s_bits[s * WAVE + lane], (uint64_t)base + lane + 1) : 0xFFFFFFFFu;
+            s_t[lane] = t;
+            bool dup = false;                           // an earlier draw had the same value
+#pragma unroll 4
+            for (int i = 0; i < n; i += 4) {
+                const uint4 ti = *reinterpret_cast<const uint4*>(s_t + i);
+                dup |= (i < lane && ti.x == t) | (i + 1 < lane && ti.y == t) | (i + 2 < lane && ti.z == t) | (i + 3 < lane && ti.w == t);
+            }
+            int cur = lane;
+            bool taken = false, done = lane >= n;
+            while (__ballot(!done) != 0) {
+                const uint32_t tc = (uint32_t)__shfl((int)t, cur, WAVE);
+                const int dc = __shfl((int)dup, cur, WAVE);
+                if (!done) {
+                    if (dc) {
+                        taken = true;
+                        done = true;
+                    } else {
+                        const int64_t q = (int64_t)tc - base;
+                        if (q < 0 || q >= cur) done = true;
+                        else cur = (int)q;
+                    }
+                }
+            }
+            const int g = taken ? base + lane : (int)t;
+            int lo = 0, hi = NCLS - 1;
+            if (lane < n) {
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (s_pre[mid] <= g) lo = mid; else hi = mid - 1;
+                }
+            }
+            const int pk = lo, ps = lane < n ? g - s_pre[lo] : 0;
+            const int64_t row = (int64_t)pk * a.S + ps;
+            const int me = s * WIN_ROWS + c + lane;
+            int src = -1, chain = -1;
+            if (lane < n) {
+                // the representatives of one step are different samples, so no two lanes share a table slot here
+                const int h = win_find_or_insert(s_hkey, (uint32_t)row);
+                const uint32_t v = s_hval[h];
+                const uint32_t writer = v & 0xFFFFu, readers = v >> 16;
+                if (writer != WIN_NONE) {
+                    // written in this window (this step included): take the row that was stored there
+                    const int ws = (int)writer / WIN_ROWS, wi = (int)writer % WIN_ROWS;
+                    src = (ws << 16) | (int)s_wpos[ws * WAVE + wi];
+                } else {
+                    // what the slot held before the window: remembered, in case a later step overwrites it
+                    chain = readers != WIN_NONE ? (int)readers : -1;
+                    s_hval[h] = ((uint32_t)me << 16) | WIN_NONE;
+                }
+            }
+            s_next[s * WAVE + lane] = (uint16_t)(chain >= 0 ? chain : (int)WIN_NONE);
+            if (lane < r) {
+                WinEntry e;
+                e.src = src;
+                e.label = lane < n ? pk : -1;
+                e.row = lane < n ? row : -1;
+                e.chain = chain;
+                e.handled = 0;
+                e.pad[0] = 0; e.pad[1] = 0;
+                entry[me] = e;
+            }
+            if (lane == 0) {
+                WinHeader hd;
+                hd.n = n;
+                hd.flags = s_flags;
+                hd.pad[0] = 0; hd.pad[1] = 0;
+                head[s] = hd;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- representatives that a candidate's workgroups serve do nothing themselves ----
+    for (int i = tid; i < WIN_HASH; i += TPB) {
+        const uint32_t v = s_hval[i];
+        if (s_hkey[i] == WIN_EMPTY || (v & 0xFFFFu) == WIN_NONE) continue;
+        uint32_t q = v >> 16;
+        while (q != WIN_NONE) {
+            entry[q].handled = 1;
+            q = s_next[(q / WIN_ROWS) * WAVE + (q % WIN_ROWS - c)];
+        }
+    }
+
+    // ---- fill counts after the window ----
+    if (4 * tid < a.nchunks * CH) *reinterpret_cast<int4*>(a.fill_new + 4 * tid) = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
+    {
+        const int4 f4 = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
+        const int wsum = lane_read(wave_scan_incl(f4.x + f4.y + f4.z + f4.w), WAVE - 1);   // a wavefront covers one chunk of CH classes
+        if (lane == 0 && wave < a.nchunks) a.chunk_new[wave] = wsum;
+    }
+}
+
+// The plan of one window.
+__global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    // it shares its compute unit with the movers of the window before: its few wavefronts are the
+    // ones every later launch waits for, so they go first whenever they have an instruction ready
+    __builtin_amdgcn_s_setprio(3);
+    plan_window(a, lds);
+}
+
+// ---------------------------------------------------------------------------
+// All steps of one window by its table: workgroup (step, entry, tile) moves one
+// tile of one row.  (The planner is a launch of its own on a second stream: inside
+// this kernel its registers and LDS would halve the movers' occupancy.)
+// ---------------------------------------------------------------------------
+template <int U, bool NT>
+__global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m)
+{
+    const int mover = blockIdx.x;
+    const int rows = m.c + m.r, per_step = rows * m.tpr;
+    const int s = mover / per_step, in_step = mover % per_step;
+    // all tiles of a row go to workgroups of one die (see rb_step_planned_kernel)
+    int e, tile;
+    const int dealt = rows / XCDS * XCDS;
+    if (in_step < dealt * m.tpr) {
+        const int die = in_step % XCDS, i = in_step / XCDS;
+        e = i / m.tpr * XCDS + die;
+        tile = i % m.tpr;
+    } else {
+        e = in_step / m.tpr;
+        tile = in_step % m.tpr;
+    }
+    const WinHeader* head = reinterpret_cast<const WinHeader*>(m.table);
+    const WinEntry* entry = reinterpret_cast<const WinEntry*>(m.table + WIN_MAX * sizeof(WinHeader));
+    const WinEntry en = entry[s * WIN_ROWS + e];
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
+    const bool first = tile == 0 && threadIdx.x == 0;
+    if (mover == 0 && threadIdx.x == 0) {
+        uint32_t flags = 0;
+        for (int q = 0; q < m.w; ++q) flags |= head[q].flags;
+        m.state->last_n = head[m.w - 1].n;
+        if (flags != 0) atomicOr(&m.state->flags, flags);
+    }
+    if (e < m.c) {
+        if (en.row < 0) return;                 // dropped within its step, or overwritten again later in the window
+        vec16* slot = m.buf_x + en.row * m.row_vec;
+        // representatives that need the slot's old content get it from here, before it is overwritten
+        for (int q = en.chain; q >= 0;) {
+            const WinEntry rq = entry[q];
+            const int qs = q / WIN_ROWS, qj = q % WIN_ROWS - m.c;
+            if (first) m.out_y[qs][qj] = rq.label;
+            Tile<U, NT> old;
+            old.load(slot, v_lo, v_hi);
+            old.store(m.out_x[qs] + (int64_t)qj * m.row_vec, v_lo, v_hi);
+            q = rq.chain;
+        }
+        // Lanes past the end of a tile move its last vector again, so a vector may be read by one
+        // wavefront and overwritten by another: everybody has read before anybody overwrites.
+        if (en.chain >= 0) __syncthreads();
+        if (first) m.buf_y[en.row] = en.label;
+        Tile<U, NT> t;
+        t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec, v_lo, v_hi);
+        t.store(slot, v_lo, v_hi);
+        return;
+    }
+    if (en.handled) return;
+    const int j = e - m.c;
+    if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
+    if (en.label < 0) return;
+    const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
+                                   : m.buf_x + en.row * m.row_vec;
+    Tile<U, NT> t;
+    t.load(src, v_lo, v_hi);
+    t.store(m.out_x[s] + (int64_t)j * m.row_vec, v_lo, v_hi);
+}
+
+}  // namespace

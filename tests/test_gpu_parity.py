@@ -295,15 +295,21 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
 
 # ------------------------------------------------ several steps from one call ---
 
+@pytest.mark.parametrize("window", [8, 3, 1])
 @pytest.mark.parametrize("w", [
     wl.variant(wl.C2, name="C2-many", S=4),
     wl.variant(wl.C5, name="C5-many", K=300, S=12, shape=(256,), b=512, c=200, r=150),
-], ids=["small", "general"])
-def test_many_steps_from_one_call(w):
+    wl.variant(wl.C1, name="C1-many-one-class", K=1, S=7, c=16, r=16),     # every step rewrites slots that representatives of the same launch read
+    wl.variant(wl.C1, name="C1-many-one-slot", K=2, S=1, c=6, r=2),        # two slots in all: each is read and rewritten in every step
+    wl.variant(wl.C4, name="C4-many-S2", S=2, shape=(3, 32, 32)),          # Zipf head: the hot classes' two slots are hit again and again
+    wl.variant(wl.C1, name="C1-many", S=20),
+], ids=["small", "general", "one-class", "one-slot", "zipf-S2", "C1"])
+def test_many_steps_from_one_call(w, window):
     rb = _rb()
     dev = torch.device("cuda:0")
     n = 14
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    buf.set_option(rb.RB_OPT_WINDOW, window)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
     xs, ys, oxs, oys = [], [], [], []
     for t in range(2 * n):
@@ -332,6 +338,37 @@ def test_many_steps_from_one_call(w):
         assert np.array_equal(got_x[:nn], ref_x[:nn]), f"{w.name} step {t}: rows differ"
         assert np.array_equal(got_x[nn:], untouched[nn:]), f"{w.name} step {t}: rows beyond n were written"
     compare_buffers(buf, orc, f"{w.name} final")
+
+
+@pytest.mark.parametrize("window", [8, 4, 2])
+def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
+    """Eight classes of one slot each, every step samples all eight rows and rewrites one class (the label
+    sequence decides which): rows that are read before a later step of the same launch overwrites them, rows
+    that are read after an earlier step wrote them, rows written twice."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    K, S, b, c, r = 8, 1, 4, 4, 8
+    shape = (3, 40)                                     # 480-byte rows
+    buf = rb.RehearsalBuffer(K, S, shape, torch.float32, device=dev)
+    buf.set_option(rb.RB_OPT_WINDOW, window)
+    orc = rbo.Buffer(K, S, 480)
+    sequence = list(range(8)) + [7, 6, 5, 4, 3, 2, 1, 0] + [0, 0, 1, 1, 0, 2, 2, 0] + [5, 5, 5, 5, 5, 5, 5, 5] + [3, 4, 3, 4, 3, 4, 3, 4]
+    g = torch.Generator(device="cpu")
+    g.manual_seed(99)
+    xs = [torch.randn((b, *shape), generator=g).to(dev) for _ in sequence]
+    ys = [torch.full((b,), k, dtype=torch.int64, device=dev) for k in sequence]
+    oxs = [torch.zeros((r, *shape), device=dev) for _ in sequence]
+    oys = [torch.full((r,), -7, dtype=torch.int64, device=dev) for _ in sequence]
+    for first in range(0, len(sequence), 8):
+        sl = slice(first, first + 8)
+        assert rb.rb_update_sample_many(buf.handle, 8, xs[sl], ys[sl], b, c, r, 3, first, oxs[sl], oys[sl]) == rb.RB_OK
+    torch.cuda.synchronize()
+    for t, k in enumerate(sequence):
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), c, 3, t)
+        n, ref_x, ref_y = orc.sample_augment(r, 3, t)
+        assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"step {t}: labels differ"
+        assert np.array_equal(parity_util._bytes(oxs[t]).cpu().numpy()[:n], ref_x[:n]), f"step {t}: rows differ"
+    compare_buffers(buf, orc, "final")
 
 
 # ----------------------------------------- the asynchronous primitive (Sec. IV-D) ---
