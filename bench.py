@@ -26,8 +26,8 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # HBM bytes per launch of the dominant kernel as counted by two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
 # known size; the text summaries with the exact commands are kept under profiles/.
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76928312,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77297208}
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76913166,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77268708}
 
 
 MANY = 64           # steps handed to one rb_update_sample_many call
