@@ -278,13 +278,11 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     n_side = min(steps, 1000)
     ms_plain = rig.timed(n_side, single_call=True)        # the same call without the announcement
     ms_two = rig.timed(n_side)
-    ms_many = rig.timed(n_side, many=MANY)                # 64 steps per host call
-    ms_win = None
-    if fused and w.b <= 2048:
-        rig.buf.set_option(rb.RB_OPT_WINDOW, 8)           # ... with up to eight steps per launch
-        rig.enqueue(MANY, many=MANY)
-        ms_win = rig.timed(n_side, many=MANY)
-        rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
+    rig.enqueue(MANY, many=MANY)
+    ms_win = rig.timed(n_side, many=MANY)                 # 64 steps per host call, up to eight steps per launch
+    rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
+    ms_many = rig.timed(n_side, many=MANY)                # ... one launch per step
+    rig.buf.set_option(rb.RB_OPT_WINDOW, 8)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).

@@ -199,9 +199,15 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
 
 /*
  * n consecutive rb_update_sample steps from one call, for callers that have
- * several mini-batches ready (e.g. a prefetching data pipeline) and want to
- * pay the host side of the call once: step i uses batch_x[i], batch_y[i],
- * step number first_step + i and writes to out_x[i], out_y[i]; b, c, r and
+ * several mini-batches ready (e.g. a prefetching data pipeline).  When the
+ * steps are eligible for the single launch (see rb_update_sample; b <= 2048)
+ * up to 8 of them share ONE launch: the rows of all of them are moved at once,
+ * by a plan that one workgroup of the launch before made (what the order of
+ * separate launches would settle between steps - a representative read from a
+ * slot that another step of the same launch writes - the plan settles), so the
+ * cost of a launch is paid once per 8 steps.  Otherwise the steps are enqueued
+ * one after the other.  Step i uses batch_x[i], batch_y[i], step number
+ * first_step + i and writes to out_x[i], out_y[i]; b, c, r and
  * seed are common.  The four pointer arrays are HOST arrays of n device
  * pointers, read before the call returns.  All n steps are validated first;
  * on an error nothing was enqueued.  Results are those of n separate calls.
@@ -264,10 +270,8 @@ int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint3
  * the other when a row fits a single tile (0 = automatic, else 1..16).
  * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
  * 0 makes it always enqueue the two kernels.  RB_OPT_WINDOW: most steps that
- * rb_update_sample_many puts into one launch (1..8; default 1 = one launch
- * per step, which measured fastest; with 2 or more the steps of a launch are
- * planned by a launch of their own on a second stream that the library
- * creates on first use). */
+ * rb_update_sample_many puts into one launch (1..8, default 8; 1 = one launch
+ * per step). */
 enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
 

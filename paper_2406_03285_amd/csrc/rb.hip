@@ -65,8 +65,6 @@ struct rb_buffer {
     // plan-ahead form of the single-launch step
     size_t off_tbl[2];       // the two plan tables
     size_t off_wtbl[2];      // the two plan tables of the several-steps-per-launch form
-    hipStream_t plan_stream; // ... its planners' stream and the events between that and the bound stream (made on first use)
-    hipEvent_t ev_start, ev_plan[2], ev_move[2];
     int tbl_next;            // table the next plan is written to
     int tbl_planned;         // table that holds the pending plan
     bool plan_valid;         // a step has been planned (and the fill counts advanced) but not yet executed
@@ -315,42 +313,19 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
 }
 
 template <bool NT>
-hipError_t launch_window(const WinMoveArgs& m, int unroll, dim3 grid, hipStream_t st)
+hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_window_kernel<1, NT><<<grid, TPB, 0, st>>>(m); break;
-    case 2: rb_window_kernel<2, NT><<<grid, TPB, 0, st>>>(m); break;
-    case 4: rb_window_kernel<4, NT><<<grid, TPB, 0, st>>>(m); break;
-    default: rb_window_kernel<8, NT><<<grid, TPB, 0, st>>>(m); break;
+    case 1: rb_window_kernel<1, NT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 2: rb_window_kernel<2, NT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 4: rb_window_kernel<4, NT><<<grid, TPB, lds, st>>>(m, next); break;
+    default: rb_window_kernel<8, NT><<<grid, TPB, lds, st>>>(m, next); break;
     }
     return hipGetLastError();
 }
 
-// The second stream (planners) and the events that order it against the bound stream; made on
-// first use, kept until rb_destroy.
-bool ensure_plan_stream(rb_buffer* rb)
-{
-    if (rb->plan_stream) return true;
-    hipStream_t st = nullptr;
-    if (hipStreamCreateWithFlags(&st, hipStreamNonBlocking) != hipSuccess) return false;
-    hipEvent_t ev[5] = {};
-    for (int i = 0; i < 5; ++i) {
-        if (hipEventCreateWithFlags(&ev[i], hipEventDisableTiming) != hipSuccess) {
-            for (int j = 0; j < i; ++j) (void)hipEventDestroy(ev[j]);
-            (void)hipStreamDestroy(st);
-            return false;
-        }
-    }
-    rb->plan_stream = st;
-    rb->ev_start = ev[0];
-    rb->ev_plan[0] = ev[1]; rb->ev_plan[1] = ev[2];
-    rb->ev_move[0] = ev[3]; rb->ev_move[1] = ev[4];
-    return true;
-}
-
-// Enqueue the plan of steps [at, at + w) on the planners' stream, into table `table`.
-int enqueue_window_plan(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
-                        uint64_t seed, uint64_t first_step, int table)
+WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
+                             uint64_t seed, uint64_t first_step, int table)
 {
     WinPlanArgs p = {};
     for (int64_t i = 0; i < w; ++i) p.batch_y[i] = batch_y[at + i];
@@ -364,42 +339,35 @@ int enqueue_window_plan(rb_buffer* rb, const int64_t* const* batch_y, int64_t at
     p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
     p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
     p.S = rb->S;
-    rb_window_plan_kernel<<<dim3(1), TPB, (size_t)b * 8, rb->plan_stream>>>(p);
-    if (hipGetLastError() != hipSuccess) return RB_EHIP;
-    if (hipEventRecord(rb->ev_plan[table], rb->plan_stream) != hipSuccess) return RB_EHIP;
-    rb->cur ^= 1;
-    return RB_OK;
+    return p;
 }
 
-// n steps as launches of up to WIN_MAX steps each.  Window i is planned on the planners' stream
-// while window i - 1 is being moved on the bound stream; the first window is a single step so that
-// the movers get going early.
+// n steps as launches of up to WIN_MAX steps each.  Workgroup 0 of every launch plans the next
+// window while the others move the rows of this one; the first window is a single step, planned by
+// a launch of its own, so that the movers get going early.
 int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
                    int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y)
 {
-    if (!ensure_plan_stream(rb)) return RB_EHIP;
     const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(WIN_MAX, rb->opt_window));
-    // With thousands of workgroups per launch the smallest tiles measured best (one vector per thread
-    // in flight, many workgroups per compute unit), unlike the one-step launches.
+    // With thousands of workgroups per launch, and the planner's LDS leaving room for four workgroups per
+    // compute unit, tiles of four vectors per thread measured best (C4: 13.9 us per step against 14.9 with
+    // two and 15.0 with eight; C3: 4.5 against 4.5 and 5.0).
     const int unroll_option = rb->opt_unroll;
-    if (unroll_option == 0) rb->opt_unroll = 1;
+    if (unroll_option == 0) rb->opt_unroll = 4;
     const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
     rb->opt_unroll = unroll_option;
-    // the planners come after everything enqueued on the bound stream so far
-    if (hipEventRecord(rb->ev_start, rb->stream) != hipSuccess) return RB_EHIP;
-    if (hipStreamWaitEvent(rb->plan_stream, rb->ev_start, 0) != hipSuccess) return RB_EHIP;
     int64_t at = 0, w = 1;
-    int i = 0;                                   // window number; its table is i & 1
-    int rc = enqueue_window_plan(rb, batch_y, at, w, b, c, r, seed, first_step, 0);
-    if (rc != RB_OK) return rc;
+    int i = 0;
+    {
+        const WinPlanArgs p = window_plan_args(rb, batch_y, 0, 1, b, c, r, seed, first_step, 0);
+        rb_window_plan_kernel<<<dim3(1), TPB, (size_t)b * 8, rb->stream>>>(p);
+        if (hipGetLastError() != hipSuccess) return RB_EHIP;
+        rb->cur ^= 1;
+    }
     while (at < n) {
         const int64_t next_at = at + w, next_w = std::min(wmax, n - next_at);
-        if (next_w > 0) {
-            // its table was last read by the movers of window i - 1
-            if (i >= 1 && hipStreamWaitEvent(rb->plan_stream, rb->ev_move[(i - 1) & 1], 0) != hipSuccess) return RB_EHIP;
-            rc = enqueue_window_plan(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
-            if (rc != RB_OK) return rc;
-        }
+        WinPlanArgs next = {};
+        if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
         WinMoveArgs m = {};
         for (int64_t k = 0; k < w; ++k) {
             m.batch_x[k] = static_cast<const vec16*>(batch_x[at + k]);
@@ -414,12 +382,11 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         m.S = rb->S;
         m.row_vec = rb->row_vec;
         m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
-        if (hipStreamWaitEvent(rb->stream, rb->ev_plan[i & 1], 0) != hipSuccess) return RB_EHIP;
-        const dim3 grid((unsigned)(w * (c + r) * sh.tpr));
-        const hipError_t e = rb->opt_nt ? launch_window<true>(m, sh.unroll, grid, rb->stream)
-                                        : launch_window<false>(m, sh.unroll, grid, rb->stream);
+        const dim3 grid((unsigned)(w * (c + r) * sh.tpr + (next_w > 0 ? 1 : 0)));
+        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, sh.unroll, grid, next_w > 0 ? (size_t)b * 8 : 0, rb->stream)
+                                        : launch_window<false>(m, next, sh.unroll, grid, next_w > 0 ? (size_t)b * 8 : 0, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
-        if (hipEventRecord(rb->ev_move[i & 1], rb->stream) != hipSuccess) return RB_EHIP;
+        if (next_w > 0) rb->cur ^= 1;
         at = next_at;
         w = next_w;
         ++i;
@@ -500,9 +467,8 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_wtbl[1] = off; off += WIN_TABLE_BYTES;
     rb->ws_bytes = off;
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
-    rb->plan_stream = nullptr;
     rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
-    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = 1;
+    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = WIN_MAX;
     *out = rb;
     return RB_OK;
 }
@@ -856,15 +822,6 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
 
 int rb_destroy(rb_buffer* rb)
 {
-    if (rb && rb->plan_stream) {
-        (void)hipStreamSynchronize(rb->plan_stream);
-        (void)hipEventDestroy(rb->ev_start);
-        for (int i = 0; i < 2; ++i) {
-            (void)hipEventDestroy(rb->ev_plan[i]);
-            (void)hipEventDestroy(rb->ev_move[i]);
-        }
-        (void)hipStreamDestroy(rb->plan_stream);
-    }
     delete rb;
     return RB_OK;
 }

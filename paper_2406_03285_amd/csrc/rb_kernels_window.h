@@ -1,8 +1,7 @@
 // Several steps per launch (rb_update_sample_many, at most 64 candidates and representatives, at
 // most 1024 classes, default policy): one workgroup plans a whole window of steps, one after the
-// other, in a launch of its own on a second stream while the previous window's rows are being
-// moved; the window's own launch then moves the rows of all its steps at once by the table the
-// planner left.
+// other, while the other workgroups of the same launch move the previous window's rows; the
+// window's own launch then moves the rows of all its steps at once by the table the planner left.
 // Included by rb.hip only, after rb_kernels_small.h (whose candidate selection it uses).
 #pragma once
 
@@ -340,25 +339,33 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
     }
 }
 
-// The plan of one window.
+// The plan of the first window of a call, on its own.
 __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a)
 {
     extern __shared__ uint32_t lds[];
-    // it shares its compute unit with the movers of the window before: its few wavefronts are the
-    // ones every later launch waits for, so they go first whenever they have an instruction ready
-    __builtin_amdgcn_s_setprio(3);
     plan_window(a, lds);
 }
 
 // ---------------------------------------------------------------------------
 // All steps of one window by its table: workgroup (step, entry, tile) moves one
-// tile of one row.  (The planner is a launch of its own on a second stream: inside
-// this kernel its registers and LDS would halve the movers' occupancy.)
+// tile of one row; if there is a next window, workgroup 0 plans it instead.  (The
+// planner's registers and LDS limit every compute unit to four workgroups of this
+// kernel.  Measured alternatives: the planner as a launch of its own on a second
+// stream frees the movers but the events that order the two streams cost more than
+// that gains.)
 // ---------------------------------------------------------------------------
 template <int U, bool NT>
-__global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m)
+__global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, const WinPlanArgs next)
 {
-    const int mover = blockIdx.x;
+    extern __shared__ uint32_t lds[];
+    if (next.w > 0 && blockIdx.x == 0) {
+        // dispatched first, and first in line whenever it has an instruction ready: the next launch
+        // waits for this one workgroup as much as for all the movers
+        __builtin_amdgcn_s_setprio(3);
+        plan_window(next, lds);
+        return;
+    }
+    const int mover = blockIdx.x - (next.w > 0 ? 1 : 0);
     const int rows = m.c + m.r, per_step = rows * m.tpr;
     const int s = mover / per_step, in_step = mover % per_step;
     // all tiles of a row go to workgroups of one die (see rb_step_planned_kernel)
