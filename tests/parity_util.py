@@ -182,3 +182,39 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
             assert buf.read_state()[1] == n
     compare_buffers(buf, orc, f"{w.name} final")
     assert buf.read_state()[2] == orc.flags
+
+
+def run_many_parity(w, steps, per_call=24, window=None):
+    """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
+    against the oracle step by step."""
+    import paper_2406_03285_amd as rb
+
+    dev = torch.device("cuda:0")
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    if window is not None:
+        buf.set_option(rb.RB_OPT_WINDOW, window)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(per_call)]
+    oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(per_call)]
+    for first in range(0, steps, per_call):
+        n = min(per_call, steps - first)
+        batches = [wl.make_batch(w, first + i, dev) for i in range(n)]
+        xs = [x.contiguous() for x, _ in batches]
+        ys = [y.contiguous() for _, y in batches]
+        for i in range(n):
+            _bytes(oxs[i]).fill_(SENTINEL)
+            oys[i].fill_(-7)
+        rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
+        assert rc == rb.RB_OK, rc
+        torch.cuda.synchronize()
+        for i in range(n):
+            t = first + i
+            orc.update(_bytes(xs[i]).cpu().numpy(), ys[i].cpu().numpy(), w.c, w.lib_seed, t)
+            ref = np.full((w.r, w.row_bytes), SENTINEL, dtype=np.uint8)
+            nn, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
+            assert np.array_equal(oys[i].cpu().numpy(), ref_y), f"{w.name} step {t}: out_y differs"
+            assert np.array_equal(_bytes(oxs[i]).cpu().numpy(), ref_x), f"{w.name} step {t}: out_x differs (n={nn})"
+        compare_state(buf, orc, f"{w.name} step {first + n - 1}")
+        assert buf.read_state()[1] == nn
+    compare_buffers(buf, orc, f"{w.name} final")
+

@@ -12,7 +12,7 @@ import torch
 import rb_workloads as wl
 from oracle import rbo
 import parity_util
-from parity_util import SENTINEL, compare_buffers, run_ahead_parity, run_parity
+from parity_util import SENTINEL, compare_buffers, run_ahead_parity, run_many_parity, run_parity
 
 pytestmark = pytest.mark.gpu
 
@@ -338,6 +338,24 @@ def test_many_steps_from_one_call(w, window):
         assert np.array_equal(got_x[:nn], ref_x[:nn]), f"{w.name} step {t}: rows differ"
         assert np.array_equal(got_x[nn:], untouched[nn:]), f"{w.name} step {t}: rows beyond n were written"
     compare_buffers(buf, orc, f"{w.name} final")
+
+
+@pytest.mark.parametrize("w,steps", [(wl.C3, 72), (wl.C4, 48)], ids=["C3", "C4"])
+def test_many_steps_at_full_size(w, steps):
+    """The configuration the bench times: real shapes, up to eight steps per launch."""
+    run_many_parity(w, w.steps if FULL else steps, per_call=24)
+
+
+@pytest.mark.parametrize("w,steps,per_call", [
+    (wl.C1, 100, 17),                                                              # fills up: append, replace, collisions
+    (wl.C2, 200, 64),
+    (wl.variant(wl.C4, name="C4-S8-many", S=8, shape=(3, 32, 32)), 96, 32),        # Zipf head: several overwrites of one class per step
+    (wl.variant(wl.C4, name="C4-S1-many", S=1, K=40, shape=(3, 32, 32)), 64, 32),  # 40 slots in all, 64 written and 64 read per step
+    (wl.variant(wl.C1, name="C1-r-large-many", S=3, c=16, r=64, b=64), 40, 9),     # r above what is stored, then r = F
+    (wl.variant(wl.C2, name="C2-odd-b-many", b=77, c=33, r=21, S=2), 60, 11),
+], ids=["C1", "C2", "C4-S8", "C4-S1", "r-large", "odd-b"])
+def test_many_steps_longer_runs(w, steps, per_call):
+    run_many_parity(w, steps, per_call=per_call)
 
 
 @pytest.mark.parametrize("window", [8, 4, 2])
