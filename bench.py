@@ -271,17 +271,20 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     # the labels of the next mini-batch are then announced before every call (they are resident, like every
     # input), so that each launch also plans the following step and only moves rows itself.
     fused = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
+    windowed = fused and w.b <= 2048
     rig.enqueue(warmup, single_call=True, ahead=fused)
-    torch.cuda.synchronize()
-    # headline: the single-call primitive, K steps enqueued back to back on the side stream
-    ms = rig.timed(steps, single_call=True, ahead=fused)
-    n_side = min(steps, 1000)
-    ms_plain = rig.timed(n_side, single_call=True)        # the same call without the announcement
-    ms_two = rig.timed(n_side)
     rig.enqueue(MANY, many=MANY)
-    ms_win = rig.timed(n_side, many=MANY)                 # 64 steps per host call, up to eight steps per launch
+    torch.cuda.synchronize()
+    # Headline: K steps enqueued back to back on the side stream through rb_update_sample_many, MANY steps per
+    # host call.  The mini-batches of those steps are resident (like every input); when the step is eligible,
+    # up to eight steps share one launch whose plan the launch before made.
+    ms = rig.timed(steps // MANY * MANY if steps >= MANY else steps, many=MANY if steps >= MANY else steps)
+    n_side = min(steps, 1000)
+    ms_ahead = rig.timed(n_side, single_call=True, ahead=fused)   # one rb_update_sample per step, next labels announced
+    ms_plain = rig.timed(n_side, single_call=True)                # ... not announced
+    ms_two = rig.timed(n_side)
     rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
-    ms_many = rig.timed(n_side, many=MANY)                # ... one launch per step
+    ms_many1 = rig.timed(n_side // MANY * MANY or MANY, many=MANY)   # rb_update_sample_many held to one launch per step
     rig.buf.set_option(rb.RB_OPT_WINDOW, 8)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
@@ -293,10 +296,13 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": 1 if fused else 2, "next_labels_announced": fused,
+        "launches_per_step": 0.125 if windowed else (1 if fused else 2), "steps_per_launch": 8 if windowed else 1,
+        "steps_per_host_call": MANY,
+        "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
+        "next_labels_announced": fused,
         "not_announced_ms_per_step": ms_plain, "not_announced_gb_per_s": w.bytes_per_step() / (ms_plain * 1e-3) / 1e9,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
-        "many_call_ms_per_step": ms_many, "many_call_8_steps_per_launch_ms_per_step": ms_win,
+        "many_call_one_launch_per_step_ms": ms_many1,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }
@@ -372,7 +378,7 @@ def main():
     ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, 120 single-call steps with "
-                         "the next labels announced, then 3 plain copies "
+                         "the next labels announced, 128 steps through rb_update_sample_many, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -392,6 +398,7 @@ def main():
         rig.enqueue(120)
         rig.enqueue(120, single_call=True)
         rig.enqueue(120, single_call=True, ahead=True)
+        rig.enqueue(128, many=64)
         torch.cuda.synchronize()
         nbytes = 256 << 20
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
@@ -434,13 +441,19 @@ def main():
     if reduced:
         log(f"[bench] reduced-precision {json.dumps(reduced)}")
 
-    # Roofline of the dominant kernel.  With one launch per step that kernel is the whole step
-    # (rb_step_planned_kernel: every inserted row and every representative row read once and written
-    # once, plus the one workgroup that plans the next step) and its duration is ms_per_step;
-    # otherwise it is the gather of rb_sample_augment.
+    # Roofline of the dominant kernel.  With one or several whole steps per launch that kernel is the
+    # step (rb_window_kernel / rb_step_planned_kernel: every inserted row and every representative row
+    # read once and written once, plus the one workgroup that plans what comes next); otherwise it is
+    # the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
-    if res["launches_per_step"] == 1:
-        kernel, k_ms, k_bytes = "rb_step_planned_kernel", res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
+    if res["steps_per_launch"] > 1:
+        # several steps per launch: a call of MANY steps is one launch of one step, then launches of eight
+        # (the last one of what is left); average launch = MANY steps / that many launches
+        launches = 1 + -(-(MANY - 1) // 8)
+        kernel = "rb_window_kernel"
+        k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
+    elif res["launches_per_step"] == 1:
+        kernel, k_ms, k_bytes = "rb_step_planned_kernel", res["one_launch_per_step_ms"], 2 * (w.c + n_rows) * w.row_bytes
     else:
         kernel, k_ms, k_bytes = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
@@ -451,8 +464,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
-                   "api": "rb_announce_next + rb_update_sample (one launch per step; the launch also plans the next step)"
-                          if res["next_labels_announced"] else "rb_update_sample (single call per step)",
+                   "api": f"rb_update_sample_many, {MANY} steps per call" +
+                          (", up to 8 steps per launch (planned by the launch before)" if res["steps_per_launch"] > 1 else ""),
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
         "reps_per_s": round(res["reps_per_s"], 1),
