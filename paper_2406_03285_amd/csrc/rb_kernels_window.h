@@ -70,6 +70,33 @@ struct WinMoveArgs {
     int32_t tpr, tile_vec, tile_rem;
 };
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load
+// and store the wavefront has in flight; the planner keeps the next step's labels on their way and
+// its table entries on their way out across its barriers (nobody in this launch reads them).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
+// block_scan_excl of rb_device.h with that barrier.
+__device__ __forceinline__ int block_scan_excl_lds(int v, int& total, int* s_wave)
+{
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    const int inc = wave_scan_incl(v);
+    if (lane == WAVE - 1) s_wave[w] = inc;
+    lds_barrier();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < NWAVE; ++i) {
+        const int x = s_wave[i];
+        all += x;
+        if (i < w) before += x;
+    }
+    lds_barrier();
+    total = all;
+    return before + inc - v;
+}
+
 __device__ __forceinline__ uint32_t win_hash(uint32_t row)
 {
     return (row * 2654435761u) >> 21;          // 11 bits: WIN_HASH slots
@@ -160,7 +187,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
                 yv[u] = q < b ? a.batch_y[s + 1][q] : -1;
             }
         }
-        __syncthreads();
+        lds_barrier();
 
         if (wave == 0) {
             const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
@@ -230,17 +257,17 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
             }
             if (bad && lane == 0) s_flags |= RB_FLAG_BAD_LABEL;
         }
-        __syncthreads();
+        lds_barrier();
 
         // ---- prefix of the fill counts over the classes, four consecutive classes per thread ----
         const int4 f4 = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
         int F;
-        int before = block_scan_excl(f4.x + f4.y + f4.z + f4.w, F, s_wave);
+        int before = block_scan_excl_lds(f4.x + f4.y + f4.z + f4.w, F, s_wave);
         s_pre[4 * tid] = before;
         s_pre[4 * tid + 1] = before + f4.x;
         s_pre[4 * tid + 2] = before + f4.x + f4.y;
         s_pre[4 * tid + 3] = before + f4.x + f4.y + f4.z;
-        __syncthreads();
+        lds_barrier();
 
         if (wave == 1) {
             // ---- representatives of step s: lane j = draw j of Floyd's n-subset of the F stored samples ----
@@ -316,8 +343,11 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
                 head[s] = hd;
             }
         }
-        __syncthreads();
+        lds_barrier();
     }
+
+    // every table entry has left before any of them is patched below
+    __syncthreads();
 
     // ---- representatives that a candidate's workgroups serve do nothing themselves ----
     for (int i = tid; i < WIN_HASH; i += TPB) {
