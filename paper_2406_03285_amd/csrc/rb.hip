@@ -360,12 +360,13 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     int i = 0;
     {
         const WinPlanArgs p = window_plan_args(rb, batch_y, 0, 1, b, c, r, seed, first_step, 0);
-        rb_window_plan_kernel<<<dim3(1), TPB, (size_t)b * 8, rb->stream>>>(p);
+        rb_window_plan_kernel<<<dim3(1), TPB, 0, rb->stream>>>(p);
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         rb->cur ^= 1;
     }
     while (at < n) {
-        const int64_t next_at = at + w, next_w = std::min(wmax, n - next_at);
+        // the windows grow (1, 3, 8, 8, ...): a launch should not have to wait for a plan much longer than its own copies
+        const int64_t next_at = at + w, next_w = std::min(std::min(wmax, 3 * w), n - next_at);
         WinPlanArgs next = {};
         if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
         WinMoveArgs m = {};
@@ -383,8 +384,8 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         m.row_vec = rb->row_vec;
         m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
         const dim3 grid((unsigned)(w * (c + r) * sh.tpr + (next_w > 0 ? 1 : 0)));
-        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, sh.unroll, grid, next_w > 0 ? (size_t)b * 8 : 0, rb->stream)
-                                        : launch_window<false>(m, next, sh.unroll, grid, next_w > 0 ? (size_t)b * 8 : 0, rb->stream);
+        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, sh.unroll, grid, 0, rb->stream)
+                                        : launch_window<false>(m, next, sh.unroll, grid, 0, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         at = next_at;

@@ -114,124 +114,189 @@ __device__ __forceinline__ int win_find_or_insert(uint32_t* s_hkey, uint32_t row
     }
 }
 
+// Orders the LDS traffic of ONE wavefront: what its lanes wrote before is what its lanes read after
+// (the lanes run in lockstep; this only keeps the compiler from moving or merging the accesses).
+__device__ __forceinline__ void wave_fence()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    __builtin_amdgcn_wave_barrier();
+}
+
+// What wavefront 0 knows of a step's candidates before they enter the row table (one lane each).
+struct WinCand {
+    int x;            // mini-batch position
+    int32_t k;        // class, LAB_* when not a valid candidate
+    int fill0;        // samples of the class stored before the step
+    int rank, total;  // class-mates earlier in the mini-batch / in all
+    int slot;         // slot within the class: appended, or drawn when the class is full
+    bool valid, bad, any_over;
+};
+
 // ---------------------------------------------------------------------------
 // The plan of a.w consecutive steps by one workgroup (all TPB threads call it).
-// Per step, as in the single-step planner: wavefront 0 = one lane per candidate,
-// all threads = prefix of the fill counts over the classes, wavefront 1 = one
-// lane per representative; the fill counts stay in LDS from step to step.
-//
-// LDS (dynamic): s_first[b] u32, s_y[b] i32.
+// Before the first step the wavefronts share the steps: each selects the
+// candidates of its steps (which depends on nothing but the seed) and requests
+// their labels, so that the only global loads the steps wait for are issued once,
+// all together.  Then, per step: wavefront 0 = one lane per candidate, all
+// threads = prefix of the fill counts over the classes, wavefront 1 = one lane
+// per representative; the fill counts stay in LDS from step to step.  The part
+// of a step's candidates that does not need the row table (insertion numbers,
+// eviction draws: win_candidates) runs in wavefront 0 while wavefront 1 still
+// works on the representatives of the step before; only entering the row table
+// is serial.  No dynamic LDS.
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
+struct WinLds {
+    int32_t* s_fill;      // [NCLS] fill counts, carried from step to step
+    int32_t* s_ck;        // [WAVE] candidate classes, positions, scratch (wavefront 0 only)
+    int32_t* s_cx;
+    int32_t* s_cw;
+    const uint16_t* s_wpos;   // [WIN_MAX * WAVE] mini-batch position of every step's candidates
+    const int16_t* s_lab;     // [WIN_MAX * WAVE] ... and their classes (LAB_* when there is none)
+};
+
+__device__ __forceinline__ Seed win_seed(const WinPlanArgs& a, int s)
+{
+    Seed sd;
+    sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
+    sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
+    return sd;
+}
+
+// Wavefront 0: candidates of step s, up to the slot each one asks for.  Needs the fill counts after step s-1.
+__device__ __forceinline__ WinCand win_candidates(const WinPlanArgs& a, int s, const WinLds& l)
+{
+    const int lane = threadIdx.x & (WAVE - 1);
+    const Seed sd = win_seed(a, s);
+    WinCand cd;
+    const int x = l.s_wpos[s * WAVE + lane];
+    const int32_t k = l.s_lab[s * WAVE + lane];
+    cd.x = x;
+    cd.k = k;
+    cd.valid = k >= 0;
+    cd.bad = __ballot(k == LAB_INVALID) != 0;
+    l.s_ck[lane] = cd.valid ? k : -1;
+    l.s_cx[lane] = x;
+    cd.fill0 = cd.valid ? l.s_fill[k] : 0;
+    wave_fence();
+    // insertion number within the class: fill0 + class-mates earlier in the mini-batch
+    int rank = 0, total = 0;
+#pragma unroll 4
+    for (int m = 0; m < a.c; m += 4) {
+        const int4 km = *reinterpret_cast<const int4*>(l.s_ck + m);
+        const int4 xm = *reinterpret_cast<const int4*>(l.s_cx + m);
+        rank += (int)(km.x == k && xm.x < x) + (int)(km.y == k && xm.y < x) + (int)(km.z == k && xm.z < x) +
+                (int)(km.w == k && xm.w < x);
+        total += (int)(km.x == k) + (int)(km.y == k) + (int)(km.z == k) + (int)(km.w == k);
+    }
+    cd.rank = rank;
+    cd.total = total;
+    const int64_t at = (int64_t)cd.fill0 + rank;
+    const bool over = cd.valid && at >= a.S;       // beyond the capacity: overwrites a drawn slot
+    cd.slot = cd.valid ? (int)at : -1;
+    cd.any_over = __ballot(over) != 0;
+    if (over) cd.slot = (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);
+    return cd;
+}
+
+__device__ __forceinline__ void plan_window(const WinPlanArgs& a)
 {
     constexpr int NCLS = DIRECT_CHUNKS * CH;
-    uint32_t* s_first = lds;                                   // [b]
-    int32_t* s_y = reinterpret_cast<int32_t*>(lds + a.b);      // [b]: labels of the current step
     __shared__ __align__(16) int32_t s_fill[NCLS];    // fill counts, carried from step to step
     __shared__ __align__(16) int32_t s_pre[NCLS];     // stored samples in the classes before each class, after the step's update
-    __shared__ uint32_t s_hkey[WIN_HASH];             // buffer rows the window touches ...
-    __shared__ uint32_t s_hval[WIN_HASH];             // ... low half: entry of the last candidate written there; high half:
+    __shared__ uint32_t s_h[2 * WIN_HASH];
+    uint32_t* s_hkey = s_h;                           // buffer rows the window touches ...
+    uint32_t* s_hval = s_h + WIN_HASH;                // ... low half: entry of the last candidate written there; high half:
                                                       //     head of the chain of representatives that read its old content
+                                                      // (before the first step: the scratch of the candidate selection)
     __shared__ uint64_t s_bits[WIN_MAX * WAVE];       // random bits of every step's sampling draws
     __shared__ uint16_t s_next[WIN_MAX * WAVE];       // per representative (step * WAVE + j): next entry of its chain
     __shared__ uint16_t s_wpos[WIN_MAX * WAVE];       // per candidate (step * WAVE + i): its mini-batch position
+    __shared__ int16_t s_lab[WIN_MAX * WAVE];         // ... and its class (LAB_INVALID, LAB_UNSELECTED)
     __shared__ int s_wave[NWAVE];
-    __shared__ __align__(16) int32_t s_ck[WAVE], s_cx[WAVE], s_cw[WAVE];
-    __shared__ __align__(16) uint32_t s_t[WAVE];
+    __shared__ __align__(16) int32_t s_ck[WAVE], s_cx[WAVE];
+    __shared__ __align__(16) uint32_t s_t[WAVE];      // wavefront 1, while it works on the representatives
+    int32_t* s_cw = reinterpret_cast<int32_t*>(s_t);  // wavefront 0, while the candidates enter the row table (wavefront 1 waits then)
     __shared__ uint32_t s_flags;
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int b = a.b, c = a.c, r = a.r, w = a.w;
     WinHeader* head = reinterpret_cast<WinHeader*>(a.table);
     WinEntry* entry = reinterpret_cast<WinEntry*>(a.table + WIN_MAX * sizeof(WinHeader));
+    WinLds l;
+    l.s_fill = s_fill; l.s_ck = s_ck; l.s_cx = s_cx; l.s_cw = s_cw; l.s_wpos = s_wpos; l.s_lab = s_lab;
 
-    // ---- before the first step: fill counts, empty row table, all sampling bits ----
-    int64_t yv[YPRE];
-#pragma unroll
-    for (int u = 0; u < YPRE; ++u) {
-        const int q = tid + u * TPB;
-        yv[u] = q < b ? a.batch_y[0][q] : -1;
-    }
+    // ---- before the first step ----
     int4 fo = make_int4(0, 0, 0, 0);
     if (4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
-    for (int i = tid; i < WIN_HASH; i += TPB) {
+    // candidates of all steps and their labels; a selecting wavefront needs b words of scratch
+    const int nsel = b <= 2 * WIN_HASH / NWAVE ? NWAVE : 2;
+    constexpr int SEL_MAX = WIN_MAX / 2;              // steps per selecting wavefront at most
+    int64_t ylab[SEL_MAX];
+    if (wave < nsel) {
+#pragma unroll
+        for (int u = 0; u < SEL_MAX; ++u) {
+            const int s = wave + u * nsel;
+            ylab[u] = -1;
+            if (s < w) {
+                bool active = false;
+                const int x = wave_select(win_seed(a, s), b, c, s_h + wave * b, active);
+                s_wpos[s * WAVE + lane] = (uint16_t)x;
+                if (active) ylab[u] = a.batch_y[s][x];
+            }
+        }
+    }
+    // all sampling bits
+    for (int s = wave; s < w; s += NWAVE)
+        if (lane < r) s_bits[s * WAVE + lane] = draw64(win_seed(a, s), PURPOSE_SAMPLE, (uint32_t)lane);
+    lds_barrier();
+    for (int i = tid; i < WIN_HASH; i += TPB) {       // empty row table
         s_hkey[i] = WIN_EMPTY;
         s_hval[i] = 0xFFFFFFFFu;
     }
-    if (wave != 0) {
-        // wavefronts 1..3 share the steps; wavefront 0 is already selecting the first step's candidates
-        for (int s = wave - 1; s < w; s += NWAVE - 1) {
-            Seed sd;
-            sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
-            sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
-            if (lane < r) s_bits[s * WAVE + lane] = draw64(sd, PURPOSE_SAMPLE, (uint32_t)lane);
-        }
-    }
     *reinterpret_cast<int4*>(s_fill + 4 * tid) = fo;
     if (tid == 0) s_flags = 0;
+    if (wave < nsel) {
+#pragma unroll
+        for (int u = 0; u < SEL_MAX; ++u) {
+            const int s = wave + u * nsel;
+            const int64_t y = ylab[u];
+            if (s < w) s_lab[s * WAVE + lane] = (int16_t)(lane < c ? ((y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID) : LAB_UNSELECTED);
+        }
+    }
+    lds_barrier();
+    WinCand cd = {};
+    if (wave == 0) cd = win_candidates(a, 0, l);
 
     for (int s = 0; s < w; ++s) {
-        Seed sd;
-        sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
-        sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
-
-        // ---- candidates of step s (wavefront 0); everybody parks the step's labels ----
-        bool active = false;
-        int x = 0;
-        if (wave == 0) x = wave_select(sd, b, c, s_first, active);
-        park_labels(yv, a.batch_y[s], b, a.K, s_y);
-        if (s + 1 < w) {                        // the next step's labels are requested now and parked a step later
-#pragma unroll
-            for (int u = 0; u < YPRE; ++u) {
-                const int q = tid + u * TPB;
-                yv[u] = q < b ? a.batch_y[s + 1][q] : -1;
-            }
-        }
-        lds_barrier();
-
         if (wave == 0) {
-            const int32_t k = active ? s_y[x] : LAB_UNSELECTED;
-            const bool valid = active && k >= 0;
-            const bool bad = __ballot(active && k == LAB_INVALID) != 0;
-            s_ck[lane] = valid ? k : -1;
-            s_cx[lane] = x;
-            s_wpos[s * WAVE + lane] = (uint16_t)x;
-            const int64_t fill0 = valid ? s_fill[k] : 0;
-            // insertion number within the class: fill0 + class-mates earlier in the mini-batch
-            int rank = 0, total = 0;
-#pragma unroll 4
-            for (int m = 0; m < c; m += 4) {
-                const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
-                const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
-                rank += (int)(km.x == k && xm.x < x) + (int)(km.y == k && xm.y < x) + (int)(km.z == k && xm.z < x) +
-                        (int)(km.w == k && xm.w < x);
-                total += (int)(km.x == k) + (int)(km.y == k) + (int)(km.z == k) + (int)(km.w == k);
-            }
-            const int64_t at = fill0 + rank;
-            const bool over = valid && at >= a.S;      // beyond the capacity: overwrites a drawn slot
-            int slot = valid ? (int)at : -1;
-            bool beaten = false;
-            if (__ballot(over) != 0) {
-                if (over) slot = (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);
-                s_cw[lane] = over ? slot : -2;
-                // not stored if a later class-mate overwrites the same slot
-#pragma unroll 4
-                for (int m = 0; m < c; m += 4) {
-                    const int4 km = *reinterpret_cast<const int4*>(s_ck + m);
-                    const int4 xm = *reinterpret_cast<const int4*>(s_cx + m);
-                    const int4 wm = *reinterpret_cast<const int4*>(s_cw + m);
-                    beaten |= (km.x == k && xm.x > x && wm.x == slot) | (km.y == k && xm.y > x && wm.y == slot) |
-                              (km.z == k && xm.z > x && wm.z == slot) | (km.w == k && xm.w > x && wm.w == slot);
-                }
-            }
-            const bool stored = valid && !beaten;
-            const int64_t row = stored ? (int64_t)k * a.S + slot : -1;
+            // ---- win_enter: the candidates of step s enter the row table ----
+            const int x = cd.x;
+            const int32_t k = cd.k;
+            const bool valid = cd.valid;
+            const int64_t row = valid ? (int64_t)k * a.S + cd.slot : -1;
             const int me = s * WIN_ROWS + lane;
+            int h = 0;
+            // candidates that share a slot share a table slot
+            if (valid) h = win_find_or_insert(s_hkey, (uint32_t)row);
+            wave_fence();
+            const uint32_t v = valid ? s_hval[h] : 0xFFFFFFFFu;
+            bool stored = valid;
+            if (cd.any_over) {
+                // of the candidates that ask for one slot only the last of the mini-batch is stored:
+                // one of them (whose lane number lands in the table slot) collects the largest position
+                s_cw[lane] = -1;
+                wave_fence();
+                if (valid) s_hval[h] = (uint32_t)lane;
+                wave_fence();
+                const int leader = valid ? (int)s_hval[h] : lane;
+                wave_fence();
+                if (valid) atomicMax(&s_cw[leader], x);
+                wave_fence();
+                stored = valid && s_cw[leader] == x;
+                wave_fence();
+            }
             int chain = -1;
             if (stored) {
-                // the stored candidates of one step go to different slots, so no two lanes share a table slot here
-                const int h = win_find_or_insert(s_hkey, (uint32_t)row);
-                const uint32_t v = s_hval[h];
                 const uint32_t before = v & 0xFFFFu, readers = v >> 16;
                 if (before != WIN_NONE) {              // an earlier step of the window wrote this slot: that write is dropped
                     entry[before].row = -1;
@@ -244,18 +309,18 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
                 WinEntry e;
                 e.src = x;
                 e.label = valid ? k : -1;
-                e.row = row;
+                e.row = stored ? row : -1;
                 e.chain = chain;
                 e.handled = 0;
                 e.pad[0] = 0; e.pad[1] = 0;
                 entry[me] = e;
             }
             // the class's fill count after this step (one lane per class: its first candidate)
-            if (valid && rank == 0) {
-                const int64_t v = fill0 + total;
-                s_fill[k] = (int32_t)(v < a.S ? v : a.S);
+            if (valid && cd.rank == 0) {
+                const int64_t f = (int64_t)cd.fill0 + cd.total;
+                s_fill[k] = (int32_t)(f < a.S ? f : a.S);
             }
-            if (bad && lane == 0) s_flags |= RB_FLAG_BAD_LABEL;
+            if (cd.bad && lane == 0) s_flags |= RB_FLAG_BAD_LABEL;
         }
         lds_barrier();
 
@@ -269,7 +334,9 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
         s_pre[4 * tid + 3] = before + f4.x + f4.y + f4.z;
         lds_barrier();
 
-        if (wave == 1) {
+        if (wave == 0) {
+            if (s + 1 < w) cd = win_candidates(a, s + 1, l);
+        } else if (wave == 1) {
             // ---- representatives of step s: lane j = draw j of Floyd's n-subset of the F stored samples ----
             const int n = r < F ? r : F;
             const int base = F - n;
@@ -298,12 +365,20 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
                 }
             }
             const int g = taken ? base + lane : (int)t;
-            int lo = 0, hi = NCLS - 1;
+            // class of stored sample number g: the last class with s_pre <= g, by three rounds of
+            // independent reads (every 64th class, every 4th, single ones)
+            int lo = 0;
             if (lane < n) {
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    if (s_pre[mid] <= g) lo = mid; else hi = mid - 1;
-                }
+                int cnt = 0;
+#pragma unroll
+                for (int i = 1; i < NCLS / 64; ++i) cnt += (int)(s_pre[64 * i] <= g);
+                lo = 64 * cnt;
+                cnt = 0;
+#pragma unroll
+                for (int i = 1; i < 16; ++i) cnt += (int)(s_pre[lo + 4 * i] <= g);
+                lo += 4 * cnt;
+                const int4 p4 = *reinterpret_cast<const int4*>(s_pre + lo);
+                lo += (int)(p4.y <= g) + (int)(p4.z <= g) + (int)(p4.w <= g);
             }
             const int pk = lo, ps = lane < n ? g - s_pre[lo] : 0;
             const int64_t row = (int64_t)pk * a.S + ps;
@@ -372,8 +447,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a, uint32_t* lds)
 // The plan of the first window of a call, on its own.
 __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a)
 {
-    extern __shared__ uint32_t lds[];
-    plan_window(a, lds);
+    plan_window(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -387,12 +461,11 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 template <int U, bool NT>
 __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, const WinPlanArgs next)
 {
-    extern __shared__ uint32_t lds[];
     if (next.w > 0 && blockIdx.x == 0) {
         // dispatched first, and first in line whenever it has an instruction ready: the next launch
         // waits for this one workgroup as much as for all the movers
         __builtin_amdgcn_s_setprio(3);
-        plan_window(next, lds);
+        plan_window(next);
         return;
     }
     const int mover = blockIdx.x - (next.w > 0 ? 1 : 0);
