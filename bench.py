@@ -447,9 +447,11 @@ def main():
     # the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
     if res["steps_per_launch"] > 1:
-        # several steps per launch: a call of MANY steps is one launch of one step, then launches of eight
-        # (the last one of what is left); average launch = MANY steps / that many launches
-        launches = 1 + -(-(MANY - 1) // 8)
+        # several steps per launch: a call of MANY steps is launches of 1, 3, 8, 8, ... steps (the last one
+        # of what is left); average launch = MANY steps / that many launches
+        launches, left, win = 0, MANY, 1
+        while left > 0:
+            launches, left, win = launches + 1, left - win, min(8, 3 * win, left - win)
         kernel = "rb_window_kernel"
         k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
     elif res["launches_per_step"] == 1:

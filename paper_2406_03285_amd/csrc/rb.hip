@@ -343,30 +343,41 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
 }
 
 // n steps as launches of up to WIN_MAX steps each.  Workgroup 0 of every launch plans the next
-// window while the others move the rows of this one; the first window is a single step, planned by
-// a launch of its own, so that the movers get going early.
+// window while the others move the rows of this one; the first window is planned by a launch of its
+// own and kept short, so that the movers get going early.
 int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
                    int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y)
 {
     const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(WIN_MAX, rb->opt_window));
-    // With thousands of workgroups per launch, and the planner's LDS leaving room for four workgroups per
+    // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
     // compute unit, tiles of four vectors per thread measured best (C4: 13.9 us per step against 14.9 with
     // two and 15.0 with eight; C3: 4.5 against 4.5 and 5.0).
     const int unroll_option = rb->opt_unroll;
     if (unroll_option == 0) rb->opt_unroll = 4;
     const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
     rb->opt_unroll = unroll_option;
-    int64_t at = 0, w = 1;
+    // Window sizes.  A launch of w steps should not have to wait for the plan of the next window, which the one
+    // planner workgroup makes meanwhile; so the windows grow as fast as that allows, and the first one (planned
+    // with nothing to hide behind) is the smallest from which they can grow.  Measured on MI355X: rows move at
+    // about 5.5 TB/s; a window's plan takes about 3 us more than a launch's own fixed cost, plus 1.6 us and
+    // 0.04 us per candidate or representative for every step.
+    const double move_us = 2.0 * (double)(c + r) * (double)rb->row_bytes / 5.5e6;
+    const double plan_us = 1.6 + 0.04 * (double)std::max(c, r);
+    const auto grown = [&](int64_t w) {
+        return std::max<int64_t>(1, std::min<int64_t>(wmax, (int64_t)((move_us * (double)w - 3.0) / plan_us)));
+    };
+    int64_t w0 = 1;
+    while (w0 < wmax && grown(w0) <= w0) ++w0;
+    int64_t at = 0, w = std::min(w0, n);
     int i = 0;
     {
-        const WinPlanArgs p = window_plan_args(rb, batch_y, 0, 1, b, c, r, seed, first_step, 0);
+        const WinPlanArgs p = window_plan_args(rb, batch_y, 0, w, b, c, r, seed, first_step, 0);
         rb_window_plan_kernel<<<dim3(1), TPB, 0, rb->stream>>>(p);
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         rb->cur ^= 1;
     }
     while (at < n) {
-        // the windows grow (1, 3, 8, 8, ...): a launch should not have to wait for a plan much longer than its own copies
-        const int64_t next_at = at + w, next_w = std::min(std::min(wmax, 3 * w), n - next_at);
+        const int64_t next_at = at + w, next_w = std::min(std::max(w, grown(w)), n - next_at);
         WinPlanArgs next = {};
         if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
         WinMoveArgs m = {};

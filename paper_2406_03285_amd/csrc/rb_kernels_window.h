@@ -162,6 +162,17 @@ __device__ __forceinline__ Seed win_seed(const WinPlanArgs& a, int s)
     return sd;
 }
 
+// Labels of step s of the window.  All WIN_MAX pointers are read from the kernel arguments at fixed offsets (one
+// batch of scalar loads at kernel entry) and the one asked for is picked by comparisons: an argument read at a
+// computed offset is a second, dependent trip to wherever the arguments live.
+__device__ __forceinline__ const int64_t* win_labels(const WinPlanArgs& a, int s)
+{
+    const int64_t* p = a.batch_y[0];
+#pragma unroll
+    for (int i = 1; i < WIN_MAX; ++i) p = s == i ? a.batch_y[i] : p;
+    return p;
+}
+
 // Wavefront 0: candidates of step s, up to the slot each one asks for.  Needs the fill counts after step s-1.
 __device__ __forceinline__ WinCand win_candidates(const WinPlanArgs& a, int s, const WinLds& l)
 {
@@ -218,7 +229,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     int32_t* s_cw = reinterpret_cast<int32_t*>(s_t);  // wavefront 0, while the candidates enter the row table (wavefront 1 waits then)
     __shared__ uint32_t s_flags;
 
-    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int b = a.b, c = a.c, r = a.r, w = a.w;
     WinHeader* head = reinterpret_cast<WinHeader*>(a.table);
     WinEntry* entry = reinterpret_cast<WinEntry*>(a.table + WIN_MAX * sizeof(WinHeader));
@@ -241,7 +252,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
                 bool active = false;
                 const int x = wave_select(win_seed(a, s), b, c, s_h + wave * b, active);
                 s_wpos[s * WAVE + lane] = (uint16_t)x;
-                if (active) ylab[u] = a.batch_y[s][x];
+                if (active) ylab[u] = win_labels(a, s)[x];
             }
         }
     }
@@ -453,8 +464,7 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 // ---------------------------------------------------------------------------
 // All steps of one window by its table: workgroup (step, entry, tile) moves one
 // tile of one row; if there is a next window, workgroup 0 plans it instead.  (The
-// planner's registers and LDS limit every compute unit to four workgroups of this
-// kernel.  Measured alternatives: the planner as a launch of its own on a second
+// planner's LDS limits every compute unit to five workgroups of this kernel.  Measured alternatives: the planner as a launch of its own on a second
 // stream frees the movers but the events that order the two streams cost more than
 // that gains.)
 // ---------------------------------------------------------------------------
