@@ -26,8 +26,12 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # HBM bytes per launch of the dominant kernel as counted by two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
 # known size; the text summaries with the exact commands are kept under profiles/.
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76913166,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77268708}
+# rb_window_kernel: the launches of one 64-step call (1, 2, 6, 8 x 6 and 7 steps) summed and divided by their
+# number, like the average launch the roofline is stated for (algorithmic: 493.25 MB; candidates that lose
+# their slot within a launch, and representatives taken from a mini-batch row still in cache, are not moved).
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 485228783,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76945479,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77295518}
 
 
 MANY = 64           # steps handed to one rb_update_sample_many call
@@ -296,7 +300,8 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": 0.125 if windowed else (1 if fused else 2), "steps_per_launch": 8 if windowed else 1,
+        "launches_per_step": len(window_schedule(w, MANY)) / MANY if windowed else (1 if fused else 2),
+        "steps_per_launch": 8 if windowed else 1, "steps_per_launch_schedule": window_schedule(w, MANY) if windowed else None,
         "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
         "next_labels_announced": fused,
@@ -307,6 +312,26 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }
     return rig, res
+
+
+def window_schedule(w, n, wmax=8):
+    """Steps per launch of one rb_update_sample_many call of n steps (the library's rule, restated: the windows
+    grow as fast as the one planner workgroup can keep ahead of the movers, from the smallest first window that
+    lets them grow)."""
+    move_us = 2.0 * (w.c + w.r) * w.row_bytes / 5.5e6
+    plan_us = 1.6 + 0.04 * max(w.c, w.r)
+
+    def grown(k):
+        return max(1, min(wmax, int((move_us * k - 3.0) / plan_us)))
+    w0 = 1
+    while w0 < wmax and grown(w0) <= w0:
+        w0 += 1
+    out, k = [], min(w0, n)
+    while n > 0:
+        out.append(k)
+        n -= k
+        k = min(max(k, grown(k)), n)
+    return out
 
 
 def host_pinned_leg(torch, rb, wl, steps=200):
@@ -447,11 +472,8 @@ def main():
     # the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
     if res["steps_per_launch"] > 1:
-        # several steps per launch: a call of MANY steps is launches of 1, 3, 8, 8, ... steps (the last one
-        # of what is left); average launch = MANY steps / that many launches
-        launches, left, win = 0, MANY, 1
-        while left > 0:
-            launches, left, win = launches + 1, left - win, min(8, 3 * win, left - win)
+        # several steps per launch; average launch = MANY steps / the launches of one call
+        launches = len(window_schedule(w, MANY))
         kernel = "rb_window_kernel"
         k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
     elif res["launches_per_step"] == 1:

@@ -287,6 +287,22 @@ class RehearsalBuffer:
             assert out_x.shape[0] >= r and out_y.shape[0] >= r
         _check(rb_update_sample(self.handle, batch_x, batch_y, b, c, r, seed, step, out_x, out_y), "rb_update_sample")
 
+    def update_sample_many(self, batch_x, batch_y, c, r, seed, first_step, out_x, out_y):
+        """len(batch_x) consecutive steps from one call (sequences of tensors, one per step)."""
+        n = len(batch_x)
+        assert len(batch_y) == n and (r == 0 or (len(out_x) == n and len(out_y) == n))
+        b = batch_y[0].shape[0]
+        for i in range(n):
+            assert batch_x[i].is_contiguous() and batch_y[i].is_contiguous() and batch_y[i].dtype == torch.int64
+            assert batch_x[i].dtype == self.dtype and tuple(batch_x[i].shape[1:]) == self.sample_shape
+            assert batch_x[i].shape[0] == b and batch_y[i].shape[0] == b
+            if r > 0:
+                assert out_x[i].is_contiguous() and out_y[i].is_contiguous() and out_y[i].dtype == torch.int64
+                assert out_x[i].dtype == self.dtype and tuple(out_x[i].shape[1:]) == self.sample_shape
+                assert out_x[i].shape[0] >= r and out_y[i].shape[0] >= r
+        _check(rb_update_sample_many(self.handle, n, batch_x, batch_y, b, c, r, seed, first_step,
+                                     out_x if r > 0 else None, out_y if r > 0 else None), "rb_update_sample_many")
+
     def read_state(self):
         rc, fill, last_n, flags = rb_read_state(self.handle, self.K)
         _check(rc, "rb_read_state")

@@ -204,8 +204,11 @@ def run_many_parity(w, steps, per_call=24, window=None):
         for i in range(n):
             _bytes(oxs[i]).fill_(SENTINEL)
             oys[i].fill_(-7)
-        rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
-        assert rc == rb.RB_OK, rc
+        if first % (2 * per_call) == 0:
+            rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
+            assert rc == rb.RB_OK, rc
+        else:           # the same through the class
+            buf.update_sample_many(xs, ys, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
         torch.cuda.synchronize()
         for i in range(n):
             t = first + i
