@@ -353,7 +353,10 @@ def test_many_steps_at_full_size(w, steps):
     (wl.variant(wl.C4, name="C4-S1-many", S=1, K=40, shape=(3, 32, 32)), 64, 32),  # 40 slots in all, 64 written and 64 read per step
     (wl.variant(wl.C1, name="C1-r-large-many", S=3, c=16, r=64, b=64), 40, 9),     # r above what is stored, then r = F
     (wl.variant(wl.C2, name="C2-odd-b-many", b=77, c=33, r=21, S=2), 60, 11),
-], ids=["C1", "C2", "C4-S8", "C4-S1", "r-large", "odd-b"])
+    (wl.variant(wl.C2, name="C2-b1500-many", b=1500, c=40, r=30, S=3, shape=(3, 8, 8)), 40, 17),   # more positions than one selecting wavefront per step gets scratch for
+    (wl.variant(wl.C4, name="C4-b2048-many", b=2048, c=64, r=64, S=2, K=1024, shape=(64,)), 32, 16),   # every limit of the several-steps launch at once
+    (wl.variant(wl.C1, name="C1-c1-many", c=1, r=1, S=2), 50, 13),
+], ids=["C1", "C2", "C4-S8", "C4-S1", "r-large", "odd-b", "b1500", "b2048", "c1"])
 def test_many_steps_longer_runs(w, steps, per_call):
     run_many_parity(w, steps, per_call=per_call)
 
@@ -387,6 +390,36 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
         assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"step {t}: labels differ"
         assert np.array_equal(parity_util._bytes(oxs[t]).cpu().numpy()[:n], ref_x[:n]), f"step {t}: rows differ"
     compare_buffers(buf, orc, "final")
+
+
+def test_many_steps_drop_and_flag_bad_labels():
+    """Labels outside [0, K) among the candidates of steps in the middle of a launch: not stored, flag raised."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    K, S, b, c, r, n = 5, 3, 12, 12, 6, 16
+    buf = rb.RehearsalBuffer(K, S, (8,), torch.float32, device=dev)
+    orc = rbo.Buffer(K, S, 32)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(5)
+    xs = [torch.randn((b, 8), generator=g).to(dev) for _ in range(n)]
+    ys = [torch.randint(0, K, (b,), generator=g, dtype=torch.int64) for _ in range(n)]
+    ys[3][::3] = -1
+    ys[9][1::4] = K
+    ys[10][5] = 10**12
+    ys = [y.to(dev) for y in ys]
+    oxs = [torch.zeros((r, 8), device=dev) for _ in range(n)]
+    oys = [torch.full((r,), -7, dtype=torch.int64, device=dev) for _ in range(n)]
+    buf.update_sample_many(xs[:3], ys[:3], c, r, 11, 0, oxs[:3], oys[:3])
+    assert buf.read_state()[2] == 0
+    buf.update_sample_many(xs[3:], ys[3:], c, r, 11, 3, oxs[3:], oys[3:])
+    torch.cuda.synchronize()
+    for t in range(n):
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), c, 11, t)
+        m, ref_x, ref_y = orc.sample_augment(r, 11, t)
+        assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"step {t}: labels differ"
+        assert np.array_equal(parity_util._bytes(oxs[t]).cpu().numpy()[:m], ref_x[:m]), f"step {t}: rows differ"
+    assert buf.read_state()[2] == rb.RB_FLAG_BAD_LABEL == orc.flags
+    compare_buffers(buf, orc, "bad labels in a window")
 
 
 # ----------------------------------------- the asynchronous primitive (Sec. IV-D) ---
