@@ -274,8 +274,11 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     # One launch per step is possible for at most 64 candidates and representatives and at most 1024 classes;
     # the labels of the next mini-batch are then announced before every call (they are resident, like every
     # input), so that each launch also plans the following step and only moves rows itself.
-    fused = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
-    windowed = fused and w.b <= 2048
+    # Larger counts (up to 1024 candidates and representatives, 10240 classes) have a plan-ahead form of their
+    # own: one launch per step that moves rows by the plan a 1024-thread workgroup of the launch before made.
+    small = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
+    fused = small or (1 <= w.c <= 1024 and 1 <= w.r <= 1024 and w.b <= 4096 and w.K <= 10240)
+    windowed = small and w.b <= 2048
     rig.enqueue(warmup, single_call=True, ahead=fused)
     rig.enqueue(MANY, many=MANY)
     torch.cuda.synchronize()
@@ -304,7 +307,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "steps_per_launch": 8 if windowed else 1, "steps_per_launch_schedule": window_schedule(w, MANY) if windowed else None,
         "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
-        "next_labels_announced": fused,
+        "next_labels_announced": fused, "plan_ahead_kernel": None if not fused else ("rb_step_planned_kernel" if small else "rb_step_big_kernel"),
         "not_announced_ms_per_step": ms_plain, "not_announced_gb_per_s": w.bytes_per_step() / (ms_plain * 1e-3) / 1e9,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
         "many_call_one_launch_per_step_ms": ms_many1,
@@ -477,7 +480,8 @@ def main():
         kernel = "rb_window_kernel"
         k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
     elif res["launches_per_step"] == 1:
-        kernel, k_ms, k_bytes = "rb_step_planned_kernel", res["one_launch_per_step_ms"], 2 * (w.c + n_rows) * w.row_bytes
+        # rb_update_sample_many announces every next step's labels for itself: one planned launch per step
+        kernel, k_ms, k_bytes = res["plan_ahead_kernel"], res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
     else:
         kernel, k_ms, k_bytes = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes
     achieved = k_bytes / (k_ms * 1e-3) / 1e9

@@ -34,6 +34,7 @@
 #include "rb_kernels_small.h"
 #include "rb_kernels_planned.h"
 #include "rb_kernels_window.h"
+#include "rb_kernels_big.h"
 #include "rb_kernels_aux.h"
 
 // ===========================================================================
@@ -306,6 +307,90 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
                              : launch_planned<true, false>(m, next, sh.unroll, grid, lds, rb->stream);
     else e = bf16 ? launch_planned<false, true>(m, next, sh.unroll, grid, lds, rb->stream)
                   : launch_planned<false, false>(m, next, sh.unroll, grid, lds, rb->stream);
+    if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
+    if (e != hipSuccess) return RB_EHIP;
+    rb->updates += 1;
+    return RB_OK;
+}
+
+// The 1024-thread kernels ask for more dynamic LDS than a kernel gets by default: allowed once per kernel and device.
+template <auto kernel>
+hipError_t allow_big_lds()
+{
+    static bool allowed[64] = {};
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return hipErrorInvalidDevice;
+    if (dev < 0 || dev >= 64 || !allowed[dev]) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void*>(kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                                                 (int)BIG_LDS_BYTES);
+        if (e != hipSuccess) return e;
+        if (dev >= 0 && dev < 64) allowed[dev] = true;
+    }
+    return hipSuccess;
+}
+
+template <int U, bool NT>
+hipError_t launch_big_u(const MoveArgs& m, const PlanArgs& next, dim3 grid, hipStream_t st)
+{
+    const size_t lds = m.plan_next ? BIG_LDS_BYTES : 0;
+    if (lds != 0) {
+        const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT>>();
+        if (e != hipSuccess) return e;
+    }
+    rb_step_big_kernel<U, NT><<<grid, BIG_TPB, lds, st>>>(m, next);
+    return hipGetLastError();
+}
+
+template <bool NT>
+hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: return launch_big_u<1, NT>(m, next, grid, st);
+    case 2: return launch_big_u<2, NT>(m, next, grid, st);
+    case 4: return launch_big_u<4, NT>(m, next, grid, st);
+    default: return launch_big_u<8, NT>(m, next, grid, st);
+    }
+}
+
+// One step of the plan-ahead form for large counts (up to BIG_MAX candidates and representatives, up to
+// BIG_CLASSES classes); same bookkeeping as step_planned, the tables are the (larger) ones that the
+// several-steps-per-launch form uses for shapes this form does not serve.
+int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
+             uint64_t seed, uint64_t step, void* out_x, int64_t* out_y, const int64_t* next_y)
+{
+    static_assert(BIG_TABLE_BYTES <= WIN_TABLE_BYTES, "the big plan's table must fit the window table");
+    if (!rb->plan_valid) {
+        PlanArgs now = make_plan(rb, batch_y, b, c, r, seed, step);
+        now.table = rb->ws + rb->off_wtbl[rb->tbl_next];
+        if (allow_big_lds<&rb_big_plan_kernel>() != hipSuccess) return RB_EHIP;
+        rb_big_plan_kernel<<<dim3(1), BIG_TPB, BIG_LDS_BYTES, rb->stream>>>(now);
+        if (hipGetLastError() != hipSuccess) return RB_EHIP;
+        plan_enqueued(rb, batch_y, b, c, r, seed, step);
+    }
+    const Shape sh = plan_shape(rb, c + r, BIG_GROUP);
+    MoveArgs m;
+    m.batch_x = static_cast<const vec16*>(batch_x);
+    m.buf_x = static_cast<vec16*>(rb->buf_x);
+    m.buf_y = rb->buf_y;
+    m.out_x = static_cast<vec16*>(out_x);
+    m.out_y = out_y;
+    m.table = rb->ws + rb->off_wtbl[rb->tbl_planned];
+    m.state = reinterpret_cast<DevState*>(rb->ws);
+    m.c = (int32_t)c; m.r = (int32_t)r;
+    m.S = rb->S;
+    m.row_vec = rb->row_vec;
+    m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
+    const int64_t items = (c + r) * sh.tpr;
+    rb->plan_valid = false;                     // this step is being executed
+    m.plan_next = next_y ? 1 : 0;
+    PlanArgs next = {};
+    if (next_y) {
+        next = make_plan(rb, next_y, b, c, r, seed, step + 1);
+        next.table = rb->ws + rb->off_wtbl[rb->tbl_next];
+    }
+    const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + m.plan_next));
+    const hipError_t e = rb->opt_nt ? launch_big<true>(m, next, sh.unroll, grid, rb->stream)
+                                    : launch_big<false>(m, next, sh.unroll, grid, rb->stream);
     if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
@@ -640,13 +725,19 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
                            rb->selection == RB_SELECT_EXACT;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
+    // larger counts have a plan-ahead form of their own (default policy, storage in the sample's own type)
+    const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
+                     rb->opt_fuse && rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM &&
+                     rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF);
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call
-    if (rb->plan_valid && !(plannable && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&
+    if (rb->plan_valid && !((plannable || big) && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&
                             rb->plan_seed == seed && rb->plan_step == step))
         discard_plan(rb);
     if (plannable && (rb->plan_valid || next_y))
         return step_planned(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y, next_y);
+    if (big && (rb->plan_valid || next_y))
+        return step_big(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y, next_y);
     if (!fused) {
         const int rc = rb_update(rb, batch_x, batch_y, b, c, seed, step);
         if (rc != RB_OK) return rc;

@@ -1,0 +1,382 @@
+// Plan-ahead kernels for the single-launch step with up to 1024 candidates and representatives and up
+// to 10240 classes (default policy): as in rb_kernels_planned.h the plan of a step is worked out by
+// ONE workgroup during the previous step's launch and left in a table, and the step's own launch only
+// moves rows by that table - but the workgroup has 1024 threads (one per candidate and per
+// representative) and finds class-mates, shared slots and repeated draws through hash tables in LDS
+// instead of loops over all candidates.
+// Included by rb.hip only, after rb_kernels_planned.h (whose table format and argument structs it uses).
+#pragma once
+
+#include "rb_device.h"
+#include "rb_kernels_planned.h"
+
+namespace {
+
+constexpr int BIG_TPB = 1024;                 // threads of a workgroup of these kernels
+constexpr int BIG_NWAVE = BIG_TPB / WAVE;
+constexpr int BIG_MAX = 1024;                 // most candidates / representatives: one thread each
+constexpr int BIG_PER = 10;                   // classes per thread in the prefix sums
+constexpr int BIG_CLASSES = BIG_TPB * BIG_PER;   // most classes
+constexpr int BIG_FILL = BIG_CLASSES + WAVE;  // words of the prefix table: one more than classes, rounded up
+constexpr int BIG_BATCH = 4096;               // largest mini-batch (words of the first-occurrence table)
+constexpr int BIG_HASH = 2048;                // slots of each hash table (at most BIG_MAX keys)
+constexpr uint32_t BIG_EMPTY = 0xFFFFFFFFu;   // free slot (no class, row or draw has this value)
+constexpr int BIG_GROUP = TPB;                // threads that move one tile together
+constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
+// LDS words: fill counts | region U | region V | selection / sampling draws
+constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX) * 4;
+constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
+
+__device__ __forceinline__ uint32_t big_hash(uint32_t key)
+{
+    return (key * 2654435761u) >> 21;          // 11 bits: BIG_HASH slots
+}
+
+// Slot of `key`, inserting it if it is not there (open addressing; at most half of the slots are ever used).
+__device__ __forceinline__ int big_find_or_insert(uint32_t* keys, uint32_t key)
+{
+    uint32_t h = big_hash(key);
+    for (;;) {
+        const uint32_t prev = atomicCAS(&keys[h], BIG_EMPTY, key);
+        if (prev == BIG_EMPTY || prev == key) return (int)h;
+        h = (h + 1) & (BIG_HASH - 1);
+    }
+}
+
+// Slot of `key`, -1 if it is not in the table (nobody inserts meanwhile).
+__device__ __forceinline__ int big_find(const uint32_t* keys, uint32_t key)
+{
+    uint32_t h = big_hash(key);
+    for (;;) {
+        const uint32_t at = keys[h];
+        if (at == key) return (int)h;
+        if (at == BIG_EMPTY) return -1;
+        h = (h + 1) & (BIG_HASH - 1);
+    }
+}
+
+// Floyd's subset, all draws at once (see wave_select): draw i is replaced by base + i iff an earlier
+// draw has the same value (`dup`, bit 31 of s_draw[i]), or it equals base + q for an earlier q whose
+// own draw was replaced.  s_draw holds every draw; returns whether draw `i` (value t) is replaced.
+__device__ __forceinline__ bool big_replaced(const uint32_t* s_draw, int i, int64_t base)
+{
+    int cur = i;
+    for (;;) {
+        const uint32_t pc = s_draw[cur];
+        if (pc >> 31) return true;
+        const int64_t q = (int64_t)pc - base;
+        if (q < 0 || q >= cur) return false;
+        cur = (int)q;
+    }
+}
+
+// Exclusive prefix sum of one int per thread over the BIG_TPB threads.  s_wave: BIG_NWAVE ints of LDS.
+__device__ __forceinline__ int big_scan_excl(int v, int& total, int* s_wave)
+{
+    const int lane = threadIdx.x & (WAVE - 1), w = threadIdx.x / WAVE;
+    const int inc = wave_scan_incl(v);
+    if (lane == WAVE - 1) s_wave[w] = inc;
+    __syncthreads();
+    int before = 0, all = 0;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) {
+        const int x = s_wave[i];
+        all += x;
+        if (i < w) before += x;
+    }
+    __syncthreads();
+    total = all;
+    return before + inc - v;
+}
+
+// ---------------------------------------------------------------------------
+// The whole plan of one step by one workgroup of BIG_TPB threads (all call it).
+// Thread i = candidate i of Floyd's emission order and representative i.  Same
+// decisions as rb_update_kernel followed by rb_sample_kernel (Alg. 1; uniform
+// sampling without replacement of Sec. IV-C), candidate by candidate and
+// representative by representative:
+//   selection      first occurrence of every draw through a table over the b
+//                  positions, then the chain walk;
+//   insertion      the candidates of a class are collected in a list (hash table
+//                  keyed by class -> counter and list start); a candidate's
+//                  insertion number is the class's fill count plus the list
+//                  members earlier in the mini-batch;
+//   last writer    hash table keyed by slot row -> largest mini-batch position
+//                  among the candidates that go there;
+//   sampling       repeated draws through a hash table keyed by the draw's value,
+//                  chain walk, class of the sample by a binary search of the
+//                  prefix sums of the fill counts after the update (all in LDS);
+//   forwarding     a representative whose slot is written in this very step is
+//                  copied from the mini-batch row stored there (row table again).
+//
+// LDS (dynamic, BIG_LDS_BYTES): s_fill[BIG_FILL], regions U and V of
+// 2 * BIG_HASH words each, s_draw[BIG_MAX].
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
+{
+    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the step, then after it, then their prefix sums
+    uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | class table | draw table
+    uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels | starts of the class lists | row table
+    uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws, then the class lists, then sampling draws (bit 31: repeated)
+    __shared__ int s_wave[BIG_NWAVE];
+    __shared__ uint32_t s_flags;
+
+    const int tid = threadIdx.x;
+    const int b = a.b, c = a.c, r = a.r, K = a.K;
+    const int64_t S = a.S;
+    PlanHeader* head = reinterpret_cast<PlanHeader*>(a.table);
+    PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
+
+    // ---- all labels and the fill counts before the step (requested now, parked after the selection draws) ----
+    static_assert(BIG_BATCH == 4 * BIG_TPB && BIG_BATCH <= 2 * BIG_HASH, "four labels per thread, parked in region V");
+    int64_t yv[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int q = tid + u * BIG_TPB;
+        yv[u] = q < b ? a.batch_y[q] : -1;
+    }
+    int32_t fo[BIG_PER];
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        fo[u] = q < K ? a.fill_old[q] : 0;
+    }
+
+    // ---- selection: Floyd's c-subset of the b positions ----
+    const bool active = tid < c;
+    const int sel_base = b - c;
+    const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)tid, (uint64_t)(sel_base + tid + 1)) : 0u;
+    if (active) s_u[t] = 0xFFFFFFFFu;
+    if (tid == 0) s_flags = 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+        const int64_t y = yv[u];
+        s_v[tid + u * BIG_TPB] = (uint32_t)((y >= 0 && y < K) ? (int32_t)y : LAB_INVALID);
+    }
+    __syncthreads();
+    if (active) atomicMin(&s_u[t], (uint32_t)tid);
+    __syncthreads();
+    if (active) s_draw[tid] = t | ((s_u[t] != (uint32_t)tid) ? 0x80000000u : 0u);     // t < 4096
+    __syncthreads();
+    const int x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : 0;
+
+    // ---- classes of the candidates; the sampling bits ----
+    const int32_t k = active ? (int32_t)s_v[x] : LAB_UNSELECTED;
+    const uint64_t bits = tid < r ? draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)tid) : 0;
+    // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
+    uint32_t* ckey = s_u;
+    uint32_t* ccnt = s_u + BIG_HASH;
+    uint32_t* list = s_draw;                    // [BIG_MAX]: position << 10 | candidate (between the two uses of s_draw)
+    uint32_t* cstart = s_v + BIG_MAX;           // [BIG_HASH]: start of the class's list
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
+        ckey[i] = BIG_EMPTY;
+        ccnt[i] = 0;
+    }
+    const bool valid = k >= 0;
+    if (k == LAB_INVALID) atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
+    __syncthreads();
+
+    // From here every stretch between two barriers carries a piece of the update's plan (thread =
+    // candidate) and an independent piece of the sampling's plan (thread = representative, or a
+    // stretch of classes), so that the round trips of the two overlap.
+
+    // ---- the candidates of every class are counted ----
+    int h = 0, arrival = 0;
+    if (valid) {
+        h = big_find_or_insert(ckey, (uint32_t)k);
+        arrival = (int)atomicAdd(&ccnt[h], 1u);
+    }
+    __syncthreads();
+    const int total = valid ? (int)ccnt[h] : 0;
+    const int64_t fill0 = valid ? s_fill[k] : 0;
+    {
+        // the lists of the classes follow each other in the order of the table's slots: two slots per thread
+        static_assert(BIG_HASH == 2 * BIG_TPB, "two table slots per thread");
+        const int c0 = (int)ccnt[2 * tid], c1 = (int)ccnt[2 * tid + 1];
+        int all;
+        const int lbefore = big_scan_excl(c0 + c1, all, s_wave);    // its barriers also end the reads of the labels in region V and of fill0
+        cstart[2 * tid] = (uint32_t)lbefore;
+        cstart[2 * tid + 1] = (uint32_t)(lbefore + c0);
+    }
+    // the class's fill count after the step (one thread per class)
+    if (valid && arrival == 0) s_fill[k] = (int32_t)(fill0 + total < S ? fill0 + total : S);
+    __syncthreads();
+
+    // ---- update: every candidate enters its class's list | sampling: fill counts out, sums of ten classes per thread ----
+    const int start = valid ? (int)cstart[h] : 0;
+    if (valid) list[start + arrival] = ((uint32_t)x << 10) | (uint32_t)tid;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        if (q < K) a.fill_new[q] = s_fill[q];
+    }
+    int nf[BIG_PER], local = 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        nf[u] = s_fill[BIG_PER * tid + u];
+        local += nf[u];
+    }
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int inc = wave_scan_incl(local);
+    if (lane == WAVE - 1) s_wave[wave] = inc;
+    __syncthreads();
+
+    // ---- update: insertion number and slot | sampling: prefix sums of the fill counts over the classes, in place ----
+    int rank = 0;
+    for (int i = 0; i < total; ++i) rank += (int)((int)(list[start + i] >> 10) < x);
+    const int64_t at = fill0 + rank;
+    const bool over = valid && at >= S;              // beyond the capacity: overwrites a uniformly drawn slot
+    int64_t slot = at;
+    if (over) slot = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S);
+    const int64_t row = valid ? (int64_t)k * S + slot : -1;
+    uint32_t* rkey = s_v;                            // slot rows written in this step (the list starts in region V have been read)
+    uint32_t* rmax = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there
+    uint32_t* dkey = s_u;                            // values of the sampling draws (the class table has been read)
+    uint32_t* dfirst = s_u + BIG_HASH;               // first draw with that value
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
+        rkey[i] = BIG_EMPTY;
+        rmax[i] = 0;
+        dkey[i] = BIG_EMPTY;
+        dfirst[i] = 0xFFFFFFFFu;
+    }
+    int F = 0, before = inc - local;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) {
+        const int v = s_wave[i];
+        F += v;
+        if (i < wave) before += v;
+    }
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        s_fill[BIG_PER * tid + u] = before;
+        before += nf[u];
+    }
+    for (int i = BIG_CLASSES + tid; i < BIG_FILL; i += BIG_TPB) s_fill[i] = F;
+    __syncthreads();
+
+    // ---- update: who goes to which slot | sampling: thread j = draw j of Floyd's n-subset of the F stored samples ----
+    int hr = 0;
+    if (valid) {
+        hr = big_find_or_insert(rkey, (uint32_t)row);
+        atomicMax(&rmax[hr], (uint32_t)x + 1u);
+    }
+    if (tid < a.nchunks) {
+        // stored samples per chunk of CH classes
+        const int lo = tid * CH, hi = lo + CH;
+        a.chunk_new[tid] = s_fill[hi] - s_fill[lo];
+    }
+    const int n = r < F ? r : F;
+    const int64_t base = (int64_t)F - n;
+    const bool drawing = tid < n;
+    const uint32_t g0 = drawing ? (uint32_t)__umul64hi(bits, (uint64_t)base + (uint64_t)tid + 1u) : 0u;   // < 2^31
+    int hd = 0;
+    if (drawing) {
+        hd = big_find_or_insert(dkey, g0);
+        atomicMin(&dfirst[hd], (uint32_t)tid);
+    }
+    __syncthreads();
+
+    // ---- update: of the candidates that go to one slot the last of the mini-batch is stored | sampling: repeated draws ----
+    const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
+    if (active) {
+        PlanEntry e;
+        e.pos = x;
+        e.label = valid ? k : -1;
+        e.row = stored ? row : -1;
+        entry[tid] = e;
+    }
+    if (drawing) s_draw[tid] = g0 | ((dfirst[hd] != (uint32_t)tid) ? 0x80000000u : 0u);
+    __syncthreads();
+
+    int32_t pk = -1;
+    int64_t prow = -1;
+    int fwd = -1;
+    if (drawing) {
+        const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
+        // its class: the last one whose prefix does not exceed g (empty classes share the prefix of the
+        // next non-empty one, which is the one meant; classes past K hold F > g)
+        int lo = 0, hi = BIG_CLASSES - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_fill[mid] <= g) lo = mid; else hi = mid - 1;
+        }
+        pk = lo;
+        prow = (int64_t)pk * S + (g - s_fill[lo]);
+        // written in this very step?  Then the stored candidate is what the slot holds.
+        const int hw = big_find(rkey, (uint32_t)prow);
+        if (hw >= 0) fwd = (int)rmax[hw] - 1;
+    }
+    if (tid < r) {
+        PlanEntry e;
+        e.pos = fwd;
+        e.label = pk;                           // -1 when fewer samples are stored than asked for
+        e.row = prow;
+        entry[c + tid] = e;
+    }
+    if (tid == 0) {
+        PlanHeader hh;
+        hh.n = n;
+        hh.flags = s_flags;
+        hh.c = c;
+        hh.r = r;
+        *head = hh;
+    }
+}
+
+// The plan of one step on its own (first step of a sequence).
+__global__ void __launch_bounds__(BIG_TPB) rb_big_plan_kernel(const PlanArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    plan_big(a, lds);
+}
+
+// ---------------------------------------------------------------------------
+// One step by its table: every group of BIG_GROUP threads moves one tile of one
+// row (candidates first, then representatives); with plan_next the first
+// workgroup of the grid plans the next step instead.
+// ---------------------------------------------------------------------------
+template <int U, bool NT>
+__global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, const PlanArgs next)
+{
+    extern __shared__ uint32_t lds[];
+    const bool plan_next = m.plan_next != 0;
+    if (plan_next && blockIdx.x == 0) {        // dispatched first: it has the longest way to go
+        __builtin_amdgcn_s_setprio(3);
+        plan_big(next, lds);
+        return;
+    }
+    const int64_t item = (int64_t)(blockIdx.x - (plan_next ? 1 : 0)) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
+    const int64_t items = (int64_t)(m.c + m.r) * m.tpr;
+    if (item >= items) return;
+    int e, tile;
+    split_item(item, m.tpr, e, tile);
+    const PlanHeader* head = reinterpret_cast<const PlanHeader*>(m.table);
+    const PlanEntry en = reinterpret_cast<const PlanEntry*>(m.table + sizeof(PlanHeader))[e];
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
+    const bool first = tile == 0 && (threadIdx.x & (BIG_GROUP - 1)) == 0;
+    if (item == 0 && first) {
+        const PlanHeader hh = *head;
+        m.state->last_n = hh.n;
+        if (hh.flags != 0) atomicOr(&m.state->flags, hh.flags);
+    }
+    if (e < m.c) {
+        if (en.row < 0) return;                 // label outside [0, K), or a later class-mate takes the slot
+        if (first) m.buf_y[en.row] = en.label;
+        Tile<U, NT, BIG_GROUP> t;
+        t.load(m.batch_x + (int64_t)en.pos * m.row_vec, v_lo, v_hi);
+        t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
+        return;
+    }
+    const int j = e - m.c;
+    if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
+    if (en.label < 0) return;
+    const vec16* src = en.pos >= 0 ? m.batch_x + (int64_t)en.pos * m.row_vec : m.buf_x + en.row * m.row_vec;
+    Tile<U, NT, BIG_GROUP> t;
+    t.load(src, v_lo, v_hi);
+    t.store(m.out_x + (int64_t)j * m.row_vec, v_lo, v_hi);
+}
+
+}  // namespace

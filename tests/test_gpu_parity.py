@@ -204,13 +204,63 @@ def test_storage_variant_argument_checks():
     (wl.variant(wl.C1, name="C1-r-large-ahead", S=3, c=16, r=64, b=64), 40),        # r above what is stored, then r = F
     (wl.variant(wl.C2, name="C2-odd-b-ahead", b=77, c=33, r=21, S=2), 60),
     (wl.variant(wl.C3, name="C3-S4-ahead", S=4, K=1000), 40),                       # full-size rows, many tiles
-    (wl.variant(wl.C5, name="C5-fallback-ahead", K=2000, S=4, shape=(64,), b=256, c=100, r=30), 15),   # not eligible: announcement ignored
+    (wl.variant(wl.C5, name="C5-fallback-ahead", K=20000, S=4, shape=(64,), b=256, c=100, r=30), 15),  # not eligible (too many classes): announcement ignored
 ], ids=["C1", "C4-S8", "one-class", "r-large", "odd-b", "C3-S4", "not-eligible"])
 def test_plan_ahead_steps(w, steps):
     run_ahead_parity(w, steps)
 
 
-@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40)], ids=["C3", "C4"])
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C5, name="C5-K300-big", K=300, S=12, shape=(256,), b=512, c=200, r=150), 40),      # classes fill up: drawn slots, shared slots
+    (wl.variant(wl.C5, name="C5-K2000-big", K=2000, S=4, shape=(64,), b=256, c=100, r=30), 25),
+    (wl.variant(wl.C5, name="C5-limits-big", K=10240, S=3, shape=(16,), b=4096, c=1024, r=1024), 12), # every limit at once
+    (wl.variant(wl.C4, name="C4-zipf-big", K=1000, S=8, shape=(3, 8, 8), b=2048, c=700, r=900), 20),  # Zipf head: a class list of hundreds
+    (wl.variant(wl.C1, name="C1-one-class-big", K=1, S=50, b=300, c=300, r=100), 10),                 # one list of 300, every slot contested
+    (wl.variant(wl.C2, name="C2-r-large-big", K=100, S=2, b=128, c=70, r=500), 12),                   # r above what is stored, then r = F
+    (wl.variant(wl.C3, name="C3-K1100-big", K=1100, S=2), 12),                                        # few full-size rows (many tiles each), too many classes for the small plan
+    (wl.variant(wl.C5, name="C5-K5000-odd-big", K=5003, S=7, shape=(12,), b=777, c=333, r=211), 25),
+], ids=["K300", "K2000", "limits", "zipf", "one-class", "r-large", "C3-K1100", "odd"])
+def test_plan_ahead_steps_with_large_counts(w, steps):
+    """More than 64 candidates or representatives, or more than 1024 classes: the plan of a 1024-thread workgroup."""
+    run_ahead_parity(w, steps)
+
+
+@pytest.mark.parametrize("seed", [4, 5])
+def test_plan_ahead_with_large_counts_survives_broken_promises(seed):
+    run_ahead_parity(wl.variant(wl.C5, name=f"C5-big-promises-{seed}", K=300, S=12, shape=(256,), b=512, c=200, r=150), 70, schedule_seed=seed)
+
+
+def test_plan_ahead_with_large_counts_drops_and_flags_bad_labels():
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    K, S, b, c, r, n = 1500, 2, 200, 150, 90, 6
+    buf = rb.RehearsalBuffer(K, S, (8,), torch.float32, device=dev)
+    orc = rbo.Buffer(K, S, 32)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(6)
+    xs = [torch.randn((b, 8), generator=g).to(dev) for _ in range(n)]
+    ys = [torch.randint(0, K, (b,), generator=g, dtype=torch.int64) for _ in range(n)]
+    ys[2][::3] = -1
+    ys[4][1::4] = K
+    ys[4][5] = 10**12
+    ys = [y.to(dev) for y in ys]
+    out_x = torch.zeros((r, 8), device=dev)
+    out_y = torch.full((r,), -7, dtype=torch.int64, device=dev)
+    for t in range(n):
+        if t + 1 < n:
+            buf.announce_next(ys[t + 1])
+        buf.update_sample(xs[t], ys[t], c, r, 21, t, out_x, out_y)
+        if t < 2:
+            assert buf.read_state()[2] == 0          # step 2 is planned during step 1, its flag is raised when it runs
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), c, 21, t)
+        m, ref_x, ref_y = orc.sample_augment(r, 21, t)
+        assert np.array_equal(out_y.cpu().numpy(), ref_y), f"step {t}: labels differ"
+        assert np.array_equal(parity_util._bytes(out_x).cpu().numpy()[:m], ref_x[:m]), f"step {t}: rows differ"
+    assert buf.read_state()[2] == rb.RB_FLAG_BAD_LABEL == orc.flags
+    compare_buffers(buf, orc, "bad labels, large counts")
+
+
+@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40), (wl.C5, 12)], ids=["C3", "C4", "C5"])
 def test_plan_ahead_at_full_size(w, steps):
     """The configuration the bench times: real shapes, one launch per step, next labels announced."""
     run_ahead_parity(w, w.steps if FULL else steps)
