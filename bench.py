@@ -30,6 +30,7 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # number, like the average launch the roofline is stated for (algorithmic: 493.25 MB; candidates that lose
 # their slot within a launch, and representatives taken from a mini-batch row still in cache, are not moved).
 MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 485228783,
+                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 137167583,      # 4, 5, 7, 8 x 6 steps; algorithmic 137.01 MB
                     ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76945479,
                     ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77295518}
 
