@@ -98,7 +98,8 @@ class Rig:
     def enqueue(self, n, do_update=True, do_sample=True, single_call=False, many=0, ahead=False):
         """Enqueue n consecutive steps on the side stream (no synchronisation).
         many: hand the steps to rb_update_sample_many, `many` of them per call.
-        ahead: with single_call, announce the next pool slot's labels before every call (plan-ahead form)."""
+        ahead: announce the labels that come next before every call (plan-ahead forms): the next pool slot's
+        with single_call, those of the next call's first eight steps with many."""
         w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
         upd, smp, both = rb.rb_update, rb.rb_sample_augment, rb.rb_update_sample
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
@@ -110,6 +111,9 @@ class Rig:
                 k = min(many, n - at)
                 o = (t % P) * C.sizeof(C.c_void_p)
                 px, py, ox, oy = (C.cast(C.byref(a, o), C.POINTER(C.c_void_p)) for a in self.ptrs)
+                if ahead:
+                    o_next = ((t + k) % P) * C.sizeof(C.c_void_p)
+                    rb.rb_announce_next_many(h, 8, C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
                 rc = rb.rb_update_sample_many(h, k, px, py, b, c, r, seed, t, ox, oy)
                 if rc:
                     raise RuntimeError(f"rb_update_sample_many -> {rc}")
@@ -281,13 +285,15 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     fused = small or (1 <= w.c <= 1024 and 1 <= w.r <= 1024 and w.b <= 4096 and w.K <= 10240)
     windowed = small and w.b <= 2048
     rig.enqueue(warmup, single_call=True, ahead=fused)
-    rig.enqueue(MANY, many=MANY)
+    rig.enqueue(MANY, many=MANY, ahead=True)
     torch.cuda.synchronize()
     # Headline: K steps enqueued back to back on the side stream through rb_update_sample_many, MANY steps per
-    # host call.  The mini-batches of those steps are resident (like every input); when the step is eligible,
-    # up to eight steps share one launch whose plan the launch before made.
-    ms = rig.timed(steps // MANY * MANY if steps >= MANY else steps, many=MANY if steps >= MANY else steps)
+    # host call, the labels of the next call's first eight steps announced before every call.  The mini-batches
+    # of all those steps are resident (like every input); when the step is eligible, up to eight steps share one
+    # launch whose plan the launch before made (also across calls: that is what the announcement is for).
+    ms = rig.timed(steps // MANY * MANY if steps >= MANY else steps, many=MANY if steps >= MANY else steps, ahead=True)
     n_side = min(steps, 1000)
+    ms_many_plain = rig.timed(n_side // MANY * MANY or MANY, many=MANY)    # the same without announcing the next call
     ms_ahead = rig.timed(n_side, single_call=True, ahead=fused)   # one rb_update_sample per step, next labels announced
     ms_plain = rig.timed(n_side, single_call=True)                # ... not announced
     ms_two = rig.timed(n_side)
@@ -304,8 +310,11 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": len(window_schedule(w, MANY)) / MANY if windowed else (1 if fused else 2),
-        "steps_per_launch": 8 if windowed else 1, "steps_per_launch_schedule": window_schedule(w, MANY) if windowed else None,
+        "launches_per_step": len(window_schedule(w, MANY, announced=True)) / MANY if windowed else (1 if fused else 2),
+        "steps_per_launch": 8 if windowed else 1,
+        "steps_per_launch_schedule": window_schedule(w, MANY, announced=True) if windowed else None,
+        "next_call_not_announced_ms_per_step": ms_many_plain,
+        "next_call_not_announced_schedule": window_schedule(w, MANY) if windowed else None,
         "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
         "next_labels_announced": fused, "plan_ahead_kernel": None if not fused else ("rb_step_planned_kernel" if small else "rb_step_big_kernel"),
@@ -318,10 +327,13 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     return rig, res
 
 
-def window_schedule(w, n, wmax=8):
+def window_schedule(w, n, wmax=8, announced=False):
     """Steps per launch of one rb_update_sample_many call of n steps (the library's rule, restated: the windows
     grow as fast as the one planner workgroup can keep ahead of the movers, from the smallest first window that
-    lets them grow)."""
+    lets them grow; when every call's first steps were announced to the call before, they have grown to the
+    largest size and stay there)."""
+    if announced:
+        return [min(wmax, n - at) for at in range(0, n, wmax)]
     move_us = 2.0 * (w.c + w.r) * w.row_bytes / 5.5e6
     plan_us = 1.6 + 0.04 * max(w.c, w.r)
 
@@ -427,7 +439,7 @@ def main():
         rig.enqueue(120)
         rig.enqueue(120, single_call=True)
         rig.enqueue(120, single_call=True, ahead=True)
-        rig.enqueue(128, many=64)
+        rig.enqueue(192, many=64, ahead=True)
         torch.cuda.synchronize()
         nbytes = 256 << 20
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
@@ -477,7 +489,7 @@ def main():
     n_rows = min(w.r, res["last_n"])
     if res["steps_per_launch"] > 1:
         # several steps per launch; average launch = MANY steps / the launches of one call
-        launches = len(window_schedule(w, MANY))
+        launches = len(window_schedule(w, MANY, announced=True))
         kernel = "rb_window_kernel"
         k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
     elif res["launches_per_step"] == 1:
@@ -493,7 +505,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
-                   "api": f"rb_update_sample_many, {MANY} steps per call" +
+                   "api": f"rb_announce_next_many + rb_update_sample_many, {MANY} steps per call" +
                           (", up to 8 steps per launch (planned by the launch before)" if res["steps_per_launch"] > 1 else ""),
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),

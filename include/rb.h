@@ -221,6 +221,29 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
                           void *const *out_x, int64_t *const *out_y);
 
 /*
+ * rb_announce_next for rb_update_sample_many: the labels of the first n steps
+ * of the call AFTER the next rb_update_sample_many call (the data pipeline has
+ * them already).  The last launch of the next call then also plans those steps
+ * (at most 8, and at most what one launch covers), so that the call after it
+ * starts moving rows at once instead of planning its first steps in a launch
+ * of its own.  The plan is used if that later call comes with the same b, c,
+ * r and seed, with first_step continuing where the call before ended, with at
+ * least the planned number of steps, and with exactly the announced label
+ * pointers for them; otherwise (or if any other call on the handle comes
+ * first) it is dropped and nothing is lost but the time it took.  Results are
+ * bit for bit those of the plain calls.  When the steps go out one by one
+ * (see rb_update_sample_many) the first announced labels serve as
+ * rb_announce_next for the call's last step.  The announcement serves the one
+ * next rb_update_sample_many call and is forgotten by any other call.
+ * next_batch_y: HOST array of n device pointers (read before the call
+ * returns; only the first 8 are kept), each to b int64 labels that must be in
+ * place, as far as the bound stream is concerned, when the next call is
+ * enqueued, and stay unchanged until their steps have run.  n = 0 withdraws.
+ * RB_EINVAL: null rb, n < 0, null or misaligned label pointers.
+ */
+int rb_announce_next_many(rb_buffer *rb, int64_t n, const int64_t *const *next_batch_y);
+
+/*
  * The asynchronous form of that primitive (Sec. IV-D, Fig. 4, Listing 1): the
  * training loop calls it once per iteration with the iteration's mini-batch;
  * the call (1) makes `train_stream` wait until the representatives that the

@@ -24,7 +24,7 @@ RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
     "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
-    "rb_announce_next", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
+    "rb_announce_next", "rb_announce_next_many", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -38,7 +38,7 @@ class RbError(RuntimeError):
 def _load():
     if not os.path.exists(LIB_PATH):
         raise ImportError(
-            f"{LIB_PATH} is missing: build it with `python -m paper_2406_03285_amd.build` "
+            f"{LIB_PATH} is missing: build it with `python paper_2406_03285_amd/build.py` "
             "(there is no fallback path)")
     L = C.CDLL(LIB_PATH)
     vp, i64, u64, i32, sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_int32, C.c_size_t
@@ -52,6 +52,7 @@ def _load():
     L.rb_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
     L.rb_update_sample.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp]
     L.rb_announce_next.argtypes = [vp, vp]
+    L.rb_announce_next_many.argtypes = [vp, i64, C.POINTER(vp)]
     L.rb_update_sample_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp)]
     L.rb_pipeline_create.argtypes = [C.POINTER(vp), vp]
     L.rb_pipeline_step.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp, vp, C.POINTER(i64)]
@@ -138,6 +139,12 @@ def rb_update_sample(rb, batch_x, batch_y, b, c, r, seed, step, out_x, out_y):
 
 def rb_announce_next(rb, next_batch_y):
     return _L.rb_announce_next(rb, _ptr(next_batch_y))
+
+
+def rb_announce_next_many(rb, n, next_batch_y):
+    """next_batch_y: sequence of n label tensors / addresses, or an array made by pointer_array."""
+    arr = next_batch_y if next_batch_y is None or isinstance(next_batch_y, (C.Array, C._Pointer)) else pointer_array(next_batch_y)
+    return _L.rb_announce_next_many(rb, int(n), arr)
 
 
 def pointer_array(items):
@@ -291,7 +298,7 @@ class RehearsalBuffer:
         """len(batch_x) consecutive steps from one call (sequences of tensors, one per step)."""
         n = len(batch_x)
         assert len(batch_y) == n and (r == 0 or (len(out_x) == n and len(out_y) == n))
-        b = batch_y[0].shape[0]
+        b = batch_y[0].shape[0] if n else 1
         for i in range(n):
             assert batch_x[i].is_contiguous() and batch_y[i].is_contiguous() and batch_y[i].dtype == torch.int64
             assert batch_x[i].dtype == self.dtype and tuple(batch_x[i].shape[1:]) == self.sample_shape
@@ -302,6 +309,12 @@ class RehearsalBuffer:
                 assert out_x[i].shape[0] >= r and out_y[i].shape[0] >= r
         _check(rb_update_sample_many(self.handle, n, batch_x, batch_y, b, c, r, seed, first_step,
                                      out_x if r > 0 else None, out_y if r > 0 else None), "rb_update_sample_many")
+
+    def announce_next_many(self, next_batch_y):
+        """Labels of the first steps of the update_sample_many call after the next one."""
+        for y in next_batch_y:
+            assert y.is_contiguous() and y.dtype == torch.int64
+        _check(rb_announce_next_many(self.handle, len(next_batch_y), next_batch_y), "rb_announce_next_many")
 
     def read_state(self):
         rc, fill, last_n, flags = rb_read_state(self.handle, self.K)

@@ -73,6 +73,16 @@ struct rb_buffer {
     int64_t plan_b, plan_c, plan_r;
     uint64_t plan_seed, plan_step;
     const int64_t* next_y;   // announced labels of the next mini-batch, consumed by the next rb_update_sample
+    // several steps per launch: labels announced for the call after the next rb_update_sample_many, and the
+    // window that the last launch of a call planned for them
+    const int64_t* ann_y[8];
+    int64_t ann_n;
+    bool wplan_valid;        // a window has been planned (and the fill counts advanced) but not yet executed
+    const int64_t* wplan_y[8];
+    int64_t wplan_w, wplan_b, wplan_c, wplan_r;
+    uint64_t wplan_seed, wplan_first;
+    int wplan_tbl;           // table that holds it
+    int64_t wplan_nat;       // size the windows have grown to (the planned one may be shorter: what was left, what was announced)
 };
 
 namespace {
@@ -233,13 +243,23 @@ hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int unroll, d
 // be executed as planned: the fill counts go back to the copy the planner read (it only wrote the
 // other one).  An announcement that has not been used yet is forgotten as well: it was made for the
 // call that should have come next.
+void discard_window_plan(rb_buffer* rb)
+{
+    if (rb->wplan_valid) {
+        rb->cur ^= 1;
+        rb->wplan_valid = false;
+    }
+}
+
 void discard_plan(rb_buffer* rb)
 {
     if (rb->plan_valid) {
         rb->cur ^= 1;
         rb->plan_valid = false;
     }
+    discard_window_plan(rb);
     rb->next_y = nullptr;
+    rb->ann_n = 0;
 }
 
 PlanArgs make_plan(const rb_buffer* rb, const int64_t* batch_y, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t step)
@@ -429,9 +449,11 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
 
 // n steps as launches of up to WIN_MAX steps each.  Workgroup 0 of every launch plans the next
 // window while the others move the rows of this one; the first window is planned by a launch of its
-// own and kept short, so that the movers get going early.
+// own and kept short, so that the movers get going early - unless the last launch of the call before
+// planned it (ann_y: labels announced for the first ann_n steps of the call after this one).
 int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
-                   int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y)
+                   int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
+                   int64_t ann_n, const int64_t* const* ann_y)
 {
     const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(WIN_MAX, rb->opt_window));
     // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
@@ -453,18 +475,37 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     };
     int64_t w0 = 1;
     while (w0 < wmax && grown(w0) <= w0) ++w0;
-    int64_t at = 0, w = std::min(w0, n);
-    int i = 0;
-    {
-        const WinPlanArgs p = window_plan_args(rb, batch_y, 0, w, b, c, r, seed, first_step, 0);
+    int64_t at = 0, w;
+    int tbl;
+    bool resume = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
+                  rb->wplan_seed == seed && rb->wplan_first == first_step;
+    for (int64_t k = 0; resume && k < rb->wplan_w; ++k) resume = rb->wplan_y[k] == batch_y[k];
+    int64_t nat;                                // size the windows have grown to, whatever a call's end cut them down to
+    if (resume) {
+        w = rb->wplan_w;
+        tbl = rb->wplan_tbl;
+        nat = rb->wplan_nat;
+        rb->wplan_valid = false;                // it is being executed
+    } else {
+        discard_window_plan(rb);
+        w = std::min(w0, n);
+        nat = w0;
+        tbl = 0;
+        const WinPlanArgs p = window_plan_args(rb, batch_y, 0, w, b, c, r, seed, first_step, tbl);
         rb_window_plan_kernel<<<dim3(1), TPB, 0, rb->stream>>>(p);
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         rb->cur ^= 1;
     }
     while (at < n) {
-        const int64_t next_at = at + w, next_w = std::min(std::max(w, grown(w)), n - next_at);
+        const int64_t next_at = at + w;
+        nat = std::min(wmax, std::max(nat, grown(nat)));
+        int64_t next_w = std::min(nat, n - next_at);
+        // the last launch of the call plans the first steps of the call that was announced
+        const bool ahead = next_w == 0 && ann_n > 0;
+        if (ahead) next_w = std::min(nat, ann_n);
         WinPlanArgs next = {};
-        if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, (i + 1) & 1);
+        if (ahead) next = window_plan_args(rb, ann_y, 0, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1);
+        else if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, tbl ^ 1);
         WinMoveArgs m = {};
         for (int64_t k = 0; k < w; ++k) {
             m.batch_x[k] = static_cast<const vec16*>(batch_x[at + k]);
@@ -473,7 +514,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         }
         m.buf_x = static_cast<vec16*>(rb->buf_x);
         m.buf_y = rb->buf_y;
-        m.table = rb->ws + rb->off_wtbl[i & 1];
+        m.table = rb->ws + rb->off_wtbl[tbl];
         m.state = reinterpret_cast<DevState*>(rb->ws);
         m.w = (int32_t)w; m.c = (int32_t)c; m.r = (int32_t)r;
         m.S = rb->S;
@@ -484,9 +525,17 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                                         : launch_window<false>(m, next, sh.unroll, grid, 0, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
+        if (ahead) {
+            rb->wplan_valid = true;
+            rb->wplan_w = next_w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
+            rb->wplan_seed = seed; rb->wplan_first = first_step + (uint64_t)n;
+            rb->wplan_tbl = tbl ^ 1;
+            rb->wplan_nat = nat;
+            for (int64_t k = 0; k < next_w; ++k) rb->wplan_y[k] = ann_y[k];
+        }
         at = next_at;
-        w = next_w;
-        ++i;
+        w = ahead ? 0 : next_w;
+        tbl ^= 1;
     }
     rb->updates += n;
     return RB_OK;
@@ -564,6 +613,7 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_wtbl[1] = off; off += WIN_TABLE_BYTES;
     rb->ws_bytes = off;
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
+    rb->ann_n = 0; rb->wplan_valid = false; rb->wplan_tbl = 0;
     rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
     rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = WIN_MAX;
     *out = rb;
@@ -610,6 +660,7 @@ int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* h
     rb->cur = 0;
     rb->updates = 0;
     rb->plan_valid = false; rb->next_y = nullptr; rb->tbl_next = 0;
+    rb->ann_n = 0; rb->wplan_valid = false;
     rb->bound = true;
     return RB_OK;
 }
@@ -720,6 +771,8 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
 {
     const int bad = check_step(rb, batch_x, batch_y, b, c, r, out_x, out_y);
     if (bad != RB_OK) return bad;
+    discard_window_plan(rb);                     // a single step is not what a planned window was made for
+    rb->ann_n = 0;
 
     // the plan-ahead form covers both storage forms; the kernel that plans and moves in one launch only the plain one
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
@@ -784,12 +837,28 @@ int rb_announce_next(rb_buffer* rb, const int64_t* next_batch_y)
     return RB_OK;
 }
 
+int rb_announce_next_many(rb_buffer* rb, int64_t n, const int64_t* const* next_batch_y)
+{
+    if (!rb || n < 0 || (n > 0 && !next_batch_y)) return RB_EINVAL;
+    const int64_t keep = std::min<int64_t>(n, WIN_MAX);        // more than one launch can cover is of no use
+    for (int64_t i = 0; i < keep; ++i)
+        if (!next_batch_y[i] || !aligned(next_batch_y[i], 8)) return RB_EINVAL;
+    for (int64_t i = 0; i < keep; ++i) rb->ann_y[i] = next_batch_y[i];
+    rb->ann_n = keep;
+    return RB_OK;
+}
+
 int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y,
                           int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
                           void* const* out_x, int64_t* const* out_y)
 {
     if (!rb || n < 0 || !batch_x || !batch_y) return RB_EINVAL;
     if (r > 0 && (!out_x || !out_y)) return RB_EINVAL;
+    // what was announced is about the call after this one and serves this call only
+    const int64_t ann_n = rb->ann_n;
+    const int64_t* ann_y[WIN_MAX];
+    for (int64_t i = 0; i < ann_n; ++i) ann_y[i] = rb->ann_y[i];
+    rb->ann_n = 0;
     for (int64_t i = 0; i < n; ++i) {
         const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (bad != RB_OK) return bad;
@@ -798,11 +867,17 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
                           rb->opt_fuse && rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT &&
                           rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
     if (windowed) {
-        discard_plan(rb);
-        return steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y);
+        if (rb->plan_valid) {                    // a single step that was planned ahead is not executed as planned
+            rb->cur ^= 1;
+            rb->plan_valid = false;
+        }
+        rb->next_y = nullptr;
+        return steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
     }
+    discard_window_plan(rb);
     for (int64_t i = 0; i < n; ++i) {
-        rb->next_y = i + 1 < n ? batch_y[i + 1] : nullptr;      // the next step's labels are known: plan ahead
+        // the next step's labels are known: plan ahead (also across calls when the next call's first labels were announced)
+        rb->next_y = i + 1 < n ? batch_y[i + 1] : (ann_n > 0 ? ann_y[0] : nullptr);
         const int rc = rb_update_sample(rb, batch_x[i], batch_y[i], b, c, r, seed, first_step + (uint64_t)i,
                                         r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (rc != RB_OK) return rc;      // only a failed launch can get here

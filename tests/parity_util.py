@@ -184,9 +184,11 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
     assert buf.read_state()[2] == orc.flags
 
 
-def run_many_parity(w, steps, per_call=24, window=None):
+def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None):
     """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
-    against the oracle step by step."""
+    against the oracle step by step.  announce: the labels of the next call's first steps are announced
+    before every call (the last launch of a call then plans them); with a schedule seed some of those
+    promises are broken (other labels, another c, fewer steps than planned, another call in between)."""
     import paper_2406_03285_amd as rb
 
     dev = torch.device("cuda:0")
@@ -196,28 +198,52 @@ def run_many_parity(w, steps, per_call=24, window=None):
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
     oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(per_call)]
     oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(per_call)]
-    for first in range(0, steps, per_call):
-        n = min(per_call, steps - first)
+    rng = np.random.default_rng(schedule_seed)
+
+    def make(first):
+        n = max(0, min(per_call, steps - first))
         batches = [wl.make_batch(w, first + i, dev) for i in range(n)]
-        xs = [x.contiguous() for x, _ in batches]
-        ys = [y.contiguous() for _, y in batches]
+        return [x.contiguous() for x, _ in batches], [y.contiguous() for _, y in batches]
+
+    first = 0
+    xs, ys = make(0)
+    while first < steps:
+        n = len(xs)
+        nxs, nys = make(first + n)              # the next call's mini-batches are there before this call is enqueued
+        what = "keep" if schedule_seed is None else rng.choice(["keep", "keep", "other-labels", "other-c", "fewer-steps", "read-state"])
+        c = w.c
+        if what == "other-labels" and n > 1:    # the call that comes is not the one that was announced
+            ys[min(1, n - 1)] = ys[min(1, n - 1)].clone()
+        if what == "other-c":
+            c = max(1, w.c - 1)
+        if what == "fewer-steps" and n > 2:     # fewer steps than the launch before may have planned
+            nxs, nys = xs[2:] + nxs, ys[2:] + nys
+            nxs, nys = nxs[:per_call], nys[:per_call]
+            xs, ys, n = xs[:2], ys[:2], 2
+        if what == "read-state":
+            assert np.array_equal(buf.read_state()[0], orc.fill)
         for i in range(n):
             _bytes(oxs[i]).fill_(SENTINEL)
             oys[i].fill_(-7)
+        if announce and nys:
+            buf.announce_next_many(nys[:8])
         if first % (2 * per_call) == 0:
-            rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
+            rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
             assert rc == rb.RB_OK, rc
         else:           # the same through the class
-            buf.update_sample_many(xs, ys, w.c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
+            buf.update_sample_many(xs, ys, c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
         torch.cuda.synchronize()
         for i in range(n):
             t = first + i
-            orc.update(_bytes(xs[i]).cpu().numpy(), ys[i].cpu().numpy(), w.c, w.lib_seed, t)
+            orc.update(_bytes(xs[i]).cpu().numpy(), ys[i].cpu().numpy(), c, w.lib_seed, t)
             ref = np.full((w.r, w.row_bytes), SENTINEL, dtype=np.uint8)
             nn, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
-            assert np.array_equal(oys[i].cpu().numpy(), ref_y), f"{w.name} step {t}: out_y differs"
-            assert np.array_equal(_bytes(oxs[i]).cpu().numpy(), ref_x), f"{w.name} step {t}: out_x differs (n={nn})"
-        compare_state(buf, orc, f"{w.name} step {first + n - 1}")
-        assert buf.read_state()[1] == nn
+            assert np.array_equal(oys[i].cpu().numpy(), ref_y), f"{w.name} step {t} ({what}): out_y differs"
+            assert np.array_equal(_bytes(oxs[i]).cpu().numpy(), ref_x), f"{w.name} step {t} ({what}): out_x differs (n={nn})"
+        if not announce:        # (reading the state would drop a window that was planned across calls)
+            compare_state(buf, orc, f"{w.name} step {first + n - 1}")
+            assert buf.read_state()[1] == nn
+        first += n
+        xs, ys = nxs, nys
     compare_buffers(buf, orc, f"{w.name} final")
-
+    assert buf.read_state()[1] == nn

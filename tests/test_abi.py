@@ -100,3 +100,15 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_pipeline_drain(None)[0] == rb.RB_EINVAL
     assert rb.rb_pipeline_destroy(None) == rb.RB_EINVAL
     assert rb.rb_update_sample_many(None, 1, [256], [256], 4, 2, 2, 0, 0, [256], [256]) == rb.RB_EINVAL
+    # announcements: only host-visible checks, nothing is dereferenced
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_F32)
+    assert rb.rb_announce_next(None, 256) == rb.RB_EINVAL and rb.rb_announce_next(h, 4) == rb.RB_EINVAL
+    assert rb.rb_announce_next(h, 256) == rb.RB_OK and rb.rb_announce_next(h, None) == rb.RB_OK
+    assert rb.rb_announce_next_many(None, 1, [256]) == rb.RB_EINVAL
+    assert rb.rb_announce_next_many(h, -1, [256]) == rb.RB_EINVAL
+    assert rb.rb_announce_next_many(h, 2, [256, 4]) == rb.RB_EINVAL          # misaligned
+    assert rb.rb_announce_next_many(h, 2, [256, 0]) == rb.RB_EINVAL          # null
+    assert rb.rb_announce_next_many(h, 1, None) == rb.RB_EINVAL
+    assert rb.rb_announce_next_many(h, 12, [256 * (i + 1) for i in range(12)]) == rb.RB_OK
+    assert rb.rb_announce_next_many(h, 0, None) == rb.RB_OK
+    rb.rb_destroy(h)

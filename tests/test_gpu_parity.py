@@ -411,6 +411,55 @@ def test_many_steps_longer_runs(w, steps, per_call):
     run_many_parity(w, steps, per_call=per_call)
 
 
+@pytest.mark.parametrize("w,steps,per_call", [
+    (wl.C1, 100, 17),
+    (wl.C2, 96, 8),                                                                # every call is one launch, planned by the call before
+    (wl.variant(wl.C4, name="C4-S8-announced", S=8, shape=(3, 32, 32)), 96, 32),
+    (wl.variant(wl.C4, name="C4-S1-announced", S=1, K=40, shape=(3, 32, 32)), 60, 20),
+    (wl.variant(wl.C3, name="C3-S4-announced", S=4), 30, 10),                      # full-size rows
+    (wl.variant(wl.C5, name="C5-announced", K=300, S=12, shape=(256,), b=512, c=200, r=150), 30, 7),   # steps go out one by one: plan-ahead chain across calls
+], ids=["C1", "C2-one-launch", "C4-S8", "C4-S1", "C3-S4", "one-by-one"])
+def test_many_steps_with_the_next_call_announced(w, steps, per_call):
+    run_many_parity(w, steps, per_call=per_call, announce=True)
+
+
+@pytest.mark.parametrize("seed", [1, 2, 3])
+def test_many_steps_announced_survive_broken_promises(seed):
+    run_many_parity(wl.variant(wl.C4, name=f"C4-S8-many-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 160, per_call=12,
+                    announce=True, schedule_seed=seed)
+    run_many_parity(wl.variant(wl.C1, name=f"C1-many-promises-{seed}"), 120, per_call=9, announce=True, schedule_seed=seed + 10)
+
+
+def test_an_announced_call_that_never_comes_is_forgotten():
+    """Labels of a next call are announced and planned, then single steps come instead."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    w = wl.C1
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    batches = [wl.make_batch(w, t, dev) for t in range(20)]
+    xs, ys = [x.contiguous() for x, _ in batches], [y.contiguous() for _, y in batches]
+    oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(20)]
+    oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(20)]
+    buf.announce_next_many(ys[6:12])
+    buf.update_sample_many(xs[:6], ys[:6], w.c, w.r, w.lib_seed, 0, oxs[:6], oys[:6])       # plans steps 6.. as well
+    buf.update_sample(xs[6], ys[6], w.c, w.r, w.lib_seed, 6, oxs[6], oys[6])               # a single step instead
+    buf.announce_next_many(ys[7:9])                                                        # announced, but the wrong call follows
+    buf.update(xs[7], ys[7], w.c, w.lib_seed, 7)
+    buf.sample_augment(w.r, w.lib_seed, 7, oxs[7], oys[7])
+    buf.update_sample_many(xs[8:14], ys[8:14], w.c, w.r, w.lib_seed, 8, oxs[8:14], oys[8:14])
+    buf.announce_next_many(ys[14:20])
+    buf.update_sample_many(xs[14:14], ys[14:14], w.c, w.r, w.lib_seed, 14, oxs[14:14], oys[14:14])   # no steps: the announcement is spent
+    buf.update_sample_many(xs[14:20], ys[14:20], w.c, w.r, w.lib_seed, 14, oxs[14:20], oys[14:20])
+    torch.cuda.synchronize()
+    for t in range(20):
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), w.c, w.lib_seed, t)
+        n, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t)
+        assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"step {t}: labels differ"
+        assert np.array_equal(parity_util._bytes(oxs[t]).cpu().numpy()[:n], ref_x[:n]), f"step {t}: rows differ"
+    compare_buffers(buf, orc, "final")
+
+
 @pytest.mark.parametrize("window", [8, 4, 2])
 def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     """Eight classes of one slot each, every step samples all eight rows and rewrites one class (the label
