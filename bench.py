@@ -52,7 +52,7 @@ class Rig:
         self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream,
                                       storage=storage, store_dtype=store_dtype)
         aug_bytes = (w.b + w.r) * w.row_bytes
-        self.P = pool_slots or min(1024, max(8, -(-POOL_BYTES // aug_bytes)))
+        self.P = pool_slots or min(1024, max(16, -(-POOL_BYTES // aug_bytes)))
         self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
         self.aug_y = torch.empty((self.P, w.b + w.r), dtype=torch.int64, device=self.dev)
         # distinct sample bytes for a few slots, replicated over the pool (generation is not what is measured);
@@ -73,7 +73,7 @@ class Rig:
             bx, by = self.aug_x[i].data_ptr(), self.aug_y[i].data_ptr()
             self.args.append((bx, by, bx + w.b * rs, by + w.b * 8))
         # host arrays of the same pointers for rb_update_sample_many: the pool several times over, so that any run
-        # of up to MANY consecutive steps is contiguous (the pool has at least 8 slots: the steps that share a
+        # of up to MANY consecutive steps is contiguous (the pool has at least 16 slots: the steps that share a
         # launch never share a slot)
         self.ptrs = [rb.pointer_array([a[i] for a in self.args] * (2 + MANY // self.P)) for i in range(4)]
         self.step = 0
@@ -113,7 +113,7 @@ class Rig:
                 px, py, ox, oy = (C.cast(C.byref(a, o), C.POINTER(C.c_void_p)) for a in self.ptrs)
                 if ahead:
                     o_next = ((t + k) % P) * C.sizeof(C.c_void_p)
-                    rb.rb_announce_next_many(h, 8, C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
+                    rb.rb_announce_next_many(h, min(16, many), C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
                 rc = rb.rb_update_sample_many(h, k, px, py, b, c, r, seed, t, ox, oy)
                 if rc:
                     raise RuntimeError(f"rb_update_sample_many -> {rc}")
@@ -299,7 +299,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     ms_two = rig.timed(n_side)
     rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
     ms_many1 = rig.timed(n_side // MANY * MANY or MANY, many=MANY)   # rb_update_sample_many held to one launch per step
-    rig.buf.set_option(rb.RB_OPT_WINDOW, 8)
+    rig.buf.set_option(rb.RB_OPT_WINDOW, 16)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).
@@ -311,7 +311,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "launches_per_step": len(window_schedule(w, MANY, announced=True)) / MANY if windowed else (1 if fused else 2),
-        "steps_per_launch": 8 if windowed else 1,
+        "steps_per_launch": max(window_schedule(w, MANY, announced=True)) if windowed else 1,
         "steps_per_launch_schedule": window_schedule(w, MANY, announced=True) if windowed else None,
         "next_call_not_announced_ms_per_step": ms_many_plain,
         "next_call_not_announced_schedule": window_schedule(w, MANY) if windowed else None,
@@ -327,11 +327,13 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     return rig, res
 
 
-def window_schedule(w, n, wmax=8, announced=False):
+def window_schedule(w, n, wmax=None, announced=False):
     """Steps per launch of one rb_update_sample_many call of n steps (the library's rule, restated: the windows
     grow as fast as the one planner workgroup can keep ahead of the movers, from the smallest first window that
     lets them grow; when every call's first steps were announced to the call before, they have grown to the
     largest size and stay there)."""
+    if wmax is None:
+        wmax = max(1, min(16, 1024 // (w.c + w.r), 512 // max(w.c, w.r)))      # what the planner's tables hold
     if announced:
         return [min(wmax, n - at) for at in range(0, n, wmax)]
     move_us = 2.0 * (w.c + w.r) * w.row_bytes / 5.5e6
@@ -342,11 +344,12 @@ def window_schedule(w, n, wmax=8, announced=False):
     w0 = 1
     while w0 < wmax and grown(w0) <= w0:
         w0 += 1
-    out, k = [], min(w0, n)
+    out, k, nat = [], min(w0, n), w0
     while n > 0:
         out.append(k)
         n -= k
-        k = min(max(k, grown(k)), n)
+        nat = min(wmax, max(nat, grown(nat)))
+        k = min(nat, n)
     return out
 
 
@@ -506,7 +509,7 @@ def main():
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
                    "api": f"rb_announce_next_many + rb_update_sample_many, {MANY} steps per call" +
-                          (", up to 8 steps per launch (planned by the launch before)" if res["steps_per_launch"] > 1 else ""),
+                          (f", {res['steps_per_launch']} steps per launch (planned by the launch before)" if res["steps_per_launch"] > 1 else ""),
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
         "reps_per_s": round(res["reps_per_s"], 1),

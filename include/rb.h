@@ -204,17 +204,18 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * n consecutive rb_update_sample steps from one call, for callers that have
  * several mini-batches ready (e.g. a prefetching data pipeline).  When the
  * steps are eligible for the single launch (see rb_update_sample; b <= 2048)
- * up to 8 of them share ONE launch: the rows of all of them are moved at once,
+ * up to 16 of them (1024 / (c + r) and 512 / max(c, r) at most) share ONE
+ * launch: the rows of all of them are moved at once,
  * by a plan that one workgroup of the launch before made (what the order of
  * separate launches would settle between steps - a representative read from a
  * slot that another step of the same launch writes - the plan settles), so the
- * cost of a launch is paid once per 8 steps.  Otherwise the steps are enqueued
+ * cost of a launch is paid once per that many steps.  Otherwise the steps are enqueued
  * one after the other.  Step i uses batch_x[i], batch_y[i], step number
  * first_step + i and writes to out_x[i], out_y[i]; b, c, r and
  * seed are common.  The four pointer arrays are HOST arrays of n device
  * pointers, read before the call returns.  All n steps are validated first;
  * on an error nothing was enqueued.  Results are those of n separate calls.
- * The outputs and mini-batches of any 8 consecutive steps must not overlap.
+ * The outputs and mini-batches of any 16 consecutive steps must not overlap.
  */
 int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
                           int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
@@ -224,7 +225,7 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
  * rb_announce_next for rb_update_sample_many: the labels of the first n steps
  * of the call AFTER the next rb_update_sample_many call (the data pipeline has
  * them already).  The last launch of the next call then also plans those steps
- * (at most 8, and at most what one launch covers), so that the call after it
+ * (at most 16, and at most what one launch covers), so that the call after it
  * starts moving rows at once instead of planning its first steps in a launch
  * of its own.  The plan is used if that later call comes with the same b, c,
  * r and seed, with first_step continuing where the call before ended, with at
@@ -236,7 +237,7 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
  * rb_announce_next for the call's last step.  The announcement serves the one
  * next rb_update_sample_many call and is forgotten by any other call.
  * next_batch_y: HOST array of n device pointers (read before the call
- * returns; only the first 8 are kept), each to b int64 labels that must be in
+ * returns; only the first 16 are kept), each to b int64 labels that must be in
  * place, as far as the bound stream is concerned, when the next call is
  * enqueued, and stay unchanged until their steps have run.  n = 0 withdraws.
  * RB_EINVAL: null rb, n < 0, null or misaligned label pointers.
@@ -296,8 +297,8 @@ int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint3
  * the other when a row fits a single tile (0 = automatic, else 1..16).
  * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
  * 0 makes it always enqueue the two kernels.  RB_OPT_WINDOW: most steps that
- * rb_update_sample_many puts into one launch (1..8, default 8; 1 = one launch
- * per step). */
+ * rb_update_sample_many puts into one launch (1..16, default 16; 1 = one
+ * launch per step). */
 enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
 

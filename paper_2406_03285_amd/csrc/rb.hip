@@ -75,10 +75,10 @@ struct rb_buffer {
     const int64_t* next_y;   // announced labels of the next mini-batch, consumed by the next rb_update_sample
     // several steps per launch: labels announced for the call after the next rb_update_sample_many, and the
     // window that the last launch of a call planned for them
-    const int64_t* ann_y[8];
+    const int64_t* ann_y[16];
     int64_t ann_n;
     bool wplan_valid;        // a window has been planned (and the fill counts advanced) but not yet executed
-    const int64_t* wplan_y[8];
+    const int64_t* wplan_y[16];
     int64_t wplan_w, wplan_b, wplan_c, wplan_r;
     uint64_t wplan_seed, wplan_first;
     int wplan_tbl;           // table that holds it
@@ -455,7 +455,10 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                    int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
                    int64_t ann_n, const int64_t* const* ann_y)
 {
-    const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(WIN_MAX, rb->opt_window));
+    static_assert(WIN_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
+    // most steps of one launch: the option, and what the planner's tables hold
+    const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
+                                                                std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
     // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
     // compute unit, tiles of four vectors per thread measured best (C4: 13.9 us per step against 14.9 with
     // two and 15.0 with eight; C3: 4.5 against 4.5 and 5.0).

@@ -10,9 +10,10 @@
 
 namespace {
 
-constexpr int WIN_MAX = 8;                    // most steps one launch covers
-constexpr int WIN_ROWS = 2 * WAVE;            // table entries per step: candidates first, then representatives
-constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_MAX * WIN_ROWS keys)
+constexpr int WIN_MAX = 16;                   // most steps one launch covers ...
+constexpr int WIN_ENTRIES = 1024;             // ... as long as steps * (c + r) table entries do not exceed this
+constexpr int WIN_SLOTS = 512;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
+constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_ENTRIES keys)
 constexpr uint32_t WIN_NONE = 0xFFFFu;        // "no entry" in the 16-bit links below
 constexpr uint32_t WIN_EMPTY = 0xFFFFFFFFu;   // free slot of the row table (no buffer row has this index)
 
@@ -29,7 +30,7 @@ struct WinHeader {        // one per step
     uint32_t flags;       // RB_FLAG_* raised by the step
     int32_t pad[2];
 };
-struct WinEntry {         // 32 bytes; entry index = step * WIN_ROWS + (candidate i | c + representative j)
+struct WinEntry {         // 32 bytes; entry index = step * (c + r) + (candidate i | c + representative j)
     int32_t src;          // candidate: its mini-batch position.  representative: -1 = read the slot, else
                           // (step in the window << 16 | mini-batch position) of the row stored there
     int32_t label;        // class; representative: -1 = fewer samples stored than asked for
@@ -40,7 +41,7 @@ struct WinEntry {         // 32 bytes; entry index = step * WIN_ROWS + (candidat
     int32_t handled;      // representative: 1 = served by a candidate's workgroups, its own do nothing
     int32_t pad[2];
 };
-constexpr size_t WIN_TABLE_BYTES = (WIN_MAX * sizeof(WinHeader) + WIN_MAX * WIN_ROWS * sizeof(WinEntry) + 255) / 256 * 256;
+constexpr size_t WIN_TABLE_BYTES = (WIN_MAX * sizeof(WinHeader) + WIN_ENTRIES * sizeof(WinEntry) + 255) / 256 * 256;
 
 struct WinPlanArgs {
     const int64_t* batch_y[WIN_MAX];   // labels of the steps that are planned
@@ -150,8 +151,9 @@ struct WinLds {
     int32_t* s_ck;        // [WAVE] candidate classes, positions, scratch (wavefront 0 only)
     int32_t* s_cx;
     int32_t* s_cw;
-    const uint16_t* s_wpos;   // [WIN_MAX * WAVE] mini-batch position of every step's candidates
-    const int16_t* s_lab;     // [WIN_MAX * WAVE] ... and their classes (LAB_* when there is none)
+    const uint16_t* s_wpos;   // [WIN_SLOTS] mini-batch position of every step's candidates (step * max(c, r) + i)
+    const int16_t* s_lab;     // [WIN_SLOTS] ... and their classes (LAB_INVALID when outside [0, K))
+    int stride;               // of the per-step arrays: max(c, r)
 };
 
 __device__ __forceinline__ Seed win_seed(const WinPlanArgs& a, int s)
@@ -179,8 +181,8 @@ __device__ __forceinline__ WinCand win_candidates(const WinPlanArgs& a, int s, c
     const int lane = threadIdx.x & (WAVE - 1);
     const Seed sd = win_seed(a, s);
     WinCand cd;
-    const int x = l.s_wpos[s * WAVE + lane];
-    const int32_t k = l.s_lab[s * WAVE + lane];
+    const int x = lane < a.c ? l.s_wpos[s * l.stride + lane] : 0;
+    const int32_t k = lane < a.c ? l.s_lab[s * l.stride + lane] : LAB_UNSELECTED;
     cd.x = x;
     cd.k = k;
     cd.valid = k >= 0;
@@ -219,10 +221,10 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     uint32_t* s_hval = s_h + WIN_HASH;                // ... low half: entry of the last candidate written there; high half:
                                                       //     head of the chain of representatives that read its old content
                                                       // (before the first step: the scratch of the candidate selection)
-    __shared__ uint64_t s_bits[WIN_MAX * WAVE];       // random bits of every step's sampling draws
-    __shared__ uint16_t s_next[WIN_MAX * WAVE];       // per representative (step * WAVE + j): next entry of its chain
-    __shared__ uint16_t s_wpos[WIN_MAX * WAVE];       // per candidate (step * WAVE + i): its mini-batch position
-    __shared__ int16_t s_lab[WIN_MAX * WAVE];         // ... and its class (LAB_INVALID, LAB_UNSELECTED)
+    __shared__ uint64_t s_bits[WIN_SLOTS];            // random bits of every step's sampling draws (step * max(c, r) + j)
+    __shared__ uint16_t s_next[WIN_SLOTS];            // per representative (step * max(c, r) + j): next entry of its chain
+    __shared__ uint16_t s_wpos[WIN_SLOTS];            // per candidate (step * max(c, r) + i): its mini-batch position
+    __shared__ int16_t s_lab[WIN_SLOTS];              // ... and its class (LAB_INVALID when outside [0, K))
     __shared__ int s_wave[NWAVE];
     __shared__ __align__(16) int32_t s_ck[WAVE], s_cx[WAVE];
     __shared__ __align__(16) uint32_t s_t[WAVE];      // wavefront 1, while it works on the representatives
@@ -231,10 +233,11 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
 
     const int tid = threadIdx.x, lane = tid & (WAVE - 1), wave = __builtin_amdgcn_readfirstlane(tid / WAVE);
     const int b = a.b, c = a.c, r = a.r, w = a.w;
+    const int stride = c > r ? c : r, rows = c + r;   // of the per-step arrays, and of the table
     WinHeader* head = reinterpret_cast<WinHeader*>(a.table);
     WinEntry* entry = reinterpret_cast<WinEntry*>(a.table + WIN_MAX * sizeof(WinHeader));
     WinLds l;
-    l.s_fill = s_fill; l.s_ck = s_ck; l.s_cx = s_cx; l.s_cw = s_cw; l.s_wpos = s_wpos; l.s_lab = s_lab;
+    l.s_fill = s_fill; l.s_ck = s_ck; l.s_cx = s_cx; l.s_cw = s_cw; l.s_wpos = s_wpos; l.s_lab = s_lab; l.stride = stride;
 
     // ---- before the first step ----
     int4 fo = make_int4(0, 0, 0, 0);
@@ -244,21 +247,21 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     constexpr int SEL_MAX = WIN_MAX / 2;              // steps per selecting wavefront at most
     int64_t ylab[SEL_MAX];
     if (wave < nsel) {
+        for (int s = wave; s < w; s += nsel) {
+            bool active = false;
+            const int x = wave_select(win_seed(a, s), b, c, s_h + wave * b, active);
+            if (active) s_wpos[s * stride + lane] = (uint16_t)x;
+        }
 #pragma unroll
-        for (int u = 0; u < SEL_MAX; ++u) {
+        for (int u = 0; u < SEL_MAX; ++u) {           // (every lane reads back what it wrote itself)
             const int s = wave + u * nsel;
             ylab[u] = -1;
-            if (s < w) {
-                bool active = false;
-                const int x = wave_select(win_seed(a, s), b, c, s_h + wave * b, active);
-                s_wpos[s * WAVE + lane] = (uint16_t)x;
-                if (active) ylab[u] = win_labels(a, s)[x];
-            }
+            if (s < w && lane < c) ylab[u] = win_labels(a, s)[s_wpos[s * stride + lane]];
         }
     }
     // all sampling bits
     for (int s = wave; s < w; s += NWAVE)
-        if (lane < r) s_bits[s * WAVE + lane] = draw64(win_seed(a, s), PURPOSE_SAMPLE, (uint32_t)lane);
+        if (lane < r) s_bits[s * stride + lane] = draw64(win_seed(a, s), PURPOSE_SAMPLE, (uint32_t)lane);
     lds_barrier();
     for (int i = tid; i < WIN_HASH; i += TPB) {       // empty row table
         s_hkey[i] = WIN_EMPTY;
@@ -271,7 +274,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
         for (int u = 0; u < SEL_MAX; ++u) {
             const int s = wave + u * nsel;
             const int64_t y = ylab[u];
-            if (s < w) s_lab[s * WAVE + lane] = (int16_t)(lane < c ? ((y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID) : LAB_UNSELECTED);
+            if (s < w && lane < c) s_lab[s * stride + lane] = (int16_t)((y >= 0 && y < a.K) ? (int32_t)y : LAB_INVALID);
         }
     }
     lds_barrier();
@@ -285,7 +288,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
             const int32_t k = cd.k;
             const bool valid = cd.valid;
             const int64_t row = valid ? (int64_t)k * a.S + cd.slot : -1;
-            const int me = s * WIN_ROWS + lane;
+            const int me = s * rows + lane;
             int h = 0;
             // candidates that share a slot share a table slot
             if (valid) h = win_find_or_insert(s_hkey, (uint32_t)row);
@@ -351,7 +354,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
             // ---- representatives of step s: lane j = draw j of Floyd's n-subset of the F stored samples ----
             const int n = r < F ? r : F;
             const int base = F - n;
-            const uint32_t t = lane < n ? (uint32_t)__umul64hi(s_bits[s * WAVE + lane], (uint64_t)base + lane + 1) : 0xFFFFFFFFu;
+            const uint32_t t = lane < n ? (uint32_t)__umul64hi(s_bits[s * stride + lane], (uint64_t)base + lane + 1) : 0xFFFFFFFFu;
             s_t[lane] = t;
             bool dup = false;                           // an earlier draw had the same value
 #pragma unroll 4
@@ -393,7 +396,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
             }
             const int pk = lo, ps = lane < n ? g - s_pre[lo] : 0;
             const int64_t row = (int64_t)pk * a.S + ps;
-            const int me = s * WIN_ROWS + c + lane;
+            const int me = s * rows + c + lane;
             int src = -1, chain = -1;
             if (lane < n) {
                 // the representatives of one step are different samples, so no two lanes share a table slot here
@@ -402,15 +405,15 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
                 const uint32_t writer = v & 0xFFFFu, readers = v >> 16;
                 if (writer != WIN_NONE) {
                     // written in this window (this step included): take the row that was stored there
-                    const int ws = (int)writer / WIN_ROWS, wi = (int)writer % WIN_ROWS;
-                    src = (ws << 16) | (int)s_wpos[ws * WAVE + wi];
+                    const int ws = (int)writer / rows, wi = (int)writer % rows;
+                    src = (ws << 16) | (int)s_wpos[ws * stride + wi];
                 } else {
                     // what the slot held before the window: remembered, in case a later step overwrites it
                     chain = readers != WIN_NONE ? (int)readers : -1;
                     s_hval[h] = ((uint32_t)me << 16) | WIN_NONE;
                 }
             }
-            s_next[s * WAVE + lane] = (uint16_t)(chain >= 0 ? chain : (int)WIN_NONE);
+            if (lane < r) s_next[s * stride + lane] = (uint16_t)(chain >= 0 ? chain : (int)WIN_NONE);
             if (lane < r) {
                 WinEntry e;
                 e.src = src;
@@ -439,10 +442,10 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     for (int i = tid; i < WIN_HASH; i += TPB) {
         const uint32_t v = s_hval[i];
         if (s_hkey[i] == WIN_EMPTY || (v & 0xFFFFu) == WIN_NONE) continue;
-        uint32_t q = v >> 16;
-        while (q != WIN_NONE) {
-            entry[q].handled = 1;
-            q = s_next[(q / WIN_ROWS) * WAVE + (q % WIN_ROWS - c)];
+        uint32_t e = v >> 16;
+        while (e != WIN_NONE) {
+            entry[e].handled = 1;
+            e = s_next[(e / rows) * stride + (e % rows - c)];
         }
     }
 
@@ -494,7 +497,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
     }
     const WinHeader* head = reinterpret_cast<const WinHeader*>(m.table);
     const WinEntry* entry = reinterpret_cast<const WinEntry*>(m.table + WIN_MAX * sizeof(WinHeader));
-    const WinEntry en = entry[s * WIN_ROWS + e];
+    const WinEntry en = entry[s * rows + e];
     int64_t v_lo, v_hi;
     tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
     const bool first = tile == 0 && threadIdx.x == 0;
@@ -510,7 +513,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         // representatives that need the slot's old content get it from here, before it is overwritten
         for (int q = en.chain; q >= 0;) {
             const WinEntry rq = entry[q];
-            const int qs = q / WIN_ROWS, qj = q % WIN_ROWS - m.c;
+            const int qs = q / rows, qj = q % rows - m.c;
             if (first) m.out_y[qs][qj] = rq.label;
             Tile<U, NT> old;
             old.load(slot, v_lo, v_hi);

@@ -345,7 +345,7 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
 
 # ------------------------------------------------ several steps from one call ---
 
-@pytest.mark.parametrize("window", [8, 3, 1])
+@pytest.mark.parametrize("window", [16, 8, 3, 1])
 @pytest.mark.parametrize("w", [
     wl.variant(wl.C2, name="C2-many", S=4),
     wl.variant(wl.C5, name="C5-many", K=300, S=12, shape=(256,), b=512, c=200, r=150),
@@ -357,7 +357,7 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
 def test_many_steps_from_one_call(w, window):
     rb = _rb()
     dev = torch.device("cuda:0")
-    n = 14
+    n = 18
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
     buf.set_option(rb.RB_OPT_WINDOW, window)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
@@ -460,7 +460,7 @@ def test_an_announced_call_that_never_comes_is_forgotten():
     compare_buffers(buf, orc, "final")
 
 
-@pytest.mark.parametrize("window", [8, 4, 2])
+@pytest.mark.parametrize("window", [16, 8, 4, 2])
 def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     """Eight classes of one slot each, every step samples all eight rows and rewrites one class (the label
     sequence decides which): rows that are read before a later step of the same launch overwrites them, rows
@@ -479,9 +479,11 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     ys = [torch.full((b,), k, dtype=torch.int64, device=dev) for k in sequence]
     oxs = [torch.zeros((r, *shape), device=dev) for _ in sequence]
     oys = [torch.full((r,), -7, dtype=torch.int64, device=dev) for _ in sequence]
-    for first in range(0, len(sequence), 8):
-        sl = slice(first, first + 8)
-        assert rb.rb_update_sample_many(buf.handle, 8, xs[sl], ys[sl], b, c, r, 3, first, oxs[sl], oys[sl]) == rb.RB_OK
+    per = max(8, window)
+    for first in range(0, len(sequence), per):
+        sl = slice(first, first + per)
+        n = len(xs[sl])
+        assert rb.rb_update_sample_many(buf.handle, n, xs[sl], ys[sl], b, c, r, 3, first, oxs[sl], oys[sl]) == rb.RB_OK
     torch.cuda.synchronize()
     for t, k in enumerate(sequence):
         orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), c, 3, t)
