@@ -26,13 +26,12 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # HBM bytes per launch of the dominant kernel as counted by two
 # `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
 # known size; the text summaries with the exact commands are kept under profiles/.
-# rb_window_kernel: the launches of one 64-step call (1, 2, 6, 8 x 6 and 7 steps) summed and divided by their
-# number, like the average launch the roofline is stated for (algorithmic: 493.25 MB; candidates that lose
-# their slot within a launch, and representatives taken from a mini-batch row still in cache, are not moved).
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 485228783,
-                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 137167583,      # 4, 5, 7, 8 x 6 steps; algorithmic 137.01 MB
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 76945479,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77295518}
+# rb_window_kernel: a launch of 8 steps at C4 (algorithmic 616.56 MB; candidates that lose their slot within a launch,
+# and representatives taken from a mini-batch row still in cache, are not moved) and of 16 steps at C3 (308.28 MB).
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 605749848,
+                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 308447607,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 77112625,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77318094}
 
 
 MANY = 64           # steps handed to one rb_update_sample_many call
