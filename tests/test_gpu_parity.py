@@ -390,10 +390,11 @@ def test_many_steps_from_one_call(w, window):
     compare_buffers(buf, orc, f"{w.name} final")
 
 
+@pytest.mark.parametrize("announce", [False, True], ids=["plain", "announced"])
 @pytest.mark.parametrize("w,steps", [(wl.C3, 72), (wl.C4, 48)], ids=["C3", "C4"])
-def test_many_steps_at_full_size(w, steps):
-    """The configuration the bench times: real shapes, up to eight steps per launch."""
-    run_many_parity(w, w.steps if FULL else steps, per_call=24)
+def test_many_steps_at_full_size(w, steps, announce):
+    """The configuration the bench times: real shapes, 16 (C3) or 8 (C4) steps per launch, calls announced."""
+    run_many_parity(w, w.steps if FULL else steps, per_call=32 if announce else 24, announce=announce)
 
 
 @pytest.mark.parametrize("w,steps,per_call", [
