@@ -65,7 +65,8 @@ struct rb_buffer {
     int64_t updates;         // rb_update calls since the last rb_bind
     // plan-ahead form of the single-launch step
     size_t off_tbl[2];       // the two plan tables
-    size_t off_wtbl[2];      // the two plan tables of the several-steps-per-launch form
+    size_t off_wtbl[2];      // the two plan tables of the several-steps-per-launch form (and of the large-count form)
+    size_t off_bfwd[2];      // large-count form: the two tables of the slot rows a step writes
     int tbl_next;            // table the next plan is written to
     int tbl_planned;         // table that holds the pending plan
     bool plan_valid;         // a step has been planned (and the fill counts advanced) but not yet executed
@@ -350,31 +351,32 @@ hipError_t allow_big_lds()
 }
 
 template <int U, bool NT>
-hipError_t launch_big_u(const MoveArgs& m, const PlanArgs& next, dim3 grid, hipStream_t st)
+hipError_t launch_big_u(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, dim3 grid, hipStream_t st)
 {
     const size_t lds = m.plan_next ? BIG_LDS_BYTES : 0;
     if (lds != 0) {
         const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT>>();
         if (e != hipSuccess) return e;
     }
-    rb_step_big_kernel<U, NT><<<grid, BIG_TPB, lds, st>>>(m, next);
+    rb_step_big_kernel<U, NT><<<grid, BIG_TPB, lds, st>>>(m, next, fwd, fwd_next);
     return hipGetLastError();
 }
 
 template <bool NT>
-hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, hipStream_t st)
+hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, int unroll, dim3 grid,
+                      hipStream_t st)
 {
     switch (unroll) {
-    case 1: return launch_big_u<1, NT>(m, next, grid, st);
-    case 2: return launch_big_u<2, NT>(m, next, grid, st);
-    case 4: return launch_big_u<4, NT>(m, next, grid, st);
-    default: return launch_big_u<8, NT>(m, next, grid, st);
+    case 1: return launch_big_u<1, NT>(m, next, fwd, fwd_next, grid, st);
+    case 2: return launch_big_u<2, NT>(m, next, fwd, fwd_next, grid, st);
+    case 4: return launch_big_u<4, NT>(m, next, fwd, fwd_next, grid, st);
+    default: return launch_big_u<8, NT>(m, next, fwd, fwd_next, grid, st);
     }
 }
 
 // One step of the plan-ahead form for large counts (up to BIG_MAX candidates and representatives, up to
 // BIG_CLASSES classes); same bookkeeping as step_planned, the tables are the (larger) ones that the
-// several-steps-per-launch form uses for shapes this form does not serve.
+// several-steps-per-launch form uses for shapes this form does not serve.  Two workgroups plan.
 int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
              uint64_t seed, uint64_t step, void* out_x, int64_t* out_y, const int64_t* next_y)
 {
@@ -383,7 +385,7 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
         PlanArgs now = make_plan(rb, batch_y, b, c, r, seed, step);
         now.table = rb->ws + rb->off_wtbl[rb->tbl_next];
         if (allow_big_lds<&rb_big_plan_kernel>() != hipSuccess) return RB_EHIP;
-        rb_big_plan_kernel<<<dim3(1), BIG_TPB, BIG_LDS_BYTES, rb->stream>>>(now);
+        rb_big_plan_kernel<<<dim3(2), BIG_TPB, BIG_LDS_BYTES, rb->stream>>>(now, reinterpret_cast<uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_next]));
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         plan_enqueued(rb, batch_y, b, c, r, seed, step);
     }
@@ -408,9 +410,11 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
         next = make_plan(rb, next_y, b, c, r, seed, step + 1);
         next.table = rb->ws + rb->off_wtbl[rb->tbl_next];
     }
-    const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + m.plan_next));
-    const hipError_t e = rb->opt_nt ? launch_big<true>(m, next, sh.unroll, grid, rb->stream)
-                                    : launch_big<false>(m, next, sh.unroll, grid, rb->stream);
+    const uint32_t* fwd = reinterpret_cast<const uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_planned]);
+    uint32_t* fwd_next = reinterpret_cast<uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_next]);
+    const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + 2 * m.plan_next));
+    const hipError_t e = rb->opt_nt ? launch_big<true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
+                                    : launch_big<false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
     if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
@@ -614,6 +618,8 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_tbl[1] = off; off += PLAN_BYTES;
     rb->off_wtbl[0] = off; off += WIN_TABLE_BYTES;
     rb->off_wtbl[1] = off; off += WIN_TABLE_BYTES;
+    rb->off_bfwd[0] = off; off += BIG_FWD_BYTES;
+    rb->off_bfwd[1] = off; off += BIG_FWD_BYTES;
     rb->ws_bytes = off;
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
     rb->ann_n = 0; rb->wplan_valid = false; rb->wplan_tbl = 0;
@@ -784,7 +790,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     // larger counts have a plan-ahead form of their own (default policy, storage in the sample's own type)
     const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
                      rb->opt_fuse && rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM &&
-                     rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF);
+                     rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call
     if (rb->plan_valid && !((plannable || big) && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&

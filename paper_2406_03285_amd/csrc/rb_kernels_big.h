@@ -1,9 +1,9 @@
 // Plan-ahead kernels for the single-launch step with up to 1024 candidates and representatives and up
 // to 10240 classes (default policy): as in rb_kernels_planned.h the plan of a step is worked out by
-// ONE workgroup during the previous step's launch and left in a table, and the step's own launch only
-// moves rows by that table - but the workgroup has 1024 threads (one per candidate and per
-// representative) and finds class-mates, shared slots and repeated draws through hash tables in LDS
-// instead of loops over all candidates.
+// extra workgroups of the previous step's launch and left in a table, and the step's own launch only
+// moves rows by that table - but the planning workgroups (two: update, sampling) have 1024 threads
+// (one per candidate, resp. representative) and find class-mates, shared slots and repeated draws
+// through hash tables in LDS instead of loops over all candidates.
 // Included by rb.hip only, after rb_kernels_planned.h (whose table format and argument structs it uses).
 #pragma once
 
@@ -26,6 +26,7 @@ constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
 // LDS words: fill counts | region U | region V | selection / sampling draws
 constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX) * 4;
 constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
+constexpr size_t BIG_FWD_BYTES = (size_t)2 * BIG_HASH * 4;      // the table of the slot rows a step writes, in memory
 
 __device__ __forceinline__ uint32_t big_hash(uint32_t key)
 {
@@ -90,44 +91,45 @@ __device__ __forceinline__ int big_scan_excl(int v, int& total, int* s_wave)
 }
 
 // ---------------------------------------------------------------------------
-// The whole plan of one step by one workgroup of BIG_TPB threads (all call it).
-// Thread i = candidate i of Floyd's emission order and representative i.  Same
-// decisions as rb_update_kernel followed by rb_sample_kernel (Alg. 1; uniform
-// sampling without replacement of Sec. IV-C), candidate by candidate and
-// representative by representative:
-//   selection      first occurrence of every draw through a table over the b
-//                  positions, then the chain walk;
-//   insertion      the candidates of a class are collected in a list (hash table
-//                  keyed by class -> counter and list start); a candidate's
-//                  insertion number is the class's fill count plus the list
-//                  members earlier in the mini-batch;
-//   last writer    hash table keyed by slot row -> largest mini-batch position
-//                  among the candidates that go there;
-//   sampling       repeated draws through a hash table keyed by the draw's value,
-//                  chain walk, class of the sample by a binary search of the
-//                  prefix sums of the fill counts after the update (all in LDS);
-//   forwarding     a representative whose slot is written in this very step is
-//                  copied from the mini-batch row stored there (row table again).
+// The plan of one step by TWO workgroups of BIG_TPB threads that run side by side
+// and do not talk to each other: one plans the update (Alg. 1), the other the
+// sampling (Sec. IV-C).  Thread i = candidate i of Floyd's emission order, resp.
+// representative i.  Same decisions as rb_update_kernel followed by
+// rb_sample_kernel, candidate by candidate and representative by representative.
+// Both start with the selection (first occurrence of every draw through a table
+// over the b positions, then the chain walk) and the candidates' classes (all b
+// labels parked in LDS at entry).  Then
+//   update    the candidates of a class are collected in a list (hash table keyed
+//             by class -> counter; list starts by a prefix sum over the table's
+//             slots); a candidate's insertion number is the class's fill count
+//             plus the list members earlier in the mini-batch; last writer wins
+//             through a hash table keyed by slot row -> largest mini-batch position
+//             among the candidates that go there.  That table also goes out to
+//             memory: a representative whose slot is written in this very step is
+//             copied from the mini-batch row stored there, and only this
+//             workgroup knows which row that is (big_forwarded, called by the
+//             workgroups that move the representative).
+//   sampling  needs of the update only how many candidates every class gets: the
+//             fill counts after the step (out to memory, this workgroup owns
+//             them) and their prefix sums over the classes, in LDS; repeated draws
+//             through a hash table keyed by the draw's value, chain walk, class of
+//             the sample by binary search of the prefix sums.  A representative of
+//             a class that gets candidates in this step is marked "look it up".
 //
-// LDS (dynamic, BIG_LDS_BYTES): s_fill[BIG_FILL], regions U and V of
-// 2 * BIG_HASH words each, s_draw[BIG_MAX].
+// LDS (dynamic, BIG_LDS_BYTES): s_fill[BIG_FILL] (sampling only), regions U and V
+// of 2 * BIG_HASH words each, s_draw[BIG_MAX].
 // ---------------------------------------------------------------------------
-__device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
+struct BigSelected {
+    int x;           // mini-batch position of the thread's candidate
+    int32_t k;       // its class, LAB_INVALID, or LAB_UNSELECTED for threads without a candidate
+};
+
+// Selection and classes; by all threads of either workgroup.  Uses region U (first occurrences), region V (labels)
+// and s_draw; ends with a barrier after which U and s_draw are free, V still holds the labels.
+__device__ __forceinline__ BigSelected big_select(const PlanArgs& a, uint32_t* s_u, uint32_t* s_v, uint32_t* s_draw)
 {
-    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the step, then after it, then their prefix sums
-    uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | class table | draw table
-    uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels | starts of the class lists | row table
-    uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws, then the class lists, then sampling draws (bit 31: repeated)
-    __shared__ int s_wave[BIG_NWAVE];
-    __shared__ uint32_t s_flags;
-
     const int tid = threadIdx.x;
-    const int b = a.b, c = a.c, r = a.r, K = a.K;
-    const int64_t S = a.S;
-    PlanHeader* head = reinterpret_cast<PlanHeader*>(a.table);
-    PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
-
-    // ---- all labels and the fill counts before the step (requested now, parked after the selection draws) ----
+    const int b = a.b, c = a.c, K = a.K;
     static_assert(BIG_BATCH == 4 * BIG_TPB && BIG_BATCH <= 2 * BIG_HASH, "four labels per thread, parked in region V");
     int64_t yv[4];
 #pragma unroll
@@ -135,21 +137,10 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
         const int q = tid + u * BIG_TPB;
         yv[u] = q < b ? a.batch_y[q] : -1;
     }
-    int32_t fo[BIG_PER];
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) {
-        const int q = tid + u * BIG_TPB;
-        fo[u] = q < K ? a.fill_old[q] : 0;
-    }
-
-    // ---- selection: Floyd's c-subset of the b positions ----
     const bool active = tid < c;
     const int sel_base = b - c;
     const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)tid, (uint64_t)(sel_base + tid + 1)) : 0u;
     if (active) s_u[t] = 0xFFFFFFFFu;
-    if (tid == 0) s_flags = 0;
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int64_t y = yv[u];
@@ -160,29 +151,41 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
     __syncthreads();
     if (active) s_draw[tid] = t | ((s_u[t] != (uint32_t)tid) ? 0x80000000u : 0u);     // t < 4096
     __syncthreads();
-    const int x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : 0;
+    BigSelected sel;
+    sel.x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : 0;
+    sel.k = active ? (int32_t)s_v[sel.x] : LAB_UNSELECTED;
+    __syncthreads();
+    return sel;
+}
 
-    // ---- classes of the candidates; the sampling bits ----
-    const int32_t k = active ? (int32_t)s_v[x] : LAB_UNSELECTED;
-    const uint64_t bits = tid < r ? draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)tid) : 0;
+// fwd: 2 * BIG_HASH words in memory: the slot rows written in the step, and 1 + the mini-batch position stored there.
+__device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds, uint32_t* fwd)
+{
+    uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | class table
+    uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels | starts of the class lists | row table
+    uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws (bit 31: repeated), then the class lists
+    __shared__ int s_wave[BIG_NWAVE];
+
+    const int tid = threadIdx.x;
+    const int c = a.c;
+    const int64_t S = a.S;
+    PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
+
+    const BigSelected sel = big_select(a, s_u, s_v, s_draw);
+    const int x = sel.x;
+    const int32_t k = sel.k;
+    const bool valid = k >= 0;
+    const int64_t fill0 = valid ? a.fill_old[k] : 0;       // on its way while the class table is built
     // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
     uint32_t* ckey = s_u;
     uint32_t* ccnt = s_u + BIG_HASH;
-    uint32_t* list = s_draw;                    // [BIG_MAX]: position << 10 | candidate (between the two uses of s_draw)
+    uint32_t* list = s_draw;                    // [BIG_MAX]: position << 10 | candidate
     uint32_t* cstart = s_v + BIG_MAX;           // [BIG_HASH]: start of the class's list
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
         ckey[i] = BIG_EMPTY;
         ccnt[i] = 0;
     }
-    const bool valid = k >= 0;
-    if (k == LAB_INVALID) atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
     __syncthreads();
-
-    // From here every stretch between two barriers carries a piece of the update's plan (thread =
-    // candidate) and an independent piece of the sampling's plan (thread = representative, or a
-    // stretch of classes), so that the round trips of the two overlap.
-
-    // ---- the candidates of every class are counted ----
     int h = 0, arrival = 0;
     if (valid) {
         h = big_find_or_insert(ckey, (uint32_t)k);
@@ -190,40 +193,21 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
     }
     __syncthreads();
     const int total = valid ? (int)ccnt[h] : 0;
-    const int64_t fill0 = valid ? s_fill[k] : 0;
     {
         // the lists of the classes follow each other in the order of the table's slots: two slots per thread
         static_assert(BIG_HASH == 2 * BIG_TPB, "two table slots per thread");
         const int c0 = (int)ccnt[2 * tid], c1 = (int)ccnt[2 * tid + 1];
         int all;
-        const int lbefore = big_scan_excl(c0 + c1, all, s_wave);    // its barriers also end the reads of the labels in region V and of fill0
+        const int lbefore = big_scan_excl(c0 + c1, all, s_wave);
         cstart[2 * tid] = (uint32_t)lbefore;
         cstart[2 * tid + 1] = (uint32_t)(lbefore + c0);
     }
-    // the class's fill count after the step (one thread per class)
-    if (valid && arrival == 0) s_fill[k] = (int32_t)(fill0 + total < S ? fill0 + total : S);
     __syncthreads();
-
-    // ---- update: every candidate enters its class's list | sampling: fill counts out, sums of ten classes per thread ----
     const int start = valid ? (int)cstart[h] : 0;
     if (valid) list[start + arrival] = ((uint32_t)x << 10) | (uint32_t)tid;
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) {
-        const int q = tid + u * BIG_TPB;
-        if (q < K) a.fill_new[q] = s_fill[q];
-    }
-    int nf[BIG_PER], local = 0;
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) {
-        nf[u] = s_fill[BIG_PER * tid + u];
-        local += nf[u];
-    }
-    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
-    const int inc = wave_scan_incl(local);
-    if (lane == WAVE - 1) s_wave[wave] = inc;
     __syncthreads();
 
-    // ---- update: insertion number and slot | sampling: prefix sums of the fill counts over the classes, in place ----
+    // ---- insertion number and slot ----
     int rank = 0;
     for (int i = 0; i < total; ++i) rank += (int)((int)(list[start + i] >> 10) < x);
     const int64_t at = fill0 + rank;
@@ -233,21 +217,105 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
     const int64_t row = valid ? (int64_t)k * S + slot : -1;
     uint32_t* rkey = s_v;                            // slot rows written in this step (the list starts in region V have been read)
     uint32_t* rmax = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there
-    uint32_t* dkey = s_u;                            // values of the sampling draws (the class table has been read)
-    uint32_t* dfirst = s_u + BIG_HASH;               // first draw with that value
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
         rkey[i] = BIG_EMPTY;
         rmax[i] = 0;
+    }
+    __syncthreads();
+    int hr = 0;
+    if (valid) {
+        hr = big_find_or_insert(rkey, (uint32_t)row);
+        atomicMax(&rmax[hr], (uint32_t)x + 1u);
+    }
+    __syncthreads();
+    // of the candidates that go to one slot the last of the mini-batch is stored
+    const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
+    if (tid < c) {
+        PlanEntry e;
+        e.pos = x;
+        e.label = valid ? k : -1;
+        e.row = stored ? row : -1;
+        entry[tid] = e;
+    }
+    for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) fwd[i] = s_v[i];
+}
+
+// Mini-batch position of the candidate that the step stores in slot row `row`, -1 if the step does not write it.
+__device__ __forceinline__ int big_forwarded(const uint32_t* __restrict__ fwd, uint32_t row)
+{
+    uint32_t h = big_hash(row);
+    for (;;) {
+        const uint32_t at = fwd[h];
+        if (at == row) return (int)fwd[BIG_HASH + h] - 1;
+        if (at == BIG_EMPTY) return -1;
+        h = (h + 1) & (BIG_HASH - 1);
+    }
+}
+
+constexpr int32_t BIG_LOOK_UP = -2;      // PlanEntry::pos of a representative: its class gets candidates in this step
+
+__device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds)
+{
+    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the step, then after it, then their prefix sums
+    uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | draw table
+    uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels
+    uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws, then sampling draws (bit 31: repeated)
+    __shared__ int s_wave[BIG_NWAVE];
+    __shared__ uint32_t s_flags;
+    __shared__ uint32_t s_hit[BIG_CLASSES / 32];           // one bit per class: it gets candidates in this step
+
+    const int tid = threadIdx.x;
+    const int c = a.c, r = a.r, K = a.K;
+    const int64_t S = a.S;
+    PlanHeader* head = reinterpret_cast<PlanHeader*>(a.table);
+    PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
+
+    // ---- fill counts before the step (requested now, parked while the selection is under way) ----
+    int32_t fo[BIG_PER];
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        fo[u] = q < K ? a.fill_old[q] : 0;
+    }
+    if (tid == 0) s_flags = 0;
+    if (tid < BIG_CLASSES / 32) s_hit[tid] = 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
+    const BigSelected sel = big_select(a, s_u, s_v, s_draw);      // (its barriers also cover the stores above)
+    const int32_t k = sel.k;
+
+    // ---- how many candidates every class gets; the sampling bits; empty draw table ----
+    if (k >= 0) {
+        atomicAdd(&s_fill[k], 1);                           // may pass the capacity: cut back below
+        atomicOr(&s_hit[k >> 5], 1u << (k & 31));
+    }
+    if (k == LAB_INVALID) atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
+    const uint64_t bits = tid < r ? draw64(a.sd, PURPOSE_SAMPLE, (uint32_t)tid) : 0;
+    uint32_t* dkey = s_u;                            // values of the sampling draws
+    uint32_t* dfirst = s_u + BIG_HASH;               // first draw with that value
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
         dkey[i] = BIG_EMPTY;
         dfirst[i] = 0xFFFFFFFFu;
     }
-    int F = 0, before = inc - local;
+    __syncthreads();
+
+    // ---- fill counts after the step: out to memory; sums of ten classes per thread ----
+    const int32_t cap = (int32_t)(S < INT32_MAX ? S : INT32_MAX);
 #pragma unroll
-    for (int i = 0; i < BIG_NWAVE; ++i) {
-        const int v = s_wave[i];
-        F += v;
-        if (i < wave) before += v;
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        const int32_t f = s_fill[q];
+        if (q < K) a.fill_new[q] = f < cap ? f : cap;
     }
+    int nf[BIG_PER], local = 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int32_t f = s_fill[BIG_PER * tid + u];
+        nf[u] = f < cap ? f : cap;
+        local += nf[u];
+    }
+    int F;
+    int before = big_scan_excl(local, F, s_wave);    // its first barrier also ends the reads of s_fill above
 #pragma unroll
     for (int u = 0; u < BIG_PER; ++u) {
         s_fill[BIG_PER * tid + u] = before;
@@ -255,18 +323,13 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
     }
     for (int i = BIG_CLASSES + tid; i < BIG_FILL; i += BIG_TPB) s_fill[i] = F;
     __syncthreads();
-
-    // ---- update: who goes to which slot | sampling: thread j = draw j of Floyd's n-subset of the F stored samples ----
-    int hr = 0;
-    if (valid) {
-        hr = big_find_or_insert(rkey, (uint32_t)row);
-        atomicMax(&rmax[hr], (uint32_t)x + 1u);
-    }
     if (tid < a.nchunks) {
         // stored samples per chunk of CH classes
         const int lo = tid * CH, hi = lo + CH;
         a.chunk_new[tid] = s_fill[hi] - s_fill[lo];
     }
+
+    // ---- thread j = draw j of Floyd's n-subset of the F stored samples ----
     const int n = r < F ? r : F;
     const int64_t base = (int64_t)F - n;
     const bool drawing = tid < n;
@@ -277,22 +340,11 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
         atomicMin(&dfirst[hd], (uint32_t)tid);
     }
     __syncthreads();
-
-    // ---- update: of the candidates that go to one slot the last of the mini-batch is stored | sampling: repeated draws ----
-    const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
-    if (active) {
-        PlanEntry e;
-        e.pos = x;
-        e.label = valid ? k : -1;
-        e.row = stored ? row : -1;
-        entry[tid] = e;
-    }
     if (drawing) s_draw[tid] = g0 | ((dfirst[hd] != (uint32_t)tid) ? 0x80000000u : 0u);
     __syncthreads();
-
     int32_t pk = -1;
     int64_t prow = -1;
-    int fwd = -1;
+    int32_t pos = -1;
     if (drawing) {
         const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
         // its class: the last one whose prefix does not exceed g (empty classes share the prefix of the
@@ -304,13 +356,11 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
         }
         pk = lo;
         prow = (int64_t)pk * S + (g - s_fill[lo]);
-        // written in this very step?  Then the stored candidate is what the slot holds.
-        const int hw = big_find(rkey, (uint32_t)prow);
-        if (hw >= 0) fwd = (int)rmax[hw] - 1;
+        if ((s_hit[pk >> 5] >> (pk & 31)) & 1u) pos = BIG_LOOK_UP;      // its slot may be written in this very step
     }
     if (tid < r) {
         PlanEntry e;
-        e.pos = fwd;
+        e.pos = pos;
         e.label = pk;                           // -1 when fewer samples are stored than asked for
         e.row = prow;
         entry[c + tid] = e;
@@ -325,11 +375,12 @@ __device__ __forceinline__ void plan_big(const PlanArgs& a, uint32_t* lds)
     }
 }
 
-// The plan of one step on its own (first step of a sequence).
-__global__ void __launch_bounds__(BIG_TPB) rb_big_plan_kernel(const PlanArgs a)
+// The plan of one step on its own (first step of a sequence): two workgroups.
+__global__ void __launch_bounds__(BIG_TPB) rb_big_plan_kernel(const PlanArgs a, uint32_t* fwd)
 {
     extern __shared__ uint32_t lds[];
-    plan_big(a, lds);
+    if (blockIdx.x == 0) plan_big_update(a, lds, fwd);
+    else plan_big_sample(a, lds);
 }
 
 // ---------------------------------------------------------------------------
@@ -338,16 +389,17 @@ __global__ void __launch_bounds__(BIG_TPB) rb_big_plan_kernel(const PlanArgs a)
 // workgroup of the grid plans the next step instead.
 // ---------------------------------------------------------------------------
 template <int U, bool NT>
-__global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, const PlanArgs next)
+__global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, const PlanArgs next, const uint32_t* fwd, uint32_t* fwd_next)
 {
     extern __shared__ uint32_t lds[];
-    const bool plan_next = m.plan_next != 0;
-    if (plan_next && blockIdx.x == 0) {        // dispatched first: it has the longest way to go
+    const int planners = m.plan_next != 0 ? 2 : 0;
+    if ((int)blockIdx.x < planners) {          // dispatched first: they have the longest way to go
         __builtin_amdgcn_s_setprio(3);
-        plan_big(next, lds);
+        if (blockIdx.x == 0) plan_big_update(next, lds, fwd_next);
+        else plan_big_sample(next, lds);
         return;
     }
-    const int64_t item = (int64_t)(blockIdx.x - (plan_next ? 1 : 0)) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
+    const int64_t item = (int64_t)((int)blockIdx.x - planners) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
     const int64_t items = (int64_t)(m.c + m.r) * m.tpr;
     if (item >= items) return;
     int e, tile;
@@ -373,7 +425,9 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
     const int j = e - m.c;
     if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
-    const vec16* src = en.pos >= 0 ? m.batch_x + (int64_t)en.pos * m.row_vec : m.buf_x + en.row * m.row_vec;
+    // written in this very step?  Then the stored candidate's mini-batch row is what the slot will hold.
+    const int pos = en.pos == BIG_LOOK_UP ? big_forwarded(fwd, (uint32_t)en.row) : -1;
+    const vec16* src = pos >= 0 ? m.batch_x + (int64_t)pos * m.row_vec : m.buf_x + en.row * m.row_vec;
     Tile<U, NT, BIG_GROUP> t;
     t.load(src, v_lo, v_hi);
     t.store(m.out_x + (int64_t)j * m.row_vec, v_lo, v_hi);
