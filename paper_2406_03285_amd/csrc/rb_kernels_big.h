@@ -125,8 +125,9 @@ struct BigSelected {
 };
 
 // Selection and classes; by all threads of either workgroup.  Uses region U (first occurrences), region V (labels)
-// and s_draw; ends with a barrier after which U and s_draw are free, V still holds the labels.
-__device__ __forceinline__ BigSelected big_select(const PlanArgs& a, uint32_t* s_u, uint32_t* s_v, uint32_t* s_draw)
+// and s_draw; ends with a barrier after which U and s_draw are free, V still holds the labels.  The fill counts
+// before the step are requested behind the labels (which are needed first) and parked in s_fill on the way.
+__device__ __forceinline__ BigSelected big_select(const PlanArgs& a, int32_t* s_fill, uint32_t* s_u, uint32_t* s_v, uint32_t* s_draw)
 {
     const int tid = threadIdx.x;
     const int b = a.b, c = a.c, K = a.K;
@@ -136,6 +137,12 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, uint32_t* s
     for (int u = 0; u < 4; ++u) {
         const int q = tid + u * BIG_TPB;
         yv[u] = q < b ? a.batch_y[q] : -1;
+    }
+    int32_t fo[BIG_PER];
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        fo[u] = q < K ? a.fill_old[q] : 0;
     }
     const bool active = tid < c;
     const int sel_base = b - c;
@@ -150,6 +157,8 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, uint32_t* s
     if (active) atomicMin(&s_u[t], (uint32_t)tid);
     __syncthreads();
     if (active) s_draw[tid] = t | ((s_u[t] != (uint32_t)tid) ? 0x80000000u : 0u);     // t < 4096
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
     __syncthreads();
     BigSelected sel;
     sel.x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : 0;
@@ -161,6 +170,7 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, uint32_t* s
 // fwd: 2 * BIG_HASH words in memory: the slot rows written in the step, and 1 + the mini-batch position stored there.
 __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds, uint32_t* fwd)
 {
+    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);         // fill counts before the step
     uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | class table
     uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels | starts of the class lists | row table
     uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws (bit 31: repeated), then the class lists
@@ -171,11 +181,11 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     const int64_t S = a.S;
     PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
 
-    const BigSelected sel = big_select(a, s_u, s_v, s_draw);
+    const BigSelected sel = big_select(a, s_fill, s_u, s_v, s_draw);
     const int x = sel.x;
     const int32_t k = sel.k;
     const bool valid = k >= 0;
-    const int64_t fill0 = valid ? a.fill_old[k] : 0;       // on its way while the class table is built
+    const int64_t fill0 = valid ? s_fill[k] : 0;
     // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
     uint32_t* ckey = s_u;
     uint32_t* ccnt = s_u + BIG_HASH;
@@ -270,18 +280,9 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
     PlanHeader* head = reinterpret_cast<PlanHeader*>(a.table);
     PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
 
-    // ---- fill counts before the step (requested now, parked while the selection is under way) ----
-    int32_t fo[BIG_PER];
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) {
-        const int q = tid + u * BIG_TPB;
-        fo[u] = q < K ? a.fill_old[q] : 0;
-    }
     if (tid == 0) s_flags = 0;
     if (tid < BIG_CLASSES / 32) s_hit[tid] = 0;
-#pragma unroll
-    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
-    const BigSelected sel = big_select(a, s_u, s_v, s_draw);      // (its barriers also cover the stores above)
+    const BigSelected sel = big_select(a, s_fill, s_u, s_v, s_draw);      // (its barriers also cover the stores above)
     const int32_t k = sel.k;
 
     // ---- how many candidates every class gets; the sampling bits; empty draw table ----
