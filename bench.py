@@ -31,7 +31,8 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 605749848,
                     ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 308447607,
                     ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 77112625,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77318094}
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77318094,
+                    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): 34001556}      # algorithmic 33.55 MB
 
 
 MANY = 64           # steps handed to one rb_update_sample_many call

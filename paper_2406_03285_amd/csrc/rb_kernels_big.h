@@ -315,8 +315,21 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
         nf[u] = f < cap ? f : cap;
         local += nf[u];
     }
-    int F;
-    int before = big_scan_excl(local, F, s_wave);    // its first barrier also ends the reads of s_fill above
+    // prefix sums over the threads, and (in registers) over the wavefronts: stretches of WAVE * BIG_PER classes
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int inc = wave_scan_incl(local);
+    if (lane == WAVE - 1) s_wave[wave] = inc;
+    __syncthreads();                                 // also ends the reads of s_fill above
+    int wpre[BIG_NWAVE];                             // stored samples before the classes of wavefront i
+    int F = 0;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) {
+        wpre[i] = F;
+        F += s_wave[i];
+    }
+    int before = inc - local;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) before += i == wave ? wpre[i] : 0;
 #pragma unroll
     for (int u = 0; u < BIG_PER; ++u) {
         s_fill[BIG_PER * tid + u] = before;
@@ -350,7 +363,11 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
         const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
         // its class: the last one whose prefix does not exceed g (empty classes share the prefix of the
         // next non-empty one, which is the one meant; classes past K hold F > g)
-        int lo = 0, hi = BIG_CLASSES - 1;
+        // first which wavefront's stretch of classes (registers), then inside it (LDS)
+        int seg = 0;
+#pragma unroll
+        for (int i = 1; i < BIG_NWAVE; ++i) seg += (int)(wpre[i] <= g);
+        int lo = seg * WAVE * BIG_PER, hi = lo + WAVE * BIG_PER - 1;
         while (lo < hi) {
             const int mid = (lo + hi + 1) >> 1;
             if (s_fill[mid] <= g) lo = mid; else hi = mid - 1;
