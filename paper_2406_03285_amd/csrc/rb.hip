@@ -421,14 +421,14 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     return RB_OK;
 }
 
-template <bool NT>
+template <bool NT, bool BF16>
 hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_window_kernel<1, NT><<<grid, TPB, lds, st>>>(m, next); break;
-    case 2: rb_window_kernel<2, NT><<<grid, TPB, lds, st>>>(m, next); break;
-    case 4: rb_window_kernel<4, NT><<<grid, TPB, lds, st>>>(m, next); break;
-    default: rb_window_kernel<8, NT><<<grid, TPB, lds, st>>>(m, next); break;
+    case 1: rb_window_kernel<1, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 2: rb_window_kernel<2, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 4: rb_window_kernel<4, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    default: rb_window_kernel<8, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
     }
     return hipGetLastError();
 }
@@ -464,8 +464,9 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
                                                                 std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
     // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
-    // compute unit, tiles of four vectors per thread measured best (C4: 13.9 us per step against 14.9 with
-    // two and 15.0 with eight; C3: 4.5 against 4.5 and 5.0).
+    // compute unit, tiles of four vectors per thread measured best (1000 classes of 3x224x224 bfloat16 samples,
+    // 64 candidates and representatives: 13.1 us per step against 14.1 with two and 14.2 with eight; binary32
+    // samples, 8 and 8: 3.9 against 4.1 and 4.1).
     const int unroll_option = rb->opt_unroll;
     if (unroll_option == 0) rb->opt_unroll = 4;
     const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
@@ -475,7 +476,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     // with nothing to hide behind) is the smallest from which they can grow.  Measured on MI355X: rows move at
     // about 5.5 TB/s; a window's plan takes about 3 us more than a launch's own fixed cost, plus 1.6 us and
     // 0.04 us per candidate or representative for every step.
-    const double move_us = 2.0 * (double)(c + r) * (double)rb->row_bytes / 5.5e6;
+    const double move_us = (double)(c + r) * (double)(rb->row_bytes + rb->sample_bytes) / 5.5e6;
     const double plan_us = 1.6 + 0.04 * (double)std::max(c, r);
     const auto grown = [&](int64_t w) {
         return std::max<int64_t>(1, std::min<int64_t>(wmax, (int64_t)((move_us * (double)w - 3.0) / plan_us)));
@@ -528,8 +529,12 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         m.row_vec = rb->row_vec;
         m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
         const dim3 grid((unsigned)(w * (c + r) * sh.tpr + (next_w > 0 ? 1 : 0)));
-        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, sh.unroll, grid, 0, rb->stream)
-                                        : launch_window<false>(m, next, sh.unroll, grid, 0, rb->stream);
+        const bool bf16 = rb->storage == RB_STORE_BF16;
+        hipError_t e;
+        if (rb->opt_nt) e = bf16 ? launch_window<true, true>(m, next, sh.unroll, grid, 0, rb->stream)
+                                 : launch_window<true, false>(m, next, sh.unroll, grid, 0, rb->stream);
+        else e = bf16 ? launch_window<false, true>(m, next, sh.unroll, grid, 0, rb->stream)
+                      : launch_window<false, false>(m, next, sh.unroll, grid, 0, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         if (ahead) {
@@ -874,7 +879,7 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
     }
     const bool windowed = n >= 2 && c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 &&
                           rb->opt_fuse && rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT &&
-                          rb->eviction == RB_EVICT_UNIFORM && rb->storage == RB_STORE_SAME;
+                          rb->eviction == RB_EVICT_UNIFORM;
     if (windowed) {
         if (rb->plan_valid) {                    // a single step that was planned ahead is not executed as planned
             rb->cur ^= 1;

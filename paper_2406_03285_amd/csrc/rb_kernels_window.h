@@ -471,7 +471,7 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 // stream frees the movers but the events that order the two streams cost more than
 // that gains.)
 // ---------------------------------------------------------------------------
-template <int U, bool NT>
+template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
 __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, const WinPlanArgs next)
 {
     if (next.w > 0 && blockIdx.x == 0) {
@@ -507,6 +507,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         m.state->last_n = head[m.w - 1].n;
         if (flags != 0) atomicOr(&m.state->flags, flags);
     }
+    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.c) {
         if (en.row < 0) return;                 // dropped within its step, or overwritten again later in the window
         vec16* slot = m.buf_x + en.row * m.row_vec;
@@ -515,17 +516,17 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
             const WinEntry rq = entry[q];
             const int qs = q / rows, qj = q % rows - m.c;
             if (first) m.out_y[qs][qj] = rq.label;
-            Tile<U, NT> old;
+            Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> old;
             old.load(slot, v_lo, v_hi);
-            old.store(m.out_x[qs] + (int64_t)qj * m.row_vec, v_lo, v_hi);
+            old.store(m.out_x[qs] + (int64_t)qj * m.row_vec * WIDE, v_lo, v_hi);
             q = rq.chain;
         }
         // Lanes past the end of a tile move its last vector again, so a vector may be read by one
         // wavefront and overwritten by another: everybody has read before anybody overwrites.
         if (en.chain >= 0) __syncthreads();
         if (first) m.buf_y[en.row] = en.label;
-        Tile<U, NT> t;
-        t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec, v_lo, v_hi);
+        Tile<U, NT, TPB, true, BF16 ? CV_NARROW : CV_NONE> t;
+        t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE, v_lo, v_hi);
         t.store(slot, v_lo, v_hi);
         return;
     }
@@ -533,11 +534,19 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
     const int j = e - m.c;
     if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
-    const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
-                                   : m.buf_x + en.row * m.row_vec;
-    Tile<U, NT> t;
-    t.load(src, v_lo, v_hi);
-    t.store(m.out_x[s] + (int64_t)j * m.row_vec, v_lo, v_hi);
+    vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
+    if (BF16 && en.src >= 0) {
+        // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
+        Tile<U, NT, TPB, true, CV_BOTH> t;
+        t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    } else {
+        const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
+                                       : m.buf_x + en.row * m.row_vec;
+        Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> t;
+        t.load(src, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    }
 }
 
 }  // namespace

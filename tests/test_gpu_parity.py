@@ -424,6 +424,17 @@ def test_many_steps_with_the_next_call_announced(w, steps, per_call):
     run_many_parity(w, steps, per_call=per_call, announce=True)
 
 
+@pytest.mark.parametrize("w,steps,per_call,announce", [
+    (wl.variant(wl.C1, name="C1-many-bf16"), 100, 17, False),                                  # fills up: append, replace, collisions
+    (wl.variant(wl.C1, name="C1-many-bf16-one-class", K=1, S=7, c=16, r=16), 60, 20, True),    # old content handed on by the writers, forwarding
+    (wl.variant(wl.C1, name="C1-many-bf16-one-slot", K=2, S=1, c=6, r=2), 48, 16, True),
+    (wl.variant(wl.C3, name="C3-many-bf16", K=50, S=6), 36, 18, True),                         # 301 056-byte stored rows, many tiles
+    (wl.variant(wl.C2, name="C2-many-bf16", S=3, shape=(3, 8, 8)), 96, 32, True),
+], ids=["C1", "one-class", "one-slot", "C3-rows", "C2-S3"])
+def test_many_steps_with_float32_samples_stored_as_bfloat16(w, steps, per_call, announce):
+    run_many_parity(w, steps, per_call=per_call, announce=announce, store_bf16=True)
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_many_steps_announced_survive_broken_promises(seed):
     run_many_parity(wl.variant(wl.C4, name=f"C4-S8-many-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 160, per_call=12,
