@@ -99,7 +99,7 @@ class Rig:
         """Enqueue n consecutive steps on the side stream (no synchronisation).
         many: hand the steps to rb_update_sample_many, `many` of them per call.
         ahead: announce the labels that come next before every call (plan-ahead forms): the next pool slot's
-        with single_call, those of the next call's first eight steps with many."""
+        with single_call, those of the next call's first steps (up to 16) with many."""
         w, rb, h, P, args = self.w, self.rb, self.buf.handle, self.P, self.args
         upd, smp, both = rb.rb_update, rb.rb_sample_augment, rb.rb_update_sample
         b, c, r, seed = w.b, w.c, w.r, w.lib_seed
@@ -113,7 +113,8 @@ class Rig:
                 px, py, ox, oy = (C.cast(C.byref(a, o), C.POINTER(C.c_void_p)) for a in self.ptrs)
                 if ahead:
                     o_next = ((t + k) % P) * C.sizeof(C.c_void_p)
-                    rb.rb_announce_next_many(h, min(16, many), C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
+                    nxt = min(many, n - (at + k)) or many           # steps of the call that follows (the next enqueue's first, at the end)
+                    rb.rb_announce_next_many(h, min(16, nxt), C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
                 rc = rb.rb_update_sample_many(h, k, px, py, b, c, r, seed, t, ox, oy)
                 if rc:
                     raise RuntimeError(f"rb_update_sample_many -> {rc}")
@@ -288,10 +289,10 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     rig.enqueue(MANY, many=MANY, ahead=True)
     torch.cuda.synchronize()
     # Headline: K steps enqueued back to back on the side stream through rb_update_sample_many, MANY steps per
-    # host call, the labels of the next call's first eight steps announced before every call.  The mini-batches
-    # of all those steps are resident (like every input); when the step is eligible, up to eight steps share one
+    # host call, the labels of the next call's first steps announced before every call.  The mini-batches
+    # of all those steps are resident (like every input); when the step is eligible, up to 16 steps share one
     # launch whose plan the launch before made (also across calls: that is what the announcement is for).
-    ms = rig.timed(steps // MANY * MANY if steps >= MANY else steps, many=MANY if steps >= MANY else steps, ahead=True)
+    ms = rig.timed(steps, many=min(MANY, steps), ahead=True)     # exactly `steps` steps: the last call takes what is left
     n_side = min(steps, 1000)
     ms_many_plain = rig.timed(n_side // MANY * MANY or MANY, many=MANY)    # the same without announcing the next call
     ms_ahead = rig.timed(n_side, single_call=True, ahead=fused)   # one rb_update_sample per step, next labels announced
@@ -425,7 +426,7 @@ def main():
     ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, 120 single-call steps with "
-                         "the next labels announced, 128 steps through rb_update_sample_many, then 3 plain copies "
+                         "the next labels announced, 192 steps through announced rb_update_sample_many calls, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
     a = ap.parse_args()
     if a.gpus != 1:
