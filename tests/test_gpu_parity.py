@@ -683,6 +683,52 @@ def test_random_configurations(chunk):
         run_parity(w, steps=6, check_state_every=3, policy=policy, options=options, single_call=single)
 
 
+def _random_planned_workload(rng, i):
+    """Shapes around the limits of the plan-ahead forms: at most 64 / 1024 candidates and representatives,
+    1024 / 10240 classes, mini-batches of 2048 / 4096."""
+    kind = rng.choice(["small", "large", "any"])
+    if kind == "small":
+        b = int(rng.choice([1, 5, 64, 65, 700, 2048, 2049]))
+        c, r = int(min(b, rng.integers(1, 66))), int(rng.integers(1, 66))
+        K = int(rng.choice([1, 3, 50, 1000, 1024, 1025]))
+    elif kind == "large":
+        b = int(rng.choice([100, 1024, 1500, 4096]))
+        c, r = int(min(b, rng.integers(1, 1100))), int(rng.integers(1, 1100))
+        K = int(rng.choice([1, 40, 1025, 5000, 10240, 10241]))
+    else:
+        b = int(rng.integers(1, 4097))
+        c, r = int(rng.integers(0, b + 1)), int(rng.integers(0, 1500))
+        K = int(rng.choice([2, 100, 3000, 20000]))
+    S = int(rng.choice([1, 2, 3, 10, 60]))
+    vecs = int(rng.choice([1, 2, 64, 65, 257, 1000]))        # 16-byte vectors per row
+    dtype = "f32" if rng.random() < 0.5 else "bf16"
+    shape = (vecs * (4 if dtype == "f32" else 8),)
+    labels = str(rng.choice(["uniform", "zipf", "active50"]))
+    return wl.Workload(f"randp{i}-{kind}-K{K}-S{S}-b{b}-c{c}-r{r}-v{vecs}", 9, K, S, shape, dtype, b, c, r, 6, "normal", labels)
+
+
+@pytest.mark.parametrize("chunk", range(4))
+def test_random_configurations_planned_ahead(chunk):
+    """Seeded random shapes through the calls that plan ahead: one announced step at a time, and several steps
+    per call (with and without the next call announced, sometimes with promises broken)."""
+    rng = np.random.default_rng(2000 + chunk)
+    for i in range(10):
+        w = _random_planned_workload(rng, chunk * 100 + i)
+        style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
+        per_call = int(rng.choice([3, 8, 17, 33]))
+        print(f"  {w.name} {style} per_call={per_call}", flush=True)
+        if style == "ahead":
+            run_ahead_parity(w, 8)
+        elif style == "ahead-broken":
+            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)))
+        elif style == "many":
+            run_many_parity(w, 40, per_call=per_call)
+        elif style == "many-announced":
+            run_many_parity(w, 40, per_call=per_call, announce=True)
+        else:
+            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)))
+
+
 # ------------------------------------------------------------- edge cases ---
 
 @pytest.mark.parametrize("K,S,shape,dtype,b,c,r", [
