@@ -284,7 +284,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     # own: one launch per step that moves rows by the plan a 1024-thread workgroup of the launch before made.
     small = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
     fused = small or (1 <= w.c <= 1024 and 1 <= w.r <= 1024 and w.b <= 4096 and w.K <= 10240)
-    windowed = small and w.b <= 2048
+    windowed = rig.buf.steps_per_launch(w.b, w.c, w.r) > 1
     rig.enqueue(warmup, single_call=True, ahead=fused)
     rig.enqueue(MANY, many=MANY, ahead=True)
     torch.cuda.synchronize()
@@ -311,11 +311,10 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": len(window_schedule(w, MANY, announced=True)) / MANY if windowed else (1 if fused else 2),
-        "steps_per_launch": max(window_schedule(w, MANY, announced=True)) if windowed else 1,
-        "steps_per_launch_schedule": window_schedule(w, MANY, announced=True) if windowed else None,
+        "launches_per_step": len(launch_sizes(rig, MANY)) / MANY if windowed else (1 if fused else 2),
+        "steps_per_launch": max(launch_sizes(rig, MANY)) if windowed else 1,
+        "steps_per_launch_schedule": launch_sizes(rig, MANY) if windowed else None,
         "next_call_not_announced_ms_per_step": ms_many_plain,
-        "next_call_not_announced_schedule": window_schedule(w, MANY) if windowed else None,
         "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
         "next_labels_announced": fused, "plan_ahead_kernel": None if not fused else ("rb_step_planned_kernel" if small else "rb_step_big_kernel"),
@@ -328,30 +327,12 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     return rig, res
 
 
-def window_schedule(w, n, wmax=None, announced=False):
-    """Steps per launch of one rb_update_sample_many call of n steps (the library's rule, restated: the windows
-    grow as fast as the one planner workgroup can keep ahead of the movers, from the smallest first window that
-    lets them grow; when every call's first steps were announced to the call before, they have grown to the
-    largest size and stay there)."""
-    if wmax is None:
-        wmax = max(1, min(16, 1024 // (w.c + w.r), 512 // max(w.c, w.r)))      # what the planner's tables hold
-    if announced:
-        return [min(wmax, n - at) for at in range(0, n, wmax)]
-    move_us = 2.0 * (w.c + w.r) * w.row_bytes / 5.5e6
-    plan_us = 1.6 + 0.04 * max(w.c, w.r)
-
-    def grown(k):
-        return max(1, min(wmax, int((move_us * k - 3.0) / plan_us)))
-    w0 = 1
-    while w0 < wmax and grown(w0) <= w0:
-        w0 += 1
-    out, k, nat = [], min(w0, n), w0
-    while n > 0:
-        out.append(k)
-        n -= k
-        nat = min(wmax, max(nat, grown(nat)))
-        k = min(nat, n)
-    return out
+def launch_sizes(rig, n):
+    """Steps per launch of one rb_update_sample_many call of n steps in a stream of calls that are announced to each
+    other: the library's limit for the shape, and a remainder."""
+    w = rig.w
+    per = rig.buf.steps_per_launch(w.b, w.c, w.r)
+    return [min(per, n - at) for at in range(0, n, per)]
 
 
 def host_pinned_leg(torch, rb, wl, steps=200):
@@ -381,11 +362,12 @@ def reduced_precision_leg(torch, rb, wl, steps=1000):
     ms_ahead = rig.timed(steps, single_call=True, ahead=True)  # one launch per step, plan made one step ahead
     ms_plain = rig.timed(steps, single_call=True)             # general kernels, two launches per step
     moved = (w.c + w.r) * (w.row_bytes + w.row_bytes // 2)
+    steps_per_launch = rig.buf.steps_per_launch(w.b, w.c, w.r)
     rig.close()
     return {"workload": w.name + " stored as bf16", "ms_per_step": round(ms, 5),
             "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1), "bytes_per_step": moved,
             "gb_per_s": round(moved / (ms * 1e-3) / 1e9, 1), "hbm_frac": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-            "buffer_gb": round(w.buffer_bytes / 2 / 1e9, 1), "steps_per_launch": max(window_schedule(w, MANY, announced=True)),
+            "buffer_gb": round(w.buffer_bytes / 2 / 1e9, 1), "steps_per_launch": steps_per_launch,
             "one_launch_per_step_ms": round(ms_ahead, 5), "not_announced_ms_per_step": round(ms_plain, 5)}
 
 
@@ -495,10 +477,11 @@ def main():
     # the gather of rb_sample_augment.
     n_rows = min(w.r, res["last_n"])
     if res["steps_per_launch"] > 1:
-        # several steps per launch; average launch = MANY steps / the launches of one call
-        launches = len(window_schedule(w, MANY, announced=True))
+        # several steps per launch, every launch of a call of MANY steps the same size
+        per = res["steps_per_launch"]
+        assert MANY % per == 0
         kernel = "rb_window_kernel"
-        k_ms, k_bytes = res["ms_per_step"] * MANY / launches, 2 * (w.c + n_rows) * w.row_bytes * MANY / launches
+        k_ms, k_bytes = res["ms_per_step"] * per, 2 * (w.c + n_rows) * w.row_bytes * per
     elif res["launches_per_step"] == 1:
         # rb_update_sample_many announces every next step's labels for itself: one planned launch per step
         kernel, k_ms, k_bytes = res["plan_ahead_kernel"], res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes

@@ -245,6 +245,16 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
 int rb_announce_next_many(rb_buffer *rb, int64_t n, const int64_t *const *next_batch_y);
 
 /*
+ * How many steps of this shape rb_update_sample_many puts into one launch at
+ * most, with the handle's present policy, storage and options (1: every step
+ * gets a launch, or two, of its own).  A stream of calls that are announced to
+ * each other (rb_announce_next_many) consists of launches of exactly this
+ * size, apart from a call's remainder.  Host only.
+ * RB_EINVAL: null pointers, b, c or r out of range (as in rb_update_sample).
+ */
+int rb_query_steps_per_launch(const rb_buffer *rb, int64_t b, int64_t c, int64_t r, int64_t *steps);
+
+/*
  * The asynchronous form of that primitive (Sec. IV-D, Fig. 4, Listing 1): the
  * training loop calls it once per iteration with the iteration's mini-batch;
  * the call (1) makes `train_stream` wait until the representatives that the

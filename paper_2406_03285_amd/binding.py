@@ -24,7 +24,7 @@ RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
     "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
-    "rb_announce_next", "rb_announce_next_many", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
+    "rb_announce_next", "rb_announce_next_many", "rb_query_steps_per_launch", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
@@ -53,6 +53,7 @@ def _load():
     L.rb_update_sample.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp]
     L.rb_announce_next.argtypes = [vp, vp]
     L.rb_announce_next_many.argtypes = [vp, i64, C.POINTER(vp)]
+    L.rb_query_steps_per_launch.argtypes = [vp, i64, i64, i64, C.POINTER(i64)]
     L.rb_update_sample_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp)]
     L.rb_pipeline_create.argtypes = [C.POINTER(vp), vp]
     L.rb_pipeline_step.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp, vp, C.POINTER(i64)]
@@ -145,6 +146,12 @@ def rb_announce_next_many(rb, n, next_batch_y):
     """next_batch_y: sequence of n label tensors / addresses, or an array made by pointer_array."""
     arr = next_batch_y if next_batch_y is None or isinstance(next_batch_y, (C.Array, C._Pointer)) else pointer_array(next_batch_y)
     return _L.rb_announce_next_many(rb, int(n), arr)
+
+
+def rb_query_steps_per_launch(rb, b, c, r):
+    steps = C.c_int64(0)
+    rc = _L.rb_query_steps_per_launch(rb, int(b), int(c), int(r), C.byref(steps))
+    return rc, steps.value
 
 
 def pointer_array(items):
@@ -315,6 +322,11 @@ class RehearsalBuffer:
         for y in next_batch_y:
             assert y.is_contiguous() and y.dtype == torch.int64
         _check(rb_announce_next_many(self.handle, len(next_batch_y), next_batch_y), "rb_announce_next_many")
+
+    def steps_per_launch(self, b, c, r):
+        rc, steps = rb_query_steps_per_launch(self.handle, b, c, r)
+        _check(rc, "rb_query_steps_per_launch")
+        return steps
 
     def read_state(self):
         rc, fill, last_n, flags = rb_read_state(self.handle, self.K)

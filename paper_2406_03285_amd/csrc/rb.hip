@@ -451,6 +451,17 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
     return p;
 }
 
+// Whether rb_update_sample_many puts several steps of this shape into one launch, and how many at most: the option,
+// and what the planner's tables hold.  1: one launch (or two) per step.
+int64_t window_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
+{
+    const bool windowed = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 && rb->opt_fuse &&
+                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
+    if (!windowed) return 1;
+    return std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
+                                                  std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
+}
+
 // n steps as launches of up to WIN_MAX steps each.  Workgroup 0 of every launch plans the next
 // window while the others move the rows of this one; the first window is planned by a launch of its
 // own and kept short, so that the movers get going early - unless the last launch of the call before
@@ -460,9 +471,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                    int64_t ann_n, const int64_t* const* ann_y)
 {
     static_assert(WIN_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
-    // most steps of one launch: the option, and what the planner's tables hold
-    const int64_t wmax = std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
-                                                                std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
+    const int64_t wmax = window_limit(rb, b, c, r);
     // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
     // compute unit, tiles of four vectors per thread measured best (1000 classes of 3x224x224 bfloat16 samples,
     // 64 candidates and representatives: 13.1 us per step against 14.1 with two and 14.2 with eight; binary32
@@ -851,6 +860,14 @@ int rb_announce_next(rb_buffer* rb, const int64_t* next_batch_y)
     return RB_OK;
 }
 
+int rb_query_steps_per_launch(const rb_buffer* rb, int64_t b, int64_t c, int64_t r, int64_t* steps)
+{
+    if (!rb || !steps) return RB_EINVAL;
+    if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b || r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
+    *steps = window_limit(rb, b, c, r);
+    return RB_OK;
+}
+
 int rb_announce_next_many(rb_buffer* rb, int64_t n, const int64_t* const* next_batch_y)
 {
     if (!rb || n < 0 || (n > 0 && !next_batch_y)) return RB_EINVAL;
@@ -877,9 +894,7 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
         const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (bad != RB_OK) return bad;
     }
-    const bool windowed = n >= 2 && c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 &&
-                          rb->opt_fuse && rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT &&
-                          rb->eviction == RB_EVICT_UNIFORM;
+    const bool windowed = n >= 2 && window_limit(rb, b, c, r) >= 2;
     if (windowed) {
         if (rb->plan_valid) {                    // a single step that was planned ahead is not executed as planned
             rb->cur ^= 1;

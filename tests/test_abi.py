@@ -111,4 +111,16 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_announce_next_many(h, 1, None) == rb.RB_EINVAL
     assert rb.rb_announce_next_many(h, 12, [256 * (i + 1) for i in range(12)]) == rb.RB_OK
     assert rb.rb_announce_next_many(h, 0, None) == rb.RB_OK
+    # steps per launch of the multi-step call: host arithmetic only
+    assert rb.rb_query_steps_per_launch(None, 8, 2, 2)[0] == rb.RB_EINVAL
+    assert rb.rb_query_steps_per_launch(h, 0, 0, 0)[0] == rb.RB_EINVAL and rb.rb_query_steps_per_launch(h, 8, 9, 2)[0] == rb.RB_EINVAL
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16)            # few rows per step: the most
+    assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 8)          # 1024 table entries / 128 rows per step
+    assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 12)         # 512 planner slots / max(c, r)
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 1)           # not eligible
+    assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 1)
+    assert rb.rb_query_steps_per_launch(h, 64, 0, 8) == (rb.RB_OK, 1)
+    assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 5) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
+    assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 17) == rb.RB_EINVAL
+    assert rb.rb_set_policy(h, rb.RB_SELECT_EXACT, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 1)
     rb.rb_destroy(h)
