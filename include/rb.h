@@ -201,20 +201,24 @@ int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
 int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
 
 /*
- * n consecutive rb_update_sample steps from one call, for callers that have
- * several mini-batches ready (e.g. a prefetching data pipeline).  When the
- * steps are eligible for the single launch (see rb_update_sample; b <= 2048)
- * up to 16 of them (1024 / (c + r) and 512 / max(c, r) at most) share ONE
- * launch: the rows of all of them are moved at once,
- * by a plan that one workgroup of the launch before made (what the order of
- * separate launches would settle between steps - a representative read from a
- * slot that another step of the same launch writes - the plan settles), so the
- * cost of a launch is paid once per that many steps.  Otherwise the steps are enqueued
- * one after the other.  Step i uses batch_x[i], batch_y[i], step number
- * first_step + i and writes to out_x[i], out_y[i]; b, c, r and
- * seed are common.  The four pointer arrays are HOST arrays of n device
- * pointers, read before the call returns.  All n steps are validated first;
- * on an error nothing was enqueued.  Results are those of n separate calls.
+ * n consecutive rb_update_sample steps (Sec. IV-D step 2: update the buffer
+ * with the mini-batch, then sample the next representatives) from one call,
+ * for callers that have several mini-batches ready (e.g. a prefetching data
+ * pipeline).  When 1 <= c <= 64, 1 <= r <= 64, classes <= 1024, b <= 2048 and
+ * the policy is the default one (either storage form), up to 16 of the steps
+ * - as many as 1024 / (c + r) and 512 / max(c, r) allow, see
+ * rb_query_steps_per_launch - share ONE launch: the rows of all of them are
+ * moved at once, by a plan that one workgroup of the launch before made.  What
+ * the order of separate launches would settle between steps (a representative
+ * read from a slot that another step of the same launch writes, a slot written
+ * twice) the plan settles, so the cost of a launch is paid once per that many
+ * steps.  Otherwise the steps are enqueued one after the other, each
+ * announcing the next one's labels (rb_announce_next) for itself.  Step i uses
+ * batch_x[i], batch_y[i], step number first_step + i and writes to out_x[i],
+ * out_y[i]; b, c, r and seed are common.  The four pointer arrays are HOST
+ * arrays of n device pointers, read before the call returns.  All n steps are
+ * validated first; on an error nothing was enqueued.  Results are those of n
+ * separate calls, bit for bit.
  * The outputs and mini-batches of any 16 consecutive steps must not overlap.
  */
 int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
