@@ -24,7 +24,7 @@ constexpr uint32_t BIG_EMPTY = 0xFFFFFFFFu;   // free slot (no class, row or dra
 constexpr int BIG_GROUP = TPB;                // threads that move one tile together
 constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
 // LDS words: fill counts | region U | region V | selection / sampling draws
-constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX) * 4;
+constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX + 4) * 4;   // (+4: the class lists are read four words at a time)
 constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
 constexpr size_t BIG_FWD_BYTES = (size_t)2 * BIG_HASH * 4;      // the table of the slot rows a step writes, in memory
 
@@ -148,15 +148,16 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, int32_t* s_
     const int sel_base = b - c;
     const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)tid, (uint64_t)(sel_base + tid + 1)) : 0u;
     if (active) s_u[t] = 0xFFFFFFFFu;
+    __syncthreads();
+    if (active) atomicMin(&s_u[t], (uint32_t)tid);
+    __syncthreads();
+    if (active) s_draw[tid] = t | ((s_u[t] != (uint32_t)tid) ? 0x80000000u : 0u);     // t < 4096
+    // the loads have had the two rounds above to arrive
 #pragma unroll
     for (int u = 0; u < 4; ++u) {
         const int64_t y = yv[u];
         s_v[tid + u * BIG_TPB] = (uint32_t)((y >= 0 && y < K) ? (int32_t)y : LAB_INVALID);
     }
-    __syncthreads();
-    if (active) atomicMin(&s_u[t], (uint32_t)tid);
-    __syncthreads();
-    if (active) s_draw[tid] = t | ((s_u[t] != (uint32_t)tid) ? 0x80000000u : 0u);     // t < 4096
 #pragma unroll
     for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
     __syncthreads();
@@ -219,7 +220,11 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
 
     // ---- insertion number and slot ----
     int rank = 0;
-    for (int i = 0; i < total; ++i) rank += (int)((int)(list[start + i] >> 10) < x);
+    for (int i = 0; i < total; i += 4) {             // four members per round; what is read past the class's list is not counted
+        const uint32_t m0 = list[start + i], m1 = list[start + i + 1], m2 = list[start + i + 2], m3 = list[start + i + 3];
+        rank += (int)((int)(m0 >> 10) < x) + (int)(i + 1 < total && (int)(m1 >> 10) < x) + (int)(i + 2 < total && (int)(m2 >> 10) < x) +
+                (int)(i + 3 < total && (int)(m3 >> 10) < x);
+    }
     const int64_t at = fill0 + rank;
     const bool over = valid && at >= S;              // beyond the capacity: overwrites a uniformly drawn slot
     int64_t slot = at;
