@@ -205,7 +205,8 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * with the mini-batch, then sample the next representatives) from one call,
  * for callers that have several mini-batches ready (e.g. a prefetching data
  * pipeline).  When 1 <= c <= 64, 1 <= r <= 64, classes <= 1024, b <= 2048 and
- * the policy is the default one (either storage form), up to 16 of the steps
+ * the selection is the exact one (any replacement strategy, either storage
+ * form), up to 16 of the steps
  * - as many as 1024 / (c + r) and 512 / max(c, r) allow, see
  * rb_query_steps_per_launch - share ONE launch: the rows of all of them are
  * moved at once, by a plan that one workgroup of the launch before made.  What

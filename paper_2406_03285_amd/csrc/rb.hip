@@ -421,16 +421,24 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     return RB_OK;
 }
 
-template <bool NT, bool BF16>
-hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
+template <bool NT, bool BF16, bool AUX>
+hipError_t launch_window_u(const WinMoveArgs& m, const WinPlanArgs& next, int unroll, dim3 grid, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_window_kernel<1, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    case 2: rb_window_kernel<2, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    case 4: rb_window_kernel<4, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    default: rb_window_kernel<8, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 1: rb_window_kernel<1, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    case 2: rb_window_kernel<2, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    case 4: rb_window_kernel<4, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    default: rb_window_kernel<8, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
     }
     return hipGetLastError();
+}
+
+// aux: the replacement strategy keeps per-class state (FIFO, reservoir)
+template <bool NT>
+hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, bool bf16, bool aux, int unroll, dim3 grid, hipStream_t st)
+{
+    if (bf16) return aux ? launch_window_u<NT, true, true>(m, next, unroll, grid, st) : launch_window_u<NT, true, false>(m, next, unroll, grid, st);
+    return aux ? launch_window_u<NT, false, true>(m, next, unroll, grid, st) : launch_window_u<NT, false, false>(m, next, unroll, grid, st);
 }
 
 WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
@@ -448,6 +456,9 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
     p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
     p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
     p.S = rb->S;
+    p.eviction = rb->eviction;
+    p.aux_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_aux[rb->cur]);
+    p.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
     return p;
 }
 
@@ -456,7 +467,7 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
 int64_t window_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
     const bool windowed = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 && rb->opt_fuse &&
-                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM;
+                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT;
     if (!windowed) return 1;
     return std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
                                                   std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
@@ -509,7 +520,8 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         nat = w0;
         tbl = 0;
         const WinPlanArgs p = window_plan_args(rb, batch_y, 0, w, b, c, r, seed, first_step, tbl);
-        rb_window_plan_kernel<<<dim3(1), TPB, 0, rb->stream>>>(p);
+        if (rb->eviction != RB_EVICT_UNIFORM) rb_window_plan_kernel<true><<<dim3(1), TPB, 0, rb->stream>>>(p);
+        else rb_window_plan_kernel<false><<<dim3(1), TPB, 0, rb->stream>>>(p);
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         rb->cur ^= 1;
     }
@@ -538,12 +550,9 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         m.row_vec = rb->row_vec;
         m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
         const dim3 grid((unsigned)(w * (c + r) * sh.tpr + (next_w > 0 ? 1 : 0)));
-        const bool bf16 = rb->storage == RB_STORE_BF16;
-        hipError_t e;
-        if (rb->opt_nt) e = bf16 ? launch_window<true, true>(m, next, sh.unroll, grid, 0, rb->stream)
-                                 : launch_window<true, false>(m, next, sh.unroll, grid, 0, rb->stream);
-        else e = bf16 ? launch_window<false, true>(m, next, sh.unroll, grid, 0, rb->stream)
-                      : launch_window<false, false>(m, next, sh.unroll, grid, 0, rb->stream);
+        const bool bf16 = rb->storage == RB_STORE_BF16, aux = rb->eviction != RB_EVICT_UNIFORM;
+        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, bf16, aux, sh.unroll, grid, rb->stream)
+                                        : launch_window<false>(m, next, bf16, aux, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         if (ahead) {

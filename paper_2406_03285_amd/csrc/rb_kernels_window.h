@@ -55,6 +55,9 @@ struct WinPlanArgs {
     int32_t b, c, r;
     int32_t K, nchunks;
     int64_t S;
+    int32_t eviction;                  // RB_EVICT_*
+    const int32_t* aux_old;            // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
+    int32_t* aux_new;
 };
 
 struct WinMoveArgs {
@@ -129,7 +132,8 @@ struct WinCand {
     int32_t k;        // class, LAB_* when not a valid candidate
     int fill0;        // samples of the class stored before the step
     int rank, total;  // class-mates earlier in the mini-batch / in all
-    int slot;         // slot within the class: appended, or drawn when the class is full
+    int slot;         // slot within the class: appended, or the one it overwrites when the class is full; -1: not kept
+    int32_t aux0;     // the class's FIFO / reservoir state before the step
     bool valid, bad, any_over;
 };
 
@@ -151,6 +155,7 @@ struct WinLds {
     int32_t* s_ck;        // [WAVE] candidate classes, positions, scratch (wavefront 0 only)
     int32_t* s_cx;
     int32_t* s_cw;
+    const int32_t* s_aux;     // [NCLS] per-class state of the FIFO / reservoir strategies (only with them)
     const uint16_t* s_wpos;   // [WIN_SLOTS] mini-batch position of every step's candidates (step * max(c, r) + i)
     const int16_t* s_lab;     // [WIN_SLOTS] ... and their classes (LAB_INVALID when outside [0, K))
     int stride;               // of the per-step arrays: max(c, r)
@@ -176,6 +181,8 @@ __device__ __forceinline__ const int64_t* win_labels(const WinPlanArgs& a, int s
 }
 
 // Wavefront 0: candidates of step s, up to the slot each one asks for.  Needs the fill counts after step s-1.
+// AUX: the replacement strategy is FIFO or reservoir (Alg. 1 with the variants of its line 5).
+template <bool AUX>
 __device__ __forceinline__ WinCand win_candidates(const WinPlanArgs& a, int s, const WinLds& l)
 {
     const int lane = threadIdx.x & (WAVE - 1);
@@ -204,17 +211,32 @@ __device__ __forceinline__ WinCand win_candidates(const WinPlanArgs& a, int s, c
     cd.rank = rank;
     cd.total = total;
     const int64_t at = (int64_t)cd.fill0 + rank;
-    const bool over = cd.valid && at >= a.S;       // beyond the capacity: overwrites a drawn slot
+    const bool over = cd.valid && at >= a.S;       // beyond the capacity: overwrites a stored sample
     cd.slot = cd.valid ? (int)at : -1;
     cd.any_over = __ballot(over) != 0;
-    if (over) cd.slot = (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);
+    cd.aux0 = 0;
+    if (!AUX) {
+        if (over) cd.slot = (int)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)a.S);      // a uniformly drawn one
+    } else {
+        cd.aux0 = cd.valid ? l.s_aux[k] : 0;
+        if (a.eviction == RB_EVICT_FIFO) {
+            if (over) cd.slot = (int)(((int64_t)cd.aux0 + at - a.S) % a.S);                   // the oldest one
+        } else if (over) {
+            // reservoir: kept with probability S / (samples offered to the class so far + 1), then in a uniform slot
+            const int64_t offers = (int64_t)cd.aux0 + rank < INT32_MAX ? (int64_t)cd.aux0 + rank : INT32_MAX;
+            const int64_t draw = (int64_t)below(sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)offers + 1);
+            cd.slot = draw < a.S ? (int)draw : -1;
+        }
+    }
     return cd;
 }
 
+template <bool AUX>
 __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
 {
     constexpr int NCLS = DIRECT_CHUNKS * CH;
     __shared__ __align__(16) int32_t s_fill[NCLS];    // fill counts, carried from step to step
+    __shared__ __align__(16) int32_t s_aux[AUX ? NCLS : 4];   // FIFO / reservoir state of the classes, carried likewise
     __shared__ __align__(16) int32_t s_pre[NCLS];     // stored samples in the classes before each class, after the step's update
     __shared__ uint32_t s_h[2 * WIN_HASH];
     uint32_t* s_hkey = s_h;                           // buffer rows the window touches ...
@@ -237,11 +259,14 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     WinHeader* head = reinterpret_cast<WinHeader*>(a.table);
     WinEntry* entry = reinterpret_cast<WinEntry*>(a.table + WIN_MAX * sizeof(WinHeader));
     WinLds l;
-    l.s_fill = s_fill; l.s_ck = s_ck; l.s_cx = s_cx; l.s_cw = s_cw; l.s_wpos = s_wpos; l.s_lab = s_lab; l.stride = stride;
+    l.s_fill = s_fill; l.s_aux = s_aux; l.s_ck = s_ck; l.s_cx = s_cx; l.s_cw = s_cw; l.s_wpos = s_wpos; l.s_lab = s_lab; l.stride = stride;
 
     // ---- before the first step ----
-    int4 fo = make_int4(0, 0, 0, 0);
-    if (4 * tid < a.nchunks * CH) fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+    int4 fo = make_int4(0, 0, 0, 0), ao = make_int4(0, 0, 0, 0);
+    if (4 * tid < a.nchunks * CH) {
+        fo = *reinterpret_cast<const int4*>(a.fill_old + 4 * tid);
+        if (AUX) ao = *reinterpret_cast<const int4*>(a.aux_old + 4 * tid);
+    }
     // candidates of all steps and their labels; a selecting wavefront needs b words of scratch
     const int nsel = b <= 2 * WIN_HASH / NWAVE ? NWAVE : 2;
     constexpr int SEL_MAX = WIN_MAX / 2;              // steps per selecting wavefront at most
@@ -268,6 +293,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
         s_hval[i] = 0xFFFFFFFFu;
     }
     *reinterpret_cast<int4*>(s_fill + 4 * tid) = fo;
+    if (AUX) *reinterpret_cast<int4*>(s_aux + 4 * tid) = ao;
     if (tid == 0) s_flags = 0;
     if (wave < nsel) {
 #pragma unroll
@@ -279,7 +305,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     }
     lds_barrier();
     WinCand cd = {};
-    if (wave == 0) cd = win_candidates(a, 0, l);
+    if (wave == 0) cd = win_candidates<AUX>(a, 0, l);
 
     for (int s = 0; s < w; ++s) {
         if (wave == 0) {
@@ -287,26 +313,27 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
             const int x = cd.x;
             const int32_t k = cd.k;
             const bool valid = cd.valid;
-            const int64_t row = valid ? (int64_t)k * a.S + cd.slot : -1;
+            const bool placed = valid && cd.slot >= 0;       // (a reservoir may not keep a candidate)
+            const int64_t row = placed ? (int64_t)k * a.S + cd.slot : -1;
             const int me = s * rows + lane;
             int h = 0;
             // candidates that share a slot share a table slot
-            if (valid) h = win_find_or_insert(s_hkey, (uint32_t)row);
+            if (placed) h = win_find_or_insert(s_hkey, (uint32_t)row);
             wave_fence();
-            const uint32_t v = valid ? s_hval[h] : 0xFFFFFFFFu;
-            bool stored = valid;
+            const uint32_t v = placed ? s_hval[h] : 0xFFFFFFFFu;
+            bool stored = placed;
             if (cd.any_over) {
                 // of the candidates that ask for one slot only the last of the mini-batch is stored:
                 // one of them (whose lane number lands in the table slot) collects the largest position
                 s_cw[lane] = -1;
                 wave_fence();
-                if (valid) s_hval[h] = (uint32_t)lane;
+                if (placed) s_hval[h] = (uint32_t)lane;
                 wave_fence();
-                const int leader = valid ? (int)s_hval[h] : lane;
+                const int leader = placed ? (int)s_hval[h] : lane;
                 wave_fence();
-                if (valid) atomicMax(&s_cw[leader], x);
+                if (placed) atomicMax(&s_cw[leader], x);
                 wave_fence();
-                stored = valid && s_cw[leader] == x;
+                stored = placed && s_cw[leader] == x;
                 wave_fence();
             }
             int chain = -1;
@@ -329,10 +356,19 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
                 e.pad[0] = 0; e.pad[1] = 0;
                 entry[me] = e;
             }
-            // the class's fill count after this step (one lane per class: its first candidate)
+            // the class's fill count (and strategy state) after this step (one lane per class: its first candidate)
             if (valid && cd.rank == 0) {
                 const int64_t f = (int64_t)cd.fill0 + cd.total;
                 s_fill[k] = (int32_t)(f < a.S ? f : a.S);
+                if (AUX) {
+                    if (a.eviction == RB_EVICT_FIFO) {
+                        // the oldest sample moves on by the number of overwrites
+                        s_aux[k] = (int32_t)(((int64_t)cd.aux0 + (f > a.S ? f - a.S : 0)) % a.S);
+                    } else {
+                        const int64_t seen = (int64_t)cd.aux0 + cd.total;
+                        s_aux[k] = (int32_t)(seen < INT32_MAX ? seen : INT32_MAX);
+                    }
+                }
             }
             if (cd.bad && lane == 0) s_flags |= RB_FLAG_BAD_LABEL;
         }
@@ -349,7 +385,7 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
         lds_barrier();
 
         if (wave == 0) {
-            if (s + 1 < w) cd = win_candidates(a, s + 1, l);
+            if (s + 1 < w) cd = win_candidates<AUX>(a, s + 1, l);
         } else if (wave == 1) {
             // ---- representatives of step s: lane j = draw j of Floyd's n-subset of the F stored samples ----
             const int n = r < F ? r : F;
@@ -450,7 +486,10 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
     }
 
     // ---- fill counts after the window ----
-    if (4 * tid < a.nchunks * CH) *reinterpret_cast<int4*>(a.fill_new + 4 * tid) = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
+    if (4 * tid < a.nchunks * CH) {
+        *reinterpret_cast<int4*>(a.fill_new + 4 * tid) = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
+        if (AUX) *reinterpret_cast<int4*>(a.aux_new + 4 * tid) = *reinterpret_cast<const int4*>(s_aux + 4 * tid);
+    }
     {
         const int4 f4 = *reinterpret_cast<const int4*>(s_fill + 4 * tid);
         const int wsum = lane_read(wave_scan_incl(f4.x + f4.y + f4.z + f4.w), WAVE - 1);   // a wavefront covers one chunk of CH classes
@@ -459,9 +498,10 @@ __device__ __forceinline__ void plan_window(const WinPlanArgs& a)
 }
 
 // The plan of the first window of a call, on its own.
+template <bool AUX>
 __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a)
 {
-    plan_window(a);
+    plan_window<AUX>(a);
 }
 
 // ---------------------------------------------------------------------------
@@ -471,14 +511,15 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 // stream frees the movers but the events that order the two streams cost more than
 // that gains.)
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+template <int U, bool NT, bool BF16, bool AUX>   // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors);
+                                                 // AUX: FIFO or reservoir replacement (the planner carries their per-class state)
 __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, const WinPlanArgs next)
 {
     if (next.w > 0 && blockIdx.x == 0) {
         // dispatched first, and first in line whenever it has an instruction ready: the next launch
         // waits for this one workgroup as much as for all the movers
         __builtin_amdgcn_s_setprio(3);
-        plan_window(next);
+        plan_window<AUX>(next);
         return;
     }
     const int mover = blockIdx.x - (next.w > 0 ? 1 : 0);

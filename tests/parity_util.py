@@ -184,7 +184,7 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
     assert buf.read_state()[2] == orc.flags
 
 
-def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False):
+def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None):
     """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
     against the oracle step by step.  announce: the labels of the next call's first steps are announced
     before every call (the last launch of a call then plans them); with a schedule seed some of those
@@ -198,6 +198,9 @@ def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
     if store_bf16:
         orc.set_storage(rbo.STORE_BF16)
+    if policy is not None:
+        buf.set_policy(*policy)
+        orc.set_policy(*policy)
     oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(per_call)]
     oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(per_call)]
     rng = np.random.default_rng(schedule_seed)

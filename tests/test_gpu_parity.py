@@ -435,6 +435,26 @@ def test_many_steps_with_float32_samples_stored_as_bfloat16(w, steps, per_call, 
     run_many_parity(w, steps, per_call=per_call, announce=announce, store_bf16=True)
 
 
+@pytest.mark.parametrize("policy", ["exact-fifo", "exact-reservoir"])
+@pytest.mark.parametrize("w,steps,per_call", [
+    (wl.C1, 100, 17),                                                                           # fills up: every strategy replaces
+    (wl.variant(wl.C4, name="C4-S8-many-policy", S=8, shape=(3, 32, 32)), 64, 32),              # Zipf head: many class-mates per step
+    (wl.Workload("laps-many", 9, 3, 2, (8,), "f32", 64, 64, 64, 30, "normal", "uniform"), 32, 8),   # ~21 candidates per class into 2 slots: whole rounds within a step
+    (wl.variant(wl.C2, name="C2-S3-many-policy", S=3), 96, 16),
+    (wl.variant(wl.C1, name="C1-one-class-many-policy", K=1, S=7, c=16, r=16), 48, 16),         # every hazard between the steps of a launch
+], ids=["C1", "C4-S8", "laps", "C2-S3", "one-class"])
+def test_many_steps_with_other_replacement_strategies(policy, w, steps, per_call):
+    run_many_parity(w, steps, per_call=per_call, announce=True, policy=POLICIES[policy])
+
+
+def test_many_steps_policy_bf16_and_broken_promises_together():
+    w = wl.variant(wl.C1, name="C1-many-fifo-bf16-promises", K=4, S=5, c=12, r=12)
+    run_many_parity(w, 90, per_call=9, announce=True, schedule_seed=7, store_bf16=True, policy=POLICIES["exact-fifo"])
+    run_many_parity(w, 90, per_call=9, announce=True, schedule_seed=8, store_bf16=True, policy=POLICIES["exact-reservoir"])
+    # the Bernoulli selection has no bound of 64 on its candidates: the steps go out one by one, results unchanged
+    run_many_parity(w, 30, per_call=9, announce=True, policy=POLICIES["bernoulli-fifo"])
+
+
 @pytest.mark.parametrize("seed", [1, 2, 3])
 def test_many_steps_announced_survive_broken_promises(seed):
     run_many_parity(wl.variant(wl.C4, name=f"C4-S8-many-promises-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 160, per_call=12,
@@ -717,16 +737,17 @@ def test_random_configurations_planned_ahead(chunk):
         style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
         per_call = int(rng.choice([3, 8, 17, 33]))
         print(f"  {w.name} {style} per_call={per_call}", flush=True)
+        policy = POLICIES[str(rng.choice(["exact-fifo", "exact-reservoir"]))] if rng.random() < 0.4 else None
         if style == "ahead":
-            run_ahead_parity(w, 8)
+            run_ahead_parity(w, 8, policy=policy)
         elif style == "ahead-broken":
-            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)))
+            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)), policy=policy)
         elif style == "many":
-            run_many_parity(w, 40, per_call=per_call)
+            run_many_parity(w, 40, per_call=per_call, policy=policy)
         elif style == "many-announced":
-            run_many_parity(w, 40, per_call=per_call, announce=True)
+            run_many_parity(w, 40, per_call=per_call, announce=True, policy=policy)
         else:
-            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)))
+            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)), policy=policy)
 
 
 # ------------------------------------------------------------- edge cases ---
