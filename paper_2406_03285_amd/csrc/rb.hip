@@ -278,6 +278,8 @@ PlanArgs make_plan(const rb_buffer* rb, const int64_t* batch_y, int64_t b, int64
     p.eviction = rb->eviction;
     p.aux_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_aux[rb->cur]);
     p.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
+    p.selection = rb->selection;
+    p.ce = (int32_t)(rb->selection == RB_SELECT_BERNOULLI ? b : c);
     return p;
 }
 
@@ -398,11 +400,12 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     m.out_y = out_y;
     m.table = rb->ws + rb->off_wtbl[rb->tbl_planned];
     m.state = reinterpret_cast<DevState*>(rb->ws);
-    m.c = (int32_t)c; m.r = (int32_t)r;
+    const int64_t ce = rb->selection == RB_SELECT_BERNOULLI ? b : c;     // candidate entries of the table
+    m.c = (int32_t)ce; m.r = (int32_t)r;
     m.S = rb->S;
     m.row_vec = rb->row_vec;
     m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
-    const int64_t items = (c + r) * sh.tpr;
+    const int64_t items = (ce + r) * sh.tpr;
     rb->plan_valid = false;                     // this step is being executed
     m.plan_next = next_y ? 1 : 0;
     PlanArgs next = {};
@@ -811,8 +814,9 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
                            rb->selection == RB_SELECT_EXACT;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
     // larger counts have a plan-ahead form of their own (default policy, storage in the sample's own type)
+    // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)
     const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
-                     rb->opt_fuse && rb->selection == RB_SELECT_EXACT && rb->eviction == RB_EVICT_UNIFORM &&
+                     rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) && rb->eviction == RB_EVICT_UNIFORM &&
                      rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call

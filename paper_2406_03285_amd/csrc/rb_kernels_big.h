@@ -144,7 +144,11 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, int32_t* s_
         const int q = tid + u * BIG_TPB;
         fo[u] = q < K ? a.fill_old[q] : 0;
     }
-    const bool active = tid < c;
+    // Bernoulli selection (b <= BIG_MAX): thread i = mini-batch position i, selected by its own coin; the rounds
+    // of Floyd's subset below then run empty
+    const bool bernoulli = a.selection == RB_SELECT_BERNOULLI;
+    const bool heads = bernoulli && tid < b && (int64_t)below(a.sd, PURPOSE_COIN, (uint32_t)tid, (uint64_t)b) < c;
+    const bool active = !bernoulli && tid < c;
     const int sel_base = b - c;
     const uint32_t t = active ? (uint32_t)below(a.sd, PURPOSE_SELECT, (uint32_t)tid, (uint64_t)(sel_base + tid + 1)) : 0u;
     if (active) s_u[t] = 0xFFFFFFFFu;
@@ -162,8 +166,8 @@ __device__ __forceinline__ BigSelected big_select(const PlanArgs& a, int32_t* s_
     for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
     __syncthreads();
     BigSelected sel;
-    sel.x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : 0;
-    sel.k = active ? (int32_t)s_v[sel.x] : LAB_UNSELECTED;
+    sel.x = active ? (big_replaced(s_draw, tid, sel_base) ? sel_base + tid : (int)t) : (heads ? tid : 0);
+    sel.k = active || heads ? (int32_t)s_v[sel.x] : LAB_UNSELECTED;
     __syncthreads();
     return sel;
 }
@@ -178,7 +182,6 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     __shared__ int s_wave[BIG_NWAVE];
 
     const int tid = threadIdx.x;
-    const int c = a.c;
     const int64_t S = a.S;
     PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
 
@@ -245,7 +248,7 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     __syncthreads();
     // of the candidates that go to one slot the last of the mini-batch is stored
     const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
-    if (tid < c) {
+    if (tid < a.ce) {
         PlanEntry e;
         e.pos = x;
         e.label = valid ? k : -1;
@@ -280,7 +283,7 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
     __shared__ uint32_t s_hit[BIG_CLASSES / 32];           // one bit per class: it gets candidates in this step
 
     const int tid = threadIdx.x;
-    const int c = a.c, r = a.r, K = a.K;
+    const int r = a.r, K = a.K;
     const int64_t S = a.S;
     PlanHeader* head = reinterpret_cast<PlanHeader*>(a.table);
     PlanEntry* entry = reinterpret_cast<PlanEntry*>(a.table + sizeof(PlanHeader));
@@ -386,13 +389,13 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
         e.pos = pos;
         e.label = pk;                           // -1 when fewer samples are stored than asked for
         e.row = prow;
-        entry[c + tid] = e;
+        entry[a.ce + tid] = e;
     }
     if (tid == 0) {
         PlanHeader hh;
         hh.n = n;
         hh.flags = s_flags;
-        hh.c = c;
+        hh.c = a.ce;
         hh.r = r;
         *head = hh;
     }

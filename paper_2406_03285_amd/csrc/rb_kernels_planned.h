@@ -40,6 +40,8 @@ struct PlanArgs {
     int32_t eviction;         // RB_EVICT_*
     const int32_t* aux_old;   // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
     int32_t* aux_new;
+    int32_t selection;        // RB_SELECT_* (the large-count form only; the others are for the exact selection)
+    int32_t ce;               // candidate entries of the table: c, or b with the Bernoulli selection (one per position)
 };
 
 struct MoveArgs {

@@ -225,6 +225,24 @@ def test_plan_ahead_steps_with_large_counts(w, steps):
     run_ahead_parity(w, steps)
 
 
+@pytest.mark.parametrize("w,steps", [
+    (wl.C1, 100),                                                                               # 16 positions, about 4 candidates: fills up, replaces
+    (wl.variant(wl.C2, name="C2-S3-bernoulli-ahead", S=3), 80),
+    (wl.variant(wl.C4, name="C4-S8-bernoulli-ahead", S=8, shape=(3, 32, 32)), 60),              # 512 positions, Zipf head
+    (wl.variant(wl.C5, name="C5-b1024-bernoulli-ahead", K=300, S=12, shape=(256,), b=1024, c=400, r=150), 30),   # the largest mini-batch this form takes
+    (wl.variant(wl.C5, name="C5-b1025-bernoulli-ahead", K=300, S=12, shape=(64,), b=1025, c=400, r=150), 10),    # one more: not eligible, announcement ignored
+    (wl.variant(wl.C1, name="C1-c-equals-b-bernoulli-ahead", b=64, c=64, r=20, S=3), 30),       # every coin shows heads
+], ids=["C1", "C2-S3", "C4-S8", "b1024", "b1025", "c=b"])
+def test_plan_ahead_with_the_bernoulli_selection(w, steps):
+    run_ahead_parity(w, steps, policy=POLICIES["bernoulli-uniform"])
+    run_many_parity(w, min(steps, 40), per_call=7, announce=True, policy=POLICIES["bernoulli-uniform"])
+
+
+def test_plan_ahead_with_the_bernoulli_selection_survives_broken_promises():
+    run_ahead_parity(wl.variant(wl.C4, name="C4-S8-bernoulli-promises", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=3,
+                     policy=POLICIES["bernoulli-uniform"])
+
+
 @pytest.mark.parametrize("seed", [4, 5])
 def test_plan_ahead_with_large_counts_survives_broken_promises(seed):
     run_ahead_parity(wl.variant(wl.C5, name=f"C5-big-promises-{seed}", K=300, S=12, shape=(256,), b=512, c=200, r=150), 70, schedule_seed=seed)
@@ -737,7 +755,7 @@ def test_random_configurations_planned_ahead(chunk):
         style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
         per_call = int(rng.choice([3, 8, 17, 33]))
         print(f"  {w.name} {style} per_call={per_call}", flush=True)
-        policy = POLICIES[str(rng.choice(["exact-fifo", "exact-reservoir"]))] if rng.random() < 0.4 else None
+        policy = POLICIES[str(rng.choice(["exact-fifo", "exact-reservoir", "bernoulli-uniform"]))] if rng.random() < 0.5 else None
         if style == "ahead":
             run_ahead_parity(w, 8, policy=policy)
         elif style == "ahead-broken":
