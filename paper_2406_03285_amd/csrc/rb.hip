@@ -313,7 +313,7 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
     m.out_y = out_y;
     m.table = rb->ws + rb->off_tbl[rb->tbl_planned];
     m.state = reinterpret_cast<DevState*>(rb->ws);
-    m.c = (int32_t)c; m.r = (int32_t)r;
+    m.c = (int32_t)c; m.r = (int32_t)r; m.cgrid = (int32_t)c;
     m.S = rb->S;
     m.row_vec = rb->row_vec;
     m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
@@ -400,12 +400,18 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     m.out_y = out_y;
     m.table = rb->ws + rb->off_wtbl[rb->tbl_planned];
     m.state = reinterpret_cast<DevState*>(rb->ws);
-    const int64_t ce = rb->selection == RB_SELECT_BERNOULLI ? b : c;     // candidate entries of the table
-    m.c = (int32_t)ce; m.r = (int32_t)r;
+    // candidate entries of the table, and how many of them the grid covers: all c, or, with the Bernoulli selection
+    // (about c of the b positions are selected), c and eight standard deviations (more are served by going round)
+    const bool bernoulli = rb->selection == RB_SELECT_BERNOULLI;
+    const int64_t ce = bernoulli ? b : c;
+    int64_t margin = 16;
+    while (margin * margin < 64 * c) ++margin;
+    const int64_t cgrid = bernoulli ? std::min(b, c + margin) : c;
+    m.c = (int32_t)ce; m.r = (int32_t)r; m.cgrid = (int32_t)cgrid;
     m.S = rb->S;
     m.row_vec = rb->row_vec;
     m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
-    const int64_t items = (ce + r) * sh.tpr;
+    const int64_t items = (cgrid + r) * sh.tpr;
     rb->plan_valid = false;                     // this step is being executed
     m.plan_next = next_y ? 1 : 0;
     PlanArgs next = {};

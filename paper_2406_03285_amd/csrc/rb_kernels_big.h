@@ -26,7 +26,8 @@ constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
 // LDS words: fill counts | region U | region V | selection / sampling draws
 constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX + 4) * 4;   // (+4: the class lists are read four words at a time)
 constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
-constexpr size_t BIG_FWD_BYTES = (size_t)2 * BIG_HASH * 4;      // the table of the slot rows a step writes, in memory
+constexpr size_t BIG_FWD_BYTES = ((size_t)2 * BIG_HASH + 4) * 4;   // the table of the slot rows a step writes, in memory, and the
+                                                                  // number of candidate entries of the plan
 
 __device__ __forceinline__ uint32_t big_hash(uint32_t key)
 {
@@ -190,6 +191,10 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     const int32_t k = sel.k;
     const bool valid = k >= 0;
     const int64_t fill0 = valid ? s_fill[k] : 0;
+    // table entry of the thread's candidate: its number in Floyd's emission order, or, with the Bernoulli
+    // selection, its number among the selected positions
+    int ent = tid, count = a.ce;
+    if (a.selection == RB_SELECT_BERNOULLI) ent = big_scan_excl(k != LAB_UNSELECTED ? 1 : 0, count, s_wave);
     // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
     uint32_t* ckey = s_u;
     uint32_t* ccnt = s_u + BIG_HASH;
@@ -248,14 +253,15 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     __syncthreads();
     // of the candidates that go to one slot the last of the mini-batch is stored
     const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
-    if (tid < a.ce) {
+    if (a.selection == RB_SELECT_BERNOULLI ? k != LAB_UNSELECTED : tid < a.ce) {
         PlanEntry e;
         e.pos = x;
         e.label = valid ? k : -1;
         e.row = stored ? row : -1;
-        entry[tid] = e;
+        entry[ent] = e;
     }
     for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) fwd[i] = s_v[i];
+    if (tid == 0) fwd[2 * BIG_HASH] = (uint32_t)count;
 }
 
 // Mini-batch position of the candidate that the step stores in slot row `row`, -1 if the step does not write it.
@@ -426,12 +432,12 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
         return;
     }
     const int64_t item = (int64_t)((int)blockIdx.x - planners) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
-    const int64_t items = (int64_t)(m.c + m.r) * m.tpr;
+    const int64_t items = (int64_t)(m.cgrid + m.r) * m.tpr;
     if (item >= items) return;
     int e, tile;
     split_item(item, m.tpr, e, tile);
     const PlanHeader* head = reinterpret_cast<const PlanHeader*>(m.table);
-    const PlanEntry en = reinterpret_cast<const PlanEntry*>(m.table + sizeof(PlanHeader))[e];
+    const PlanEntry* entry = reinterpret_cast<const PlanEntry*>(m.table + sizeof(PlanHeader));
     int64_t v_lo, v_hi;
     tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
     const bool first = tile == 0 && (threadIdx.x & (BIG_GROUP - 1)) == 0;
@@ -440,15 +446,22 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
         m.state->last_n = hh.n;
         if (hh.flags != 0) atomicOr(&m.state->flags, hh.flags);
     }
-    if (e < m.c) {
-        if (en.row < 0) return;                 // label outside [0, K), or a later class-mate takes the slot
-        if (first) m.buf_y[en.row] = en.label;
-        Tile<U, NT, BIG_GROUP> t;
-        t.load(m.batch_x + (int64_t)en.pos * m.row_vec, v_lo, v_hi);
-        t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
+    if (e < m.cgrid) {
+        // the grid covers cgrid candidate rows; when the plan has more (Bernoulli selection: their number is random),
+        // a group goes on to the entry cgrid further on
+        const int count = (int)fwd[2 * BIG_HASH];
+        for (int ee = e; ee < count; ee += m.cgrid) {
+            const PlanEntry en = entry[ee];
+            if (en.row < 0) continue;           // label outside [0, K), or a later class-mate takes the slot
+            if (first) m.buf_y[en.row] = en.label;
+            Tile<U, NT, BIG_GROUP> t;
+            t.load(m.batch_x + (int64_t)en.pos * m.row_vec, v_lo, v_hi);
+            t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
+        }
         return;
     }
-    const int j = e - m.c;
+    const int j = e - m.cgrid;
+    const PlanEntry en = entry[m.c + j];
     if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
     // written in this very step?  Then the stored candidate's mini-batch row is what the slot will hold.

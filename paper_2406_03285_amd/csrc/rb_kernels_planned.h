@@ -57,6 +57,7 @@ struct MoveArgs {
     int64_t row_vec;
     int32_t tpr, tile_vec, tile_rem;
     int32_t plan_next;        // 1: workgroup 0 plans the next step and the movers start at workgroup 1
+    int32_t cgrid;            // large-count form: candidate rows the grid covers (c; with the Bernoulli selection c plus a margin)
 };
 
 // ---------------------------------------------------------------------------
