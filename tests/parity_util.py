@@ -128,7 +128,7 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     return buf, orc
 
 
-def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None):
+def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None, options=()):
     """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
     broken at random (other labels, other arguments, other calls in between) and the plan must be
     dropped without a trace."""
@@ -142,6 +142,8 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
     if policy is not None:
         buf.set_policy(*policy)
         orc.set_policy(*policy)
+    for opt, val in options:
+        buf.set_option(opt, val)
 
     def batch(t):
         x, y = wl.make_batch(w, t, dev)
@@ -184,7 +186,8 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
     assert buf.read_state()[2] == orc.flags
 
 
-def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None):
+def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None,
+                    options=()):
     """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
     against the oracle step by step.  announce: the labels of the next call's first steps are announced
     before every call (the last launch of a call then plans them); with a schedule seed some of those
@@ -201,6 +204,8 @@ def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule
     if policy is not None:
         buf.set_policy(*policy)
         orc.set_policy(*policy)
+    for opt, val in options:
+        buf.set_option(opt, val)
     oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(per_call)]
     oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(per_call)]
     rng = np.random.default_rng(schedule_seed)

@@ -745,27 +745,30 @@ def _random_planned_workload(rng, i):
     return wl.Workload(f"randp{i}-{kind}-K{K}-S{S}-b{b}-c{c}-r{r}-v{vecs}", 9, K, S, shape, dtype, b, c, r, 6, "normal", labels)
 
 
-@pytest.mark.parametrize("chunk", range(4))
+@pytest.mark.parametrize("chunk", range(6))
 def test_random_configurations_planned_ahead(chunk):
     """Seeded random shapes through the calls that plan ahead: one announced step at a time, and several steps
     per call (with and without the next call announced, sometimes with promises broken)."""
+    rb = _rb()
     rng = np.random.default_rng(2000 + chunk)
     for i in range(10):
         w = _random_planned_workload(rng, chunk * 100 + i)
         style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
         per_call = int(rng.choice([3, 8, 17, 33]))
-        print(f"  {w.name} {style} per_call={per_call}", flush=True)
+        options = ((rb.RB_OPT_UNROLL, int(rng.choice([0, 1, 2, 4, 8]))), (rb.RB_OPT_NONTEMPORAL, int(rng.integers(0, 2))),
+                   (rb.RB_OPT_WINDOW, int(rng.choice([16, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
+        print(f"  {w.name} {style} per_call={per_call} options={[v for _, v in options]}", flush=True)
         policy = POLICIES[str(rng.choice(["exact-fifo", "exact-reservoir", "bernoulli-uniform"]))] if rng.random() < 0.5 else None
         if style == "ahead":
-            run_ahead_parity(w, 8, policy=policy)
+            run_ahead_parity(w, 8, policy=policy, options=options)
         elif style == "ahead-broken":
-            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)), policy=policy)
+            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options)
         elif style == "many":
-            run_many_parity(w, 40, per_call=per_call, policy=policy)
+            run_many_parity(w, 40, per_call=per_call, policy=policy, options=options)
         elif style == "many-announced":
-            run_many_parity(w, 40, per_call=per_call, announce=True, policy=policy)
+            run_many_parity(w, 40, per_call=per_call, announce=True, policy=policy, options=options)
         else:
-            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)), policy=policy)
+            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options)
 
 
 # ------------------------------------------------------------- edge cases ---
