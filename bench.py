@@ -295,6 +295,12 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     ms = rig.timed(steps, many=min(MANY, steps), ahead=True)     # exactly `steps` steps: the last call takes what is left
     n_side = min(steps, 1000)
     ms_many_plain = rig.timed(n_side // MANY * MANY or MANY, many=MANY)    # the same without announcing the next call
+    # ... and with calls of exactly one launch each (what a loader that prefetches 8 or 16 mini-batches can feed)
+    per_launch = rig.buf.steps_per_launch(w.b, w.c, w.r)
+    ms_launch_calls = None
+    if per_launch > 1:
+        rig.enqueue(per_launch, many=per_launch, ahead=True)
+        ms_launch_calls = rig.timed(n_side // per_launch * per_launch, many=per_launch, ahead=True)
     ms_ahead = rig.timed(n_side, single_call=True, ahead=fused)   # one rb_update_sample per step, next labels announced
     ms_plain = rig.timed(n_side, single_call=True)                # ... not announced
     ms_two = rig.timed(n_side)
@@ -314,7 +320,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "launches_per_step": len(launch_sizes(rig, MANY)) / MANY if windowed else (1 if fused else 2),
         "steps_per_launch": max(launch_sizes(rig, MANY)) if windowed else 1,
         "steps_per_launch_schedule": launch_sizes(rig, MANY) if windowed else None,
-        "next_call_not_announced_ms_per_step": ms_many_plain,
+        "next_call_not_announced_ms_per_step": ms_many_plain, "one_launch_per_call_announced_ms_per_step": ms_launch_calls,
         "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
         "next_labels_announced": fused, "plan_ahead_kernel": None if not fused else ("rb_step_planned_kernel" if small else "rb_step_big_kernel"),
