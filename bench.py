@@ -388,8 +388,8 @@ def variants_leg(w, torch, rb, wl, steps):
         rig = Rig(w, torch, rb, wl)
         rig.buf.set_policy(sel, ev)
         rig.prefill()                       # every slot filled, so that every insertion exercises the eviction strategy
-        # plan-ahead launches: exact selection with small counts, Bernoulli selection with uniform replacement and b <= 1024
-        planned = (small and sel == 0) or (sel == 1 and ev == 0 and w.b <= 1024 and w.K <= 10240)
+        # plan-ahead launches: exact selection with small counts, Bernoulli selection with b <= 1024
+        planned = (small and sel == 0) or (sel == 1 and w.b <= 1024 and w.K <= 10240)
         per = rig.buf.steps_per_launch(w.b, w.c, w.r)            # several steps per launch (exact selection only)
         rig.enqueue(100, single_call=True, ahead=planned)
         if per > 1:

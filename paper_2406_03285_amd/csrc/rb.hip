@@ -819,10 +819,10 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
                            rb->selection == RB_SELECT_EXACT;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
-    // larger counts have a plan-ahead form of their own (default policy, storage in the sample's own type)
+    // larger counts have a plan-ahead form of their own (storage in the sample's own type)
     // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)
     const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
-                     rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) && rb->eviction == RB_EVICT_UNIFORM &&
+                     rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) &&
                      rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call

@@ -191,6 +191,10 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     const int32_t k = sel.k;
     const bool valid = k >= 0;
     const int64_t fill0 = valid ? s_fill[k] : 0;
+    // FIFO / reservoir replacement: the class's state before the step (slot of the oldest sample / samples offered so
+    // far), on its way while the class table is built; this workgroup owns that state and writes its next copy
+    const bool strategy = a.eviction != RB_EVICT_UNIFORM;
+    const int64_t aux0 = strategy && valid ? a.aux_old[k] : 0;
     // table entry of the thread's candidate: its number in Floyd's emission order, or, with the Bernoulli
     // selection, its number among the selected positions
     int ent = tid, count = a.ce;
@@ -234,10 +238,34 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
                 (int)(i + 3 < total && (int)(m3 >> 10) < x);
     }
     const int64_t at = fill0 + rank;
-    const bool over = valid && at >= S;              // beyond the capacity: overwrites a uniformly drawn slot
+    const bool over = valid && at >= S;              // beyond the capacity: overwrites a stored sample
     int64_t slot = at;
-    if (over) slot = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S);
-    const int64_t row = valid ? (int64_t)k * S + slot : -1;
+    if (over) {
+        if (a.eviction == RB_EVICT_FIFO) {
+            slot = (aux0 + at - S) % S;                                                      // the oldest one
+        } else if (a.eviction == RB_EVICT_RESERVOIR) {
+            // kept with probability S / (samples offered to the class so far + 1), then in a uniform slot
+            const int64_t offers = aux0 + rank < INT32_MAX ? aux0 + rank : INT32_MAX;
+            const int64_t draw = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)offers + 1);
+            slot = draw < S ? draw : -1;
+        } else {
+            slot = (int64_t)below(a.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S);           // a uniformly drawn one
+        }
+    }
+    const bool placed = valid && slot >= 0;          // (a reservoir may not keep a candidate)
+    const int64_t row = placed ? (int64_t)k * S + slot : -1;
+    if (strategy) {
+        // the strategy's state after the step: classes with candidates by their first arrival, the others copied
+        if (valid && arrival == 0) {
+            const int64_t f = fill0 + total;
+            int64_t next;
+            if (a.eviction == RB_EVICT_FIFO) next = (aux0 + (f > S ? f - S : 0)) % S;     // the oldest sample moves on by the overwrites
+            else next = aux0 + total < INT32_MAX ? aux0 + total : INT32_MAX;
+            a.aux_new[k] = (int32_t)next;
+        }
+        for (int q = tid; q < a.K; q += BIG_TPB)
+            if (big_find(ckey, (uint32_t)q) < 0) a.aux_new[q] = a.aux_old[q];
+    }
     uint32_t* rkey = s_v;                            // slot rows written in this step (the list starts in region V have been read)
     uint32_t* rmax = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
@@ -246,13 +274,13 @@ __device__ __forceinline__ void plan_big_update(const PlanArgs& a, uint32_t* lds
     }
     __syncthreads();
     int hr = 0;
-    if (valid) {
+    if (placed) {
         hr = big_find_or_insert(rkey, (uint32_t)row);
         atomicMax(&rmax[hr], (uint32_t)x + 1u);
     }
     __syncthreads();
     // of the candidates that go to one slot the last of the mini-batch is stored
-    const bool stored = valid && rmax[hr] == (uint32_t)x + 1u;
+    const bool stored = placed && rmax[hr] == (uint32_t)x + 1u;
     if (a.selection == RB_SELECT_BERNOULLI ? k != LAB_UNSELECTED : tid < a.ce) {
         PlanEntry e;
         e.pos = x;

@@ -238,6 +238,17 @@ def test_plan_ahead_with_the_bernoulli_selection(w, steps):
     run_many_parity(w, min(steps, 40), per_call=7, announce=True, policy=POLICIES["bernoulli-uniform"])
 
 
+@pytest.mark.parametrize("policy", ["exact-fifo", "exact-reservoir", "bernoulli-fifo", "bernoulli-reservoir"])
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C5, name="C5-K300-big-policy", K=300, S=12, shape=(256,), b=512, c=200, r=150), 40),   # classes fill up, then every strategy replaces
+    (wl.Workload("laps-big", 9, 3, 2, (8,), "f32", 600, 300, 100, 20, "normal", "uniform"), 20),          # ~100 candidates per class into 2 slots: many rounds within a step
+    (wl.variant(wl.C4, name="C4-zipf-big-policy", K=1000, S=8, shape=(3, 8, 8), b=1024, c=700, r=900), 20),
+    (wl.variant(wl.C2, name="C2-K1100-big-policy", K=1100, S=2), 60),                                     # few candidates, too many classes for the small plan
+], ids=["K300", "laps", "zipf", "K1100"])
+def test_plan_ahead_with_large_counts_and_other_policies(policy, w, steps):
+    run_ahead_parity(w, steps, policy=POLICIES[policy])
+
+
 def test_plan_ahead_with_the_bernoulli_selection_survives_broken_promises():
     run_ahead_parity(wl.variant(wl.C4, name="C4-S8-bernoulli-promises", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=3,
                      policy=POLICIES["bernoulli-uniform"])
@@ -758,7 +769,7 @@ def test_random_configurations_planned_ahead(chunk):
         options = ((rb.RB_OPT_UNROLL, int(rng.choice([0, 1, 2, 4, 8]))), (rb.RB_OPT_NONTEMPORAL, int(rng.integers(0, 2))),
                    (rb.RB_OPT_WINDOW, int(rng.choice([16, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
         print(f"  {w.name} {style} per_call={per_call} options={[v for _, v in options]}", flush=True)
-        policy = POLICIES[str(rng.choice(["exact-fifo", "exact-reservoir", "bernoulli-uniform"]))] if rng.random() < 0.5 else None
+        policy = POLICIES[str(rng.choice(sorted(POLICIES)))] if rng.random() < 0.5 else None
         if style == "ahead":
             run_ahead_parity(w, 8, policy=policy, options=options)
         elif style == "ahead-broken":
