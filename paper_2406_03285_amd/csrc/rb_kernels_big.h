@@ -26,7 +26,7 @@ constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
 // LDS words: fill counts | region U | region V | selection / sampling draws
 constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX + 4) * 4;   // (+4: the class lists are read four words at a time)
 constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
-constexpr size_t BIG_FWD_BYTES = ((size_t)2 * BIG_HASH + 4) * 4;   // the table of the slot rows a step writes, in memory, and the
+constexpr size_t BIG_FWD_BYTES = (((size_t)2 * BIG_HASH + 1) * 4 + 255) / 256 * 256;   // the table of the slot rows a step writes, in memory, and the
                                                                   // number of candidate entries of the plan
 
 __device__ __forceinline__ uint32_t big_hash(uint32_t key)
