@@ -189,11 +189,10 @@ int rb_update_sample(rb_buffer *rb, const void *batch_x, const int64_t *batch_y,
  * other call comes first, the plan is dropped and nothing is lost but the time
  * it took.  The match is by address: memory that held announced labels must
  * not be given other contents and passed as the next step's labels.  Used when the step is
- * eligible for the single launch (see rb_update_sample), and - with storage in
- * the sample's own type - also for up to 1024 candidates and representatives,
- * b <= 4096 (b <= 1024 with the Bernoulli selection) and up to 10240 classes
- * (the step is then one launch that moves rows by the plan, instead of two
- * kernels); ignored otherwise.
+ * eligible for the single launch (see rb_update_sample), and also for up to
+ * 1024 candidates and representatives, b <= 4096 (b <= 1024 with the Bernoulli
+ * selection) and up to 10240 classes (the step is then one launch that moves
+ * rows by the plan, instead of two kernels); ignored otherwise.
  * next_batch_y: device, b int64 labels that must be in place, as far as the
  * bound stream is concerned, when the announcing step is enqueued, and stay
  * unchanged until the step they belong to has run; null withdraws an

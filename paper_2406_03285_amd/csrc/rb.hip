@@ -352,27 +352,27 @@ hipError_t allow_big_lds()
     return hipSuccess;
 }
 
-template <int U, bool NT>
+template <int U, bool NT, bool BF16>
 hipError_t launch_big_u(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, dim3 grid, hipStream_t st)
 {
     const size_t lds = m.plan_next ? BIG_LDS_BYTES : 0;
     if (lds != 0) {
-        const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT>>();
+        const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT, BF16>>();
         if (e != hipSuccess) return e;
     }
-    rb_step_big_kernel<U, NT><<<grid, BIG_TPB, lds, st>>>(m, next, fwd, fwd_next);
+    rb_step_big_kernel<U, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next, fwd, fwd_next);
     return hipGetLastError();
 }
 
-template <bool NT>
+template <bool NT, bool BF16>
 hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, int unroll, dim3 grid,
                       hipStream_t st)
 {
     switch (unroll) {
-    case 1: return launch_big_u<1, NT>(m, next, fwd, fwd_next, grid, st);
-    case 2: return launch_big_u<2, NT>(m, next, fwd, fwd_next, grid, st);
-    case 4: return launch_big_u<4, NT>(m, next, fwd, fwd_next, grid, st);
-    default: return launch_big_u<8, NT>(m, next, fwd, fwd_next, grid, st);
+    case 1: return launch_big_u<1, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    case 2: return launch_big_u<2, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    case 4: return launch_big_u<4, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    default: return launch_big_u<8, NT, BF16>(m, next, fwd, fwd_next, grid, st);
     }
 }
 
@@ -422,8 +422,12 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     const uint32_t* fwd = reinterpret_cast<const uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_planned]);
     uint32_t* fwd_next = reinterpret_cast<uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_next]);
     const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + 2 * m.plan_next));
-    const hipError_t e = rb->opt_nt ? launch_big<true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
-                                    : launch_big<false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
+    const bool bf16 = rb->storage == RB_STORE_BF16;
+    hipError_t e;
+    if (rb->opt_nt) e = bf16 ? launch_big<true, true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
+                             : launch_big<true, false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
+    else e = bf16 ? launch_big<false, true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
+                  : launch_big<false, false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
     if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
@@ -819,11 +823,11 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
                            rb->selection == RB_SELECT_EXACT;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
-    // larger counts have a plan-ahead form of their own (storage in the sample's own type)
+    // larger counts have a plan-ahead form of their own
     // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)
     const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
                      rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) &&
-                     rb->storage == RB_STORE_SAME && rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
+                     rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call
     if (rb->plan_valid && !((plannable || big) && rb->plan_y == batch_y && rb->plan_b == b && rb->plan_c == c && rb->plan_r == r &&

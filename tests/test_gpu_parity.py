@@ -249,6 +249,16 @@ def test_plan_ahead_with_large_counts_and_other_policies(policy, w, steps):
     run_ahead_parity(w, steps, policy=POLICIES[policy])
 
 
+@pytest.mark.parametrize("w,steps,policy", [
+    (wl.variant(wl.C5, name="C5-K300-big-bf16", K=300, S=12, shape=(256,), b=512, c=200, r=150), 40, None),          # forwarding through the rounded row
+    (wl.variant(wl.C5, name="C5-K300-big-bf16-fifo", K=300, S=12, shape=(256,), b=512, c=200, r=150), 30, "exact-fifo"),
+    (wl.variant(wl.C3, name="C3-K1100-big-bf16", K=1100, S=2), 12, None),                                            # full-size rows, many tiles
+    (wl.variant(wl.C1, name="C1-bernoulli-big-bf16", S=3), 60, "bernoulli-uniform"),
+], ids=["K300", "K300-fifo", "C3-K1100", "bernoulli"])
+def test_plan_ahead_with_large_counts_and_bfloat16_storage(w, steps, policy):
+    run_ahead_parity(w, steps, store_bf16=True, policy=POLICIES[policy] if policy else None)
+
+
 def test_plan_ahead_with_the_bernoulli_selection_survives_broken_promises():
     run_ahead_parity(wl.variant(wl.C4, name="C4-S8-bernoulli-promises", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=3,
                      policy=POLICIES["bernoulli-uniform"])
@@ -770,16 +780,18 @@ def test_random_configurations_planned_ahead(chunk):
                    (rb.RB_OPT_WINDOW, int(rng.choice([16, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
         print(f"  {w.name} {style} per_call={per_call} options={[v for _, v in options]}", flush=True)
         policy = POLICIES[str(rng.choice(sorted(POLICIES)))] if rng.random() < 0.5 else None
+        bf16 = bool(rng.random() < 0.4 and w.dtype == "f32" and (w.row_bytes // 2) % 16 == 0)   # binary32 samples stored as bfloat16
         if style == "ahead":
-            run_ahead_parity(w, 8, policy=policy, options=options)
+            run_ahead_parity(w, 8, policy=policy, options=options, store_bf16=bf16)
         elif style == "ahead-broken":
-            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options)
+            run_ahead_parity(w, 12, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options, store_bf16=bf16)
         elif style == "many":
-            run_many_parity(w, 40, per_call=per_call, policy=policy, options=options)
+            run_many_parity(w, 40, per_call=per_call, policy=policy, options=options, store_bf16=bf16)
         elif style == "many-announced":
-            run_many_parity(w, 40, per_call=per_call, announce=True, policy=policy, options=options)
+            run_many_parity(w, 40, per_call=per_call, announce=True, policy=policy, options=options, store_bf16=bf16)
         else:
-            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options)
+            run_many_parity(w, 40, per_call=per_call, announce=True, schedule_seed=int(rng.integers(1, 1000)), policy=policy, options=options,
+                            store_bf16=bf16)
 
 
 # ------------------------------------------------------------- edge cases ---
