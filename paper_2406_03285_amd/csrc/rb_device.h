@@ -91,6 +91,14 @@ __device__ __forceinline__ int lane_read(int v, int src)
     return __builtin_amdgcn_readlane(v, src);
 }
 
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load
+// and store the wavefront has in flight; the planners keep loads on their way in and table entries
+// and fill counts on their way out across these barriers (nobody in the same launch reads them).
+__device__ __forceinline__ void lds_barrier()
+{
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+}
+
 // ---------------------------------------------------------------------------
 // Workgroup-wide exclusive prefix sum of one int per thread.  s_wave: NWAVE
 // ints of LDS.  Must be called by all threads of the workgroup.

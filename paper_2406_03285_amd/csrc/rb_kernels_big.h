@@ -361,7 +361,7 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
     const int lane = tid & (WAVE - 1), wave = tid / WAVE;
     const int inc = wave_scan_incl(local);
     if (lane == WAVE - 1) s_wave[wave] = inc;
-    __syncthreads();                                 // also ends the reads of s_fill above
+    lds_barrier();                                   // also ends the reads of s_fill above; the fill counts stay on their way out
     int wpre[BIG_NWAVE];                             // stored samples before the classes of wavefront i
     int F = 0;
 #pragma unroll
@@ -378,7 +378,7 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
         before += nf[u];
     }
     for (int i = BIG_CLASSES + tid; i < BIG_FILL; i += BIG_TPB) s_fill[i] = F;
-    __syncthreads();
+    lds_barrier();
     if (tid < a.nchunks) {
         // stored samples per chunk of CH classes
         const int lo = tid * CH, hi = lo + CH;
@@ -395,9 +395,9 @@ __device__ __forceinline__ void plan_big_sample(const PlanArgs& a, uint32_t* lds
         hd = big_find_or_insert(dkey, g0);
         atomicMin(&dfirst[hd], (uint32_t)tid);
     }
-    __syncthreads();
+    lds_barrier();
     if (drawing) s_draw[tid] = g0 | ((dfirst[hd] != (uint32_t)tid) ? 0x80000000u : 0u);
-    __syncthreads();
+    lds_barrier();
     int32_t pk = -1;
     int64_t prow = -1;
     int32_t pos = -1;

@@ -74,14 +74,6 @@ struct WinMoveArgs {
     int32_t tpr, tile_vec, tile_rem;
 };
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every global load
-// and store the wavefront has in flight; the planner keeps the next step's labels on their way and
-// its table entries on their way out across its barriers (nobody in this launch reads them).
-__device__ __forceinline__ void lds_barrier()
-{
-    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
-}
-
 // block_scan_excl of rb_device.h with that barrier.
 __device__ __forceinline__ int block_scan_excl_lds(int v, int& total, int* s_wave)
 {
