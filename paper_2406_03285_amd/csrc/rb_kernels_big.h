@@ -1,5 +1,6 @@
 // Plan-ahead kernels for the single-launch step with up to 1024 candidates and representatives and up
-// to 10240 classes (default policy): as in rb_kernels_planned.h the plan of a step is worked out by
+// to 10240 classes (any replacement strategy, either storage form; exact selection, or the Bernoulli
+// selection for mini-batches of at most 1024 samples): as in rb_kernels_planned.h the plan of a step is worked out by
 // extra workgroups of the previous step's launch and left in a table, and the step's own launch only
 // moves rows by that table - but the planning workgroups (two: update, sampling) have 1024 threads
 // (one per candidate, resp. representative) and find class-mates, shared slots and repeated draws
@@ -24,10 +25,10 @@ constexpr uint32_t BIG_EMPTY = 0xFFFFFFFFu;   // free slot (no class, row or dra
 constexpr int BIG_GROUP = TPB;                // threads that move one tile together
 constexpr int BIG_GROUPS = BIG_TPB / BIG_GROUP;
 // LDS words: fill counts | region U | region V | selection / sampling draws
-constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX + 4) * 4;   // (+4: the class lists are read four words at a time)
+constexpr size_t BIG_LDS_BYTES = (size_t)(BIG_FILL + 2 * BIG_HASH + 2 * BIG_HASH + BIG_MAX + 4) * 4;
 constexpr size_t BIG_TABLE_BYTES = (sizeof(PlanHeader) + 2 * BIG_MAX * sizeof(PlanEntry) + 255) / 256 * 256;
-constexpr size_t BIG_FWD_BYTES = (((size_t)2 * BIG_HASH + 1) * 4 + 255) / 256 * 256;   // the table of the slot rows a step writes, in memory, and the
-                                                                  // number of candidate entries of the plan
+// in memory: the table of the slot rows a step writes, and the number of candidate entries of its plan
+constexpr size_t BIG_FWD_BYTES = (((size_t)2 * BIG_HASH + 1) * 4 + 255) / 256 * 256;
 
 __device__ __forceinline__ uint32_t big_hash(uint32_t key)
 {
@@ -117,8 +118,9 @@ __device__ __forceinline__ int big_scan_excl(int v, int& total, int* s_wave)
 //             the sample by binary search of the prefix sums.  A representative of
 //             a class that gets candidates in this step is marked "look it up".
 //
-// LDS (dynamic, BIG_LDS_BYTES): s_fill[BIG_FILL] (sampling only), regions U and V
-// of 2 * BIG_HASH words each, s_draw[BIG_MAX].
+// LDS (dynamic, BIG_LDS_BYTES): s_fill[BIG_FILL], regions U and V of 2 * BIG_HASH
+// words each, s_draw[BIG_MAX] (+4 words: the class lists, kept there, are read
+// four members at a time).
 // ---------------------------------------------------------------------------
 struct BigSelected {
     int x;           // mini-batch position of the thread's candidate
