@@ -430,6 +430,8 @@ def main():
 
     import torch
     import rb_workloads as wl
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # compiles only when no library has been built yet
     import paper_2406_03285_amd as rb
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; there is no CPU path")

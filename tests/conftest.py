@@ -12,6 +12,8 @@ if HERE not in sys.path:
 
 
 def pytest_configure(config):
+    import __graft_entry__
+    __graft_entry__.ensure_built()          # compiles only when no library has been built yet
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 
 
