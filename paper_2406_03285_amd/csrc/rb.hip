@@ -499,9 +499,10 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
     // compute unit, tiles of four vectors per thread measured best (1000 classes of 3x224x224 bfloat16 samples,
     // 64 candidates and representatives: 13.1 us per step against 14.1 with two and 14.2 with eight; binary32
-    // samples, 8 and 8: 3.9 against 4.1 and 4.1).
+    // samples, 8 and 8: 3.9 against 4.1 and 4.1).  With binary32 samples stored as bfloat16 a thread holds twice as
+    // many half vectors, and two per thread measured best (8 and 8: 2.6 us against 2.7).
     const int unroll_option = rb->opt_unroll;
-    if (unroll_option == 0) rb->opt_unroll = 4;
+    if (unroll_option == 0) rb->opt_unroll = rb->storage == RB_STORE_BF16 ? 2 : 4;
     const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
     rb->opt_unroll = unroll_option;
     // Window sizes.  A launch of w steps should not have to wait for the plan of the next window, which the one

@@ -25,6 +25,7 @@ constexpr int32_t LAB_UNSELECTED = -2; // LDS label table: position is not a can
 constexpr int32_t LAB_INVALID = -1;    // candidate whose label is outside [0, K)
 
 typedef uint32_t vec16 __attribute__((ext_vector_type(4)));   // one 16-byte transfer
+typedef uint32_t vec8 __attribute__((ext_vector_type(2)));    // half of one: four bfloat16
 
 // Device-resident state words at the start of the workspace.
 struct DevState {
@@ -131,22 +132,19 @@ __device__ __forceinline__ uint32_t bf16_of(uint32_t u)
     return (u & 0x7FFFFFFFu) > 0x7F800000u ? ((u >> 16) | 0x0040u) : rounded;
 }
 
-// Eight consecutive binary32 elements (two vectors) -> eight bfloat16 (one vector), element order kept.
-__device__ __forceinline__ vec16 narrow8(const vec16 a, const vec16 b)
+// Four consecutive binary32 elements (one vector) -> four bfloat16 (half a vector), element order kept; and back: exact
+__device__ __forceinline__ vec8 narrow4(const vec16 a)
 {
-    vec16 o;
+    vec8 o;
     o.x = bf16_of(a.x) | (bf16_of(a.y) << 16);
     o.y = bf16_of(a.z) | (bf16_of(a.w) << 16);
-    o.z = bf16_of(b.x) | (bf16_of(b.y) << 16);
-    o.w = bf16_of(b.z) | (bf16_of(b.w) << 16);
     return o;
 }
-
-// and back: exact
-__device__ __forceinline__ void widen8(const vec16 s, vec16& a, vec16& b)
+__device__ __forceinline__ vec16 widen4(const vec8 s)
 {
+    vec16 a;
     a.x = s.x << 16; a.y = s.x & 0xFFFF0000u; a.z = s.y << 16; a.w = s.y & 0xFFFF0000u;
-    b.x = s.z << 16; b.y = s.z & 0xFFFF0000u; b.z = s.w << 16; b.w = s.w & 0xFFFF0000u;
+    return a;
 }
 
 enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3 };   // bit 0: convert while loading, bit 1: while storing
@@ -161,7 +159,11 @@ enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3 };   // bit 0: conv
 // vectors of the narrow (stored) row.
 template <int U, bool NT, int W = TPB, bool PACED = true, int CV = CV_NONE>
 struct Tile {
-    vec16 v[U];
+    // Without conversion a lane holds U vectors.  With one, it holds 2 U half vectors (four bfloat16 each):
+    // a lane then touches 8 bytes of the narrow row and 16 bytes of the binary32 row per access, so every
+    // instruction of a wavefront covers one contiguous run of bytes on either side.
+    vec16 v[CV ? 1 : U];
+    vec8 h[CV ? 2 * U : 1];
 
     // Requires lo < hi.  No lane is ever masked off: a lane whose index falls past the end of
     // the tile moves the tile's last vector again (same source, same destination, same bytes as
@@ -170,17 +172,25 @@ struct Tile {
     // to drain these - and keeps the compiler from moving loads down into a guarded store.
     __device__ __forceinline__ void load(const vec16* __restrict__ src, int64_t lo, int64_t hi)
     {
+        if (CV) {
+#pragma unroll
+            for (int u = 0; u < 2 * U; ++u) {
+                int64_t j = 2 * lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+                j = j < 2 * hi ? j : 2 * hi - 1;
+                if (CV & CV_NARROW) {
+                    h[u] = narrow4(NT ? __builtin_nontemporal_load(src + j) : src[j]);
+                } else {
+                    const vec8* half = reinterpret_cast<const vec8*>(src);
+                    h[u] = NT ? __builtin_nontemporal_load(half + j) : half[j];
+                }
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            if (CV & CV_NARROW) {
-                const vec16 a = NT ? __builtin_nontemporal_load(src + 2 * i) : src[2 * i];
-                const vec16 b = NT ? __builtin_nontemporal_load(src + 2 * i + 1) : src[2 * i + 1];
-                v[u] = narrow8(a, b);
-            } else {
-                v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
-            }
+            v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
         }
     }
     // All loads are waited for first and every store is waited for before the next one is
@@ -190,25 +200,30 @@ struct Tile {
     __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
     {
         if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (CV) {
+#pragma unroll
+            for (int u = 0; u < 2 * U; ++u) {
+                int64_t j = 2 * lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+                j = j < 2 * hi ? j : 2 * hi - 1;
+                if (CV & CV_WIDEN) {
+                    const vec16 a = widen4(h[u]);
+                    if (NT) __builtin_nontemporal_store(a, dst + j);
+                    else dst[j] = a;
+                } else {
+                    vec8* half = reinterpret_cast<vec8*>(dst);
+                    if (NT) __builtin_nontemporal_store(h[u], half + j);
+                    else half[j] = h[u];
+                }
+                if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            return;
+        }
 #pragma unroll
         for (int u = 0; u < U; ++u) {
             int64_t i = lo + (int64_t)u * W + (threadIdx.x & (W - 1));
             i = i < hi ? i : hi - 1;
-            if (CV & CV_WIDEN) {
-                vec16 a, b;
-                widen8(v[u], a, b);
-                if (NT) {
-                    __builtin_nontemporal_store(a, dst + 2 * i);
-                    __builtin_nontemporal_store(b, dst + 2 * i + 1);
-                } else {
-                    dst[2 * i] = a;
-                    dst[2 * i + 1] = b;
-                }
-            } else if (NT) {
-                __builtin_nontemporal_store(v[u], dst + i);
-            } else {
-                dst[i] = v[u];
-            }
+            if (NT) __builtin_nontemporal_store(v[u], dst + i);
+            else dst[i] = v[u];
             if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
