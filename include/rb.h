@@ -95,7 +95,8 @@ int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *h
  * keep the full row size; buf_x rows shrink to half: call this BEFORE
  * rb_query_sizes / rb_bind (RB_ESTATE once bound).  The sample's byte size
  * must be a multiple of 32.  Served by the general kernels (two launches per
- * step) and by the plan-ahead form of the single launch (rb_announce_next).
+ * step), by the plan-ahead forms of the single launch (rb_announce_next) and
+ * by the several-steps launch (rb_update_sample_many).
  */
 enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1 };
 int rb_set_storage(rb_buffer *rb, int32_t storage);
@@ -113,10 +114,12 @@ int rb_set_storage(rb_buffer *rb, int32_t storage);
  * offered to a full class replaces a uniformly drawn slot with probability
  * slots_per_class / n and is dropped otherwise (exact while a class has been
  * offered fewer than 2^31 - 1 samples).
- * With a variant selected the general kernels are used and rb_update_sample
- * enqueues two launches; the plan-ahead form of the single launch
- * (rb_announce_next) also serves FIFO and reservoir with the exact selection.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update
- * was already enqueued since the last rb_bind.
+ * With a variant selected a plain rb_update_sample enqueues the two general
+ * kernels.  The plan-ahead forms of the single launch (rb_announce_next) serve
+ * every variant (the Bernoulli selection for b <= 1024), and the several-steps
+ * launch (rb_update_sample_many) serves FIFO and reservoir with the exact
+ * selection.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update was already
+ * enqueued since the last rb_bind.
  */
 enum rb_selection { RB_SELECT_EXACT = 0, RB_SELECT_BERNOULLI = 1 };
 enum rb_eviction { RB_EVICT_UNIFORM = 0, RB_EVICT_FIFO = 1, RB_EVICT_RESERVOIR = 2 };
