@@ -372,8 +372,49 @@ hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* f
     case 1: return launch_big_u<1, NT, BF16>(m, next, fwd, fwd_next, grid, st);
     case 2: return launch_big_u<2, NT, BF16>(m, next, fwd, fwd_next, grid, st);
     case 4: return launch_big_u<4, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    default: return launch_big_u<8, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    case 6: return launch_big_u<6, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    case 8: return launch_big_u<8, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    default: break;
     }
+    if constexpr (!BF16) {          // (the converting mover would not fit the registers of a 1024-thread workgroup)
+        if (unroll == 10) return launch_big_u<10, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+        if (unroll == 12) return launch_big_u<12, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+    }
+    return hipErrorInvalidValue;
+}
+
+// Tiles of the large-count launch.  Its workgroups hold four groups of movers each, and a compute unit has room for
+// at most two of them (the planners' LDS); a launch whose workgroups do not spread evenly over the 256 compute
+// units runs at the pace of the fullest ones (measured on MI355X with a bare mover, 129 rows of 301 056 bytes: 323
+// workgroups of four 32 KiB tiles 18.9 us, 226 workgroups of four 42 KiB tiles 14.9 us, 258 workgroups 20.1 us;
+// 256 rows: 640 workgroups 33.6 us, 448 workgroups 31.4 us; the whole step gains less: 65 candidates and 64
+// representatives 17.3 -> 16.5 us, 128 and 128 33.0 -> 32.0 us).  So, when the rows are long enough (tiles of
+// 12 KiB and more), a row gets as many tiles as keep the whole launch, planners included, within one workgroup
+// per compute unit, or else within two.
+Shape big_shape(const rb_buffer* rb, int64_t rows, int planners)
+{
+    Shape s = plan_shape(rb, rows, BIG_GROUP);
+    if (rb->opt_unroll != 0) return s;
+    constexpr int64_t CUS = 256;
+    const int64_t nunits = (rb->row_vec + TILE_UNIT - 1) / TILE_UNIT;
+    for (int64_t k = 1; k <= 2; ++k) {
+        int64_t tpr = (CUS * k - planners) * BIG_GROUPS / rows;
+        if (tpr > nunits) tpr = nunits;
+        if (tpr < 1) continue;
+        const int64_t tile = (nunits / tpr + (nunits % tpr ? 1 : 0)) * TILE_UNIT;      // vectors of the longest tile
+        int u = (int)((tile + BIG_GROUP - 1) / BIG_GROUP);
+        if (u > (rb->storage == RB_STORE_BF16 ? 8 : 12)) continue;
+        if (u < 4) break;                                                                 // short rows: the plain split
+        u = (u + 1) / 2 * 2;                                                              // 4, 6, 8, 10 or 12
+        s.unroll = u;
+        s.tpr = (int)tpr;
+        s.tile_vec = (int)(nunits / tpr);
+        s.tile_rem = (int)(nunits % tpr);
+        s.rpb = 1;
+        s.groups = rows;
+        return s;
+    }
+    return s;
 }
 
 // One step of the plan-ahead form for large counts (up to BIG_MAX candidates and representatives, up to
@@ -391,7 +432,14 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         plan_enqueued(rb, batch_y, b, c, r, seed, step);
     }
-    const Shape sh = plan_shape(rb, c + r, BIG_GROUP);
+    // candidate entries of the table, and how many of them the grid covers: all c, or, with the Bernoulli selection
+    // (about c of the b positions are selected), c and eight standard deviations (more are served by going round)
+    const bool bernoulli = rb->selection == RB_SELECT_BERNOULLI;
+    const int64_t ce = bernoulli ? b : c;
+    int64_t margin = 16;
+    while (margin * margin < 64 * c) ++margin;
+    const int64_t cgrid = bernoulli ? std::min(b, c + margin) : c;
+    const Shape sh = big_shape(rb, cgrid + r, next_y ? 2 : 0);
     MoveArgs m;
     m.batch_x = static_cast<const vec16*>(batch_x);
     m.buf_x = static_cast<vec16*>(rb->buf_x);
@@ -400,13 +448,6 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     m.out_y = out_y;
     m.table = rb->ws + rb->off_wtbl[rb->tbl_planned];
     m.state = reinterpret_cast<DevState*>(rb->ws);
-    // candidate entries of the table, and how many of them the grid covers: all c, or, with the Bernoulli selection
-    // (about c of the b positions are selected), c and eight standard deviations (more are served by going round)
-    const bool bernoulli = rb->selection == RB_SELECT_BERNOULLI;
-    const int64_t ce = bernoulli ? b : c;
-    int64_t margin = 16;
-    while (margin * margin < 64 * c) ++margin;
-    const int64_t cgrid = bernoulli ? std::min(b, c + margin) : c;
     m.c = (int32_t)ce; m.r = (int32_t)r; m.cgrid = (int32_t)cgrid;
     m.S = rb->S;
     m.row_vec = rb->row_vec;
@@ -496,7 +537,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
 {
     static_assert(WIN_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
     const int64_t wmax = window_limit(rb, b, c, r);
-    // With thousands of workgroups per launch, and the planner's LDS leaving room for five workgroups per
+    // With thousands of workgroups per launch, and the planner's LDS leaving room for four workgroups per
     // compute unit, tiles of four vectors per thread measured best (1000 classes of 3x224x224 bfloat16 samples,
     // 64 candidates and representatives: 13.1 us per step against 14.1 with two and 14.2 with eight; binary32
     // samples, 8 and 8: 3.9 against 4.1 and 4.1).  With binary32 samples stored as bfloat16 a thread holds twice as

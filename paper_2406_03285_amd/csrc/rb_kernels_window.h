@@ -499,7 +499,7 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 // ---------------------------------------------------------------------------
 // All steps of one window by its table: workgroup (step, entry, tile) moves one
 // tile of one row; if there is a next window, workgroup 0 plans it instead.  (The
-// planner's LDS limits every compute unit to five workgroups of this kernel.  Measured alternatives: the planner as a launch of its own on a second
+// planner's LDS limits every compute unit to four workgroups of this kernel; five measured no better.  Measured alternatives: the planner as a launch of its own on a second
 // stream frees the movers but the events that order the two streams cost more than
 // that gains.)
 // ---------------------------------------------------------------------------

@@ -259,6 +259,28 @@ def test_plan_ahead_with_large_counts_and_bfloat16_storage(w, steps, policy):
     run_ahead_parity(w, steps, store_bf16=True, policy=POLICIES[policy] if policy else None)
 
 
+def _long(name, vecs, b, c, r, K=12, S=3, dtype="f32"):
+    """A few classes of a few slots with rows of `vecs` 16-byte vectors: every step replaces and collides."""
+    return wl.Workload(name, 9, K, S, (vecs * (4 if dtype == "f32" else 8),), dtype, b, c, r, 8, "normal", "uniform")
+
+
+@pytest.mark.parametrize("w,bf16,policy", [
+    (_long("long-u12", 18816, 512, 65, 64), False, None),            # 129 rows in 7 tiles of up to 2688 vectors: one workgroup per compute unit
+    (_long("long-u8", 9000, 300, 100, 100), False, None),            # 5 tiles of 1856
+    (_long("long-u6-ragged", 5003, 400, 150, 100), False, None),     # row length not a multiple of the tile unit
+    (_long("long-u10", 12001, 200, 80, 90), False, "exact-fifo"),
+    (_long("long-two-per-cu", 6000, 700, 300, 300), False, None),    # too many rows for one workgroup per compute unit: two
+    (_long("long-bf16", 18816, 512, 65, 64), True, None),            # stored rows of 9408 vectors, converting mover
+    (_long("long-bf16-wide", 37632, 128, 65, 64, K=6, S=2), True, "exact-reservoir"),
+    (_long("long-bernoulli", 18816, 512, 64, 64, dtype="bf16"), False, "bernoulli-uniform"),   # the grid covers 128 candidate entries
+], ids=lambda v: v.name if hasattr(v, "name") else None)
+def test_plan_ahead_with_large_counts_and_long_rows(w, bf16, policy):
+    """The large-count launch cuts long rows so that its workgroups spread evenly over the compute units."""
+    pol = POLICIES[policy] if policy else None
+    run_ahead_parity(w, 8, policy=pol, store_bf16=bf16)
+    run_many_parity(w, 12, per_call=5, announce=True, policy=pol, store_bf16=bf16)
+
+
 def test_plan_ahead_with_the_bernoulli_selection_survives_broken_promises():
     run_ahead_parity(wl.variant(wl.C4, name="C4-S8-bernoulli-promises", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 90, schedule_seed=3,
                      policy=POLICIES["bernoulli-uniform"])
