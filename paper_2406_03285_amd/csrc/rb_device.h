@@ -157,7 +157,7 @@ enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3 };   // bit 0: conv
 // the destination row is binary32, converted from the tile's bfloat16 while it is stored; CV_BOTH -
 // binary32 to binary32 through the bfloat16 a stored copy would hold.  Tile indices always count
 // vectors of the narrow (stored) row.
-template <int U, bool NT, int W = TPB, bool PACED = true, int CV = CV_NONE>
+template <int U, bool NT, int W = TPB, int PACED = 1, int CV = CV_NONE>
 struct Tile {
     // Without conversion a lane holds U vectors.  With one, it holds 2 U half vectors (four bfloat16 each):
     // a lane then touches 8 bytes of the narrow row and 16 bytes of the binary32 row per access, so every
@@ -193,10 +193,14 @@ struct Tile {
             v[u] = NT ? __builtin_nontemporal_load(src + i) : src[i];
         }
     }
-    // All loads are waited for first and every store is waited for before the next one is
-    // issued.  Measured on MI355X with a bare mover of the same shape (64 rows of 301 056 bytes,
+    // PACED = 1: all loads are waited for first and every store is waited for before the next one
+    // is issued.  Measured on MI355X with a bare mover of the same shape (64 rows of 301 056 bytes,
     // U = 4): 7.6 us against 8.6 us when each store is issued as soon as its load has arrived
-    // and 8.9 us with the guarded form; the memory system does better with few writes in flight.
+    // and 8.9 us with the guarded form; a launch of about one workgroup wave does better with few
+    // writes in flight.  PACED = n > 1: a wait after every n-th store; n > U: the stores go out in
+    // one burst once the loads have arrived, which is what launches of many workgroup waves do
+    // best with (1024 rows of 301 056 bytes in 19 456 tiles: 105.6 us against 107.1 us paced;
+    // 256 rows of 602 112 bytes: 52.1 against 54.1).  PACED = 0: no waits of its own.
     __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
     {
         if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
@@ -214,7 +218,7 @@ struct Tile {
                     if (NT) __builtin_nontemporal_store(h[u], half + j);
                     else half[j] = h[u];
                 }
-                if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                if (PACED && (u + 1) % PACED == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             }
             return;
         }
@@ -224,7 +228,7 @@ struct Tile {
             i = i < hi ? i : hi - 1;
             if (NT) __builtin_nontemporal_store(v[u], dst + i);
             else dst[i] = v[u];
-            if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            if (PACED && (u + 1) % PACED == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         }
     }
 };

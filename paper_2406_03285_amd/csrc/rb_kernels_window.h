@@ -13,6 +13,7 @@ namespace {
 constexpr int WIN_MAX = 16;                   // most steps one launch covers ...
 constexpr int WIN_ENTRIES = 1024;             // ... as long as steps * (c + r) table entries do not exceed this
 constexpr int WIN_SLOTS = 512;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
+constexpr int WIN_PACE = 64;                  // stores of a tile go out in one burst once its loads have arrived (no wait between them)
 constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_ENTRIES keys)
 constexpr uint32_t WIN_NONE = 0xFFFFu;        // "no entry" in the 16-bit links below
 constexpr uint32_t WIN_EMPTY = 0xFFFFFFFFu;   // free slot of the row table (no buffer row has this index)
@@ -549,7 +550,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
             const WinEntry rq = entry[q];
             const int qs = q / rows, qj = q % rows - m.c;
             if (first) m.out_y[qs][qj] = rq.label;
-            Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> old;
+            Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> old;
             old.load(slot, v_lo, v_hi);
             old.store(m.out_x[qs] + (int64_t)qj * m.row_vec * WIDE, v_lo, v_hi);
             q = rq.chain;
@@ -558,7 +559,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         // wavefront and overwritten by another: everybody has read before anybody overwrites.
         if (en.chain >= 0) __syncthreads();
         if (first) m.buf_y[en.row] = en.label;
-        Tile<U, NT, TPB, true, BF16 ? CV_NARROW : CV_NONE> t;
+        Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
         t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE, v_lo, v_hi);
         t.store(slot, v_lo, v_hi);
         return;
@@ -570,13 +571,13 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
     vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
     if (BF16 && en.src >= 0) {
         // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
-        Tile<U, NT, TPB, true, CV_BOTH> t;
+        Tile<U, NT, TPB, WIN_PACE, CV_BOTH> t;
         t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
                                        : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }
