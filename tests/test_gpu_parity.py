@@ -816,6 +816,49 @@ def test_random_configurations_planned_ahead(chunk):
                             store_bf16=bf16)
 
 
+# ------------------------------------------- two buffers at the same time ---
+
+def test_two_buffers_on_two_streams_do_not_disturb_each_other():
+    """Two handles of different shape, each on a stream of its own, enqueued alternately with no host
+    synchronisation until the end: every handle has its own workspace and plans, the library keeps no
+    state outside them."""
+    rb = _rb()
+    from oracle import rbo
+    from parity_util import _bytes, compare_buffers
+    dev = torch.device("cuda:0")
+    wa = wl.variant(wl.C3, name="two-a", K=40, S=3, shape=(3, 32, 32))                               # several steps per launch
+    wb = wl.variant(wl.C5, name="two-b", K=300, S=4, shape=(256,), b=512, c=200, r=150)              # large-count launches
+    sides = []
+    for w in (wa, wb):
+        st = torch.cuda.Stream(dev)
+        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=st)
+        steps, per_call = 36, 12
+        batches = [wl.make_batch(w, t, dev) for t in range(steps)]
+        xs, ys = [x.contiguous() for x, _ in batches], [y.contiguous() for _, y in batches]
+        oxs = [torch.full((w.r, *w.shape), 3, dtype=w.torch_dtype, device=dev) for _ in range(steps)]
+        oys = [torch.full((w.r,), -7, dtype=torch.int64, device=dev) for _ in range(steps)]
+        sides.append((w, st, buf, xs, ys, oxs, oys, steps, per_call))
+    torch.cuda.synchronize()
+    for first in range(0, 36, 12):
+        for w, st, buf, xs, ys, oxs, oys, steps, per_call in sides:
+            nxt = ys[first + per_call:first + 2 * per_call]
+            if nxt:
+                buf.announce_next_many(nxt)
+            buf.update_sample_many(xs[first:first + per_call], ys[first:first + per_call], w.c, w.r, w.lib_seed, first,
+                                   oxs[first:first + per_call], oys[first:first + per_call])
+    torch.cuda.synchronize()
+    for w, st, buf, xs, ys, oxs, oys, steps, per_call in sides:
+        orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+        for t in range(steps):
+            orc.update(_bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), w.c, w.lib_seed, t)
+            ref = _bytes(torch.full((w.r, *w.shape), 3, dtype=w.torch_dtype)).numpy().copy()
+            n, ref_x, ref_y = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
+            assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"{w.name} step {t}: out_y differs"
+            assert np.array_equal(_bytes(oxs[t]).cpu().numpy(), ref_x), f"{w.name} step {t}: out_x differs (n={n})"
+        compare_buffers(buf, orc, f"{w.name} final")
+        buf.close()
+
+
 # ------------------------------------------------------------- edge cases ---
 
 @pytest.mark.parametrize("K,S,shape,dtype,b,c,r", [
