@@ -383,14 +383,18 @@ hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* f
     return hipErrorInvalidValue;
 }
 
-// Tiles of the large-count launch.  Its workgroups hold four groups of movers each, and a compute unit has room for
-// at most two of them (the planners' LDS); a launch whose workgroups do not spread evenly over the 256 compute
-// units runs at the pace of the fullest ones (measured on MI355X with a bare mover, 129 rows of 301 056 bytes: 323
-// workgroups of four 32 KiB tiles 18.9 us, 226 workgroups of four 42 KiB tiles 14.9 us, 258 workgroups 20.1 us;
-// 256 rows: 640 workgroups 33.6 us, 448 workgroups 31.4 us; the whole step gains less: 65 candidates and 64
-// representatives 17.3 -> 16.5 us, 128 and 128 33.0 -> 32.0 us).  So, when the rows are long enough (tiles of
-// 12 KiB and more), a row gets as many tiles as keep the whole launch, planners included, within one workgroup
-// per compute unit, or else within two.
+// Tiles of the large-count launch.  Its workgroups hold four groups of movers each, and a compute unit holds one such
+// workgroup at a time (traced: of 325 workgroups the last 69 start when the first ones end), so a launch of a few
+// hundred workgroups runs in rounds of 256, and a round that is nearly empty costs as much as a full one (measured
+// on MI355X with a bare mover, 129 rows of 301 056 bytes: 323 workgroups of four 32 KiB tiles 18.9 us, 226
+// workgroups of four 42 KiB tiles 14.9 us, 258 workgroups 20.1 us; 256 rows: 640 workgroups 33.6 us, 448
+// workgroups 31.4 us; the whole step gains less: 65 candidates and 64 representatives 17.3 -> 16.5 us, 128 and 128
+// 33.0 -> 32.0 us).  So, when the rows are long enough (tiles of 12 KiB and more), a row gets as many tiles as keep
+// the whole launch, planners included, within one round, or else within two.  Measured and not adopted: at most
+// one mover workgroup per compute unit whose groups go round the tiles themselves (5 to 10 % slower than letting
+// the second round of workgroups start as the first ones end); for many short rows a wavefront per row, sixteen
+// rows per workgroup, so that one round suffices (10000 classes, 1024 + 1024 rows of 8 KiB: no change, the step is
+// bound by the planners and the launch itself).
 Shape big_shape(const rb_buffer* rb, int64_t rows, int planners)
 {
     Shape s = plan_shape(rb, rows, BIG_GROUP);
