@@ -160,13 +160,14 @@ class Rig:
 
 
 def copy_ceiling(torch, rb, nbytes=1 << 30, reps=20):
-    """GB/s (read + write) of a plain large device copy with the mover's inner loop."""
+    """GB/s (read + write) of a plain large device copy with the mover's inner loop: the best of 1 to 8 vectors per
+    thread, plain / streaming with paced stores / streaming with burst stores."""
     src = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
     dst = torch.empty(nbytes, dtype=torch.uint8, device="cuda:0")
     src.fill_(1)
     best = 0.0
-    for unroll in (2, 4, 8):
-        for nt in (0, 1):
+    for unroll in (1, 2, 4, 8):
+        for nt in (0, 1, 2):
             for _ in range(3):
                 rb.rb_copy_bytes(None, dst, src, nbytes, unroll, nt)
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

@@ -340,6 +340,10 @@ int rb_standin_compute(void *hip_stream, float *sink, int64_t blocks, int64_t it
  * Plain contiguous device-to-device copy of `bytes` (multiple of 16, both
  * pointers 16-byte aligned) with the same per-thread inner loop the row mover
  * uses: the practical ceiling of that loop, and an HBM-bound stand-in load.
+ * unroll: 1, 2, 4 or 8 vectors per thread.  nontemporal: 0 - plain loads and
+ * stores; 1 - streaming ones, every store waited for before the next (the
+ * one-step kernels' form); 2 - streaming ones, the stores of a tile in one
+ * burst (the several-steps kernel's form).
  */
 int rb_copy_bytes(void *hip_stream, void *dst, const void *src, size_t bytes, int32_t unroll, int32_t nontemporal);
 

@@ -204,16 +204,16 @@ hipError_t launch_step(const StepArgs& a, int unroll, dim3 grid, size_t lds, hip
     return hipGetLastError();
 }
 
-template <bool NT>
+template <bool NT, int PACE>
 hipError_t launch_copy(vec16* dst, const vec16* src, int64_t nvec, int unroll, hipStream_t st)
 {
     const int64_t cap = (int64_t)TPB * unroll;
     dim3 grid((unsigned)((nvec + cap - 1) / cap));
     switch (unroll) {
-    case 1: rb_copy_kernel<1, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
-    case 2: rb_copy_kernel<2, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
-    case 4: rb_copy_kernel<4, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
-    default: rb_copy_kernel<8, NT><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    case 1: rb_copy_kernel<1, NT, PACE><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    case 2: rb_copy_kernel<2, NT, PACE><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    case 4: rb_copy_kernel<4, NT, PACE><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
+    default: rb_copy_kernel<8, NT, PACE><<<grid, TPB, 0, st>>>(dst, src, nvec); break;
     }
     return hipGetLastError();
 }
@@ -1128,8 +1128,11 @@ int rb_copy_bytes(void* hip_stream, void* dst, const void* src, size_t bytes, in
     const int64_t nvec = (int64_t)(bytes / 16);
     if ((nvec + (int64_t)TPB * unroll - 1) / ((int64_t)TPB * unroll) > 0x7FFFFFFF) return RB_EINVAL;
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
-    hipError_t e = nontemporal ? launch_copy<true>(static_cast<vec16*>(dst), static_cast<const vec16*>(src), nvec, unroll, st)
-                               : launch_copy<false>(static_cast<vec16*>(dst), static_cast<const vec16*>(src), nvec, unroll, st);
+    vec16* d = static_cast<vec16*>(dst);
+    const vec16* s = static_cast<const vec16*>(src);
+    hipError_t e = nontemporal == 2 ? launch_copy<true, 64>(d, s, nvec, unroll, st)
+                 : nontemporal      ? launch_copy<true, 1>(d, s, nvec, unroll, st)
+                                    : launch_copy<false, 1>(d, s, nvec, unroll, st);
     return e == hipSuccess ? RB_OK : RB_EHIP;
 }
 

@@ -20,12 +20,12 @@ __global__ void __launch_bounds__(TPB) rb_standin_kernel(float* __restrict__ sin
     sink[(int64_t)blockIdx.x * TPB + threadIdx.x] = x0 + x1 + x2 + x3;
 }
 
-template <int U, bool NT>
+template <int U, bool NT, int PACE>       // PACE: 1 - every store waited for; 64 - the stores of a tile in one burst
 __global__ void __launch_bounds__(TPB) rb_copy_kernel(vec16* __restrict__ dst, const vec16* __restrict__ src, int64_t nvec)
 {
     const int64_t lo = (int64_t)blockIdx.x * (TPB * U);
     const int64_t hi = lo + TPB * U < nvec ? lo + TPB * U : nvec;
-    Tile<U, NT> t;
+    Tile<U, NT, TPB, PACE> t;
     t.load(src, lo, hi);
     t.store(dst, lo, hi);
 }

@@ -948,7 +948,7 @@ def test_copy_helper_moves_bytes():
     rb = _rb()
     src = torch.randint(0, 255, (3_000_016,), dtype=torch.uint8, device="cuda:0")
     for unroll in (1, 2, 4, 8):
-        for nt in (0, 1):
+        for nt in (0, 1, 2):
             dst = torch.zeros_like(src)
             assert rb.rb_copy_bytes(None, dst, src, src.numel(), unroll, nt) == rb.RB_OK
             assert torch.equal(dst, src)
