@@ -28,11 +28,11 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # known size; the text summaries with the exact commands are kept under profiles/.
 # rb_window_kernel: a launch of 8 steps at C4 (algorithmic 616.56 MB; candidates that lose their slot within a launch,
 # and representatives taken from a mini-batch row still in cache, are not moved) and of 16 steps at C3 (308.28 MB).
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 605795154,
-                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 308368653,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 77117264,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77321901,
-                    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): 34020011}      # algorithmic 33.55 MB
+MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 605764878,
+                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 308354440,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 77116977,
+                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77312701,
+                    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): 34009498}      # algorithmic 33.55 MB
 
 
 MANY = 64           # steps handed to one rb_update_sample_many call
