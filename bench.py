@@ -3,11 +3,15 @@
 
 A step is one update of the buffer with a mini-batch plus one sampling of r
 representatives into the augmented mini-batch, on synthetic input that is
-already resident in HBM.  The headline drives it through the single-call
-primitive rb_update_sample (one kernel launch per step where eligible); the
-same step issued as rb_update + rb_sample_augment (two launches) is reported
-beside it.  Prints ONE JSON line: augmented samples/s of the whole job, the HBM
-roofline of the dominant kernel, and the CPU oracle timed on the host.
+already resident in HBM.  The headline drives it through rb_update_sample_many
+(with the next call announced), which puts several steps into one launch where
+the shape allows; the same steps issued one launch per step, as the fused
+single call and as rb_update + rb_sample_augment are reported beside it.
+Every figure is the median of several timed regions of exactly --steps steps
+each, enqueued back to back behind a pre-roll of the same calls (so that the
+GPU never waits for the host), with HIP events on the side stream between them.
+Prints ONE JSON line: augmented samples/s of the whole job, the HBM roofline
+of the dominant kernel, and the CPU oracle timed on the host.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload C4] [--prefill]
 """
@@ -23,19 +27,18 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this much memory (>> 256 MB of last-level cache)
-# HBM bytes per launch of the dominant kernel as counted by two
-# `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE), each scaled by the reading of a plain copy of
-# known size; the text summaries with the exact commands are kept under profiles/.
-# rb_window_kernel: a launch of 8 steps at C4 (algorithmic 616.56 MB; candidates that lose their slot within a launch,
-# and representatives taken from a mini-batch row still in cache, are not moved) and of 16 steps at C3 (308.28 MB).
-MEASURED_TRAFFIC = {("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): 605764878,
-                    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): 308354440,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_planned_kernel"): 77116977,
-                    ("C4-1000x300-bf16-3x224x224-zipf", "rb_step_small_kernel"): 77312701,
-                    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): 34009498}      # algorithmic 33.55 MB
-
+# HBM bytes per STEP of the dominant kernel as counted by two `rocprofv3 --pmc` runs (FETCH_SIZE, WRITE_SIZE) of
+# `bench.py --pmc-run`, each scaled by the reading of a plain copy of known size in the same run; the text summaries
+# with the exact commands are the files named here.  Not measured by this run: the line says where it is from.
+PROFILED_TRAFFIC = {
+    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75720610, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),
+    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19272153, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),
+    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): (34009498, "profiles/rb_step_big_kernel_C5_pmc_hbm_traffic.txt"),
+}
 
 MANY = 64           # steps handed to one rb_update_sample_many call
+REPEATS = 5         # timed regions per figure (the median is reported, with the smallest and the largest)
+PREROLL = 64        # steps enqueued, untimed, right in front of the first timed region (the GPU works on them while the host queues the rest)
 
 
 def log(*a):
@@ -142,16 +145,27 @@ class Rig:
             t += 1
         self.step = t
 
-    def timed(self, n, **kw):
-        """ms per step over n steps enqueued back to back, HIP events on the side stream."""
+    def timed_regions(self, n, repeats=REPEATS, **kw):
+        """ms per step of `repeats` regions of exactly n steps each.  Everything is enqueued back to back on the
+        side stream, behind a pre-roll of the same calls that keeps the GPU busy while the host queues the timed
+        launches (so the regions hold no time in which the GPU waits for the host, as in a training loop whose data
+        pipeline runs ahead); HIP events on that stream mark the regions, the device is drained only at the end."""
         torch = self.torch
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        per = kw.get("many") or 1
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(repeats + 1)]
         torch.cuda.synchronize()
-        e0.record(self.stream)
-        self.enqueue(n, **kw)
-        e1.record(self.stream)
+        self.enqueue(-(-PREROLL // per) * per, **kw)
+        ev[0].record(self.stream)
+        for i in range(repeats):
+            self.enqueue(n, **kw)
+            ev[i + 1].record(self.stream)
         torch.cuda.synchronize()
-        return e0.elapsed_time(e1) / n
+        return [ev[i].elapsed_time(ev[i + 1]) / n for i in range(repeats)]
+
+    def timed(self, n, repeats=3, **kw):
+        """Median ms per step over `repeats` regions of n steps (see timed_regions)."""
+        ms = sorted(self.timed_regions(n, repeats, **kw))
+        return ms[len(ms) // 2]
 
     def close(self):
         self.buf.close()
@@ -241,37 +255,120 @@ def overlap_leg(rig, steps, target_ms, kind="fma"):
     e1.record(main)
     torch.cuda.synchronize()
     t_both = e0.elapsed_time(e1) / steps
+    # The same loop with a data pipeline that is a whole launch ahead: one rb_pipeline_step_many call per `group`
+    # iterations (the group's launch runs under the first iteration's stand-in, the other iterations follow
+    # rb_pipeline_drain), every call announced to the one before.
+    import ctypes as C
+    group = rig.buf.steps_per_launch(w.b, w.c, w.r)
+    t_rb_many = t_both_many = None
+    if group > 1:
+        n_groups = max(2, steps // group)
+        t_rb_many = rig.timed(n_groups * group, many=group, ahead=True)
+        torch.cuda.synchronize()
+        e0.record(main)
+        for _ in range(n_groups):
+            t = rig.step
+            o, o_next = (t % P) * C.sizeof(C.c_void_p), ((t + group) % P) * C.sizeof(C.c_void_p)
+            px, py, ox, oy = (C.cast(C.byref(a, o), C.POINTER(C.c_void_p)) for a in rig.ptrs)
+            rb.rb_announce_next_many(rig.buf.handle, group, C.cast(C.byref(rig.ptrs[1], o_next), C.POINTER(C.c_void_p)))
+            rc, _ = rb.rb_pipeline_step_many(h, group, px, py, w.b, w.c, w.r, w.lib_seed, t, ox, oy, main)
+            if rc:
+                raise RuntimeError(f"rb_pipeline_step_many -> {rc}")
+            rig.step = t + group
+            standin(amount)                            # iteration t: overlaps the group's launch
+            pipe.drain(main)
+            for _ in range(group - 1):
+                standin(amount)                        # the group's other iterations
+        e1.record(main)
+        torch.cuda.synchronize()
+        t_both_many = e0.elapsed_time(e1) / (n_groups * group)
     pipe.close()
     del big
-    return {"standin": kind, "standin_ms": round(t_alone, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
-            "overhead_frac": round((t_both - t_alone) / t_alone, 4)}
+    out = {"standin": kind, "standin_ms": round(t_alone, 4), "buffer_ms": round(t_rb, 4), "overlapped_ms": round(t_both, 4),
+           "overhead_frac": round((t_both - t_alone) / t_alone, 4)}
+    if group > 1:
+        out.update({"iterations_per_call": group, "many_buffer_ms": round(t_rb_many, 5), "many_overlapped_ms": round(t_both_many, 4),
+                    "many_overhead_frac": round((t_both_many - t_alone) / t_alone, 4)})
+    return out
 
 
-def cpu_baseline(w, wl, budget_s=12.0, max_steps=4000):
-    """The CPU oracle on the same workload from an empty buffer, host batches cycled from a small pool."""
+def cpu_baseline(w, wl, budget_s=12.0, max_steps=4000, threads=0, pool=None):
+    """The CPU oracle as it stands on the same workload from an empty buffer, host batches cycled from a pool
+    larger than the host's last-level cache.  threads > 0: the oracle's timing variant, policy sequential, the row
+    copies of every call spread over that many host threads."""
     from oracle import rbo
     import numpy as np
-    pool = []
-    for i in range(3):
-        x, y = wl.make_batch(w, i)
-        pool.append((wl.as_row_bytes(x), y.numpy()))
+    if pool is None:
+        pool = cpu_pool(w, wl)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    workers = rbo.Pool(threads) if threads else None
     out = np.zeros((w.r, w.row_bytes), dtype=np.uint8)
     t0 = time.perf_counter()
     steps = 0
     while steps < max_steps:
         x, y = pool[steps % len(pool)]
-        orc.update(x, y, w.c, w.lib_seed, steps)
-        orc.sample_augment(w.r, w.lib_seed, steps, out_x=out)
+        if workers:
+            orc.update_mt(workers, x, y, w.c, w.lib_seed, steps)
+            orc.sample_augment_mt(workers, w.r, w.lib_seed, steps, out_x=out)
+        else:
+            orc.update(x, y, w.c, w.lib_seed, steps)
+            orc.sample_augment(w.r, w.lib_seed, steps, out_x=out)
         steps += 1
         if steps % 10 == 0 and time.perf_counter() - t0 > budget_s:
             break
     dt = time.perf_counter() - t0
     orc.close()
-    return {"value": round((w.b + w.r) * steps / dt, 1), "unit": "augmented samples/s", "cores": 1, "kind": "oracle",
-            "sample": f"first {steps} steps of {w.name} from an empty buffer, {dt:.1f} s, host batches cycled from a pool of {len(pool)}",
+    if workers:
+        workers.close()
+    pool_mb = sum(x.nbytes for x, _ in pool) / 1e6
+    return {"value": round((w.b + w.r) * steps / dt, 1), "unit": "augmented samples/s", "cores": threads or 1, "kind": "oracle",
+            "sample": f"first {steps} steps of {w.name} from an empty buffer, {dt:.1f} s, host batches cycled from a pool of "
+                      f"{len(pool)} ({pool_mb:.0f} MB); rows are allocated on first write" +
+                      (f"; policy sequential, row copies of each call spread over {threads} threads" if threads else ""),
             "ms_per_step": round(dt / steps * 1e3, 4),
             "gb_per_s": round(w.bytes_per_step() * steps / dt / 1e9, 3)}
+
+
+def cpu_pool(w, wl, min_bytes=1 << 30, max_batches=12):
+    """Host mini-batches for the CPU baseline: at least min_bytes of them (more than a last-level cache)."""
+    n = max(3, min(max_batches, -(-min_bytes // (w.b * w.row_bytes))))
+    pool = []
+    for i in range(n):
+        x, y = wl.make_batch(w, i)
+        pool.append((wl.as_row_bytes(x), y.numpy()))
+    return pool
+
+
+def call_sizes(n, per_call):
+    """Steps per rb_update_sample_many call of a region of n steps."""
+    return [min(per_call, n - at) for at in range(0, n, per_call)]
+
+
+def spread(ms):
+    """median, smallest and largest of a list of timings"""
+    o = sorted(ms)
+    return o[len(o) // 2], o[0], o[-1]
+
+
+def headline(rig, steps, warmup=0):
+    """The headline figure on one rig: REPEATS regions of exactly `steps` steps through announced
+    rb_update_sample_many calls of at most MANY steps.  Returns a dict with the median, the spread, the launches
+    of one region and the rows that were really moved per step (counted by the kernels, read outside the regions)."""
+    w = rig.w
+    per_call = min(MANY, steps)
+    if warmup:
+        rig.enqueue(warmup, many=min(MANY, warmup), ahead=True)
+    rows0, steps0 = rig.buf.moved_rows(), rig.step          # (synchronises; outside the timed regions)
+    ms_all = rig.timed_regions(steps, REPEATS, many=per_call, ahead=True)
+    rows1, steps1 = rig.buf.moved_rows(), rig.step
+    ms, lo, hi = spread(ms_all)
+    launches = [k for n in call_sizes(steps, per_call) for k in launch_sizes(rig, n)]
+    moved_per_step = (rows1 - rows0) / (steps1 - steps0)
+    return {"ms_per_step": ms, "ms_per_step_min": lo, "ms_per_step_max": hi, "regions": REPEATS, "ms_per_step_regions": ms_all,
+            "steps_per_call": call_sizes(steps, per_call) if steps <= 4 * MANY else f"{steps // per_call} x {per_call} + {steps % per_call}",
+            "launch_steps": launches if len(launches) <= 16 else f"{len(launches)} launches, {max(launches)} steps at most",
+            "n_launches": len(launches), "rows_moved_per_step": moved_per_step,
+            "gb_per_s_actual": 2 * moved_per_step * w.row_bytes / (ms * 1e-3) / 1e9}
 
 
 def measure(w, torch, rb, wl, steps, warmup, prefill):
@@ -287,20 +384,18 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     fused = small or (1 <= w.c <= 1024 and 1 <= w.r <= 1024 and w.b <= 4096 and w.K <= 10240)
     windowed = rig.buf.steps_per_launch(w.b, w.c, w.r) > 1
     rig.enqueue(warmup, single_call=True, ahead=fused)
-    rig.enqueue(MANY, many=MANY, ahead=True)
-    torch.cuda.synchronize()
-    # Headline: K steps enqueued back to back on the side stream through rb_update_sample_many, MANY steps per
-    # host call, the labels of the next call's first steps announced before every call.  The mini-batches
-    # of all those steps are resident (like every input); when the step is eligible, up to 16 steps share one
-    # launch whose plan the launch before made (also across calls: that is what the announcement is for).
-    ms = rig.timed(steps, many=min(MANY, steps), ahead=True)     # exactly `steps` steps: the last call takes what is left
-    n_side = min(steps, 1000)
+    # Headline: exactly `steps` steps per timed region through rb_update_sample_many, at most MANY steps per host
+    # call, the labels of the next call's first steps announced before every call.  The mini-batches of all those
+    # steps are resident (like every input); when the step is eligible, up to 16 steps share one launch whose plan
+    # the launch before made (also across calls: that is what the announcement is for).
+    head = headline(rig, steps)
+    ms = head["ms_per_step"]
+    n_side = min(max(steps, 256), 1000)
     ms_many_plain = rig.timed(n_side // MANY * MANY or MANY, many=MANY)    # the same without announcing the next call
     # ... and with calls of exactly one launch each (what a loader that prefetches 8 or 16 mini-batches can feed)
     per_launch = rig.buf.steps_per_launch(w.b, w.c, w.r)
     ms_launch_calls = None
     if per_launch > 1:
-        rig.enqueue(per_launch, many=per_launch, ahead=True)
         ms_launch_calls = rig.timed(n_side // per_launch * per_launch, many=per_launch, ahead=True)
     ms_ahead = rig.timed(n_side, single_call=True, ahead=fused)   # one rb_update_sample per step, next labels announced
     ms_plain = rig.timed(n_side, single_call=True)                # ... not announced
@@ -318,20 +413,41 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
         "workload": w.name, "ms_per_step": ms, "aug_samples_per_s": (w.b + w.r) / (ms * 1e-3),
         "reps_per_s": w.r / (ms * 1e-3), "gb_per_s": w.bytes_per_step() / (ms * 1e-3) / 1e9,
         "hbm_frac": w.bytes_per_step() / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        "launches_per_step": len(launch_sizes(rig, MANY)) / MANY if windowed else (1 if fused else 2),
-        "steps_per_launch": max(launch_sizes(rig, MANY)) if windowed else 1,
-        "steps_per_launch_schedule": launch_sizes(rig, MANY) if windowed else None,
+        "headline": head,
+        "launches_per_step": head["n_launches"] / steps if windowed else (1 if fused else 2),
+        "steps_per_launch": per_launch if windowed else 1,
         "next_call_not_announced_ms_per_step": ms_many_plain, "one_launch_per_call_announced_ms_per_step": ms_launch_calls,
-        "steps_per_host_call": MANY,
         "one_launch_per_step_ms": ms_ahead, "one_launch_per_step_gb_per_s": w.bytes_per_step() / (ms_ahead * 1e-3) / 1e9,
         "next_labels_announced": fused, "plan_ahead_kernel": None if not fused else ("rb_step_planned_kernel" if small else "rb_step_big_kernel"),
         "not_announced_ms_per_step": ms_plain, "not_announced_gb_per_s": w.bytes_per_step() / (ms_plain * 1e-3) / 1e9,
         "two_call_ms_per_step": ms_two, "two_call_gb_per_s": w.bytes_per_step() / (ms_two * 1e-3) / 1e9,
         "many_call_one_launch_per_step_ms": ms_many1,
         "update_kernel_ms": ms_update, "sample_kernel_ms": ms_sample,
+        "side_legs_steps_per_region": n_side,
         "stored_samples": int(fill.sum()), "last_n": int(last_n), "prefilled": bool(prefill),
     }
     return rig, res
+
+
+def rows_per_call_sweep(rig, counts=(8, 16, 32, 64)):
+    """The same rig with c = r = 8 ... 64 rows per step (announced rb_update_sample_many calls, steps per launch as
+    the library chooses): how the achieved rate approaches the plain-copy ceiling as a launch carries more rows."""
+    import dataclasses
+    w0 = rig.w
+    out = []
+    for k in counts:
+        if k > w0.b or k > w0.r:          # the pool's augmented mini-batches have room for w0.r representatives
+            continue
+        rig.w = dataclasses.replace(w0, c=k, r=k)
+        per = rig.buf.steps_per_launch(w0.b, k, k)
+        n = max(MANY, 512 // MANY * MANY)
+        ms = rig.timed(n, many=MANY, ahead=True)
+        out.append({"c": k, "r": k, "rows_per_step": 2 * k, "steps_per_launch": per, "rows_per_launch": 2 * k * per,
+                    "mb_per_launch": round(2 * 2 * k * per * w0.row_bytes / 1e6, 2), "ms_per_step": round(ms, 5),
+                    "gb_per_s": round(2 * 2 * k * w0.row_bytes / (ms * 1e-3) / 1e9, 1),
+                    "hbm_frac": round(2 * 2 * k * w0.row_bytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)})
+    rig.w = w0
+    return out
 
 
 def launch_sizes(rig, n):
@@ -460,22 +576,38 @@ def main():
     log(f"[bench] plain copy ceiling {ceiling:.0f} GB/s")
     rig, res = measure(w, torch, rb, wl, a.steps, a.warmup, a.prefill)
     log(f"[bench] {json.dumps(res)}")
+    sweeps = {}
+    if not a.no_variants:
+        sweeps[w.name] = rows_per_call_sweep(rig)
+        log(f"[bench] rows-per-call sweep {json.dumps(sweeps[w.name])}")
+    rig.close()
+    # The same headline on a second, fresh allocation of the buffer and the pool: the rate depends a little on the
+    # physical placement the driver hands out, so two draws of it are shown.
+    rig = Rig(w, torch, rb, wl)
+    if a.prefill:
+        rig.prefill()
+    again = headline(rig, a.steps, warmup=max(a.warmup, MANY))
+    log(f"[bench] second allocation {json.dumps(again)}")
+    rig.close()
     pre = None
     if not a.prefill:
-        rig.close()
         rig, pre = measure(w, torch, rb, wl, min(a.steps, 500), a.warmup, True)
         log(f"[bench] prefilled {json.dumps(pre)}")
-    rig.close()
+        rig.close()
 
     others = {}
     for name in [s for s in a.others.split(",") if s]:
         ow = wl.by_name(name)
-        orig, ores = measure(ow, torch, rb, wl, min(a.steps, ow.steps), a.warmup, False)
+        # (regions of at least 256 steps: with fewer, a region is one or two launches and mostly their start and end)
+        orig, ores = measure(ow, torch, rb, wl, max(256, min(a.steps, ow.steps)), a.warmup, False)
+        ores["steps_per_region"] = max(256, min(a.steps, ow.steps))
+        if ow.name.startswith("C3") and not a.no_variants:
+            sweeps[ow.name] = rows_per_call_sweep(orig)
         if ow.name.startswith("C3") and not a.no_overlap:
             ores["overlap"] = {f"fma_{d}ms": overlap_leg(orig, 200, d) for d in (0.5, 2.0, 10.0)}
             ores["overlap"]["hbm_copy_0.3ms"] = overlap_leg(orig, 200, 0.3, kind="hbm")
         orig.close()
-        others[ow.name] = {k: (round(v, 5) if isinstance(v, float) else v) for k, v in ores.items()}
+        others[ow.name] = rounded(ores)
         log(f"[bench] {json.dumps(others[ow.name])}")
 
     variants = None if a.no_variants else variants_leg(w, torch, rb, wl, min(a.steps, 500))
@@ -488,23 +620,24 @@ def main():
     if reduced:
         log(f"[bench] reduced-precision {json.dumps(reduced)}")
 
-    # Roofline of the dominant kernel.  With one or several whole steps per launch that kernel is the
-    # step (rb_window_kernel / rb_step_planned_kernel: every inserted row and every representative row
-    # read once and written once, plus the one workgroup that plans what comes next); otherwise it is
-    # the gather of rb_sample_augment.
+    # Roofline of the dominant kernel over the timed regions of the headline.  With one or several whole steps per
+    # launch that kernel is the step (rb_window_kernel / rb_step_big_kernel: every inserted row and every
+    # representative row read once and written once, plus the workgroups that plan what comes next), launched back
+    # to back with nothing else in the stream: its average launch is a region's bytes and a region's time divided
+    # by the launches of a region.  Otherwise it is the gather of rb_sample_augment, timed alone.
     n_rows = min(w.r, res["last_n"])
-    if res["steps_per_launch"] > 1:
-        # several steps per launch, every launch of a call of MANY steps the same size
-        per = res["steps_per_launch"]
-        assert MANY % per == 0
-        kernel = "rb_window_kernel"
-        k_ms, k_bytes = res["ms_per_step"] * per, 2 * (w.c + n_rows) * w.row_bytes * per
-    elif res["launches_per_step"] == 1:
-        # rb_update_sample_many announces every next step's labels for itself: one planned launch per step
-        kernel, k_ms, k_bytes = res["plan_ahead_kernel"], res["ms_per_step"], 2 * (w.c + n_rows) * w.row_bytes
+    head = res["headline"]
+    if res["launches_per_step"] <= 1:
+        kernel = "rb_window_kernel" if res["steps_per_launch"] > 1 else res["plan_ahead_kernel"]
+        launches = head["n_launches"]
+        k_ms = res["ms_per_step"] * a.steps / launches
+        k_bytes = 2 * (w.c + n_rows) * w.row_bytes * a.steps / launches
+        steps_per_avg_launch = a.steps / launches
     else:
-        kernel, k_ms, k_bytes = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes
+        kernel, k_ms, k_bytes, steps_per_avg_launch = "rb_sample_kernel", res["sample_kernel_ms"], 2 * n_rows * w.row_bytes, 1
     achieved = k_bytes / (k_ms * 1e-3) / 1e9
+    profiled = PROFILED_TRAFFIC.get((w.name, kernel)) if not a.prefill else None
+    calls = call_sizes(a.steps, min(MANY, a.steps))
     line = {
         "metric": "augmented samples/sec and achieved HBM GB/s (% of peak) per update+sample step",
         "value": round(res["aug_samples_per_s"], 1), "unit": "augmented samples/s",
@@ -512,26 +645,57 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "u8", "data": "synthetic",
         "config": {"workload": w.name, "classes": w.K, "slots_per_class": w.S, "sample_shape": list(w.shape),
                    "sample_dtype": w.dtype, "b": w.b, "c": w.c, "r": w.r, "prefilled": bool(a.prefill),
-                   "api": f"rb_announce_next_many + rb_update_sample_many, {MANY} steps per call" +
-                          (f", {res['steps_per_launch']} steps per launch (planned by the launch before)" if res["steps_per_launch"] > 1 else ""),
+                   "api": f"rb_announce_next_many + rb_update_sample_many, calls of {sorted(set(calls), reverse=True)} steps, launches of "
+                          f"{sorted(set(launch_sizes_of(calls, res['steps_per_launch'])), reverse=True)} steps (each planned by the launch before)",
+                   "timing": f"median of {REPEATS} regions of {a.steps} steps each, back to back behind {PREROLL} untimed steps of the same calls",
                    "stream": "side stream, inputs resident in HBM, pool rotation"},
         "gb_per_s": round(res["gb_per_s"], 1), "hbm_frac": round(res["hbm_frac"], 4),
+        "gb_per_s_actual": round(head["gb_per_s_actual"], 1),
+        "ms_per_step_min_max": [round(head["ms_per_step_min"], 5), round(head["ms_per_step_max"], 5)],
+        "second_allocation": {"ms_per_step": round(again["ms_per_step"], 5),
+                              "ms_per_step_min_max": [round(again["ms_per_step_min"], 5), round(again["ms_per_step_max"], 5)],
+                              "hbm_frac": round(w.bytes_per_step() / (again["ms_per_step"] * 1e-3) / 1e9 / HBM_PEAK_GBS, 4)},
         "reps_per_s": round(res["reps_per_s"], 1),
         "roofline": {"bound": "hbm", "kernel": kernel, "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": round(achieved / HBM_PEAK_GBS, 4),
-                     "traffic": MEASURED_TRAFFIC.get((w.name, kernel)) if not a.prefill else None,
-                     "bytes_per_launch": k_bytes, "kernel_ms": round(k_ms, 5),
+                     "traffic": None if profiled is None else round(profiled[0] * steps_per_avg_launch),
+                     "traffic_source": None if profiled is None else f"{profiled[1]}: {profiled[0]} bytes per step, times the "
+                                                                     f"{steps_per_avg_launch:.2f} steps of this run's average launch (not measured by this run)",
+                     "bytes_per_launch": round(k_bytes), "kernel_ms": round(k_ms, 5),
+                     "launches_per_region": head["n_launches"] if res["launches_per_step"] <= 1 else None,
                      "copy_ceiling_gbs": round(ceiling, 1)},
-        "detail": {k: (round(v, 5) if isinstance(v, float) else v) for k, v in res.items()},
-        "prefilled": None if pre is None else {k: (round(v, 5) if isinstance(v, float) else v) for k, v in pre.items()},
+        "rows_per_call_sweep": sweeps or None,
+        "detail": rounded(res),
+        "prefilled": None if pre is None else rounded(pre),
         "others": others,
         "policy_variants": variants,
         "host_pinned_rows": pinned,
         "bf16_stored_rows": reduced,
     }
     if not a.no_cpu_baseline:
-        line["cpu_baseline"] = cpu_baseline(w, wl)
+        pool = cpu_pool(w, wl)
+        line["cpu_baseline"] = cpu_baseline(w, wl, pool=pool)
+        log(f"[bench] cpu {json.dumps(line['cpu_baseline'])}")
+        line["cpu_baseline_mt"] = cpu_baseline(w, wl, pool=pool, threads=max(2, min(os.cpu_count() or 2, 16)))
+        log(f"[bench] cpu mt {json.dumps(line['cpu_baseline_mt'])}")
     print(json.dumps(line), flush=True)
+
+
+def launch_sizes_of(calls, per_launch):
+    return [min(per_launch, n - at) for n in calls for at in range(0, n, per_launch)]
+
+
+def rounded(d):
+    out = {}
+    for k, v in d.items():
+        if isinstance(v, float):
+            v = round(v, 5)
+        elif isinstance(v, dict):
+            v = rounded(v)
+        elif isinstance(v, list):
+            v = [round(x, 5) if isinstance(x, float) else x for x in v]
+        out[k] = v
+    return out
 
 
 if __name__ == "__main__":

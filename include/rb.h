@@ -299,6 +299,31 @@ int rb_pipeline_step(rb_pipeline *p, const void *batch_x, const int64_t *batch_y
                      int64_t r, uint64_t seed, uint64_t step, void *next_x, int64_t *next_y,
                      void *train_stream, int64_t *ready_rows);
 int rb_pipeline_drain(rb_pipeline *p, void *train_stream, int64_t *ready_rows);
+
+/*
+ * rb_pipeline_step for a training loop whose data pipeline holds the next n
+ * mini-batches already (Sec. IV-D, Fig. 4, with a prefetching loader): one call
+ * every n iterations, at the start of iteration first_step.  (1) train_stream
+ * is made to wait for the representatives that the previous call (of either
+ * kind) started to collect; (2) the buffer's stream is made to wait for
+ * train_stream and then runs rb_update_sample_many with these n mini-batches:
+ * step i updates the buffer with mini-batch i and writes the representatives
+ * for iteration first_step + i + 1 to next_x[i] / next_y[i].  When the shape
+ * is eligible, several of the steps share one launch (see
+ * rb_update_sample_many), and an rb_announce_next_many before this call lets
+ * its last launch plan the first steps of the following call.  The training
+ * computation of iteration first_step, enqueued on train_stream afterwards,
+ * overlaps (2); before iteration first_step + 1 the caller makes train_stream
+ * wait for this call's representatives with rb_pipeline_drain (they are all
+ * complete then), and trains the remaining n - 1 iterations of the group.
+ * Every iteration thus trains on exactly the representatives that
+ * rb_pipeline_step would have given it.  Arguments, limits and errors are those
+ * of rb_update_sample_many; *ready_rows as in rb_pipeline_step.  n = 0 does
+ * nothing.  On an error nothing was enqueued and the pipeline is unchanged.
+ */
+int rb_pipeline_step_many(rb_pipeline *p, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
+                          int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
+                          void *const *next_x, int64_t *const *next_y, void *train_stream, int64_t *ready_rows);
 int rb_pipeline_destroy(rb_pipeline *p);
 
 /*
@@ -307,6 +332,15 @@ int rb_pipeline_destroy(rb_pipeline *p);
  * *flags_host (RB_FLAG_*).  Any pointer may be null.  Not for the hot path.
  */
 int rb_read_state(rb_buffer *rb, int32_t *fill_host, int64_t *last_n_host, uint32_t *flags_host);
+
+/*
+ * Synchronise the bound stream and report how many sample rows the kernels have
+ * moved since the last bind: every candidate that was actually stored (one that
+ * loses its slot to a later candidate is not moved) and every representative
+ * that was handed out.  2 * row_bytes times the difference between two readings
+ * is the sample traffic of the steps in between.  Not for the hot path.
+ */
+int rb_read_moved_rows(rb_buffer *rb, uint64_t *rows_host);
 
 /* Launch-shape knobs for measurement sweeps.  RB_OPT_UNROLL: 16-byte vectors a
  * thread keeps in flight while moving a row (0 = automatic, else 1, 2, 4 or 8).

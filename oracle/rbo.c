@@ -30,7 +30,9 @@
  * the paper (its two-iteration figures carry no numbers) -- "parity unpinned
  * by the paper" for those, pinned only through the properties above.
  */
+#define _POSIX_C_SOURCE 200809L   /* pthread barriers (timing variant at the end of the file) */
 #include <limits.h>
+#include <pthread.h>
 #include <stdint.h>
 #include <stdlib.h>
 #include <string.h>
@@ -165,7 +167,27 @@ typedef struct rbo_buffer {
     int selection, eviction;   /* policy variant, see the enums above */
     int32_t *head;        /* [K] FIFO: slot of the oldest representative of a full class       */
     int32_t *seen;        /* [K] RESERVOIR: samples offered to the class so far (saturating)   */
+    /* timing variant only (see the end of this file): row copies are listed instead of carried out */
+    int defer;
+    struct rbo_copy *jobs;
+    int64_t n_jobs, cap_jobs;
 } rbo_buffer;
+
+struct rbo_copy { unsigned char *dst; const unsigned char *src; };
+
+/* Timing variant: remember a row copy for later.  Returns 0, or -1 when out of memory. */
+static int defer_copy(rbo_buffer *rb, unsigned char *dst, const unsigned char *src)
+{
+    if (rb->n_jobs == rb->cap_jobs) {
+        int64_t cap = rb->cap_jobs ? 2 * rb->cap_jobs : 256;
+        struct rbo_copy *j = (struct rbo_copy *)realloc(rb->jobs, (size_t)cap * sizeof *j);
+        if (!j) return -1;
+        rb->jobs = j; rb->cap_jobs = cap;
+    }
+    rb->jobs[rb->n_jobs].dst = dst; rb->jobs[rb->n_jobs].src = src;
+    rb->n_jobs += 1;
+    return 0;
+}
 
 rbo_buffer *rbo_create(int64_t classes, int64_t slots_per_class, int64_t row_bytes)
 {
@@ -193,7 +215,7 @@ void rbo_destroy(rbo_buffer *rb)
     size_t slots = (size_t)rb->K * (size_t)rb->S;
     for (size_t i = 0; i < slots; ++i) free(rb->rows[i]);
     free(rb->rows); free(rb->buf_y); free(rb->fill); free(rb->head); free(rb->seen);
-    free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot); free(rb->smp_g);
+    free(rb->ins_pos); free(rb->ins_class); free(rb->ins_slot); free(rb->smp_g); free(rb->jobs);
     free(rb);
 }
 
@@ -223,8 +245,9 @@ int rbo_set_storage(rbo_buffer *rb, int storage)
 
 /* One sample into its stored form / back (both rows may be unaligned: bytes are assembled by hand,
  * little-endian like the machines this runs on). */
-static void store_row(const rbo_buffer *rb, unsigned char *stored, const unsigned char *sample)
+static void store_row(rbo_buffer *rb, unsigned char *stored, const unsigned char *sample)
 {
+    if (rb->defer && defer_copy(rb, stored, sample) == 0) return;
     if (rb->storage == RBO_STORE_SAME) { memcpy(stored, sample, (size_t)rb->row_bytes); return; }
     for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
         uint32_t bits;
@@ -234,8 +257,9 @@ static void store_row(const rbo_buffer *rb, unsigned char *stored, const unsigne
     }
 }
 
-static void load_row(const rbo_buffer *rb, unsigned char *sample, const unsigned char *stored)
+static void load_row(rbo_buffer *rb, unsigned char *sample, const unsigned char *stored)
 {
+    if (rb->defer && defer_copy(rb, sample, stored) == 0) return;
     if (rb->storage == RBO_STORE_SAME) { memcpy(sample, stored, (size_t)rb->row_bytes); return; }
     for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
         uint16_t h;
@@ -396,4 +420,106 @@ void rbo_export_rows(const rbo_buffer *rb, int64_t first, int64_t count, void *d
         if (src) memcpy(d + (size_t)i * (size_t)rb->stored_bytes, src, (size_t)rb->stored_bytes);
         else memset(d + (size_t)i * (size_t)rb->stored_bytes, 0, (size_t)rb->stored_bytes);
     }
+}
+
+/* ------------------------------------------------------------------------ */
+/* Timing variant: the same two calls with the row copies of a call spread   */
+/* over host threads.  The policy (selection, slot assignment, sampling)     */
+/* stays the sequential code above, which only lists its row copies instead  */
+/* of carrying them out; then every thread walks the list in order and       */
+/* copies its own slice of every row.  Copies to one destination therefore   */
+/* still land in list order, byte for byte, so the result is that of the     */
+/* plain calls.  Only for the storage form RBO_STORE_SAME.  This is a        */
+/* reported baseline of the benchmark, not the parity reference.             */
+/* ------------------------------------------------------------------------ */
+typedef struct rbo_pool {
+    int n;                          /* worker threads                              */
+    pthread_t *threads;
+    pthread_barrier_t start, done;  /* workers and the caller meet at both         */
+    const struct rbo_copy *jobs;
+    int64_t n_jobs, row_bytes;
+    int quit;
+} rbo_pool;
+
+struct rbo_worker { rbo_pool *pool; int index; };
+
+static void *pool_worker(void *arg)
+{
+    struct rbo_worker *me = (struct rbo_worker *)arg;
+    rbo_pool *pool = me->pool;
+    const int t = me->index;
+    free(me);
+    for (;;) {
+        pthread_barrier_wait(&pool->start);
+        if (pool->quit) return NULL;
+        /* slice t of every row, in multiples of 64 bytes */
+        int64_t units = (pool->row_bytes + 63) / 64;
+        int64_t lo = units * t / pool->n * 64, hi = units * (t + 1) / pool->n * 64;
+        if (hi > pool->row_bytes) hi = pool->row_bytes;
+        if (lo < hi)
+            for (int64_t j = 0; j < pool->n_jobs; ++j)
+                memcpy(pool->jobs[j].dst + lo, pool->jobs[j].src + lo, (size_t)(hi - lo));
+        pthread_barrier_wait(&pool->done);
+    }
+}
+
+rbo_pool *rbo_pool_create(int threads)
+{
+    if (threads < 1 || threads > 1024) return NULL;
+    rbo_pool *pool = (rbo_pool *)calloc(1, sizeof *pool);
+    if (!pool) return NULL;
+    pool->threads = (pthread_t *)calloc((size_t)threads, sizeof(pthread_t));
+    if (!pool->threads) { free(pool); return NULL; }
+    pthread_barrier_init(&pool->start, NULL, (unsigned)threads + 1);
+    pthread_barrier_init(&pool->done, NULL, (unsigned)threads + 1);
+    pool->n = threads;
+    for (int t = 0; t < threads; ++t) {
+        struct rbo_worker *w = (struct rbo_worker *)malloc(sizeof *w);
+        if (!w) abort();
+        w->pool = pool; w->index = t;
+        if (pthread_create(&pool->threads[t], NULL, pool_worker, w) != 0) abort();
+    }
+    return pool;
+}
+
+void rbo_pool_destroy(rbo_pool *pool)
+{
+    if (!pool) return;
+    pool->quit = 1;
+    pthread_barrier_wait(&pool->start);
+    for (int t = 0; t < pool->n; ++t) pthread_join(pool->threads[t], NULL);
+    pthread_barrier_destroy(&pool->start);
+    pthread_barrier_destroy(&pool->done);
+    free(pool->threads);
+    free(pool);
+}
+
+static void pool_run(rbo_pool *pool, rbo_buffer *rb)
+{
+    pool->jobs = rb->jobs; pool->n_jobs = rb->n_jobs; pool->row_bytes = rb->row_bytes;
+    pthread_barrier_wait(&pool->start);
+    pthread_barrier_wait(&pool->done);
+    rb->n_jobs = 0;
+}
+
+int rbo_update_mt(rbo_pool *pool, rbo_buffer *rb, const void *batch_x, const int64_t *batch_y,
+                  int64_t b, int64_t c, uint64_t seed, uint64_t step)
+{
+    if (!pool || !rb || rb->storage != RBO_STORE_SAME) return -1;
+    rb->defer = 1; rb->n_jobs = 0;
+    int rc = rbo_update(rb, batch_x, batch_y, b, c, seed, step);
+    rb->defer = 0;
+    pool_run(pool, rb);
+    return rc;
+}
+
+int64_t rbo_sample_augment_mt(rbo_pool *pool, rbo_buffer *rb, int64_t r, uint64_t seed, uint64_t step,
+                              void *out_x, int64_t *out_y)
+{
+    if (!pool || !rb || rb->storage != RBO_STORE_SAME) return -1;
+    rb->defer = 1; rb->n_jobs = 0;
+    int64_t n = rbo_sample_augment(rb, r, seed, step, out_x, out_y);
+    rb->defer = 0;
+    pool_run(pool, rb);
+    return n;
 }

@@ -66,6 +66,14 @@ def lib():
         L.rbo_row.restype = vp
         L.rbo_export_rows.argtypes = [vp, i64, i64, vp]
         L.rbo_export_rows.restype = None
+        L.rbo_pool_create.argtypes = [C.c_int]
+        L.rbo_pool_create.restype = vp
+        L.rbo_pool_destroy.argtypes = [vp]
+        L.rbo_pool_destroy.restype = None
+        L.rbo_update_mt.argtypes = [vp, vp, vp, vp, i64, i64, u64, u64]
+        L.rbo_update_mt.restype = C.c_int
+        L.rbo_sample_augment_mt.argtypes = [vp, vp, i64, u64, u64, vp, vp]
+        L.rbo_sample_augment_mt.restype = i64
         _lib = L
     return _lib
 
@@ -165,6 +173,27 @@ class Buffer:
             raise ValueError("rbo_sample_augment rejected the arguments")
         return int(n), out_x, out_y
 
+    # ---- timing variant: the row copies of a call spread over the threads of a Pool ----
+    def update_mt(self, pool, batch_x, batch_y, c, seed, step):
+        x = self._bytes2d(batch_x)
+        y = np.ascontiguousarray(batch_y, dtype=np.int64)
+        b = y.shape[0]
+        assert x.shape == (b, self.row_bytes), (x.shape, b, self.row_bytes)
+        rc = lib().rbo_update_mt(pool._h, self._h, x.ctypes.data, y.ctypes.data, b, int(c), int(seed), int(step))
+        if rc != 0:
+            raise ValueError("rbo_update_mt rejected the arguments")
+
+    def sample_augment_mt(self, pool, r, seed, step, out_x=None):
+        r = int(r)
+        if out_x is None:
+            out_x = np.zeros((r, self.row_bytes), dtype=np.uint8)
+        out_y = np.empty(r, dtype=np.int64)
+        assert out_x.dtype == np.uint8 and out_x.shape == (r, self.row_bytes) and out_x.flags.c_contiguous
+        n = lib().rbo_sample_augment_mt(pool._h, self._h, r, int(seed), int(step), out_x.ctypes.data, out_y.ctypes.data)
+        if n < 0:
+            raise ValueError("rbo_sample_augment_mt rejected the arguments")
+        return int(n), out_x, out_y
+
     @property
     def fill(self):
         return _view(lib().rbo_fill(self._h), self.K, np.int32)
@@ -202,3 +231,21 @@ class Buffer:
         out = np.empty((int(count), self.stored_row_bytes), dtype=np.uint8)
         lib().rbo_export_rows(self._h, int(first), int(count), out.ctypes.data)
         return out
+
+
+class Pool:
+    """Host threads that carry out the row copies of Buffer.update_mt / sample_augment_mt."""
+
+    def __init__(self, threads):
+        self.threads = int(threads)
+        self._h = lib().rbo_pool_create(self.threads)
+        if not self._h:
+            raise ValueError("rbo_pool_create rejected the thread count")
+
+    def close(self):
+        if self._h:
+            lib().rbo_pool_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        self.close()

@@ -24,8 +24,8 @@ RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
     "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
-    "rb_announce_next", "rb_announce_next_many", "rb_query_steps_per_launch", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_drain", "rb_pipeline_destroy",
-    "rb_read_state", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
+    "rb_announce_next", "rb_announce_next_many", "rb_query_steps_per_launch", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_step_many", "rb_pipeline_drain", "rb_pipeline_destroy",
+    "rb_read_state", "rb_read_moved_rows", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
 
 
@@ -57,7 +57,10 @@ def _load():
     L.rb_update_sample_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp)]
     L.rb_pipeline_create.argtypes = [C.POINTER(vp), vp]
     L.rb_pipeline_step.argtypes = [vp, vp, vp, i64, i64, i64, u64, u64, vp, vp, vp, C.POINTER(i64)]
+    L.rb_pipeline_step_many.argtypes = [vp, i64, C.POINTER(vp), C.POINTER(vp), i64, i64, i64, u64, u64, C.POINTER(vp), C.POINTER(vp), vp,
+                                        C.POINTER(i64)]
     L.rb_pipeline_drain.argtypes = [vp, vp, C.POINTER(i64)]
+    L.rb_read_moved_rows.argtypes = [vp, C.POINTER(u64)]
     L.rb_pipeline_destroy.argtypes = [vp]
     L.rb_read_state.argtypes = [vp, vp, C.POINTER(i64), C.POINTER(C.c_uint32)]
     L.rb_set_option.argtypes = [vp, i32, i64]
@@ -180,6 +183,16 @@ def rb_pipeline_step(p, batch_x, batch_y, b, c, r, seed, step, next_x, next_y, t
     return rc, n.value
 
 
+def rb_pipeline_step_many(p, n, batch_x, batch_y, b, c, r, seed, first_step, next_x, next_y, train_stream=None):
+    """batch_x, batch_y, next_x, next_y: sequences of n tensors / addresses, or arrays made by pointer_array.
+    Returns (status, ready_rows)."""
+    arrs = [a if a is None or isinstance(a, (C.Array, C._Pointer)) else pointer_array(a) for a in (batch_x, batch_y, next_x, next_y)]
+    rows = C.c_int64()
+    rc = _L.rb_pipeline_step_many(p, int(n), arrs[0], arrs[1], int(b), int(c), int(r), int(seed), int(first_step),
+                                  arrs[2], arrs[3], _stream(train_stream), C.byref(rows))
+    return rc, rows.value
+
+
 def rb_pipeline_drain(p, train_stream=None):
     """Returns (status, ready_rows)."""
     n = C.c_int64()
@@ -198,6 +211,13 @@ def rb_read_state(rb, classes):
     n, fl = C.c_int64(), C.c_uint32()
     rc = _L.rb_read_state(rb, fill.ctypes.data, C.byref(n), C.byref(fl))
     return rc, fill, n.value, fl.value
+
+
+def rb_read_moved_rows(rb):
+    """Returns (status, rows moved since the last bind)."""
+    rows = C.c_uint64()
+    rc = _L.rb_read_moved_rows(rb, C.byref(rows))
+    return rc, rows.value
 
 
 def rb_set_option(rb, option, value):
@@ -333,6 +353,11 @@ class RehearsalBuffer:
         _check(rc, "rb_read_state")
         return fill, last_n, flags
 
+    def moved_rows(self):
+        rc, rows = rb_read_moved_rows(self.handle)
+        _check(rc, "rb_read_moved_rows")
+        return rows
+
     def set_option(self, option, value):
         _check(rb_set_option(self.handle, option, value), "rb_set_option")
 
@@ -369,6 +394,14 @@ class Pipeline:
             assert next_x.shape[0] >= r and next_y.shape[0] >= r
         rc, rows = rb_pipeline_step(self.handle, batch_x, batch_y, b, c, r, seed, step, next_x, next_y, train_stream)
         _check(rc, "rb_pipeline_step")
+        return rows
+
+    def step_many(self, batch_x, batch_y, c, r, seed, first_step, next_x, next_y, train_stream=None):
+        """len(batch_x) consecutive iterations from one call (sequences of tensors or pointer arrays are passed through)."""
+        n = len(batch_x)
+        b = batch_y[0].shape[0] if n else 1
+        rc, rows = rb_pipeline_step_many(self.handle, n, batch_x, batch_y, b, c, r, seed, first_step, next_x, next_y, train_stream)
+        _check(rc, "rb_pipeline_step_many")
         return rows
 
     def drain(self, train_stream=None):

@@ -1042,6 +1042,41 @@ int rb_pipeline_drain(rb_pipeline* p, void* train_stream, int64_t* ready_rows)
     return RB_OK;
 }
 
+int rb_pipeline_step_many(rb_pipeline* p, int64_t n, const void* const* batch_x, const int64_t* const* batch_y,
+                          int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,
+                          void* const* next_x, int64_t* const* next_y, void* train_stream, int64_t* ready_rows)
+{
+    if (!p || n < 0 || !batch_x || !batch_y) return RB_EINVAL;
+    if (r > 0 && (!next_x || !next_y)) return RB_EINVAL;
+    rb_buffer* rb = p->rb;
+    // everything is checked before the first stream operation, so that an error leaves nothing behind
+    for (int64_t i = 0; i < n; ++i) {
+        const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? next_x[i] : nullptr, r > 0 ? next_y[i] : nullptr);
+        if (bad != RB_OK) return bad;
+    }
+    if (n == 0) {
+        if (ready_rows) *ready_rows = p->started ? p->prev_r : 0;
+        return RB_OK;
+    }
+    hipStream_t train = static_cast<hipStream_t>(train_stream);
+    const bool two_streams = train != rb->stream;
+    if (two_streams) {
+        // (1) the training stream may go on once the previous call's representatives are complete
+        if (p->started && hipStreamWaitEvent(train, p->done, 0) != hipSuccess) return RB_EHIP;
+        // the buffer's stream starts these steps once the training stream has got this far
+        if (hipEventRecord(p->ready, train) != hipSuccess) return RB_EHIP;
+        if (hipStreamWaitEvent(rb->stream, p->ready, 0) != hipSuccess) return RB_EHIP;
+    }
+    // (2) the n updates, each followed by the collection of the next representatives
+    const int rc = rb_update_sample_many(rb, n, batch_x, batch_y, b, c, r, seed, first_step, next_x, next_y);
+    if (rc != RB_OK) return rc;
+    if (two_streams && hipEventRecord(p->done, rb->stream) != hipSuccess) return RB_EHIP;
+    if (ready_rows) *ready_rows = p->started ? p->prev_r : 0;
+    p->prev_r = r;
+    p->started = true;
+    return RB_OK;
+}
+
 int rb_pipeline_destroy(rb_pipeline* p)
 {
     if (!p) return RB_EINVAL;
@@ -1064,6 +1099,18 @@ int rb_read_state(rb_buffer* rb, int32_t* fill_host, int64_t* last_n_host, uint3
         return RB_EHIP;
     if (last_n_host) *last_n_host = st.last_n;
     if (flags_host) *flags_host = st.flags;
+    return RB_OK;
+}
+
+int rb_read_moved_rows(rb_buffer* rb, uint64_t* rows_host)
+{
+    if (!rb || !rows_host) return RB_EINVAL;
+    if (!rb->bound) return RB_ESTATE;
+    discard_plan(rb);
+    if (hipStreamSynchronize(rb->stream) != hipSuccess) return RB_EHIP;
+    DevState st;
+    if (hipMemcpy(&st, rb->ws, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) return RB_EHIP;
+    *rows_host = st.moved_rows;
     return RB_OK;
 }
 

@@ -32,7 +32,14 @@ struct DevState {
     uint32_t flags;
     uint32_t pad;
     int64_t last_n;
+    unsigned long long moved_rows;   // rows moved since the last bind (stored candidates + representatives handed out)
 };
+
+// One more row is being moved (called by the one thread that also writes the row's label).
+__device__ __forceinline__ void count_moved(DevState* state)
+{
+    atomicAdd(&state->moved_rows, 1ull);
+}
 constexpr size_t STATE_BYTES = 256;
 
 struct Seed {

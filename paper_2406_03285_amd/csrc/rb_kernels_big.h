@@ -484,7 +484,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
         for (int ee = e; ee < count; ee += m.cgrid) {
             const PlanEntry en = entry[ee];
             if (en.row < 0) continue;           // label outside [0, K), or a later class-mate takes the slot
-            if (first) m.buf_y[en.row] = en.label;
+            if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
             Tile<U, NT, BIG_GROUP, true, BF16 ? CV_NARROW : CV_NONE> t;
             t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
             t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
@@ -495,6 +495,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
     const PlanEntry en = entry[m.c + j];
     if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
+    if (first) count_moved(m.state);
     // written in this very step?  Then the stored candidate's mini-batch row is what the slot will hold.
     const int pos = en.pos == BIG_LOOK_UP ? big_forwarded(fwd, (uint32_t)en.row) : -1;
     vec16* dst = m.out_x + (int64_t)j * m.row_vec * WIDE;

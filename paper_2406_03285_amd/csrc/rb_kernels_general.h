@@ -299,7 +299,7 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         }
         const int64_t dst_row = (int64_t)ki * a.S + slot;
         t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-        if (tile == 0 && lane == 0) a.buf_y[dst_row] = ki;
+        if (tile == 0 && lane == 0) { a.buf_y[dst_row] = ki; count_moved(a.state); }
     }
 }
 
@@ -405,7 +405,7 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
     Tile<U, NT, WAVE, false, WIDEN ? CV_WIDEN : CV_NONE> t;
     t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
     t.store(a.out_x + (int64_t)j * a.row_vec * (WIDEN ? 2 : 1), v_lo, v_hi);
-    if (tile == 0 && lane == 0) a.out_y[j] = pk;
+    if (tile == 0 && lane == 0) { a.out_y[j] = pk; count_moved(a.state); }
 }
 
 }  // namespace

@@ -352,7 +352,7 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
     constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.c) {
         if (en.row < 0) return;                 // label outside [0, K), or a later class-mate takes the slot
-        if (first) m.buf_y[en.row] = en.label;
+        if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
         Tile<U, NT, TPB, true, BF16 ? CV_NARROW : CV_NONE> t;
         t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
         t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
@@ -361,6 +361,7 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
     const int j = e - m.c;
     if (first) m.out_y[j] = en.label;           // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
+    if (first) count_moved(m.state);
     vec16* dst = m.out_x + (int64_t)j * m.row_vec * WIDE;
     if (BF16 && en.pos >= 0) {
         // forwarded from the mini-batch: what the slot will hold is the row rounded to bfloat16

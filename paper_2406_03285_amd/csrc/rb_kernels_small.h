@@ -192,7 +192,7 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
         const int64_t dst_row = s_dst[0];
         if (dst_row >= 0) {
             t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+            if (tile == 0 && tid == 0) { a.buf_y[dst_row] = dst_row / a.S; count_moved(a.state); }
         }
     }
     for (int rr = 1; rr < a.rpb; ++rr) {
@@ -216,7 +216,7 @@ __global__ void __launch_bounds__(TPB) rb_update_small_kernel(const UpdateArgs a
         const int64_t dst_row = s_dst[par];
         if (dst_row >= 0) {
             t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+            if (tile == 0 && tid == 0) { a.buf_y[dst_row] = dst_row / a.S; count_moved(a.state); }
         }
     }
 }
@@ -335,7 +335,7 @@ __global__ void __launch_bounds__(TPB) rb_sample_small_kernel(const SampleArgs a
         Tile<U, NT> t2;
         t2.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
         t2.store(a.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
-        if (tile == 0 && tid == 0) a.out_y[j] = pk;
+        if (tile == 0 && tid == 0) { a.out_y[j] = pk; count_moved(a.state); }
     }
 }
 
@@ -452,7 +452,7 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
         const int64_t dst_row = s_dst;
         if (dst_row >= 0) {
             t.store(a.buf_x + dst_row * a.row_vec, v_lo, v_hi);
-            if (tile == 0 && tid == 0) a.buf_y[dst_row] = dst_row / a.S;
+            if (tile == 0 && tid == 0) { a.buf_y[dst_row] = dst_row / a.S; count_moved(a.state); }
         }
         return;
     }
@@ -557,7 +557,7 @@ __global__ void __launch_bounds__(TPB) rb_step_small_kernel(const StepArgs sa)
     Tile<U, NT> t;
     t.load(src, v_lo, v_hi);
     t.store(sa.out_x + (int64_t)j * a.row_vec, v_lo, v_hi);
-    if (tile == 0 && tid == 0) sa.out_y[j] = pk;
+    if (tile == 0 && tid == 0) { sa.out_y[j] = pk; count_moved(a.state); }
 }
 
 }  // namespace

@@ -549,7 +549,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         for (int q = en.chain; q >= 0;) {
             const WinEntry rq = entry[q];
             const int qs = q / rows, qj = q % rows - m.c;
-            if (first) m.out_y[qs][qj] = rq.label;
+            if (first) { m.out_y[qs][qj] = rq.label; count_moved(m.state); }
             Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> old;
             old.load(slot, v_lo, v_hi);
             old.store(m.out_x[qs] + (int64_t)qj * m.row_vec * WIDE, v_lo, v_hi);
@@ -558,7 +558,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         // Lanes past the end of a tile move its last vector again, so a vector may be read by one
         // wavefront and overwritten by another: everybody has read before anybody overwrites.
         if (en.chain >= 0) __syncthreads();
-        if (first) m.buf_y[en.row] = en.label;
+        if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
         Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
         t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE, v_lo, v_hi);
         t.store(slot, v_lo, v_hi);
@@ -568,6 +568,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
     const int j = e - m.c;
     if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
+    if (first) count_moved(m.state);
     vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
     if (BF16 && en.src >= 0) {
         // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16

@@ -33,7 +33,8 @@ class Workload:
     r: int                    # representatives per augmented mini-batch
     steps: int
     values: str               # "normal" (N(0,1)) or "uniform" (U(0,1))
-    labels: str               # "uniform", "zipf" (P(k) ~ (k+1)^-1.1) or "active50"
+    labels: str               # "uniform", "zipf" (P(k) ~ (k+1)^-1.1), "active50" (50 classes drawn afresh every step)
+                              # or "fixed50" (one set of 50 classes for the whole run)
     lib_seed: int = 0         # seed handed to rb_update / rb_sample_augment
 
     @property
@@ -69,10 +70,15 @@ C3 = Workload("C3-1000x130-f32-3x224x224", 3, 1000, 130, (3, 224, 224), "f32", 6
 C4 = Workload("C4-1000x300-bf16-3x224x224-zipf", 4, 1000, 300, (3, 224, 224), "bf16", 512, 64, 64, 2000, "uniform", "zipf")
 C5 = Workload("C5-10000x1000-f32-2048-active50", 5, 10000, 1000, (2048,), "f32", 4096, 1024, 1024, 500, "normal", "active50")
 CONFIGS = (C1, C2, C3, C4, C5)
+# C5 with ONE set of 50 active classes for the whole run (the configured C5 draws a fresh set every step, so its
+# classes never fill): 1024 candidates per step into 50 classes of 1000 slots, which are all full after about 50
+# steps; from then on every step overwrites about 20 slots per class and several candidates share a slot.
+C5F = Workload("C5F-10000x1000-f32-2048-fixed50", 5, 10000, 1000, (2048,), "f32", 4096, 1024, 1024, 500, "normal", "fixed50")
+EXTRA = (C5F,)
 
 
 def by_name(name: str) -> Workload:
-    for w in CONFIGS:
+    for w in CONFIGS + EXTRA:
         if w.name == name or w.name.split("-")[0] == name:
             return w
     raise KeyError(name)
@@ -114,6 +120,13 @@ def make_labels(w: Workload, step: int, device="cpu") -> torch.Tensor:
     if w.labels == "active50":
         n_active = min(50, w.K)
         active = torch.randperm(w.K, generator=g, device=device)[:n_active]
+        pick = torch.randint(0, n_active, (w.b,), generator=g, device=device)
+        return active[pick].to(torch.int64)
+    if w.labels == "fixed50":
+        n_active = min(50, w.K)
+        g0 = torch.Generator(device=device)
+        g0.manual_seed((1000 + w.wid) * 1_000_003 + 999_983)      # the same set in every step
+        active = torch.randperm(w.K, generator=g0, device=device)[:n_active]
         pick = torch.randint(0, n_active, (w.b,), generator=g, device=device)
         return active[pick].to(torch.int64)
     raise ValueError(w.labels)

@@ -16,7 +16,10 @@ from parity_util import SENTINEL, compare_buffers, run_ahead_parity, run_many_pa
 
 pytestmark = pytest.mark.gpu
 
-FULL = os.environ.get("RB_FULL", "0") == "1"      # run the large workloads for all their steps
+# The three large workloads run for ALL their configured steps (2000 / 2000 / 500) through the two calls and through
+# the call form the bench times (announced several-steps calls for C3 and C4, announced single steps for C5); the
+# other call forms run them for fewer steps unless RB_FULL=1 asks for everything.
+FULL = os.environ.get("RB_FULL", "0") == "1"
 
 
 @pytest.fixture(autouse=True)
@@ -41,11 +44,19 @@ def test_c2_all_steps():
     run_parity(wl.C2, check_state_every=250, progress=250)
 
 
-@pytest.mark.parametrize("w,steps", [(wl.C3, 120), (wl.C4, 50), (wl.C5, 40)], ids=["C3", "C4", "C5"])
-def test_full_size_workloads(w, steps):
-    """Real shapes (78-90 GB buffers) in the launch configuration the bench times."""
-    print(f"\n{w.name}: buffer {w.buffer_bytes / 1e9:.1f} GB", flush=True)
-    run_parity(w, steps=w.steps if FULL else steps, progress=10 if not FULL else 100)
+@pytest.mark.parametrize("w", [wl.C3, wl.C4, wl.C5], ids=["C3", "C4", "C5"])
+def test_full_size_workloads(w):
+    """Real shapes (78-90 GB buffers), every configured step, rb_update + rb_sample_augment."""
+    print(f"\n{w.name}: buffer {w.buffer_bytes / 1e9:.1f} GB, {w.steps} steps", flush=True)
+    run_parity(w, steps=w.steps, progress=100)
+
+
+def test_c5_with_one_fixed_set_of_active_classes():
+    """C5's shape with the same 50 active classes in every step: they are full after about 50 steps, then every
+    step overwrites about 20 slots of each and several candidates share a slot (the configured C5, whose active
+    classes change every step, never fills a class).  The two general kernels, all 500 steps."""
+    buf, orc = run_parity(wl.C5F, steps=wl.C5F.steps, progress=100)
+    assert int((orc.fill == wl.C5F.S).sum()) == 50
 
 
 def test_c3_on_a_side_stream():
@@ -321,9 +332,10 @@ def test_plan_ahead_with_large_counts_drops_and_flags_bad_labels():
     compare_buffers(buf, orc, "bad labels, large counts")
 
 
-@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40), (wl.C5, 12)], ids=["C3", "C4", "C5"])
+@pytest.mark.parametrize("w,steps", [(wl.C3, 60), (wl.C4, 40), (wl.C5, wl.C5.steps), (wl.C5F, wl.C5F.steps)], ids=["C3", "C4", "C5", "C5F"])
 def test_plan_ahead_at_full_size(w, steps):
-    """The configuration the bench times: real shapes, one launch per step, next labels announced."""
+    """Real shapes, one launch per step, next labels announced; C5 (the form the bench times it in) and its
+    variant with a fixed set of active classes for all their steps."""
     run_ahead_parity(w, w.steps if FULL else steps)
 
 
@@ -454,8 +466,9 @@ def test_many_steps_from_one_call(w, window):
 @pytest.mark.parametrize("announce", [False, True], ids=["plain", "announced"])
 @pytest.mark.parametrize("w,steps", [(wl.C3, 72), (wl.C4, 48)], ids=["C3", "C4"])
 def test_many_steps_at_full_size(w, steps, announce):
-    """The configuration the bench times: real shapes, 16 (C3) or 8 (C4) steps per launch, calls announced."""
-    run_many_parity(w, w.steps if FULL else steps, per_call=32 if announce else 24, announce=announce)
+    """The configuration the bench times: real shapes, 16 (C3) or 8 (C4) steps per launch, calls announced: every
+    configured step.  Without the announcement: a shorter run."""
+    run_many_parity(w, w.steps if FULL or announce else steps, per_call=32 if announce else 24, announce=announce)
 
 
 @pytest.mark.parametrize("w,steps,per_call", [
@@ -667,6 +680,124 @@ def test_pipelined_primitive_returns_the_previous_iterations_representatives(w, 
             want = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
     compare_buffers(buf, orc, f"{w.name} final")
     pipe.close()
+
+
+@pytest.mark.parametrize("w,steps,group,announce", [
+    (wl.variant(wl.C2, name="C2-pipeline-many", S=6), 64, 16, True),                            # 16 steps per launch, planned by the call before
+    (wl.variant(wl.C3, name="C3-pipeline-many", K=50, S=6), 40, 8, True),                       # full-size rows; windows of 8
+    (wl.variant(wl.C4, name="C4-pipeline-many", S=2, shape=(3, 32, 32)), 30, 7, False),         # every call plans its own first window
+    (wl.variant(wl.C5, name="C5-pipeline-many", K=300, S=12, shape=(256,), b=512, c=200, r=150), 24, 6, True),   # steps go out one by one
+], ids=["C2", "C3-rows", "C4-S2", "one-by-one"])
+def test_pipelined_primitive_with_several_iterations_per_call(w, steps, group, announce):
+    """One rb_pipeline_step_many call per `group` training iterations: the first iteration of a group trains (a
+    stand-in) while the group's launch runs on the buffer's stream, the others after rb_pipeline_drain; every
+    iteration must see exactly the representatives that the step before it sampled."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    side = torch.cuda.Stream(dev)
+    train = torch.cuda.current_stream(dev)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=side)
+    pipe = rb.Pipeline(buf)
+    orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+    # one augmented mini-batch per iteration (the data pipeline is `group` iterations ahead, and one group more when it announces)
+    aug_x = torch.empty((steps + 1, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=dev)
+    aug_y = torch.empty((steps + 1, w.b + w.r), dtype=torch.int64, device=dev)
+    sink = torch.empty(64 * 256, dtype=torch.float32, device=dev)
+    produced = 0
+
+    def produce(upto):
+        nonlocal produced
+        for t in range(produced, min(upto, steps)):
+            x, y = wl.make_batch(w, t, dev)
+            aug_x[t, :w.b].copy_(x)
+            aug_y[t, :w.b].copy_(y)
+            parity_util._bytes(aug_x[t + 1, w.b:]).fill_(parity_util.SENTINEL)     # where iteration t's sampling goes
+            aug_y[t + 1, w.b:].fill_(-7)
+        produced = max(produced, min(upto, steps))
+
+    want = {}
+
+    def check(t):
+        """Iteration t reads its representatives on the training stream."""
+        if t == 0:
+            return
+        n, ref_x, ref_y = want.pop(t)
+        assert np.array_equal(aug_y[t, w.b:].cpu().numpy(), ref_y), f"{w.name} iteration {t}: labels of the representatives differ"
+        assert np.array_equal(parity_util._bytes(aug_x[t, w.b:]).cpu().numpy(), ref_x), f"{w.name} iteration {t}: representatives differ (n={n})"
+
+    for g in range(0, steps, group):
+        n = min(group, steps - g)
+        produce(g + n + (group if announce else 0))
+        if announce and g + n < steps:
+            buf.announce_next_many([aug_y[t, :w.b] for t in range(g + n, min(g + 2 * n, steps))][:16])
+        ts = range(g, g + n)
+        rows = pipe.step_many([aug_x[t, :w.b] for t in ts], [aug_y[t, :w.b] for t in ts], w.c, w.r, w.lib_seed, g,
+                              [aug_x[t + 1, w.b:] for t in ts], [aug_y[t + 1, w.b:] for t in ts], train_stream=train)
+        assert rows == (0 if g == 0 else w.r)
+        assert rb.rb_standin_compute(train, sink, 64, 2000) == rb.RB_OK     # iteration g's "forward and backward pass"
+        check(g)
+        for t in ts:
+            orc.update(parity_util._bytes(aug_x[t, :w.b]).cpu().numpy(), aug_y[t, :w.b].cpu().numpy(), w.c, w.lib_seed, t)
+            ref = np.full((w.r, w.row_bytes), parity_util.SENTINEL, dtype=np.uint8)
+            want[t + 1] = orc.sample_augment(w.r, w.lib_seed, t, out_x=ref)
+        assert pipe.drain(train) == w.r
+        for t in range(g + 1, g + n):
+            assert rb.rb_standin_compute(train, sink, 64, 500) == rb.RB_OK
+            check(t)
+    check(steps)                                    # what the last step sampled (drained above)
+    compare_buffers(buf, orc, f"{w.name} final")
+    # argument checks: nothing enqueued, pipeline unchanged
+    bad = [aug_x[0, :w.b], aug_x[1, :w.b].data_ptr() + 4]
+    rc, _ = rb.rb_pipeline_step_many(pipe.handle, 2, bad, [aug_y[0, :w.b], aug_y[1, :w.b]], w.b, w.c, w.r, w.lib_seed, steps,
+                                     [aug_x[1, w.b:], aug_x[2, w.b:]], [aug_y[1, w.b:], aug_y[2, w.b:]], train)
+    assert rc == rb.RB_EINVAL
+    assert rb.rb_pipeline_step_many(pipe.handle, 0, [], [], w.b, w.c, w.r, w.lib_seed, steps, [], [], train) == (rb.RB_OK, w.r)
+    assert rb.rb_pipeline_step_many(None, 0, [], [], w.b, w.c, w.r, w.lib_seed, steps, [], [], train)[0] == rb.RB_EINVAL
+    torch.cuda.synchronize()
+    compare_buffers(buf, orc, f"{w.name} after rejected calls")
+    pipe.close()
+
+
+def test_moved_rows_counter_counts_stored_candidates_and_representatives():
+    """rb_read_moved_rows against the oracle's record of every step, through each family of kernels."""
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    for w, style in [(wl.variant(wl.C1, name="C1-moved"), "two"), (wl.variant(wl.C1, name="C1-moved-single"), "single"),
+                     (wl.variant(wl.C1, name="C1-moved-ahead"), "ahead"), (wl.variant(wl.C1, name="C1-moved-many"), "many"),
+                     (wl.variant(wl.C5, name="C5-moved", K=20, S=8, shape=(64,), b=512, c=200, r=150), "two"),
+                     (wl.variant(wl.C5, name="C5-moved-ahead", K=20, S=8, shape=(64,), b=512, c=200, r=150), "ahead")]:
+        buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
+        orc = rbo.Buffer(w.K, w.S, w.row_bytes)
+        steps = 48
+        batches = [wl.make_batch(w, t, dev) for t in range(steps + 1)]
+        xs, ys = [x.contiguous() for x, _ in batches], [y.contiguous() for _, y in batches]
+        oxs = [torch.empty((w.r, *w.shape), dtype=w.torch_dtype, device=dev) for _ in range(steps)]
+        oys = [torch.empty(w.r, dtype=torch.int64, device=dev) for _ in range(steps)]
+        expect = 0
+        for t in range(steps):
+            orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), w.c, w.lib_seed, t)
+            pos, cls, slot = orc.last_insertions()
+            expect += len(set(zip(cls.tolist(), slot.tolist())))      # of the insertions into one slot only the last is moved
+            expect += orc.sample_augment(w.r, w.lib_seed, t)[0]
+        if style == "many":
+            for first in range(0, steps, 16):
+                buf.update_sample_many(xs[first:first + 16], ys[first:first + 16], w.c, w.r, w.lib_seed, first, oxs[first:first + 16], oys[first:first + 16])
+        else:
+            for t in range(steps):
+                if style == "two":
+                    buf.update(xs[t], ys[t], w.c, w.lib_seed, t)
+                    buf.sample_augment(w.r, w.lib_seed, t, oxs[t], oys[t])
+                else:
+                    if style == "ahead":
+                        buf.announce_next(ys[t + 1])
+                    buf.update_sample(xs[t], ys[t], w.c, w.r, w.lib_seed, t, oxs[t], oys[t])
+        if style == "many":
+            # within a launch of several steps a slot written twice is moved once, and the oracle's per-step count is an upper bound
+            assert buf.moved_rows() <= expect, (w.name, style)
+            assert buf.moved_rows() >= expect - steps * w.c
+        else:
+            assert buf.moved_rows() == expect, (w.name, style, buf.moved_rows(), expect)
+        assert rb.rb_read_moved_rows(None)[0] == rb.RB_EINVAL
 
 
 def test_pipeline_argument_checks_leave_it_unchanged():

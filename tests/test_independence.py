@@ -42,8 +42,8 @@ def test_oracle_never_touches_the_hip_path():
             assert "paper_2406_03285_amd" not in name and name.lstrip(".") != "torch", f"{path} imports {name}"
     for path in _files(ORACLE, (".c", ".h")):
         for inc in re.findall(r'#\s*include\s*[<"]([^>"]+)[>"]', open(path).read()):
-            assert inc.startswith(("std", "string", "math", "limits", "assert")) or inc in ("stdint.h", "stddef.h"), \
-                f"{path} includes {inc}: only the C library"
+            assert inc.startswith(("std", "string", "math", "limits", "assert")) or inc in ("stdint.h", "stddef.h", "pthread.h"), \
+                f"{path} includes {inc}: only the C library (and POSIX threads for the timing variant)"
 
 
 def test_bench_reaches_the_oracle_only_in_its_cpu_baseline():
@@ -52,7 +52,7 @@ def test_bench_reaches_the_oracle_only_in_its_cpu_baseline():
     for node in ast.walk(tree):
         if isinstance(node, ast.FunctionDef):
             uses = [n for n, _ in _imports_in(node) if n.lstrip(".").startswith("oracle")]
-            assert not uses or node.name == "cpu_baseline", f"bench.py:{node.name} imports the oracle"
+            assert not uses or node.name.startswith("cpu_baseline"), f"bench.py:{node.name} imports the oracle"
     top = [n for n, node in _imports(path) if n.lstrip(".").startswith("oracle") and node.col_offset == 0]
     assert not top, "bench.py imports the oracle at module level"
 
