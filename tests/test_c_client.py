@@ -69,7 +69,7 @@ def test_a_c_program_drives_the_gpu_path(tmp_path, K, S, vecs, b, c, r, steps):
     rng = np.random.default_rng(K * 1000 + S)
     xs = rng.integers(0, 256, (steps, b, row_bytes), dtype=np.uint8)
     ys = rng.integers(0, K, (steps, b)).astype(np.int64)
-    ys[steps // 3, 1] = K + 2                       # a label outside [0, K): dropped and flagged
+    ys[steps // 3, :] = K + 2                       # labels outside [0, K): every candidate of this step is dropped and flagged
     with open(tmp_path / "in.bin", "wb") as f:
         f.write(np.array([K, S, row_bytes, b, c, r, steps, seed], dtype=np.int64).tobytes())
         for t in range(steps):
