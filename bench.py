@@ -601,12 +601,17 @@ def main():
         # (regions of at least 256 steps: with fewer, a region is one or two launches and mostly their start and end)
         orig, ores = measure(ow, torch, rb, wl, max(256, min(a.steps, ow.steps)), a.warmup, False)
         ores["steps_per_region"] = max(256, min(a.steps, ow.steps))
-        if ow.name.startswith("C3") and not a.no_variants:
-            sweeps[ow.name] = rows_per_call_sweep(orig)
         if ow.name.startswith("C3") and not a.no_overlap:
             ores["overlap"] = {f"fma_{d}ms": overlap_leg(orig, 200, d) for d in (0.5, 2.0, 10.0)}
             ores["overlap"]["hbm_copy_0.3ms"] = overlap_leg(orig, 200, 0.3, kind="hbm")
         orig.close()
+        if ow.name.startswith("C3") and not a.no_variants:
+            # the sweep at this row size needs room for 64 representatives behind every pooled mini-batch
+            srig = Rig(wl.variant(ow, r=64), torch, rb, wl)
+            srig.enqueue(MANY, many=MANY, ahead=True)
+            sweeps[ow.name] = rows_per_call_sweep(srig)
+            srig.close()
+            log(f"[bench] rows-per-call sweep {json.dumps(sweeps[ow.name])}")
         others[ow.name] = rounded(ores)
         log(f"[bench] {json.dumps(others[ow.name])}")
 

@@ -1108,9 +1108,12 @@ int rb_read_moved_rows(rb_buffer* rb, uint64_t* rows_host)
     if (!rb->bound) return RB_ESTATE;
     discard_plan(rb);
     if (hipStreamSynchronize(rb->stream) != hipSuccess) return RB_EHIP;
-    DevState st;
-    if (hipMemcpy(&st, rb->ws, sizeof st, hipMemcpyDeviceToHost) != hipSuccess) return RB_EHIP;
-    *rows_host = st.moved_rows;
+    static_assert(MOVED_STRIDE % sizeof(uint64_t) == 0, "counters are read as an array of 64-bit words");
+    uint64_t words[MOVED_COUNTERS * MOVED_STRIDE / sizeof(uint64_t)];
+    if (hipMemcpy(words, rb->ws + STATE_HEAD_BYTES, sizeof words, hipMemcpyDeviceToHost) != hipSuccess) return RB_EHIP;
+    uint64_t sum = 0;
+    for (int i = 0; i < MOVED_COUNTERS; ++i) sum += words[i * (MOVED_STRIDE / sizeof(uint64_t))];
+    *rows_host = sum;
     return RB_OK;
 }
 
