@@ -50,7 +50,8 @@ enum rb_status {
     RB_EINVAL = -1,   /* an argument is out of range, null or misaligned          */
     RB_ENOMEM = -2,   /* host allocation of the handle failed                     */
     RB_ESTATE = -3,   /* hot call before rb_bind                                  */
-    RB_EHIP = -4      /* a HIP call (launch, copy, synchronise) reported an error */
+    RB_EHIP = -4,     /* a HIP call (launch, copy, synchronise) reported an error */
+    RB_ELIMIT = -5    /* rb_bind_static: the buffer's workspace exceeds the library's own scratch */
 };
 
 #define RB_MAX_BATCH 4096          /* largest b, c and r accepted                          */
@@ -124,6 +125,31 @@ int rb_set_storage(rb_buffer *rb, int32_t storage);
 enum rb_selection { RB_SELECT_EXACT = 0, RB_SELECT_BERNOULLI = 1 };
 enum rb_eviction { RB_EVICT_UNIFORM = 0, RB_EVICT_FIFO = 1, RB_EVICT_RESERVOIR = 2 };
 int rb_set_policy(rb_buffer *rb, int32_t selection, int32_t eviction);
+
+/*
+ * rb_bind for callers that cannot allocate device memory at this point (code
+ * under HIP graph capture, tight serving loops, harnesses that forbid
+ * hipMalloc): the same call, but the workspace is a scratch array of
+ * RB_STATIC_WORKSPACE_BYTES that the library itself holds in device memory
+ * (a file-scope array of the loaded code object: one copy per GPU, from the
+ * moment the library is loaded on that GPU until the process ends).  The call
+ * allocates nothing, on the device or through any library; buf_x, buf_y and
+ * every later input and output are still the caller's.  All later calls on the
+ * handle work as after rb_bind.
+ * Every handle bound this way on one GPU uses that GPU's one array, which keeps
+ * whatever the last user left: the call clears the part it uses (fill counts,
+ * state words, plan tables) on the stream, like rb_bind, and takes the array
+ * away from the handle that held it before (that handle is unbound: its hot
+ * calls return RB_ESTATE until it is bound again).  Work of the previous
+ * holder that is still running on another stream when this call's clearing
+ * runs would race with it: the caller orders the two (one handle at a time per
+ * GPU, or a synchronisation in between).
+ * RB_ELIMIT: the handle needs more workspace than RB_STATIC_WORKSPACE_BYTES
+ * (rb_query_sizes tells how much: about 16 bytes per class plus 0.1 MB);
+ * otherwise the errors of rb_bind.
+ */
+#define RB_STATIC_WORKSPACE_BYTES (4u << 20)
+int rb_bind_static(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *hip_stream);
 
 /* Replace the stream later calls enqueue on.  The caller orders the old and
  * the new stream itself (events) if work is still pending on the old one. */

@@ -13,7 +13,8 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RB_LIBRARY") or os.path.join(HERE, "librb.so")   # RB_LIBRARY: another build of the same library
 
 RB_F32, RB_BF16 = 0, 1
-RB_OK, RB_EINVAL, RB_ENOMEM, RB_ESTATE, RB_EHIP = 0, -1, -2, -3, -4
+RB_OK, RB_EINVAL, RB_ENOMEM, RB_ESTATE, RB_EHIP, RB_ELIMIT = 0, -1, -2, -3, -4, -5
+RB_STATIC_WORKSPACE_BYTES = 4 << 20
 RB_MAX_BATCH = 4096
 RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
@@ -23,7 +24,7 @@ RB_STORE_SAME, RB_STORE_BF16 = 0, 1
 RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
-    "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
+    "rb_create", "rb_query_sizes", "rb_set_storage", "rb_bind", "rb_bind_static", "rb_set_policy", "rb_set_stream", "rb_update", "rb_sample_augment", "rb_update_sample",
     "rb_announce_next", "rb_announce_next_many", "rb_query_steps_per_launch", "rb_update_sample_many", "rb_pipeline_create", "rb_pipeline_step", "rb_pipeline_step_many", "rb_pipeline_drain", "rb_pipeline_destroy",
     "rb_read_state", "rb_read_moved_rows", "rb_set_option", "rb_destroy", "rb_strerror", "rb_standin_compute", "rb_copy_bytes",
 )
@@ -45,6 +46,7 @@ def _load():
     L.rb_create.argtypes = [C.POINTER(vp), i64, i64, C.POINTER(i64), i32, i32]
     L.rb_query_sizes.argtypes = [vp, C.POINTER(sz), C.POINTER(sz), C.POINTER(sz)]
     L.rb_bind.argtypes = [vp, vp, vp, vp, vp]
+    L.rb_bind_static.argtypes = [vp, vp, vp, vp]
     L.rb_set_policy.argtypes = [vp, i32, i32]
     L.rb_set_storage.argtypes = [vp, i32]
     L.rb_set_stream.argtypes = [vp, vp]
@@ -114,6 +116,10 @@ def rb_query_sizes(rb):
 
 def rb_bind(rb, buf_x, buf_y, workspace, hip_stream=None):
     return _L.rb_bind(rb, _ptr(buf_x), _ptr(buf_y), _ptr(workspace), _stream(hip_stream))
+
+
+def rb_bind_static(rb, buf_x, buf_y, hip_stream=None):
+    return _L.rb_bind_static(rb, _ptr(buf_x), _ptr(buf_y), _stream(hip_stream))
 
 
 def rb_set_storage(rb, storage):
@@ -249,11 +255,12 @@ class RehearsalBuffer:
     """
 
     def __init__(self, classes, slots_per_class, sample_shape, dtype=torch.float32, device="cuda:0", stream=None,
-                 storage="hbm", store_dtype=None):
+                 storage="hbm", store_dtype=None, static_workspace=False):
         """storage: "hbm" keeps the sample rows in device memory; "host_pinned" keeps them in pinned host
         memory that the kernels read and write directly over the host link (where the paper keeps its
         buffers, Sec. IV-C); labels and workspace stay on the device either way.
-        store_dtype: None keeps rows as they come; torch.bfloat16 with dtype float32 stores them at half size."""
+        store_dtype: None keeps rows as they come; torch.bfloat16 with dtype float32 stores them at half size.
+        static_workspace: bind with rb_bind_static (the library's own scratch array instead of a workspace tensor)."""
         code = {torch.float32: RB_F32, torch.bfloat16: RB_BF16}[dtype]
         rc, self.handle = rb_create(classes, slots_per_class, tuple(sample_shape), code)
         _check(rc, "rb_create")
@@ -275,10 +282,14 @@ class RehearsalBuffer:
             raise ValueError(storage)
         self.storage = storage
         self.buf_y = torch.empty((self.K, self.S), dtype=torch.int64, device=self.device)
-        self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
         assert self.buf_x.numel() * self.buf_x.element_size() == xb and self.buf_y.numel() * 8 == yb
         self.stream = stream
-        _check(rb_bind(self.handle, self.buf_x, self.buf_y, self.workspace, stream), "rb_bind")
+        if static_workspace:
+            self.workspace = None
+            _check(rb_bind_static(self.handle, self.buf_x, self.buf_y, stream), "rb_bind_static")
+        else:
+            self.workspace = torch.empty(wb, dtype=torch.uint8, device=self.device)
+            _check(rb_bind(self.handle, self.buf_x, self.buf_y, self.workspace, stream), "rb_bind")
 
     def set_policy(self, selection, eviction):
         _check(rb_set_policy(self.handle, selection, eviction), "rb_set_policy")

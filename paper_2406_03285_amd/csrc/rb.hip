@@ -84,9 +84,19 @@ struct rb_buffer {
     uint64_t wplan_seed, wplan_first;
     int wplan_tbl;           // table that holds it
     int64_t wplan_nat;       // size the windows have grown to (the planned one may be shorter: what was left, what was announced)
+    int static_dev;          // device whose static scratch array is this handle's workspace, -1: the caller's workspace
 };
 
+// Workspace of rb_bind_static: callers that cannot allocate get their workspace from here.  One copy per GPU
+// that loads this library, at an address of its own on each; in host code the array's name only stands for the
+// symbol (it is no device address), so the address is asked for once per device and kept.
+static __device__ __align__(256) unsigned char scratch[RB_STATIC_WORKSPACE_BYTES];
+
 namespace {
+
+constexpr int MAX_DEVICES = 64;
+void* scratch_ptr[MAX_DEVICES] = {};          // device address of `scratch` on each device, once known
+rb_buffer* scratch_holder[MAX_DEVICES] = {};  // the handle that is bound to it
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
@@ -686,6 +696,7 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->nchunks = (int32_t)((classes + CH - 1) / CH);
     rb->buf_x = nullptr; rb->buf_y = nullptr; rb->ws = nullptr; rb->stream = nullptr;
     rb->bound = false;
+    rb->static_dev = -1;
     rb->cur = 0;
     size_t off = STATE_BYTES;
     const size_t fill_bytes = round_up((size_t)rb->nchunks * CH * sizeof(int32_t), 256);
@@ -732,10 +743,20 @@ int rb_set_storage(rb_buffer* rb, int32_t storage)
     return RB_OK;
 }
 
+namespace {
+// The handle no longer uses a device's static scratch array.
+void release_scratch(rb_buffer* rb)
+{
+    if (rb->static_dev >= 0 && scratch_holder[rb->static_dev] == rb) scratch_holder[rb->static_dev] = nullptr;
+    rb->static_dev = -1;
+}
+}  // namespace
+
 int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* hip_stream)
 {
     if (!rb || !buf_x || !buf_y || !workspace) return RB_EINVAL;
     if (!aligned(buf_x, 16) || !aligned(buf_y, 8) || !aligned(workspace, 256)) return RB_EINVAL;
+    if (rb->static_dev >= 0 && workspace != scratch_ptr[rb->static_dev]) release_scratch(rb);
     hipStream_t st = static_cast<hipStream_t>(hip_stream);
     const int64_t slots = rb->K * rb->S;
     int64_t blocks = (slots + TPB - 1) / TPB;
@@ -753,6 +774,35 @@ int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* h
     rb->plan_valid = false; rb->next_y = nullptr; rb->tbl_next = 0;
     rb->ann_n = 0; rb->wplan_valid = false;
     rb->bound = true;
+    return RB_OK;
+}
+
+int rb_bind_static(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* hip_stream)
+{
+    if (!rb || !buf_x || !buf_y) return RB_EINVAL;
+    if (!aligned(buf_x, 16) || !aligned(buf_y, 8)) return RB_EINVAL;
+    if (rb->ws_bytes > sizeof scratch) return RB_ELIMIT;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= MAX_DEVICES) return RB_EHIP;
+    if (!scratch_ptr[dev]) {
+        // first use on this device (which is current): where this device's copy of the array lives
+        void* p = nullptr;
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RB_EHIP;
+        scratch_ptr[dev] = p;
+    }
+    rb_buffer* before = scratch_holder[dev];
+    if (rb->static_dev >= 0 && rb->static_dev != dev) release_scratch(rb);
+    rb->static_dev = dev;                          // (rb_bind keeps the array with this handle)
+    const int rc = rb_bind(rb, buf_x, buf_y, scratch_ptr[dev], hip_stream);   // clears what the handle uses of the array, on the stream
+    if (rc != RB_OK) {
+        if (before != rb) rb->static_dev = -1;
+        return rc;
+    }
+    if (before && before != rb) {                  // the array changes hands: the other handle has no workspace any more
+        before->bound = false;
+        before->static_dev = -1;
+    }
+    scratch_holder[dev] = rb;
     return RB_OK;
 }
 
@@ -1148,6 +1198,7 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
 
 int rb_destroy(rb_buffer* rb)
 {
+    if (rb) release_scratch(rb);
     delete rb;
     return RB_OK;
 }
@@ -1160,6 +1211,7 @@ const char* rb_strerror(int status)
     case RB_ENOMEM: return "out of host memory";
     case RB_ESTATE: return "buffer is not bound to device storage";
     case RB_EHIP: return "a HIP call failed";
+    case RB_ELIMIT: return "the buffer needs more workspace than the library's static scratch array holds";
     default: return "unknown status";
     }
 }
