@@ -633,7 +633,8 @@ def main():
     n_rows = min(w.r, res["last_n"])
     head = res["headline"]
     if res["launches_per_step"] <= 1:
-        kernel = "rb_window_kernel" if res["steps_per_launch"] > 1 else res["plan_ahead_kernel"]
+        small = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
+        kernel = ("rb_window_kernel" if small else "rb_bigwin_kernel") if res["steps_per_launch"] > 1 else res["plan_ahead_kernel"]
         launches = head["n_launches"]
         k_ms = res["ms_per_step"] * a.steps / launches
         k_bytes = 2 * (w.c + n_rows) * w.row_bytes * a.steps / launches

@@ -58,6 +58,9 @@ enum rb_status {
 #define RB_MAX_CLASSES (1 << 20)   /* largest number of classes                            */
 #define RB_MAX_SLOTS 2147483647LL  /* classes * slots_per_class must not exceed this       */
 #define RB_FLAG_BAD_LABEL 1u       /* state flag: a candidate's label was outside [0, K)   */
+#define RB_FLAG_PLAN_TIMEOUT 2u    /* state flag: the workgroups that plan a several-steps launch for large counts
+                                      did not hear from each other within 2 s; that launch moved nothing and the
+                                      buffer's state is no longer defined (bind again) */
 
 /*
  * Describe a buffer of `classes` sub-buffers of `slots_per_class` samples each
@@ -145,7 +148,7 @@ int rb_set_policy(rb_buffer *rb, int32_t selection, int32_t eviction);
  * runs would race with it: the caller orders the two (one handle at a time per
  * GPU, or a synchronisation in between).
  * RB_ELIMIT: the handle needs more workspace than RB_STATIC_WORKSPACE_BYTES
- * (rb_query_sizes tells how much: about 16 bytes per class plus 0.1 MB);
+ * (rb_query_sizes tells how much: about 16 bytes per class plus 1.8 MB);
  * otherwise the errors of rb_bind.
  */
 #define RB_STATIC_WORKSPACE_BYTES (4u << 20)

@@ -35,6 +35,7 @@
 #include "rb_kernels_planned.h"
 #include "rb_kernels_window.h"
 #include "rb_kernels_big.h"
+#include "rb_kernels_bigwin.h"
 #include "rb_kernels_aux.h"
 
 // ===========================================================================
@@ -67,6 +68,9 @@ struct rb_buffer {
     size_t off_tbl[2];       // the two plan tables
     size_t off_wtbl[2];      // the two plan tables of the several-steps-per-launch form (and of the large-count form)
     size_t off_bfwd[2];      // large-count form: the two tables of the slot rows a step writes
+    size_t off_bwtbl[2];     // the two plan tables of the several-steps-per-launch form for large counts
+    uint32_t bw_number;      // number of the last window planned in that form (its planners' flags are set to it)
+    uint32_t bw_table_number[2];   // ... and which window each of the two tables holds
     int tbl_next;            // table the next plan is written to
     int tbl_planned;         // table that holds the pending plan
     bool plan_valid;         // a step has been planned (and the fill counts advanced) but not yet executed
@@ -640,6 +644,149 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     return RB_OK;
 }
 
+template <int U, bool NT, bool BF16>
+hipError_t launch_bigwin_u(const BwMoveArgs& m, const BwPlanArgs& next, dim3 grid, hipStream_t st)
+{
+    const size_t lds = next.w > 0 ? BIG_LDS_BYTES : 0;
+    if (lds != 0) {
+        const hipError_t e = allow_big_lds<&rb_bigwin_kernel<U, NT, BF16>>();
+        if (e != hipSuccess) return e;
+    }
+    rb_bigwin_kernel<U, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next);
+    return hipGetLastError();
+}
+
+template <bool NT, bool BF16>
+hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int unroll, dim3 grid, hipStream_t st)
+{
+    switch (unroll) {
+    case 1: return launch_bigwin_u<1, NT, BF16>(m, next, grid, st);
+    case 2: return launch_bigwin_u<2, NT, BF16>(m, next, grid, st);
+    case 4: return launch_bigwin_u<4, NT, BF16>(m, next, grid, st);
+    default: return launch_bigwin_u<8, NT, BF16>(m, next, grid, st);
+    }
+}
+
+// Whether rb_update_sample_many puts several steps of this shape into one launch of the large-count form, and how
+// many at most (1: it does not).  Shapes that the small form takes (window_limit) are not meant.
+int64_t bigwin_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
+{
+    const bool eligible = c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES && rb->opt_fuse &&
+                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->K * rb->S <= INT64_C(0x7FFFFFFF) &&
+                          rb->S <= INT32_MAX - (int64_t)BW_MAX * RB_MAX_BATCH;
+    if (!eligible) return 1;
+    return std::min<int64_t>(BW_MAX, rb->opt_window);
+}
+
+BwPlanArgs bigwin_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
+                            uint64_t seed, uint64_t first_step, int table)
+{
+    BwPlanArgs p = {};
+    for (int64_t i = 0; i < w; ++i) p.batch_y[i] = batch_y[at + i];
+    p.fill_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_fill[rb->cur]);
+    p.fill_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_fill[rb->cur ^ 1]);
+    p.chunk_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_chunk[rb->cur ^ 1]);
+    p.table = rb->ws + rb->off_bwtbl[table];
+    p.seed_lo = (uint32_t)seed; p.seed_hi = (uint32_t)(seed >> 32);
+    p.first_step = first_step + (uint64_t)at;
+    p.w = (int32_t)w;
+    p.b = (int32_t)b; p.c = (int32_t)c; p.r = (int32_t)r;
+    p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
+    p.S = rb->S;
+    p.eviction = rb->eviction;
+    rb->bw_number += 1;
+    if (rb->bw_number == 0) rb->bw_number = 1;          // 0 is what a cleared flag shows
+    p.number = rb->bw_number;
+    rb->bw_table_number[table] = p.number;
+    p.aux_old = reinterpret_cast<const int32_t*>(rb->ws + rb->off_aux[rb->cur]);
+    p.aux_new = reinterpret_cast<int32_t*>(rb->ws + rb->off_aux[rb->cur ^ 1]);
+    return p;
+}
+
+// n steps of the large-count form as launches of up to BW_MAX steps each: the first 2 w' workgroups of every launch
+// plan the next window of w' steps (rb_kernels_bigwin.h) while the others move the rows of this one.  Bookkeeping as
+// in steps_windowed.  The planners of a window work side by side, so a plan takes about as long whatever the
+// window's size (measured on MI355X, 1024 candidates and representatives of 10000 classes: about 12 us), and the
+// windows can be of full size as soon as one launch moves rows for that long.
+int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
+                 int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
+                 int64_t ann_n, const int64_t* const* ann_y)
+{
+    static_assert(BW_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
+    const int64_t wmax = bigwin_limit(rb, b, c, r);
+    const Shape sh = plan_shape(rb, wmax * (c + r), BIG_GROUP);
+    const double move_us = (double)(c + r) * (double)(rb->row_bytes + rb->sample_bytes) / 5.5e6;
+    int64_t w0 = 1;
+    while (w0 < wmax && move_us * (double)w0 < 12.0) ++w0;
+    if (allow_big_lds<&rb_bigwin_plan_kernel>() != hipSuccess) return RB_EHIP;
+    int64_t at = 0, w;
+    int tbl;
+    bool resume = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
+                  rb->wplan_seed == seed && rb->wplan_first == first_step;
+    for (int64_t k = 0; resume && k < rb->wplan_w; ++k) resume = rb->wplan_y[k] == batch_y[k];
+    if (resume) {
+        w = rb->wplan_w;
+        tbl = rb->wplan_tbl;
+        rb->wplan_valid = false;                // it is being executed
+    } else {
+        discard_window_plan(rb);
+        w = std::min(w0, n);
+        tbl = 0;
+        const BwPlanArgs p = bigwin_plan_args(rb, batch_y, 0, w, b, c, r, seed, first_step, tbl);
+        rb_bigwin_plan_kernel<<<dim3((unsigned)(2 * w)), BIG_TPB, BIG_LDS_BYTES, rb->stream>>>(p);
+        if (hipGetLastError() != hipSuccess) return RB_EHIP;
+        rb->cur ^= 1;
+    }
+    while (at < n) {
+        const int64_t next_at = at + w;
+        int64_t next_w = std::min(wmax, n - next_at);
+        // the last launch of the call plans the first steps of the call that was announced
+        const bool ahead = next_w == 0 && ann_n > 0;
+        if (ahead) next_w = std::min(wmax, ann_n);
+        BwMoveArgs m = {};
+        for (int64_t k = 0; k < w; ++k) {
+            m.batch_x[k] = static_cast<const vec16*>(batch_x[at + k]);
+            m.out_x[k] = static_cast<vec16*>(out_x[at + k]);
+            m.out_y[k] = out_y[at + k];
+        }
+        m.buf_x = static_cast<vec16*>(rb->buf_x);
+        m.buf_y = rb->buf_y;
+        m.table = rb->ws + rb->off_bwtbl[tbl];
+        m.state = reinterpret_cast<DevState*>(rb->ws);
+        m.w = (int32_t)w; m.c = (int32_t)c; m.r = (int32_t)r;
+        m.number = rb->bw_table_number[tbl];
+        m.S = rb->S;
+        m.row_vec = rb->row_vec;
+        m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
+        BwPlanArgs next = {};
+        if (ahead) next = bigwin_plan_args(rb, ann_y, 0, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1);
+        else if (next_w > 0) next = bigwin_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, tbl ^ 1);
+        const int64_t items = w * (c + r) * sh.tpr;
+        const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + 2 * next_w));
+        const bool bf16 = rb->storage == RB_STORE_BF16;
+        hipError_t e;
+        if (rb->opt_nt) e = bf16 ? launch_bigwin<true, true>(m, next, sh.unroll, grid, rb->stream)
+                                 : launch_bigwin<true, false>(m, next, sh.unroll, grid, rb->stream);
+        else e = bf16 ? launch_bigwin<false, true>(m, next, sh.unroll, grid, rb->stream)
+                      : launch_bigwin<false, false>(m, next, sh.unroll, grid, rb->stream);
+        if (e != hipSuccess) return RB_EHIP;
+        if (next_w > 0) rb->cur ^= 1;
+        if (ahead) {
+            rb->wplan_valid = true;
+            rb->wplan_w = next_w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
+            rb->wplan_seed = seed; rb->wplan_first = first_step + (uint64_t)n;
+            rb->wplan_tbl = tbl ^ 1;
+            rb->wplan_nat = wmax;
+            for (int64_t k = 0; k < next_w; ++k) rb->wplan_y[k] = ann_y[k];
+        }
+        at = next_at;
+        w = ahead ? 0 : next_w;
+        tbl ^= 1;
+    }
+    rb->updates += n;
+    return RB_OK;
+}
+
 // What the host can check of the arguments of one update + sample step.
 int check_step(const rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t b, int64_t c, int64_t r,
                const void* out_x, const int64_t* out_y)
@@ -713,6 +860,9 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->off_wtbl[1] = off; off += WIN_TABLE_BYTES;
     rb->off_bfwd[0] = off; off += BIG_FWD_BYTES;
     rb->off_bfwd[1] = off; off += BIG_FWD_BYTES;
+    rb->off_bwtbl[0] = off; off += BW_TABLE_BYTES;
+    rb->off_bwtbl[1] = off; off += BW_TABLE_BYTES;
+    rb->bw_number = 0; rb->bw_table_number[0] = 0; rb->bw_table_number[1] = 0;
     rb->ws_bytes = off;
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
     rb->ann_n = 0; rb->wplan_valid = false; rb->wplan_tbl = 0;
@@ -773,6 +923,7 @@ int rb_bind(rb_buffer* rb, void* buf_x, int64_t* buf_y, void* workspace, void* h
     rb->updates = 0;
     rb->plan_valid = false; rb->next_y = nullptr; rb->tbl_next = 0;
     rb->ann_n = 0; rb->wplan_valid = false;
+    rb->bw_number = 0; rb->bw_table_number[0] = 0; rb->bw_table_number[1] = 0;     // (the reset clears the planners' flags)
     rb->bound = true;
     return RB_OK;
 }
@@ -984,6 +1135,7 @@ int rb_query_steps_per_launch(const rb_buffer* rb, int64_t b, int64_t c, int64_t
     if (!rb || !steps) return RB_EINVAL;
     if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b || r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
     *steps = window_limit(rb, b, c, r);
+    if (*steps == 1) *steps = bigwin_limit(rb, b, c, r);
     return RB_OK;
 }
 
@@ -1021,6 +1173,14 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
         }
         rb->next_y = nullptr;
         return steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
+    }
+    if (n >= 2 && bigwin_limit(rb, b, c, r) >= 2) {
+        if (rb->plan_valid) {
+            rb->cur ^= 1;
+            rb->plan_valid = false;
+        }
+        rb->next_y = nullptr;
+        return steps_bigwin(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
     }
     discard_window_plan(rb);
     for (int64_t i = 0; i < n; ++i) {

@@ -1,0 +1,661 @@
+// Several steps per launch for large counts (rb_update_sample_many with up to 1024 candidates and
+// representatives, up to 10240 classes, exact selection; any replacement strategy, either storage form).
+// As in rb_kernels_window.h a launch moves the rows of all steps of a window by a table that extra
+// workgroups of the launch before made; as in rb_kernels_big.h those workgroups have 1024 threads, one per
+// candidate or representative, and there are two per step (update, sampling).  The 2 w planners of a window of
+// w steps run side by side and tell each other, through the workspace, the little that one step needs of
+// the others:
+//   A  every update planner selects its step's candidates and publishes their classes.  The fill counts at
+//      the start of step s are the counts before the window plus the candidates that the steps before s bring
+//      (cut off at the capacity: min(min(f + a, S) + b, S) = min(f + a + b, S)), and the per-class state of the
+//      FIFO / reservoir strategies follows from the same sums in closed form; so a planner waits for the
+//      classes of the steps before its own and needs nothing else of them to plan its step as
+//      rb_kernels_big.h does;
+//   B  every planner writes its step's table entries, and publishes a hash table of the slot rows its step
+//      writes (update) or reads (sampling);
+//   C  what the order of separate launches would settle between steps (rb_kernels_window.h) every planner
+//      settles for its OWN entries by looking rows up in the other steps' tables: a representative whose slot
+//      an earlier step of the window (or its own) writes is copied from the mini-batch row stored there; of
+//      several writes to one slot only the last is carried out; and a representative that needs what a slot
+//      held before the window while a later step overwrites it is left to the workgroups that carry out that
+//      write (they find it through the step's table of rows read and copy the old content out first).
+// What planners read of each other (classes, row tables, flags) is written with stores that go through to
+// memory and read with loads that do not stop at a cache of their own die (agent-scope atomics: the dies of
+// the chip do not see each other's caches), and a flag is set only when the stores before it have been
+// acknowledged; the table entries have one writer each and are only read by the next launch.  No cache is
+// written back or invalidated as a whole: with the movers' traffic in them that took longer than the plan.
+// The planners are the first workgroups of their launch, which starts when the launch before has ended: they
+// are all resident from the start and never wait for a workgroup that has not been dispatched.  Every wait is
+// bounded all the same (BW_TIMEOUT_TICKS): a planner that gives up marks the window's table as failed, the
+// window's launch then moves nothing and raises RB_FLAG_PLAN_TIMEOUT.
+// Included by rb.hip only, after rb_kernels_window.h (table entry format) and rb_kernels_big.h (selection, hash tables).
+#pragma once
+
+#include "rb_device.h"
+#include "rb_kernels_window.h"
+#include "rb_kernels_big.h"
+
+namespace {
+
+constexpr int BW_MAX = 8;                           // most steps one launch covers
+constexpr uint64_t BW_TIMEOUT_TICKS = 200000000ull; // bound of every wait: 2 s of the 100 MHz wall clock
+constexpr uint32_t BW_MISSING = 0xFFFFFFFFu;        // bw_lookup: the row is not in the table
+
+// The table of one window in the workspace (two of them, used in turn).
+struct BwFlags {
+    uint32_t classes[BW_MAX];   // = the window's number once step s's candidate classes are published (A)
+    uint32_t update[BW_MAX];    // ... once step s's update planner has published entries and write table (B)
+    uint32_t sample[BW_MAX];    // ... once step s's sampling planner has published entries and read table (B)
+    uint32_t failed;            // = the window's number if a planner gave up waiting
+    uint32_t pad[7];
+};
+constexpr size_t BW_OFF_HEAD = 0;                                                    // BW_MAX WinHeader
+constexpr size_t BW_OFF_FLAGS = BW_OFF_HEAD + BW_MAX * sizeof(WinHeader);            // BwFlags
+constexpr size_t BW_OFF_ENTRY = BW_OFF_FLAGS + sizeof(BwFlags);                      // entry index = step * (c + r) + (candidate i | c + representative j)
+constexpr size_t BW_OFF_CLASS = BW_OFF_ENTRY + (size_t)BW_MAX * 2 * BIG_MAX * sizeof(WinEntry);   // [step][BIG_MAX] candidate classes
+constexpr size_t BW_OFF_WROTE = BW_OFF_CLASS + (size_t)BW_MAX * BIG_MAX * 4;         // [step][2 BIG_HASH]: rows written | position << 16 | candidate
+constexpr size_t BW_OFF_READ = BW_OFF_WROTE + (size_t)BW_MAX * 2 * BIG_HASH * 4;     // [step][2 BIG_HASH]: rows read | representative
+constexpr size_t BW_TABLE_BYTES = (BW_OFF_READ + (size_t)BW_MAX * 2 * BIG_HASH * 4 + 255) / 256 * 256;
+static_assert(sizeof(BwFlags) % 16 == 0 && BW_OFF_ENTRY % 16 == 0, "entries are 16-byte aligned");
+
+struct BwPlanArgs {
+    const int64_t* batch_y[BW_MAX];    // labels of the steps that are planned
+    const int32_t* fill_old;           // fill counts before the window
+    int32_t* fill_new;                 // ... and after it
+    int32_t* chunk_new;
+    char* table;
+    uint32_t seed_lo, seed_hi;
+    uint64_t first_step;
+    int32_t w;                         // steps in the window
+    int32_t b, c, r;
+    int32_t K, nchunks;
+    int64_t S;
+    int32_t eviction;                  // RB_EVICT_*
+    uint32_t number;                   // the window's number (never 0): what its flags are set to
+    const int32_t* aux_old;            // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
+    int32_t* aux_new;
+};
+
+struct BwMoveArgs {
+    const vec16* batch_x[BW_MAX];
+    vec16* out_x[BW_MAX];
+    int64_t* out_y[BW_MAX];
+    vec16* buf_x;
+    int64_t* buf_y;
+    const char* table;
+    DevState* state;
+    int32_t w, c, r;
+    uint32_t number;                   // the number of the window this table was planned as
+    int64_t S;
+    int64_t row_vec;
+    int32_t tpr, tile_vec, tile_rem;
+};
+
+__device__ __forceinline__ const int64_t* bw_labels(const BwPlanArgs& a, int s)
+{
+    const int64_t* p = a.batch_y[0];   // (fixed offsets into the kernel arguments, see win_labels)
+#pragma unroll
+    for (int i = 1; i < BW_MAX; ++i) p = s == i ? a.batch_y[i] : p;
+    return p;
+}
+
+// Stores and loads of what planners tell each other within a launch.
+__device__ __forceinline__ void bw_put(uint32_t* p, uint32_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t bw_get(const uint32_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// What this workgroup has told the others (bw_put) so far has arrived when they see `flag` = number.  All threads call it.
+__device__ __forceinline__ void bw_publish(uint32_t* flag, uint32_t number)
+{
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    if (threadIdx.x == 0) bw_put(flag, number);
+}
+
+// Wait until flags[lo .. hi) all show `number` (thread i watches flag lo + i; at most BW_MAX of them).
+// All threads call it; false if a wait ran out.
+__device__ __forceinline__ bool bw_await(const uint32_t* flags, int lo, int hi, uint32_t number, int* s_ok)
+{
+    const int i = (int)threadIdx.x;
+    if (i == 0) *s_ok = 1;
+    __syncthreads();
+    if (i < hi - lo) {
+        const uint64_t t0 = wall_clock64();
+        while (bw_get(flags + lo + i) != number) {
+            if (wall_clock64() - t0 > BW_TIMEOUT_TICKS) {
+                *s_ok = 0;
+                break;
+            }
+            __builtin_amdgcn_s_sleep(4);
+        }
+    }
+    __syncthreads();
+    const bool ok = *s_ok != 0;
+    __syncthreads();                                  // (everybody has read the verdict before the next wait resets it)
+    return ok;
+}
+
+// Value stored under `row` in a published table (keys in [0, BIG_HASH), values behind them), BW_MISSING if absent.
+__device__ __forceinline__ uint32_t bw_lookup(const uint32_t* tab, uint32_t row)
+{
+    uint32_t h = big_hash(row);
+    for (int probes = 0; probes < BIG_HASH; ++probes) {     // (a table holds at most BIG_HASH / 2 rows: the walk ends long before)
+        const uint32_t at = bw_get(tab + h);
+        if (at == row) return bw_get(tab + BIG_HASH + h);
+        if (at == BIG_EMPTY) break;
+        h = (h + 1) & (BIG_HASH - 1);
+    }
+    return BW_MISSING;
+}
+
+struct BwTable {
+    WinHeader* head;
+    BwFlags* flags;
+    WinEntry* entry;
+    int32_t* classes;
+    uint32_t* wrote;
+    uint32_t* read;
+};
+__device__ __forceinline__ BwTable bw_table(char* table)
+{
+    BwTable t;
+    t.head = reinterpret_cast<WinHeader*>(table + BW_OFF_HEAD);
+    t.flags = reinterpret_cast<BwFlags*>(table + BW_OFF_FLAGS);
+    t.entry = reinterpret_cast<WinEntry*>(table + BW_OFF_ENTRY);
+    t.classes = reinterpret_cast<int32_t*>(table + BW_OFF_CLASS);
+    t.wrote = reinterpret_cast<uint32_t*>(table + BW_OFF_WROTE);
+    t.read = reinterpret_cast<uint32_t*>(table + BW_OFF_READ);
+    return t;
+}
+
+// The arguments of rb_kernels_big.h's selection for step s of the window.
+__device__ __forceinline__ PlanArgs bw_step_args(const BwPlanArgs& a, int s)
+{
+    PlanArgs p;
+    p.batch_y = bw_labels(a, s);
+    p.fill_old = a.fill_old;
+    p.fill_new = nullptr; p.chunk_new = nullptr; p.table = nullptr;
+    p.sd.seed_lo = a.seed_lo; p.sd.seed_hi = a.seed_hi;
+    p.sd.step_lo = (uint32_t)(a.first_step + s); p.sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
+    p.b = a.b; p.c = a.c; p.r = a.r;
+    p.K = a.K; p.nchunks = a.nchunks;
+    p.S = a.S;
+    p.eviction = a.eviction;
+    p.aux_old = a.aux_old; p.aux_new = nullptr;
+    p.selection = RB_SELECT_EXACT;
+    p.ce = a.c;
+    return p;
+}
+
+// ---------------------------------------------------------------------------
+// Update planner of step s of the window (Alg. 1): thread i = candidate i of Floyd's emission order.
+// LDS as in plan_big_update.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint32_t* lds)
+{
+    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the window, then at the start of step s (not cut off)
+    uint32_t* s_u = lds + BIG_FILL;                        // first occurrences | class table
+    uint32_t* s_v = s_u + 2 * BIG_HASH;                    // the mini-batch's labels | starts of the class lists | row table
+    uint32_t* s_draw = s_v + 2 * BIG_HASH;                 // selection draws (bit 31: repeated), then the class lists
+    __shared__ int s_wave[BIG_NWAVE];
+    __shared__ int s_ok;
+
+    const int tid = threadIdx.x;
+    const int c = a.c, w = a.w, rows = a.c + a.r;
+    const int64_t S = a.S;
+    const BwTable t = bw_table(a.table);
+    const PlanArgs pa = bw_step_args(a, s);
+
+    // ---- A: selection, classes ----
+    const BigSelected sel = big_select(pa, s_fill, s_u, s_v, s_draw);
+    const int x = sel.x;
+    const int32_t k = sel.k;
+    const bool valid = k >= 0;
+    const bool strategy = a.eviction != RB_EVICT_UNIFORM;
+    const int64_t before_window = valid ? s_fill[k] : 0;             // samples of the class stored before the window
+    const int64_t aux_window = strategy && valid ? a.aux_old[k] : 0;  // the strategy's state before the window
+    if (tid < c) bw_put(reinterpret_cast<uint32_t*>(t.classes) + s * BIG_MAX + tid, (uint32_t)k);   // LAB_INVALID for a label outside [0, K)
+    bw_publish(&t.flags->classes[s], a.number);
+    bool ok = bw_await(t.flags->classes, 0, s, a.number, &s_ok);
+    // the candidates that the steps before this one bring
+    if (ok && tid < c)
+        for (int q = 0; q < s; ++q) {
+            const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
+            if (kq >= 0) atomicAdd(&s_fill[kq], 1);
+        }
+
+    // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
+    uint32_t* ckey = s_u;
+    uint32_t* ccnt = s_u + BIG_HASH;
+    uint32_t* list = s_draw;                    // [BIG_MAX]: position << 10 | candidate
+    uint32_t* cstart = s_v + BIG_MAX;           // [BIG_HASH]: start of the class's list
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
+        ckey[i] = BIG_EMPTY;
+        ccnt[i] = 0;
+    }
+    __syncthreads();
+    // the class at the start of this step: what it would hold without a capacity, what it holds, the strategy's state
+    const int64_t offered = valid ? s_fill[k] : 0;                   // before_window + candidates of the earlier steps
+    const int64_t fill0 = offered < S ? offered : S;
+    int64_t aux0 = 0;
+    if (a.eviction == RB_EVICT_FIFO) aux0 = (aux_window + (offered > S ? offered - S : 0)) % S;   // the oldest sample moved on by the overwrites
+    else if (a.eviction == RB_EVICT_RESERVOIR) aux0 = aux_window + (offered - before_window) < INT32_MAX ? aux_window + (offered - before_window) : INT32_MAX;
+    int h = 0, arrival = 0;
+    if (valid) {
+        h = big_find_or_insert(ckey, (uint32_t)k);
+        arrival = (int)atomicAdd(&ccnt[h], 1u);
+    }
+    __syncthreads();
+    const int total = valid ? (int)ccnt[h] : 0;
+    {
+        static_assert(BIG_HASH == 2 * BIG_TPB, "two table slots per thread");
+        const int c0 = (int)ccnt[2 * tid], c1 = (int)ccnt[2 * tid + 1];
+        int all;
+        const int lbefore = big_scan_excl(c0 + c1, all, s_wave);
+        cstart[2 * tid] = (uint32_t)lbefore;
+        cstart[2 * tid + 1] = (uint32_t)(lbefore + c0);
+    }
+    __syncthreads();
+    const int start = valid ? (int)cstart[h] : 0;
+    if (valid) list[start + arrival] = ((uint32_t)x << 10) | (uint32_t)tid;
+    __syncthreads();
+
+    // ---- insertion number and slot (as plan_big_update) ----
+    int rank = 0;
+    for (int i = 0; i < total; i += 4) {
+        const uint32_t m0 = list[start + i], m1 = list[start + i + 1], m2 = list[start + i + 2], m3 = list[start + i + 3];
+        rank += (int)((int)(m0 >> 10) < x) + (int)(i + 1 < total && (int)(m1 >> 10) < x) + (int)(i + 2 < total && (int)(m2 >> 10) < x) +
+                (int)(i + 3 < total && (int)(m3 >> 10) < x);
+    }
+    const int64_t at = fill0 + rank;
+    const bool over = valid && at >= S;              // beyond the capacity: overwrites a stored sample
+    int64_t slot = at;
+    if (over) {
+        if (a.eviction == RB_EVICT_FIFO) {
+            slot = (aux0 + at - S) % S;                                                      // the oldest one
+        } else if (a.eviction == RB_EVICT_RESERVOIR) {
+            const int64_t offers = aux0 + rank < INT32_MAX ? aux0 + rank : INT32_MAX;
+            const int64_t draw = (int64_t)below(pa.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)offers + 1);
+            slot = draw < S ? draw : -1;
+        } else {
+            slot = (int64_t)below(pa.sd, PURPOSE_EVICT, (uint32_t)x, (uint64_t)S);          // a uniformly drawn one
+        }
+    }
+    const bool placed = valid && slot >= 0;          // (a reservoir may not keep a candidate)
+    const int64_t row = placed ? (int64_t)k * S + slot : -1;
+    uint32_t* rkey = s_v;                            // slot rows written in this step
+    uint32_t* rval = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there, then position << 16 | candidate
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
+        rkey[i] = BIG_EMPTY;
+        rval[i] = 0;
+    }
+    __syncthreads();
+    int hr = 0;
+    if (placed) {
+        hr = big_find_or_insert(rkey, (uint32_t)row);
+        atomicMax(&rval[hr], (uint32_t)x + 1u);
+    }
+    __syncthreads();
+    // of the candidates of this step that go to one slot the last of the mini-batch is stored
+    const bool stored = placed && rval[hr] == (uint32_t)x + 1u;
+    __syncthreads();
+    if (stored) rval[hr] = ((uint32_t)x << 16) | (uint32_t)tid;
+    const int me = s * rows + tid;
+    if (tid < c) {
+        WinEntry e;
+        e.src = x;
+        e.label = valid ? k : -1;
+        e.row = stored ? row : -1;
+        e.chain = -1;
+        e.handled = 0;
+        e.pad[0] = 0; e.pad[1] = 0;
+        t.entry[me] = e;
+    }
+    __syncthreads();
+    uint32_t* wrote = t.wrote + (size_t)s * 2 * BIG_HASH;
+    for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) bw_put(wrote + i, s_v[i]);
+    bw_publish(&t.flags->update[s], a.number);
+
+    // ---- C: this step's writes against the other steps of the window ----
+    ok = bw_await(t.flags->update, s + 1, w, a.number, &s_ok) && ok;
+    ok = bw_await(t.flags->sample, 0, s, a.number, &s_ok) && ok;
+    if (ok && stored) {
+        bool later = false;                          // a later step writes the same slot: this write is not carried out
+        for (int q = s + 1; q < w; ++q) later |= bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING;
+        if (later) {
+            t.entry[me].row = -1;
+        } else if (slot < before_window) {
+            // the slot held a sample before the window.  Representatives of the steps before the first write to it
+            // read that sample: this write's workgroups copy it out to them before they overwrite it (bw_old_readers).
+            int first_write = s;
+            for (int q = s - 1; q >= 0; --q)
+                if (bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING) first_write = q;
+            bool readers = false;
+            for (int q = first_write - 1; q >= 0; --q) readers |= bw_lookup(t.read + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING;
+            if (readers) t.entry[me].chain = 1;
+        }
+    }
+    if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
+}
+
+// ---------------------------------------------------------------------------
+// Sampling planner of step s of the window (Sec. IV-C): thread j = representative j.
+// LDS as in plan_big_sample.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint32_t* lds)
+{
+    int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the window, after step s, then their prefix sums
+    uint32_t* s_u = lds + BIG_FILL;                        // draw table, then the table of the rows read
+    uint32_t* s_draw = s_u + 4 * BIG_HASH;                 // sampling draws (bit 31: repeated)
+    __shared__ int s_wave[BIG_NWAVE];
+    __shared__ int s_ok;
+    __shared__ uint32_t s_flags;
+    __shared__ uint32_t s_hit[BIG_CLASSES / 32];           // one bit per class: it gets candidates in this window up to step s
+    __shared__ uint32_t s_hit_later[BIG_CLASSES / 32];     // ... in the steps after s
+
+    const int tid = threadIdx.x;
+    const int c = a.c, r = a.r, K = a.K, w = a.w, rows = a.c + a.r;
+    const int64_t S = a.S;
+    const bool last = s == w - 1;
+    const BwTable t = bw_table(a.table);
+    Seed sd;
+    sd.seed_lo = a.seed_lo; sd.seed_hi = a.seed_hi;
+    sd.step_lo = (uint32_t)(a.first_step + s); sd.step_hi = (uint32_t)((a.first_step + s) >> 32);
+
+    int32_t fo[BIG_PER];
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int q = tid + u * BIG_TPB;
+        fo[u] = q < K ? a.fill_old[q] : 0;
+    }
+    if (tid == 0) s_flags = 0;
+    if (tid < BIG_CLASSES / 32) {
+        s_hit[tid] = 0;
+        s_hit_later[tid] = 0;
+    }
+    const uint64_t bits = tid < r ? draw64(sd, PURPOSE_SAMPLE, (uint32_t)tid) : 0;
+    uint32_t* dkey = s_u;                            // values of the sampling draws
+    uint32_t* dfirst = s_u + BIG_HASH;               // first draw with that value
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
+        dkey[i] = BIG_EMPTY;
+        dfirst[i] = 0xFFFFFFFFu;
+    }
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) s_fill[tid + u * BIG_TPB] = fo[u];
+    for (int i = BIG_CLASSES + tid; i < BIG_FILL; i += BIG_TPB) s_fill[i] = 0;
+
+    // ---- the candidates of this step and of the steps before it: how many every class gets; which classes the later steps touch ----
+    bool ok = bw_await(t.flags->classes, 0, w, a.number, &s_ok);
+    if (ok && tid < c)
+        for (int q = 0; q < w; ++q) {
+            const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
+            if (kq >= 0 && q <= s) {
+                atomicAdd(&s_fill[kq], 1);                       // may pass the capacity: cut back below
+                atomicOr(&s_hit[kq >> 5], 1u << (kq & 31));
+            } else if (kq >= 0) {
+                atomicOr(&s_hit_later[kq >> 5], 1u << (kq & 31));
+            } else if (q == s && kq == LAB_INVALID) {
+                atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
+            }
+        }
+    __syncthreads();
+
+    // ---- fill counts after the step; after the last step of the window they go out to memory, with the strategies' state ----
+    const int32_t cap = (int32_t)(S < INT32_MAX ? S : INT32_MAX);
+    if (last) {
+#pragma unroll
+        for (int u = 0; u < BIG_PER; ++u) {
+            const int q = tid + u * BIG_TPB;
+            if (q >= K) continue;
+            const int32_t f = s_fill[q];
+            a.fill_new[q] = f < cap ? f : cap;
+            if (a.eviction == RB_EVICT_FIFO) {
+                a.aux_new[q] = (int32_t)(((int64_t)a.aux_old[q] + (f > cap ? f - cap : 0)) % S);
+            } else if (a.eviction == RB_EVICT_RESERVOIR) {
+                const int64_t seen = (int64_t)a.aux_old[q] + (f - fo[u]);
+                a.aux_new[q] = (int32_t)(seen < INT32_MAX ? seen : INT32_MAX);
+            }
+        }
+    }
+    int nf[BIG_PER], local = 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        const int32_t f = s_fill[BIG_PER * tid + u];
+        nf[u] = f < cap ? f : cap;
+        local += nf[u];
+    }
+    const int lane = tid & (WAVE - 1), wave = tid / WAVE;
+    const int inc = wave_scan_incl(local);
+    if (lane == WAVE - 1) s_wave[wave] = inc;
+    __syncthreads();                                 // also ends the reads of s_fill above
+    int wpre[BIG_NWAVE];                             // stored samples before the classes of wavefront i
+    int F = 0;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) {
+        wpre[i] = F;
+        F += s_wave[i];
+    }
+    int before = inc - local;
+#pragma unroll
+    for (int i = 0; i < BIG_NWAVE; ++i) before += i == wave ? wpre[i] : 0;
+#pragma unroll
+    for (int u = 0; u < BIG_PER; ++u) {
+        s_fill[BIG_PER * tid + u] = before;
+        before += nf[u];
+    }
+    for (int i = BIG_CLASSES + tid; i < BIG_FILL; i += BIG_TPB) s_fill[i] = F;
+    __syncthreads();
+    if (last && tid < a.nchunks) {
+        const int lo = tid * CH, hi = lo + CH;
+        a.chunk_new[tid] = s_fill[hi] - s_fill[lo];
+    }
+
+    // ---- thread j = draw j of Floyd's n-subset of the F stored samples (as plan_big_sample) ----
+    const int n = r < F ? r : F;
+    const int64_t base = (int64_t)F - n;
+    const bool drawing = tid < n;
+    const uint32_t g0 = drawing ? (uint32_t)__umul64hi(bits, (uint64_t)base + (uint64_t)tid + 1u) : 0u;   // < 2^31
+    int hd = 0;
+    if (drawing) {
+        hd = big_find_or_insert(dkey, g0);
+        atomicMin(&dfirst[hd], (uint32_t)tid);
+    }
+    __syncthreads();
+    if (drawing) s_draw[tid] = g0 | ((dfirst[hd] != (uint32_t)tid) ? 0x80000000u : 0u);
+    __syncthreads();
+    int32_t pk = -1;
+    int64_t prow = -1;
+    bool look = false, look_later = false;
+    if (drawing) {
+        const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
+        int seg = 0;
+#pragma unroll
+        for (int i = 1; i < BIG_NWAVE; ++i) seg += (int)(wpre[i] <= g);
+        int lo = seg * WAVE * BIG_PER, hi = lo + WAVE * BIG_PER - 1;
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (s_fill[mid] <= g) lo = mid; else hi = mid - 1;
+        }
+        pk = lo;
+        prow = (int64_t)pk * S + (g - s_fill[lo]);
+        look = (s_hit[pk >> 5] >> (pk & 31)) & 1u;          // its slot may be written in this window, up to this step
+        look_later = (s_hit_later[pk >> 5] >> (pk & 31)) & 1u;   // ... or by a later step
+    }
+    // the rows this step reads, for the update planners of the later steps
+    uint32_t* rkey = s_u + 2 * BIG_HASH;
+    uint32_t* rval = rkey + BIG_HASH;
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) rkey[i] = BIG_EMPTY;
+    __syncthreads();
+    if (drawing) rval[big_find_or_insert(rkey, (uint32_t)prow)] = (uint32_t)tid;      // (the representatives of a step are different samples)
+    const int me = s * rows + c + tid;
+    if (tid < r) {
+        WinEntry e;
+        e.src = -1;
+        e.label = pk;                           // -1 when fewer samples are stored than asked for
+        e.row = prow;
+        e.chain = -1;
+        e.handled = 0;
+        e.pad[0] = 0; e.pad[1] = 0;
+        t.entry[me] = e;
+    }
+    if (tid == 0) {
+        WinHeader hh;
+        hh.n = n;
+        hh.flags = s_flags;
+        hh.pad[0] = 0; hh.pad[1] = 0;
+        t.head[s] = hh;
+    }
+    __syncthreads();
+    uint32_t* read = t.read + (size_t)s * 2 * BIG_HASH;
+    for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) bw_put(read + i, rkey[i]);
+    bw_publish(&t.flags->sample[s], a.number);
+
+    // ---- C: a slot that this step or an earlier one of the window writes is read from the mini-batch row stored there;
+    //         what a later step overwrites is handed out by the workgroups that overwrite it ----
+    ok = bw_await(t.flags->update, 0, w, a.number, &s_ok) && ok;
+    if (ok && (look || look_later)) {
+        bool forwarded = false;
+        if (look)
+            for (int q = s; q >= 0; --q) {
+                const uint32_t v = bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)prow);
+                if (v == BW_MISSING) continue;
+                t.entry[me].src = (q << 16) | (int)(v >> 16);
+                forwarded = true;
+                break;
+            }
+        if (!forwarded && look_later) {
+            bool later = false;
+            for (int q = s + 1; q < w; ++q) later |= bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)prow) != BW_MISSING;
+            if (later) t.entry[me].handled = 1;
+        }
+    }
+    if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
+}
+
+// The plan of the first window of a call, on its own: 2 w workgroups.
+__global__ void __launch_bounds__(BIG_TPB) rb_bigwin_plan_kernel(const BwPlanArgs a)
+{
+    extern __shared__ uint32_t lds[];
+    const int s = (int)blockIdx.x >> 1;
+    if (blockIdx.x & 1) bw_plan_sample(a, s, lds);
+    else bw_plan_update(a, s, lds);
+}
+
+// ---------------------------------------------------------------------------
+// All steps of one window by its table: every group of BIG_GROUP threads moves one tile of one row; the
+// first 2 next.w workgroups plan the next window instead.
+// ---------------------------------------------------------------------------
+template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+__global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, const BwPlanArgs next)
+{
+    extern __shared__ uint32_t lds[];
+    const int planners = 2 * next.w;
+    if ((int)blockIdx.x < planners) {          // dispatched first: they have the longest way to go
+        __builtin_amdgcn_s_setprio(3);
+        const int s = (int)blockIdx.x >> 1;
+        if (blockIdx.x & 1) bw_plan_sample(next, s, lds);
+        else bw_plan_update(next, s, lds);
+        return;
+    }
+    const int rows = m.c + m.r;
+    const int64_t per_step = (int64_t)rows * m.tpr;
+    const int64_t item = (int64_t)((int)blockIdx.x - planners) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
+    if (item >= per_step * m.w) return;
+    const int s = (int)(item / per_step);
+    int e, tile;
+    split_item(item - (int64_t)s * per_step, m.tpr, e, tile);
+    const WinHeader* head = reinterpret_cast<const WinHeader*>(m.table + BW_OFF_HEAD);
+    const BwFlags* flags = reinterpret_cast<const BwFlags*>(m.table + BW_OFF_FLAGS);
+    const WinEntry* entry = reinterpret_cast<const WinEntry*>(m.table + BW_OFF_ENTRY);
+    const int lane = threadIdx.x & (BIG_GROUP - 1);
+    const bool first = tile == 0 && lane == 0;
+    if (bw_get(&flags->failed) == m.number) {           // the planners of this window gave up on each other: nothing is moved
+        if (item == 0 && first) atomicOr(&m.state->flags, (uint32_t)RB_FLAG_PLAN_TIMEOUT);
+        return;
+    }
+    const WinEntry en = entry[s * rows + e];
+    int64_t v_lo, v_hi;
+    tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
+    if (item == 0 && first) {
+        uint32_t raised = 0;
+        for (int q = 0; q < m.w; ++q) raised |= head[q].flags;
+        m.state->last_n = head[m.w - 1].n;
+        if (raised != 0) atomicOr(&m.state->flags, raised);
+    }
+    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
+    if (e < m.c) {
+        if (en.row < 0) return;                 // dropped within its step, or overwritten again later in the window
+        vec16* slot = m.buf_x + en.row * m.row_vec;
+        const vec16* fresh = m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE;
+        if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
+        if (en.chain >= 0) {
+            // Representatives of earlier steps need what the slot held before the window (those that the sampling planner
+            // of their step marked as handed out from here).  Every lane copies its own vectors out to them and only then
+            // overwrites these same vectors: no lane waits for another.
+            const uint32_t* read_tables = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_READ);
+            vec16* reader_x[BW_MAX - 1];             // (indexed by compile-time constants only: registers) of step q, null: none
+#pragma unroll
+            for (int q = 0; q < BW_MAX - 1; ++q) {
+                reader_x[q] = nullptr;
+                if (q >= s) continue;
+                const uint32_t j = bw_lookup(read_tables + (size_t)q * 2 * BIG_HASH, (uint32_t)en.row);
+                if (j == BW_MISSING) continue;
+                const WinEntry rq = entry[q * rows + m.c + (int)j];
+                if (!rq.handled) continue;
+                reader_x[q] = m.out_x[q] + (int64_t)j * m.row_vec * WIDE;
+                if (first) {
+                    m.out_y[q][j] = rq.label;
+                    count_moved(m.state);
+                }
+            }
+            if (BF16) {
+                vec8* half = reinterpret_cast<vec8*>(slot);
+                for (int64_t i = 2 * v_lo + lane; i < 2 * v_hi; i += BIG_GROUP) {
+                    const vec16 old = widen4(half[i]);
+#pragma unroll
+                    for (int q = 0; q < BW_MAX - 1; ++q)
+                        if (reader_x[q]) reader_x[q][i] = old;
+                    half[i] = narrow4(fresh[i]);
+                }
+            } else {
+                for (int64_t i = v_lo + lane; i < v_hi; i += BIG_GROUP) {
+                    const vec16 old = slot[i];
+#pragma unroll
+                    for (int q = 0; q < BW_MAX - 1; ++q)
+                        if (reader_x[q]) reader_x[q][i] = old;
+                    slot[i] = fresh[i];
+                }
+            }
+            return;
+        }
+        Tile<U, NT, BIG_GROUP, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
+        t.load(fresh, v_lo, v_hi);
+        t.store(slot, v_lo, v_hi);
+        return;
+    }
+    if (en.handled) return;
+    const int j = e - m.c;
+    if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
+    if (en.label < 0) return;
+    if (first) count_moved(m.state);
+    vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
+    if (BF16 && en.src >= 0) {
+        // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
+        Tile<U, NT, BIG_GROUP, WIN_PACE, CV_BOTH> t;
+        t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    } else {
+        const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
+                                       : m.buf_x + en.row * m.row_vec;
+        Tile<U, NT, BIG_GROUP, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
+        t.load(src, v_lo, v_hi);
+        t.store(dst, v_lo, v_hi);
+    }
+}
+
+}  // namespace

@@ -35,7 +35,7 @@ def test_create_validation_and_sizes():
     rc, h = rb.rb_create(1000, 130, (3, 224, 224), rb.RB_F32)
     assert rc == rb.RB_OK and h
     rc, xb, yb, wb = rb.rb_query_sizes(h)
-    assert rc == rb.RB_OK and xb == 1000 * 130 * 602112 and yb == 1000 * 130 * 8 and wb % 256 == 0 and wb < (1 << 20)
+    assert rc == rb.RB_OK and xb == 1000 * 130 * 602112 and yb == 1000 * 130 * 8 and wb % 256 == 0 and wb < (4 << 20)
     # hot calls before rb_bind
     assert rb.rb_update(h, 256, 256, 4, 2, 0, 0) == rb.RB_ESTATE
     assert rb.rb_sample_augment(h, 2, 0, 0, 256, 256) == rb.RB_ESTATE
@@ -117,8 +117,9 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16)            # few rows per step: the most
     assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 8)          # 1024 table entries / 128 rows per step
     assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 12)         # 512 planner slots / max(c, r)
-    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 1)           # not eligible
-    assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 1)
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 8)           # beyond the small form: the large-count form's 8
+    assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 8)
+    assert rb.rb_query_steps_per_launch(h, 4096, 1025, 8) == (rb.RB_OK, 1)        # not eligible for either
     assert rb.rb_query_steps_per_launch(h, 64, 0, 8) == (rb.RB_OK, 1)
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 5) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 17) == rb.RB_EINVAL

@@ -599,6 +599,75 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     compare_buffers(buf, orc, "final")
 
 
+# ------------------------- several steps per launch with large counts (1024-thread planners side by side) ---
+
+@pytest.mark.parametrize("window", [8, 5, 2])
+@pytest.mark.parametrize("w,policy,bf16", [
+    (wl.variant(wl.C5, name="bw-two-classes", K=2, S=40, shape=(64,), b=256, c=100, r=70), None, False),        # 80 slots in all: every step reads and rewrites most of them
+    (wl.variant(wl.C5, name="bw-one-class", K=1, S=150, shape=(32,), b=300, c=120, r=150), None, False),        # r = everything stored: every slot is read in every step
+    (wl.variant(wl.C5, name="bw-K300", K=300, S=12, shape=(256,), b=512, c=200, r=150), None, False),           # fills up, then replaces
+    (wl.variant(wl.C5, name="bw-K300-fifo", K=300, S=12, shape=(256,), b=512, c=200, r=150), "exact-fifo", False),
+    (wl.variant(wl.C5, name="bw-K40-reservoir", K=40, S=10, shape=(64,), b=512, c=200, r=150), "exact-reservoir", False),
+    (wl.variant(wl.C5, name="bw-two-classes-bf16", K=2, S=40, shape=(64,), b=256, c=100, r=70), None, True),    # old content handed on through the conversion
+    (wl.variant(wl.C5, name="bw-K300-bf16-fifo", K=300, S=12, shape=(264,), b=512, c=200, r=150), "exact-fifo", True),
+    (wl.variant(wl.C2, name="bw-K1100-few", K=1100, S=2), None, False),                                         # few candidates, too many classes for the small form
+    (wl.variant(wl.C5, name="bw-limits", K=10240, S=3, shape=(16,), b=4096, c=1024, r=1024), None, False),      # every limit at once
+], ids=lambda v: v.name if hasattr(v, "name") else None)
+def test_many_steps_with_large_counts(w, policy, bf16, window):
+    """rb_update_sample_many for shapes beyond the small several-steps form: up to 8 steps per launch, planned by
+    two 1024-thread workgroups per step that settle between them what the steps do to each other's slots."""
+    rb = _rb()
+    pol = POLICIES[policy] if policy else None
+    run_many_parity(w, 40, per_call=19, window=window, policy=pol, store_bf16=bf16)
+    run_many_parity(w, 40, per_call=16, window=window, announce=True, policy=pol, store_bf16=bf16)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, store_dtype=torch.bfloat16 if bf16 else None)
+    buf.set_option(rb.RB_OPT_WINDOW, window)
+    assert buf.steps_per_launch(w.b, w.c, w.r) == window
+
+
+@pytest.mark.parametrize("seed", [1, 2])
+def test_many_steps_with_large_counts_survive_broken_promises(seed):
+    run_many_parity(wl.variant(wl.C5, name=f"bw-promises-{seed}", K=30, S=12, shape=(64,), b=512, c=200, r=150), 160, per_call=12,
+                    announce=True, schedule_seed=seed)
+
+
+def test_many_steps_with_large_counts_drop_and_flag_bad_labels():
+    rb = _rb()
+    dev = torch.device("cuda:0")
+    K, S, b, c, r, n = 1500, 2, 200, 150, 90, 14
+    buf = rb.RehearsalBuffer(K, S, (8,), torch.float32, device=dev)
+    assert buf.steps_per_launch(b, c, r) == 8
+    orc = rbo.Buffer(K, S, 32)
+    g = torch.Generator(device="cpu")
+    g.manual_seed(6)
+    xs = [torch.randn((b, 8), generator=g).to(dev) for _ in range(n)]
+    ys = [torch.randint(0, K, (b,), generator=g, dtype=torch.int64) for _ in range(n)]
+    ys[5][::3] = -1
+    ys[9][1::4] = K
+    ys[9][5] = 10**12
+    ys = [y.to(dev) for y in ys]
+    oxs = [torch.zeros((r, 8), device=dev) for _ in range(n)]
+    oys = [torch.full((r,), -7, dtype=torch.int64, device=dev) for _ in range(n)]
+    buf.update_sample_many(xs[:4], ys[:4], c, r, 21, 0, oxs[:4], oys[:4])
+    assert buf.read_state()[2] == 0
+    buf.update_sample_many(xs[4:], ys[4:], c, r, 21, 4, oxs[4:], oys[4:])
+    torch.cuda.synchronize()
+    for t in range(n):
+        orc.update(parity_util._bytes(xs[t]).cpu().numpy(), ys[t].cpu().numpy(), c, 21, t)
+        m, ref_x, ref_y = orc.sample_augment(r, 21, t)
+        assert np.array_equal(oys[t].cpu().numpy(), ref_y), f"step {t}: labels differ"
+        assert np.array_equal(parity_util._bytes(oxs[t]).cpu().numpy()[:m], ref_x[:m]), f"step {t}: rows differ"
+    assert buf.read_state()[2] == rb.RB_FLAG_BAD_LABEL == orc.flags
+    compare_buffers(buf, orc, "bad labels, large counts, several steps per launch")
+
+
+@pytest.mark.parametrize("w", [wl.C5, wl.C5F], ids=["C5", "C5F"])
+def test_many_steps_with_large_counts_at_full_size(w):
+    """C5 and its variant with a fixed set of active classes in the form the bench times them in: announced
+    rb_update_sample_many calls, 8 steps per launch, every configured step."""
+    run_many_parity(w, w.steps, per_call=32, announce=True)
+
+
 def test_many_steps_drop_and_flag_bad_labels():
     """Labels outside [0, K) among the candidates of steps in the middle of a launch: not stored, flag raised."""
     rb = _rb()
