@@ -644,27 +644,49 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     return RB_OK;
 }
 
-template <int U, bool NT, bool BF16>
+template <int U, int W, bool NT, bool BF16>
 hipError_t launch_bigwin_u(const BwMoveArgs& m, const BwPlanArgs& next, dim3 grid, hipStream_t st)
 {
     const size_t lds = next.w > 0 ? BIG_LDS_BYTES : 0;
     if (lds != 0) {
-        const hipError_t e = allow_big_lds<&rb_bigwin_kernel<U, NT, BF16>>();
+        const hipError_t e = allow_big_lds<&rb_bigwin_kernel<U, W, NT, BF16>>();
         if (e != hipSuccess) return e;
     }
-    rb_bigwin_kernel<U, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next);
+    rb_bigwin_kernel<U, W, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next);
     return hipGetLastError();
 }
 
+// width: threads per tile (bigwin_width), unroll: vectors per thread
 template <bool NT, bool BF16>
-hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int unroll, dim3 grid, hipStream_t st)
+hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int width, int unroll, dim3 grid, hipStream_t st)
 {
+    if (width == WAVE) return unroll == 2 ? launch_bigwin_u<2, WAVE, NT, BF16>(m, next, grid, st) : launch_bigwin_u<8, WAVE, NT, BF16>(m, next, grid, st);
+    if (width == 2 * WAVE) return launch_bigwin_u<8, 2 * WAVE, NT, BF16>(m, next, grid, st);
     switch (unroll) {
-    case 1: return launch_bigwin_u<1, NT, BF16>(m, next, grid, st);
-    case 2: return launch_bigwin_u<2, NT, BF16>(m, next, grid, st);
-    case 4: return launch_bigwin_u<4, NT, BF16>(m, next, grid, st);
-    default: return launch_bigwin_u<8, NT, BF16>(m, next, grid, st);
+    case 1: return launch_bigwin_u<1, TPB, NT, BF16>(m, next, grid, st);
+    case 2: return launch_bigwin_u<2, TPB, NT, BF16>(m, next, grid, st);
+    case 4: return launch_bigwin_u<4, TPB, NT, BF16>(m, next, grid, st);
+    default: return launch_bigwin_u<8, TPB, NT, BF16>(m, next, grid, st);
     }
+}
+
+// Tiles of the several-steps launch for large counts.  A compute unit holds a fixed number of wavefronts, so the bytes it
+// has in flight are what a wavefront has in flight: rows of up to 8 KiB are moved by one wavefront each (eight vectors per
+// lane), rows of up to 16 KiB by two; longer rows are cut into tiles for 256 threads like everywhere else.
+Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
+{
+    width = TPB;
+    if (rb->opt_unroll == 0 && rb->row_vec <= 2 * WAVE * 8) width = rb->row_vec <= WAVE * 8 ? WAVE : 2 * WAVE;
+    if (width == TPB) return plan_shape(rb, rows, TPB);
+    Shape s;
+    s.unroll = width == WAVE && rb->row_vec <= WAVE * 2 ? 2 : 8;
+    s.tpr = 1;
+    const int64_t nunits = (rb->row_vec + TILE_UNIT - 1) / TILE_UNIT;
+    s.tile_vec = (int)nunits;
+    s.tile_rem = 0;
+    s.rpb = 1;
+    s.groups = rows;
+    return s;
 }
 
 // Whether rb_update_sample_many puts several steps of this shape into one launch of the large-count form, and how
@@ -706,15 +728,18 @@ BwPlanArgs bigwin_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_
 // n steps of the large-count form as launches of up to BW_MAX steps each: the first 2 w' workgroups of every launch
 // plan the next window of w' steps (rb_kernels_bigwin.h) while the others move the rows of this one.  Bookkeeping as
 // in steps_windowed.  The planners of a window work side by side, so a plan takes about as long whatever the
-// window's size (measured on MI355X, 1024 candidates and representatives of 10000 classes: about 12 us), and the
-// windows can be of full size as soon as one launch moves rows for that long.
+// window's size: a chain of about fifteen dependent trips to memory (measured on MI355X, 1024 candidates and
+// representatives of 10000 classes: 20 to 26 us on an idle chip, 30 to 45 us under the movers' traffic), so the
+// windows are of full size from the second launch on; the first window, planned with nothing to hide behind, is
+// short, so that rows start to move early.
 int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int64_t* const* batch_y, int64_t b, int64_t c,
                  int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
                  int64_t ann_n, const int64_t* const* ann_y)
 {
     static_assert(BW_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
     const int64_t wmax = bigwin_limit(rb, b, c, r);
-    const Shape sh = plan_shape(rb, wmax * (c + r), BIG_GROUP);
+    int width;
+    const Shape sh = bigwin_shape(rb, wmax * (c + r), width);
     const double move_us = (double)(c + r) * (double)(rb->row_bytes + rb->sample_bytes) / 5.5e6;
     int64_t w0 = 1;
     while (w0 < wmax && move_us * (double)w0 < 12.0) ++w0;
@@ -762,13 +787,14 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
         if (ahead) next = bigwin_plan_args(rb, ann_y, 0, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1);
         else if (next_w > 0) next = bigwin_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, tbl ^ 1);
         const int64_t items = w * (c + r) * sh.tpr;
-        const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + 2 * next_w));
+        const int64_t per_block = BIG_TPB / width;
+        const dim3 grid((unsigned)((items + per_block - 1) / per_block + 2 * next_w));
         const bool bf16 = rb->storage == RB_STORE_BF16;
         hipError_t e;
-        if (rb->opt_nt) e = bf16 ? launch_bigwin<true, true>(m, next, sh.unroll, grid, rb->stream)
-                                 : launch_bigwin<true, false>(m, next, sh.unroll, grid, rb->stream);
-        else e = bf16 ? launch_bigwin<false, true>(m, next, sh.unroll, grid, rb->stream)
-                      : launch_bigwin<false, false>(m, next, sh.unroll, grid, rb->stream);
+        if (rb->opt_nt) e = bf16 ? launch_bigwin<true, true>(m, next, width, sh.unroll, grid, rb->stream)
+                                 : launch_bigwin<true, false>(m, next, width, sh.unroll, grid, rb->stream);
+        else e = bf16 ? launch_bigwin<false, true>(m, next, width, sh.unroll, grid, rb->stream)
+                      : launch_bigwin<false, false>(m, next, width, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         if (ahead) {

@@ -53,8 +53,8 @@ constexpr size_t BW_OFF_HEAD = 0;                                               
 constexpr size_t BW_OFF_FLAGS = BW_OFF_HEAD + BW_MAX * sizeof(WinHeader);            // BwFlags
 constexpr size_t BW_OFF_ENTRY = BW_OFF_FLAGS + sizeof(BwFlags);                      // entry index = step * (c + r) + (candidate i | c + representative j)
 constexpr size_t BW_OFF_CLASS = BW_OFF_ENTRY + (size_t)BW_MAX * 2 * BIG_MAX * sizeof(WinEntry);   // [step][BIG_MAX] candidate classes
-constexpr size_t BW_OFF_WROTE = BW_OFF_CLASS + (size_t)BW_MAX * BIG_MAX * 4;         // [step][2 BIG_HASH]: rows written | position << 16 | candidate
-constexpr size_t BW_OFF_READ = BW_OFF_WROTE + (size_t)BW_MAX * 2 * BIG_HASH * 4;     // [step][2 BIG_HASH]: rows read | representative
+constexpr size_t BW_OFF_WROTE = BW_OFF_CLASS + (size_t)BW_MAX * BIG_MAX * 4;         // [step][BIG_HASH] 64-bit words: see BwTable
+constexpr size_t BW_OFF_READ = BW_OFF_WROTE + (size_t)BW_MAX * 2 * BIG_HASH * 4;     // likewise
 constexpr size_t BW_TABLE_BYTES = (BW_OFF_READ + (size_t)BW_MAX * 2 * BIG_HASH * 4 + 255) / 256 * 256;
 static_assert(sizeof(BwFlags) % 16 == 0 && BW_OFF_ENTRY % 16 == 0, "entries are 16-byte aligned");
 
@@ -140,17 +140,58 @@ __device__ __forceinline__ bool bw_await(const uint32_t* flags, int lo, int hi, 
     return ok;
 }
 
-// Value stored under `row` in a published table (keys in [0, BIG_HASH), values behind them), BW_MISSING if absent.
-__device__ __forceinline__ uint32_t bw_lookup(const uint32_t* tab, uint32_t row)
+__device__ __forceinline__ void bw_put64(uint64_t* p, uint64_t v)
+{
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint64_t bw_get64(const uint64_t* p)
+{
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// A published table: BIG_HASH words of (value << 32 | row), open addressing as in the planners' LDS tables, free
+// slots hold BIG_EMPTY as row.  Value stored under `row`, BW_MISSING if absent.
+__device__ __forceinline__ uint32_t bw_lookup(const uint64_t* tab, uint32_t row)
 {
     uint32_t h = big_hash(row);
     for (int probes = 0; probes < BIG_HASH; ++probes) {     // (a table holds at most BIG_HASH / 2 rows: the walk ends long before)
-        const uint32_t at = bw_get(tab + h);
-        if (at == row) return bw_get(tab + BIG_HASH + h);
-        if (at == BIG_EMPTY) break;
+        const uint64_t at = bw_get64(tab + h);
+        if ((uint32_t)at == row) return (uint32_t)(at >> 32);
+        if ((uint32_t)at == BIG_EMPTY) break;
         h = (h + 1) & (BIG_HASH - 1);
     }
     return BW_MISSING;
+}
+
+// `row` looked up in the tables of all steps q with bit q of `steps` set, all at once: a round trip to memory per
+// probe round, not per table (a dependent trip costs 1 to 2 us while the movers are running).  Returns the steps
+// whose table holds the row, their values in val[q].
+__device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_MAX])
+{
+    uint32_t h[BW_MAX];
+#pragma unroll
+    for (int q = 0; q < BW_MAX; ++q) h[q] = big_hash(row);
+    uint32_t pending = steps, found = 0;
+    for (int probes = 0; pending != 0 && probes < BIG_HASH; ++probes) {
+        uint64_t at[BW_MAX];
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q)
+            if ((pending >> q) & 1u) at[q] = bw_get64(tabs + (size_t)q * BIG_HASH + h[q]);
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) {
+            if (!((pending >> q) & 1u)) continue;
+            if ((uint32_t)at[q] == row) {
+                found |= 1u << q;
+                val[q] = (uint32_t)(at[q] >> 32);
+                pending &= ~(1u << q);
+            } else if ((uint32_t)at[q] == BIG_EMPTY) {
+                pending &= ~(1u << q);
+            } else {
+                h[q] = (h[q] + 1) & (BIG_HASH - 1);
+            }
+        }
+    }
+    return found;
 }
 
 struct BwTable {
@@ -158,8 +199,8 @@ struct BwTable {
     BwFlags* flags;
     WinEntry* entry;
     int32_t* classes;
-    uint32_t* wrote;
-    uint32_t* read;
+    uint64_t* wrote;      // [step][BIG_HASH]: rows the step writes -> mini-batch position << 16 | candidate
+    uint64_t* read;       // [step][BIG_HASH]: rows the step reads -> representative
 };
 __device__ __forceinline__ BwTable bw_table(char* table)
 {
@@ -168,8 +209,8 @@ __device__ __forceinline__ BwTable bw_table(char* table)
     t.flags = reinterpret_cast<BwFlags*>(table + BW_OFF_FLAGS);
     t.entry = reinterpret_cast<WinEntry*>(table + BW_OFF_ENTRY);
     t.classes = reinterpret_cast<int32_t*>(table + BW_OFF_CLASS);
-    t.wrote = reinterpret_cast<uint32_t*>(table + BW_OFF_WROTE);
-    t.read = reinterpret_cast<uint32_t*>(table + BW_OFF_READ);
+    t.wrote = reinterpret_cast<uint64_t*>(table + BW_OFF_WROTE);
+    t.read = reinterpret_cast<uint64_t*>(table + BW_OFF_READ);
     return t;
 }
 
@@ -317,27 +358,41 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
         t.entry[me] = e;
     }
     __syncthreads();
-    uint32_t* wrote = t.wrote + (size_t)s * 2 * BIG_HASH;
-    for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) bw_put(wrote + i, s_v[i]);
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) bw_put64(t.wrote + (size_t)s * BIG_HASH + i, (uint64_t)rval[i] << 32 | rkey[i]);
     bw_publish(&t.flags->update[s], a.number);
 
     // ---- C: this step's writes against the other steps of the window ----
     ok = bw_await(t.flags->update, s + 1, w, a.number, &s_ok) && ok;
     ok = bw_await(t.flags->sample, 0, s, a.number, &s_ok) && ok;
+    // Which other steps bring candidates of this step's classes (one byte of step bits per slot of the class table, in the
+    // words that held the class lists): only their tables can hold this step's rows.
+    uint32_t* cmask = s_draw;
+    for (int i = tid; i < BIG_HASH / 4; i += BIG_TPB) cmask[i] = 0;
+    __syncthreads();
+    if (ok && tid < c) {
+        int32_t kq[BW_MAX];
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) kq[q] = q < w && q != s ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) {
+            if (kq[q] < 0) continue;
+            const int hq = big_find(ckey, (uint32_t)kq[q]);
+            if (hq >= 0) atomicOr(&cmask[hq >> 2], (1u << q) << (8 * (hq & 3)));
+        }
+    }
+    __syncthreads();
     if (ok && stored) {
-        bool later = false;                          // a later step writes the same slot: this write is not carried out
-        for (int q = s + 1; q < w; ++q) later |= bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING;
-        if (later) {
-            t.entry[me].row = -1;
+        const uint32_t others = (cmask[h >> 2] >> (8 * (h & 3))) & 0xFFu;
+        uint32_t val[BW_MAX];
+        const uint32_t writers = bw_lookup_steps(t.wrote, (uint32_t)row, others, val);
+        if (writers >> (s + 1)) {
+            t.entry[me].row = -1;                    // a later step writes the same slot: this write is not carried out
         } else if (slot < before_window) {
             // the slot held a sample before the window.  Representatives of the steps before the first write to it
-            // read that sample: this write's workgroups copy it out to them before they overwrite it (bw_old_readers).
-            int first_write = s;
-            for (int q = s - 1; q >= 0; --q)
-                if (bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING) first_write = q;
-            bool readers = false;
-            for (int q = first_write - 1; q >= 0; --q) readers |= bw_lookup(t.read + (size_t)q * 2 * BIG_HASH, (uint32_t)row) != BW_MISSING;
-            if (readers) t.entry[me].chain = 1;
+            // read that sample: this write's workgroups copy it out to them before they overwrite it.
+            const uint32_t earlier = writers & ((1u << s) - 1u);
+            const int first_write = earlier ? __builtin_ctz(earlier) : s;
+            if (bw_lookup_steps(t.read, (uint32_t)row, (1u << first_write) - 1u, val) != 0) t.entry[me].chain = 1;
         }
     }
     if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
@@ -351,12 +406,12 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
 {
     int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the window, after step s, then their prefix sums
     uint32_t* s_u = lds + BIG_FILL;                        // draw table, then the table of the rows read
+    uint32_t* s_hit = s_u + 2 * BIG_HASH;                  // one byte per class: the steps of the window (bit q) that bring it candidates
     uint32_t* s_draw = s_u + 4 * BIG_HASH;                 // sampling draws (bit 31: repeated)
+    static_assert(BIG_CLASSES / 4 <= 2 * BIG_HASH, "a byte per class in the second table region");
     __shared__ int s_wave[BIG_NWAVE];
     __shared__ int s_ok;
     __shared__ uint32_t s_flags;
-    __shared__ uint32_t s_hit[BIG_CLASSES / 32];           // one bit per class: it gets candidates in this window up to step s
-    __shared__ uint32_t s_hit_later[BIG_CLASSES / 32];     // ... in the steps after s
 
     const int tid = threadIdx.x;
     const int c = a.c, r = a.r, K = a.K, w = a.w, rows = a.c + a.r;
@@ -374,10 +429,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         fo[u] = q < K ? a.fill_old[q] : 0;
     }
     if (tid == 0) s_flags = 0;
-    if (tid < BIG_CLASSES / 32) {
-        s_hit[tid] = 0;
-        s_hit_later[tid] = 0;
-    }
+    for (int i = tid; i < BIG_CLASSES / 4; i += BIG_TPB) s_hit[i] = 0;
     const uint64_t bits = tid < r ? draw64(sd, PURPOSE_SAMPLE, (uint32_t)tid) : 0;
     uint32_t* dkey = s_u;                            // values of the sampling draws
     uint32_t* dfirst = s_u + BIG_HASH;               // first draw with that value
@@ -394,11 +446,9 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
     if (ok && tid < c)
         for (int q = 0; q < w; ++q) {
             const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
-            if (kq >= 0 && q <= s) {
-                atomicAdd(&s_fill[kq], 1);                       // may pass the capacity: cut back below
-                atomicOr(&s_hit[kq >> 5], 1u << (kq & 31));
-            } else if (kq >= 0) {
-                atomicOr(&s_hit_later[kq >> 5], 1u << (kq & 31));
+            if (kq >= 0) {
+                if (q <= s) atomicAdd(&s_fill[kq], 1);           // may pass the capacity: cut back below
+                atomicOr(&s_hit[kq >> 2], (1u << q) << (8 * (kq & 3)));
             } else if (q == s && kq == LAB_INVALID) {
                 atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
             }
@@ -470,7 +520,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
     __syncthreads();
     int32_t pk = -1;
     int64_t prow = -1;
-    bool look = false, look_later = false;
+    uint32_t touched = 0;                            // steps of the window that bring candidates to the sample's class
     if (drawing) {
         const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
         int seg = 0;
@@ -483,11 +533,11 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         }
         pk = lo;
         prow = (int64_t)pk * S + (g - s_fill[lo]);
-        look = (s_hit[pk >> 5] >> (pk & 31)) & 1u;          // its slot may be written in this window, up to this step
-        look_later = (s_hit_later[pk >> 5] >> (pk & 31)) & 1u;   // ... or by a later step
+        touched = (s_hit[pk >> 2] >> (8 * (pk & 3))) & 0xFFu;
     }
     // the rows this step reads, for the update planners of the later steps
-    uint32_t* rkey = s_u + 2 * BIG_HASH;
+    __syncthreads();                                 // (the draw table has been read)
+    uint32_t* rkey = s_u;
     uint32_t* rval = rkey + BIG_HASH;
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) rkey[i] = BIG_EMPTY;
     __syncthreads();
@@ -511,27 +561,24 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         t.head[s] = hh;
     }
     __syncthreads();
-    uint32_t* read = t.read + (size_t)s * 2 * BIG_HASH;
-    for (int i = tid; i < 2 * BIG_HASH; i += BIG_TPB) bw_put(read + i, rkey[i]);
+    for (int i = tid; i < BIG_HASH; i += BIG_TPB) bw_put64(t.read + (size_t)s * BIG_HASH + i, (uint64_t)rval[i] << 32 | rkey[i]);
     bw_publish(&t.flags->sample[s], a.number);
 
     // ---- C: a slot that this step or an earlier one of the window writes is read from the mini-batch row stored there;
     //         what a later step overwrites is handed out by the workgroups that overwrite it ----
     ok = bw_await(t.flags->update, 0, w, a.number, &s_ok) && ok;
-    if (ok && (look || look_later)) {
-        bool forwarded = false;
-        if (look)
-            for (int q = s; q >= 0; --q) {
-                const uint32_t v = bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)prow);
-                if (v == BW_MISSING) continue;
-                t.entry[me].src = (q << 16) | (int)(v >> 16);
-                forwarded = true;
-                break;
-            }
-        if (!forwarded && look_later) {
-            bool later = false;
-            for (int q = s + 1; q < w; ++q) later |= bw_lookup(t.wrote + (size_t)q * 2 * BIG_HASH, (uint32_t)prow) != BW_MISSING;
-            if (later) t.entry[me].handled = 1;
+    if (ok && touched != 0) {
+        uint32_t val[BW_MAX];
+        const uint32_t writers = bw_lookup_steps(t.wrote, (uint32_t)prow, touched, val);
+        const uint32_t upto = writers & ((2u << s) - 1u);
+        if (upto != 0) {
+            const int q = 31 - __builtin_clz(upto);            // the latest write up to this step
+            uint32_t v = 0;
+#pragma unroll
+            for (int i = 0; i < BW_MAX; ++i) v = i == q ? val[i] : v;
+            t.entry[me].src = (q << 16) | (int)(v >> 16);
+        } else if (writers != 0) {
+            t.entry[me].handled = 1;                           // overwritten by a later step, whose workgroups hand the old content out
         }
     }
     if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
@@ -550,7 +597,9 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_plan_kernel(const BwPlanArg
 // All steps of one window by its table: every group of BIG_GROUP threads moves one tile of one row; the
 // first 2 next.w workgroups plan the next window instead.
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+template <int U, int W, bool NT, bool BF16>   // W: threads that move one tile together (short rows: one wavefront, which then has the
+                                              // most bytes in flight; a compute unit holds a fixed number of wavefronts, not of bytes);
+                                              // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
 __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, const BwPlanArgs next)
 {
     extern __shared__ uint32_t lds[];
@@ -564,7 +613,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     }
     const int rows = m.c + m.r;
     const int64_t per_step = (int64_t)rows * m.tpr;
-    const int64_t item = (int64_t)((int)blockIdx.x - planners) * BIG_GROUPS + threadIdx.x / BIG_GROUP;
+    const int64_t item = (int64_t)((int)blockIdx.x - planners) * (BIG_TPB / W) + threadIdx.x / W;
     if (item >= per_step * m.w) return;
     const int s = (int)(item / per_step);
     int e, tile;
@@ -572,9 +621,9 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     const WinHeader* head = reinterpret_cast<const WinHeader*>(m.table + BW_OFF_HEAD);
     const BwFlags* flags = reinterpret_cast<const BwFlags*>(m.table + BW_OFF_FLAGS);
     const WinEntry* entry = reinterpret_cast<const WinEntry*>(m.table + BW_OFF_ENTRY);
-    const int lane = threadIdx.x & (BIG_GROUP - 1);
+    const int lane = threadIdx.x & (W - 1);
     const bool first = tile == 0 && lane == 0;
-    if (bw_get(&flags->failed) == m.number) {           // the planners of this window gave up on each other: nothing is moved
+    if (flags->failed == m.number) {           // (written by the launch before: an ordinary, cached load)           // the planners of this window gave up on each other: nothing is moved
         if (item == 0 && first) atomicOr(&m.state->flags, (uint32_t)RB_FLAG_PLAN_TIMEOUT);
         return;
     }
@@ -597,13 +646,13 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
             // Representatives of earlier steps need what the slot held before the window (those that the sampling planner
             // of their step marked as handed out from here).  Every lane copies its own vectors out to them and only then
             // overwrites these same vectors: no lane waits for another.
-            const uint32_t* read_tables = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_READ);
+            const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(m.table + BW_OFF_READ);
             vec16* reader_x[BW_MAX - 1];             // (indexed by compile-time constants only: registers) of step q, null: none
 #pragma unroll
             for (int q = 0; q < BW_MAX - 1; ++q) {
                 reader_x[q] = nullptr;
                 if (q >= s) continue;
-                const uint32_t j = bw_lookup(read_tables + (size_t)q * 2 * BIG_HASH, (uint32_t)en.row);
+                const uint32_t j = bw_lookup(read_tables + (size_t)q * BIG_HASH, (uint32_t)en.row);
                 if (j == BW_MISSING) continue;
                 const WinEntry rq = entry[q * rows + m.c + (int)j];
                 if (!rq.handled) continue;
@@ -615,7 +664,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
             }
             if (BF16) {
                 vec8* half = reinterpret_cast<vec8*>(slot);
-                for (int64_t i = 2 * v_lo + lane; i < 2 * v_hi; i += BIG_GROUP) {
+                for (int64_t i = 2 * v_lo + lane; i < 2 * v_hi; i += W) {
                     const vec16 old = widen4(half[i]);
 #pragma unroll
                     for (int q = 0; q < BW_MAX - 1; ++q)
@@ -623,7 +672,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
                     half[i] = narrow4(fresh[i]);
                 }
             } else {
-                for (int64_t i = v_lo + lane; i < v_hi; i += BIG_GROUP) {
+                for (int64_t i = v_lo + lane; i < v_hi; i += W) {
                     const vec16 old = slot[i];
 #pragma unroll
                     for (int q = 0; q < BW_MAX - 1; ++q)
@@ -633,7 +682,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
             }
             return;
         }
-        Tile<U, NT, BIG_GROUP, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
+        Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
         t.load(fresh, v_lo, v_hi);
         t.store(slot, v_lo, v_hi);
         return;
@@ -646,13 +695,13 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
     if (BF16 && en.src >= 0) {
         // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
-        Tile<U, NT, BIG_GROUP, WIN_PACE, CV_BOTH> t;
+        Tile<U, NT, W, WIN_PACE, CV_BOTH> t;
         t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
                                        : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, BIG_GROUP, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, W, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }
