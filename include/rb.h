@@ -120,9 +120,10 @@ int rb_set_storage(rb_buffer *rb, int32_t storage);
  * offered fewer than 2^31 - 1 samples).
  * With a variant selected a plain rb_update_sample enqueues the two general
  * kernels.  The plan-ahead forms of the single launch (rb_announce_next) serve
- * every variant (the Bernoulli selection for b <= 1024), and the several-steps
- * launch (rb_update_sample_many) serves FIFO and reservoir with the exact
- * selection.  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update was already
+ * every variant (the Bernoulli selection for b <= 1024), and so do the
+ * several-steps launches of rb_update_sample_many (the form for small counts
+ * with the exact selection only; the form for large counts takes over for the
+ * Bernoulli selection, again for b <= 1024).  RB_EINVAL: unknown value.  RB_ESTATE: an rb_update was already
  * enqueued since the last rb_bind.
  */
 enum rb_selection { RB_SELECT_EXACT = 0, RB_SELECT_BERNOULLI = 1 };
@@ -245,7 +246,13 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * the order of separate launches would settle between steps (a representative
  * read from a slot that another step of the same launch writes, a slot written
  * twice) the plan settles, so the cost of a launch is paid once per that many
- * steps.  Otherwise the steps are enqueued one after the other, each
+ * steps.  Beyond those limits, for up to 1024 candidates and representatives,
+ * b <= 4096 (b <= 1024 with the Bernoulli selection) and up to 10240 classes,
+ * up to 8 steps share one launch in the same way; their plan is made by two
+ * workgroups per step of the launch before, which work side by side (should
+ * they ever fail to hear from each other within 2 s, that launch moves nothing
+ * and raises RB_FLAG_PLAN_TIMEOUT).  Otherwise the steps are enqueued one
+ * after the other, each
  * announcing the next one's labels (rb_announce_next) for itself.  Step i uses
  * batch_x[i], batch_y[i], step number first_step + i and writes to out_x[i],
  * out_y[i]; b, c, r and seed are common.  The four pointer arrays are HOST
@@ -253,6 +260,8 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * validated first; on an error nothing was enqueued.  Results are those of n
  * separate calls, bit for bit.
  * The outputs and mini-batches of any 16 consecutive steps must not overlap.
+ * The workspace behind the handle is used by the launches of this call while
+ * they run: one stream of calls per handle.
  */
 int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, const int64_t *const *batch_y,
                           int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step,

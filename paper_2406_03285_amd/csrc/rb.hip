@@ -694,7 +694,7 @@ Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
 int64_t bigwin_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
     const bool eligible = c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES && rb->opt_fuse &&
-                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->K * rb->S <= INT64_C(0x7FFFFFFF) &&
+                          rb->opt_window >= 2 && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) && rb->K * rb->S <= INT64_C(0x7FFFFFFF) &&
                           rb->S <= INT32_MAX - (int64_t)BW_MAX * RB_MAX_BATCH;
     if (!eligible) return 1;
     return std::min<int64_t>(BW_MAX, rb->opt_window);
@@ -716,6 +716,8 @@ BwPlanArgs bigwin_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_
     p.K = (int32_t)rb->K; p.nchunks = rb->nchunks;
     p.S = rb->S;
     p.eviction = rb->eviction;
+    p.selection = rb->selection;
+    p.ce = (int32_t)(rb->selection == RB_SELECT_BERNOULLI ? b : c);     // with the Bernoulli selection one thread and one entry per position
     rb->bw_number += 1;
     if (rb->bw_number == 0) rb->bw_number = 1;          // 0 is what a cleared flag shows
     p.number = rb->bw_number;
@@ -738,8 +740,15 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
 {
     static_assert(BW_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
     const int64_t wmax = bigwin_limit(rb, b, c, r);
+    // candidate entries of a step in the table, and how many of them the grid covers: all c, or, with the Bernoulli selection
+    // (about c of the b positions are selected), c and eight standard deviations (more are served by going round)
+    const bool bernoulli = rb->selection == RB_SELECT_BERNOULLI;
+    const int64_t ce = bernoulli ? b : c;
+    int64_t margin = 16;
+    while (margin * margin < 64 * c) ++margin;
+    const int64_t cgrid = bernoulli ? std::min(b, c + margin) : c;
     int width;
-    const Shape sh = bigwin_shape(rb, wmax * (c + r), width);
+    const Shape sh = bigwin_shape(rb, wmax * (cgrid + r), width);
     const double move_us = (double)(c + r) * (double)(rb->row_bytes + rb->sample_bytes) / 5.5e6;
     int64_t w0 = 1;
     while (w0 < wmax && move_us * (double)w0 < 12.0) ++w0;
@@ -778,7 +787,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
         m.buf_y = rb->buf_y;
         m.table = rb->ws + rb->off_bwtbl[tbl];
         m.state = reinterpret_cast<DevState*>(rb->ws);
-        m.w = (int32_t)w; m.c = (int32_t)c; m.r = (int32_t)r;
+        m.w = (int32_t)w; m.c = (int32_t)ce; m.r = (int32_t)r; m.cgrid = (int32_t)cgrid;
         m.number = rb->bw_table_number[tbl];
         m.S = rb->S;
         m.row_vec = rb->row_vec;
@@ -786,7 +795,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
         BwPlanArgs next = {};
         if (ahead) next = bigwin_plan_args(rb, ann_y, 0, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1);
         else if (next_w > 0) next = bigwin_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, tbl ^ 1);
-        const int64_t items = w * (c + r) * sh.tpr;
+        const int64_t items = w * (cgrid + r) * sh.tpr;
         const int64_t per_block = BIG_TPB / width;
         const dim3 grid((unsigned)((items + per_block - 1) / per_block + 2 * next_w));
         const bool bf16 = rb->storage == RB_STORE_BF16;

@@ -48,6 +48,7 @@ struct BwFlags {
     uint32_t sample[BW_MAX];    // ... once step s's sampling planner has published entries and read table (B)
     uint32_t failed;            // = the window's number if a planner gave up waiting
     uint32_t pad[7];
+    uint32_t count[BW_MAX];     // candidate entries of step s (the Bernoulli selection yields any number of them)
 };
 constexpr size_t BW_OFF_HEAD = 0;                                                    // BW_MAX WinHeader
 constexpr size_t BW_OFF_FLAGS = BW_OFF_HEAD + BW_MAX * sizeof(WinHeader);            // BwFlags
@@ -72,6 +73,8 @@ struct BwPlanArgs {
     int64_t S;
     int32_t eviction;                  // RB_EVICT_*
     uint32_t number;                   // the window's number (never 0): what its flags are set to
+    int32_t selection;                 // RB_SELECT_*
+    int32_t ce;                        // candidate entries per step in the table: c, or b with the Bernoulli selection (one thread per position)
     const int32_t* aux_old;            // per class: FIFO: slot of the oldest sample; RESERVOIR: samples offered so far
     int32_t* aux_new;
 };
@@ -84,7 +87,8 @@ struct BwMoveArgs {
     int64_t* buf_y;
     const char* table;
     DevState* state;
-    int32_t w, c, r;
+    int32_t w, c, r;                   // c: candidate entries per step in the table (BwPlanArgs::ce)
+    int32_t cgrid;                     // candidate rows per step that the grid covers (with the Bernoulli selection c and a margin; the groups go round)
     uint32_t number;                   // the number of the window this table was planned as
     int64_t S;
     int64_t row_vec;
@@ -228,13 +232,14 @@ __device__ __forceinline__ PlanArgs bw_step_args(const BwPlanArgs& a, int s)
     p.S = a.S;
     p.eviction = a.eviction;
     p.aux_old = a.aux_old; p.aux_new = nullptr;
-    p.selection = RB_SELECT_EXACT;
-    p.ce = a.c;
+    p.selection = a.selection;
+    p.ce = a.ce;
     return p;
 }
 
 // ---------------------------------------------------------------------------
-// Update planner of step s of the window (Alg. 1): thread i = candidate i of Floyd's emission order.
+// Update planner of step s of the window (Alg. 1): thread i = candidate i of Floyd's emission order, or, with the
+// Bernoulli selection (mini-batches of at most BIG_MAX), mini-batch position i, which is a candidate if its coin says so.
 // LDS as in plan_big_update.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint32_t* lds)
@@ -247,7 +252,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     __shared__ int s_ok;
 
     const int tid = threadIdx.x;
-    const int c = a.c, w = a.w, rows = a.c + a.r;
+    const int ce = a.ce, w = a.w, rows = a.ce + a.r;
     const int64_t S = a.S;
     const BwTable t = bw_table(a.table);
     const PlanArgs pa = bw_step_args(a, s);
@@ -260,11 +265,16 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     const bool strategy = a.eviction != RB_EVICT_UNIFORM;
     const int64_t before_window = valid ? s_fill[k] : 0;             // samples of the class stored before the window
     const int64_t aux_window = strategy && valid ? a.aux_old[k] : 0;  // the strategy's state before the window
-    if (tid < c) bw_put(reinterpret_cast<uint32_t*>(t.classes) + s * BIG_MAX + tid, (uint32_t)k);   // LAB_INVALID for a label outside [0, K)
+    if (tid < ce) bw_put(reinterpret_cast<uint32_t*>(t.classes) + s * BIG_MAX + tid, (uint32_t)k);   // LAB_INVALID: label outside [0, K); LAB_UNSELECTED: tails
+    // table entry of the thread's candidate: its number in Floyd's emission order, or its number among the selected positions
+    int ent = tid, count = ce;
+    if (a.selection == RB_SELECT_BERNOULLI) ent = big_scan_excl(k != LAB_UNSELECTED ? 1 : 0, count, s_wave);
+    const bool has_entry = a.selection == RB_SELECT_BERNOULLI ? k != LAB_UNSELECTED : tid < ce;
+    if (tid == 0) t.flags->count[s] = (uint32_t)count;
     bw_publish(&t.flags->classes[s], a.number);
     bool ok = bw_await(t.flags->classes, 0, s, a.number, &s_ok);
     // the candidates that the steps before this one bring
-    if (ok && tid < c)
+    if (ok && tid < ce)
         for (int q = 0; q < s; ++q) {
             const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
             if (kq >= 0) atomicAdd(&s_fill[kq], 1);
@@ -346,8 +356,8 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     const bool stored = placed && rval[hr] == (uint32_t)x + 1u;
     __syncthreads();
     if (stored) rval[hr] = ((uint32_t)x << 16) | (uint32_t)tid;
-    const int me = s * rows + tid;
-    if (tid < c) {
+    const int me = s * rows + ent;
+    if (has_entry) {
         WinEntry e;
         e.src = x;
         e.label = valid ? k : -1;
@@ -369,7 +379,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     uint32_t* cmask = s_draw;
     for (int i = tid; i < BIG_HASH / 4; i += BIG_TPB) cmask[i] = 0;
     __syncthreads();
-    if (ok && tid < c) {
+    if (ok && tid < ce) {
         int32_t kq[BW_MAX];
 #pragma unroll
         for (int q = 0; q < BW_MAX; ++q) kq[q] = q < w && q != s ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
@@ -414,7 +424,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
     __shared__ uint32_t s_flags;
 
     const int tid = threadIdx.x;
-    const int c = a.c, r = a.r, K = a.K, w = a.w, rows = a.c + a.r;
+    const int ce = a.ce, r = a.r, K = a.K, w = a.w, rows = a.ce + a.r;
     const int64_t S = a.S;
     const bool last = s == w - 1;
     const BwTable t = bw_table(a.table);
@@ -443,7 +453,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
 
     // ---- the candidates of this step and of the steps before it: how many every class gets; which classes the later steps touch ----
     bool ok = bw_await(t.flags->classes, 0, w, a.number, &s_ok);
-    if (ok && tid < c)
+    if (ok && tid < ce)
         for (int q = 0; q < w; ++q) {
             const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
             if (kq >= 0) {
@@ -542,7 +552,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) rkey[i] = BIG_EMPTY;
     __syncthreads();
     if (drawing) rval[big_find_or_insert(rkey, (uint32_t)prow)] = (uint32_t)tid;      // (the representatives of a step are different samples)
-    const int me = s * rows + c + tid;
+    const int me = s * rows + ce + tid;
     if (tid < r) {
         WinEntry e;
         e.src = -1;
@@ -611,8 +621,8 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
         else bw_plan_update(next, s, lds);
         return;
     }
-    const int rows = m.c + m.r;
-    const int64_t per_step = (int64_t)rows * m.tpr;
+    const int rows = m.c + m.r;                 // entries per step in the table
+    const int64_t per_step = (int64_t)(m.cgrid + m.r) * m.tpr;
     const int64_t item = (int64_t)((int)blockIdx.x - planners) * (BIG_TPB / W) + threadIdx.x / W;
     if (item >= per_step * m.w) return;
     const int s = (int)(item / per_step);
@@ -623,11 +633,10 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     const WinEntry* entry = reinterpret_cast<const WinEntry*>(m.table + BW_OFF_ENTRY);
     const int lane = threadIdx.x & (W - 1);
     const bool first = tile == 0 && lane == 0;
-    if (flags->failed == m.number) {           // (written by the launch before: an ordinary, cached load)           // the planners of this window gave up on each other: nothing is moved
+    if (flags->failed == m.number) {           // the planners of this window gave up on each other: nothing is moved
         if (item == 0 && first) atomicOr(&m.state->flags, (uint32_t)RB_FLAG_PLAN_TIMEOUT);
         return;
     }
-    const WinEntry en = entry[s * rows + e];
     int64_t v_lo, v_hi;
     tile_bounds(tile, m.tile_vec, m.tile_rem, m.row_vec, v_lo, v_hi);
     if (item == 0 && first) {
@@ -637,17 +646,23 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
         if (raised != 0) atomicOr(&m.state->flags, raised);
     }
     constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
-    if (e < m.c) {
-        if (en.row < 0) return;                 // dropped within its step, or overwritten again later in the window
-        vec16* slot = m.buf_x + en.row * m.row_vec;
-        const vec16* fresh = m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE;
-        if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-        if (en.chain >= 0) {
+    if (e < m.cgrid) {
+        const auto store_candidate = [&](const WinEntry& en) {
+            if (en.row < 0) return;             // dropped within its step, or overwritten again later in the window
+            vec16* slot = m.buf_x + en.row * m.row_vec;
+            const vec16* fresh = m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE;
+            if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
+            if (en.chain < 0) {
+                Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
+                t.load(fresh, v_lo, v_hi);
+                t.store(slot, v_lo, v_hi);
+                return;
+            }
             // Representatives of earlier steps need what the slot held before the window (those that the sampling planner
             // of their step marked as handed out from here).  Every lane copies its own vectors out to them and only then
             // overwrites these same vectors: no lane waits for another.
             const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(m.table + BW_OFF_READ);
-            vec16* reader_x[BW_MAX - 1];             // (indexed by compile-time constants only: registers) of step q, null: none
+            vec16* reader_x[BW_MAX - 1];        // (indexed by compile-time constants only: registers) of step q, null: none
 #pragma unroll
             for (int q = 0; q < BW_MAX - 1; ++q) {
                 reader_x[q] = nullptr;
@@ -680,15 +695,19 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
                     slot[i] = fresh[i];
                 }
             }
-            return;
-        }
-        Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
-        t.load(fresh, v_lo, v_hi);
-        t.store(slot, v_lo, v_hi);
+        };
+        // The grid covers cgrid candidate rows per step; when the plan has more (Bernoulli selection), a group goes on to
+        // the entry cgrid further on.  (The first entry is asked for before the step's count is known: it is inside the
+        // step's part of the table whatever the count.)
+        const WinEntry en0 = entry[s * rows + e];
+        const int count = (int)flags->count[s];
+        if (e < count) store_candidate(en0);
+        for (int ee = e + m.cgrid; ee < count; ee += m.cgrid) store_candidate(entry[s * rows + ee]);
         return;
     }
+    const int j = e - m.cgrid;
+    const WinEntry en = entry[s * rows + m.c + j];
     if (en.handled) return;
-    const int j = e - m.c;
     if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
     if (first) count_moved(m.state);

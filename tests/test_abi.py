@@ -124,5 +124,6 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 5) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 17) == rb.RB_EINVAL
     assert rb.rb_set_policy(h, rb.RB_SELECT_EXACT, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
-    assert rb.rb_set_policy(h, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 1)
+    assert rb.rb_set_policy(h, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)   # the large-count form takes it
+    assert rb.rb_query_steps_per_launch(h, 1025, 8, 8) == (rb.RB_OK, 1)         # ... for mini-batches of at most 1024
     rb.rb_destroy(h)

@@ -525,7 +525,7 @@ def test_many_steps_policy_bf16_and_broken_promises_together():
     w = wl.variant(wl.C1, name="C1-many-fifo-bf16-promises", K=4, S=5, c=12, r=12)
     run_many_parity(w, 90, per_call=9, announce=True, schedule_seed=7, store_bf16=True, policy=POLICIES["exact-fifo"])
     run_many_parity(w, 90, per_call=9, announce=True, schedule_seed=8, store_bf16=True, policy=POLICIES["exact-reservoir"])
-    # the Bernoulli selection has no bound of 64 on its candidates: the steps go out one by one, results unchanged
+    # the Bernoulli selection has no bound of 64 on its candidates: the large-count form takes these steps, results unchanged
     run_many_parity(w, 30, per_call=9, announce=True, policy=POLICIES["bernoulli-fifo"])
 
 
@@ -610,6 +610,11 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     (wl.variant(wl.C5, name="bw-K40-reservoir", K=40, S=10, shape=(64,), b=512, c=200, r=150), "exact-reservoir", False),
     (wl.variant(wl.C5, name="bw-two-classes-bf16", K=2, S=40, shape=(64,), b=256, c=100, r=70), None, True),    # old content handed on through the conversion
     (wl.variant(wl.C5, name="bw-K300-bf16-fifo", K=300, S=12, shape=(264,), b=512, c=200, r=150), "exact-fifo", True),
+    (wl.variant(wl.C5, name="bw-K300-bernoulli", K=300, S=12, shape=(256,), b=1024, c=400, r=150), "bernoulli-uniform", False),   # the largest mini-batch the Bernoulli selection may have here
+    (wl.variant(wl.C4, name="bw-C4-S8-bernoulli", S=8, shape=(3, 32, 32)), "bernoulli-uniform", False),        # small counts: the small form does not take this selection
+    (wl.variant(wl.C1, name="bw-C1-bernoulli-fifo", S=5), "bernoulli-fifo", False),                             # about 4 of 16 positions; fills up, replaces
+    (wl.variant(wl.C5, name="bw-two-classes-bernoulli-reservoir-bf16", K=2, S=40, shape=(64,), b=256, c=100, r=70), "bernoulli-reservoir", True),
+    (wl.variant(wl.C1, name="bw-c-equals-b-bernoulli", b=64, c=64, r=20, S=3), "bernoulli-uniform", False),     # every coin shows heads
     (wl.variant(wl.C2, name="bw-K1100-few", K=1100, S=2), None, False),                                         # few candidates, too many classes for the small form
     (wl.variant(wl.C5, name="bw-limits", K=10240, S=3, shape=(16,), b=4096, c=1024, r=1024), None, False),      # every limit at once
 ], ids=lambda v: v.name if hasattr(v, "name") else None)
@@ -629,6 +634,8 @@ def test_many_steps_with_large_counts(w, policy, bf16, window):
 def test_many_steps_with_large_counts_survive_broken_promises(seed):
     run_many_parity(wl.variant(wl.C5, name=f"bw-promises-{seed}", K=30, S=12, shape=(64,), b=512, c=200, r=150), 160, per_call=12,
                     announce=True, schedule_seed=seed)
+    run_many_parity(wl.variant(wl.C4, name=f"bw-promises-bernoulli-{seed}", S=8, shape=(3, 32, 32), b=128, c=40, r=40), 120, per_call=12,
+                    announce=True, schedule_seed=seed + 20, policy=POLICIES["bernoulli-uniform"])
 
 
 def test_many_steps_with_large_counts_drop_and_flag_bad_labels():
