@@ -31,9 +31,9 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # `bench.py --pmc-run`, each scaled by the reading of a plain copy of known size in the same run; the text summaries
 # with the exact commands are the files named here.  Not measured by this run: the line says where it is from.
 PROFILED_TRAFFIC = {
-    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75720610, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),
-    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19272153, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),
-    ("C5-10000x1000-f32-2048-active50", "rb_step_big_kernel"): (34009498, "profiles/rb_step_big_kernel_C5_pmc_hbm_traffic.txt"),
+    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75727346, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),   # algorithmic 77070336: slot losers are not moved, forwarded rows hit the cache
+    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19272954, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),          # algorithmic 19267584
+    ("C5-10000x1000-f32-2048-active50", "rb_bigwin_kernel"): (34017989, "profiles/rb_bigwin_kernel_C5_pmc_hbm_traffic.txt"),    # algorithmic 33554432
 }
 
 MANY = 64           # steps handed to one rb_update_sample_many call
@@ -495,9 +495,9 @@ def reduced_precision_leg(torch, rb, wl, steps=1000):
 
 
 def variants_leg(w, torch, rb, wl, steps):
-    """The policy variants of Algorithm 1 on the same workload.  The other replacement strategies go through the
-    same announced multi-step calls as the headline (several steps per launch); the Bernoulli selection has no
-    bound on its number of candidates and always takes the general kernels (two launches per step)."""
+    """The policy variants of Algorithm 1 on the same workload, all through the same announced multi-step calls as
+    the headline: the other replacement strategies in the same several-steps launch, the Bernoulli selection (whose
+    number of candidates is only bounded by b) in the several-steps launch for large counts."""
     out = {}
     names = {(1, 0): "bernoulli+uniform", (0, 1): "exact+fifo", (0, 2): "exact+reservoir", (1, 1): "bernoulli+fifo"}
     small = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024
