@@ -55,7 +55,7 @@ class Rig:
         self.buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=self.dev, stream=self.stream,
                                       storage=storage, store_dtype=store_dtype)
         aug_bytes = (w.b + w.r) * w.row_bytes
-        self.P = pool_slots or min(1024, max(16, -(-POOL_BYTES // aug_bytes)))
+        self.P = pool_slots or min(1024, max(32, -(-POOL_BYTES // aug_bytes)))
         self.aug_x = torch.empty((self.P, w.b + w.r, *w.shape), dtype=w.torch_dtype, device=self.dev)
         self.aug_y = torch.empty((self.P, w.b + w.r), dtype=torch.int64, device=self.dev)
         # distinct sample bytes for a few slots, replicated over the pool (generation is not what is measured);
@@ -76,7 +76,7 @@ class Rig:
             bx, by = self.aug_x[i].data_ptr(), self.aug_y[i].data_ptr()
             self.args.append((bx, by, bx + w.b * rs, by + w.b * 8))
         # host arrays of the same pointers for rb_update_sample_many: the pool several times over, so that any run
-        # of up to MANY consecutive steps is contiguous (the pool has at least 16 slots: the steps that share a
+        # of up to MANY consecutive steps is contiguous (the pool has at least 32 slots: the steps that share a
         # launch never share a slot)
         self.ptrs = [rb.pointer_array([a[i] for a in self.args] * (2 + MANY // self.P)) for i in range(4)]
         self.step = 0
@@ -117,7 +117,7 @@ class Rig:
                 if ahead:
                     o_next = ((t + k) % P) * C.sizeof(C.c_void_p)
                     nxt = min(many, n - (at + k)) or many           # steps of the call that follows (the next enqueue's first, at the end)
-                    rb.rb_announce_next_many(h, min(16, nxt), C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
+                    rb.rb_announce_next_many(h, min(32, nxt), C.cast(C.byref(self.ptrs[1], o_next), C.POINTER(C.c_void_p)))
                 rc = rb.rb_update_sample_many(h, k, px, py, b, c, r, seed, t, ox, oy)
                 if rc:
                     raise RuntimeError(f"rb_update_sample_many -> {rc}")
@@ -402,7 +402,7 @@ def measure(w, torch, rb, wl, steps, warmup, prefill):
     ms_two = rig.timed(n_side)
     rig.buf.set_option(rb.RB_OPT_WINDOW, 1)
     ms_many1 = rig.timed(n_side // MANY * MANY or MANY, many=MANY)   # rb_update_sample_many held to one launch per step
-    rig.buf.set_option(rb.RB_OPT_WINDOW, 16)
+    rig.buf.set_option(rb.RB_OPT_WINDOW, 32)
     # One kernel alone, launched back to back on the same stream with HIP events around the whole
     # loop: launches pipeline, so the time per launch is that kernel's duration plus the dispatch
     # gap (an event pair around every single launch would add several microseconds to each).

@@ -239,7 +239,7 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * for callers that have several mini-batches ready (e.g. a prefetching data
  * pipeline).  When 1 <= c <= 64, 1 <= r <= 64, classes <= 1024, b <= 2048 and
  * the selection is the exact one (any replacement strategy, either storage
- * form), up to 16 of the steps
+ * form), up to 32 of the steps
  * - as many as 1024 / (c + r) and 512 / max(c, r) allow, see
  * rb_query_steps_per_launch - share ONE launch: the rows of all of them are
  * moved at once, by a plan that one workgroup of the launch before made.  What
@@ -259,7 +259,7 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * arrays of n device pointers, read before the call returns.  All n steps are
  * validated first; on an error nothing was enqueued.  Results are those of n
  * separate calls, bit for bit.
- * The outputs and mini-batches of any 16 consecutive steps must not overlap.
+ * The outputs and mini-batches of any 32 consecutive steps must not overlap.
  * The workspace behind the handle is used by the launches of this call while
  * they run: one stream of calls per handle.
  */
@@ -271,7 +271,7 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
  * rb_announce_next for rb_update_sample_many: the labels of the first n steps
  * of the call AFTER the next rb_update_sample_many call (the data pipeline has
  * them already).  The last launch of the next call then also plans those steps
- * (at most 16, and at most what one launch covers), so that the call after it
+ * (at most 32, and at most what one launch covers), so that the call after it
  * starts moving rows at once instead of planning its first steps in a launch
  * of its own.  The plan is used if that later call comes with the same b, c,
  * r and seed, with first_step continuing where the call before ended, with at
@@ -283,7 +283,7 @@ int rb_update_sample_many(rb_buffer *rb, int64_t n, const void *const *batch_x, 
  * rb_announce_next for the call's last step.  The announcement serves the one
  * next rb_update_sample_many call and is forgotten by any other call.
  * next_batch_y: HOST array of n device pointers (read before the call
- * returns; only the first 16 are kept), each to b int64 labels that must be in
+ * returns; only the first 32 are kept), each to b int64 labels that must be in
  * place, as far as the bound stream is concerned, when the next call is
  * enqueued, and stay unchanged until their steps have run.  n = 0 withdraws.
  * RB_EINVAL: null rb, n < 0, null or misaligned label pointers.
@@ -387,7 +387,7 @@ int rb_read_moved_rows(rb_buffer *rb, uint64_t *rows_host);
  * the other when a row fits a single tile (0 = automatic, else 1..16).
  * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
  * 0 makes it always enqueue the two kernels.  RB_OPT_WINDOW: most steps that
- * rb_update_sample_many puts into one launch (1..16, default 16; 1 = one
+ * rb_update_sample_many puts into one launch (1..32, default 32; 1 = one
  * launch per step). */
 enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);

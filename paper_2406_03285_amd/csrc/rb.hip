@@ -80,10 +80,10 @@ struct rb_buffer {
     const int64_t* next_y;   // announced labels of the next mini-batch, consumed by the next rb_update_sample
     // several steps per launch: labels announced for the call after the next rb_update_sample_many, and the
     // window that the last launch of a call planned for them
-    const int64_t* ann_y[16];
+    const int64_t* ann_y[WIN_MAX];
     int64_t ann_n;
     bool wplan_valid;        // a window has been planned (and the fill counts advanced) but not yet executed
-    const int64_t* wplan_y[16];
+    const int64_t* wplan_y[WIN_MAX];
     int64_t wplan_w, wplan_b, wplan_c, wplan_r;
     uint64_t wplan_seed, wplan_first;
     int wplan_tbl;           // table that holds it
@@ -553,7 +553,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                    int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
                    int64_t ann_n, const int64_t* const* ann_y)
 {
-    static_assert(WIN_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
+    static_assert(sizeof(rb_buffer::ann_y) / sizeof(void*) >= WIN_MAX, "announced labels and planned windows are kept for a whole launch");
     const int64_t wmax = window_limit(rb, b, c, r);
     // With thousands of workgroups per launch, and the planner's LDS leaving room for four workgroups per
     // compute unit, tiles of four vectors per thread measured best (1000 classes of 3x224x224 bfloat16 samples,
@@ -738,7 +738,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
                  int64_t r, uint64_t seed, uint64_t first_step, void* const* out_x, int64_t* const* out_y,
                  int64_t ann_n, const int64_t* const* ann_y)
 {
-    static_assert(BW_MAX <= 16, "announced labels and planned windows are kept for at most 16 steps");
+    static_assert(BW_MAX <= WIN_MAX, "announced labels and planned windows are kept for at most WIN_MAX steps");
     const int64_t wmax = bigwin_limit(rb, b, c, r);
     // candidate entries of a step in the table, and how many of them the grid covers: all c, or, with the Bernoulli selection
     // (about c of the b positions are selected), c and eight standard deviations (more are served by going round)

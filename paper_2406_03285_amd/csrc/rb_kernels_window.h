@@ -10,7 +10,7 @@
 
 namespace {
 
-constexpr int WIN_MAX = 16;                   // most steps one launch covers ...
+constexpr int WIN_MAX = 32;                   // most steps one launch covers ...
 constexpr int WIN_ENTRIES = 1024;             // ... as long as steps * (c + r) table entries do not exceed this
 constexpr int WIN_SLOTS = 512;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
 constexpr int WIN_PACE = 64;                  // stores of a tile go out in one burst once its loads have arrived (no wait between them)

@@ -236,7 +236,7 @@ def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule
             _bytes(oxs[i]).fill_(SENTINEL)
             oys[i].fill_(-7)
         if announce and nys:
-            buf.announce_next_many(nys[:16])
+            buf.announce_next_many(nys[:32])
         if first % (2 * per_call) == 0:
             rc = rb.rb_update_sample_many(buf.handle, n, xs, ys, w.b, c, w.r, w.lib_seed, first, oxs[:n], oys[:n])
             assert rc == rb.RB_OK, rc

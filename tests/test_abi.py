@@ -114,7 +114,7 @@ def test_variant_setters_validate_on_the_host():
     # steps per launch of the multi-step call: host arithmetic only
     assert rb.rb_query_steps_per_launch(None, 8, 2, 2)[0] == rb.RB_EINVAL
     assert rb.rb_query_steps_per_launch(h, 0, 0, 0)[0] == rb.RB_EINVAL and rb.rb_query_steps_per_launch(h, 8, 9, 2)[0] == rb.RB_EINVAL
-    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16)            # few rows per step: the most
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)            # few rows per step: the most
     assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 8)          # 1024 table entries / 128 rows per step
     assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 12)         # 512 planner slots / max(c, r)
     assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 8)           # beyond the small form: the large-count form's 8
@@ -122,7 +122,7 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_query_steps_per_launch(h, 4096, 1025, 8) == (rb.RB_OK, 1)        # not eligible for either
     assert rb.rb_query_steps_per_launch(h, 64, 0, 8) == (rb.RB_OK, 1)
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 5) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
-    assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 17) == rb.RB_EINVAL
+    assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 33) == rb.RB_EINVAL
     assert rb.rb_set_policy(h, rb.RB_SELECT_EXACT, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
     assert rb.rb_set_policy(h, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)   # the large-count form takes it
     assert rb.rb_query_steps_per_launch(h, 1025, 8, 8) == (rb.RB_OK, 1)         # ... for mini-batches of at most 1024

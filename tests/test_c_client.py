@@ -27,7 +27,7 @@ CLIENT = textwrap.dedent(r"""
         if (rb_create(&rb, 1000, 130, shape, 3, RB_F32) != RB_OK || !rb) return 1;
         if (rb_query_sizes(rb, &xb, &yb, &wb) != RB_OK) return 2;
         if (xb != (size_t)1000 * 130 * 602112 || yb != (size_t)1000 * 130 * 8 || wb == 0 || wb % 256 != 0) return 3;
-        if (rb_query_steps_per_launch(rb, 64, 8, 8, &steps) != RB_OK || steps != 16) return 4;
+        if (rb_query_steps_per_launch(rb, 64, 8, 8, &steps) != RB_OK || steps != 32) return 4;
         if (rb_set_option(rb, RB_OPT_WINDOW, 4) != RB_OK) return 5;
         if (rb_query_steps_per_launch(rb, 64, 8, 8, &steps) != RB_OK || steps != 4) return 6;
         if (rb_set_policy(rb, RB_SELECT_EXACT, RB_EVICT_RESERVOIR) != RB_OK) return 7;

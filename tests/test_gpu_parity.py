@@ -418,7 +418,7 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
 
 # ------------------------------------------------ several steps from one call ---
 
-@pytest.mark.parametrize("window", [16, 8, 3, 1])
+@pytest.mark.parametrize("window", [32, 16, 8, 3, 1])
 @pytest.mark.parametrize("w", [
     wl.variant(wl.C2, name="C2-many", S=4),
     wl.variant(wl.C5, name="C5-many", K=300, S=12, shape=(256,), b=512, c=200, r=150),
@@ -430,7 +430,7 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
 def test_many_steps_from_one_call(w, window):
     rb = _rb()
     dev = torch.device("cuda:0")
-    n = 18
+    n = 36 if window == 32 else 18
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
     buf.set_option(rb.RB_OPT_WINDOW, window)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
@@ -468,7 +468,7 @@ def test_many_steps_from_one_call(w, window):
 def test_many_steps_at_full_size(w, steps, announce):
     """The configuration the bench times: real shapes, 16 (C3) or 8 (C4) steps per launch, calls announced: every
     configured step.  Without the announcement: a shorter run."""
-    run_many_parity(w, w.steps if FULL or announce else steps, per_call=32 if announce else 24, announce=announce)
+    run_many_parity(w, w.steps if FULL or announce else steps, per_call=64 if announce else 24, announce=announce)
 
 
 @pytest.mark.parametrize("w,steps,per_call", [
@@ -566,7 +566,7 @@ def test_an_announced_call_that_never_comes_is_forgotten():
     compare_buffers(buf, orc, "final")
 
 
-@pytest.mark.parametrize("window", [16, 8, 4, 2])
+@pytest.mark.parametrize("window", [32, 16, 8, 4, 2])
 def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     """Eight classes of one slot each, every step samples all eight rows and rewrites one class (the label
     sequence decides which): rows that are read before a later step of the same launch overwrites them, rows
@@ -1006,7 +1006,7 @@ def test_random_configurations_planned_ahead(chunk):
         style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
         per_call = int(rng.choice([3, 8, 17, 33]))
         options = ((rb.RB_OPT_UNROLL, int(rng.choice([0, 1, 2, 4, 8]))), (rb.RB_OPT_NONTEMPORAL, int(rng.integers(0, 2))),
-                   (rb.RB_OPT_WINDOW, int(rng.choice([16, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
+                   (rb.RB_OPT_WINDOW, int(rng.choice([32, 32, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
         print(f"  {w.name} {style} per_call={per_call} options={[v for _, v in options]}", flush=True)
         policy = POLICIES[str(rng.choice(sorted(POLICIES)))] if rng.random() < 0.5 else None
         bf16 = bool(rng.random() < 0.4 and w.dtype == "f32" and (w.row_bytes // 2) % 16 == 0)   # binary32 samples stored as bfloat16
