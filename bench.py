@@ -494,6 +494,22 @@ def reduced_precision_leg(torch, rb, wl, steps=1000):
             "one_launch_per_step_ms": round(ms_ahead, 5), "not_announced_ms_per_step": round(ms_plain, 5)}
 
 
+def eight_bit_leg(torch, rb, wl, steps=1000):
+    """Workload C3 (float32 images with values in [0, 1)) with rows stored in 8 bits per element (Sec. VII): a quarter
+    of the buffer, 5/8 of the bytes per step.  Served by the general kernels: two launches per step in every call form."""
+    w = wl.C3
+    rig = Rig(w, torch, rb, wl, store_dtype=torch.uint8)
+    rig.enqueue(100, single_call=True)
+    torch.cuda.synchronize()
+    ms = rig.timed(steps, single_call=True)
+    moved = (w.c + w.r) * (w.row_bytes + w.row_bytes // 4)
+    rig.close()
+    return {"workload": w.name + " stored as u8", "ms_per_step": round(ms, 5), "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1),
+            "bytes_per_step": moved, "gb_per_s": round(moved / (ms * 1e-3) / 1e9, 1),
+            "hbm_frac": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "buffer_gb": round(w.buffer_bytes / 4 / 1e9, 1),
+            "launches_per_step": 2}
+
+
 def variants_leg(w, torch, rb, wl, steps):
     """The policy variants of Algorithm 1 on the same workload, all through the same announced multi-step calls as
     the headline: the other replacement strategies in the same several-steps launch, the Bernoulli selection (whose
@@ -533,7 +549,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=100)
     ap.add_argument("--workload", default="C4")
     ap.add_argument("--prefill", action="store_true", help="fill every slot before timing (all inserts replace)")
-    ap.add_argument("--others", default="C3,C5,C2,C1", help="comma list of further workloads reported inside the line ('' = none)")
+    ap.add_argument("--others", default="C3,C5,C5F,C2,C1", help="comma list of further workloads reported inside the line ('' = none)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-overlap", action="store_true")
     ap.add_argument("--no-variants", action="store_true")
@@ -624,6 +640,9 @@ def main():
     reduced = None if a.no_variants else reduced_precision_leg(torch, rb, wl)
     if reduced:
         log(f"[bench] reduced-precision {json.dumps(reduced)}")
+    eight = None if a.no_variants else eight_bit_leg(torch, rb, wl)
+    if eight:
+        log(f"[bench] 8-bit storage {json.dumps(eight)}")
 
     # Roofline of the dominant kernel over the timed regions of the headline.  With one or several whole steps per
     # launch that kernel is the step (rb_window_kernel / rb_step_big_kernel: every inserted row and every
@@ -677,6 +696,7 @@ def main():
         "policy_variants": variants,
         "host_pinned_rows": pinned,
         "bf16_stored_rows": reduced,
+        "u8_stored_rows": eight,
     }
     if not a.no_cpu_baseline:
         pool = cpu_pool(w, wl)

@@ -101,8 +101,16 @@ int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *h
  * must be a multiple of 32.  Served by the general kernels (two launches per
  * step), by the plan-ahead forms of the single launch (rb_announce_next) and
  * by the several-steps launch (rb_update_sample_many).
+ * RB_STORE_U8: samples are binary32 with values meant to lie in [0, 1] (image
+ * tensors); an element x is stored as the byte nearest to 255 * x - product
+ * and rounding in binary32, ties to even; x <= 0 and NaN give 0, 255 * x >= 255
+ * gives 255 - and handed out as byte / 255 (binary32 division, correctly
+ * rounded): a quarter of the memory, an absolute error of at most 1/510 for
+ * values in [0, 1].  The sample's byte size must be a multiple of 64.  Served
+ * by the general kernels only: every call form works and gives the same bytes,
+ * each step as two launches.
  */
-enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1 };
+enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1, RB_STORE_U8 = 2 };
 int rb_set_storage(rb_buffer *rb, int32_t storage);
 
 /*

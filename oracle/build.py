@@ -10,7 +10,7 @@ LIB = os.path.join(HERE, "librbo.so")
 def build(force: bool = True) -> str:
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
-    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC", "-pthread", SRC, "-o", LIB]
+    cmd = ["gcc", "-std=c11", "-O2", "-Wall", "-Wextra", "-shared", "-fPIC", "-pthread", SRC, "-o", LIB, "-lm"]
     subprocess.run(cmd, check=True)
     return LIB
 

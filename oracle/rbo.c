@@ -32,6 +32,7 @@
  */
 #define _POSIX_C_SOURCE 200809L   /* pthread barriers (timing variant at the end of the file) */
 #include <limits.h>
+#include <math.h>
 #include <pthread.h>
 #include <stdint.h>
 #include <stdlib.h>
@@ -61,8 +62,13 @@ enum { RBO_EVICT_UNIFORM = 0, RBO_EVICT_FIFO = 1, RBO_EVICT_RESERVOIR = 2 };
  * samples: keep every IEEE binary32 element as a bfloat16.
  *   SAME - a stored row is the sample's bytes;
  *   BF16 - the sample is an array of binary32 values; each is stored as the bfloat16 nearest to it (ties
- *          to the one whose last bit is 0), and handed out widened back to binary32, which is exact. */
-enum { RBO_STORE_SAME = 0, RBO_STORE_BF16 = 1 };
+ *          to the one whose last bit is 0), and handed out widened back to binary32, which is exact.
+ *   U8   - the sample is an array of binary32 values meant to lie in [0, 1] (an image tensor); each value x is
+ *          stored as one byte, the integer nearest to 255 * x, and handed out as that integer divided by 255.
+ *          So that two implementations agree on every bit, the arithmetic is fixed: the product 255 * x is the
+ *          binary32 product, it is rounded to an integer in the nearest-even sense, values not above 0 (and
+ *          NaN) give 0 and products of 255 or more give 255; the quotient is the binary32 quotient. */
+enum { RBO_STORE_SAME = 0, RBO_STORE_BF16 = 1, RBO_STORE_U8 = 2 };
 
 /* ------------------------------------------------------------------------ */
 /* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as  */
@@ -142,6 +148,27 @@ uint16_t rbo_f32_to_bf16(uint32_t bits)
 }
 
 uint32_t rbo_bf16_to_f32(uint16_t h) { return (uint32_t)h << 16; }
+
+/* binary32 (given by its bit pattern) -> byte, and back; see RBO_STORE_U8. */
+uint8_t rbo_f32_to_u8(uint32_t bits)
+{
+    float x;
+    memcpy(&x, &bits, 4);
+    volatile float product = x * 255.0f;     /* (volatile: rounded to binary32 here, whatever the compiler keeps in registers) */
+    float t = product;
+    if (!(t > 0.0f)) return 0;               /* not above zero, or NaN */
+    if (t >= 255.0f) return 255;
+    return (uint8_t)lrintf(t);               /* nearest integer, ties to even (the default rounding mode) */
+}
+
+uint32_t rbo_u8_to_f32(uint8_t q)
+{
+    volatile float quotient = (float)q / 255.0f;
+    float y = quotient;
+    uint32_t bits;
+    memcpy(&bits, &y, 4);
+    return bits;
+}
 
 /* ------------------------------------------------------------------------ */
 /* The buffer                                                                */
@@ -234,12 +261,12 @@ int rbo_set_policy(rbo_buffer *rb, int selection, int eviction)
  * binary32 elements.  Returns 0, or -1. */
 int rbo_set_storage(rbo_buffer *rb, int storage)
 {
-    if (!rb || (storage != RBO_STORE_SAME && storage != RBO_STORE_BF16)) return -1;
-    if (storage == RBO_STORE_BF16 && rb->row_bytes % 4 != 0) return -1;
+    if (!rb || (storage != RBO_STORE_SAME && storage != RBO_STORE_BF16 && storage != RBO_STORE_U8)) return -1;
+    if (storage != RBO_STORE_SAME && rb->row_bytes % 4 != 0) return -1;
     for (int64_t k = 0; k < rb->K; ++k)
         if (rb->fill[k] != 0 || rb->seen[k] != 0) return -1;
     rb->storage = storage;
-    rb->stored_bytes = storage == RBO_STORE_BF16 ? rb->row_bytes / 2 : rb->row_bytes;
+    rb->stored_bytes = storage == RBO_STORE_BF16 ? rb->row_bytes / 2 : storage == RBO_STORE_U8 ? rb->row_bytes / 4 : rb->row_bytes;
     return 0;
 }
 
@@ -252,6 +279,7 @@ static void store_row(rbo_buffer *rb, unsigned char *stored, const unsigned char
     for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
         uint32_t bits;
         memcpy(&bits, sample + 4 * e, 4);
+        if (rb->storage == RBO_STORE_U8) { stored[e] = rbo_f32_to_u8(bits); continue; }
         uint16_t h = rbo_f32_to_bf16(bits);
         memcpy(stored + 2 * e, &h, 2);
     }
@@ -262,9 +290,14 @@ static void load_row(rbo_buffer *rb, unsigned char *sample, const unsigned char 
     if (rb->defer && defer_copy(rb, sample, stored) == 0) return;
     if (rb->storage == RBO_STORE_SAME) { memcpy(sample, stored, (size_t)rb->row_bytes); return; }
     for (int64_t e = 0; e < rb->row_bytes / 4; ++e) {
-        uint16_t h;
-        memcpy(&h, stored + 2 * e, 2);
-        uint32_t bits = rbo_bf16_to_f32(h);
+        uint32_t bits;
+        if (rb->storage == RBO_STORE_U8) {
+            bits = rbo_u8_to_f32(stored[e]);
+        } else {
+            uint16_t h;
+            memcpy(&h, stored + 2 * e, 2);
+            bits = rbo_bf16_to_f32(h);
+        }
         memcpy(sample + 4 * e, &bits, 4);
     }
 }

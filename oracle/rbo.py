@@ -14,7 +14,7 @@ from . import build as _build
 SELECT, EVICT, SAMPLE, COIN = 1, 2, 3, 4
 SELECT_EXACT, SELECT_BERNOULLI = 0, 1
 EVICT_UNIFORM, EVICT_FIFO, EVICT_RESERVOIR = 0, 1, 2
-STORE_SAME, STORE_BF16 = 0, 1
+STORE_SAME, STORE_BF16, STORE_U8 = 0, 1, 2
 
 _lib = None
 
@@ -49,6 +49,10 @@ def lib():
         L.rbo_f32_to_bf16.restype = C.c_uint16
         L.rbo_bf16_to_f32.argtypes = [C.c_uint16]
         L.rbo_bf16_to_f32.restype = u32
+        L.rbo_f32_to_u8.argtypes = [u32]
+        L.rbo_f32_to_u8.restype = C.c_uint8
+        L.rbo_u8_to_f32.argtypes = [C.c_uint8]
+        L.rbo_u8_to_f32.restype = u32
         L.rbo_update.argtypes = [vp, vp, vp, i64, i64, u64, u64]
         L.rbo_update.restype = C.c_int
         L.rbo_sample_augment.argtypes = [vp, i64, u64, u64, vp, vp]
@@ -108,6 +112,16 @@ def f32_to_bf16(bits):
 
 def bf16_to_f32(h):
     return int(lib().rbo_bf16_to_f32(int(h)))
+
+
+def f32_to_u8(bits):
+    """Byte that stores the binary32 with bit pattern `bits` (8-bit storage form)."""
+    return int(lib().rbo_f32_to_u8(int(bits)))
+
+
+def u8_to_f32(q):
+    """Bit pattern of the binary32 that byte q is handed out as."""
+    return int(lib().rbo_u8_to_f32(int(q)))
 
 
 def _view(ptr, n, dtype):

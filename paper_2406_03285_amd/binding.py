@@ -20,7 +20,7 @@ RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
 RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE, RB_OPT_WINDOW = 0, 1, 2, 3, 4
 RB_SELECT_EXACT, RB_SELECT_BERNOULLI = 0, 1
-RB_STORE_SAME, RB_STORE_BF16 = 0, 1
+RB_STORE_SAME, RB_STORE_BF16, RB_STORE_U8 = 0, 1, 2
 RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2
 
 EXPORTS = (
@@ -259,7 +259,8 @@ class RehearsalBuffer:
         """storage: "hbm" keeps the sample rows in device memory; "host_pinned" keeps them in pinned host
         memory that the kernels read and write directly over the host link (where the paper keeps its
         buffers, Sec. IV-C); labels and workspace stay on the device either way.
-        store_dtype: None keeps rows as they come; torch.bfloat16 with dtype float32 stores them at half size.
+        store_dtype: None keeps rows as they come; with dtype float32, torch.bfloat16 stores them at half size and
+        torch.uint8 (values in [0, 1] as bytes) at a quarter.
         static_workspace: bind with rb_bind_static (the library's own scratch array instead of a workspace tensor)."""
         code = {torch.float32: RB_F32, torch.bfloat16: RB_BF16}[dtype]
         rc, self.handle = rb_create(classes, slots_per_class, tuple(sample_shape), code)
@@ -267,9 +268,9 @@ class RehearsalBuffer:
         self.K, self.S, self.sample_shape, self.dtype = int(classes), int(slots_per_class), tuple(sample_shape), dtype
         self.store_dtype = dtype if store_dtype is None else store_dtype
         if self.store_dtype != dtype:
-            if (dtype, self.store_dtype) != (torch.float32, torch.bfloat16):
-                raise ValueError("only float32 samples stored as bfloat16")
-            _check(rb_set_storage(self.handle, RB_STORE_BF16), "rb_set_storage")
+            if dtype != torch.float32 or self.store_dtype not in (torch.bfloat16, torch.uint8):
+                raise ValueError("only float32 samples stored as bfloat16 or uint8")
+            _check(rb_set_storage(self.handle, RB_STORE_BF16 if self.store_dtype == torch.bfloat16 else RB_STORE_U8), "rb_set_storage")
         rc, xb, yb, wb = rb_query_sizes(self.handle)
         _check(rc, "rb_query_sizes")
         self.row_bytes = xb // (self.K * self.S)          # of a stored row

@@ -147,7 +147,7 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
 }
 
 template <bool NT>
-hipError_t launch_update(const UpdateArgs& a, bool small, bool narrow, int unroll, dim3 grid, size_t lds, hipStream_t st)
+hipError_t launch_update(const UpdateArgs& a, bool small, int narrow, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     if (small) {
         switch (unroll) {
@@ -158,26 +158,31 @@ hipError_t launch_update(const UpdateArgs& a, bool small, bool narrow, int unrol
         }
         return hipGetLastError();
     }
-    if (narrow) {
+    if (narrow == 2) {                  // 8 bits per element: a lane holds four accesses per vector of the tile (at most two vectors)
+        if (unroll == 1) rb_update_kernel<1, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else rb_update_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        return hipGetLastError();
+    }
+    if (narrow == 1) {
         switch (unroll) {
-        case 1: rb_update_kernel<1, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        case 2: rb_update_kernel<2, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        case 4: rb_update_kernel<4, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        default: rb_update_kernel<8, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 1: rb_update_kernel<1, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_update_kernel<2, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_update_kernel<4, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_update_kernel<8, NT, 1><<<grid, TPB, lds, st>>>(a); break;
         }
         return hipGetLastError();
     }
     switch (unroll) {
-    case 1: rb_update_kernel<1, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    case 2: rb_update_kernel<2, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    case 4: rb_update_kernel<4, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    default: rb_update_kernel<8, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 1: rb_update_kernel<1, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_update_kernel<2, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_update_kernel<4, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_update_kernel<8, NT, 0><<<grid, TPB, lds, st>>>(a); break;
     }
     return hipGetLastError();
 }
 
 template <bool NT>
-hipError_t launch_sample(const SampleArgs& a, bool small, bool widen, int unroll, dim3 grid, size_t lds, hipStream_t st)
+hipError_t launch_sample(const SampleArgs& a, bool small, int widen, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     if (small) {
         switch (unroll) {
@@ -188,20 +193,25 @@ hipError_t launch_sample(const SampleArgs& a, bool small, bool widen, int unroll
         }
         return hipGetLastError();
     }
-    if (widen) {
+    if (widen == 2) {
+        if (unroll == 1) rb_sample_kernel<1, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else rb_sample_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        return hipGetLastError();
+    }
+    if (widen == 1) {
         switch (unroll) {
-        case 1: rb_sample_kernel<1, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        case 2: rb_sample_kernel<2, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        case 4: rb_sample_kernel<4, NT, true><<<grid, TPB, lds, st>>>(a); break;
-        default: rb_sample_kernel<8, NT, true><<<grid, TPB, lds, st>>>(a); break;
+        case 1: rb_sample_kernel<1, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        case 2: rb_sample_kernel<2, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        case 4: rb_sample_kernel<4, NT, 1><<<grid, TPB, lds, st>>>(a); break;
+        default: rb_sample_kernel<8, NT, 1><<<grid, TPB, lds, st>>>(a); break;
         }
         return hipGetLastError();
     }
     switch (unroll) {
-    case 1: rb_sample_kernel<1, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    case 2: rb_sample_kernel<2, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    case 4: rb_sample_kernel<4, NT, false><<<grid, TPB, lds, st>>>(a); break;
-    default: rb_sample_kernel<8, NT, false><<<grid, TPB, lds, st>>>(a); break;
+    case 1: rb_sample_kernel<1, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    case 2: rb_sample_kernel<2, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    case 4: rb_sample_kernel<4, NT, 0><<<grid, TPB, lds, st>>>(a); break;
+    default: rb_sample_kernel<8, NT, 0><<<grid, TPB, lds, st>>>(a); break;
     }
     return hipGetLastError();
 }
@@ -539,7 +549,7 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
 int64_t window_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
     const bool windowed = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 && rb->opt_fuse &&
-                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT;
+                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->storage != RB_STORE_U8;
     if (!windowed) return 1;
     return std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
                                                   std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
@@ -693,7 +703,8 @@ Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
 // many at most (1: it does not).  Shapes that the small form takes (window_limit) are not meant.
 int64_t bigwin_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
-    const bool eligible = c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES && rb->opt_fuse &&
+    const bool eligible = rb->storage != RB_STORE_U8 && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
+                          rb->K <= BIG_CLASSES && rb->opt_fuse &&
                           rb->opt_window >= 2 && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) && rb->K * rb->S <= INT64_C(0x7FFFFFFF) &&
                           rb->S <= INT32_MAX - (int64_t)BW_MAX * RB_MAX_BATCH;
     if (!eligible) return 1;
@@ -919,11 +930,12 @@ int rb_query_sizes(const rb_buffer* rb, size_t* x_bytes, size_t* y_bytes, size_t
 int rb_set_storage(rb_buffer* rb, int32_t storage)
 {
     if (!rb) return RB_EINVAL;
-    if (storage != RB_STORE_SAME && storage != RB_STORE_BF16) return RB_EINVAL;
+    if (storage != RB_STORE_SAME && storage != RB_STORE_BF16 && storage != RB_STORE_U8) return RB_EINVAL;
     if (rb->bound) return RB_ESTATE;                 // the storage the caller bound was sized for the other form
     if (storage == RB_STORE_BF16 && (rb->dtype != RB_F32 || rb->sample_bytes % 32 != 0)) return RB_EINVAL;
+    if (storage == RB_STORE_U8 && (rb->dtype != RB_F32 || rb->sample_bytes % 64 != 0)) return RB_EINVAL;
     rb->storage = storage;
-    rb->row_bytes = storage == RB_STORE_BF16 ? rb->sample_bytes / 2 : rb->sample_bytes;
+    rb->row_bytes = storage == RB_STORE_BF16 ? rb->sample_bytes / 2 : storage == RB_STORE_U8 ? rb->sample_bytes / 4 : rb->sample_bytes;
     rb->row_vec = rb->row_bytes / 16;
     return RB_OK;
 }
@@ -1021,7 +1033,7 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     if (c == 0) return RB_OK;
 
     const bool variant = rb->selection != RB_SELECT_EXACT || rb->eviction != RB_EVICT_UNIFORM;
-    const bool narrow = rb->storage == RB_STORE_BF16;
+    const int narrow = rb->storage == RB_STORE_BF16 ? 1 : rb->storage == RB_STORE_U8 ? 2 : 0;
     const bool small = c <= WAVE && !variant && !narrow;
     // Rows the grid is sized for.  The Bernoulli selection yields a random number of candidates
     // (mean c, at most b); the movers loop over the work items, so any number is handled, and
@@ -1032,7 +1044,13 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
         while (slack * slack < 36 * c) ++slack;          // about six standard deviations
         rows = c + slack < b ? c + slack : b;
     }
-    const Shape sh = plan_shape(rb, rows, small ? TPB : WAVE);
+    Shape sh = plan_shape(rb, rows, small ? TPB : WAVE);
+    if (narrow == 2 && sh.unroll > 2) {              // the 8-bit mover holds at most two vectors per lane
+        const int keep = rb->opt_unroll;
+        rb->opt_unroll = 2;
+        sh = plan_shape(rb, rows, WAVE);
+        rb->opt_unroll = keep;
+    }
     UpdateArgs a;
     a.batch_x = static_cast<const vec16*>(batch_x);
     a.batch_y = batch_y;
@@ -1070,9 +1088,15 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     discard_plan(rb);
     if (r == 0) return RB_OK;
 
-    const bool widen = rb->storage == RB_STORE_BF16;
+    const int widen = rb->storage == RB_STORE_BF16 ? 1 : rb->storage == RB_STORE_U8 ? 2 : 0;
     const bool small = r <= WAVE && rb->nchunks <= WAVE && !widen;
-    const Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
+    Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
+    if (widen == 2 && sh.unroll > 2) {
+        const int keep = rb->opt_unroll;
+        rb->opt_unroll = 2;
+        sh = plan_shape(rb, r, WAVE);
+        rb->opt_unroll = keep;
+    }
     SampleArgs a;
     a.buf_x = static_cast<const vec16*>(rb->buf_x);
     a.out_x = static_cast<vec16*>(out_x);
@@ -1103,12 +1127,12 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
 
     // the plan-ahead form covers both storage forms; the kernel that plans and moves in one launch only the plain one
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
-                           rb->selection == RB_SELECT_EXACT;
+                           rb->selection == RB_SELECT_EXACT && rb->storage != RB_STORE_U8;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
     // larger counts have a plan-ahead form of their own
     // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)
-    const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH && rb->K <= BIG_CLASSES &&
-                     rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) &&
+    const bool big = !plannable && rb->storage != RB_STORE_U8 && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
+                     rb->K <= BIG_CLASSES && rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) &&
                      rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;
     rb->next_y = nullptr;                        // an announcement serves one call

@@ -162,7 +162,32 @@ __device__ __forceinline__ vec16 widen4(const vec8 s)
     return a;
 }
 
-enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3 };   // bit 0: convert while loading, bit 1: while storing
+// Reduced-precision storage in 8 bits (Sec. VII: data reduction of the stored samples): a binary32 element x is kept as the
+// byte nearest to 255 x (product and rounding in binary32, ties to even; below 0 and NaN give 0, above 255 gives 255)
+// and handed out as byte / 255 (binary32 division, correctly rounded).  Meant for samples in [0, 1], like image tensors.
+__device__ __forceinline__ uint32_t u8_of(uint32_t bits)
+{
+    const float t = __uint_as_float(bits) * 255.0f;
+    if (!(t > 0.0f)) return 0u;                 // not above zero, or NaN
+    if (t >= 255.0f) return 255u;
+    return (uint32_t)(int)rintf(t);             // nearest, ties to even
+}
+__device__ __forceinline__ uint32_t pack4_u8(const vec16 a)      // four consecutive elements -> four bytes, element order kept
+{
+    return u8_of(a.x) | (u8_of(a.y) << 8) | (u8_of(a.z) << 16) | (u8_of(a.w) << 24);
+}
+__device__ __forceinline__ vec16 unpack4_u8(const uint32_t s)
+{
+    vec16 a;
+    a.x = __float_as_uint((float)(s & 0xFFu) / 255.0f);
+    a.y = __float_as_uint((float)((s >> 8) & 0xFFu) / 255.0f);
+    a.z = __float_as_uint((float)((s >> 16) & 0xFFu) / 255.0f);
+    a.w = __float_as_uint((float)(s >> 24) / 255.0f);
+    return a;
+}
+
+// bit 0: convert while loading, bit 1: while storing; bit 2: the narrow form is 8 bits per element instead of bfloat16
+enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3, CV_Q8 = 4, CV_NARROW8 = CV_Q8 | CV_NARROW, CV_WIDEN8 = CV_Q8 | CV_WIDEN };
 
 // ---------------------------------------------------------------------------
 // Row mover: one tile of one row, U vectors per thread in flight.
@@ -178,7 +203,9 @@ struct Tile {
     // a lane then touches 8 bytes of the narrow row and 16 bytes of the binary32 row per access, so every
     // instruction of a wavefront covers one contiguous run of bytes on either side.
     vec16 v[CV ? 1 : U];
-    vec8 h[CV ? 2 * U : 1];
+    vec8 h[CV && !(CV & CV_Q8) ? 2 * U : 1];
+    // 8-bit storage: 4 U quarter vectors (four bytes of the stored row against 16 bytes of the binary32 row per access)
+    uint32_t q[CV & CV_Q8 ? 4 * U : 1];
 
     // Requires lo < hi.  No lane is ever masked off: a lane whose index falls past the end of
     // the tile moves the tile's last vector again (same source, same destination, same bytes as
@@ -187,6 +214,20 @@ struct Tile {
     // to drain these - and keeps the compiler from moving loads down into a guarded store.
     __device__ __forceinline__ void load(const vec16* __restrict__ src, int64_t lo, int64_t hi)
     {
+        if (CV & CV_Q8) {
+#pragma unroll
+            for (int u = 0; u < 4 * U; ++u) {
+                int64_t j = 4 * lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+                j = j < 4 * hi ? j : 4 * hi - 1;
+                if (CV & CV_NARROW) {
+                    q[u] = pack4_u8(NT ? __builtin_nontemporal_load(src + j) : src[j]);
+                } else {
+                    const uint32_t* quarter = reinterpret_cast<const uint32_t*>(src);
+                    q[u] = NT ? __builtin_nontemporal_load(quarter + j) : quarter[j];
+                }
+            }
+            return;
+        }
         if (CV) {
 #pragma unroll
             for (int u = 0; u < 2 * U; ++u) {
@@ -219,6 +260,24 @@ struct Tile {
     __device__ __forceinline__ void store(vec16* __restrict__ dst, int64_t lo, int64_t hi) const
     {
         if (PACED) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        if (CV & CV_Q8) {
+#pragma unroll
+            for (int u = 0; u < 4 * U; ++u) {
+                int64_t j = 4 * lo + (int64_t)u * W + (threadIdx.x & (W - 1));
+                j = j < 4 * hi ? j : 4 * hi - 1;
+                if (CV & CV_WIDEN) {
+                    const vec16 a = unpack4_u8(q[u]);
+                    if (NT) __builtin_nontemporal_store(a, dst + j);
+                    else dst[j] = a;
+                } else {
+                    uint32_t* quarter = reinterpret_cast<uint32_t*>(dst);
+                    if (NT) __builtin_nontemporal_store(q[u], quarter + j);
+                    else quarter[j] = q[u];
+                }
+                if (PACED && (u + 1) % PACED == 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            }
+            return;
+        }
         if (CV) {
 #pragma unroll
             for (int u = 0; u < 2 * U; ++u) {

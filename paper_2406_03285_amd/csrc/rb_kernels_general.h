@@ -36,7 +36,7 @@ __global__ void __launch_bounds__(TPB) rb_reset_kernel(uint32_t* __restrict__ ws
 // classes each), then ceil(c * tpr / NWAVE) mover workgroups.
 // ---------------------------------------------------------------------------
 
-template <int U, bool NT, bool NARROW>      // NARROW: binary32 mini-batch rows are stored as bfloat16
+template <int U, bool NT, int NARROW>       // NARROW: binary32 mini-batch rows are stored 0 - as they come, 1 - as bfloat16, 2 - in 8 bits per element
 __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -185,8 +185,8 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
         const int64_t fill0 = a.fill_old[ki];
         const int64_t aux0 = a.eviction != RB_EVICT_UNIFORM ? a.aux_old[ki] : 0;
         // the row is read while the wavefront works out where it goes
-        Tile<U, NT, WAVE, false, NARROW ? CV_NARROW : CV_NONE> t;
-        t.load(a.batch_x + (int64_t)p * a.row_vec * (NARROW ? 2 : 1), v_lo, v_hi);
+        Tile<U, NT, WAVE, false, NARROW == 2 ? CV_NARROW8 : NARROW ? CV_NARROW : CV_NONE> t;
+        t.load(a.batch_x + (int64_t)p * a.row_vec * (NARROW == 2 ? 4 : NARROW ? 2 : 1), v_lo, v_hi);
 
         // Candidates of class ki, in mini-batch order: the one with `rank` class-mates before it is
         // insertion number fill0 + rank of the class.  Each lane looks at every WAVE-th candidate,
@@ -318,7 +318,7 @@ __global__ void __launch_bounds__(TPB) rb_update_kernel(const UpdateArgs a)
 // Grid: ceil(r * tpr / NWAVE) workgroups.
 // ---------------------------------------------------------------------------
 
-template <int U, bool NT, bool WIDEN>       // WIDEN: rows stored as bfloat16 are handed out as binary32
+template <int U, bool NT, int WIDEN>        // WIDEN: rows are handed out 0 - as stored, 1 - widened from bfloat16, 2 - from 8 bits per element to binary32
 __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
 {
     extern __shared__ uint32_t lds[];
@@ -402,9 +402,9 @@ __global__ void __launch_bounds__(TPB) rb_sample_kernel(const SampleArgs a)
     const int pk = lane_read(lo * CH + 4 * lane + u, owner);
     const int ps = lane_read(gl - acc, owner);
 
-    Tile<U, NT, WAVE, false, WIDEN ? CV_WIDEN : CV_NONE> t;
+    Tile<U, NT, WAVE, false, WIDEN == 2 ? CV_WIDEN8 : WIDEN ? CV_WIDEN : CV_NONE> t;
     t.load(a.buf_x + ((int64_t)pk * a.S + ps) * a.row_vec, v_lo, v_hi);
-    t.store(a.out_x + (int64_t)j * a.row_vec * (WIDEN ? 2 : 1), v_lo, v_hi);
+    t.store(a.out_x + (int64_t)j * a.row_vec * (WIDEN == 2 ? 4 : WIDEN ? 2 : 1), v_lo, v_hi);
     if (tile == 0 && lane == 0) { a.out_y[j] = pk; count_moved(a.state); }
 }
 

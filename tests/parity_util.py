@@ -61,12 +61,12 @@ def compare_buffers(buf, orc, tag, chunk_bytes=256 << 20):
 
 def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_state_every=0,
                first_step=0, progress=None, buf=None, orc=None, final_check=True, single_call=False,
-               policy=None, storage="hbm", store_bf16=False):
+               policy=None, storage="hbm", store_bf16=False, store_u8=False):
     """Runs `steps` update+sample steps of workload `w` on both sides.
 
     single_call: drive the HIP side through rb_update_sample instead of the two calls.
     policy: (selection, eviction) variant codes, set on both sides (the codes are the same numbers).
-    store_bf16: float32 samples stored as bfloat16 on both sides.
+    store_bf16 / store_u8: float32 samples stored as bfloat16 / in 8 bits per element on both sides.
     Every step: out_y equal, the n sampled rows byte-equal, rows >= n untouched.
     At the end (and every `check_state_every` steps): fill, flags, buf_y and all
     filled buf_x rows.  Returns (buf, orc) for further checks.
@@ -78,10 +78,9 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     own = buf is None
     if own:
         buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, stream=stream, storage=storage,
-                                 store_dtype=torch.bfloat16 if store_bf16 else None)
+                                 store_dtype=_store_dtype(store_bf16, store_u8))
         orc = rbo.Buffer(w.K, w.S, w.row_bytes)
-        if store_bf16:
-            orc.set_storage(rbo.STORE_BF16)
+        _set_oracle_storage(orc, store_bf16, store_u8)
         for opt, val in options:
             buf.set_option(opt, val)
         if policy is not None:
@@ -128,17 +127,27 @@ def run_parity(w, steps=None, device="cuda:0", stream=None, options=(), check_st
     return buf, orc
 
 
-def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None, options=()):
+def _store_dtype(store_bf16, store_u8):
+    return torch.bfloat16 if store_bf16 else torch.uint8 if store_u8 else None
+
+
+def _set_oracle_storage(orc, store_bf16, store_u8):
+    if store_bf16:
+        orc.set_storage(rbo.STORE_BF16)
+    elif store_u8:
+        orc.set_storage(rbo.STORE_U8)
+
+
+def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None, options=(), store_u8=False):
     """update_sample with the next mini-batch's labels announced; with a schedule seed, promises are
     broken at random (other labels, other arguments, other calls in between) and the plan must be
     dropped without a trace."""
     import paper_2406_03285_amd as rb
 
     dev = torch.device("cuda:0")
-    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=torch.bfloat16 if store_bf16 else None)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=_store_dtype(store_bf16, store_u8))
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
-    if store_bf16:
-        orc.set_storage(rbo.STORE_BF16)
+    _set_oracle_storage(orc, store_bf16, store_u8)
     if policy is not None:
         buf.set_policy(*policy)
         orc.set_policy(*policy)
@@ -187,7 +196,7 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
 
 
 def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None,
-                    options=()):
+                    options=(), store_u8=False):
     """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
     against the oracle step by step.  announce: the labels of the next call's first steps are announced
     before every call (the last launch of a call then plans them); with a schedule seed some of those
@@ -195,12 +204,11 @@ def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule
     import paper_2406_03285_amd as rb
 
     dev = torch.device("cuda:0")
-    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=torch.bfloat16 if store_bf16 else None)
+    buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=_store_dtype(store_bf16, store_u8))
     if window is not None:
         buf.set_option(rb.RB_OPT_WINDOW, window)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
-    if store_bf16:
-        orc.set_storage(rbo.STORE_BF16)
+    _set_oracle_storage(orc, store_bf16, store_u8)
     if policy is not None:
         buf.set_policy(*policy)
         orc.set_policy(*policy)

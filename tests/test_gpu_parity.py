@@ -206,6 +206,74 @@ def test_storage_variant_argument_checks():
     assert rb.rb_set_storage(buf.handle, rb.RB_STORE_BF16) == rb.RB_ESTATE   # already bound
 
 
+# ------------------------------------------------- 8-bit storage (Sec. VII) ---
+
+def _image_like_batch(w, step, dev):
+    """Values as an image pipeline gives them, plus everything the conversion has to decide: every k/255, the values
+    around every tie (k + 1/2)/255, values outside [0, 1], zeros of both signs, subnormals, infinities and NaNs."""
+    x, y = _plain_make_batch(w, step, dev)
+    x = x.abs().fmod(1.0) if w.values == "normal" else x
+    flat = x.reshape(-1)
+    k = torch.arange(256, dtype=torch.float32)
+    ties = ((torch.arange(255, dtype=torch.float32) + 0.5) / 255.0)
+    special = torch.cat([k / 255.0, ties, torch.nextafter(ties, torch.zeros(())), torch.nextafter(ties, torch.ones(())),
+                         torch.tensor([-0.0, -0.25, 1.0000001, 7.5, float("inf"), -float("inf"), float("nan"), 1e-45, -1e-45])])
+    g = torch.Generator(device="cpu")
+    g.manual_seed(step)
+    where = torch.randint(0, flat.numel(), (special.numel() * 3,), generator=g).to(dev)
+    flat[where] = special.repeat(3).to(dev)
+    return x, y
+
+
+@pytest.mark.parametrize("w,steps", [
+    (wl.variant(wl.C2, name="C2-u8-store", S=4), 60),                                                 # N(0,1) values: half of them saturate
+    (wl.variant(wl.C5, name="C5-u8-store", K=300, S=12, shape=(272,), b=512, c=200, r=150), 25),     # 17 stored vectors per row: ragged tiles
+    (wl.variant(wl.C3, name="C3-u8-store", K=50, S=6), 20),                                          # U(0,1) images, 150 528-byte stored rows
+], ids=["C2", "C5", "C3"])
+def test_float32_samples_stored_in_8_bits(w, steps):
+    buf, orc = run_parity(w, steps=steps, check_state_every=max(1, steps // 2), store_u8=True)
+    assert buf.buf_x.dtype == torch.uint8 and buf.row_bytes == w.row_bytes // 4
+
+
+def test_8_bit_storage_decides_every_value_like_the_oracle(monkeypatch):
+    w = wl.variant(wl.C2, name="C2-u8-special", S=3, c=64, r=64, values="uniform")
+    monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _image_like_batch(ww, step, dev))
+    buf, orc = run_parity(w, steps=12, check_state_every=4, store_u8=True)
+    assert len(torch.unique(buf.buf_x)) == 256                       # every byte value is in use
+
+
+@pytest.mark.parametrize("style", ["single", "ahead", "many", "many-announced", "fifo-bernoulli"])
+def test_8_bit_storage_through_every_call_form(style):
+    """The 8-bit form is served by the general kernels only: announcements and multi-step calls fall back to them, the
+    bytes are the oracle's in every call form."""
+    w = wl.variant(wl.C4, name=f"C4-u8-{style}", S=8, shape=(3, 32, 32), dtype="f32", b=128, c=40, r=40)
+    if style == "single":
+        run_parity(w, steps=40, store_u8=True, single_call=True)
+    elif style == "ahead":
+        run_ahead_parity(w, 40, schedule_seed=4, store_u8=True)
+    elif style == "many":
+        run_many_parity(w, 48, per_call=16, store_u8=True)
+    elif style == "many-announced":
+        run_many_parity(w, 48, per_call=16, announce=True, schedule_seed=6, store_u8=True)
+    else:
+        run_many_parity(w, 48, per_call=16, announce=True, store_u8=True, policy=POLICIES["bernoulli-fifo"])
+
+
+def test_8_bit_storage_argument_checks():
+    rb = _rb()
+    rc, h = rb.rb_create(4, 2, (16,), rb.RB_BF16)
+    assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_EINVAL       # samples are not binary32
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (8,), rb.RB_F32)
+    assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_EINVAL       # 32-byte samples: a stored row would be 8 bytes
+    rb.rb_destroy(h)
+    rc, h = rb.rb_create(4, 2, (16,), rb.RB_F32)
+    assert rb.rb_set_storage(h, 3) == rb.RB_EINVAL
+    assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_OK and rb.rb_query_sizes(h)[1] == 4 * 2 * 16
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 1)    # the several-steps launches do not serve it
+    rb.rb_destroy(h)
+
+
 # ------------------------------------------------------- plan-ahead steps ---
 
 @pytest.mark.parametrize("w,steps", [

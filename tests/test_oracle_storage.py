@@ -128,7 +128,7 @@ def test_buffer_with_bf16_storage_round_trips_through_the_library_routine():
 def test_storage_variant_is_fixed_once_the_buffer_is_in_use():
     buf = rbo.Buffer(3, 2, 16)
     with pytest.raises(ValueError):
-        buf.set_storage(2)
+        buf.set_storage(3)                                        # no such variant
     with pytest.raises(ValueError):
         rbo.Buffer(3, 2, 6).set_storage(rbo.STORE_BF16)           # rows are not made of 4-byte elements
     buf.set_storage(rbo.STORE_BF16)
