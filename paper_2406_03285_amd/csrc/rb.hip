@@ -158,9 +158,10 @@ hipError_t launch_update(const UpdateArgs& a, bool small, int narrow, int unroll
         }
         return hipGetLastError();
     }
-    if (narrow == 2) {                  // 8 bits per element: a lane holds four accesses per vector of the tile (at most two vectors)
+    if (narrow == 2) {                  // 8 bits per element: a lane holds four accesses per vector of the tile (at most four vectors)
         if (unroll == 1) rb_update_kernel<1, NT, 2><<<grid, TPB, lds, st>>>(a);
-        else rb_update_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else if (unroll == 2) rb_update_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else rb_update_kernel<4, NT, 2><<<grid, TPB, lds, st>>>(a);
         return hipGetLastError();
     }
     if (narrow == 1) {
@@ -195,7 +196,8 @@ hipError_t launch_sample(const SampleArgs& a, bool small, int widen, int unroll,
     }
     if (widen == 2) {
         if (unroll == 1) rb_sample_kernel<1, NT, 2><<<grid, TPB, lds, st>>>(a);
-        else rb_sample_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else if (unroll == 2) rb_sample_kernel<2, NT, 2><<<grid, TPB, lds, st>>>(a);
+        else rb_sample_kernel<4, NT, 2><<<grid, TPB, lds, st>>>(a);
         return hipGetLastError();
     }
     if (widen == 1) {
@@ -1045,9 +1047,9 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
         rows = c + slack < b ? c + slack : b;
     }
     Shape sh = plan_shape(rb, rows, small ? TPB : WAVE);
-    if (narrow == 2 && sh.unroll > 2) {              // the 8-bit mover holds at most two vectors per lane
+    if (narrow == 2 && sh.unroll > 4) {              // the 8-bit mover holds at most four vectors per lane
         const int keep = rb->opt_unroll;
-        rb->opt_unroll = 2;
+        rb->opt_unroll = 4;
         sh = plan_shape(rb, rows, WAVE);
         rb->opt_unroll = keep;
     }
@@ -1091,9 +1093,9 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
     const int widen = rb->storage == RB_STORE_BF16 ? 1 : rb->storage == RB_STORE_U8 ? 2 : 0;
     const bool small = r <= WAVE && rb->nchunks <= WAVE && !widen;
     Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
-    if (widen == 2 && sh.unroll > 2) {
+    if (widen == 2 && sh.unroll > 4) {
         const int keep = rb->opt_unroll;
-        rb->opt_unroll = 2;
+        rb->opt_unroll = 4;
         sh = plan_shape(rb, r, WAVE);
         rb->opt_unroll = keep;
     }

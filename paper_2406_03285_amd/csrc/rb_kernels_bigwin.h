@@ -154,44 +154,40 @@ __device__ __forceinline__ uint64_t bw_get64(const uint64_t* p)
 }
 
 // A published table: BIG_HASH words of (value << 32 | row), open addressing as in the planners' LDS tables, free
-// slots hold BIG_EMPTY as row.  Value stored under `row`, BW_MISSING if absent.
-__device__ __forceinline__ uint32_t bw_lookup(const uint64_t* tab, uint32_t row)
-{
-    uint32_t h = big_hash(row);
-    for (int probes = 0; probes < BIG_HASH; ++probes) {     // (a table holds at most BIG_HASH / 2 rows: the walk ends long before)
-        const uint64_t at = bw_get64(tab + h);
-        if ((uint32_t)at == row) return (uint32_t)(at >> 32);
-        if ((uint32_t)at == BIG_EMPTY) break;
-        h = (h + 1) & (BIG_HASH - 1);
-    }
-    return BW_MISSING;
-}
-
+// slots hold BIG_EMPTY as row.
 // `row` looked up in the tables of all steps q with bit q of `steps` set, all at once: a round trip to memory per
 // probe round, not per table (a dependent trip costs 1 to 2 us while the movers are running).  Returns the steps
 // whose table holds the row, their values in val[q].
+// PLAIN: the tables were published by an earlier launch (the movers' case): ordinary, cached loads.
+template <bool PLAIN = false>
 __device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_MAX])
 {
     uint32_t h[BW_MAX];
 #pragma unroll
     for (int q = 0; q < BW_MAX; ++q) h[q] = big_hash(row);
     uint32_t pending = steps, found = 0;
-    for (int probes = 0; pending != 0 && probes < BIG_HASH; ++probes) {
-        uint64_t at[BW_MAX];
+    // two consecutive slots per table and round: the tables are half full, so most walks end in the first round
+    for (int probes = 0; pending != 0 && probes < BIG_HASH; probes += 2) {
+        uint64_t at[BW_MAX], nx[BW_MAX];
 #pragma unroll
         for (int q = 0; q < BW_MAX; ++q)
-            if ((pending >> q) & 1u) at[q] = bw_get64(tabs + (size_t)q * BIG_HASH + h[q]);
+            if ((pending >> q) & 1u) {
+                const uint64_t* tab = tabs + (size_t)q * BIG_HASH;
+                const uint32_t h1 = (h[q] + 1) & (BIG_HASH - 1);
+                at[q] = PLAIN ? tab[h[q]] : bw_get64(tab + h[q]);
+                nx[q] = PLAIN ? tab[h1] : bw_get64(tab + h1);
+            }
 #pragma unroll
         for (int q = 0; q < BW_MAX; ++q) {
             if (!((pending >> q) & 1u)) continue;
-            if ((uint32_t)at[q] == row) {
+            if ((uint32_t)at[q] == row || ((uint32_t)at[q] != BIG_EMPTY && (uint32_t)nx[q] == row)) {
                 found |= 1u << q;
-                val[q] = (uint32_t)(at[q] >> 32);
+                val[q] = (uint32_t)(((uint32_t)at[q] == row ? at[q] : nx[q]) >> 32);
                 pending &= ~(1u << q);
-            } else if ((uint32_t)at[q] == BIG_EMPTY) {
+            } else if ((uint32_t)at[q] == BIG_EMPTY || (uint32_t)nx[q] == BIG_EMPTY) {
                 pending &= ~(1u << q);
             } else {
-                h[q] = (h[q] + 1) & (BIG_HASH - 1);
+                h[q] = (h[q] + 2) & (BIG_HASH - 1);
             }
         }
     }
@@ -663,12 +659,13 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
             // overwrites these same vectors: no lane waits for another.
             const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(m.table + BW_OFF_READ);
             vec16* reader_x[BW_MAX - 1];        // (indexed by compile-time constants only: registers) of step q, null: none
+            uint32_t reader[BW_MAX];
+            const uint32_t reading = bw_lookup_steps<true>(read_tables, (uint32_t)en.row, (1u << s) - 1u, reader);   // all earlier steps at once
 #pragma unroll
             for (int q = 0; q < BW_MAX - 1; ++q) {
                 reader_x[q] = nullptr;
-                if (q >= s) continue;
-                const uint32_t j = bw_lookup(read_tables + (size_t)q * BIG_HASH, (uint32_t)en.row);
-                if (j == BW_MISSING) continue;
+                if (!((reading >> q) & 1u)) continue;
+                const uint32_t j = reader[q];
                 const WinEntry rq = entry[q * rows + m.c + (int)j];
                 if (!rq.handled) continue;
                 reader_x[q] = m.out_x[q] + (int64_t)j * m.row_vec * WIDE;
@@ -677,22 +674,47 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
                     count_moved(m.state);
                 }
             }
+            // (all of a lane's vectors are read before any is written: the reads are in flight together)
             if (BF16) {
                 vec8* half = reinterpret_cast<vec8*>(slot);
-                for (int64_t i = 2 * v_lo + lane; i < 2 * v_hi; i += W) {
-                    const vec16 old = widen4(half[i]);
+                vec8 old[2 * U];
+                vec16 in[2 * U];
+#pragma unroll
+                for (int u = 0; u < 2 * U; ++u) {
+                    const int64_t i = 2 * v_lo + lane + (int64_t)u * W;
+                    if (i < 2 * v_hi) {
+                        old[u] = half[i];
+                        in[u] = fresh[i];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < 2 * U; ++u) {
+                    const int64_t i = 2 * v_lo + lane + (int64_t)u * W;
+                    if (i >= 2 * v_hi) continue;
+                    const vec16 wide = widen4(old[u]);
 #pragma unroll
                     for (int q = 0; q < BW_MAX - 1; ++q)
-                        if (reader_x[q]) reader_x[q][i] = old;
-                    half[i] = narrow4(fresh[i]);
+                        if (reader_x[q]) reader_x[q][i] = wide;
+                    half[i] = narrow4(in[u]);
                 }
             } else {
-                for (int64_t i = v_lo + lane; i < v_hi; i += W) {
-                    const vec16 old = slot[i];
+                vec16 old[U], in[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = v_lo + lane + (int64_t)u * W;
+                    if (i < v_hi) {
+                        old[u] = slot[i];
+                        in[u] = fresh[i];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = v_lo + lane + (int64_t)u * W;
+                    if (i >= v_hi) continue;
 #pragma unroll
                     for (int q = 0; q < BW_MAX - 1; ++q)
-                        if (reader_x[q]) reader_x[q][i] = old;
-                    slot[i] = fresh[i];
+                        if (reader_x[q]) reader_x[q][i] = old[u];
+                    slot[i] = in[u];
                 }
             }
         };
