@@ -270,11 +270,14 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     bw_publish(&t.flags->classes[s], a.number);
     bool ok = bw_await(t.flags->classes, 0, s, a.number, &s_ok);
     // the candidates that the steps before this one bring
-    if (ok && tid < ce)
-        for (int q = 0; q < s; ++q) {
-            const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
-            if (kq >= 0) atomicAdd(&s_fill[kq], 1);
-        }
+    if (ok && tid < ce) {
+        int32_t kq[BW_MAX];                          // (all steps' loads first: one trip to memory, not one per step)
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) kq[q] = q < s ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q)
+            if (kq[q] >= 0) atomicAdd(&s_fill[kq[q]], 1);
+    }
 
     // class table: keys in U[0, BIG_HASH), members per class in U[BIG_HASH, 2 BIG_HASH)
     uint32_t* ckey = s_u;
@@ -449,16 +452,20 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
 
     // ---- the candidates of this step and of the steps before it: how many every class gets; which classes the later steps touch ----
     bool ok = bw_await(t.flags->classes, 0, w, a.number, &s_ok);
-    if (ok && tid < ce)
-        for (int q = 0; q < w; ++q) {
-            const int32_t kq = (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid);
-            if (kq >= 0) {
-                if (q <= s) atomicAdd(&s_fill[kq], 1);           // may pass the capacity: cut back below
-                atomicOr(&s_hit[kq >> 2], (1u << q) << (8 * (kq & 3)));
-            } else if (q == s && kq == LAB_INVALID) {
+    if (ok && tid < ce) {
+        int32_t kq[BW_MAX];                          // (all steps' loads first: one trip to memory, not one per step)
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) kq[q] = q < w ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
+#pragma unroll
+        for (int q = 0; q < BW_MAX; ++q) {
+            if (kq[q] >= 0) {
+                if (q <= s) atomicAdd(&s_fill[kq[q]], 1);        // may pass the capacity: cut back below
+                atomicOr(&s_hit[kq[q] >> 2], (1u << q) << (8 * (kq[q] & 3)));
+            } else if (q == s && kq[q] == LAB_INVALID) {
                 atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
             }
         }
+    }
     __syncthreads();
 
     // ---- fill counts after the step; after the last step of the window they go out to memory, with the strategies' state ----
