@@ -256,7 +256,7 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * twice) the plan settles, so the cost of a launch is paid once per that many
  * steps.  Beyond those limits, for up to 1024 candidates and representatives,
  * b <= 4096 (b <= 1024 with the Bernoulli selection) and up to 10240 classes,
- * up to 8 steps share one launch in the same way; their plan is made by two
+ * up to 16 steps share one launch in the same way; their plan is made by two
  * workgroups per step of the launch before, which work side by side (should
  * they ever fail to hear from each other within 2 s, that launch moves nothing
  * and raises RB_FLAG_PLAN_TIMEOUT).  Otherwise the steps are enqueued one

@@ -37,7 +37,9 @@
 
 namespace {
 
-constexpr int BW_MAX = 8;                           // most steps one launch covers
+constexpr int BW_MAX = 16;                          // most steps one launch covers
+constexpr int BW_HALF = 8;                          // steps whose tables one batch of lookups covers (registers)
+static_assert(BW_MAX % BW_HALF == 0 && BW_MAX <= 16, "step masks are 16-bit");
 constexpr uint64_t BW_TIMEOUT_TICKS = 200000000ull; // bound of every wait: 2 s of the 100 MHz wall clock
 constexpr uint32_t BW_MISSING = 0xFFFFFFFFu;        // bw_lookup: the row is not in the table
 
@@ -94,6 +96,23 @@ struct BwMoveArgs {
     int64_t row_vec;
     int32_t tpr, tile_vec, tile_rem;
 };
+
+// Pointer number i of one of the per-step pointer arrays of BwMoveArgs, for kernels whose FIRST argument that struct is
+// (it then starts the kernel's argument segment, `args`).  One load at a computed offset in place of a choice among
+// BW_MAX values; where i is the same in all lanes it is a scalar load.
+// bw_kernel_args() has a meaning in the kernel function itself only (elsewhere the compiler yields a null pointer):
+// functions that are called take `args` as a parameter.
+typedef const char __attribute__((address_space(4))) * BwArgBytes;
+__device__ __forceinline__ BwArgBytes bw_kernel_args()
+{
+    return (BwArgBytes)__builtin_amdgcn_kernarg_segment_ptr();
+}
+template <typename T>
+__device__ __forceinline__ T* bw_step_pointer(BwArgBytes args, size_t array_offset, int i)
+{
+    typedef T* const __attribute__((address_space(4))) * ArgPointer;
+    return *(ArgPointer)(args + array_offset + sizeof(void*) * (size_t)i);
+}
 
 __device__ __forceinline__ const int64_t* bw_labels(const BwPlanArgs& a, int s)
 {
@@ -159,18 +178,18 @@ __device__ __forceinline__ uint64_t bw_get64(const uint64_t* p)
 // probe round, not per table (a dependent trip costs 1 to 2 us while the movers are running).  Returns the steps
 // whose table holds the row, their values in val[q].
 // PLAIN: the tables were published by an earlier launch (the movers' case): ordinary, cached loads.
-template <bool PLAIN = false>
-__device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_MAX])
+template <bool PLAIN>
+__device__ __forceinline__ uint32_t bw_lookup_half(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_HALF])
 {
-    uint32_t h[BW_MAX];
+    uint32_t h[BW_HALF];
 #pragma unroll
-    for (int q = 0; q < BW_MAX; ++q) h[q] = big_hash(row);
+    for (int q = 0; q < BW_HALF; ++q) h[q] = big_hash(row);
     uint32_t pending = steps, found = 0;
     // two consecutive slots per table and round: the tables are half full, so most walks end in the first round
     for (int probes = 0; pending != 0 && probes < BIG_HASH; probes += 2) {
-        uint64_t at[BW_MAX], nx[BW_MAX];
+        uint64_t at[BW_HALF], nx[BW_HALF];
 #pragma unroll
-        for (int q = 0; q < BW_MAX; ++q)
+        for (int q = 0; q < BW_HALF; ++q)
             if ((pending >> q) & 1u) {
                 const uint64_t* tab = tabs + (size_t)q * BIG_HASH;
                 const uint32_t h1 = (h[q] + 1) & (BIG_HASH - 1);
@@ -178,7 +197,7 @@ __device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32
                 nx[q] = PLAIN ? tab[h1] : bw_get64(tab + h1);
             }
 #pragma unroll
-        for (int q = 0; q < BW_MAX; ++q) {
+        for (int q = 0; q < BW_HALF; ++q) {
             if (!((pending >> q) & 1u)) continue;
             if ((uint32_t)at[q] == row || ((uint32_t)at[q] != BIG_EMPTY && (uint32_t)nx[q] == row)) {
                 found |= 1u << q;
@@ -190,6 +209,24 @@ __device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32
                 h[q] = (h[q] + 2) & (BIG_HASH - 1);
             }
         }
+    }
+    return found;
+}
+// (BW_HALF tables at a time: their words of one round are all in registers together)
+template <bool PLAIN = false>
+__device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_MAX])
+{
+    uint32_t found = 0;
+#pragma unroll
+    for (int p = 0; p < BW_MAX / BW_HALF; ++p) {
+        const uint32_t part = (steps >> (p * BW_HALF)) & ((1u << BW_HALF) - 1u);
+        if (part == 0) continue;
+        uint32_t v[BW_HALF];
+        const uint32_t f = bw_lookup_half<PLAIN>(tabs + (size_t)p * BW_HALF * BIG_HASH, row, part, v);
+#pragma unroll
+        for (int q = 0; q < BW_HALF; ++q)
+            if ((f >> q) & 1u) val[p * BW_HALF + q] = v[q];
+        found |= f << (p * BW_HALF);
     }
     return found;
 }
@@ -373,10 +410,11 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     // ---- C: this step's writes against the other steps of the window ----
     ok = bw_await(t.flags->update, s + 1, w, a.number, &s_ok) && ok;
     ok = bw_await(t.flags->sample, 0, s, a.number, &s_ok) && ok;
-    // Which other steps bring candidates of this step's classes (one byte of step bits per slot of the class table, in the
+    // Which other steps bring candidates of this step's classes (16 step bits per slot of the class table, in the
     // words that held the class lists): only their tables can hold this step's rows.
     uint32_t* cmask = s_draw;
-    for (int i = tid; i < BIG_HASH / 4; i += BIG_TPB) cmask[i] = 0;
+    static_assert(BIG_HASH / 2 <= BIG_MAX + 4, "the step bits fit where the class lists were");
+    for (int i = tid; i < BIG_HASH / 2; i += BIG_TPB) cmask[i] = 0;
     __syncthreads();
     if (ok && tid < ce) {
         int32_t kq[BW_MAX];
@@ -386,12 +424,12 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
         for (int q = 0; q < BW_MAX; ++q) {
             if (kq[q] < 0) continue;
             const int hq = big_find(ckey, (uint32_t)kq[q]);
-            if (hq >= 0) atomicOr(&cmask[hq >> 2], (1u << q) << (8 * (hq & 3)));
+            if (hq >= 0) atomicOr(&cmask[hq >> 1], (1u << q) << (16 * (hq & 1)));
         }
     }
     __syncthreads();
     if (ok && stored) {
-        const uint32_t others = (cmask[h >> 2] >> (8 * (h & 3))) & 0xFFu;
+        const uint32_t others = (cmask[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
         uint32_t val[BW_MAX];
         const uint32_t writers = bw_lookup_steps(t.wrote, (uint32_t)row, others, val);
         if (writers >> (s + 1)) {
@@ -415,7 +453,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
 {
     int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the window, after step s, then their prefix sums
     uint32_t* s_u = lds + BIG_FILL;                        // draw table, then the table of the rows read
-    uint32_t* s_hit = s_u + 2 * BIG_HASH;                  // one byte per class: the steps of the window (bit q) that bring it candidates
+    uint32_t* s_hit = s_u + 2 * BIG_HASH;                  // one byte per class: bit i: a step q of the window with q mod 8 = i brings it candidates
     uint32_t* s_draw = s_u + 4 * BIG_HASH;                 // sampling draws (bit 31: repeated)
     static_assert(BIG_CLASSES / 4 <= 2 * BIG_HASH, "a byte per class in the second table region");
     __shared__ int s_wave[BIG_NWAVE];
@@ -460,7 +498,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         for (int q = 0; q < BW_MAX; ++q) {
             if (kq[q] >= 0) {
                 if (q <= s) atomicAdd(&s_fill[kq[q]], 1);        // may pass the capacity: cut back below
-                atomicOr(&s_hit[kq[q] >> 2], (1u << q) << (8 * (kq[q] & 3)));
+                atomicOr(&s_hit[kq[q] >> 2], (1u << (q & 7)) << (8 * (kq[q] & 3)));
             } else if (q == s && kq[q] == LAB_INVALID) {
                 atomicOr(&s_flags, (uint32_t)RB_FLAG_BAD_LABEL);
             }
@@ -533,7 +571,7 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
     __syncthreads();
     int32_t pk = -1;
     int64_t prow = -1;
-    uint32_t touched = 0;                            // steps of the window that bring candidates to the sample's class
+    uint32_t touched = 0;                            // steps of the window that may bring candidates to the sample's class
     if (drawing) {
         const int64_t g = big_replaced(s_draw, tid, base) ? base + tid : (int64_t)g0;     // class-major index of the sample
         int seg = 0;
@@ -546,7 +584,9 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         }
         pk = lo;
         prow = (int64_t)pk * S + (g - s_fill[lo]);
-        touched = (s_hit[pk >> 2] >> (8 * (pk & 3))) & 0xFFu;
+        const uint32_t hit = (s_hit[pk >> 2] >> (8 * (pk & 3))) & 0xFFu;
+        touched = (hit | hit << 8) & ((1u << w) - 1u);
+        static_assert(BW_MAX <= 16, "two steps per bit at most");
     }
     // the rows this step reads, for the update planners of the later steps
     __syncthreads();                                 // (the draw table has been read)
@@ -606,6 +646,96 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_plan_kernel(const BwPlanArg
     else bw_plan_update(a, s, lds);
 }
 
+// A candidate's row stored in a slot whose content from before the window representatives of earlier steps of the
+// window still need (those that the sampling planner of their step marked as handed out by the writer): every lane
+// copies its own vectors out to them and only then overwrites these same vectors, so no lane waits for another.
+// Kept out of line: the movers' common path is short, and stays so whatever this one needs.
+// args: the calling kernel's argument segment, which BwMoveArgs starts (bw_step_pointer).
+template <int U, int W, bool BF16>
+__device__ __noinline__ void bw_hand_off(BwArgBytes args, const char* table, DevState* state, vec16* slot, const vec16* fresh, uint32_t row, int s,
+                                          int c, int r, int64_t row_vec, int64_t v_lo, int64_t v_hi, bool first)
+{
+    constexpr int WIDE = BF16 ? 2 : 1;
+    const int lane = threadIdx.x & (W - 1);
+    const int rows = c + r;
+    const WinEntry* entry = reinterpret_cast<const WinEntry*>(table + BW_OFF_ENTRY);
+    const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(table + BW_OFF_READ);
+    // BW_HALF earlier steps at a time (their output pointers are in registers together); the pass over the last
+    // of them also stores the candidate.
+#pragma unroll
+    for (int p = 0; p < BW_MAX / BW_HALF; ++p) {
+        const bool final_pass = p == BW_MAX / BW_HALF - 1;
+        const uint32_t part = (((1u << s) - 1u) >> (p * BW_HALF)) & ((1u << BW_HALF) - 1u);
+        if (part == 0 && !final_pass) continue;
+        vec16* reader_x[BW_HALF];       // (indexed by compile-time constants only: registers) of step q, null: none
+        uint32_t reader[BW_HALF];
+        const uint32_t reading = part ? bw_lookup_half<true>(read_tables + (size_t)p * BW_HALF * BIG_HASH, row, part, reader) : 0u;
+        bool any = false;
+#pragma unroll
+        for (int q = 0; q < BW_HALF; ++q) {
+            reader_x[q] = nullptr;
+            if (!((reading >> q) & 1u)) continue;
+            const int step = p * BW_HALF + q;
+            const uint32_t j = reader[q];
+            const WinEntry rq = entry[step * rows + c + (int)j];
+            if (!rq.handled) continue;
+            reader_x[q] = bw_step_pointer<vec16>(args, offsetof(BwMoveArgs, out_x), step) + (int64_t)j * row_vec * WIDE;
+            any = true;
+            if (first) {
+                bw_step_pointer<int64_t>(args, offsetof(BwMoveArgs, out_y), step)[j] = rq.label;
+                count_moved(state);
+            }
+        }
+        if (!any && !final_pass) continue;
+        // (all of a lane's vectors are read before any is written: the reads are in flight together)
+        if (BF16) {
+            vec8* half = reinterpret_cast<vec8*>(slot);
+#pragma unroll
+            for (int g = 0; g < 2; ++g) {       // (a lane's vectors in two batches: registers)
+                vec8 old[U];
+                vec16 in[U];
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = 2 * v_lo + lane + (int64_t)(g * U + u) * W;
+                    if (i < 2 * v_hi) {
+                        if (any) old[u] = half[i];
+                        if (final_pass) in[u] = fresh[i];
+                    }
+                }
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    const int64_t i = 2 * v_lo + lane + (int64_t)(g * U + u) * W;
+                    if (i >= 2 * v_hi) continue;
+                    const vec16 wide = widen4(old[u]);
+#pragma unroll
+                    for (int q = 0; q < BW_HALF; ++q)
+                        if (reader_x[q]) reader_x[q][i] = wide;
+                    if (final_pass) half[i] = narrow4(in[u]);
+                }
+            }
+        } else {
+            vec16 old[U], in[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t i = v_lo + lane + (int64_t)u * W;
+                if (i < v_hi) {
+                    if (any) old[u] = slot[i];
+                    if (final_pass) in[u] = fresh[i];
+                }
+            }
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                const int64_t i = v_lo + lane + (int64_t)u * W;
+                if (i >= v_hi) continue;
+#pragma unroll
+                for (int q = 0; q < BW_HALF; ++q)
+                    if (reader_x[q]) reader_x[q][i] = old[u];
+                if (final_pass) slot[i] = in[u];
+            }
+        }
+    }
+}
+
 // ---------------------------------------------------------------------------
 // All steps of one window by its table: every group of BIG_GROUP threads moves one tile of one row; the
 // first 2 next.w workgroups plan the next window instead.
@@ -624,9 +754,15 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
         else bw_plan_update(next, s, lds);
         return;
     }
+    // the per-step pointers of m, by step number
+    const BwArgBytes args = bw_kernel_args();
+    const auto batch_x_of = [args](int q) { return bw_step_pointer<const vec16>(args, offsetof(BwMoveArgs, batch_x), q); };
+    const auto out_x_of = [args](int q) { return bw_step_pointer<vec16>(args, offsetof(BwMoveArgs, out_x), q); };
+    const auto out_y_of = [args](int q) { return bw_step_pointer<int64_t>(args, offsetof(BwMoveArgs, out_y), q); };
     const int rows = m.c + m.r;                 // entries per step in the table
     const int64_t per_step = (int64_t)(m.cgrid + m.r) * m.tpr;
-    const int64_t item = (int64_t)((int)blockIdx.x - planners) * (BIG_TPB / W) + threadIdx.x / W;
+    static_assert(W % WAVE == 0, "a wavefront works on one tile: what follows from its number is the same in all lanes");
+    const int64_t item = (int64_t)((int)blockIdx.x - planners) * (BIG_TPB / W) + __builtin_amdgcn_readfirstlane((int)threadIdx.x / W);
     if (item >= per_step * m.w) return;
     const int s = (int)(item / per_step);
     int e, tile;
@@ -653,101 +789,43 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
         const auto store_candidate = [&](const WinEntry& en) {
             if (en.row < 0) return;             // dropped within its step, or overwritten again later in the window
             vec16* slot = m.buf_x + en.row * m.row_vec;
-            const vec16* fresh = m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE;
+            const vec16* fresh = batch_x_of(s) + (int64_t)en.src * m.row_vec * WIDE;
             if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-            if (en.chain < 0) {
+            if (__builtin_expect(en.chain < 0, 1)) {
                 Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
                 t.load(fresh, v_lo, v_hi);
                 t.store(slot, v_lo, v_hi);
                 return;
             }
-            // Representatives of earlier steps need what the slot held before the window (those that the sampling planner
-            // of their step marked as handed out from here).  Every lane copies its own vectors out to them and only then
-            // overwrites these same vectors: no lane waits for another.
-            const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(m.table + BW_OFF_READ);
-            vec16* reader_x[BW_MAX - 1];        // (indexed by compile-time constants only: registers) of step q, null: none
-            uint32_t reader[BW_MAX];
-            const uint32_t reading = bw_lookup_steps<true>(read_tables, (uint32_t)en.row, (1u << s) - 1u, reader);   // all earlier steps at once
-#pragma unroll
-            for (int q = 0; q < BW_MAX - 1; ++q) {
-                reader_x[q] = nullptr;
-                if (!((reading >> q) & 1u)) continue;
-                const uint32_t j = reader[q];
-                const WinEntry rq = entry[q * rows + m.c + (int)j];
-                if (!rq.handled) continue;
-                reader_x[q] = m.out_x[q] + (int64_t)j * m.row_vec * WIDE;
-                if (first) {
-                    m.out_y[q][j] = rq.label;
-                    count_moved(m.state);
-                }
-            }
-            // (all of a lane's vectors are read before any is written: the reads are in flight together)
-            if (BF16) {
-                vec8* half = reinterpret_cast<vec8*>(slot);
-                vec8 old[2 * U];
-                vec16 in[2 * U];
-#pragma unroll
-                for (int u = 0; u < 2 * U; ++u) {
-                    const int64_t i = 2 * v_lo + lane + (int64_t)u * W;
-                    if (i < 2 * v_hi) {
-                        old[u] = half[i];
-                        in[u] = fresh[i];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < 2 * U; ++u) {
-                    const int64_t i = 2 * v_lo + lane + (int64_t)u * W;
-                    if (i >= 2 * v_hi) continue;
-                    const vec16 wide = widen4(old[u]);
-#pragma unroll
-                    for (int q = 0; q < BW_MAX - 1; ++q)
-                        if (reader_x[q]) reader_x[q][i] = wide;
-                    half[i] = narrow4(in[u]);
-                }
-            } else {
-                vec16 old[U], in[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = v_lo + lane + (int64_t)u * W;
-                    if (i < v_hi) {
-                        old[u] = slot[i];
-                        in[u] = fresh[i];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = v_lo + lane + (int64_t)u * W;
-                    if (i >= v_hi) continue;
-#pragma unroll
-                    for (int q = 0; q < BW_MAX - 1; ++q)
-                        if (reader_x[q]) reader_x[q][i] = old[u];
-                    slot[i] = in[u];
-                }
-            }
+            bw_hand_off<U, W, BF16>(args, m.table, m.state, slot, fresh, (uint32_t)en.row, s, m.c, m.r, m.row_vec, v_lo, v_hi, first);
         };
         // The grid covers cgrid candidate rows per step; when the plan has more (Bernoulli selection), a group goes on to
         // the entry cgrid further on.  (The first entry is asked for before the step's count is known: it is inside the
         // step's part of the table whatever the count.)
-        const WinEntry en0 = entry[s * rows + e];
+        int ee = e;
+        WinEntry en = entry[s * rows + ee];
         const int count = (int)flags->count[s];
-        if (e < count) store_candidate(en0);
-        for (int ee = e + m.cgrid; ee < count; ee += m.cgrid) store_candidate(entry[s * rows + ee]);
+        while (ee < count) {
+            store_candidate(en);
+            ee += m.cgrid;
+            if (ee < count) en = entry[s * rows + ee];
+        }
         return;
     }
     const int j = e - m.cgrid;
     const WinEntry en = entry[s * rows + m.c + j];
     if (en.handled) return;
-    if (first) m.out_y[s][j] = en.label;        // -1 when fewer samples are stored than asked for
+    if (first) out_y_of(s)[j] = en.label;        // -1 when fewer samples are stored than asked for
     if (en.label < 0) return;
     if (first) count_moved(m.state);
-    vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
+    vec16* dst = out_x_of(s) + (int64_t)j * m.row_vec * WIDE;
     if (BF16 && en.src >= 0) {
         // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
         Tile<U, NT, W, WIN_PACE, CV_BOTH> t;
-        t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
+        t.load(batch_x_of(en.src >> 16) + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
-        const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
+        const vec16* src = en.src >= 0 ? batch_x_of(en.src >> 16) + (int64_t)(en.src & 0xFFFF) * m.row_vec
                                        : m.buf_x + en.row * m.row_vec;
         Tile<U, NT, W, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
         t.load(src, v_lo, v_hi);

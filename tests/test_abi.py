@@ -117,8 +117,8 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)            # few rows per step: the most
     assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 8)          # 1024 table entries / 128 rows per step
     assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 12)         # 512 planner slots / max(c, r)
-    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 8)           # beyond the small form: the large-count form's 8
-    assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 8)
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 16)          # beyond the small form: the large-count form's 16
+    assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 16)
     assert rb.rb_query_steps_per_launch(h, 4096, 1025, 8) == (rb.RB_OK, 1)        # not eligible for either
     assert rb.rb_query_steps_per_launch(h, 64, 0, 8) == (rb.RB_OK, 1)
     assert rb.rb_set_option(h, rb.RB_OPT_WINDOW, 5) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)

@@ -669,7 +669,7 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
 
 # ------------------------- several steps per launch with large counts (1024-thread planners side by side) ---
 
-@pytest.mark.parametrize("window", [8, 5, 2])
+@pytest.mark.parametrize("window", [16, 11, 5, 2])
 @pytest.mark.parametrize("w,policy,bf16", [
     (wl.variant(wl.C5, name="bw-two-classes", K=2, S=40, shape=(64,), b=256, c=100, r=70), None, False),        # 80 slots in all: every step reads and rewrites most of them
     (wl.variant(wl.C5, name="bw-one-class", K=1, S=150, shape=(32,), b=300, c=120, r=150), None, False),        # r = everything stored: every slot is read in every step
@@ -687,13 +687,15 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     (wl.variant(wl.C5, name="bw-limits", K=10240, S=3, shape=(16,), b=4096, c=1024, r=1024), None, False),      # every limit at once
 ], ids=lambda v: v.name if hasattr(v, "name") else None)
 def test_many_steps_with_large_counts(w, policy, bf16, window):
-    """rb_update_sample_many for shapes beyond the small several-steps form: up to 8 steps per launch, planned by
+    """rb_update_sample_many for shapes beyond the small several-steps form: up to 16 steps per launch, planned by
     two 1024-thread workgroups per step that settle between them what the steps do to each other's slots."""
     rb = _rb()
     pol = POLICIES[policy] if policy else None
     run_many_parity(w, 40, per_call=19, window=window, policy=pol, store_bf16=bf16)
     run_many_parity(w, 40, per_call=16, window=window, announce=True, policy=pol, store_bf16=bf16)
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, store_dtype=torch.bfloat16 if bf16 else None)
+    if pol:
+        buf.set_policy(*pol)
     buf.set_option(rb.RB_OPT_WINDOW, window)
     assert buf.steps_per_launch(w.b, w.c, w.r) == window
 
@@ -711,7 +713,7 @@ def test_many_steps_with_large_counts_drop_and_flag_bad_labels():
     dev = torch.device("cuda:0")
     K, S, b, c, r, n = 1500, 2, 200, 150, 90, 14
     buf = rb.RehearsalBuffer(K, S, (8,), torch.float32, device=dev)
-    assert buf.steps_per_launch(b, c, r) == 8
+    assert buf.steps_per_launch(b, c, r) == 16
     orc = rbo.Buffer(K, S, 32)
     g = torch.Generator(device="cpu")
     g.manual_seed(6)
@@ -739,7 +741,7 @@ def test_many_steps_with_large_counts_drop_and_flag_bad_labels():
 @pytest.mark.parametrize("w", [wl.C5, wl.C5F], ids=["C5", "C5F"])
 def test_many_steps_with_large_counts_at_full_size(w):
     """C5 and its variant with a fixed set of active classes in the form the bench times them in: announced
-    rb_update_sample_many calls, 8 steps per launch, every configured step."""
+    rb_update_sample_many calls, 16 steps per launch, every configured step."""
     run_many_parity(w, w.steps, per_call=32, announce=True)
 
 
