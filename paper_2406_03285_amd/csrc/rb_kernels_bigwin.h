@@ -11,25 +11,28 @@
 //      FIFO / reservoir strategies follows from the same sums in closed form; so a planner waits for the
 //      classes of the steps before its own and needs nothing else of them to plan its step as
 //      rb_kernels_big.h does;
-//   B  every planner writes its step's table entries, and publishes a hash table of the slot rows its step
-//      writes (update) or reads (sampling);
+//   B  every planner writes its step's table entries; an update planner also publishes a hash table of the slot
+//      rows its step writes;
 //   C  what the order of separate launches would settle between steps (rb_kernels_window.h) every planner
-//      settles for its OWN entries by looking rows up in the other steps' tables: a representative whose slot
-//      an earlier step of the window (or its own) writes is copied from the mini-batch row stored there; of
-//      several writes to one slot only the last is carried out; and a representative that needs what a slot
-//      held before the window while a later step overwrites it is left to the workgroups that carry out that
-//      write (they find it through the step's table of rows read and copy the old content out first).
-// What planners read of each other (classes, row tables, flags) is written with stores that go through to
-// memory and read with loads that do not stop at a cache of their own die (agent-scope atomics: the dies of
-// the chip do not see each other's caches), and a flag is set only when the stores before it have been
-// acknowledged; the table entries have one writer each and are only read by the next launch.  No cache is
-// written back or invalidated as a whole: with the movers' traffic in them that took longer than the plan.
+//      settles for its OWN entries by looking rows up in the other steps' tables: of several writes to one slot
+//      only the last is carried out; a representative whose slot an earlier step of the window (or its own)
+//      writes is copied from the mini-batch row stored there; and a representative that needs what a slot held
+//      before the window while a later step overwrites it is left to the workgroups that carry out that write:
+//      its planner puts it on a list that hangs off the writing candidate (an exchange on the list's head), and
+//      those workgroups copy the old content out to the list's members before they overwrite it.
+// What planners read of each other (classes, row tables, list heads, flags) is written with stores that go
+// through to memory and read with loads that do not stop at a cache of their own die (agent-scope atomics: the
+// dies of the chip do not see each other's caches), and a flag is set only when the stores before it have been
+// acknowledged; the table entries and list links have one writer each and are only read by the next launch.  No
+// cache is written back or invalidated as a whole: with the movers' traffic in them that took longer than the plan.
 // The planners are the first workgroups of their launch, which starts when the launch before has ended: they
 // are all resident from the start and never wait for a workgroup that has not been dispatched.  Every wait is
 // bounded all the same (BW_TIMEOUT_TICKS): a planner that gives up marks the window's table as failed, the
 // window's launch then moves nothing and raises RB_FLAG_PLAN_TIMEOUT.
 // Included by rb.hip only, after rb_kernels_window.h (table entry format) and rb_kernels_big.h (selection, hash tables).
 #pragma once
+
+#include <type_traits>
 
 #include "rb_device.h"
 #include "rb_kernels_window.h"
@@ -46,8 +49,7 @@ constexpr uint32_t BW_MISSING = 0xFFFFFFFFu;        // bw_lookup: the row is not
 // The table of one window in the workspace (two of them, used in turn).
 struct BwFlags {
     uint32_t classes[BW_MAX];   // = the window's number once step s's candidate classes are published (A)
-    uint32_t update[BW_MAX];    // ... once step s's update planner has published entries and write table (B)
-    uint32_t sample[BW_MAX];    // ... once step s's sampling planner has published entries and read table (B)
+    uint32_t update[BW_MAX];    // ... once step s's update planner has published entries, write table and list heads (B)
     uint32_t failed;            // = the window's number if a planner gave up waiting
     uint32_t pad[7];
     uint32_t count[BW_MAX];     // candidate entries of step s (the Bernoulli selection yields any number of them)
@@ -57,8 +59,10 @@ constexpr size_t BW_OFF_FLAGS = BW_OFF_HEAD + BW_MAX * sizeof(WinHeader);       
 constexpr size_t BW_OFF_ENTRY = BW_OFF_FLAGS + sizeof(BwFlags);                      // entry index = step * (c + r) + (candidate i | c + representative j)
 constexpr size_t BW_OFF_CLASS = BW_OFF_ENTRY + (size_t)BW_MAX * 2 * BIG_MAX * sizeof(WinEntry);   // [step][BIG_MAX] candidate classes
 constexpr size_t BW_OFF_WROTE = BW_OFF_CLASS + (size_t)BW_MAX * BIG_MAX * 4;         // [step][BIG_HASH] 64-bit words: see BwTable
-constexpr size_t BW_OFF_READ = BW_OFF_WROTE + (size_t)BW_MAX * 2 * BIG_HASH * 4;     // likewise
-constexpr size_t BW_TABLE_BYTES = (BW_OFF_READ + (size_t)BW_MAX * 2 * BIG_HASH * 4 + 255) / 256 * 256;
+constexpr size_t BW_OFF_FIRST = BW_OFF_WROTE + (size_t)BW_MAX * 2 * BIG_HASH * 4;    // [step][BIG_MAX] list heads, by candidate entry
+constexpr size_t BW_OFF_NEXT = BW_OFF_FIRST + (size_t)BW_MAX * BIG_MAX * 4;          // [step][BIG_MAX] list links, by representative
+constexpr size_t BW_TABLE_BYTES = (BW_OFF_NEXT + (size_t)BW_MAX * BIG_MAX * 4 + 255) / 256 * 256;
+constexpr uint32_t BW_NONE = 0xFFFFFFFFu;           // end of a list; otherwise step << 16 | representative
 static_assert(sizeof(BwFlags) % 16 == 0 && BW_OFF_ENTRY % 16 == 0, "entries are 16-byte aligned");
 
 struct BwPlanArgs {
@@ -177,8 +181,6 @@ __device__ __forceinline__ uint64_t bw_get64(const uint64_t* p)
 // `row` looked up in the tables of all steps q with bit q of `steps` set, all at once: a round trip to memory per
 // probe round, not per table (a dependent trip costs 1 to 2 us while the movers are running).  Returns the steps
 // whose table holds the row, their values in val[q].
-// PLAIN: the tables were published by an earlier launch (the movers' case): ordinary, cached loads.
-template <bool PLAIN>
 __device__ __forceinline__ uint32_t bw_lookup_half(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_HALF])
 {
     uint32_t h[BW_HALF];
@@ -193,8 +195,8 @@ __device__ __forceinline__ uint32_t bw_lookup_half(const uint64_t* tabs, uint32_
             if ((pending >> q) & 1u) {
                 const uint64_t* tab = tabs + (size_t)q * BIG_HASH;
                 const uint32_t h1 = (h[q] + 1) & (BIG_HASH - 1);
-                at[q] = PLAIN ? tab[h[q]] : bw_get64(tab + h[q]);
-                nx[q] = PLAIN ? tab[h1] : bw_get64(tab + h1);
+                at[q] = bw_get64(tab + h[q]);
+                nx[q] = bw_get64(tab + h1);
             }
 #pragma unroll
         for (int q = 0; q < BW_HALF; ++q) {
@@ -213,7 +215,6 @@ __device__ __forceinline__ uint32_t bw_lookup_half(const uint64_t* tabs, uint32_
     return found;
 }
 // (BW_HALF tables at a time: their words of one round are all in registers together)
-template <bool PLAIN = false>
 __device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32_t row, uint32_t steps, uint32_t (&val)[BW_MAX])
 {
     uint32_t found = 0;
@@ -222,7 +223,7 @@ __device__ __forceinline__ uint32_t bw_lookup_steps(const uint64_t* tabs, uint32
         const uint32_t part = (steps >> (p * BW_HALF)) & ((1u << BW_HALF) - 1u);
         if (part == 0) continue;
         uint32_t v[BW_HALF];
-        const uint32_t f = bw_lookup_half<PLAIN>(tabs + (size_t)p * BW_HALF * BIG_HASH, row, part, v);
+        const uint32_t f = bw_lookup_half(tabs + (size_t)p * BW_HALF * BIG_HASH, row, part, v);
 #pragma unroll
         for (int q = 0; q < BW_HALF; ++q)
             if ((f >> q) & 1u) val[p * BW_HALF + q] = v[q];
@@ -236,8 +237,10 @@ struct BwTable {
     BwFlags* flags;
     WinEntry* entry;
     int32_t* classes;
-    uint64_t* wrote;      // [step][BIG_HASH]: rows the step writes -> mini-batch position << 16 | candidate
-    uint64_t* read;       // [step][BIG_HASH]: rows the step reads -> representative
+    uint64_t* wrote;      // [step][BIG_HASH]: rows the step writes -> mini-batch position << 16 | candidate entry
+    uint32_t* first;      // [step][BIG_MAX]: by candidate entry: the first representative (step << 16 | number) that
+                          // gets the slot's old content from the candidate's workgroups, BW_NONE: none
+    uint32_t* next;       // [step][BIG_MAX]: by representative: the one after it on that list
 };
 __device__ __forceinline__ BwTable bw_table(char* table)
 {
@@ -247,7 +250,8 @@ __device__ __forceinline__ BwTable bw_table(char* table)
     t.entry = reinterpret_cast<WinEntry*>(table + BW_OFF_ENTRY);
     t.classes = reinterpret_cast<int32_t*>(table + BW_OFF_CLASS);
     t.wrote = reinterpret_cast<uint64_t*>(table + BW_OFF_WROTE);
-    t.read = reinterpret_cast<uint64_t*>(table + BW_OFF_READ);
+    t.first = reinterpret_cast<uint32_t*>(table + BW_OFF_FIRST);
+    t.next = reinterpret_cast<uint32_t*>(table + BW_OFF_NEXT);
     return t;
 }
 
@@ -376,7 +380,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     const bool placed = valid && slot >= 0;          // (a reservoir may not keep a candidate)
     const int64_t row = placed ? (int64_t)k * S + slot : -1;
     uint32_t* rkey = s_v;                            // slot rows written in this step
-    uint32_t* rval = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there, then position << 16 | candidate
+    uint32_t* rval = s_v + BIG_HASH;                 // 1 + the largest mini-batch position that goes there, then position << 16 | candidate entry
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) {
         rkey[i] = BIG_EMPTY;
         rval[i] = 0;
@@ -391,7 +395,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     // of the candidates of this step that go to one slot the last of the mini-batch is stored
     const bool stored = placed && rval[hr] == (uint32_t)x + 1u;
     __syncthreads();
-    if (stored) rval[hr] = ((uint32_t)x << 16) | (uint32_t)tid;
+    if (stored) rval[hr] = ((uint32_t)x << 16) | (uint32_t)ent;
     const int me = s * rows + ent;
     if (has_entry) {
         WinEntry e;
@@ -402,15 +406,15 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
         e.handled = 0;
         e.pad[0] = 0; e.pad[1] = 0;
         t.entry[me] = e;
+        bw_put(t.first + s * BIG_MAX + ent, BW_NONE);          // nobody waits for the slot's old content yet
     }
     __syncthreads();
     for (int i = tid; i < BIG_HASH; i += BIG_TPB) bw_put64(t.wrote + (size_t)s * BIG_HASH + i, (uint64_t)rval[i] << 32 | rkey[i]);
     bw_publish(&t.flags->update[s], a.number);
 
-    // ---- C: this step's writes against the other steps of the window ----
+    // ---- C: this step's writes against the later steps of the window ----
     ok = bw_await(t.flags->update, s + 1, w, a.number, &s_ok) && ok;
-    ok = bw_await(t.flags->sample, 0, s, a.number, &s_ok) && ok;
-    // Which other steps bring candidates of this step's classes (16 step bits per slot of the class table, in the
+    // Which later steps bring candidates of this step's classes (16 step bits per slot of the class table, in the
     // words that held the class lists): only their tables can hold this step's rows.
     uint32_t* cmask = s_draw;
     static_assert(BIG_HASH / 2 <= BIG_MAX + 4, "the step bits fit where the class lists were");
@@ -419,7 +423,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     if (ok && tid < ce) {
         int32_t kq[BW_MAX];
 #pragma unroll
-        for (int q = 0; q < BW_MAX; ++q) kq[q] = q < w && q != s ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
+        for (int q = 0; q < BW_MAX; ++q) kq[q] = q < w && q > s ? (int32_t)bw_get(reinterpret_cast<const uint32_t*>(t.classes) + q * BIG_MAX + tid) : -1;
 #pragma unroll
         for (int q = 0; q < BW_MAX; ++q) {
             if (kq[q] < 0) continue;
@@ -429,18 +433,10 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
     }
     __syncthreads();
     if (ok && stored) {
-        const uint32_t others = (cmask[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
+        const uint32_t later = (cmask[h >> 1] >> (16 * (h & 1))) & 0xFFFFu;
         uint32_t val[BW_MAX];
-        const uint32_t writers = bw_lookup_steps(t.wrote, (uint32_t)row, others, val);
-        if (writers >> (s + 1)) {
-            t.entry[me].row = -1;                    // a later step writes the same slot: this write is not carried out
-        } else if (slot < before_window) {
-            // the slot held a sample before the window.  Representatives of the steps before the first write to it
-            // read that sample: this write's workgroups copy it out to them before they overwrite it.
-            const uint32_t earlier = writers & ((1u << s) - 1u);
-            const int first_write = earlier ? __builtin_ctz(earlier) : s;
-            if (bw_lookup_steps(t.read, (uint32_t)row, (1u << first_write) - 1u, val) != 0) t.entry[me].chain = 1;
-        }
+        // a later step writes the same slot: this write is not carried out
+        if (later != 0 && bw_lookup_steps(t.wrote, (uint32_t)row, later, val) != 0) t.entry[me].row = -1;
     }
     if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
 }
@@ -588,13 +584,6 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         touched = (hit | hit << 8) & ((1u << w) - 1u);
         static_assert(BW_MAX <= 16, "two steps per bit at most");
     }
-    // the rows this step reads, for the update planners of the later steps
-    __syncthreads();                                 // (the draw table has been read)
-    uint32_t* rkey = s_u;
-    uint32_t* rval = rkey + BIG_HASH;
-    for (int i = tid; i < BIG_HASH; i += BIG_TPB) rkey[i] = BIG_EMPTY;
-    __syncthreads();
-    if (drawing) rval[big_find_or_insert(rkey, (uint32_t)prow)] = (uint32_t)tid;      // (the representatives of a step are different samples)
     const int me = s * rows + ce + tid;
     if (tid < r) {
         WinEntry e;
@@ -613,9 +602,6 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         hh.pad[0] = 0; hh.pad[1] = 0;
         t.head[s] = hh;
     }
-    __syncthreads();
-    for (int i = tid; i < BIG_HASH; i += BIG_TPB) bw_put64(t.read + (size_t)s * BIG_HASH + i, (uint64_t)rval[i] << 32 | rkey[i]);
-    bw_publish(&t.flags->sample[s], a.number);
 
     // ---- C: a slot that this step or an earlier one of the window writes is read from the mini-batch row stored there;
     //         what a later step overwrites is handed out by the workgroups that overwrite it ----
@@ -624,14 +610,19 @@ __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint3
         uint32_t val[BW_MAX];
         const uint32_t writers = bw_lookup_steps(t.wrote, (uint32_t)prow, touched, val);
         const uint32_t upto = writers & ((2u << s) - 1u);
-        if (upto != 0) {
-            const int q = 31 - __builtin_clz(upto);            // the latest write up to this step
-            uint32_t v = 0;
+        const int q = 31 - __builtin_clz(upto != 0 ? upto : (writers | 1u));   // the latest write up to this step, else the last one of the window
+        uint32_t v = 0;
 #pragma unroll
-            for (int i = 0; i < BW_MAX; ++i) v = i == q ? val[i] : v;
+        for (int i = 0; i < BW_MAX; ++i) v = i == q ? val[i] : v;
+        if (upto != 0) {
             t.entry[me].src = (q << 16) | (int)(v >> 16);
         } else if (writers != 0) {
-            t.entry[me].handled = 1;                           // overwritten by a later step, whose workgroups hand the old content out
+            // Overwritten later in the window; of those writes the last is the one carried out.  This representative joins
+            // the list of that candidate, whose workgroups hand the slot's old content out to the list's members.
+            t.entry[me].handled = 1;
+            const uint32_t before = __hip_atomic_exchange(t.first + q * BIG_MAX + (int)(v & 0xFFFFu), ((uint32_t)s << 16) | (uint32_t)tid,
+                                                          __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            t.next[s * BIG_MAX + tid] = before;
         }
     }
     if (!ok && tid == 0) bw_put(&t.flags->failed, a.number);
@@ -647,91 +638,59 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_plan_kernel(const BwPlanArg
 }
 
 // A candidate's row stored in a slot whose content from before the window representatives of earlier steps of the
-// window still need (those that the sampling planner of their step marked as handed out by the writer): every lane
-// copies its own vectors out to them and only then overwrites these same vectors, so no lane waits for another.
-// Kept out of line: the movers' common path is short, and stays so whatever this one needs.
+// window still need: the members of the list that starts with `heir` (their sampling planners put them there).  Every
+// lane copies its own vectors out to them and only then overwrites these same vectors, so no lane waits for another.
 // args: the calling kernel's argument segment, which BwMoveArgs starts (bw_step_pointer).
 template <int U, int W, bool BF16>
-__device__ __noinline__ void bw_hand_off(BwArgBytes args, const char* table, DevState* state, vec16* slot, const vec16* fresh, uint32_t row, int s,
-                                          int c, int r, int64_t row_vec, int64_t v_lo, int64_t v_hi, bool first)
+__device__ __forceinline__ void bw_hand_off(BwArgBytes args, const uint32_t* next, DevState* state, vec16* slot, const vec16* fresh,
+                                            uint32_t heir, int32_t label, int w, int r, int64_t row_vec, int64_t v_lo, int64_t v_hi, bool first)
 {
-    constexpr int WIDE = BF16 ? 2 : 1;
+    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of an output row per vector of a stored row
+    constexpr int UB = U > 4 ? 4 : U;           // a lane's vectors go in batches of that many (registers)
+    constexpr int PART = WIDE * U / UB;
+    typedef typename std::conditional<BF16, vec8, vec16>::type Stored;
     const int lane = threadIdx.x & (W - 1);
-    const int rows = c + r;
-    const WinEntry* entry = reinterpret_cast<const WinEntry*>(table + BW_OFF_ENTRY);
-    const uint64_t* read_tables = reinterpret_cast<const uint64_t*>(table + BW_OFF_READ);
-    // BW_HALF earlier steps at a time (their output pointers are in registers together); the pass over the last
-    // of them also stores the candidate.
+    Stored* stored = reinterpret_cast<Stored*>(slot);
+    const int64_t lo = WIDE * v_lo, hi = WIDE * v_hi;       // in vectors of the output rows
 #pragma unroll
-    for (int p = 0; p < BW_MAX / BW_HALF; ++p) {
-        const bool final_pass = p == BW_MAX / BW_HALF - 1;
-        const uint32_t part = (((1u << s) - 1u) >> (p * BW_HALF)) & ((1u << BW_HALF) - 1u);
-        if (part == 0 && !final_pass) continue;
-        vec16* reader_x[BW_HALF];       // (indexed by compile-time constants only: registers) of step q, null: none
-        uint32_t reader[BW_HALF];
-        const uint32_t reading = part ? bw_lookup_half<true>(read_tables + (size_t)p * BW_HALF * BIG_HASH, row, part, reader) : 0u;
-        bool any = false;
+    for (int g = 0; g < PART; ++g) {
+        // (all of a lane's vectors are read before any is written: the reads are in flight together)
+        Stored old[UB];
+        vec16 in[UB];
 #pragma unroll
-        for (int q = 0; q < BW_HALF; ++q) {
-            reader_x[q] = nullptr;
-            if (!((reading >> q) & 1u)) continue;
-            const int step = p * BW_HALF + q;
-            const uint32_t j = reader[q];
-            const WinEntry rq = entry[step * rows + c + (int)j];
-            if (!rq.handled) continue;
-            reader_x[q] = bw_step_pointer<vec16>(args, offsetof(BwMoveArgs, out_x), step) + (int64_t)j * row_vec * WIDE;
-            any = true;
-            if (first) {
-                bw_step_pointer<int64_t>(args, offsetof(BwMoveArgs, out_y), step)[j] = rq.label;
+        for (int u = 0; u < UB; ++u) {
+            const int64_t i = lo + lane + (int64_t)(g * UB + u) * W;
+            const int64_t at = i < hi ? i : hi - 1;          // (beyond the tile: its last vector again, not used)
+            old[u] = stored[at];
+            in[u] = fresh[at];
+        }
+        // (a list has at most one member per earlier step of the window; the bounds keep a walk finite and inside the
+        // outputs whatever the list's words hold)
+        uint32_t member = heir;
+        for (int walked = 0; member != BW_NONE && walked < BW_MAX; ++walked) {
+            const int q = (int)(member >> 16), j = (int)(member & 0xFFFFu);
+            if (q >= w || j >= r) break;
+            const uint32_t after = next[q * BIG_MAX + j];
+            vec16* out = bw_step_pointer<vec16>(args, offsetof(BwMoveArgs, out_x), q) + (int64_t)j * row_vec * WIDE;
+            if (first && g == 0) {
+                bw_step_pointer<int64_t>(args, offsetof(BwMoveArgs, out_y), q)[j] = label;
                 count_moved(state);
             }
+#pragma unroll
+            for (int u = 0; u < UB; ++u) {
+                const int64_t i = lo + lane + (int64_t)(g * UB + u) * W;
+                if (i >= hi) continue;
+                if constexpr (BF16) out[i] = widen4(old[u]);
+                else out[i] = old[u];
+            }
+            member = after;
         }
-        if (!any && !final_pass) continue;
-        // (all of a lane's vectors are read before any is written: the reads are in flight together)
-        if (BF16) {
-            vec8* half = reinterpret_cast<vec8*>(slot);
 #pragma unroll
-            for (int g = 0; g < 2; ++g) {       // (a lane's vectors in two batches: registers)
-                vec8 old[U];
-                vec16 in[U];
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = 2 * v_lo + lane + (int64_t)(g * U + u) * W;
-                    if (i < 2 * v_hi) {
-                        if (any) old[u] = half[i];
-                        if (final_pass) in[u] = fresh[i];
-                    }
-                }
-#pragma unroll
-                for (int u = 0; u < U; ++u) {
-                    const int64_t i = 2 * v_lo + lane + (int64_t)(g * U + u) * W;
-                    if (i >= 2 * v_hi) continue;
-                    const vec16 wide = widen4(old[u]);
-#pragma unroll
-                    for (int q = 0; q < BW_HALF; ++q)
-                        if (reader_x[q]) reader_x[q][i] = wide;
-                    if (final_pass) half[i] = narrow4(in[u]);
-                }
-            }
-        } else {
-            vec16 old[U], in[U];
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t i = v_lo + lane + (int64_t)u * W;
-                if (i < v_hi) {
-                    if (any) old[u] = slot[i];
-                    if (final_pass) in[u] = fresh[i];
-                }
-            }
-#pragma unroll
-            for (int u = 0; u < U; ++u) {
-                const int64_t i = v_lo + lane + (int64_t)u * W;
-                if (i >= v_hi) continue;
-#pragma unroll
-                for (int q = 0; q < BW_HALF; ++q)
-                    if (reader_x[q]) reader_x[q][i] = old[u];
-                if (final_pass) slot[i] = in[u];
-            }
+        for (int u = 0; u < UB; ++u) {
+            const int64_t i = lo + lane + (int64_t)(g * UB + u) * W;
+            if (i >= hi) continue;
+            if constexpr (BF16) stored[i] = narrow4(in[u]);
+            else stored[i] = in[u];
         }
     }
 }
@@ -786,29 +745,35 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     }
     constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.cgrid) {
-        const auto store_candidate = [&](const WinEntry& en) {
+        const uint32_t* first_of = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_FIRST) + s * BIG_MAX;
+        const uint32_t* next = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_NEXT);
+        const auto store_candidate = [&](const WinEntry& en, uint32_t heir) {
             if (en.row < 0) return;             // dropped within its step, or overwritten again later in the window
             vec16* slot = m.buf_x + en.row * m.row_vec;
             const vec16* fresh = batch_x_of(s) + (int64_t)en.src * m.row_vec * WIDE;
             if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-            if (__builtin_expect(en.chain < 0, 1)) {
+            if (__builtin_expect(heir == BW_NONE, 1)) {
                 Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
                 t.load(fresh, v_lo, v_hi);
                 t.store(slot, v_lo, v_hi);
                 return;
             }
-            bw_hand_off<U, W, BF16>(args, m.table, m.state, slot, fresh, (uint32_t)en.row, s, m.c, m.r, m.row_vec, v_lo, v_hi, first);
+            bw_hand_off<U, W, BF16>(args, next, m.state, slot, fresh, heir, en.label, m.w, m.r, m.row_vec, v_lo, v_hi, first);
         };
         // The grid covers cgrid candidate rows per step; when the plan has more (Bernoulli selection), a group goes on to
         // the entry cgrid further on.  (The first entry is asked for before the step's count is known: it is inside the
         // step's part of the table whatever the count.)
         int ee = e;
         WinEntry en = entry[s * rows + ee];
+        uint32_t heir = first_of[ee];
         const int count = (int)flags->count[s];
         while (ee < count) {
-            store_candidate(en);
+            store_candidate(en, heir);
             ee += m.cgrid;
-            if (ee < count) en = entry[s * rows + ee];
+            if (ee < count) {
+                en = entry[s * rows + ee];
+                heir = first_of[ee];
+            }
         }
         return;
     }
