@@ -31,9 +31,9 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # `bench.py --pmc-run`, each scaled by the reading of a plain copy of known size in the same run; the text summaries
 # with the exact commands are the files named here.  Not measured by this run: the line says where it is from.
 PROFILED_TRAFFIC = {
-    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75727346, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),   # algorithmic 77070336: slot losers are not moved, forwarded rows hit the cache
-    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19272954, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),          # algorithmic 19267584
-    ("C5-10000x1000-f32-2048-active50", "rb_bigwin_kernel"): (34017989, "profiles/rb_bigwin_kernel_C5_pmc_hbm_traffic.txt"),    # algorithmic 33554432
+    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75688192, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),   # algorithmic 77070336: slot losers are not moved, forwarded rows hit the cache
+    ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19274335, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),          # algorithmic 19267584
+    ("C5-10000x1000-f32-2048-active50", "rb_bigwin_kernel"): (34014628, "profiles/rb_bigwin_kernel_C5_pmc_hbm_traffic.txt"),    # algorithmic 33554432
 }
 
 MANY = 64           # steps handed to one rb_update_sample_many call
@@ -555,7 +555,7 @@ def main():
     ap.add_argument("--no-variants", action="store_true")
     ap.add_argument("--pmc-run", action="store_true",
                     help="short fixed sequence for `rocprofv3 --pmc`: 120 two-call steps, 120 single-call steps, 120 single-call steps with "
-                         "the next labels announced, 192 steps through announced rb_update_sample_many calls, then 3 plain copies "
+                         "the next labels announced, 320 steps through announced rb_update_sample_many calls, then 3 plain copies "
                          "of 256 MiB whose known traffic calibrates the counters; prints no JSON line")
     a = ap.parse_args()
     if a.gpus != 1:
@@ -577,7 +577,7 @@ def main():
         rig.enqueue(120)
         rig.enqueue(120, single_call=True)
         rig.enqueue(120, single_call=True, ahead=True)
-        rig.enqueue(192, many=64, ahead=True)
+        rig.enqueue(320, many=64, ahead=True)
         torch.cuda.synchronize()
         nbytes = 256 << 20
         src = torch.full((nbytes,), 7, dtype=torch.uint8, device="cuda:0")
