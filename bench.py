@@ -708,7 +708,16 @@ def main():
 
 
 def launch_sizes_of(calls, per_launch):
-    return [min(per_launch, n - at) for n in calls for at in range(0, n, per_launch)]
+    """Steps per launch of announced calls of these sizes: the library makes a call's launches as equal as it can."""
+    out = []
+    for n in calls:
+        left = n
+        while left > 0:
+            launches = -(-left // per_launch)
+            w = -(-left // launches)
+            out.append(w)
+            left -= w
+    return out
 
 
 def rounded(d):

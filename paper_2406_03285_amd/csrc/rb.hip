@@ -546,6 +546,15 @@ WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64
     return p;
 }
 
+// `left` steps go into launches of at most `cap` steps: the size of the first of them when they are made as equal
+// as possible (20 steps, 16 at most: 10 and 10, not 16 and 4 - a short launch hides little of the next window's plan).
+int64_t even_share(int64_t left, int64_t cap)
+{
+    if (left <= 0) return 0;
+    const int64_t launches = (left + cap - 1) / cap;
+    return (left + launches - 1) / launches;
+}
+
 // Whether rb_update_sample_many puts several steps of this shape into one launch, and how many at most: the option,
 // and what the planner's tables hold.  1: one launch (or two) per step.
 int64_t window_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
@@ -613,10 +622,11 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     while (at < n) {
         const int64_t next_at = at + w;
         nat = std::min(wmax, std::max(nat, grown(nat)));
-        int64_t next_w = std::min(nat, n - next_at);
+        // the next window: the steps that are left in equal parts rather than full windows and a short one
+        int64_t next_w = even_share(n - next_at, nat);
         // the last launch of the call plans the first steps of the call that was announced
         const bool ahead = next_w == 0 && ann_n > 0;
-        if (ahead) next_w = std::min(nat, ann_n);
+        if (ahead) next_w = even_share(ann_n, nat);
         WinPlanArgs next = {};
         if (ahead) next = window_plan_args(rb, ann_y, 0, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1);
         else if (next_w > 0) next = window_plan_args(rb, batch_y, next_at, next_w, b, c, r, seed, first_step, tbl ^ 1);
@@ -786,10 +796,10 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
     }
     while (at < n) {
         const int64_t next_at = at + w;
-        int64_t next_w = std::min(wmax, n - next_at);
+        int64_t next_w = even_share(n - next_at, wmax);
         // the last launch of the call plans the first steps of the call that was announced
         const bool ahead = next_w == 0 && ann_n > 0;
-        if (ahead) next_w = std::min(wmax, ann_n);
+        if (ahead) next_w = even_share(ann_n, wmax);
         BwMoveArgs m = {};
         for (int64_t k = 0; k < w; ++k) {
             m.batch_x[k] = static_cast<const vec16*>(batch_x[at + k]);
