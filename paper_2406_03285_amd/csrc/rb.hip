@@ -583,8 +583,18 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     // many half vectors, and two per thread measured best (8 and 8: 2.6 us against 2.7).
     const int unroll_option = rb->opt_unroll;
     if (unroll_option == 0) rb->opt_unroll = rb->storage == RB_STORE_BF16 ? 2 : 4;
-    const Shape sh = plan_shape(rb, wmax * (c + r), TPB);
+    Shape sh = plan_shape(rb, wmax * (c + r), TPB);
     rb->opt_unroll = unroll_option;
+    // ... and a third more tiles than that needs, i.e. tiles about three quarters full (most threads hold three vectors):
+    // the launch's workgroups come in more and shorter rounds.  Measured with 301 KB rows, 64 + 64 per step: 12.42 us per step
+    // with 25 to 28 tiles per row against 12.74 with the 19 that four vectors per thread need, 13.4 with 38; 602 KB rows,
+    // 8 + 8 per step: 3.06 with 38 to 46 against 3.07 with 37, 3.12 with 56.
+    if (unroll_option == 0 && sh.unroll == 4 && sh.tpr > 1) {
+        const int64_t nunits = (rb->row_vec + TILE_UNIT - 1) / TILE_UNIT;
+        sh.tpr = (int)((rb->row_vec + (int64_t)TPB * 3 - 1) / ((int64_t)TPB * 3));
+        sh.tile_vec = (int)(nunits / sh.tpr);
+        sh.tile_rem = (int)(nunits % sh.tpr);
+    }
     // Window sizes.  A launch of w steps should not have to wait for the plan of the next window, which the one
     // planner workgroup makes meanwhile; so the windows grow as fast as that allows, and the first one (planned
     // with nothing to hide behind) is the smallest from which they can grow.  Measured on MI355X: rows move at
