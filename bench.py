@@ -496,18 +496,23 @@ def reduced_precision_leg(torch, rb, wl, steps=1000):
 
 def eight_bit_leg(torch, rb, wl, steps=1000):
     """Workload C3 (float32 images with values in [0, 1)) with rows stored in 8 bits per element (Sec. VII): a quarter
-    of the buffer, 5/8 of the bytes per step.  Served by the general kernels: two launches per step in every call form."""
+    of the buffer, 5/8 of the bytes per step.  Several steps per launch through announced multi-step calls; a single
+    step is served by the general kernels (two launches)."""
     w = wl.C3
     rig = Rig(w, torch, rb, wl, store_dtype=torch.uint8)
     rig.enqueue(100, single_call=True)
+    rig.enqueue(MANY, many=MANY, ahead=True)
     torch.cuda.synchronize()
-    ms = rig.timed(steps, single_call=True)
+    n = max(MANY, steps // MANY * MANY)
+    ms = rig.timed(n, many=MANY, ahead=True)
+    ms_plain = rig.timed(steps, single_call=True)
     moved = (w.c + w.r) * (w.row_bytes + w.row_bytes // 4)
+    steps_per_launch = rig.buf.steps_per_launch(w.b, w.c, w.r)
     rig.close()
     return {"workload": w.name + " stored as u8", "ms_per_step": round(ms, 5), "aug_samples_per_s": round((w.b + w.r) / (ms * 1e-3), 1),
             "bytes_per_step": moved, "gb_per_s": round(moved / (ms * 1e-3) / 1e9, 1),
             "hbm_frac": round(moved / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "buffer_gb": round(w.buffer_bytes / 4 / 1e9, 1),
-            "launches_per_step": 2}
+            "steps_per_launch": steps_per_launch, "two_launches_per_step_ms": round(ms_plain, 5)}
 
 
 def variants_leg(w, torch, rb, wl, steps):

@@ -505,24 +505,33 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     return RB_OK;
 }
 
-template <bool NT, bool BF16, bool AUX>
+template <bool NT, int ST, bool AUX>
 hipError_t launch_window_u(const WinMoveArgs& m, const WinPlanArgs& next, int unroll, dim3 grid, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_window_kernel<1, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
-    case 2: rb_window_kernel<2, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
-    case 4: rb_window_kernel<4, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
-    default: rb_window_kernel<8, NT, BF16, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    case 1: rb_window_kernel<1, NT, ST, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    case 2: rb_window_kernel<2, NT, ST, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    case 4: rb_window_kernel<4, NT, ST, AUX><<<grid, TPB, 0, st>>>(m, next); break;
+    default:
+        if constexpr (ST == RB_STORE_U8) return hipErrorInvalidValue;    // (a lane holds four accesses per vector: at most four vectors)
+        else rb_window_kernel<8, NT, ST, AUX><<<grid, TPB, 0, st>>>(m, next);
+        break;
     }
     return hipGetLastError();
 }
 
 // aux: the replacement strategy keeps per-class state (FIFO, reservoir)
 template <bool NT>
-hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, bool bf16, bool aux, int unroll, dim3 grid, hipStream_t st)
+hipError_t launch_window(const WinMoveArgs& m, const WinPlanArgs& next, int storage, bool aux, int unroll, dim3 grid, hipStream_t st)
 {
-    if (bf16) return aux ? launch_window_u<NT, true, true>(m, next, unroll, grid, st) : launch_window_u<NT, true, false>(m, next, unroll, grid, st);
-    return aux ? launch_window_u<NT, false, true>(m, next, unroll, grid, st) : launch_window_u<NT, false, false>(m, next, unroll, grid, st);
+    switch (storage) {
+    case RB_STORE_BF16:
+        return aux ? launch_window_u<NT, RB_STORE_BF16, true>(m, next, unroll, grid, st) : launch_window_u<NT, RB_STORE_BF16, false>(m, next, unroll, grid, st);
+    case RB_STORE_U8:
+        return aux ? launch_window_u<NT, RB_STORE_U8, true>(m, next, unroll, grid, st) : launch_window_u<NT, RB_STORE_U8, false>(m, next, unroll, grid, st);
+    default:
+        return aux ? launch_window_u<NT, RB_STORE_SAME, true>(m, next, unroll, grid, st) : launch_window_u<NT, RB_STORE_SAME, false>(m, next, unroll, grid, st);
+    }
 }
 
 WinPlanArgs window_plan_args(rb_buffer* rb, const int64_t* const* batch_y, int64_t at, int64_t w, int64_t b, int64_t c, int64_t r,
@@ -560,7 +569,7 @@ int64_t even_share(int64_t left, int64_t cap)
 int64_t window_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
     const bool windowed = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && b <= 2048 && rb->opt_fuse &&
-                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT && rb->storage != RB_STORE_U8;
+                          rb->opt_window >= 2 && rb->selection == RB_SELECT_EXACT;
     if (!windowed) return 1;
     return std::max<int64_t>(1, std::min<int64_t>(std::min<int64_t>(WIN_MAX, rb->opt_window),
                                                   std::min<int64_t>(WIN_ENTRIES / (c + r), WIN_SLOTS / std::max(c, r))));
@@ -582,7 +591,9 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     // samples, 8 and 8: 3.9 against 4.1 and 4.1).  With binary32 samples stored as bfloat16 a thread holds twice as
     // many half vectors, and two per thread measured best (8 and 8: 2.6 us against 2.7).
     const int unroll_option = rb->opt_unroll;
-    if (unroll_option == 0) rb->opt_unroll = rb->storage == RB_STORE_BF16 ? 2 : 4;
+    // With 8-bit storage a thread holds four quarter vectors per vector of the tile (16 bytes of the sample each): one.
+    if (unroll_option == 0) rb->opt_unroll = rb->storage == RB_STORE_U8 ? 1 : rb->storage == RB_STORE_BF16 ? 2 : 4;
+    else if (rb->storage == RB_STORE_U8 && unroll_option > 4) rb->opt_unroll = 4;
     Shape sh = plan_shape(rb, wmax * (c + r), TPB);
     rb->opt_unroll = unroll_option;
     // ... and a third more tiles than that needs, i.e. tiles about three quarters full (most threads hold three vectors):
@@ -655,9 +666,9 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
         m.row_vec = rb->row_vec;
         m.tpr = sh.tpr; m.tile_vec = sh.tile_vec; m.tile_rem = sh.tile_rem;
         const dim3 grid((unsigned)(w * (c + r) * sh.tpr + (next_w > 0 ? 1 : 0)));
-        const bool bf16 = rb->storage == RB_STORE_BF16, aux = rb->eviction != RB_EVICT_UNIFORM;
-        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, bf16, aux, sh.unroll, grid, rb->stream)
-                                        : launch_window<false>(m, next, bf16, aux, sh.unroll, grid, rb->stream);
+        const bool aux = rb->eviction != RB_EVICT_UNIFORM;
+        const hipError_t e = rb->opt_nt ? launch_window<true>(m, next, rb->storage, aux, sh.unroll, grid, rb->stream)
+                                        : launch_window<false>(m, next, rb->storage, aux, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         if (ahead) {

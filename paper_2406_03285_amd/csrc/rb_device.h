@@ -189,6 +189,18 @@ __device__ __forceinline__ vec16 unpack4_u8(const uint32_t s)
 // bit 0: convert while loading, bit 1: while storing; bit 2: the narrow form is 8 bits per element instead of bfloat16
 enum { CV_NONE = 0, CV_NARROW = 1, CV_WIDEN = 2, CV_BOTH = 3, CV_Q8 = 4, CV_NARROW8 = CV_Q8 | CV_NARROW, CV_WIDEN8 = CV_Q8 | CV_WIDEN };
 
+// The Tile conversion of a mover whose stored rows have the form `storage` (RB_STORE_*); dir: CV_NARROW (a sample is
+// stored), CV_WIDEN (a stored sample is handed out), CV_BOTH (sample to sample through the stored form).  And the vectors
+// of a sample per vector of its stored row.
+constexpr int stored_cv(int storage, int dir)
+{
+    return storage == RB_STORE_U8 ? (CV_Q8 | dir) : storage == RB_STORE_BF16 ? dir : CV_NONE;
+}
+constexpr int stored_wide(int storage)
+{
+    return storage == RB_STORE_U8 ? 4 : storage == RB_STORE_BF16 ? 2 : 1;
+}
+
 // ---------------------------------------------------------------------------
 // Row mover: one tile of one row, U vectors per thread in flight.
 // ---------------------------------------------------------------------------

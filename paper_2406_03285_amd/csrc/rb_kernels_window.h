@@ -506,7 +506,8 @@ __global__ void __launch_bounds__(TPB) rb_window_plan_kernel(const WinPlanArgs a
 // stream frees the movers but the events that order the two streams cost more than
 // that gains.)
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool BF16, bool AUX>   // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors);
+template <int U, bool NT, int ST, bool AUX>      // ST: RB_STORE_*: binary32 samples are stored as they are, as bfloat16 or as 8-bit
+                                                 // codes (row_vec counts stored vectors);
                                                  // AUX: FIFO or reservoir replacement (the planner carries their per-class state)
 __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, const WinPlanArgs next)
 {
@@ -543,7 +544,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         m.state->last_n = head[m.w - 1].n;
         if (flags != 0) atomicOr(&m.state->flags, flags);
     }
-    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
+    constexpr int WIDE = stored_wide(ST);       // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.c) {
         if (en.row < 0) return;                 // dropped within its step, or overwritten again later in the window
         vec16* slot = m.buf_x + en.row * m.row_vec;
@@ -552,7 +553,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
             const WinEntry rq = entry[q];
             const int qs = q / rows, qj = q % rows - m.c;
             if (first) { m.out_y[qs][qj] = rq.label; count_moved(m.state); }
-            Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> old;
+            Tile<U, NT, TPB, WIN_PACE, stored_cv(ST, CV_WIDEN)> old;
             old.load(slot, v_lo, v_hi);
             old.store(m.out_x[qs] + (int64_t)qj * m.row_vec * WIDE, v_lo, v_hi);
             q = rq.chain;
@@ -561,7 +562,7 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
         // wavefront and overwritten by another: everybody has read before anybody overwrites.
         if (en.chain >= 0) __syncthreads();
         if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-        Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
+        Tile<U, NT, TPB, WIN_PACE, stored_cv(ST, CV_NARROW)> t;
         t.load(m.batch_x[s] + (int64_t)en.src * m.row_vec * WIDE, v_lo, v_hi);
         t.store(slot, v_lo, v_hi);
         return;
@@ -572,15 +573,15 @@ __global__ void __launch_bounds__(TPB) rb_window_kernel(const WinMoveArgs m, con
     if (en.label < 0) return;
     if (first) count_moved(m.state);
     vec16* dst = m.out_x[s] + (int64_t)j * m.row_vec * WIDE;
-    if (BF16 && en.src >= 0) {
-        // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
-        Tile<U, NT, TPB, WIN_PACE, CV_BOTH> t;
+    if (ST != RB_STORE_SAME && en.src >= 0) {
+        // taken from a mini-batch row of this launch: what the slot will hold is that row in its stored form
+        Tile<U, NT, TPB, WIN_PACE, stored_cv(ST, CV_BOTH)> t;
         t.load(m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = en.src >= 0 ? m.batch_x[en.src >> 16] + (int64_t)(en.src & 0xFFFF) * m.row_vec
                                        : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, TPB, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, TPB, WIN_PACE, stored_cv(ST, CV_WIDEN)> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }

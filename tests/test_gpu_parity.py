@@ -242,10 +242,29 @@ def test_8_bit_storage_decides_every_value_like_the_oracle(monkeypatch):
     assert len(torch.unique(buf.buf_x)) == 256                       # every byte value is in use
 
 
+def test_8_bit_storage_decides_every_value_like_the_oracle_with_several_steps_per_launch(monkeypatch):
+    """Few classes: most representatives of a launch come from mini-batch rows of the same launch (through the 8-bit code
+    the slot will hold) or are handed the slot's old content by the candidate that overwrites it."""
+    w = wl.variant(wl.C2, name="C2-u8-special-many", K=3, S=30, c=32, r=32, values="uniform")
+    monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _image_like_batch(ww, step, dev))
+    run_many_parity(w, 48, per_call=16, announce=True, store_u8=True)
+    run_many_parity(w, 40, per_call=19, store_u8=True, policy=POLICIES["exact-fifo"])
+
+
+@pytest.mark.parametrize("w,steps,per_call", [
+    (wl.variant(wl.C3, name="C3-u8-many", K=50, S=6), 96, 64),                                       # full-size rows, 32 steps per launch
+    (wl.variant(wl.C4, name="C4-u8-many", S=3, K=40, dtype="f32", shape=(3, 64, 64)), 60, 20),        # 64 + 64 rows per step, 8 steps per launch
+    (wl.variant(wl.C1, name="C1-u8-many-ragged", shape=(3, 20, 20), S=4), 70, 33),                    # 75 stored vectors per row
+], ids=["C3", "C4", "ragged"])
+def test_8_bit_storage_with_several_steps_per_launch(w, steps, per_call):
+    run_many_parity(w, steps, per_call=per_call, announce=True, store_u8=True)
+    run_many_parity(w, steps // 2, per_call=per_call, store_u8=True)
+
+
 @pytest.mark.parametrize("style", ["single", "ahead", "many", "many-announced", "fifo-bernoulli"])
 def test_8_bit_storage_through_every_call_form(style):
-    """The 8-bit form is served by the general kernels only: announcements and multi-step calls fall back to them, the
-    bytes are the oracle's in every call form."""
+    """The 8-bit form is served by the general kernels and by the several-steps launch for small counts: announced single
+    steps and the large-count forms fall back to the general kernels; the bytes are the oracle's in every call form."""
     w = wl.variant(wl.C4, name=f"C4-u8-{style}", S=8, shape=(3, 32, 32), dtype="f32", b=128, c=40, r=40)
     if style == "single":
         run_parity(w, steps=40, store_u8=True, single_call=True)
@@ -270,7 +289,8 @@ def test_8_bit_storage_argument_checks():
     rc, h = rb.rb_create(4, 2, (16,), rb.RB_F32)
     assert rb.rb_set_storage(h, 3) == rb.RB_EINVAL
     assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_OK and rb.rb_query_sizes(h)[1] == 4 * 2 * 16
-    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 1)    # the several-steps launches do not serve it
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)   # the several-steps launch for small counts serves it
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 1)  # ... the one for large counts does not
     rb.rb_destroy(h)
 
 
