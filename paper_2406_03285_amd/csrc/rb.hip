@@ -254,16 +254,29 @@ Seed make_seed(uint64_t seed, uint64_t step)
     return s;
 }
 
-template <bool NT, bool BF16>
-hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
+template <bool NT, int ST>
+hipError_t launch_planned_s(const MoveArgs& m, const PlanArgs& next, int unroll, dim3 grid, size_t lds, hipStream_t st)
 {
     switch (unroll) {
-    case 1: rb_step_planned_kernel<1, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    case 2: rb_step_planned_kernel<2, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    case 4: rb_step_planned_kernel<4, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
-    default: rb_step_planned_kernel<8, NT, BF16><<<grid, TPB, lds, st>>>(m, next); break;
+    case 1: rb_step_planned_kernel<1, NT, ST><<<grid, TPB, lds, st>>>(m, next); break;
+    case 2: rb_step_planned_kernel<2, NT, ST><<<grid, TPB, lds, st>>>(m, next); break;
+    case 4: rb_step_planned_kernel<4, NT, ST><<<grid, TPB, lds, st>>>(m, next); break;
+    default:
+        if constexpr (ST == RB_STORE_U8) return hipErrorInvalidValue;    // (at most four vectors per lane: step_planned)
+        else rb_step_planned_kernel<8, NT, ST><<<grid, TPB, lds, st>>>(m, next);
+        break;
     }
     return hipGetLastError();
+}
+
+template <bool NT>
+hipError_t launch_planned(const MoveArgs& m, const PlanArgs& next, int storage, int unroll, dim3 grid, size_t lds, hipStream_t st)
+{
+    switch (storage) {
+    case RB_STORE_BF16: return launch_planned_s<NT, RB_STORE_BF16>(m, next, unroll, grid, lds, st);
+    case RB_STORE_U8: return launch_planned_s<NT, RB_STORE_U8>(m, next, unroll, grid, lds, st);
+    default: return launch_planned_s<NT, RB_STORE_SAME>(m, next, unroll, grid, lds, st);
+    }
 }
 
 // Called by every entry point other than rb_update_sample.  A step that was planned ahead will not
@@ -330,7 +343,13 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         plan_enqueued(rb, batch_y, b, c, r, seed, step);
     }
-    const Shape sh = plan_shape(rb, c + r, TPB);
+    Shape sh = plan_shape(rb, c + r, TPB);
+    if (rb->storage == RB_STORE_U8 && sh.unroll > 4) {         // a lane holds four accesses per vector: at most four vectors
+        const int unroll_option = rb->opt_unroll;
+        rb->opt_unroll = 4;
+        sh = plan_shape(rb, c + r, TPB);
+        rb->opt_unroll = unroll_option;
+    }
     MoveArgs m;
     m.batch_x = static_cast<const vec16*>(batch_x);
     m.buf_x = static_cast<vec16*>(rb->buf_x);
@@ -350,12 +369,8 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
     if (next_y) next = make_plan(rb, next_y, b, c, r, seed, step + 1);
     const dim3 grid((unsigned)(movers + m.plan_next));
     const size_t lds = next_y ? (size_t)b * 8 : 0;
-    const bool bf16 = rb->storage == RB_STORE_BF16;
-    hipError_t e;
-    if (rb->opt_nt) e = bf16 ? launch_planned<true, true>(m, next, sh.unroll, grid, lds, rb->stream)
-                             : launch_planned<true, false>(m, next, sh.unroll, grid, lds, rb->stream);
-    else e = bf16 ? launch_planned<false, true>(m, next, sh.unroll, grid, lds, rb->stream)
-                  : launch_planned<false, false>(m, next, sh.unroll, grid, lds, rb->stream);
+    const hipError_t e = rb->opt_nt ? launch_planned<true>(m, next, rb->storage, sh.unroll, grid, lds, rb->stream)
+                                    : launch_planned<false>(m, next, rb->storage, sh.unroll, grid, lds, rb->stream);
     if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
@@ -687,29 +702,43 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     return RB_OK;
 }
 
-template <int U, int W, bool NT, bool BF16>
+template <int U, int W, bool NT, int ST>
 hipError_t launch_bigwin_u(const BwMoveArgs& m, const BwPlanArgs& next, dim3 grid, hipStream_t st)
 {
-    const size_t lds = next.w > 0 ? BIG_LDS_BYTES : 0;
-    if (lds != 0) {
-        const hipError_t e = allow_big_lds<&rb_bigwin_kernel<U, W, NT, BF16>>();
-        if (e != hipSuccess) return e;
+    if constexpr (ST == RB_STORE_U8 && U > 2) {
+        return hipErrorInvalidValue;           // (a lane holds four accesses per vector, and these workgroups have 128 registers per lane: bigwin_shape)
+    } else {
+        const size_t lds = next.w > 0 ? BIG_LDS_BYTES : 0;
+        if (lds != 0) {
+            const hipError_t e = allow_big_lds<&rb_bigwin_kernel<U, W, NT, ST>>();
+            if (e != hipSuccess) return e;
+        }
+        rb_bigwin_kernel<U, W, NT, ST><<<grid, BIG_TPB, lds, st>>>(m, next);
+        return hipGetLastError();
     }
-    rb_bigwin_kernel<U, W, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next);
-    return hipGetLastError();
 }
 
 // width: threads per tile (bigwin_width), unroll: vectors per thread
-template <bool NT, bool BF16>
-hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int width, int unroll, dim3 grid, hipStream_t st)
+template <bool NT, int ST>
+hipError_t launch_bigwin_s(const BwMoveArgs& m, const BwPlanArgs& next, int width, int unroll, dim3 grid, hipStream_t st)
 {
-    if (width == WAVE) return unroll == 2 ? launch_bigwin_u<2, WAVE, NT, BF16>(m, next, grid, st) : launch_bigwin_u<8, WAVE, NT, BF16>(m, next, grid, st);
-    if (width == 2 * WAVE) return launch_bigwin_u<8, 2 * WAVE, NT, BF16>(m, next, grid, st);
+    if (width == WAVE) return unroll == 2 ? launch_bigwin_u<2, WAVE, NT, ST>(m, next, grid, st) : launch_bigwin_u<8, WAVE, NT, ST>(m, next, grid, st);
+    if (width == 2 * WAVE) return launch_bigwin_u<8, 2 * WAVE, NT, ST>(m, next, grid, st);
     switch (unroll) {
-    case 1: return launch_bigwin_u<1, TPB, NT, BF16>(m, next, grid, st);
-    case 2: return launch_bigwin_u<2, TPB, NT, BF16>(m, next, grid, st);
-    case 4: return launch_bigwin_u<4, TPB, NT, BF16>(m, next, grid, st);
-    default: return launch_bigwin_u<8, TPB, NT, BF16>(m, next, grid, st);
+    case 1: return launch_bigwin_u<1, TPB, NT, ST>(m, next, grid, st);
+    case 2: return launch_bigwin_u<2, TPB, NT, ST>(m, next, grid, st);
+    case 4: return launch_bigwin_u<4, TPB, NT, ST>(m, next, grid, st);
+    default: return launch_bigwin_u<8, TPB, NT, ST>(m, next, grid, st);
+    }
+}
+
+template <bool NT>
+hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int storage, int width, int unroll, dim3 grid, hipStream_t st)
+{
+    switch (storage) {
+    case RB_STORE_BF16: return launch_bigwin_s<NT, RB_STORE_BF16>(m, next, width, unroll, grid, st);
+    case RB_STORE_U8: return launch_bigwin_s<NT, RB_STORE_U8>(m, next, width, unroll, grid, st);
+    default: return launch_bigwin_s<NT, RB_STORE_SAME>(m, next, width, unroll, grid, st);
     }
 }
 
@@ -719,8 +748,18 @@ hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int width,
 Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
 {
     width = TPB;
-    if (rb->opt_unroll == 0 && rb->row_vec <= 2 * WAVE * 8) width = rb->row_vec <= WAVE * 8 ? WAVE : 2 * WAVE;
-    if (width == TPB) return plan_shape(rb, rows, TPB);
+    const bool q8 = rb->storage == RB_STORE_U8;        // at most two vectors per lane: a wavefront per row up to 128 vectors
+    if (rb->opt_unroll == 0 && rb->row_vec <= (q8 ? WAVE * 2 : 2 * WAVE * 8)) width = rb->row_vec <= WAVE * 8 ? WAVE : 2 * WAVE;
+    if (width == TPB) {
+        const int unroll_option = rb->opt_unroll;
+        Shape s = plan_shape(rb, rows, TPB);
+        if (q8 && s.unroll > 2) {
+            rb->opt_unroll = 2;
+            s = plan_shape(rb, rows, TPB);
+            rb->opt_unroll = unroll_option;
+        }
+        return s;
+    }
     Shape s;
     s.unroll = width == WAVE && rb->row_vec <= WAVE * 2 ? 2 : 8;
     s.tpr = 1;
@@ -736,7 +775,7 @@ Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
 // many at most (1: it does not).  Shapes that the small form takes (window_limit) are not meant.
 int64_t bigwin_limit(const rb_buffer* rb, int64_t b, int64_t c, int64_t r)
 {
-    const bool eligible = rb->storage != RB_STORE_U8 && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
+    const bool eligible = c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
                           rb->K <= BIG_CLASSES && rb->opt_fuse &&
                           rb->opt_window >= 2 && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) && rb->K * rb->S <= INT64_C(0x7FFFFFFF) &&
                           rb->S <= INT32_MAX - (int64_t)BW_MAX * RB_MAX_BATCH;
@@ -842,12 +881,8 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
         const int64_t items = w * (cgrid + r) * sh.tpr;
         const int64_t per_block = BIG_TPB / width;
         const dim3 grid((unsigned)((items + per_block - 1) / per_block + 2 * next_w));
-        const bool bf16 = rb->storage == RB_STORE_BF16;
-        hipError_t e;
-        if (rb->opt_nt) e = bf16 ? launch_bigwin<true, true>(m, next, width, sh.unroll, grid, rb->stream)
-                                 : launch_bigwin<true, false>(m, next, width, sh.unroll, grid, rb->stream);
-        else e = bf16 ? launch_bigwin<false, true>(m, next, width, sh.unroll, grid, rb->stream)
-                      : launch_bigwin<false, false>(m, next, width, sh.unroll, grid, rb->stream);
+        const hipError_t e = rb->opt_nt ? launch_bigwin<true>(m, next, rb->storage, width, sh.unroll, grid, rb->stream)
+                                        : launch_bigwin<false>(m, next, rb->storage, width, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
         if (ahead) {
@@ -1160,7 +1195,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
 
     // the plan-ahead form covers both storage forms; the kernel that plans and moves in one launch only the plain one
     const bool plannable = c >= 1 && c <= WAVE && r >= 1 && r <= WAVE && rb->nchunks <= DIRECT_CHUNKS && rb->opt_fuse &&
-                           rb->selection == RB_SELECT_EXACT && rb->storage != RB_STORE_U8;
+                           rb->selection == RB_SELECT_EXACT;
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
     // larger counts have a plan-ahead form of their own
     // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)

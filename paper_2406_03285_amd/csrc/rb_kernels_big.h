@@ -450,7 +450,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_big_plan_kernel(const PlanArgs a, 
 // row (candidates first, then representatives); with plan_next the first
 // workgroup of the grid plans the next step instead.
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+template <int U, bool NT, int ST>           // ST: RB_STORE_*, the form binary32 samples are stored in (row_vec counts stored vectors)
 __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, const PlanArgs next, const uint32_t* fwd, uint32_t* fwd_next)
 {
     extern __shared__ uint32_t lds[];
@@ -476,7 +476,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
         m.state->last_n = hh.n;
         if (hh.flags != 0) atomicOr(&m.state->flags, hh.flags);
     }
-    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
+    constexpr int WIDE = stored_wide(ST);         // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.cgrid) {
         // the grid covers cgrid candidate rows; when the plan has more (Bernoulli selection: their number is random),
         // a group goes on to the entry cgrid further on
@@ -485,7 +485,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
             const PlanEntry en = entry[ee];
             if (en.row < 0) continue;           // label outside [0, K), or a later class-mate takes the slot
             if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-            Tile<U, NT, BIG_GROUP, true, BF16 ? CV_NARROW : CV_NONE> t;
+            Tile<U, NT, BIG_GROUP, true, stored_cv(ST, CV_NARROW)> t;
             t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
             t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
         }
@@ -499,14 +499,14 @@ __global__ void __launch_bounds__(BIG_TPB) rb_step_big_kernel(const MoveArgs m, 
     // written in this very step?  Then the stored candidate's mini-batch row is what the slot will hold.
     const int pos = en.pos == BIG_LOOK_UP ? big_forwarded(fwd, (uint32_t)en.row) : -1;
     vec16* dst = m.out_x + (int64_t)j * m.row_vec * WIDE;
-    if (BF16 && pos >= 0) {
-        // forwarded from the mini-batch: what the slot will hold is the row rounded to bfloat16
-        Tile<U, NT, BIG_GROUP, true, CV_BOTH> t;
+    if (ST != RB_STORE_SAME && pos >= 0) {
+        // forwarded from the mini-batch: what the slot will hold is the row in its stored form
+        Tile<U, NT, BIG_GROUP, true, stored_cv(ST, CV_BOTH)> t;
         t.load(m.batch_x + (int64_t)pos * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = pos >= 0 ? m.batch_x + (int64_t)pos * m.row_vec : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, BIG_GROUP, true, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, BIG_GROUP, true, stored_cv(ST, CV_WIDEN)> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }

@@ -641,14 +641,15 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_plan_kernel(const BwPlanArg
 // window still need: the members of the list that starts with `heir` (their sampling planners put them there).  Every
 // lane copies its own vectors out to them and only then overwrites these same vectors, so no lane waits for another.
 // args: the calling kernel's argument segment, which BwMoveArgs starts (bw_step_pointer).
-template <int U, int W, bool BF16>
+template <int U, int W, int ST>
 __device__ __forceinline__ void bw_hand_off(BwArgBytes args, const uint32_t* next, DevState* state, vec16* slot, const vec16* fresh,
                                             uint32_t heir, int32_t label, int w, int r, int64_t row_vec, int64_t v_lo, int64_t v_hi, bool first)
 {
-    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of an output row per vector of a stored row
+    constexpr int WIDE = stored_wide(ST);       // vectors of an output row per vector of a stored row
     constexpr int UB = U > 4 ? 4 : U;           // a lane's vectors go in batches of that many (registers)
     constexpr int PART = WIDE * U / UB;
-    typedef typename std::conditional<BF16, vec8, vec16>::type Stored;
+    // what a lane holds of the stored row per vector of the sample: the vector itself, half of one (four bfloat16), a quarter (four bytes)
+    typedef typename std::conditional<ST == RB_STORE_U8, uint32_t, typename std::conditional<ST == RB_STORE_BF16, vec8, vec16>::type>::type Stored;
     const int lane = threadIdx.x & (W - 1);
     Stored* stored = reinterpret_cast<Stored*>(slot);
     const int64_t lo = WIDE * v_lo, hi = WIDE * v_hi;       // in vectors of the output rows
@@ -680,7 +681,8 @@ __device__ __forceinline__ void bw_hand_off(BwArgBytes args, const uint32_t* nex
             for (int u = 0; u < UB; ++u) {
                 const int64_t i = lo + lane + (int64_t)(g * UB + u) * W;
                 if (i >= hi) continue;
-                if constexpr (BF16) out[i] = widen4(old[u]);
+                if constexpr (ST == RB_STORE_U8) out[i] = unpack4_u8(old[u]);
+                else if constexpr (ST == RB_STORE_BF16) out[i] = widen4(old[u]);
                 else out[i] = old[u];
             }
             member = after;
@@ -689,7 +691,8 @@ __device__ __forceinline__ void bw_hand_off(BwArgBytes args, const uint32_t* nex
         for (int u = 0; u < UB; ++u) {
             const int64_t i = lo + lane + (int64_t)(g * UB + u) * W;
             if (i >= hi) continue;
-            if constexpr (BF16) stored[i] = narrow4(in[u]);
+            if constexpr (ST == RB_STORE_U8) stored[i] = pack4_u8(in[u]);
+            else if constexpr (ST == RB_STORE_BF16) stored[i] = narrow4(in[u]);
             else stored[i] = in[u];
         }
     }
@@ -699,9 +702,9 @@ __device__ __forceinline__ void bw_hand_off(BwArgBytes args, const uint32_t* nex
 // All steps of one window by its table: every group of BIG_GROUP threads moves one tile of one row; the
 // first 2 next.w workgroups plan the next window instead.
 // ---------------------------------------------------------------------------
-template <int U, int W, bool NT, bool BF16>   // W: threads that move one tile together (short rows: one wavefront, which then has the
+template <int U, int W, bool NT, int ST>      // W: threads that move one tile together (short rows: one wavefront, which then has the
                                               // most bytes in flight; a compute unit holds a fixed number of wavefronts, not of bytes);
-                                              // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+                                              // ST: RB_STORE_*, the form binary32 samples are stored in (row_vec counts stored vectors)
 __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, const BwPlanArgs next)
 {
     extern __shared__ uint32_t lds[];
@@ -743,7 +746,7 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
         m.state->last_n = head[m.w - 1].n;
         if (raised != 0) atomicOr(&m.state->flags, raised);
     }
-    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
+    constexpr int WIDE = stored_wide(ST);         // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.cgrid) {
         const uint32_t* first_of = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_FIRST) + s * BIG_MAX;
         const uint32_t* next = reinterpret_cast<const uint32_t*>(m.table + BW_OFF_NEXT);
@@ -753,12 +756,12 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
             const vec16* fresh = batch_x_of(s) + (int64_t)en.src * m.row_vec * WIDE;
             if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
             if (__builtin_expect(heir == BW_NONE, 1)) {
-                Tile<U, NT, W, WIN_PACE, BF16 ? CV_NARROW : CV_NONE> t;
+                Tile<U, NT, W, WIN_PACE, stored_cv(ST, CV_NARROW)> t;
                 t.load(fresh, v_lo, v_hi);
                 t.store(slot, v_lo, v_hi);
                 return;
             }
-            bw_hand_off<U, W, BF16>(args, next, m.state, slot, fresh, heir, en.label, m.w, m.r, m.row_vec, v_lo, v_hi, first);
+            bw_hand_off<U, W, ST>(args, next, m.state, slot, fresh, heir, en.label, m.w, m.r, m.row_vec, v_lo, v_hi, first);
         };
         // The grid covers cgrid candidate rows per step; when the plan has more (Bernoulli selection), a group goes on to
         // the entry cgrid further on.  (The first entry is asked for before the step's count is known: it is inside the
@@ -784,15 +787,15 @@ __global__ void __launch_bounds__(BIG_TPB) rb_bigwin_kernel(const BwMoveArgs m, 
     if (en.label < 0) return;
     if (first) count_moved(m.state);
     vec16* dst = out_x_of(s) + (int64_t)j * m.row_vec * WIDE;
-    if (BF16 && en.src >= 0) {
-        // taken from a mini-batch row of this launch: what the slot will hold is that row rounded to bfloat16
-        Tile<U, NT, W, WIN_PACE, CV_BOTH> t;
+    if (ST != RB_STORE_SAME && en.src >= 0) {
+        // taken from a mini-batch row of this launch: what the slot will hold is that row in its stored form
+        Tile<U, NT, W, WIN_PACE, stored_cv(ST, CV_BOTH)> t;
         t.load(batch_x_of(en.src >> 16) + (int64_t)(en.src & 0xFFFF) * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = en.src >= 0 ? batch_x_of(en.src >> 16) + (int64_t)(en.src & 0xFFFF) * m.row_vec
                                        : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, W, WIN_PACE, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, W, WIN_PACE, stored_cv(ST, CV_WIDEN)> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }

@@ -316,7 +316,7 @@ __global__ void __launch_bounds__(TPB) rb_plan_kernel(const PlanArgs a)
 // first, then representatives); with plan_next the first workgroup of the grid
 // plans the next step instead.
 // ---------------------------------------------------------------------------
-template <int U, bool NT, bool BF16>        // BF16: binary32 samples are stored as bfloat16 (row_vec counts stored vectors)
+template <int U, bool NT, int ST>           // ST: RB_STORE_*, the form binary32 samples are stored in (row_vec counts stored vectors)
 __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, const PlanArgs next)
 {
     extern __shared__ uint32_t lds[];
@@ -349,11 +349,11 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
         m.state->last_n = h.n;
         if (h.flags != 0) atomicOr(&m.state->flags, h.flags);
     }
-    constexpr int WIDE = BF16 ? 2 : 1;          // vectors of a mini-batch / output row per vector of a stored row
+    constexpr int WIDE = stored_wide(ST);         // vectors of a mini-batch / output row per vector of a stored row
     if (e < m.c) {
         if (en.row < 0) return;                 // label outside [0, K), or a later class-mate takes the slot
         if (first) { m.buf_y[en.row] = en.label; count_moved(m.state); }
-        Tile<U, NT, TPB, true, BF16 ? CV_NARROW : CV_NONE> t;
+        Tile<U, NT, TPB, true, stored_cv(ST, CV_NARROW)> t;
         t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
         t.store(m.buf_x + en.row * m.row_vec, v_lo, v_hi);
         return;
@@ -363,14 +363,14 @@ __global__ void __launch_bounds__(TPB) rb_step_planned_kernel(const MoveArgs m, 
     if (en.label < 0) return;
     if (first) count_moved(m.state);
     vec16* dst = m.out_x + (int64_t)j * m.row_vec * WIDE;
-    if (BF16 && en.pos >= 0) {
-        // forwarded from the mini-batch: what the slot will hold is the row rounded to bfloat16
-        Tile<U, NT, TPB, true, CV_BOTH> t;
+    if (ST != RB_STORE_SAME && en.pos >= 0) {
+        // forwarded from the mini-batch: what the slot will hold is the row in its stored form
+        Tile<U, NT, TPB, true, stored_cv(ST, CV_BOTH)> t;
         t.load(m.batch_x + (int64_t)en.pos * m.row_vec * WIDE, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     } else {
         const vec16* src = en.pos >= 0 ? m.batch_x + (int64_t)en.pos * m.row_vec : m.buf_x + en.row * m.row_vec;
-        Tile<U, NT, TPB, true, BF16 ? CV_WIDEN : CV_NONE> t;
+        Tile<U, NT, TPB, true, stored_cv(ST, CV_WIDEN)> t;
         t.load(src, v_lo, v_hi);
         t.store(dst, v_lo, v_hi);
     }

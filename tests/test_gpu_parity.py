@@ -261,10 +261,29 @@ def test_8_bit_storage_with_several_steps_per_launch(w, steps, per_call):
     run_many_parity(w, steps // 2, per_call=per_call, store_u8=True)
 
 
+@pytest.mark.parametrize("w,policy", [
+    (wl.variant(wl.C5, name="bw-u8-two-classes", K=2, S=40, shape=(64,), b=256, c=100, r=70), None),                # 4 stored vectors per row; every step reads and rewrites most slots
+    (wl.variant(wl.C5, name="bw-u8-K300-fifo", K=300, S=12, shape=(272,), b=512, c=200, r=150), "exact-fifo"),        # 17 stored vectors: ragged
+    (wl.variant(wl.C5, name="bw-u8-long-rows", K=6, S=30, shape=(3, 64, 64), b=256, c=100, r=70), None),              # 768 stored vectors: tiles for 256 threads
+    (wl.variant(wl.C5, name="bw-u8-bernoulli-reservoir", K=2, S=40, shape=(64,), b=256, c=100, r=70), "bernoulli-reservoir"),
+    (wl.variant(wl.C5, name="bw-u8-C5-rows", K=40, S=30, b=1024, c=300, r=300), None),                               # C5's rows: one wavefront per 2 KiB stored row
+], ids=lambda v: v.name if hasattr(v, "name") else None)
+def test_8_bit_storage_with_large_counts(w, policy):
+    pol = POLICIES[policy] if policy else None
+    run_many_parity(w, 40, per_call=19, policy=pol, store_u8=True)
+    run_many_parity(w, 40, per_call=16, announce=True, policy=pol, store_u8=True)
+
+
+def test_8_bit_storage_decides_every_value_like_the_oracle_with_large_counts(monkeypatch):
+    w = wl.variant(wl.C5, name="bw-u8-special", K=3, S=60, shape=(3, 32, 32), b=256, c=100, r=100, values="uniform")
+    monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _image_like_batch(ww, step, dev))
+    run_many_parity(w, 40, per_call=16, announce=True, store_u8=True)
+
+
 @pytest.mark.parametrize("style", ["single", "ahead", "many", "many-announced", "fifo-bernoulli"])
 def test_8_bit_storage_through_every_call_form(style):
-    """The 8-bit form is served by the general kernels and by the several-steps launch for small counts: announced single
-    steps and the large-count forms fall back to the general kernels; the bytes are the oracle's in every call form."""
+    """The 8-bit form is served by the general kernels, by the plan-ahead step for small counts and by both several-steps
+    launches; the bytes are the oracle's in every call form."""
     w = wl.variant(wl.C4, name=f"C4-u8-{style}", S=8, shape=(3, 32, 32), dtype="f32", b=128, c=40, r=40)
     if style == "single":
         run_parity(w, steps=40, store_u8=True, single_call=True)
@@ -290,7 +309,7 @@ def test_8_bit_storage_argument_checks():
     assert rb.rb_set_storage(h, 3) == rb.RB_EINVAL
     assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_OK and rb.rb_query_sizes(h)[1] == 4 * 2 * 16
     assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)   # the several-steps launch for small counts serves it
-    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 1)  # ... the one for large counts does not
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 16)  # ... and so does the one for large counts
     rb.rb_destroy(h)
 
 
