@@ -107,9 +107,9 @@ int rb_bind(rb_buffer *rb, void *buf_x, int64_t *buf_y, void *workspace, void *h
  * gives 255 - and handed out as byte / 255 (binary32 division, correctly
  * rounded): a quarter of the memory, an absolute error of at most 1/510 for
  * values in [0, 1].  The sample's byte size must be a multiple of 64.  Served
- * by the general kernels, by the plan-ahead form of the single launch for up
- * to 64 candidates and representatives, and by the several-steps launches of
- * rb_update_sample_many; every call form gives the same bytes.
+ * by the general kernels, by the plan-ahead forms of the single launch and by
+ * the several-steps launches of rb_update_sample_many; every call form gives
+ * the same bytes.
  */
 enum rb_storage { RB_STORE_SAME = 0, RB_STORE_BF16 = 1, RB_STORE_U8 = 2 };
 int rb_set_storage(rb_buffer *rb, int32_t storage);

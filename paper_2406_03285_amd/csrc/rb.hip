@@ -393,35 +393,48 @@ hipError_t allow_big_lds()
     return hipSuccess;
 }
 
-template <int U, bool NT, bool BF16>
+template <int U, bool NT, int ST>
 hipError_t launch_big_u(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, dim3 grid, hipStream_t st)
 {
-    const size_t lds = m.plan_next ? BIG_LDS_BYTES : 0;
-    if (lds != 0) {
-        const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT, BF16>>();
-        if (e != hipSuccess) return e;
+    // (the converting movers have to fit the 128 registers per lane of a 1024-thread workgroup: big_shape)
+    if constexpr ((ST == RB_STORE_U8 && U > 2) || (ST == RB_STORE_BF16 && U > 8)) {
+        return hipErrorInvalidValue;
+    } else {
+        const size_t lds = m.plan_next ? BIG_LDS_BYTES : 0;
+        if (lds != 0) {
+            const hipError_t e = allow_big_lds<&rb_step_big_kernel<U, NT, ST>>();
+            if (e != hipSuccess) return e;
+        }
+        rb_step_big_kernel<U, NT, ST><<<grid, BIG_TPB, lds, st>>>(m, next, fwd, fwd_next);
+        return hipGetLastError();
     }
-    rb_step_big_kernel<U, NT, BF16><<<grid, BIG_TPB, lds, st>>>(m, next, fwd, fwd_next);
-    return hipGetLastError();
 }
 
-template <bool NT, bool BF16>
-hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, int unroll, dim3 grid,
-                      hipStream_t st)
+template <bool NT, int ST>
+hipError_t launch_big_s(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, int unroll, dim3 grid,
+                        hipStream_t st)
 {
     switch (unroll) {
-    case 1: return launch_big_u<1, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    case 2: return launch_big_u<2, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    case 4: return launch_big_u<4, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    case 6: return launch_big_u<6, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    case 8: return launch_big_u<8, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-    default: break;
+    case 1: return launch_big_u<1, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 2: return launch_big_u<2, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 4: return launch_big_u<4, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 6: return launch_big_u<6, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 8: return launch_big_u<8, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 10: return launch_big_u<10, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    case 12: return launch_big_u<12, NT, ST>(m, next, fwd, fwd_next, grid, st);
+    default: return hipErrorInvalidValue;
     }
-    if constexpr (!BF16) {          // (the converting mover would not fit the registers of a 1024-thread workgroup)
-        if (unroll == 10) return launch_big_u<10, NT, BF16>(m, next, fwd, fwd_next, grid, st);
-        if (unroll == 12) return launch_big_u<12, NT, BF16>(m, next, fwd, fwd_next, grid, st);
+}
+
+template <bool NT>
+hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* fwd, uint32_t* fwd_next, int storage, int unroll,
+                      dim3 grid, hipStream_t st)
+{
+    switch (storage) {
+    case RB_STORE_BF16: return launch_big_s<NT, RB_STORE_BF16>(m, next, fwd, fwd_next, unroll, grid, st);
+    case RB_STORE_U8: return launch_big_s<NT, RB_STORE_U8>(m, next, fwd, fwd_next, unroll, grid, st);
+    default: return launch_big_s<NT, RB_STORE_SAME>(m, next, fwd, fwd_next, unroll, grid, st);
     }
-    return hipErrorInvalidValue;
 }
 
 // Tiles of the large-count launch.  Its workgroups hold four groups of movers each, and a compute unit holds one such
@@ -436,9 +449,18 @@ hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* f
 // the second round of workgroups start as the first ones end); for many short rows a wavefront per row, sixteen
 // rows per workgroup, so that one round suffices (10000 classes, 1024 + 1024 rows of 8 KiB: no change, the step is
 // bound by the planners and the launch itself).
-Shape big_shape(const rb_buffer* rb, int64_t rows, int planners)
+Shape big_shape(rb_buffer* rb, int64_t rows, int planners)
 {
     Shape s = plan_shape(rb, rows, BIG_GROUP);
+    if (rb->storage == RB_STORE_U8) {           // a lane holds four accesses per vector: at most two vectors
+        if (s.unroll > 2) {
+            const int unroll_option = rb->opt_unroll;
+            rb->opt_unroll = 2;
+            s = plan_shape(rb, rows, BIG_GROUP);
+            rb->opt_unroll = unroll_option;
+        }
+        return s;
+    }
     if (rb->opt_unroll != 0) return s;
     constexpr int64_t CUS = 256;
     const int64_t nunits = (rb->row_vec + TILE_UNIT - 1) / TILE_UNIT;
@@ -508,12 +530,8 @@ int step_big(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int64_t
     const uint32_t* fwd = reinterpret_cast<const uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_planned]);
     uint32_t* fwd_next = reinterpret_cast<uint32_t*>(rb->ws + rb->off_bfwd[rb->tbl_next]);
     const dim3 grid((unsigned)((items + BIG_GROUPS - 1) / BIG_GROUPS + 2 * m.plan_next));
-    const bool bf16 = rb->storage == RB_STORE_BF16;
-    hipError_t e;
-    if (rb->opt_nt) e = bf16 ? launch_big<true, true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
-                             : launch_big<true, false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
-    else e = bf16 ? launch_big<false, true>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream)
-                  : launch_big<false, false>(m, next, fwd, fwd_next, sh.unroll, grid, rb->stream);
+    const hipError_t e = rb->opt_nt ? launch_big<true>(m, next, fwd, fwd_next, rb->storage, sh.unroll, grid, rb->stream)
+                                    : launch_big<false>(m, next, fwd, fwd_next, rb->storage, sh.unroll, grid, rb->stream);
     if (e == hipSuccess && next_y) plan_enqueued(rb, next_y, b, c, r, seed, step + 1);
     if (e != hipSuccess) return RB_EHIP;
     rb->updates += 1;
@@ -1199,7 +1217,7 @@ int rb_update_sample(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
     const bool fused = plannable && rb->storage == RB_STORE_SAME && rb->eviction == RB_EVICT_UNIFORM;
     // larger counts have a plan-ahead form of their own
     // (with the Bernoulli selection, whose number of candidates is only bounded by b, for mini-batches of at most BIG_MAX)
-    const bool big = !plannable && rb->storage != RB_STORE_U8 && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
+    const bool big = !plannable && c >= 1 && c <= BIG_MAX && r >= 1 && r <= BIG_MAX && b <= BIG_BATCH &&
                      rb->K <= BIG_CLASSES && rb->opt_fuse && (rb->selection == RB_SELECT_EXACT || b <= BIG_MAX) &&
                      rb->K * rb->S <= INT64_C(0x7FFFFFFF) && rb->S <= INT32_MAX - RB_MAX_BATCH;
     const int64_t* next_y = rb->next_y;

@@ -272,18 +272,21 @@ def test_8_bit_storage_with_large_counts(w, policy):
     pol = POLICIES[policy] if policy else None
     run_many_parity(w, 40, per_call=19, policy=pol, store_u8=True)
     run_many_parity(w, 40, per_call=16, announce=True, policy=pol, store_u8=True)
+    run_ahead_parity(w, 30, policy=pol, store_u8=True)                 # one launch per step, planned by the launch before
+    run_ahead_parity(w, 30, schedule_seed=3, policy=pol, store_u8=True)
 
 
 def test_8_bit_storage_decides_every_value_like_the_oracle_with_large_counts(monkeypatch):
     w = wl.variant(wl.C5, name="bw-u8-special", K=3, S=60, shape=(3, 32, 32), b=256, c=100, r=100, values="uniform")
     monkeypatch.setattr(wl, "make_batch", lambda ww, step, dev="cpu": _image_like_batch(ww, step, dev))
     run_many_parity(w, 40, per_call=16, announce=True, store_u8=True)
+    run_ahead_parity(w, 20, store_u8=True)
 
 
 @pytest.mark.parametrize("style", ["single", "ahead", "many", "many-announced", "fifo-bernoulli"])
 def test_8_bit_storage_through_every_call_form(style):
-    """The 8-bit form is served by the general kernels, by the plan-ahead step for small counts and by both several-steps
-    launches; the bytes are the oracle's in every call form."""
+    """The 8-bit form is served by the general kernels, the plan-ahead steps and the several-steps launches; the bytes are
+    the oracle's in every call form."""
     w = wl.variant(wl.C4, name=f"C4-u8-{style}", S=8, shape=(3, 32, 32), dtype="f32", b=128, c=40, r=40)
     if style == "single":
         run_parity(w, steps=40, store_u8=True, single_call=True)
