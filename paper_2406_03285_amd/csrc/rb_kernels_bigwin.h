@@ -44,7 +44,6 @@ constexpr int BW_MAX = 16;                          // most steps one launch cov
 constexpr int BW_HALF = 8;                          // steps whose tables one batch of lookups covers (registers)
 static_assert(BW_MAX % BW_HALF == 0 && BW_MAX <= 16, "step masks are 16-bit");
 constexpr uint64_t BW_TIMEOUT_TICKS = 200000000ull; // bound of every wait: 2 s of the 100 MHz wall clock
-constexpr uint32_t BW_MISSING = 0xFFFFFFFFu;        // bw_lookup: the row is not in the table
 
 // The table of one window in the workspace (two of them, used in turn).
 struct BwFlags {
@@ -448,7 +447,7 @@ __device__ __forceinline__ void bw_plan_update(const BwPlanArgs& a, int s, uint3
 __device__ __forceinline__ void bw_plan_sample(const BwPlanArgs& a, int s, uint32_t* lds)
 {
     int32_t* s_fill = reinterpret_cast<int32_t*>(lds);     // fill counts before the window, after step s, then their prefix sums
-    uint32_t* s_u = lds + BIG_FILL;                        // draw table, then the table of the rows read
+    uint32_t* s_u = lds + BIG_FILL;                        // draw table
     uint32_t* s_hit = s_u + 2 * BIG_HASH;                  // one byte per class: bit i: a step q of the window with q mod 8 = i brings it candidates
     uint32_t* s_draw = s_u + 4 * BIG_HASH;                 // sampling draws (bit 31: repeated)
     static_assert(BIG_CLASSES / 4 <= 2 * BIG_HASH, "a byte per class in the second table region");

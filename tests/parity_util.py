@@ -197,7 +197,7 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
 
 def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None,
                     options=(), store_u8=False):
-    """rb_update_sample_many, `per_call` steps per call (several launches of up to eight steps each),
+    """rb_update_sample_many, `per_call` steps per call (several launches, each of as many steps as the shape allows),
     against the oracle step by step.  announce: the labels of the next call's first steps are announced
     before every call (the last launch of a call then plans them); with a schedule seed some of those
     promises are broken (other labels, another c, fewer steps than planned, another call in between)."""
