@@ -576,9 +576,16 @@ def test_many_steps_from_one_call(w, window):
 @pytest.mark.parametrize("announce", [False, True], ids=["plain", "announced"])
 @pytest.mark.parametrize("w,steps", [(wl.C3, 72), (wl.C4, 48)], ids=["C3", "C4"])
 def test_many_steps_at_full_size(w, steps, announce):
-    """The configuration the bench times: real shapes, 16 (C3) or 8 (C4) steps per launch, calls announced: every
+    """The configuration the bench times: real shapes, 32 (C3) or 8 (C4) steps per launch, calls announced: every
     configured step.  Without the announcement: a shorter run."""
     run_many_parity(w, w.steps if FULL or announce else steps, per_call=64 if announce else 24, announce=announce)
+
+
+@pytest.mark.parametrize("form", ["u8", "bf16"])
+def test_many_steps_at_full_size_with_reduced_storage(form):
+    """C3 at its real shape with the rows stored in 8 bits resp. as bfloat16, as the bench's legs run it (announced calls of
+    64 steps, 32 steps per launch), 600 steps."""
+    run_many_parity(wl.C3, wl.C3.steps if FULL else 600, per_call=64, announce=True, store_u8=form == "u8", store_bf16=form == "bf16")
 
 
 @pytest.mark.parametrize("w,steps,per_call", [
