@@ -15,7 +15,7 @@ constexpr int WIN_ENTRIES = 1024;             // ... as long as steps * (c + r) 
 constexpr int WIN_SLOTS = 512;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
 constexpr int WIN_PACE = 64;                  // stores of a tile go out in one burst once its loads have arrived (no wait between them)
 constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_ENTRIES keys)
-// (The planner's LDS, about 36 KB, is reserved for every workgroup of the launch, the movers included: four of them
+// (The planner's LDS, 32.5 KB - 36.6 KB with the replacement strategies' state -, is reserved for every workgroup of the launch, the movers included: four of them
 // share a compute unit.  Tables of twice the size left room for two, which cost the 16-row steps 8 % of their rate.)
 constexpr uint32_t WIN_NONE = 0xFFFFu;        // "no entry" in the 16-bit links below
 constexpr uint32_t WIN_EMPTY = 0xFFFFFFFFu;   // free slot of the row table (no buffer row has this index)
