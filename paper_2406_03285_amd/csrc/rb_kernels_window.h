@@ -11,8 +11,8 @@
 namespace {
 
 constexpr int WIN_MAX = 32;                   // most steps one launch covers ...
-constexpr int WIN_ENTRIES = 1024;             // ... as long as steps * (c + r) table entries do not exceed this
-constexpr int WIN_SLOTS = 512;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
+constexpr int WIN_ENTRIES = 1280;             // ... as long as steps * (c + r) table entries do not exceed this
+constexpr int WIN_SLOTS = 640;                // ... and steps * max(c, r) not this (per-step arrays of the planner)
 constexpr int WIN_PACE = 64;                  // stores of a tile go out in one burst once its loads have arrived (no wait between them)
 constexpr int WIN_HASH = 2048;                // slots of the window's table of buffer rows (at most WIN_ENTRIES keys)
 // (The planner's LDS, 32.5 KB - 36.6 KB with the replacement strategies' state -, is reserved for every workgroup of the launch, the movers included: four of them
@@ -102,7 +102,7 @@ __device__ __forceinline__ uint32_t win_hash(uint32_t row)
 }
 
 // Slot of `row` in the row table, inserting it if it is not there (open addressing; the table
-// never fills: at most half of its slots are ever used).
+// never fills: at most WIN_ENTRIES of its WIN_HASH slots are ever used).
 __device__ __forceinline__ int win_find_or_insert(uint32_t* s_hkey, uint32_t row)
 {
     uint32_t h = win_hash(row);

@@ -115,8 +115,8 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_query_steps_per_launch(None, 8, 2, 2)[0] == rb.RB_EINVAL
     assert rb.rb_query_steps_per_launch(h, 0, 0, 0)[0] == rb.RB_EINVAL and rb.rb_query_steps_per_launch(h, 8, 9, 2)[0] == rb.RB_EINVAL
     assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)            # few rows per step: the most
-    assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 8)          # 1024 table entries / 128 rows per step
-    assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 12)         # 512 planner slots / max(c, r)
+    assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 10)         # 1280 table entries / 128 rows per step
+    assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 16)         # 640 planner slots / max(c, r)
     assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 16)          # beyond the small form: the large-count form's 16
     assert rb.rb_query_steps_per_launch(h, 4096, 8, 8) == (rb.RB_OK, 16)
     assert rb.rb_query_steps_per_launch(h, 4096, 1025, 8) == (rb.RB_OK, 1)        # not eligible for either
