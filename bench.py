@@ -31,7 +31,7 @@ POOL_BYTES = 2 << 30           # inputs/outputs rotate through at least this muc
 # `bench.py --pmc-run`, each scaled by the reading of a plain copy of known size in the same run; the text summaries
 # with the exact commands are the files named here.  Not measured by this run: the line says where it is from.
 PROFILED_TRAFFIC = {
-    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75835660, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),   # algorithmic 77070336: slot losers are not moved, forwarded rows hit the cache
+    ("C4-1000x300-bf16-3x224x224-zipf", "rb_window_kernel"): (75656761, "profiles/rb_window_kernel_C4_pmc_hbm_traffic.txt"),   # algorithmic 77070336: slot losers are not moved, forwarded rows hit the cache
     ("C3-1000x130-f32-3x224x224", "rb_window_kernel"): (19325318, "profiles/rb_window_kernel_C3_pmc_hbm_traffic.txt"),          # algorithmic 19267584
     ("C5-10000x1000-f32-2048-active50", "rb_bigwin_kernel"): (34013328, "profiles/rb_bigwin_kernel_C5_pmc_hbm_traffic.txt"),    # algorithmic 33554432
 }
