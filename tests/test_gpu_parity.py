@@ -576,7 +576,7 @@ def test_many_steps_from_one_call(w, window):
 @pytest.mark.parametrize("announce", [False, True], ids=["plain", "announced"])
 @pytest.mark.parametrize("w,steps", [(wl.C3, 72), (wl.C4, 48)], ids=["C3", "C4"])
 def test_many_steps_at_full_size(w, steps, announce):
-    """The configuration the bench times: real shapes, 32 (C3) or 8 (C4) steps per launch, calls announced: every
+    """The configuration the bench times: real shapes, 32 (C3) or 9 to 10 (C4) steps per launch, calls announced: every
     configured step.  Without the announcement: a shorter run."""
     run_many_parity(w, w.steps if FULL or announce else steps, per_call=64 if announce else 24, announce=announce)
 
