@@ -113,11 +113,13 @@ struct Shape {
 // Split `rows` rows of `row_vec` vectors into tiles of at most width * unroll vectors, where `width`
 // is the number of threads that share a tile: TPB in the small-count kernels (a workgroup per tile),
 // WAVE in the general ones (a wavefront per tile).
-Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
+// most: the most vectors per thread the caller's kernel can hold (the converting movers hold several accesses per
+// vector); preferred: what the caller's kernel does best with, taken when the option leaves the choice open.
+Shape plan_shape(const rb_buffer* rb, int64_t rows, int width, int most = 8, int preferred = 0)
 {
     Shape s;
     const int64_t row_vec = rb->row_vec;
-    int u = rb->opt_unroll;
+    int u = rb->opt_unroll != 0 ? rb->opt_unroll : preferred;
     if (u == 0) {
         // Largest unroll that still leaves at least 1024 tiles (four workgroups per compute unit in
         // the small-count kernels, four wavefronts in the general ones); never below two vectors in
@@ -126,6 +128,7 @@ Shape plan_shape(const rb_buffer* rb, int64_t rows, int width)
         while (u > 2 && rows * ((row_vec + (int64_t)width * u - 1) / ((int64_t)width * u)) < 1024) u >>= 1;
         while (u > 1 && (int64_t)width * (u / 2) >= row_vec) u >>= 1;
     }
+    if (u > most) u = most;
     s.unroll = u;
     const int64_t cap = (int64_t)width * u;
     s.tpr = (int)((row_vec + cap - 1) / cap);
@@ -343,13 +346,8 @@ int step_planned(rb_buffer* rb, const void* batch_x, const int64_t* batch_y, int
         if (hipGetLastError() != hipSuccess) return RB_EHIP;
         plan_enqueued(rb, batch_y, b, c, r, seed, step);
     }
-    Shape sh = plan_shape(rb, c + r, TPB);
-    if (rb->storage == RB_STORE_U8 && sh.unroll > 4) {         // a lane holds four accesses per vector: at most four vectors
-        const int unroll_option = rb->opt_unroll;
-        rb->opt_unroll = 4;
-        sh = plan_shape(rb, c + r, TPB);
-        rb->opt_unroll = unroll_option;
-    }
+    // (with 8-bit storage a lane holds four accesses per vector: at most four vectors)
+    const Shape sh = plan_shape(rb, c + r, TPB, rb->storage == RB_STORE_U8 ? 4 : 8);
     MoveArgs m;
     m.batch_x = static_cast<const vec16*>(batch_x);
     m.buf_x = static_cast<vec16*>(rb->buf_x);
@@ -449,18 +447,11 @@ hipError_t launch_big(const MoveArgs& m, const PlanArgs& next, const uint32_t* f
 // the second round of workgroups start as the first ones end); for many short rows a wavefront per row, sixteen
 // rows per workgroup, so that one round suffices (10000 classes, 1024 + 1024 rows of 8 KiB: no change, the step is
 // bound by the planners and the launch itself).
-Shape big_shape(rb_buffer* rb, int64_t rows, int planners)
+Shape big_shape(const rb_buffer* rb, int64_t rows, int planners)
 {
+    // (with 8-bit storage a lane holds four accesses per vector, and these workgroups have 128 registers per lane: two vectors)
+    if (rb->storage == RB_STORE_U8) return plan_shape(rb, rows, BIG_GROUP, 2);
     Shape s = plan_shape(rb, rows, BIG_GROUP);
-    if (rb->storage == RB_STORE_U8) {           // a lane holds four accesses per vector: at most two vectors
-        if (s.unroll > 2) {
-            const int unroll_option = rb->opt_unroll;
-            rb->opt_unroll = 2;
-            s = plan_shape(rb, rows, BIG_GROUP);
-            rb->opt_unroll = unroll_option;
-        }
-        return s;
-    }
     if (rb->opt_unroll != 0) return s;
     constexpr int64_t CUS = 256;
     const int64_t nunits = (rb->row_vec + TILE_UNIT - 1) / TILE_UNIT;
@@ -623,12 +614,10 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     // 64 candidates and representatives: 13.1 us per step against 14.1 with two and 14.2 with eight; binary32
     // samples, 8 and 8: 3.9 against 4.1 and 4.1).  With binary32 samples stored as bfloat16 a thread holds twice as
     // many half vectors, and two per thread measured best (8 and 8: 2.6 us against 2.7).
-    const int unroll_option = rb->opt_unroll;
     // With 8-bit storage a thread holds four quarter vectors per vector of the tile (16 bytes of the sample each): one.
-    if (unroll_option == 0) rb->opt_unroll = rb->storage == RB_STORE_U8 ? 1 : rb->storage == RB_STORE_BF16 ? 2 : 4;
-    else if (rb->storage == RB_STORE_U8 && unroll_option > 4) rb->opt_unroll = 4;
-    Shape sh = plan_shape(rb, wmax * (c + r), TPB);
-    rb->opt_unroll = unroll_option;
+    const int unroll_option = rb->opt_unroll;
+    Shape sh = plan_shape(rb, wmax * (c + r), TPB, rb->storage == RB_STORE_U8 ? 4 : 8,
+                          rb->storage == RB_STORE_U8 ? 1 : rb->storage == RB_STORE_BF16 ? 2 : 4);
     // ... and a third more tiles than that needs, i.e. tiles about three quarters full (most threads hold three vectors):
     // the launch's workgroups come in more and shorter rounds.  Measured with 301 KB rows, 64 + 64 per step: 12.42 us per step
     // with 25 to 28 tiles per row against 12.74 with the 19 that four vectors per thread need, 13.4 with 38; 602 KB rows,
@@ -763,21 +752,12 @@ hipError_t launch_bigwin(const BwMoveArgs& m, const BwPlanArgs& next, int storag
 // Tiles of the several-steps launch for large counts.  A compute unit holds a fixed number of wavefronts, so the bytes it
 // has in flight are what a wavefront has in flight: rows of up to 8 KiB are moved by one wavefront each (eight vectors per
 // lane), rows of up to 16 KiB by two; longer rows are cut into tiles for 256 threads like everywhere else.
-Shape bigwin_shape(rb_buffer* rb, int64_t rows, int& width)
+Shape bigwin_shape(const rb_buffer* rb, int64_t rows, int& width)
 {
     width = TPB;
     const bool q8 = rb->storage == RB_STORE_U8;        // at most two vectors per lane: a wavefront per row up to 128 vectors
     if (rb->opt_unroll == 0 && rb->row_vec <= (q8 ? WAVE * 2 : 2 * WAVE * 8)) width = rb->row_vec <= WAVE * 8 ? WAVE : 2 * WAVE;
-    if (width == TPB) {
-        const int unroll_option = rb->opt_unroll;
-        Shape s = plan_shape(rb, rows, TPB);
-        if (q8 && s.unroll > 2) {
-            rb->opt_unroll = 2;
-            s = plan_shape(rb, rows, TPB);
-            rb->opt_unroll = unroll_option;
-        }
-        return s;
-    }
+    if (width == TPB) return plan_shape(rb, rows, TPB, q8 ? 2 : 8);
     Shape s;
     s.unroll = width == WAVE && rb->row_vec <= WAVE * 2 ? 2 : 8;
     s.tpr = 1;
@@ -1130,13 +1110,7 @@ int rb_update(rb_buffer* rb, const void* batch_x, const int64_t* batch_y,
         while (slack * slack < 36 * c) ++slack;          // about six standard deviations
         rows = c + slack < b ? c + slack : b;
     }
-    Shape sh = plan_shape(rb, rows, small ? TPB : WAVE);
-    if (narrow == 2 && sh.unroll > 4) {              // the 8-bit mover holds at most four vectors per lane
-        const int keep = rb->opt_unroll;
-        rb->opt_unroll = 4;
-        sh = plan_shape(rb, rows, WAVE);
-        rb->opt_unroll = keep;
-    }
+    const Shape sh = plan_shape(rb, rows, small ? TPB : WAVE, narrow == 2 ? 4 : 8);   // (the 8-bit mover holds at most four vectors per lane)
     UpdateArgs a;
     a.batch_x = static_cast<const vec16*>(batch_x);
     a.batch_y = batch_y;
@@ -1176,13 +1150,7 @@ int rb_sample_augment(rb_buffer* rb, int64_t r, uint64_t seed, uint64_t step, vo
 
     const int widen = rb->storage == RB_STORE_BF16 ? 1 : rb->storage == RB_STORE_U8 ? 2 : 0;
     const bool small = r <= WAVE && rb->nchunks <= WAVE && !widen;
-    Shape sh = plan_shape(rb, r, small ? TPB : WAVE);
-    if (widen == 2 && sh.unroll > 4) {
-        const int keep = rb->opt_unroll;
-        rb->opt_unroll = 4;
-        sh = plan_shape(rb, r, WAVE);
-        rb->opt_unroll = keep;
-    }
+    const Shape sh = plan_shape(rb, r, small ? TPB : WAVE, widen == 2 ? 4 : 8);
     SampleArgs a;
     a.buf_x = static_cast<const vec16*>(rb->buf_x);
     a.out_x = static_cast<vec16*>(out_x);
