@@ -294,6 +294,29 @@ void discard_window_plan(rb_buffer* rb)
     }
 }
 
+// Whether the window that the call before planned ahead (window_plan_kept) is the start of this call: same shape, seed
+// and step number, and the very label arrays that were announced.
+bool window_plan_matches(const rb_buffer* rb, int64_t n, const int64_t* const* batch_y, int64_t b, int64_t c, int64_t r,
+                         uint64_t seed, uint64_t first_step)
+{
+    bool same = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
+                rb->wplan_seed == seed && rb->wplan_first == first_step;
+    for (int64_t k = 0; same && k < rb->wplan_w; ++k) same = rb->wplan_y[k] == batch_y[k];
+    return same;
+}
+
+// The last launch of a call has planned the first w steps of the call that was announced, into table tbl.
+void window_plan_kept(rb_buffer* rb, int64_t w, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step, int tbl,
+                      int64_t nat, const int64_t* const* ann_y)
+{
+    rb->wplan_valid = true;
+    rb->wplan_w = w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
+    rb->wplan_seed = seed; rb->wplan_first = first_step;
+    rb->wplan_tbl = tbl;
+    rb->wplan_nat = nat;
+    for (int64_t k = 0; k < w; ++k) rb->wplan_y[k] = ann_y[k];
+}
+
 void discard_plan(rb_buffer* rb)
 {
     if (rb->plan_valid) {
@@ -642,9 +665,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     while (w0 < wmax && grown(w0) <= w0) ++w0;
     int64_t at = 0, w;
     int tbl;
-    bool resume = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
-                  rb->wplan_seed == seed && rb->wplan_first == first_step;
-    for (int64_t k = 0; resume && k < rb->wplan_w; ++k) resume = rb->wplan_y[k] == batch_y[k];
+    const bool resume = window_plan_matches(rb, n, batch_y, b, c, r, seed, first_step);
     int64_t nat;                                // size the windows have grown to, whatever a call's end cut them down to
     if (resume) {
         w = rb->wplan_w;
@@ -693,14 +714,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                                         : launch_window<false>(m, next, rb->storage, aux, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
-        if (ahead) {
-            rb->wplan_valid = true;
-            rb->wplan_w = next_w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
-            rb->wplan_seed = seed; rb->wplan_first = first_step + (uint64_t)n;
-            rb->wplan_tbl = tbl ^ 1;
-            rb->wplan_nat = nat;
-            for (int64_t k = 0; k < next_w; ++k) rb->wplan_y[k] = ann_y[k];
-        }
+        if (ahead) window_plan_kept(rb, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, nat, ann_y);
         at = next_at;
         w = ahead ? 0 : next_w;
         tbl ^= 1;
@@ -836,9 +850,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
     if (allow_big_lds<&rb_bigwin_plan_kernel>() != hipSuccess) return RB_EHIP;
     int64_t at = 0, w;
     int tbl;
-    bool resume = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
-                  rb->wplan_seed == seed && rb->wplan_first == first_step;
-    for (int64_t k = 0; resume && k < rb->wplan_w; ++k) resume = rb->wplan_y[k] == batch_y[k];
+    const bool resume = window_plan_matches(rb, n, batch_y, b, c, r, seed, first_step);
     if (resume) {
         w = rb->wplan_w;
         tbl = rb->wplan_tbl;
@@ -883,14 +895,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
                                         : launch_bigwin<false>(m, next, rb->storage, width, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
-        if (ahead) {
-            rb->wplan_valid = true;
-            rb->wplan_w = next_w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
-            rb->wplan_seed = seed; rb->wplan_first = first_step + (uint64_t)n;
-            rb->wplan_tbl = tbl ^ 1;
-            rb->wplan_nat = wmax;
-            for (int64_t k = 0; k < next_w; ++k) rb->wplan_y[k] = ann_y[k];
-        }
+        if (ahead) window_plan_kept(rb, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, wmax, ann_y);
         at = next_at;
         w = ahead ? 0 : next_w;
         tbl ^= 1;
