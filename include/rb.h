@@ -249,13 +249,15 @@ int rb_announce_next(rb_buffer *rb, const int64_t *next_batch_y);
  * pipeline).  When 1 <= c <= 64, 1 <= r <= 64, classes <= 1024, b <= 2048 and
  * the selection is the exact one (any replacement strategy, either storage
  * form), up to 32 of the steps
- * - as many as 1024 / (c + r) and 512 / max(c, r) allow, see
+ * - as many as 1280 / (c + r) and 640 / max(c, r) allow, see
  * rb_query_steps_per_launch - share ONE launch: the rows of all of them are
  * moved at once, by a plan that one workgroup of the launch before made.  What
  * the order of separate launches would settle between steps (a representative
  * read from a slot that another step of the same launch writes, a slot written
  * twice) the plan settles, so the cost of a launch is paid once per that many
- * steps.  Beyond those limits, for up to 1024 candidates and representatives,
+ * steps.  Beyond those limits - and within them when a step's rows are so
+ * short that they are moved sooner than one workgroup plans a step
+ * (RB_OPT_PLANNERS) -, for up to 1024 candidates and representatives,
  * b <= 4096 (b <= 1024 with the Bernoulli selection) and up to 10240 classes,
  * up to 16 steps share one launch in the same way; their plan is made by two
  * workgroups per step of the launch before, which work side by side (should
@@ -397,8 +399,15 @@ int rb_read_moved_rows(rb_buffer *rb, uint64_t *rows_host);
  * RB_OPT_FUSE: 1 (default) lets rb_update_sample use its single-launch form,
  * 0 makes it always enqueue the two kernels.  RB_OPT_WINDOW: most steps that
  * rb_update_sample_many puts into one launch (1..32, default 32; 1 = one
- * launch per step). */
-enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4 };
+ * launch per step).  RB_OPT_PLANNERS: which of its two several-steps forms
+ * rb_update_sample_many uses for a shape that both can serve (at most 64
+ * candidates and representatives, at most 1024 classes, exact selection):
+ * 0 (default) = the library chooses by the time a step's rows take to move,
+ * 1 = one workgroup per launch plans the next launch's steps one after the
+ * other (up to 32 steps per launch), 2 = two workgroups per step plan them
+ * side by side (up to 16 steps per launch).  Results do not depend on it. */
+enum rb_option { RB_OPT_UNROLL = 0, RB_OPT_NONTEMPORAL = 1, RB_OPT_ROWS_PER_BLOCK = 2, RB_OPT_FUSE = 3, RB_OPT_WINDOW = 4,
+                 RB_OPT_PLANNERS = 5 };
 int rb_set_option(rb_buffer *rb, int32_t option, int64_t value);
 
 /* Free the host handle.  Device memory stays the caller's. */

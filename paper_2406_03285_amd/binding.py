@@ -18,7 +18,7 @@ RB_STATIC_WORKSPACE_BYTES = 4 << 20
 RB_MAX_BATCH = 4096
 RB_MAX_CLASSES = 1 << 20
 RB_FLAG_BAD_LABEL = 1
-RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE, RB_OPT_WINDOW = 0, 1, 2, 3, 4
+RB_OPT_UNROLL, RB_OPT_NONTEMPORAL, RB_OPT_ROWS_PER_BLOCK, RB_OPT_FUSE, RB_OPT_WINDOW, RB_OPT_PLANNERS = 0, 1, 2, 3, 4, 5
 RB_SELECT_EXACT, RB_SELECT_BERNOULLI = 0, 1
 RB_STORE_SAME, RB_STORE_BF16, RB_STORE_U8 = 0, 1, 2
 RB_EVICT_UNIFORM, RB_EVICT_FIFO, RB_EVICT_RESERVOIR = 0, 1, 2

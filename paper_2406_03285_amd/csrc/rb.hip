@@ -59,7 +59,7 @@ struct rb_buffer {
     // workspace layout (byte offsets)
     size_t off_fill[2], off_chunk[2], ws_bytes;
     // launch-shape knobs
-    int opt_unroll, opt_nt, opt_rpb, opt_fuse, opt_window;
+    int opt_unroll, opt_nt, opt_rpb, opt_fuse, opt_window, opt_planners;
     // policy variant and its per-class state (two copies, like the fill counts)
     int selection, eviction;
     size_t off_aux[2];
@@ -84,6 +84,7 @@ struct rb_buffer {
     int64_t ann_n;
     bool wplan_valid;        // a window has been planned (and the fill counts advanced) but not yet executed
     const int64_t* wplan_y[WIN_MAX];
+    int wplan_form;          // MANY_SMALL or MANY_LARGE: whose table it is in
     int64_t wplan_w, wplan_b, wplan_c, wplan_r;
     uint64_t wplan_seed, wplan_first;
     int wplan_tbl;           // table that holds it
@@ -104,6 +105,10 @@ rb_buffer* scratch_holder[MAX_DEVICES] = {};  // the handle that is bound to it
 
 inline bool aligned(const void* p, size_t a) { return (reinterpret_cast<uintptr_t>(p) & (a - 1)) == 0; }
 inline size_t round_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// How rb_update_sample_many carries out a call: step by step, or several steps per launch planned by one workgroup per
+// launch (rb_kernels_window.h) or by two per step (rb_kernels_bigwin.h).
+enum { MANY_SINGLE = 0, MANY_SMALL = 1, MANY_LARGE = 2 };
 
 struct Shape {
     int unroll, tpr, tile_vec, tile_rem, rpb;
@@ -296,20 +301,22 @@ void discard_window_plan(rb_buffer* rb)
 
 // Whether the window that the call before planned ahead (window_plan_kept) is the start of this call: same shape, seed
 // and step number, and the very label arrays that were announced.
-bool window_plan_matches(const rb_buffer* rb, int64_t n, const int64_t* const* batch_y, int64_t b, int64_t c, int64_t r,
+bool window_plan_matches(const rb_buffer* rb, int form, int64_t n, const int64_t* const* batch_y, int64_t b, int64_t c, int64_t r,
                          uint64_t seed, uint64_t first_step)
 {
-    bool same = rb->wplan_valid && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
+    bool same = rb->wplan_valid && rb->wplan_form == form && rb->wplan_w <= n && rb->wplan_b == b && rb->wplan_c == c && rb->wplan_r == r &&
                 rb->wplan_seed == seed && rb->wplan_first == first_step;
     for (int64_t k = 0; same && k < rb->wplan_w; ++k) same = rb->wplan_y[k] == batch_y[k];
     return same;
 }
 
-// The last launch of a call has planned the first w steps of the call that was announced, into table tbl.
-void window_plan_kept(rb_buffer* rb, int64_t w, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step, int tbl,
+// The last launch of a call has planned the first w steps of the call that was announced, into table tbl of the given
+// form (MANY_SMALL, MANY_LARGE).
+void window_plan_kept(rb_buffer* rb, int form, int64_t w, int64_t b, int64_t c, int64_t r, uint64_t seed, uint64_t first_step, int tbl,
                       int64_t nat, const int64_t* const* ann_y)
 {
     rb->wplan_valid = true;
+    rb->wplan_form = form;
     rb->wplan_w = w; rb->wplan_b = b; rb->wplan_c = c; rb->wplan_r = r;
     rb->wplan_seed = seed; rb->wplan_first = first_step;
     rb->wplan_tbl = tbl;
@@ -665,7 +672,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
     while (w0 < wmax && grown(w0) <= w0) ++w0;
     int64_t at = 0, w;
     int tbl;
-    const bool resume = window_plan_matches(rb, n, batch_y, b, c, r, seed, first_step);
+    const bool resume = window_plan_matches(rb, MANY_SMALL, n, batch_y, b, c, r, seed, first_step);
     int64_t nat;                                // size the windows have grown to, whatever a call's end cut them down to
     if (resume) {
         w = rb->wplan_w;
@@ -714,7 +721,7 @@ int steps_windowed(rb_buffer* rb, int64_t n, const void* const* batch_x, const i
                                         : launch_window<false>(m, next, rb->storage, aux, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
-        if (ahead) window_plan_kept(rb, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, nat, ann_y);
+        if (ahead) window_plan_kept(rb, MANY_SMALL, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, nat, ann_y);
         at = next_at;
         w = ahead ? 0 : next_w;
         tbl ^= 1;
@@ -850,7 +857,7 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
     if (allow_big_lds<&rb_bigwin_plan_kernel>() != hipSuccess) return RB_EHIP;
     int64_t at = 0, w;
     int tbl;
-    const bool resume = window_plan_matches(rb, n, batch_y, b, c, r, seed, first_step);
+    const bool resume = window_plan_matches(rb, MANY_LARGE, n, batch_y, b, c, r, seed, first_step);
     if (resume) {
         w = rb->wplan_w;
         tbl = rb->wplan_tbl;
@@ -895,13 +902,41 @@ int steps_bigwin(rb_buffer* rb, int64_t n, const void* const* batch_x, const int
                                         : launch_bigwin<false>(m, next, rb->storage, width, sh.unroll, grid, rb->stream);
         if (e != hipSuccess) return RB_EHIP;
         if (next_w > 0) rb->cur ^= 1;
-        if (ahead) window_plan_kept(rb, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, wmax, ann_y);
+        if (ahead) window_plan_kept(rb, MANY_LARGE, next_w, b, c, r, seed, first_step + (uint64_t)n, tbl ^ 1, wmax, ann_y);
         at = next_at;
         w = ahead ? 0 : next_w;
         tbl ^= 1;
     }
     rb->updates += n;
     return RB_OK;
+}
+
+// Which several-steps form serves this shape (MANY_SINGLE: none) and how many steps it puts into one launch at most.
+// Where both forms could: the one workgroup that plans a window of the small form does so step after step (about
+// 1.6 us + 0.04 us per candidate or representative each, 2.3 to 2.7 us under load), which is hidden as long as the rows
+// of a step take longer to move; the two planners per step of the large form work side by side and take as long for
+// sixteen steps as for one, but their launch moves long rows about 6 % slower, and rows that are converted on the way
+// 15 to 25 % slower.  Measured on MI355X, us per step, small form against large form: 8 + 8 rows of 12 KB 2.7 : 1.05;
+// 8 + 8 rows of 301 KB 2.59 : 2.07, 12 + 12 of them 2.88 : 2.86, 16 + 16 3.09 : 3.37; 4 + 4 rows of 602 KB 2.26 : 2.07,
+// 6 + 6 2.52 : 2.58, 8 + 8 3.08 : 3.32; 8 + 8 rows of 602 KB stored as bfloat16 2.54 : 3.22, in 8 bits 2.5 : 2.9.  So the
+// large form takes a shape when its rows move (at 5.5 TB/s) in less than 1.25 times the small form's nominal plan time,
+// in less than 0.8 times when they are converted.  RB_OPT_PLANNERS overrides the choice where the shape allows.
+int many_form(const rb_buffer* rb, int64_t b, int64_t c, int64_t r, int64_t& steps)
+{
+    const int64_t small = window_limit(rb, b, c, r), large = bigwin_limit(rb, b, c, r);
+    int form = MANY_SINGLE;
+    if (small >= 2 && large >= 2) {
+        const double move_us = (double)(c + r) * (double)(rb->row_bytes + rb->sample_bytes) / 5.5e6;
+        const double plan_us = 1.6 + 0.04 * (double)std::max(c, r);
+        form = move_us < (rb->storage == RB_STORE_SAME ? 1.25 : 0.8) * plan_us ? MANY_LARGE : MANY_SMALL;
+        if (rb->opt_planners != 0) form = rb->opt_planners;
+    } else if (small >= 2) {
+        form = MANY_SMALL;
+    } else if (large >= 2) {
+        form = MANY_LARGE;
+    }
+    steps = form == MANY_SMALL ? small : form == MANY_LARGE ? large : 1;
+    return form;
 }
 
 // What the host can check of the arguments of one update + sample step.
@@ -984,7 +1019,7 @@ int rb_create(rb_buffer** out, int64_t classes, int64_t slots_per_class,
     rb->tbl_next = 0; rb->tbl_planned = 0; rb->plan_valid = false; rb->plan_y = nullptr; rb->next_y = nullptr;
     rb->ann_n = 0; rb->wplan_valid = false; rb->wplan_tbl = 0;
     rb->selection = RB_SELECT_EXACT; rb->eviction = RB_EVICT_UNIFORM; rb->updates = 0;
-    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = WIN_MAX;
+    rb->opt_unroll = 0; rb->opt_nt = 1; rb->opt_rpb = 0; rb->opt_fuse = 1; rb->opt_window = WIN_MAX; rb->opt_planners = 0;
     *out = rb;
     return RB_OK;
 }
@@ -1252,8 +1287,7 @@ int rb_query_steps_per_launch(const rb_buffer* rb, int64_t b, int64_t c, int64_t
 {
     if (!rb || !steps) return RB_EINVAL;
     if (b < 1 || b > RB_MAX_BATCH || c < 0 || c > b || r < 0 || r > RB_MAX_BATCH) return RB_EINVAL;
-    *steps = window_limit(rb, b, c, r);
-    if (*steps == 1) *steps = bigwin_limit(rb, b, c, r);
+    (void)many_form(rb, b, c, r, *steps);
     return RB_OK;
 }
 
@@ -1283,22 +1317,16 @@ int rb_update_sample_many(rb_buffer* rb, int64_t n, const void* const* batch_x, 
         const int bad = check_step(rb, batch_x[i], batch_y[i], b, c, r, r > 0 ? out_x[i] : nullptr, r > 0 ? out_y[i] : nullptr);
         if (bad != RB_OK) return bad;
     }
-    const bool windowed = n >= 2 && window_limit(rb, b, c, r) >= 2;
-    if (windowed) {
+    int64_t per_launch;
+    const int form = n >= 2 ? many_form(rb, b, c, r, per_launch) : MANY_SINGLE;
+    if (form != MANY_SINGLE) {
         if (rb->plan_valid) {                    // a single step that was planned ahead is not executed as planned
             rb->cur ^= 1;
             rb->plan_valid = false;
         }
         rb->next_y = nullptr;
-        return steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
-    }
-    if (n >= 2 && bigwin_limit(rb, b, c, r) >= 2) {
-        if (rb->plan_valid) {
-            rb->cur ^= 1;
-            rb->plan_valid = false;
-        }
-        rb->next_y = nullptr;
-        return steps_bigwin(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
+        return form == MANY_SMALL ? steps_windowed(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y)
+                                  : steps_bigwin(rb, n, batch_x, batch_y, b, c, r, seed, first_step, out_x, out_y, ann_n, ann_y);
     }
     discard_window_plan(rb);
     for (int64_t i = 0; i < n; ++i) {
@@ -1468,6 +1496,10 @@ int rb_set_option(rb_buffer* rb, int32_t option, int64_t value)
     case RB_OPT_WINDOW:
         if (value < 1 || value > WIN_MAX) return RB_EINVAL;
         rb->opt_window = (int)value;
+        return RB_OK;
+    case RB_OPT_PLANNERS:
+        if (value < 0 || value > 2) return RB_EINVAL;
+        rb->opt_planners = (int)value;
         return RB_OK;
     default:
         return RB_EINVAL;

@@ -196,15 +196,26 @@ def run_ahead_parity(w, steps, schedule_seed=None, store_bf16=False, policy=None
 
 
 def run_many_parity(w, steps, per_call=24, window=None, announce=False, schedule_seed=None, store_bf16=False, policy=None,
-                    options=(), store_u8=False):
+                    options=(), store_u8=False, planners=None):
     """rb_update_sample_many, `per_call` steps per call (several launches, each of as many steps as the shape allows),
     against the oracle step by step.  announce: the labels of the next call's first steps are announced
     before every call (the last launch of a call then plans them); with a schedule seed some of those
-    promises are broken (other labels, another c, fewer steps than planned, another call in between)."""
+    promises are broken (other labels, another c, fewer steps than planned, another call in between).
+    planners: RB_OPT_PLANNERS (1: one planner workgroup per launch, 2: two per step, 0: the library's choice); None: runs of
+    up to 200 steps go through both forms when the shape allows either, longer ones through the library's choice."""
     import paper_2406_03285_amd as rb
 
+    if planners is None:
+        exact = policy is None or policy[0] == 0
+        either = 1 <= w.c <= 64 and 1 <= w.r <= 64 and w.K <= 1024 and w.b <= 2048 and exact
+        if either and steps <= 200 and (window is None or window > 1) and not any(opt == rb.RB_OPT_PLANNERS for opt, _ in options):
+            for form in (1, 2):
+                run_many_parity(w, steps, per_call, window, announce, schedule_seed, store_bf16, policy, options, store_u8, form)
+            return
+        planners = 0
     dev = torch.device("cuda:0")
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev, store_dtype=_store_dtype(store_bf16, store_u8))
+    buf.set_option(rb.RB_OPT_PLANNERS, planners)
     if window is not None:
         buf.set_option(rb.RB_OPT_WINDOW, window)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)

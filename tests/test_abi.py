@@ -114,6 +114,11 @@ def test_variant_setters_validate_on_the_host():
     # steps per launch of the multi-step call: host arithmetic only
     assert rb.rb_query_steps_per_launch(None, 8, 2, 2)[0] == rb.RB_EINVAL
     assert rb.rb_query_steps_per_launch(h, 0, 0, 0)[0] == rb.RB_EINVAL and rb.rb_query_steps_per_launch(h, 8, 9, 2)[0] == rb.RB_EINVAL
+    # (32-byte samples: rows move sooner than one workgroup plans a step, so the form with two planners per step is chosen)
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16) and rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 16)
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 3) == rb.RB_EINVAL and rb.rb_set_option(h, rb.RB_OPT_PLANNERS, -1) == rb.RB_EINVAL
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 2) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16)
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 1) == rb.RB_OK                 # one planner workgroup per launch:
     assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)            # few rows per step: the most
     assert rb.rb_query_steps_per_launch(h, 512, 64, 64) == (rb.RB_OK, 10)         # 1280 table entries / 128 rows per step
     assert rb.rb_query_steps_per_launch(h, 512, 40, 24) == (rb.RB_OK, 16)         # 640 planner slots / max(c, r)
@@ -126,4 +131,11 @@ def test_variant_setters_validate_on_the_host():
     assert rb.rb_set_policy(h, rb.RB_SELECT_EXACT, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)
     assert rb.rb_set_policy(h, rb.RB_SELECT_BERNOULLI, rb.RB_EVICT_FIFO) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 5)   # the large-count form takes it
     assert rb.rb_query_steps_per_launch(h, 1025, 8, 8) == (rb.RB_OK, 1)         # ... for mini-batches of at most 1024
+    rb.rb_destroy(h)
+    # the library's choice between the two forms follows the time a step's rows take to move
+    rc, h = rb.rb_create(10, 4, (3, 224, 224), rb.RB_F32)
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)            # 16 rows of 602 KB: one planner workgroup keeps up
+    assert rb.rb_query_steps_per_launch(h, 64, 4, 4) == (rb.RB_OK, 16)            # 8 rows: it would not
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 2) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 16)
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 1) == rb.RB_OK and rb.rb_query_steps_per_launch(h, 64, 4, 4) == (rb.RB_OK, 32)
     rb.rb_destroy(h)

@@ -311,8 +311,9 @@ def test_8_bit_storage_argument_checks():
     rc, h = rb.rb_create(4, 2, (16,), rb.RB_F32)
     assert rb.rb_set_storage(h, 3) == rb.RB_EINVAL
     assert rb.rb_set_storage(h, rb.RB_STORE_U8) == rb.RB_OK and rb.rb_query_sizes(h)[1] == 4 * 2 * 16
-    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)   # the several-steps launch for small counts serves it
-    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 16)  # ... and so does the one for large counts
+    assert rb.rb_query_steps_per_launch(h, 512, 65, 8) == (rb.RB_OK, 16)  # the several-steps launch for large counts serves it
+    assert rb.rb_set_option(h, rb.RB_OPT_PLANNERS, 1) == rb.RB_OK
+    assert rb.rb_query_steps_per_launch(h, 64, 8, 8) == (rb.RB_OK, 32)   # ... and so does the one for small counts
     rb.rb_destroy(h)
 
 
@@ -537,12 +538,14 @@ def test_plan_ahead_flags_a_bad_label_only_when_its_step_runs():
     wl.variant(wl.C4, name="C4-many-S2", S=2, shape=(3, 32, 32)),          # Zipf head: the hot classes' two slots are hit again and again
     wl.variant(wl.C1, name="C1-many", S=20),
 ], ids=["small", "general", "one-class", "one-slot", "zipf-S2", "C1"])
-def test_many_steps_from_one_call(w, window):
+@pytest.mark.parametrize("planners", [1, 2], ids=["one-planner", "planners-side-by-side"])
+def test_many_steps_from_one_call(w, window, planners):
     rb = _rb()
     dev = torch.device("cuda:0")
     n = 36 if window == 32 else 18
     buf = rb.RehearsalBuffer(w.K, w.S, w.shape, w.torch_dtype, device=dev)
     buf.set_option(rb.RB_OPT_WINDOW, window)
+    buf.set_option(rb.RB_OPT_PLANNERS, planners)
     orc = rbo.Buffer(w.K, w.S, w.row_bytes)
     xs, ys, oxs, oys = [], [], [], []
     for t in range(2 * n):
@@ -684,7 +687,8 @@ def test_an_announced_call_that_never_comes_is_forgotten():
 
 
 @pytest.mark.parametrize("window", [32, 16, 8, 4, 2])
-def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
+@pytest.mark.parametrize("planners", [1, 2], ids=["one-planner", "planners-side-by-side"])
+def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window, planners):
     """Eight classes of one slot each, every step samples all eight rows and rewrites one class (the label
     sequence decides which): rows that are read before a later step of the same launch overwrites them, rows
     that are read after an earlier step wrote them, rows written twice."""
@@ -694,6 +698,7 @@ def test_many_steps_with_every_hazard_between_the_steps_of_one_launch(window):
     shape = (3, 40)                                     # 480-byte rows
     buf = rb.RehearsalBuffer(K, S, shape, torch.float32, device=dev)
     buf.set_option(rb.RB_OPT_WINDOW, window)
+    buf.set_option(rb.RB_OPT_PLANNERS, planners)
     orc = rbo.Buffer(K, S, 480)
     sequence = list(range(8)) + [7, 6, 5, 4, 3, 2, 1, 0] + [0, 0, 1, 1, 0, 2, 2, 0] + [5, 5, 5, 5, 5, 5, 5, 5] + [3, 4, 3, 4, 3, 4, 3, 4]
     g = torch.Generator(device="cpu")
@@ -794,12 +799,14 @@ def test_many_steps_with_large_counts_at_full_size(w):
     run_many_parity(w, w.steps, per_call=32, announce=True)
 
 
-def test_many_steps_drop_and_flag_bad_labels():
+@pytest.mark.parametrize("planners", [1, 2], ids=["one-planner", "planners-side-by-side"])
+def test_many_steps_drop_and_flag_bad_labels(planners):
     """Labels outside [0, K) among the candidates of steps in the middle of a launch: not stored, flag raised."""
     rb = _rb()
     dev = torch.device("cuda:0")
     K, S, b, c, r, n = 5, 3, 12, 12, 6, 16
     buf = rb.RehearsalBuffer(K, S, (8,), torch.float32, device=dev)
+    buf.set_option(rb.RB_OPT_PLANNERS, planners)
     orc = rbo.Buffer(K, S, 32)
     g = torch.Generator(device="cpu")
     g.manual_seed(5)
@@ -1125,7 +1132,8 @@ def test_random_configurations_planned_ahead(chunk):
         style = str(rng.choice(["ahead", "ahead-broken", "many", "many-announced", "many-broken"]))
         per_call = int(rng.choice([3, 8, 17, 33]))
         options = ((rb.RB_OPT_UNROLL, int(rng.choice([0, 1, 2, 4, 8]))), (rb.RB_OPT_NONTEMPORAL, int(rng.integers(0, 2))),
-                   (rb.RB_OPT_WINDOW, int(rng.choice([32, 32, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))))
+                   (rb.RB_OPT_WINDOW, int(rng.choice([32, 32, 16, 7, 2, 1]))), (rb.RB_OPT_FUSE, int(rng.choice([1, 1, 1, 0]))),
+                   (rb.RB_OPT_PLANNERS, int(rng.choice([0, 1, 2]))))
         print(f"  {w.name} {style} per_call={per_call} options={[v for _, v in options]}", flush=True)
         policy = POLICIES[str(rng.choice(sorted(POLICIES)))] if rng.random() < 0.5 else None
         bf16 = bool(rng.random() < 0.4 and w.dtype == "f32" and (w.row_bytes // 2) % 16 == 0)   # binary32 samples stored as bfloat16
