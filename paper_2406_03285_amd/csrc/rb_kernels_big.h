@@ -1,5 +1,5 @@
 // Plan-ahead kernels for the single-launch step with up to 1024 candidates and representatives and up
-// to 10240 classes (any replacement strategy, either storage form; exact selection, or the Bernoulli
+// to 10240 classes (any replacement strategy, any storage form; exact selection, or the Bernoulli
 // selection for mini-batches of at most 1024 samples): as in rb_kernels_planned.h the plan of a step is worked out by
 // extra workgroups of the previous step's launch and left in a table, and the step's own launch only
 // moves rows by that table - but the planning workgroups (two: update, sampling) have 1024 threads

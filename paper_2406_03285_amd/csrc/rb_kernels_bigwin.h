@@ -1,5 +1,6 @@
-// Several steps per launch for large counts (rb_update_sample_many with up to 1024 candidates and
-// representatives, up to 10240 classes, exact selection; any replacement strategy, either storage form).
+// Several steps per launch for large counts, and for short rows (rb_update_sample_many with up to 1024 candidates and
+// representatives, up to 10240 classes; exact selection, or the Bernoulli selection for mini-batches of at most 1024
+// samples; any replacement strategy, any storage form).
 // As in rb_kernels_window.h a launch moves the rows of all steps of a window by a table that extra
 // workgroups of the launch before made; as in rb_kernels_big.h those workgroups have 1024 threads, one per
 // candidate or representative, and there are two per step (update, sampling).  The 2 w planners of a window of

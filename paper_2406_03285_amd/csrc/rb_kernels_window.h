@@ -1,7 +1,9 @@
 // Several steps per launch (rb_update_sample_many, at most 64 candidates and representatives, at
-// most 1024 classes, default policy): one workgroup plans a whole window of steps, one after the
-// other, while the other workgroups of the same launch move the previous window's rows; the
-// window's own launch then moves the rows of all its steps at once by the table the planner left.
+// most 1024 classes, exact selection; any replacement strategy, any storage form): one workgroup
+// plans a whole window of steps, one after the other, while the other workgroups of the same launch
+// move the previous window's rows; the window's own launch then moves the rows of all its steps at
+// once by the table the planner left.  (The host sends shapes whose rows move sooner than that one
+// workgroup plans to rb_kernels_bigwin.h, whose planners work side by side.)
 // Included by rb.hip only, after rb_kernels_small.h (whose candidate selection it uses).
 #pragma once
 
