@@ -158,7 +158,7 @@ int rb_set_policy(rb_buffer *rb, int32_t selection, int32_t eviction);
  * runs would race with it: the caller orders the two (one handle at a time per
  * GPU, or a synchronisation in between).
  * RB_ELIMIT: the handle needs more workspace than RB_STATIC_WORKSPACE_BYTES
- * (rb_query_sizes tells how much: about 16 bytes per class plus 1.8 MB);
+ * (rb_query_sizes tells how much: about 16 bytes per class plus 3.2 MB);
  * otherwise the errors of rb_bind.
  */
 #define RB_STATIC_WORKSPACE_BYTES (4u << 20)
