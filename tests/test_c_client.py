@@ -4,7 +4,6 @@ needed), and, on a GPU, tests/c_client/rb_client.c: a C program with its own dev
 workload through the library and whose dump is compared with the oracle."""
 import os
 import subprocess
-import sys
 import textwrap
 
 import pytest

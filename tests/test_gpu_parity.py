@@ -12,7 +12,7 @@ import torch
 import rb_workloads as wl
 from oracle import rbo
 import parity_util
-from parity_util import SENTINEL, compare_buffers, run_ahead_parity, run_many_parity, run_parity
+from parity_util import compare_buffers, run_ahead_parity, run_many_parity, run_parity
 
 pytestmark = pytest.mark.gpu
 
